@@ -1,0 +1,211 @@
+/*
+ * clover.h -- C ABI of the MI355X (gfx950) Clover-2 speculative-step library.
+ *
+ * One speculative step (paper Sec. 2.1 and Sec. 3):
+ *   draft_tree          the Clover-2 draft head proposes a token tree,
+ *   verify_tree         the target LLM scores every tree node in one pass (tree attention),
+ *   accept_and_compact  greedy verification keeps the longest correct root path.
+ *
+ * Conventions
+ *  - Every function returns CLOVER_OK (0) or a negative CLOVER_E_* code; nothing throws.
+ *  - Arguments are validated on the host before anything is launched.
+ *  - "dev" pointers are device (HBM) addresses, "host" pointers are ordinary host memory.
+ *  - The library allocates no device memory: KV caches, lengths and all scratch live in the
+ *    caller's workspace; weights are borrowed for the lifetime of the context.
+ *  - Calls enqueue work on the stream given at init and return without synchronising, unless
+ *    stated otherwise.  A HIP error found while launching is returned as CLOVER_E_HIP.
+ *  - Model tensors (weights, norm gains, biases) are in the model dtype (fp32 or bf16 bit
+ *    patterns); hidden states and logits cross the boundary as fp32; ids are int32.
+ *  - Linear weights are row-major [out_features, in_features].
+ *  - Rows are laid out [batch, max-nodes stride]: row (b, i) of a [B, R, ...] buffer is at
+ *    index b*R + i where R is the stride named for that argument.
+ */
+#ifndef CLOVER_H_
+#define CLOVER_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  CLOVER_OK = 0,
+  CLOVER_E_NULL = -1,      /* a required pointer is null */
+  CLOVER_E_CONFIG = -2,    /* inconsistent model configuration */
+  CLOVER_E_TREE = -3,      /* tree is not a breadth-first rooted tree / rank or depth out of range */
+  CLOVER_E_CAPACITY = -4,  /* workspace too small, or a sequence would outgrow max_seq */
+  CLOVER_E_SHAPE = -5,     /* batch / row counts outside what the context was sized for */
+  CLOVER_E_HIP = -6,       /* HIP runtime error (see clover_last_error) */
+  CLOVER_E_STATE = -7      /* device-side guard tripped (reported by clover_seq_len) */
+};
+
+enum { CLOVER_DTYPE_F32 = 0, CLOVER_DTYPE_BF16 = 1 };
+enum {
+  CLOVER_FLAG_GENERIC = 1,   /* use the plain fp32-ALU kernels everywhere (no MFMA path) */
+  CLOVER_FLAG_NO_GRAPH = 2   /* never replay captured HIP graphs */
+};
+#define CLOVER_MAX_NODES 128 /* upper bound on max_nodes (ancestor masks are 2 x 64 bit) */
+#define CLOVER_MAX_DEPTH 8   /* upper bound on draft_depths */
+#define CLOVER_MAX_RANK 16   /* ranks are < 16 */
+
+/* Model + capacity description.  Plain data, copied at init. */
+typedef struct {
+  int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+  float rope_base, rms_eps;
+  int32_t dtype;         /* CLOVER_DTYPE_*: type of every model tensor and of the KV caches */
+  int32_t aug_layers;    /* decoder layers in the Augmenting Block (Sec. 3.3) */
+  int32_t ad_heads;      /* heads of the Attention Decoder's cosine gate (Appendix A.3) */
+  int32_t draft_depths;  /* D: deepest tree level the draft head can fill (FC_0 .. FC_{D-1}) */
+  int32_t max_batch, max_seq, max_nodes;
+  int32_t flags;         /* CLOVER_FLAG_* */
+} clover_config;
+
+/* Static tree topology (Sec. 2.1: candidates merged on common prefixes form a tree).
+ * HOST arrays, copied.  Nodes in breadth-first order: parent[0] = -1, 0 <= parent[u] < u,
+ * depth non-decreasing in u.  rank[u] says node u carries the rank[u]-th best continuation
+ * of its parent (0 = best); siblings have distinct ranks. */
+typedef struct {
+  int32_t n_nodes;
+  const int32_t *parent;
+  const int32_t *rank;
+} clover_tree;
+
+/* One LLaMA-style decoder layer.  dev pointers, model dtype. */
+typedef struct {
+  const void *attn_norm; /* [H] */
+  const void *wq;        /* [n_q*d, H] */
+  const void *wk;        /* [n_kv*d, H] */
+  const void *wv;        /* [n_kv*d, H] */
+  const void *wo;        /* [H, n_q*d] */
+  const void *ffn_norm;  /* [H] */
+  const void *w_gate;    /* [F, H] */
+  const void *w_up;      /* [F, H] */
+  const void *w_down;    /* [H, F] */
+} clover_layer_weights;
+
+/* Attention Decoder (Appendix A.3): norm on x, q from x, k and v from y, all with bias. */
+typedef struct {
+  const void *norm;          /* [H] */
+  const void *wq, *bq;       /* [H,H], [H] */
+  const void *wk, *bk;
+  const void *wv, *bv;
+} clover_ad_weights;
+
+/* All weights.  The struct and the `layers`/`aug`/`fc_w`/`fc_b` arrays are HOST memory (copied
+ * at init); every tensor pointer inside is a dev pointer borrowed until clover_destroy. */
+typedef struct {
+  const void *embed;                     /* [V,H] target input embedding */
+  const clover_layer_weights *layers;    /* host array [n_layers] */
+  const void *final_norm;                /* [H] */
+  const void *lm_head;                   /* [V,H]; its rows are also the draft's token embeddings */
+  clover_ad_weights ad1, ad2;            /* before the Augmenting Block / in the regressive loop */
+  const clover_layer_weights *aug;       /* host array [aug_layers] */
+  const void *fc0_w, *fc0_b;             /* head 0: [H,H], [H] */
+  const void *const *fc_w;               /* host array [draft_depths]: fc_w[j] = [H,2H] for j>=1, fc_w[0] unused */
+  const void *const *fc_b;               /* host array [draft_depths]: [H] */
+  const void *head_norm;                 /* [H] norm before the shared LM head */
+} clover_weights;
+
+typedef struct clover_ctx clover_ctx;    /* opaque; owned by the library */
+
+/* Bytes of device workspace a context of this configuration needs (256-byte aligned base). */
+int clover_workspace_bytes(const clover_config *cfg, size_t *bytes_out);
+
+/* Create a context.  `workspace` is a dev pointer to >= clover_workspace_bytes bytes that the
+ * caller keeps alive; `hip_stream` is a hipStream_t (NULL = default stream).  Sequence lengths
+ * start at zero.  Synchronises the stream once (uploads the tree tables). */
+int clover_init(const clover_config *cfg, const clover_weights *weights, const clover_tree *tree,
+                void *workspace, size_t workspace_bytes, void *hip_stream, clover_ctx **ctx_out);
+int clover_destroy(clover_ctx *ctx);
+
+/* Forget all sequences: target and augmenting-block cache lengths become zero. */
+int clover_reset(clover_ctx *ctx);
+
+/* Replace the static tree (e.g. a chain for prompt chunks, one node for plain decoding).
+ * n_nodes <= max_nodes.  Synchronises the stream. */
+int clover_set_tree(clover_ctx *ctx, const clover_tree *tree);
+
+/* Draft head (Sec. 3; Sec. 3.1-3.3; Appendix A.3).  For every sequence b < batch with
+ * m[b] >= 1: rows i < m[b] pair hid_acc[b,i] (target hidden state before the final norm) with
+ * next_tok[b,i] (the token that followed it; the last is the new root).  AD1 and the Augmenting
+ * Block run on those rows and append m[b] rows to the block's own KV cache; then head 0 and the
+ * regressive AD2/FC updates fill the tree level by level through the shared LM head.
+ *   hid_acc     dev in  fp32 [batch, max_nodes, H]
+ *   next_tok    dev in  int32 [batch, max_nodes]
+ *   m           dev in  int32 [batch], 0 <= m[b] <= max_nodes; m[b] = 0 skips sequence b
+ *   tree_tokens dev out int32 [batch, max_nodes]: node u of sequence b at [b, u]; [b,0] = root
+ * Ranking ties go to the lower token id. */
+int draft_tree(clover_ctx *ctx, int32_t batch, const float *hid_acc, const int32_t *next_tok,
+               const int32_t *m, int32_t *tree_tokens);
+
+/* Verification pass (Sec. 2.1, tree attention).  Node u of sequence b is embedded, rotated to
+ * position len[b] + depth(u), its K/V stored at cache slot len[b] + u, and it attends to all
+ * cached slots and to the tree nodes on its own root path.  Lengths are not changed.
+ *   tree_tokens dev in  int32 [batch, max_nodes]
+ *   logits      dev out fp32 [batch, max_nodes, V]  (rows >= n_nodes untouched)
+ *   hidden      dev out fp32 [batch, max_nodes, H]  last block's output, before the final norm
+ * Fails with CLOVER_E_CAPACITY if a sequence could exceed max_seq. */
+int verify_tree(clover_ctx *ctx, int32_t batch, const int32_t *tree_tokens, float *logits, float *hidden);
+
+/* Greedy verification and cache compaction (Sec. 2.1; temperature 0).  Per sequence: start at
+ * the root; while a child of the current node carries argmax(logits[node]) move to it.  The
+ * visited nodes are accepted, the argmax at the last one is the bonus token.  K/V rows of the
+ * accepted nodes are moved to slots len..len+m-1 in every target layer and len += m.
+ *   m          dev out int32 [batch]              accepted rows (>= 1)
+ *   acc_idx    dev out int32 [batch, max_nodes]   accepted node indices, first m valid
+ *   new_tokens dev out int32 [batch, max_nodes]   tokens of accepted nodes 1..m-1, then the bonus
+ *   hid_acc    dev out fp32  [batch, max_nodes, H] hidden rows of the accepted nodes
+ *   next_tok   dev out int32 [batch, max_nodes]   = new_tokens (input of the next draft_tree)
+ * argmax ties go to the lower token id. */
+int accept_and_compact(clover_ctx *ctx, int32_t batch, const int32_t *tree_tokens, const float *logits,
+                       const float *hidden, int32_t *m, int32_t *acc_idx, int32_t *new_tokens,
+                       float *hid_acc, int32_t *next_tok);
+
+/* Prompt hand-off for a chain-shaped tree (the prefill phase of Sec. 1 run as chunks of plain
+ * decoding): accept nodes 0..n_rows[b]-1 of sequence b unconditionally (n_rows[b] = 0 leaves
+ * the sequence untouched).  The token after the last row is forced_next[b], or the target's
+ * argmax there when forced_next[b] < 0.  Outputs as accept_and_compact.  The current tree must
+ * be a chain.
+ *   n_rows, forced_next  dev in int32 [batch] */
+int clover_accept_forced(clover_ctx *ctx, int32_t batch, const int32_t *tree_tokens, const float *logits,
+                         const float *hidden, const int32_t *n_rows, const int32_t *forced_next,
+                         int32_t *m, int32_t *acc_idx, int32_t *new_tokens, float *hid_acc, int32_t *next_tok);
+
+/* Synchronise and read the target cache lengths into out_host[max_batch]; refreshes the
+ * host-side bound used by the capacity check.  Returns CLOVER_E_STATE if a device guard fired. */
+int clover_seq_len(clover_ctx *ctx, int32_t *out_host);
+
+/* Test helper (synchronises): copy cache rows [slot0, slot0+n_slots) of one layer and sequence
+ * to host as fp32 [n_slots, n_kv, d].  stack 0 = target, 1 = augmenting block. */
+int clover_read_kv(clover_ctx *ctx, int32_t stack, int32_t layer, int32_t b, int32_t slot0, int32_t n_slots,
+                   float *k_out_host, float *v_out_host);
+
+/* Per-kernel-class timing with HIP events on the library's stream.  While enabled, every launch
+ * is bracketed by two events (and HIP graphs are not used).  collect synchronises, adds up the
+ * elapsed milliseconds and launch counts per class since the last collect, and clears them.
+ * Class names: clover_kernel_class_name(i), i < clover_kernel_class_count(). */
+int clover_profile_enable(clover_ctx *ctx, int32_t on);
+int clover_profile_collect(clover_ctx *ctx, double *ms_by_class, int64_t *launches_by_class, int32_t n_classes);
+int clover_kernel_class_count(void);
+const char *clover_kernel_class_name(int32_t cls);
+
+/* Message of the last error on this context ("" if none); valid until the next call. */
+const char *clover_last_error(clover_ctx *ctx);
+/* Message of the last error of a call that had no context (init, workspace_bytes). */
+const char *clover_last_global_error(void);
+
+/* ---- single operators, exported for unit tests and kernel benchmarks -------------------- */
+
+/* Y[M,N] (fp32, leading dimension ldy) = X[M,K] (fp32, ld = K) * W[N,K]^T, W in `dtype`.
+ * path 0 = generic fp32-ALU kernel, 1 = MFMA weight-streaming kernel (bf16 only).
+ * `scratch` dev, >= clover_op_gemm_scratch_bytes(M,N,K).  Stream as given. */
+size_t clover_op_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K);
+int clover_op_gemm(int32_t path, int32_t dtype, const float *X, const void *W, float *Y, int32_t ldy,
+                   int32_t M, int32_t N, int32_t K, void *scratch, size_t scratch_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CLOVER_H_ */

@@ -1,0 +1,743 @@
+// C-ABI layer of libclover.so: context, validation, workspace carving and the kernel sequences of
+// the three calls of a speculative step.  All arithmetic runs in the kernels this file launches.
+#include "../../include/clover.h"
+#include "clover_internal.h"
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+using namespace clv;
+
+namespace {
+
+thread_local std::string g_err;
+
+const char* kClassNames[KC_COUNT] = {"embed",     "rmsnorm",     "gemm_qkv",   "rope_kv_write", "tree_attention", "gemm_wo",
+                                     "gemm_gate_up", "gemm_down", "gemm_lm_head", "gemm_draft",  "ad_gate",        "topk",
+                                     "draft_misc", "accept_walk", "compact_kv", "eltwise"};
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct TreeHost {
+  int n = 0, max_depth = 0;
+  std::vector<int> parent, rank, depth, first_child, n_child;
+  std::vector<int> lvl_nodes;           // internal nodes, grouped by depth
+  std::vector<int> lvl_off;             // [max_depth+2]: internal nodes of depth j are lvl_nodes[lvl_off[j]..lvl_off[j+1])
+  std::vector<int> par_row;             // per node: index of its parent within the parent's depth group
+  std::vector<int> node_off;            // [max_depth+2]: nodes of depth j are [node_off[j], node_off[j+1])
+  std::vector<int> kmax;                // per depth j: 1 + max rank among children of depth-j nodes
+  std::vector<unsigned long long> anc;  // [n][2]
+  bool is_chain = false;
+};
+
+struct ProfEvent {
+  int cls;
+  hipEvent_t a, b;
+};
+
+}  // namespace
+
+struct clover_ctx {
+  clover_config cfg;
+  hipStream_t st;
+  clover_weights w;
+  std::vector<clover_layer_weights> layers, aug;
+  std::vector<const void*> fc_w, fc_b;
+  TreeHost tree;
+  std::string err;
+  // sizes
+  int R, max_rows, H, QKVN, NQD;
+  KVLayout kv;
+  size_t k_layer_elems, v_layer_elems, esz;
+  // device regions
+  int *d_seq_len, *d_aug_len, *d_err;
+  int *d_depth, *d_parent, *d_rank, *d_first_child, *d_n_child, *d_lvl_nodes, *d_par_row;
+  unsigned long long *d_anc, *d_anc_chain;
+  char *kc, *vc, *aug_kc, *aug_vc;
+  float *xd, *a_norm, *qkv, *q_rot, *attn_out, *h_ffn, *tmp_ffn, *cos_t, *sin_t;
+  float *ad_q, *ad_k, *ad_v, *d_xs, *d_e, *d_cat, *d_g, *d_s, *d_state, *d_rootx, *z;
+  void* cand;
+  int* topk_ids;
+  float* partial;
+  size_t partial_bytes;
+  int* counters;
+  int n_counters;
+  // host-side bounds
+  std::vector<int> len_ub, aug_ub;
+  int m_upper;
+  // profiling
+  bool prof = false;
+  std::vector<ProfEvent> prof_events;
+  std::vector<ProfEvent> prof_pool;
+};
+
+namespace {
+
+int fail(clover_ctx* ctx, int code, const std::string& msg) {
+  if (ctx) ctx->err = msg; else g_err = msg;
+  return code;
+}
+
+int check_config(const clover_config* c, std::string& why) {
+  auto bad = [&](const char* m) { why = m; return CLOVER_E_CONFIG; };
+  if (c->n_layers < 1 || c->hidden < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->ffn < 1) return bad("non-positive model dimension");
+  if (c->head_dim != 64 && c->head_dim != 128) return bad("head_dim must be 64 or 128");
+  if (c->n_q_heads % c->n_kv_heads != 0) return bad("n_q_heads must be a multiple of n_kv_heads");
+  if (c->ad_heads < 1 || c->hidden % c->ad_heads != 0) return bad("hidden must be a multiple of ad_heads");
+  if (c->hidden % 4 != 0 || c->ffn % 4 != 0) return bad("hidden and ffn must be multiples of 4");
+  if (c->vocab < 16 || c->vocab > 262144) return bad("vocab must be in [16, 262144]");
+  if (c->dtype != CLOVER_DTYPE_F32 && c->dtype != CLOVER_DTYPE_BF16) return bad("unknown dtype");
+  if (c->aug_layers < 1 || c->aug_layers > 8) return bad("aug_layers must be in [1, 8]");
+  if (c->draft_depths < 1 || c->draft_depths > CLOVER_MAX_DEPTH) return bad("draft_depths out of range");
+  if (c->max_batch < 1 || c->max_batch > 1024) return bad("max_batch out of range");
+  if (c->max_nodes < 1 || c->max_nodes > CLOVER_MAX_NODES) return bad("max_nodes must be in [1, 128]");
+  if (c->max_seq < c->max_nodes) return bad("max_seq smaller than max_nodes");
+  if (!(c->rope_base > 1.f) || !(c->rms_eps > 0.f)) return bad("rope_base must be > 1 and rms_eps > 0");
+  return CLOVER_OK;
+}
+
+int build_tree(const clover_config& cfg, const clover_tree* t, TreeHost& out, std::string& why) {
+  auto bad = [&](const char* m) { why = m; return CLOVER_E_TREE; };
+  if (!t->parent || !t->rank) { why = "tree arrays are null"; return CLOVER_E_NULL; }
+  const int n = t->n_nodes;
+  if (n < 1 || n > cfg.max_nodes) return bad("n_nodes outside [1, max_nodes]");
+  if (t->parent[0] != -1) return bad("parent[0] must be -1");
+  TreeHost h;
+  h.n = n;
+  h.parent.assign(t->parent, t->parent + n);
+  h.rank.assign(t->rank, t->rank + n);
+  h.depth.assign(n, 0);
+  h.first_child.assign(n, 0);
+  h.n_child.assign(n, 0);
+  h.par_row.assign(n, 0);
+  for (int u = 1; u < n; ++u) {
+    const int p = h.parent[u];
+    if (p < 0 || p >= u) return bad("parent index must satisfy 0 <= parent[u] < u");
+    if (u >= 2 && p < h.parent[u - 1]) return bad("nodes must be in breadth-first order (parent non-decreasing)");
+    if (h.rank[u] < 0 || h.rank[u] >= CLOVER_MAX_RANK) return bad("rank outside [0, 16)");
+    h.depth[u] = h.depth[p] + 1;
+    if (h.n_child[p] == 0) h.first_child[p] = u;
+    h.n_child[p]++;
+  }
+  for (int u = 0; u < n; ++u) {
+    unsigned seen = 0;
+    for (int c = h.first_child[u]; c < h.first_child[u] + h.n_child[u]; ++c) {
+      if (seen & (1u << h.rank[c])) return bad("siblings must have distinct ranks");
+      seen |= 1u << h.rank[c];
+    }
+  }
+  h.max_depth = h.depth[n - 1];
+  h.is_chain = true;
+  for (int u = 1; u < n; ++u) h.is_chain = h.is_chain && (h.parent[u] == u - 1);
+  h.lvl_off.assign(h.max_depth + 2, 0);
+  h.node_off.assign(h.max_depth + 2, 0);
+  h.kmax.assign(h.max_depth + 1, 0);
+  std::vector<int> row_in_level(n, -1);
+  for (int j = 0; j <= h.max_depth; ++j) {
+    h.lvl_off[j] = (int)h.lvl_nodes.size();
+    for (int u = 0; u < n; ++u) {
+      if (h.depth[u] != j) continue;
+      if (h.n_child[u] > 0) {
+        row_in_level[u] = (int)h.lvl_nodes.size() - h.lvl_off[j];
+        h.lvl_nodes.push_back(u);
+        for (int c = h.first_child[u]; c < h.first_child[u] + h.n_child[u]; ++c) h.kmax[j] = std::max(h.kmax[j], h.rank[c] + 1);
+      }
+    }
+  }
+  h.lvl_off[h.max_depth + 1] = (int)h.lvl_nodes.size();
+  {
+    int u = 0;
+    for (int j = 0; j <= h.max_depth; ++j) {
+      h.node_off[j] = u;
+      while (u < n && h.depth[u] == j) ++u;
+    }
+    h.node_off[h.max_depth + 1] = n;
+    if (u != n) return bad("depth must be non-decreasing");
+  }
+  for (int u = 1; u < n; ++u) h.par_row[u] = row_in_level[h.parent[u]];
+  h.anc.assign((size_t)2 * n, 0ull);
+  for (int u = 0; u < n; ++u) {
+    if (u > 0) { h.anc[2 * u] = h.anc[2 * h.parent[u]]; h.anc[2 * u + 1] = h.anc[2 * h.parent[u] + 1]; }
+    h.anc[2 * u + (u >> 6)] |= 1ull << (u & 63);
+  }
+  out = std::move(h);
+  return CLOVER_OK;
+}
+
+// ---- workspace carving ---------------------------------------------------------------------
+struct Carver {
+  char* base;
+  size_t off = 0;
+  template <typename T>
+  T* take(size_t count) {
+    T* p = base ? (T*)(base + off) : nullptr;
+    off = align256(off + count * sizeof(T));
+    return p;
+  }
+};
+
+struct GemmShape { int N, K, mode; };
+
+void model_gemm_shapes(const clover_config& c, std::vector<GemmShape>& v) {
+  const int H = c.hidden, nqd = c.n_q_heads * c.head_dim, qkvn = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+  v = {{qkvn, H, 0}, {H, nqd, 1}, {c.ffn, H, 2}, {H, c.ffn, 1}, {c.vocab, H, 0}, {H, H, 0}, {H, 2 * H, 0}};
+}
+
+void carve(clover_ctx* x, char* base, size_t* total) {
+  const clover_config& c = x->cfg;
+  Carver cv{base};
+  const int B = c.max_batch, R = c.max_nodes, rows = B * R, H = c.hidden, d = c.head_dim;
+  const size_t esz = c.dtype == CLOVER_DTYPE_F32 ? 4 : 2;
+  x->R = R; x->max_rows = rows; x->H = H; x->esz = esz;
+  x->NQD = c.n_q_heads * d;
+  x->QKVN = (c.n_q_heads + 2 * c.n_kv_heads) * d;
+  x->kv = KVLayout{B, c.max_seq, c.n_kv_heads, d};
+  x->k_layer_elems = (size_t)B * c.max_seq * c.n_kv_heads * d;
+  x->v_layer_elems = x->k_layer_elems;
+  x->d_seq_len = cv.take<int>(B);
+  x->d_aug_len = cv.take<int>(B);
+  x->d_err = cv.take<int>(1);
+  x->d_depth = cv.take<int>(R);
+  x->d_parent = cv.take<int>(R);
+  x->d_rank = cv.take<int>(R);
+  x->d_first_child = cv.take<int>(R);
+  x->d_n_child = cv.take<int>(R);
+  x->d_lvl_nodes = cv.take<int>(R);
+  x->d_par_row = cv.take<int>(R);
+  x->d_anc = cv.take<unsigned long long>(2 * R);
+  x->d_anc_chain = cv.take<unsigned long long>(2 * R);
+  x->kc = cv.take<char>(x->k_layer_elems * esz * c.n_layers);
+  x->vc = cv.take<char>(x->v_layer_elems * esz * c.n_layers);
+  x->aug_kc = cv.take<char>(x->k_layer_elems * esz * c.aug_layers);
+  x->aug_vc = cv.take<char>(x->v_layer_elems * esz * c.aug_layers);
+  x->xd = cv.take<float>((size_t)rows * H);
+  x->a_norm = cv.take<float>((size_t)rows * 2 * H);
+  x->qkv = cv.take<float>((size_t)rows * x->QKVN);
+  x->q_rot = cv.take<float>((size_t)rows * x->NQD);
+  x->attn_out = cv.take<float>((size_t)rows * x->NQD);
+  x->h_ffn = cv.take<float>((size_t)rows * c.ffn);
+  x->tmp_ffn = cv.take<float>((size_t)rows * c.ffn);
+  x->cos_t = cv.take<float>((size_t)rows * d / 2);
+  x->sin_t = cv.take<float>((size_t)rows * d / 2);
+  x->ad_q = cv.take<float>((size_t)rows * H);
+  x->ad_k = cv.take<float>((size_t)rows * H);
+  x->ad_v = cv.take<float>((size_t)rows * H);
+  x->d_xs = cv.take<float>((size_t)rows * H);
+  x->d_e = cv.take<float>((size_t)rows * H);
+  x->d_cat = cv.take<float>((size_t)rows * 2 * H);
+  x->d_g = cv.take<float>((size_t)rows * H);
+  x->d_s = cv.take<float>((size_t)rows * H);
+  x->d_state = cv.take<float>((size_t)rows * H);
+  x->d_rootx = cv.take<float>((size_t)B * H);
+  x->z = cv.take<float>((size_t)rows * c.vocab);
+  x->cand = cv.take<unsigned long long>((size_t)rows * topk_chunks(c.vocab) * 16);
+  x->topk_ids = cv.take<int>((size_t)rows * 16);
+  // split-K scratch of the MFMA GEMM, sized for the largest shape of this model
+  size_t pbytes = 0;
+  int ncount = 1;
+  if (c.dtype == CLOVER_DTYPE_BF16) {
+    std::vector<GemmShape> shapes;
+    model_gemm_shapes(c, shapes);
+    const int Mmax = std::min(rows, 256);
+    for (const GemmShape& s : shapes) {
+      if (!mfma_gemm_supported(Mmax, s.N, s.K, s.mode)) continue;
+      ncount = std::max(ncount, mfma_gemm_counters(s.N, s.mode));
+      for (int M = 16; M <= 256; M *= 2) {
+        const int mm = std::min(M, Mmax);
+        pbytes = std::max(pbytes, mfma_gemm_partial_bytes(mm, s.N, s.K, s.mode, mfma_gemm_pick_splits(mm, s.N, s.K, s.mode)));
+      }
+    }
+  }
+  x->partial_bytes = pbytes;
+  x->partial = (float*)cv.take<char>(pbytes ? pbytes : 256);
+  x->n_counters = ncount;
+  x->counters = cv.take<int>(ncount);
+  *total = cv.off;
+}
+
+// ---- profiling ------------------------------------------------------------------------------
+struct Scope {
+  clover_ctx* x;
+  ProfEvent ev;
+  bool on;
+  Scope(clover_ctx* ctx, int cls) : x(ctx), on(ctx->prof) {
+    if (!on) return;
+    if (!x->prof_pool.empty()) { ev = x->prof_pool.back(); x->prof_pool.pop_back(); }
+    else { hipEventCreate(&ev.a); hipEventCreate(&ev.b); }
+    ev.cls = cls;
+    hipEventRecord(ev.a, x->st);
+  }
+  ~Scope() {
+    if (!on) return;
+    hipEventRecord(ev.b, x->st);
+    x->prof_events.push_back(ev);
+  }
+};
+
+// ---- GEMM dispatch ----------------------------------------------------------------------------
+// Y[M, N] = X[M, K] * [W0; W1; W2]^T (row segments of seg_n[] rows) ; mode 2 uses W0 = gate and w_up.
+void gemm(clover_ctx* x, int cls, const float* X, int ldx, int nseg, const void* const* W, const int* seg_n,
+          const void* w_up, const void* bias, float* Y, int ldy, int M, int N, int K, int mode) {
+  Scope sc(x, cls);
+  const bool bf16 = x->cfg.dtype == CLOVER_DTYPE_BF16;
+  bool fast = bf16 && !(x->cfg.flags & CLOVER_FLAG_GENERIC) && mfma_gemm_supported(std::min(M, 256), N, K, mode) &&
+              (ldx % 4 == 0) && (ldy % 4 == 0);
+  for (int s = 0; s < nseg && fast && mode != 2; ++s) fast = (seg_n[s] % 32 == 0);
+  if (fast) {
+    for (int m0 = 0; m0 < M; m0 += 256) {
+      const int mm = std::min(256, M - m0);
+      MfmaGemm g;
+      memset(&g, 0, sizeof(g));
+      g.X = X + (size_t)m0 * ldx; g.ldx = ldx;
+      int off = 0;
+      for (int s = 0; s < 3; ++s) {
+        g.W[s] = (const bf16_t*)(s < nseg ? W[s] : W[nseg - 1]);
+        g.seg_begin[s] = s < nseg ? off : 0x7fffffff;
+        if (s < nseg) off += seg_n[s];
+      }
+      g.seg_begin[0] = 0;
+      g.seg_begin[3] = 0x7fffffff;
+      g.W_up = (const bf16_t*)w_up;
+      g.bias = (const bf16_t*)bias;
+      g.Y = Y + (size_t)m0 * ldy; g.ldy = ldy;
+      g.M = mm; g.N = N; g.K = K; g.mode = mode;
+      g.splits = mfma_gemm_pick_splits(mm, N, K, mode);
+      if (mfma_gemm_partial_bytes(mm, N, K, mode, g.splits) > x->partial_bytes || mfma_gemm_counters(N, mode) > x->n_counters) g.splits = 1;
+      g.partial = x->partial;
+      g.counters = x->counters;
+      launch_gemm_mfma(g, x->st);
+    }
+    return;
+  }
+  const int wd = x->cfg.dtype;
+  if (mode == 2) {
+    launch_gemm_generic(X, ldx, W[0], nullptr, wd, x->tmp_ffn, N, M, N, K, 0, x->st);
+    launch_gemm_generic(X, ldx, w_up, nullptr, wd, Y, ldy, M, N, K, 0, x->st);
+    if (ldy == N) launch_swiglu(x->tmp_ffn, Y, Y, (size_t)M * N, x->st);
+    else for (int r = 0; r < M; ++r) launch_swiglu(x->tmp_ffn + (size_t)r * N, Y + (size_t)r * ldy, Y + (size_t)r * ldy, N, x->st);
+    return;
+  }
+  int off = 0;
+  for (int s = 0; s < nseg; ++s) {
+    const void* b = bias ? (const void*)((const char*)bias + (size_t)off * x->esz) : nullptr;
+    launch_gemm_generic(X, ldx, W[s], b, wd, Y + off, ldy, M, seg_n[s], K, mode, x->st);
+    off += seg_n[s];
+  }
+}
+
+void gemm1(clover_ctx* x, int cls, const float* X, int ldx, const void* W, const void* bias, float* Y, int ldy, int M,
+           int N, int K, int mode) {
+  const void* ws[1] = {W};
+  const int sn[1] = {N};
+  gemm(x, cls, X, ldx, 1, ws, sn, nullptr, bias, Y, ldy, M, N, K, mode);
+}
+
+// One LLaMA decoder layer over the rows of `rm` (residual stream x, leading dimension H).
+void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMap rm, int M, char* kc_layer,
+               char* vc_layer, const int* base_len, const unsigned long long* anc) {
+  const clover_config& c = x->cfg;
+  const int H = x->H, d = c.head_dim;
+  { Scope s(x, KC_RMSNORM); launch_rmsnorm(xres, H, lw.attn_norm, c.dtype, c.rms_eps, x->a_norm, H, H, M, x->st); }
+  const void* ws[3] = {lw.wq, lw.wk, lw.wv};
+  const int sn[3] = {c.n_q_heads * d, c.n_kv_heads * d, c.n_kv_heads * d};
+  gemm(x, KC_GEMM_QKV, x->a_norm, H, 3, ws, sn, nullptr, nullptr, x->qkv, x->QKVN, M, x->QKVN, H, 0);
+  { Scope s(x, KC_ROPE_KV);
+    launch_rope_kv_write(x->qkv, x->QKVN, x->cos_t, x->sin_t, x->q_rot, x->NQD, kc_layer, vc_layer, c.dtype, x->kv,
+                         base_len, c.n_q_heads, rm, x->d_err, x->st); }
+  { Scope s(x, KC_ATTN);
+    launch_attn_generic(x->q_rot, x->NQD, kc_layer, vc_layer, c.dtype, x->kv, base_len, anc, c.n_q_heads, x->attn_out,
+                        x->NQD, rm, x->st); }
+  gemm1(x, KC_GEMM_WO, x->attn_out, x->NQD, lw.wo, nullptr, xres, H, M, H, x->NQD, 1);
+  { Scope s(x, KC_RMSNORM); launch_rmsnorm(xres, H, lw.ffn_norm, c.dtype, c.rms_eps, x->a_norm, H, H, M, x->st); }
+  const void* wg[1] = {lw.w_gate};
+  const int gn[1] = {c.ffn};
+  gemm(x, KC_GEMM_GATEUP, x->a_norm, H, 1, wg, gn, lw.w_up, nullptr, x->h_ffn, c.ffn, M, c.ffn, H, 2);
+  gemm1(x, KC_GEMM_DOWN, x->h_ffn, c.ffn, lw.w_down, nullptr, xres, H, M, H, c.ffn, 1);
+}
+
+// Attention Decoder on `rows` contiguous rows: out = x + gate(q(norm(x)), k(y)) * v(y)
+void run_ad(clover_ctx* x, const clover_ad_weights& ad, const float* xin, const float* y, int rows, float* out) {
+  const clover_config& c = x->cfg;
+  const int H = x->H;
+  { Scope s(x, KC_RMSNORM); launch_rmsnorm(xin, H, ad.norm, c.dtype, c.rms_eps, x->a_norm, H, H, rows, x->st); }
+  gemm1(x, KC_GEMM_DRAFT, x->a_norm, H, ad.wq, ad.bq, x->ad_q, H, rows, H, H, 0);
+  gemm1(x, KC_GEMM_DRAFT, y, H, ad.wk, ad.bk, x->ad_k, H, rows, H, H, 0);
+  gemm1(x, KC_GEMM_DRAFT, y, H, ad.wv, ad.bv, x->ad_v, H, rows, H, H, 0);
+  { Scope s(x, KC_AD_GATE);
+    launch_ad_gate(xin, H, x->ad_q, x->ad_k, x->ad_v, H, c.ad_heads, out, H, nullptr, 0, rows, x->st); }
+}
+
+// logits of `rows` contiguous rows of g through the head norm and the shared LM head, then top-k
+void run_head(clover_ctx* x, const float* g, int rows, int k) {
+  const clover_config& c = x->cfg;
+  const int H = x->H;
+  { Scope s(x, KC_RMSNORM); launch_rmsnorm(g, H, x->w.head_norm, c.dtype, c.rms_eps, x->a_norm, H, H, rows, x->st); }
+  gemm1(x, KC_GEMM_LMHEAD, x->a_norm, H, x->w.lm_head, nullptr, x->z, c.vocab, rows, c.vocab, H, 0);
+  { Scope s(x, KC_TOPK); launch_topk(x->z, c.vocab, c.vocab, rows, k, x->cand, x->topk_ids, x->st); }
+}
+
+int upload_tree(clover_ctx* x) {
+  const TreeHost& t = x->tree;
+  const int n = t.n;
+  hipError_t e = hipSuccess;
+  auto up = [&](void* dst, const void* src, size_t bytes) {
+    if (bytes && e == hipSuccess) e = hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, x->st);
+  };
+  up(x->d_depth, t.depth.data(), n * sizeof(int));
+  up(x->d_parent, t.parent.data(), n * sizeof(int));
+  up(x->d_rank, t.rank.data(), n * sizeof(int));
+  up(x->d_first_child, t.first_child.data(), n * sizeof(int));
+  up(x->d_n_child, t.n_child.data(), n * sizeof(int));
+  up(x->d_lvl_nodes, t.lvl_nodes.data(), t.lvl_nodes.size() * sizeof(int));
+  up(x->d_par_row, t.par_row.data(), n * sizeof(int));
+  up(x->d_anc, t.anc.data(), 2 * n * sizeof(unsigned long long));
+  if (e == hipSuccess) e = hipStreamSynchronize(x->st);  // the host vectors may change after return
+  if (e != hipSuccess) return fail(x, CLOVER_E_HIP, std::string("tree upload: ") + hipGetErrorString(e));
+  return CLOVER_OK;
+}
+
+int finish(clover_ctx* x, const char* what) {
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(x, CLOVER_E_HIP, std::string(what) + ": " + hipGetErrorString(e));
+  return CLOVER_OK;
+}
+
+int check_batch(clover_ctx* x, int batch) {
+  if (batch < 1 || batch > x->cfg.max_batch) return fail(x, CLOVER_E_SHAPE, "batch outside [1, max_batch]");
+  return CLOVER_OK;
+}
+
+int accept_common(clover_ctx* x, int batch, const int* tree_tokens, const float* logits, const float* hidden,
+                  const int* n_forced, const int* forced_next, int* m, int* acc_idx, int* new_tokens, float* hid_acc,
+                  int* next_tok) {
+  const clover_config& c = x->cfg;
+  const TreeHost& t = x->tree;
+  const int R = x->R, M = (batch - 1) * R + t.n;
+  { Scope s(x, KC_TOPK); launch_topk(logits, c.vocab, c.vocab, M, 1, x->cand, x->topk_ids, x->st); }
+  { Scope s(x, KC_ACCEPT);
+    launch_accept_walk(x->topk_ids, tree_tokens, x->d_first_child, x->d_n_child, t.n, batch, R, n_forced, forced_next,
+                       m, acc_idx, new_tokens, next_tok, x->st); }
+  { Scope s(x, KC_COMPACT);
+    launch_compact_kv(x->kc, x->vc, c.dtype, x->kv, c.n_layers, x->k_layer_elems, x->v_layer_elems, x->d_seq_len, m,
+                      acc_idx, batch, R, x->st);
+    launch_gather_hidden(hidden, acc_idx, m, batch, R, x->H, hid_acc, x->st);
+    launch_add_len(x->d_seq_len, m, batch, x->st); }
+  return finish(x, "accept");
+}
+
+}  // namespace
+
+// ================================================================================================
+extern "C" {
+
+int clover_workspace_bytes(const clover_config* cfg, size_t* bytes_out) {
+  if (!cfg || !bytes_out) return fail(nullptr, CLOVER_E_NULL, "null argument");
+  std::string why;
+  const int rc = check_config(cfg, why);
+  if (rc) return fail(nullptr, rc, why);
+  clover_ctx tmp{};
+  tmp.cfg = *cfg;
+  size_t total = 0;
+  carve(&tmp, nullptr, &total);
+  *bytes_out = total;
+  return CLOVER_OK;
+}
+
+int clover_init(const clover_config* cfg, const clover_weights* w, const clover_tree* tree, void* workspace,
+                size_t workspace_bytes, void* hip_stream, clover_ctx** ctx_out) {
+  if (!cfg || !w || !tree || !workspace || !ctx_out) return fail(nullptr, CLOVER_E_NULL, "null argument");
+  std::string why;
+  int rc = check_config(cfg, why);
+  if (rc) return fail(nullptr, rc, why);
+  if (((uintptr_t)workspace & 255) != 0) return fail(nullptr, CLOVER_E_CONFIG, "workspace must be 256-byte aligned");
+  if (!w->embed || !w->layers || !w->final_norm || !w->lm_head || !w->aug || !w->fc0_w || !w->fc0_b || !w->fc_w ||
+      !w->fc_b || !w->head_norm)
+    return fail(nullptr, CLOVER_E_NULL, "null weight pointer");
+  const clover_ad_weights* ads[2] = {&w->ad1, &w->ad2};
+  for (const clover_ad_weights* a : ads)
+    if (!a->norm || !a->wq || !a->bq || !a->wk || !a->bk || !a->wv || !a->bv) return fail(nullptr, CLOVER_E_NULL, "null Attention-Decoder weight");
+  auto layer_ok = [](const clover_layer_weights& l) {
+    return l.attn_norm && l.wq && l.wk && l.wv && l.wo && l.ffn_norm && l.w_gate && l.w_up && l.w_down;
+  };
+  for (int i = 0; i < cfg->n_layers; ++i) if (!layer_ok(w->layers[i])) return fail(nullptr, CLOVER_E_NULL, "null target layer weight");
+  for (int i = 0; i < cfg->aug_layers; ++i) if (!layer_ok(w->aug[i])) return fail(nullptr, CLOVER_E_NULL, "null augmenting layer weight");
+  for (int j = 1; j < cfg->draft_depths; ++j) if (!w->fc_w[j] || !w->fc_b[j]) return fail(nullptr, CLOVER_E_NULL, "null FC weight");
+  TreeHost th;
+  rc = build_tree(*cfg, tree, th, why);
+  if (rc) return fail(nullptr, rc, why);
+
+  clover_ctx* x = new clover_ctx{};
+  x->cfg = *cfg;
+  x->st = (hipStream_t)hip_stream;
+  x->w = *w;
+  x->layers.assign(w->layers, w->layers + cfg->n_layers);
+  x->aug.assign(w->aug, w->aug + cfg->aug_layers);
+  x->fc_w.assign(w->fc_w, w->fc_w + cfg->draft_depths);
+  x->fc_b.assign(w->fc_b, w->fc_b + cfg->draft_depths);
+  x->tree = std::move(th);
+  size_t total = 0;
+  carve(x, (char*)workspace, &total);
+  if (total > workspace_bytes) { delete x; return fail(nullptr, CLOVER_E_CAPACITY, "workspace too small"); }
+  x->len_ub.assign(cfg->max_batch, 0);
+  x->aug_ub.assign(cfg->max_batch, 0);
+  x->m_upper = cfg->max_nodes;
+  // chain masks for the Augmenting Block's causal rows: row i sees new rows 0..i
+  std::vector<unsigned long long> chain((size_t)2 * cfg->max_nodes, 0ull);
+  for (int u = 0; u < cfg->max_nodes; ++u) {
+    if (u > 0) { chain[2 * u] = chain[2 * (u - 1)]; chain[2 * u + 1] = chain[2 * (u - 1) + 1]; }
+    chain[2 * u + (u >> 6)] |= 1ull << (u & 63);
+  }
+  hipError_t e = hipMemcpyAsync(x->d_anc_chain, chain.data(), chain.size() * sizeof(unsigned long long), hipMemcpyHostToDevice, x->st);
+  if (e == hipSuccess) e = hipStreamSynchronize(x->st);
+  if (e != hipSuccess) { std::string m = hipGetErrorString(e); delete x; return fail(nullptr, CLOVER_E_HIP, "init upload: " + m); }
+  launch_fill_i32(x->d_seq_len, 0, cfg->max_batch, x->st);
+  launch_fill_i32(x->d_aug_len, 0, cfg->max_batch, x->st);
+  launch_fill_i32(x->d_err, 0, 1, x->st);
+  launch_fill_i32(x->counters, 0, x->n_counters, x->st);
+  rc = upload_tree(x);
+  if (rc == CLOVER_OK) rc = finish(x, "init");
+  if (rc) { g_err = x->err; delete x; return rc; }
+  *ctx_out = x;
+  return CLOVER_OK;
+}
+
+int clover_destroy(clover_ctx* x) {
+  if (!x) return CLOVER_E_NULL;
+  hipStreamSynchronize(x->st);
+  for (ProfEvent& ev : x->prof_events) { hipEventDestroy(ev.a); hipEventDestroy(ev.b); }
+  for (ProfEvent& ev : x->prof_pool) { hipEventDestroy(ev.a); hipEventDestroy(ev.b); }
+  delete x;
+  return CLOVER_OK;
+}
+
+int clover_reset(clover_ctx* x) {
+  if (!x) return CLOVER_E_NULL;
+  launch_fill_i32(x->d_seq_len, 0, x->cfg.max_batch, x->st);
+  launch_fill_i32(x->d_aug_len, 0, x->cfg.max_batch, x->st);
+  launch_fill_i32(x->d_err, 0, 1, x->st);
+  std::fill(x->len_ub.begin(), x->len_ub.end(), 0);
+  std::fill(x->aug_ub.begin(), x->aug_ub.end(), 0);
+  x->m_upper = x->cfg.max_nodes;
+  return finish(x, "reset");
+}
+
+int clover_set_tree(clover_ctx* x, const clover_tree* tree) {
+  if (!x || !tree) return fail(x, CLOVER_E_NULL, "null argument");
+  TreeHost th;
+  std::string why;
+  const int rc = build_tree(x->cfg, tree, th, why);
+  if (rc) return fail(x, rc, why);
+  hipError_t e = hipStreamSynchronize(x->st);  // kernels in flight still read the old tables
+  if (e != hipSuccess) return fail(x, CLOVER_E_HIP, hipGetErrorString(e));
+  x->tree = std::move(th);
+  return upload_tree(x);
+}
+
+int draft_tree(clover_ctx* x, int32_t batch, const float* hid_acc, const int32_t* next_tok, const int32_t* m,
+               int32_t* tree_tokens) {
+  if (!x || !hid_acc || !next_tok || !m || !tree_tokens) return fail(x, CLOVER_E_NULL, "null argument");
+  int rc = check_batch(x, batch);
+  if (rc) return rc;
+  const clover_config& c = x->cfg;
+  const TreeHost& t = x->tree;
+  const int B = batch, R = x->R, H = x->H, n = std::min(x->m_upper, R);
+  for (int b = 0; b < B; ++b)
+    if (x->aug_ub[b] + n > c.max_seq) return fail(x, CLOVER_E_CAPACITY, "augmenting-block cache could exceed max_seq");
+  const RowMap rm{B, R, n, m};
+  const int M = (B - 1) * R + n;
+  // embeddings of the follow-up tokens come from the LM-head rows
+  { Scope s(x, KC_EMBED); launch_embed(x->w.lm_head, c.dtype, next_tok, c.vocab, x->d_e, H, H, rm, x->st); }
+  run_ad(x, x->w.ad1, hid_acc, x->d_e, M, x->xd);
+  { Scope s(x, KC_ROPE_KV); launch_rope_table(x->d_aug_len, nullptr, c.rope_base, c.head_dim, x->cos_t, x->sin_t, rm, x->st); }
+  for (int l = 0; l < c.aug_layers; ++l)
+    run_layer(x, x->aug[l], x->xd, rm, M, x->aug_kc + (size_t)l * x->k_layer_elems * x->esz,
+              x->aug_vc + (size_t)l * x->v_layer_elems * x->esz, x->d_aug_len, x->d_anc_chain);
+  { Scope s(x, KC_DRAFT_MISC);
+    launch_draft_root(x->xd, next_tok, m, B, R, H, x->d_rootx, x->d_state, tree_tokens, x->st);
+    launch_add_len(x->d_aug_len, m, B, x->st); }
+  for (int b = 0; b < B; ++b) x->aug_ub[b] += n;
+  // expansion, level by level; a tree deeper than the head (e.g. a prompt chain) is not expanded
+  if (t.max_depth <= c.draft_depths) {
+    for (int j = 0; j < t.max_depth; ++j) {
+      const int n_lvl = t.lvl_off[j + 1] - t.lvl_off[j];
+      if (n_lvl == 0) break;
+      const int rows = B * n_lvl;
+      if (j == 0) {
+        gemm1(x, KC_GEMM_DRAFT, x->d_rootx, H, x->w.fc0_w, x->w.fc0_b, x->d_g, H, rows, H, H, 0);
+      } else {
+        const int* nodes = x->d_lvl_nodes + t.lvl_off[j];
+        { Scope s(x, KC_DRAFT_MISC);
+          launch_draft_gather(x->d_state, tree_tokens, nodes, x->d_parent, n_lvl, B, R, H, x->w.lm_head, c.dtype,
+                              c.vocab, x->d_xs, x->d_e, x->d_cat, x->st); }
+        run_ad(x, x->w.ad2, x->d_xs, x->d_e, rows, x->d_s);
+        { Scope s(x, KC_DRAFT_MISC);
+          launch_draft_scatter_state(x->d_s, nodes, n_lvl, B, R, H, x->d_state, x->d_cat, x->st); }
+        gemm1(x, KC_GEMM_DRAFT, x->d_cat, 2 * H, x->fc_w[j], x->fc_b[j], x->d_g, H, rows, H, 2 * H, 0);
+      }
+      run_head(x, x->d_g, rows, t.kmax[j]);
+      { Scope s(x, KC_DRAFT_MISC);
+        launch_draft_assign(x->topk_ids, x->d_par_row, x->d_rank, t.node_off[j + 1], t.node_off[j + 2], n_lvl, B, R, m,
+                            tree_tokens, x->st); }
+    }
+  }
+  return finish(x, "draft_tree");
+}
+
+int verify_tree(clover_ctx* x, int32_t batch, const int32_t* tree_tokens, float* logits, float* hidden) {
+  if (!x || !tree_tokens || !logits || !hidden) return fail(x, CLOVER_E_NULL, "null argument");
+  int rc = check_batch(x, batch);
+  if (rc) return rc;
+  const clover_config& c = x->cfg;
+  const TreeHost& t = x->tree;
+  const int B = batch, R = x->R, H = x->H;
+  for (int b = 0; b < B; ++b)
+    if (x->len_ub[b] + t.n > c.max_seq) return fail(x, CLOVER_E_CAPACITY, "sequence could exceed max_seq (call clover_seq_len to refresh the bound)");
+  const RowMap rm{B, R, t.n, nullptr};
+  const int M = (B - 1) * R + t.n;
+  { Scope s(x, KC_EMBED); launch_embed(x->w.embed, c.dtype, tree_tokens, c.vocab, hidden, H, H, rm, x->st); }
+  { Scope s(x, KC_ROPE_KV); launch_rope_table(x->d_seq_len, x->d_depth, c.rope_base, c.head_dim, x->cos_t, x->sin_t, rm, x->st); }
+  for (int l = 0; l < c.n_layers; ++l)
+    run_layer(x, x->layers[l], hidden, rm, M, x->kc + (size_t)l * x->k_layer_elems * x->esz,
+              x->vc + (size_t)l * x->v_layer_elems * x->esz, x->d_seq_len, x->d_anc);
+  { Scope s(x, KC_RMSNORM); launch_rmsnorm(hidden, H, x->w.final_norm, c.dtype, c.rms_eps, x->a_norm, H, H, M, x->st); }
+  gemm1(x, KC_GEMM_LMHEAD, x->a_norm, H, x->w.lm_head, nullptr, logits, c.vocab, M, c.vocab, H, 0);
+  return finish(x, "verify_tree");
+}
+
+int accept_and_compact(clover_ctx* x, int32_t batch, const int32_t* tree_tokens, const float* logits,
+                       const float* hidden, int32_t* m, int32_t* acc_idx, int32_t* new_tokens, float* hid_acc,
+                       int32_t* next_tok) {
+  if (!x || !tree_tokens || !logits || !hidden || !m || !acc_idx || !new_tokens || !hid_acc || !next_tok)
+    return fail(x, CLOVER_E_NULL, "null argument");
+  int rc = check_batch(x, batch);
+  if (rc) return rc;
+  rc = accept_common(x, batch, tree_tokens, logits, hidden, nullptr, nullptr, m, acc_idx, new_tokens, hid_acc, next_tok);
+  if (rc) return rc;
+  x->m_upper = std::min(x->tree.max_depth + 1, x->R);
+  for (int b = 0; b < batch; ++b) x->len_ub[b] += x->m_upper;
+  return CLOVER_OK;
+}
+
+int clover_accept_forced(clover_ctx* x, int32_t batch, const int32_t* tree_tokens, const float* logits,
+                         const float* hidden, const int32_t* n_rows, const int32_t* forced_next, int32_t* m,
+                         int32_t* acc_idx, int32_t* new_tokens, float* hid_acc, int32_t* next_tok) {
+  if (!x || !tree_tokens || !logits || !hidden || !n_rows || !forced_next || !m || !acc_idx || !new_tokens ||
+      !hid_acc || !next_tok)
+    return fail(x, CLOVER_E_NULL, "null argument");
+  int rc = check_batch(x, batch);
+  if (rc) return rc;
+  if (!x->tree.is_chain) return fail(x, CLOVER_E_TREE, "clover_accept_forced needs a chain-shaped tree");
+  rc = accept_common(x, batch, tree_tokens, logits, hidden, n_rows, forced_next, m, acc_idx, new_tokens, hid_acc, next_tok);
+  if (rc) return rc;
+  x->m_upper = x->tree.n;
+  for (int b = 0; b < batch; ++b) x->len_ub[b] += x->tree.n;
+  return CLOVER_OK;
+}
+
+int clover_seq_len(clover_ctx* x, int32_t* out_host) {
+  if (!x || !out_host) return fail(x, CLOVER_E_NULL, "null argument");
+  const int B = x->cfg.max_batch;
+  std::vector<int> aug(B);
+  int err = 0;
+  hipError_t e = hipMemcpyAsync(out_host, x->d_seq_len, B * sizeof(int), hipMemcpyDeviceToHost, x->st);
+  if (e == hipSuccess) e = hipMemcpyAsync(aug.data(), x->d_aug_len, B * sizeof(int), hipMemcpyDeviceToHost, x->st);
+  if (e == hipSuccess) e = hipMemcpyAsync(&err, x->d_err, sizeof(int), hipMemcpyDeviceToHost, x->st);
+  if (e == hipSuccess) e = hipStreamSynchronize(x->st);
+  if (e != hipSuccess) return fail(x, CLOVER_E_HIP, std::string("clover_seq_len: ") + hipGetErrorString(e));
+  for (int b = 0; b < B; ++b) { x->len_ub[b] = out_host[b]; x->aug_ub[b] = aug[b]; }
+  if (err) return fail(x, CLOVER_E_STATE, "a kernel refused to write past max_seq");
+  return CLOVER_OK;
+}
+
+int clover_read_kv(clover_ctx* x, int32_t stack, int32_t layer, int32_t b, int32_t slot0, int32_t n_slots,
+                   float* k_out_host, float* v_out_host) {
+  if (!x || !k_out_host || !v_out_host) return fail(x, CLOVER_E_NULL, "null argument");
+  const clover_config& c = x->cfg;
+  const int nl = stack == 0 ? c.n_layers : c.aug_layers;
+  if (stack < 0 || stack > 1 || layer < 0 || layer >= nl || b < 0 || b >= c.max_batch || slot0 < 0 || n_slots < 0 ||
+      slot0 + n_slots > c.max_seq)
+    return fail(x, CLOVER_E_SHAPE, "clover_read_kv: index out of range");
+  const size_t n = (size_t)n_slots * c.n_kv_heads * c.head_dim;
+  if (2 * n > (size_t)x->max_rows * c.vocab) return fail(x, CLOVER_E_SHAPE, "clover_read_kv: too many slots at once");
+  if (n == 0) return CLOVER_OK;
+  const char* kbase = (stack == 0 ? x->kc : x->aug_kc) + (size_t)layer * x->k_layer_elems * x->esz;
+  const char* vbase = (stack == 0 ? x->vc : x->aug_vc) + (size_t)layer * x->v_layer_elems * x->esz;
+  launch_read_kv(kbase, vbase, c.dtype, x->kv, b, slot0, n_slots, x->z, x->z + n, x->st);
+  hipError_t e = hipMemcpyAsync(k_out_host, x->z, n * sizeof(float), hipMemcpyDeviceToHost, x->st);
+  if (e == hipSuccess) e = hipMemcpyAsync(v_out_host, x->z + n, n * sizeof(float), hipMemcpyDeviceToHost, x->st);
+  if (e == hipSuccess) e = hipStreamSynchronize(x->st);
+  if (e != hipSuccess) return fail(x, CLOVER_E_HIP, std::string("clover_read_kv: ") + hipGetErrorString(e));
+  return CLOVER_OK;
+}
+
+int clover_profile_enable(clover_ctx* x, int32_t on) {
+  if (!x) return CLOVER_E_NULL;
+  x->prof = on != 0;
+  return CLOVER_OK;
+}
+
+int clover_profile_collect(clover_ctx* x, double* ms, int64_t* launches, int32_t n_classes) {
+  if (!x || !ms || !launches) return fail(x, CLOVER_E_NULL, "null argument");
+  if (n_classes < KC_COUNT) return fail(x, CLOVER_E_SHAPE, "n_classes too small");
+  for (int i = 0; i < n_classes; ++i) { ms[i] = 0.0; launches[i] = 0; }
+  hipError_t e = hipStreamSynchronize(x->st);
+  if (e != hipSuccess) return fail(x, CLOVER_E_HIP, hipGetErrorString(e));
+  for (ProfEvent& ev : x->prof_events) {
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, ev.a, ev.b) == hipSuccess) { ms[ev.cls] += t; launches[ev.cls] += 1; }
+    x->prof_pool.push_back(ev);
+  }
+  x->prof_events.clear();
+  return CLOVER_OK;
+}
+
+int clover_kernel_class_count(void) { return KC_COUNT; }
+const char* clover_kernel_class_name(int32_t cls) { return (cls >= 0 && cls < KC_COUNT) ? kClassNames[cls] : ""; }
+
+const char* clover_last_error(clover_ctx* x) { return x ? x->err.c_str() : ""; }
+const char* clover_last_global_error(void) { return g_err.c_str(); }
+
+size_t clover_op_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K) {
+  if (M < 1 || N < 1 || K < 1) return 256;
+  size_t bytes = 256;
+  const int mm = std::min(M, 256);
+  if (mfma_gemm_supported(mm, N, K, 0)) {
+    const int s = mfma_gemm_pick_splits(mm, N, K, 0);
+    bytes = align256(mfma_gemm_partial_bytes(mm, N, K, 0, s)) + align256((size_t)mfma_gemm_counters(N, 0) * sizeof(int)) + 256;
+  }
+  return bytes;
+}
+
+int clover_op_gemm(int32_t path, int32_t dtype, const float* X, const void* W, float* Y, int32_t ldy, int32_t M,
+                   int32_t N, int32_t K, void* scratch, size_t scratch_bytes, void* hip_stream) {
+  if (!X || !W || !Y || !scratch) return fail(nullptr, CLOVER_E_NULL, "null argument");
+  if (M < 1 || N < 1 || K < 1 || ldy < N) return fail(nullptr, CLOVER_E_SHAPE, "bad GEMM shape");
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (path == 0) {
+    launch_gemm_generic(X, K, W, nullptr, dtype, Y, ldy, M, N, K, 0, st);
+  } else {
+    if (dtype != CLOVER_DTYPE_BF16 || M > 256 || !mfma_gemm_supported(M, N, K, 0) || (ldy % 4) != 0)
+      return fail(nullptr, CLOVER_E_SHAPE, "shape not supported by the MFMA GEMM");
+    if (scratch_bytes < clover_op_gemm_scratch_bytes(M, N, K)) return fail(nullptr, CLOVER_E_CAPACITY, "scratch too small");
+    MfmaGemm g;
+    memset(&g, 0, sizeof(g));
+    g.X = X; g.ldx = K;
+    g.W[0] = g.W[1] = g.W[2] = (const bf16_t*)W;
+    g.seg_begin[0] = 0; g.seg_begin[1] = g.seg_begin[2] = g.seg_begin[3] = 0x7fffffff;
+    g.Y = Y; g.ldy = ldy; g.M = M; g.N = N; g.K = K; g.mode = 0;
+    g.splits = mfma_gemm_pick_splits(M, N, K, 0);
+    const size_t pb = align256(mfma_gemm_partial_bytes(M, N, K, 0, g.splits));
+    g.partial = (float*)scratch;
+    g.counters = (int*)((char*)scratch + pb);
+    launch_fill_i32(g.counters, 0, mfma_gemm_counters(N, 0), st);
+    launch_gemm_mfma(g, st);
+  }
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(nullptr, CLOVER_E_HIP, hipGetErrorString(e));
+  return CLOVER_OK;
+}
+
+}  // extern "C"

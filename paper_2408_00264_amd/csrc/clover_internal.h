@@ -1,0 +1,104 @@
+// Internal declarations shared by the translation units of libclover.so.
+// Host-side launch wrappers only: every wrapper validates nothing (the C-ABI layer does) and
+// enqueues on the given stream.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace clv {
+
+typedef unsigned short bf16_t;  // raw bfloat16 bit pattern
+
+enum KernelClass {
+  KC_EMBED = 0, KC_RMSNORM, KC_GEMM_QKV, KC_ROPE_KV, KC_ATTN, KC_GEMM_WO, KC_GEMM_GATEUP, KC_GEMM_DOWN,
+  KC_GEMM_LMHEAD, KC_GEMM_DRAFT, KC_AD_GATE, KC_TOPK, KC_DRAFT_MISC, KC_ACCEPT, KC_COMPACT, KC_ELTWISE,
+  KC_COUNT
+};
+
+// Rows are laid out [B, R]; row (b,i) exists for i < n and is valid iff i < (n_valid ? n_valid[b] : n).
+struct RowMap {
+  int B, R, n;
+  const int* n_valid;  // dev [B] or null
+};
+
+struct KVLayout {
+  // K: [max_batch][max_seq][n_kv][d]; V (transposed): [max_batch][n_kv][d][max_seq]; one such pair per layer.
+  int max_batch, max_seq, n_kv, d;
+};
+
+// ---- generic (fp32 ALU) kernels; wdtype: 0 fp32, 1 bf16 ---------------------------------------
+void launch_embed(const void* table, int wdtype, const int* tok, int vocab, float* out, int ldo, int H,
+                  RowMap rm, hipStream_t st);
+void launch_rmsnorm(const float* x, int ldx, const void* gain, int wdtype, float eps, float* out, int ldo, int H,
+                    int rows, hipStream_t st);
+void launch_rope_table(const int* base_len, const int* depth /*null: row index*/, float rope_base, int d,
+                       float* cos_t, float* sin_t, RowMap rm, hipStream_t st);
+void launch_rope_kv_write(const float* qkv, int ldqkv, const float* cos_t, const float* sin_t, float* q_out, int ldq,
+                          void* k_cache, void* v_cache, int kvdtype, KVLayout kv, const int* base_len, int n_q,
+                          RowMap rm, int* err_flag, hipStream_t st);
+void launch_attn_generic(const float* q, int ldq, const void* k_cache, const void* v_cache, int kvdtype, KVLayout kv,
+                         const int* base_len, const unsigned long long* anc /*[n][2]*/, int n_q, float* out, int ldo,
+                         RowMap rm, hipStream_t st);
+// mode 0: Y = X W^T (+bias); mode 1: Y += X W^T (+bias)
+void launch_gemm_generic(const float* X, int ldx, const void* W, const void* bias, int wdtype, float* Y, int ldy,
+                         int M, int N, int K, int mode, hipStream_t st);
+void launch_swiglu(const float* g, const float* u, float* h, size_t n, hipStream_t st);
+void launch_ad_gate(const float* x, int ldx, const float* q, const float* k, const float* v, int H, int heads,
+                    float* out, int ldo, float* out2, int ldo2, int rows, hipStream_t st);
+
+// top-k of each row of z[rows, V] by (value desc, id asc); k <= CLOVER_MAX_RANK.
+// cand: scratch [rows][chunks][16] of (float,int) pairs; out_ids [rows][16]; chunks = topk_chunks(V).
+int topk_chunks(int V);
+void launch_topk(const float* z, int ldz, int V, int rows, int k, void* cand, int* out_ids, hipStream_t st);
+
+// ---- draft-tree bookkeeping -------------------------------------------------------------------
+// gather for level rows: row (b,r) <- node u = lvl_nodes[r]; xs = state[b][parent(u)], e = lm_head[token[b][u]]
+void launch_draft_gather(const float* state, const int* tokens, const int* lvl_nodes, const int* parent, int n_lvl,
+                         int B, int R, int H, const void* lm_head, int wdtype, int vocab, float* xs, float* e,
+                         float* cat /*[rows,2H], second half <- e*/, hipStream_t st);
+// state[b][u] <- s rows (also first half of cat)
+void launch_draft_scatter_state(const float* s, const int* lvl_nodes, int n_lvl, int B, int R, int H, float* state,
+                                float* cat, hipStream_t st);
+// root rows: xs_root[b] = a[b][m[b]-1]; state[b][0] = same; tokens[b][0] = next_tok[b][m[b]-1]
+void launch_draft_root(const float* a, const int* next_tok, const int* m, int B, int R, int H, float* root_x,
+                       float* state, int* tokens, hipStream_t st);
+// tokens[b][c] = ids[(b*n_par + par_row[c])*16 + rank[c]] for children c in [c0,c1); skipped when m[b] < 1
+void launch_draft_assign(const int* ids, const int* par_row, const int* rank, int c0, int c1, int n_par, int B, int R,
+                         const int* m, int* tokens, hipStream_t st);
+void launch_add_len(int* len, const int* m, int B, hipStream_t st);
+
+// ---- accept / compact -------------------------------------------------------------------------
+void launch_accept_walk(const int* argmax, const int* tokens, const int* first_child, const int* n_child, int n_nodes,
+                        int B, int R, const int* n_forced, const int* forced_next, int* m, int* acc_idx,
+                        int* new_tokens, int* next_tok, hipStream_t st);
+void launch_compact_kv(void* k_cache, void* v_cache, int kvdtype, KVLayout kv, int n_layers, size_t k_layer_elems,
+                       size_t v_layer_elems, const int* len, const int* m, const int* acc_idx, int B, int R,
+                       hipStream_t st);
+void launch_gather_hidden(const float* hidden, const int* acc_idx, const int* m, int B, int R, int H, float* hid_acc,
+                          hipStream_t st);
+void launch_read_kv(const void* k_cache, const void* v_cache, int kvdtype, KVLayout kv, int b, int slot0, int n_slots,
+                    float* k_out, float* v_out, hipStream_t st);
+void launch_fill_i32(int* p, int v, int n, hipStream_t st);
+
+// ---- MFMA weight-streaming GEMM (bf16 weights, fp32 activations in, fp32 out) -------------------
+struct MfmaGemm {
+  const float* X; int ldx;
+  const bf16_t* W[3];      // up to three row-segments (fused QKV); plain GEMM uses W[0]
+  int seg_begin[4];        // segment s covers output columns [seg_begin[s], seg_begin[s+1])
+  const bf16_t* W_up;      // mode 2: second matrix (W[0] = gate)
+  const bf16_t* bias;      // optional [N]
+  float* Y; int ldy;
+  int M, N, K;
+  int mode;                // 0 store, 1 add into Y, 2 Y = silu(X Wg^T) * (X Wu^T)
+  int splits;              // split-K factor (>=1)
+  float* partial;          // scratch for split-K partial tiles
+  int* counters;           // one int per workgroup column, zero before and after each launch
+};
+bool mfma_gemm_supported(int M, int N, int K, int mode);
+int mfma_gemm_pick_splits(int M, int N, int K, int mode);
+size_t mfma_gemm_partial_bytes(int M, int N, int K, int mode, int splits);
+int mfma_gemm_counters(int N, int mode);
+void launch_gemm_mfma(const MfmaGemm& g, hipStream_t st);
+
+}  // namespace clv

@@ -1,0 +1,255 @@
+"""Lock-step parity harness: the HIP path (through the C ABI) beside the CPU oracle.
+
+Both sides get identical seeded weights and inputs every call.  Integer results must be
+identical except inside the tie zone: a GPU argmax / rank choice is tolerated only if, under the
+ORACLE's logits, its value is within `tol` of the oracle's own choice; the oracle then follows
+the GPU's choice so later calls stay comparable.  Everything else is compared element-wise.
+"""
+from __future__ import annotations
+
+from typing import Callable, Dict, List, Optional
+
+import numpy as np
+
+from oracle import clover2_oracle as O
+from paper_2408_00264_amd import clover, synth
+
+
+def bfs_tree_random(rng, n, max_depth, max_kids=4):
+    """Random rooted tree in true breadth-first order with distinct sibling ranks."""
+    parent, rank, depth = [-1], [0], [0]
+    frontier = [0]
+    while len(parent) < n and frontier:
+        nxt = []
+        for u in frontier:
+            if depth[u] >= max_depth:
+                continue
+            k = int(rng.integers(0, max_kids + 1))
+            if u == 0 or (not nxt and u == frontier[-1]):
+                k = max(k, 1)
+            ranks = rng.permutation(8)[:k]
+            for r in sorted(ranks):
+                if len(parent) >= n:
+                    break
+                parent.append(u); rank.append(int(r)); depth.append(depth[u] + 1)
+                nxt.append(len(parent) - 1)
+        frontier = nxt
+    return np.asarray(parent, np.int32), np.asarray(rank, np.int32)
+
+
+class Lockstep:
+    def __init__(self, shape, parent, rank, max_seq: int, flags: int = 0, gain_jitter: float = 0.0,
+                 oracle_dtype=np.float64, max_nodes: Optional[int] = None, batch: int = 1,
+                 overrides: Optional[Dict[str, np.ndarray]] = None):
+        self.shape = shape
+        self.parent = np.asarray(parent, np.int32)
+        self.rank = np.asarray(rank, np.int32)
+        self.tol = 3e-2 if shape.bf16 else 1e-4
+        self.store = synth.WeightStore(shape, gain_jitter=gain_jitter, overrides=overrides)
+        self.ocfg = O.OracleConfig.from_shape(shape, max_seq, oracle_dtype)
+        self.W = O.Weights(self.store.get_f32, oracle_dtype)
+        self.B = batch
+        self.R = max_nodes or len(parent)
+        self.dev_w = clover.upload_weights(self.store)
+        self.gpu = clover.Clover(shape, self.dev_w, self.parent, self.rank, batch, max_seq, self.R, flags)
+        self.seqs = [O.SeqState(self.ocfg) for _ in range(batch)]
+        self.acc: List[dict] = [None] * batch
+        self.tie_events = 0
+        self.max_logit_err = 0.0
+        self.max_hidden_err = 0.0
+
+    # ------------------------------------------------------------------------------------
+    def _check_draft(self, b: int, gpu_tokens: np.ndarray, parent, rank) -> None:
+        """Oracle draft for sequence b on the oracle's own hand-off state, following the GPU's tokens."""
+        acc = self.acc[b]
+        toks, zs = O.draft_tree(self.W, self.ocfg, self.seqs[b], acc["hid_acc"], acc["next_tok"], parent, rank,
+                                forced_tokens=gpu_tokens)
+        assert int(gpu_tokens[0]) == int(acc["next_tok"][-1]), "root token"
+        kids = O.children_of(parent)
+        for u, z in zs.items():
+            need = 1 + max(rank[c] for c in kids[u])
+            top = O.ranked_ids(z, need)
+            got = [int(gpu_tokens[c]) for c in kids[u]]
+            assert len(set(got)) == len(got), f"duplicate sibling tokens under node {u}"
+            for c in kids[u]:
+                want = int(top[rank[c]])
+                if int(gpu_tokens[c]) != want:
+                    gap = abs(float(z[want]) - float(z[int(gpu_tokens[c])]))
+                    assert gap <= self.tol, (f"seq {b} node {c} (rank {rank[c]} of node {u}): gpu token "
+                                             f"{int(gpu_tokens[c])} vs oracle {want}, oracle logit gap {gap:.3e}")
+                    self.tie_events += 1
+
+    def prefill(self, prompts: List[np.ndarray], chunk: int) -> None:
+        g = self.gpu
+        g.prefill(prompts, self.parent, self.rank, chunk)
+        g.torch.cuda.synchronize()
+        toks = g.tree_tokens.cpu().numpy()
+        lens = g.seq_len()
+        for b, p in enumerate(prompts):
+            # oracle prefill, chunked the same way (right-aligned ragged first chunk does not matter
+            # to the result: a chain is plain decoding whatever the chunking)
+            seq = self.seqs[b]
+            n_chunks_b = (len(p) + chunk - 1) // chunk
+            acc = None
+            for ci in range(n_chunks_b):
+                part = [int(t) for t in p[ci * chunk:(ci + 1) * chunk]]
+                chain = list(range(-1, len(part) - 1))
+                hidden, logits = O.verify_tree(self.W, self.ocfg, seq, part, chain)
+                nxt = int(p[(ci + 1) * chunk]) if (ci + 1) * chunk < len(p) else -1
+                if nxt < 0:
+                    # the bonus token is an argmax: follow the GPU inside the tie zone
+                    gpu_bonus = int(toks[b, 0])
+                    best = int(O.ranked_ids(logits[len(part) - 1], 1)[0])
+                    if gpu_bonus != best:
+                        gap = float(logits[len(part) - 1][best] - logits[len(part) - 1][gpu_bonus])
+                        assert gap <= self.tol, f"prefill bonus token: gpu {gpu_bonus} oracle {best} gap {gap:.3e}"
+                        self.tie_events += 1
+                    nxt_eff = gpu_bonus
+                else:
+                    nxt_eff = nxt
+                acc = O.accept_forced(seq, part, logits, hidden, len(part), nxt_eff)
+                if ci < n_chunks_b - 1:
+                    O.draft_tree(self.W, self.ocfg, seq, acc["hid_acc"], acc["next_tok"], [-1], [0])
+            self.acc[b] = acc
+            assert lens[b] == seq.L == len(p), (lens[b], seq.L, len(p))
+            self._check_draft(b, toks[b, :len(self.parent)], self.parent, self.rank)
+            assert seq.aug_L == seq.L
+            self.compare_kv(b, 0, seq.L)
+
+    def compare_kv(self, b: int, slot0: int, slot1: int, atol: Optional[float] = None, stacks=(0, 1)) -> None:
+        """Target and augmenting-block cache rows [slot0, slot1) against the oracle's."""
+        atol = atol if atol is not None else (4e-2 if self.shape.bf16 else 1e-4)
+        if slot1 <= slot0:
+            return
+        seq = self.seqs[b]
+        for stack, n_layers, kv in ((0, self.shape.n_layers, seq.kv), (1, self.shape.aug_layers, seq.aug_kv)):
+            if stack not in stacks:
+                continue
+            for l in range(n_layers):
+                k, v = self.gpu.read_kv(stack, l, b, slot0, slot1 - slot0)
+                ek = np.abs(k - kv.k[l, slot0:slot1]).max()
+                ev = np.abs(v - kv.v[l, slot0:slot1]).max()
+                assert ek <= atol and ev <= atol, f"KV stack {stack} layer {l} seq {b}: |dK| {ek:.3e} |dV| {ev:.3e}"
+
+    def step(self, tree_hook: Optional[Callable[[int, np.ndarray], np.ndarray]] = None,
+             check_compaction_bits: bool = True) -> List[int]:
+        """One speculative step on both sides; returns the accepted lengths."""
+        g, B, N = self.gpu, self.B, len(self.parent)
+        torch = g.torch
+        if tree_hook is not None:
+            t = g.tree_tokens.cpu().numpy()
+            for b in range(B):
+                t[b, :N] = tree_hook(b, t[b, :N].copy())
+            g.tree_tokens.copy_(torch.from_numpy(t))
+        tokens = g.tree_tokens.cpu().numpy()
+        L_before = g.seq_len()
+        g.verify_tree(B)
+        torch.cuda.synchronize()
+        logits = g.logits.cpu().numpy()
+        hidden = g.hidden.cpu().numpy()
+        pre_kv = [[g.read_kv(0, l, b, int(L_before[b]), N) for l in range(self.shape.n_layers)] for b in range(B)]
+        g.accept_and_compact(B)
+        torch.cuda.synchronize()
+        m = g.m.cpu().numpy(); acc_idx = g.acc_idx.cpu().numpy(); new_tokens = g.new_tokens.cpu().numpy()
+        next_tok = g.next_tok.cpu().numpy(); hid_acc = g.hid_acc.cpu().numpy()
+        L_after = g.seq_len()
+        ms = []
+        for b in range(B):
+            seq = self.seqs[b]
+            assert seq.L == L_before[b]
+            o_hidden, o_logits = O.verify_tree(self.W, self.ocfg, seq, tokens[b, :N], self.parent)
+            le = float(np.abs(logits[b, :N] - o_logits).max())
+            he = float(np.abs(hidden[b, :N] - o_hidden).max())
+            self.max_logit_err = max(self.max_logit_err, le)
+            self.max_hidden_err = max(self.max_hidden_err, he)
+            assert le <= self.tol, f"seq {b}: logits max-abs error {le:.3e} > {self.tol}"
+            # uncompacted tree rows of the cache (read back before the GPU compacted them)
+            atol = 4e-2 if self.shape.bf16 else 1e-4
+            for l in range(self.shape.n_layers):
+                ek = np.abs(pre_kv[b][l][0] - seq.kv.k[l, seq.L:seq.L + N]).max()
+                ev = np.abs(pre_kv[b][l][1] - seq.kv.v[l, seq.L:seq.L + N]).max()
+                assert ek <= atol and ev <= atol, f"tree KV rows layer {l} seq {b}: |dK| {ek:.3e} |dV| {ev:.3e}"
+            # acceptance: the GPU's implied argmax at each visited node must be (near-)optimal for the oracle
+            mb = int(m[b])
+            path = [int(a) for a in acc_idx[b, :mb]]
+            assert mb >= 1 and path[0] == 0
+            implied = {}
+            for i, u in enumerate(path):
+                implied[u] = int(tokens[b, path[i + 1]]) if i + 1 < mb else int(new_tokens[b, mb - 1])
+            override = {}
+            for u, t in implied.items():
+                best = int(O.ranked_ids(o_logits[u], 1)[0])
+                if t != best:
+                    gap = float(o_logits[u][best] - o_logits[u][t])
+                    assert gap <= self.tol, f"seq {b} node {u}: gpu argmax {t} vs oracle {best}, gap {gap:.3e}"
+                    override[u] = t
+                    self.tie_events += 1
+            acc = O.accept_and_compact(self.ocfg, seq, tokens[b, :N], o_logits, o_hidden, self.parent, override)
+            assert acc["path"] == path, f"seq {b}: accepted path gpu {path} oracle {acc['path']}"
+            assert acc["new_tokens"] == [int(t) for t in new_tokens[b, :mb]]
+            assert acc["next_tok"] == [int(t) for t in next_tok[b, :mb]]
+            assert L_after[b] == seq.L
+            he2 = float(np.abs(hid_acc[b, :mb] - acc["hid_acc"]).max())
+            assert he2 <= max(he, 1e-12) + 1e-12
+            np.testing.assert_array_equal(hid_acc[b, :mb], hidden[b, path])       # the gather itself is exact
+            if check_compaction_bits:
+                for l in range(self.shape.n_layers):
+                    k2, v2 = g.read_kv(0, l, b, int(L_before[b]), mb)
+                    np.testing.assert_array_equal(k2, pre_kv[b][l][0][path])      # compaction moves bits
+                    np.testing.assert_array_equal(v2, pre_kv[b][l][1][path])
+            self.acc[b] = acc
+            ms.append(mb)
+        g.draft_tree(B)
+        torch.cuda.synchronize()
+        toks = g.tree_tokens.cpu().numpy()
+        for b in range(B):
+            self._check_draft(b, toks[b, :N], self.parent, self.rank)
+            assert self.seqs[b].aug_L == self.seqs[b].L
+            self.compare_kv(b, self.seqs[b].L - ms[b], self.seqs[b].L)
+        return ms
+
+
+def truth_hook_factory(ls: Lockstep, want: List[int]):
+    """tree_hook that plants the target's true greedy continuation (computed by the oracle from
+    its current state, token by token) down one root path for want[step]-1 levels and wrong
+    tokens elsewhere (random-init drafts almost never match on their own)."""
+    parent = ls.parent
+    kids = O.children_of(parent)
+    n = len(parent)
+    height = np.zeros(n, dtype=np.int64)
+    for u in range(n - 1, 0, -1):
+        height[parent[u]] = max(height[parent[u]], height[u] + 1)
+    state = {"step": 0}
+
+    def continuation(seq, root: int, k: int) -> List[int]:
+        c = O.SeqState(ls.ocfg)
+        c.kv = seq.kv.copy()
+        c.L = seq.L
+        out, t = [], int(root)
+        for _ in range(k):
+            _, lg = O.verify_tree(ls.W, ls.ocfg, c, [t], [-1])
+            c.L += 1
+            t = int(O.ranked_ids(lg[0], 1)[0])
+            out.append(t)
+        return out
+
+    def hook(b: int, tokens: np.ndarray) -> np.ndarray:
+        w = want[state["step"]]
+        truth = continuation(ls.seqs[b], int(tokens[0]), max(w, 1))
+        rng = np.random.default_rng(1000 * state["step"] + b)
+        tokens[1:] = (truth[0] + 1 + rng.integers(1, 50, n - 1)) % ls.shape.vocab
+        u = 0
+        for lvl in range(w - 1):
+            if not kids[u]:
+                break
+            c = max(kids[u], key=lambda c_: (height[c_], c_))
+            tokens[c] = truth[lvl]
+            for s_ in kids[u]:                      # siblings stay distinct from the planted token
+                if s_ != c and tokens[s_] == tokens[c]:
+                    tokens[s_] = (tokens[s_] + 1) % ls.shape.vocab
+            u = c
+        if b == ls.B - 1:
+            state["step"] += 1
+        return tokens
+
+    return hook

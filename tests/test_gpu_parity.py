@@ -1,0 +1,185 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle (run with -m gpu)."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+from paper_2408_00264_amd import clover, synth
+
+pytestmark = pytest.mark.gpu
+
+TINY = synth.CONFIGS[1]
+# reduced bf16 shape with the structure of the LLaMA3-8B-shaped workload (GQA, head_dim 128)
+MINI = synth.scaled(synth.CONFIGS[3], name="mini-bf16", n_layers=2, hidden=512, n_q_heads=4, n_kv_heads=2,
+                    ffn=1536, vocab=8192, tree_k=(4, 3, 2, 2), tree_nodes=24, draft_depths=4, seed=11)
+
+
+def _torch():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return torch
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+# ------------------------------------------------------------------------------------------
+# GEMM operator
+# ------------------------------------------------------------------------------------------
+GEMM_CASES = [
+    # path, dtype, M, N, K
+    (0, 0, 16, 1024, 256), (0, 0, 5, 77, 100), (0, 1, 64, 512, 512), (0, 1, 33, 130, 264),
+    (1, 1, 64, 6144, 4096), (1, 1, 5, 4096, 8192), (1, 1, 16, 4096, 4096), (1, 1, 24, 1024, 512),
+    (1, 1, 96, 4096, 14336), (1, 1, 256, 4096, 4096), (1, 1, 1, 32000, 4096), (1, 1, 130, 8192, 512),
+    (1, 1, 64, 160, 256),
+]
+
+
+@pytest.mark.parametrize("path,dtype,M,N,K", GEMM_CASES)
+def test_op_gemm(path, dtype, M, N, K):
+    torch = _torch()
+    say(f"gemm path={path} dtype={dtype} M={M} N={N} K={K}")
+    lib = clover.load_library()
+    rng = np.random.default_rng(M * 7 + N * 3 + K)
+    X = rng.standard_normal((M, K)).astype(np.float32)
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    if dtype == 1:
+        Wb = synth.f32_to_bf16_bits(W)
+        Wf = synth.bf16_bits_to_f32(Wb).astype(np.float64)
+        Wd = torch.from_numpy(Wb.view(np.int16)).cuda()
+    else:
+        Wf = W.astype(np.float64)
+        Wd = torch.from_numpy(W).cuda()
+    Xd = torch.from_numpy(X).cuda()
+    ldy = N + 4
+    Y = torch.full((M, ldy), -7.0, dtype=torch.float32, device="cuda")
+    nb = lib.clover_op_gemm_scratch_bytes(M, N, K)
+    scratch = torch.zeros(nb, dtype=torch.uint8, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    for rep in range(2):       # twice: the split-K counters must be back at zero
+        rc = lib.clover_op_gemm(path, dtype, C.c_void_p(Xd.data_ptr()), C.c_void_p(Wd.data_ptr()),
+                                C.c_void_p(Y.data_ptr()), ldy, M, N, K, C.c_void_p(scratch.data_ptr()), nb,
+                                C.c_void_p(st))
+        assert rc == 0, lib.clover_last_global_error()
+        torch.cuda.synchronize()
+        got = Y.cpu().numpy()
+        assert np.all(got[:, N:] == -7.0)
+        if path == 1:   # the MFMA path feeds bf16-rounded activations
+            Xr = synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(X)).astype(np.float64)
+            ref = Xr @ Wf.T
+            scale = np.sqrt(K) * 0.02
+            assert np.abs(got[:, :N] - ref).max() <= 2e-5 * scale * 10
+        ref = X.astype(np.float64) @ Wf.T
+        tol = (1e-5 if path == 0 else 1.5e-2) * np.sqrt(K) * 0.02 * 4
+        err = np.abs(got[:, :N] - ref).max()
+        assert err <= tol, (err, tol)
+
+
+# ------------------------------------------------------------------------------------------
+# whole calls, lock-step with the oracle
+# ------------------------------------------------------------------------------------------
+def _lockstep(shape, flags=0, gain_jitter=0.0, batch=1, max_seq=256, tree=None, max_nodes=None):
+    from tests.parity import Lockstep
+    parent, rank = tree if tree is not None else synth.tree_for(shape)
+    return Lockstep(shape, parent, rank, max_seq, flags=flags, gain_jitter=gain_jitter, batch=batch,
+                    max_nodes=max_nodes)
+
+
+def test_config1_fp32_eight_steps():
+    _torch()
+    ls = _lockstep(TINY, max_seq=256)
+    prompts = synth.make_prompts(TINY)
+    say("config 1: prefill 64 tokens in chunks of 16")
+    ls.prefill(prompts, chunk=16)
+    for s in range(TINY.steps):
+        ms = ls.step()
+        say(f"  step {s}: m={ms} max|dlogit|={ls.max_logit_err:.2e} ties={ls.tie_events}")
+    assert ls.max_logit_err <= 1e-4
+
+
+def test_config1_gain_jitter_injected_accept_lengths():
+    _torch()
+    from tests.parity import truth_hook_factory
+    ls = _lockstep(TINY, gain_jitter=0.1, max_seq=256)
+    prompts = [synth.make_prompts(TINY, seed=5)[0][:37]]        # ragged last chunk
+    ls.prefill(prompts, chunk=16)
+    want = [4, 1, 3, 2, 4, 2]
+    hook = truth_hook_factory(ls, want)
+    got = []
+    for s in range(len(want)):
+        ties = ls.tie_events
+        ms = ls.step(tree_hook=hook)
+        say(f"  step {s}: want {want[s]} got {ms}")
+        if ls.tie_events == ties:
+            assert ms == [want[s]]
+        got.append(ms[0])
+    assert max(got) == 4 and min(got) == 1
+
+
+@pytest.mark.parametrize("flags", [clover.FLAG_GENERIC, 0], ids=["generic", "mfma"])
+def test_mini_bf16(flags):
+    _torch()
+    from tests.parity import truth_hook_factory
+    ls = _lockstep(MINI, flags=flags, gain_jitter=0.1, max_seq=512)
+    prompts = [synth.make_prompts(MINI, seed=3)[0][:150]]
+    say(f"mini bf16 flags={flags}: prefill 150 tokens in chunks of 24")
+    ls.prefill(prompts, chunk=24)
+    want = [5, 1, 2, 4, 3]
+    hook = truth_hook_factory(ls, want)
+    for s in range(len(want)):
+        ties = ls.tie_events
+        ms = ls.step(tree_hook=hook)
+        say(f"  step {s}: want {want[s]} got {ms} max|dlogit|={ls.max_logit_err:.2e} ties={ls.tie_events}")
+        if ls.tie_events == ties:
+            assert ms == [want[s]]
+    for s in range(2):
+        ms = ls.step()
+        say(f"  free step {s}: m={ms} max|dlogit|={ls.max_logit_err:.2e}")
+    assert ls.max_logit_err <= 3e-2
+
+
+def test_mini_bf16_batch_ragged():
+    _torch()
+    shape = synth.scaled(MINI, batch=3, tree_nodes=12, tree_k=(3, 2, 2, 1), prompt_len=(20, 90), seed=13)
+    ls = _lockstep(shape, batch=3, max_seq=256, max_nodes=16)
+    prompts = synth.make_prompts(shape)
+    say("ragged batch prompt lengths", [len(p) for p in prompts])
+    ls.prefill(prompts, chunk=16)
+    for s in range(3):
+        ms = ls.step()
+        say(f"  step {s}: m={ms} max|dlogit|={ls.max_logit_err:.2e} ties={ls.tie_events}")
+
+
+def test_random_tree_and_chain_mask():
+    """Tree attention against the oracle for a random topology (ancestor bit masks, tree-depth positions)."""
+    _torch()
+    from tests.parity import bfs_tree_random
+    rng = np.random.default_rng(21)
+    parent, rank = bfs_tree_random(rng, 16, 3)
+    say("random tree parents", parent.tolist())
+    ls = _lockstep(TINY, gain_jitter=0.1, tree=(parent, rank), max_seq=128, max_nodes=16)
+    ls.prefill([synth.make_prompts(TINY, seed=8)[0][:21]], chunk=8)
+    for s in range(2):
+        ls.step()
+    assert ls.max_logit_err <= 1e-4
+
+
+# ------------------------------------------------------------------------------------------
+# error paths reachable without touching the kernels
+# ------------------------------------------------------------------------------------------
+def test_capacity_and_shape_errors():
+    _torch()
+    ls = _lockstep(TINY, max_seq=40)
+    g = ls.gpu
+    with pytest.raises(clover.CloverError) as e:
+        g.verify_tree(2)
+    assert e.value.code == clover.E_SHAPE
+    ls.prefill([synth.make_prompts(TINY, seed=2)[0][:16]], chunk=16)
+    g.verify_tree(1)
+    g.accept_and_compact(1)
+    with pytest.raises(clover.CloverError) as e:      # the host-side length bound grows by D+1 per step
+        for _ in range(6):
+            g.draft_tree(1); g.verify_tree(1); g.accept_and_compact(1)
+    assert e.value.code == clover.E_CAPACITY
+    assert g.seq_len()[0] <= 40
