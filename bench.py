@@ -1,0 +1,222 @@
+#!/usr/bin/env python3
+"""Benchmark of one Clover-2 speculative step (draft_tree -> verify_tree -> accept_and_compact)
+on one MI355X.  Prints ONE JSON line.
+
+  python bench.py --gpus 1 --steps K --warmup W [--config 3]
+
+A "step" is one pass of the whole hot path over one batch of synthetic input (weights and KV
+cache resident in HBM, prompt prefilled before the timed region).  The default workload is the
+LLaMA3-8B-shaped batch-1 configuration (64-node tree over 1024 cached tokens).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def verify_bytes(shape, B, N, L_sum):
+    """Algorithmic HBM bytes of one verify_tree: every target weight once (2 bytes each), the
+    cached K/V rows read once, the new K/V rows written once."""
+    H, d = shape.hidden, shape.head_dim
+    nq, nkv, F, V = shape.n_q_heads, shape.n_kv_heads, shape.ffn, shape.vocab
+    per_layer = (nq * d * H) + 2 * (nkv * d * H) + (H * nq * d) + 3 * F * H
+    weights = 2 * (shape.n_layers * per_layer + V * H)
+    kv_row = 2 * nkv * d * 2
+    kv_read = shape.n_layers * kv_row * (L_sum + B * N)
+    kv_write = shape.n_layers * kv_row * B * N
+    return weights + kv_read + kv_write
+
+
+def draft_bytes(shape, n_levels):
+    H, d = shape.hidden, shape.head_dim
+    nq, nkv, F, V = shape.n_q_heads, shape.n_kv_heads, shape.ffn, shape.vocab
+    per_layer = (nq * d * H) + 2 * (nkv * d * H) + (H * nq * d) + 3 * F * H
+    w = 3 * H * H + shape.aug_layers * per_layer + H * H + (n_levels - 1) * (3 * H * H + 2 * H * H) + n_levels * V * H
+    return 2 * w
+
+
+def cpu_baseline(shape, parent, rank, L, sample_layers, store):
+    """The oracle, as it stands, timed on this host on a bounded sample of the same workload:
+    `sample_layers` decoder layers of the verify pass (scaled to all layers), the LM head, the
+    acceptance and one full draft_tree, for one sequence with L cached tokens."""
+    from oracle import clover2_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    N = len(parent)
+    dt = np.float32
+    cfg = O.OracleConfig.from_shape(shape, L + 2 * N + 16, dt)
+    cfg.n_layers = sample_layers
+    W = O.Weights(store.get_f32, dt)
+    rng = np.random.default_rng(0)
+    seq = O.SeqState(cfg)
+    seq.kv.k[:, :L] = rng.standard_normal(seq.kv.k[:, :L].shape, dtype=dt)
+    seq.kv.v[:, :L] = rng.standard_normal(seq.kv.v[:, :L].shape, dtype=dt)
+    seq.aug_kv.k[:, :L] = rng.standard_normal(seq.aug_kv.k[:, :L].shape, dtype=dt)
+    seq.aug_kv.v[:, :L] = rng.standard_normal(seq.aug_kv.v[:, :L].shape, dtype=dt)
+    seq.L = seq.aug_L = L
+    tokens = rng.integers(0, shape.vocab, N)
+    # touch every weight once so conversion to fp32 is outside the timing
+    O.verify_tree(W, cfg, seq, tokens[:1], [-1])
+    t0 = time.perf_counter()
+    x = W("embed")[tokens].astype(dt)
+    depth = O.tree_depths(parent)
+    vis = O.ancestor_matrix(parent)
+    for li in range(sample_layers):
+        x = O.decoder_layer(W, f"layers.{li}.", cfg, x, seq.kv, li, L, L + depth, L + np.arange(N), vis)
+    t1 = time.perf_counter()
+    logits = O.rmsnorm(x, W("final_norm"), cfg.rms_eps) @ W("lm_head").T
+    acc = O.accept_and_compact(cfg, seq, tokens, logits, x, parent)
+    t2 = time.perf_counter()
+    O.draft_tree(W, cfg, seq, acc["hid_acc"], acc["next_tok"], parent, rank)      # warm the draft weights
+    seq.aug_L = L
+    t3 = time.perf_counter()
+    O.draft_tree(W, cfg, seq, acc["hid_acc"], acc["next_tok"], parent, rank)
+    t4 = time.perf_counter()
+    step_s = (t1 - t0) * shape.n_layers / sample_layers + (t2 - t1) + (t4 - t3)
+    return {"value": N / step_s, "unit": "tree-tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"1 sequence, L={L}, {N}-node tree: {sample_layers} of {shape.n_layers} verify layers timed "
+                      f"({t1 - t0:.2f}s, scaled), LM head + accept ({t2 - t1:.2f}s), full draft_tree ({t4 - t3:.2f}s); "
+                      f"fp32 NumPy", "est_step_ms": step_s * 1e3}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--layers", type=int, default=0, help="debug: override the number of target layers")
+    ap.add_argument("--prompt", type=int, default=0, help="debug: override the prompt length")
+    ap.add_argument("--flags", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-layers", type=int, default=2)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+            "(the speculative step of one sequence batch lives on one device)")
+        sys.exit(2)
+
+    import torch
+    from paper_2408_00264_amd import clover, synth
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(1)
+    shape = synth.CONFIGS[args.config]
+    if args.layers:
+        shape = synth.scaled(shape, n_layers=args.layers)
+    if args.prompt:
+        shape = synth.scaled(shape, prompt_len=(args.prompt, args.prompt))
+    B, N, D = shape.batch, shape.tree_nodes, shape.draft_depths
+    parent, rank = synth.tree_for(shape)
+    prompts = synth.make_prompts(shape)
+    K, Wm = args.steps, args.warmup
+    n_passes = 2 * K + Wm + 4
+    max_seq = max(len(p) for p in prompts) + n_passes * (D + 1) + 2 * N + 64
+    max_seq = (max_seq + 255) // 256 * 256
+
+    t0 = time.time()
+    store = synth.WeightStore(shape)
+    keep = []
+    if not args.no_cpu_baseline:
+        sl = min(args.cpu_sample_layers, shape.n_layers)
+        keep = [n for n in store.names() if not n.startswith("layers.") or int(n.split(".")[1]) < sl]
+    dev_w = clover.upload_weights(store, keep_host=keep)
+    log(f"[bench] weights generated and uploaded in {time.time() - t0:.1f}s")
+    g = clover.Clover(shape, dev_w, parent, rank, B, max_seq, N, flags=args.flags)
+    t0 = time.time()
+    g.prefill(prompts, parent, rank)
+    torch.cuda.synchronize()
+    lens0 = g.seq_len()
+    log(f"[bench] prefill of {[len(p) for p in prompts]} tokens in {time.time() - t0:.1f}s; lengths {lens0[:B].tolist()}")
+
+    def run_steps(n, events=None):
+        for i in range(n):
+            if events is not None:
+                ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+                ev[0].record(); g.verify_tree(B); ev[1].record(); g.accept_and_compact(B); ev[2].record()
+                g.draft_tree(B); ev[3].record()
+                events.append(ev)
+            else:
+                g.verify_tree(B); g.accept_and_compact(B); g.draft_tree(B)
+
+    run_steps(Wm)
+    torch.cuda.synchronize()
+    g.seq_len()
+    # ---- timed region: exactly K steps ----
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_steps(K)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    lens1 = g.seq_len()
+    # ---- second pass of K steps with per-call events and per-kernel-class events ----
+    g.profile_enable(True)
+    events = []
+    torch.cuda.synchronize()
+    run_steps(K, events)
+    torch.cuda.synchronize()
+    prof = g.profile_collect()
+    g.profile_enable(False)
+    lens2 = g.seq_len()
+    ver = np.array([e[0].elapsed_time(e[1]) for e in events])
+    acc = np.array([e[1].elapsed_time(e[2]) for e in events])
+    dra = np.array([e[2].elapsed_time(e[3]) for e in events])
+    L_sum = int(lens1[:B].sum())
+    vbytes = verify_bytes(shape, B, N, L_sum)
+    n_levels = D
+    dbytes = draft_bytes(shape, n_levels)
+    # dominant kernel: the fused gate/up projection (largest weight stream of a layer)
+    gu_ms, gu_n = prof["gemm_gate_up"]
+    gu_bytes = 2 * 2 * shape.ffn * shape.hidden
+    gu_avg_ms = gu_ms / max(gu_n, 1)
+    achieved = gu_bytes / (gu_avg_ms * 1e-3) / 1e9 if gu_n else 0.0
+    kernels = {k: {"ms_per_step": v[0] / K, "launches_per_step": v[1] / K} for k, v in prof.items() if v[1]}
+    out = {
+        "metric": "verified tree-tokens/s over the whole speculative step (draft_tree + verify_tree + accept_and_compact)",
+        "value": B * N / (ms_per_step * 1e-3), "unit": "tree-tokens/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if shape.bf16 else "f32", "data": "synthetic",
+        "config": {"workload": f"config {args.config}: {shape.name}, batch {B}, {N}-node tree, "
+                               f"cached lengths {lens1[:B].tolist()}, {shape.n_layers} layers",
+                   "accepted_per_step": float((lens2[:B] - lens1[:B]).sum()) / (K * B)},
+        "calls_ms": {"verify_tree": {"median": float(np.median(ver)), "p10": float(np.percentile(ver, 10)),
+                                     "p90": float(np.percentile(ver, 90))},
+                     "accept_and_compact": {"median": float(np.median(acc))},
+                     "draft_tree": {"median": float(np.median(dra))}},
+        "verify_hbm": {"algorithmic_bytes": vbytes, "GBps": vbytes / (float(np.median(ver)) * 1e-3) / 1e9,
+                       "frac_of_peak": vbytes / (float(np.median(ver)) * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       "tree_tokens_per_s": B * N / (float(np.median(ver)) * 1e-3)},
+        "draft_hbm": {"algorithmic_bytes": dbytes, "GBps": dbytes / (float(np.median(dra)) * 1e-3) / 1e9},
+        "roofline": {"kernel": "gemm_gate_up (fused SwiGLU projection)", "bound": "hbm", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": gu_bytes, "avg_launch_ms": gu_avg_ms},
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        t0 = time.time()
+        out["cpu_baseline"] = cpu_baseline(shape, parent, rank, int(lens0[0]), min(args.cpu_sample_layers, shape.n_layers), store)
+        log(f"[bench] cpu baseline in {time.time() - t0:.1f}s")
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -297,17 +297,26 @@ class Clover:
         self.draft_tree(batch)
 
 
-def upload_weights(store, device: str = "cuda:0", names: Optional[Sequence[str]] = None, drop_host: bool = False):
-    """Copy a synth.WeightStore to the GPU: bf16 tensors for bf16 models, fp32 otherwise."""
+def upload_weights(store, device: str = "cuda:0", names: Optional[Sequence[str]] = None,
+                   keep_host: Optional[Sequence[str]] = None, threads: int = 0, group: int = 24):
+    """Copy a synth.WeightStore to the GPU: bf16 tensors for bf16 models, fp32 otherwise.
+    Tensors are generated `group` at a time on `threads` host threads and dropped from host
+    memory after the copy unless listed in `keep_host` (None keeps all)."""
     import torch
+    names = list(names or store.names())
+    keep = None if keep_host is None else set(keep_host)
+    threads = threads or min(16, os.cpu_count() or 1)
     out = {}
-    for n in (names or store.names()):
-        a = store.get(n)
-        if a.dtype == np.uint16:
-            t = torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
-        else:
-            t = torch.from_numpy(a).to(device)
-        out[n] = t.contiguous()
-        if drop_host:
-            store.drop(n)
+    for g0 in range(0, len(names), group):
+        part = names[g0:g0 + group]
+        store.prefetch(part, threads=threads)
+        for n in part:
+            a = store.get(n)
+            if a.dtype == np.uint16:
+                t = torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+            else:
+                t = torch.from_numpy(a).to(device)
+            out[n] = t.contiguous()
+            if keep is not None and n not in keep:
+                store.drop(n)
     return out

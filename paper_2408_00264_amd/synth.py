@@ -7,9 +7,9 @@ and the HIP path can be fed from it without sharing any computation.
 
 Recipes
 -------
-* Weights: every tensor is drawn N(0, std=0.02) from its own counter-based
-  Philox stream keyed by (seed, crc32(tensor name)), so a tensor's values do
-  not depend on which other tensors were generated or in what order.
+* Weights: every tensor is drawn N(0, std=0.02) from its own SFC64 stream
+  seeded by (key, seed, crc32(tensor name)), so a tensor's values do not
+  depend on which other tensors were generated or in what order.
   Norm gains are 1.0 (optionally 1 + gain_jitter*N(0,1) for stronger tests).
   For bf16 models each tensor is rounded once to bf16 (round-to-nearest-even)
   and handed out as uint16 bit patterns; `bf16_bits_to_f32` widens them.
@@ -28,7 +28,7 @@ from typing import Dict, Iterable, List, Sequence, Tuple
 
 import numpy as np
 
-WEIGHT_KEY = 240800264  # Philox key word shared by all weight streams
+WEIGHT_KEY = 240800264  # seed word shared by all weight streams
 
 
 @dataclass(frozen=True)
@@ -88,11 +88,23 @@ def scaled(shape: ModelShape, **kw) -> ModelShape:
 # ----------------------------------------------------------------------------
 # bf16 bit patterns
 # ----------------------------------------------------------------------------
-def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
-    """Round float32 to bfloat16 (nearest, ties to even); returns uint16 bits."""
+def _f32_to_bf16_bits_np(x: np.ndarray) -> np.ndarray:
     u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
     r = (u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))) >> np.uint32(16)
     return r.astype(np.uint16)
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 to bfloat16 (nearest, ties to even); returns uint16 bits.
+    Large arrays go through torch's CPU conversion (same rounding, much faster)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if x.size >= (1 << 20):
+        try:
+            import torch
+            return torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        except ImportError:
+            pass
+    return _f32_to_bf16_bits_np(x)
 
 
 def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
@@ -103,9 +115,8 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
 # weights
 # ----------------------------------------------------------------------------
 def _stream(name: str, seed: int) -> np.random.Generator:
-    key = np.array([np.uint64(WEIGHT_KEY) + np.uint64(seed), np.uint64(zlib.crc32(name.encode()))],
-                   dtype=np.uint64)
-    return np.random.Generator(np.random.Philox(key=key))
+    ss = np.random.SeedSequence([WEIGHT_KEY, int(seed), zlib.crc32(name.encode())])
+    return np.random.Generator(np.random.SFC64(ss))
 
 
 def tensor_normal(name: str, shape: Sequence[int], seed: int, std: float = 0.02) -> np.ndarray:

@@ -475,4 +475,6 @@ def test_bf16_rounding_bits():
     torch = pytest.importorskip("torch")
     r = np.random.default_rng(0).standard_normal(10000).astype(np.float32)
     t = torch.tensor(r).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
-    np.testing.assert_array_equal(synth.f32_to_bf16_bits(r), t)
+    np.testing.assert_array_equal(synth._f32_to_bf16_bits_np(r), t)
+    big = np.random.default_rng(1).standard_normal(1 << 20).astype(np.float32)
+    np.testing.assert_array_equal(synth.f32_to_bf16_bits(big), synth._f32_to_bf16_bits_np(big))
