@@ -51,7 +51,8 @@ struct clover_ctx {
   // sizes
   int R, max_rows, H, QKVN, NQD;
   KVLayout kv;
-  size_t k_layer_elems, v_layer_elems, esz;
+  size_t k_layer_elems, v_layer_elems, esz, kv_esz;
+  int kvdtype;  // element type of the KV caches (fp32: a random-init 32-layer stack amplifies bf16 cache rounding ~20x)
   // device regions
   int *d_seq_len, *d_aug_len, *d_err;
   int *d_depth, *d_parent, *d_rank, *d_first_child, *d_n_child, *d_lvl_nodes, *d_par_row;
@@ -192,6 +193,7 @@ void carve(clover_ctx* x, char* base, size_t* total) {
   const int B = c.max_batch, R = c.max_nodes, rows = B * R, H = c.hidden, d = c.head_dim;
   const size_t esz = c.dtype == CLOVER_DTYPE_F32 ? 4 : 2;
   x->R = R; x->max_rows = rows; x->H = H; x->esz = esz;
+  x->kvdtype = CLOVER_DTYPE_F32; x->kv_esz = 4;
   x->NQD = c.n_q_heads * d;
   x->QKVN = (c.n_q_heads + 2 * c.n_kv_heads) * d;
   x->kv = KVLayout{B, c.max_seq, c.n_kv_heads, d};
@@ -209,10 +211,10 @@ void carve(clover_ctx* x, char* base, size_t* total) {
   x->d_par_row = cv.take<int>(R);
   x->d_anc = cv.take<unsigned long long>(2 * R);
   x->d_anc_chain = cv.take<unsigned long long>(2 * R);
-  x->kc = cv.take<char>(x->k_layer_elems * esz * c.n_layers);
-  x->vc = cv.take<char>(x->v_layer_elems * esz * c.n_layers);
-  x->aug_kc = cv.take<char>(x->k_layer_elems * esz * c.aug_layers);
-  x->aug_vc = cv.take<char>(x->v_layer_elems * esz * c.aug_layers);
+  x->kc = cv.take<char>(x->k_layer_elems * x->kv_esz * c.n_layers);
+  x->vc = cv.take<char>(x->v_layer_elems * x->kv_esz * c.n_layers);
+  x->aug_kc = cv.take<char>(x->k_layer_elems * x->kv_esz * c.aug_layers);
+  x->aug_vc = cv.take<char>(x->v_layer_elems * x->kv_esz * c.aug_layers);
   x->xd = cv.take<float>((size_t)rows * H);
   x->a_norm = cv.take<float>((size_t)rows * 2 * H);
   x->qkv = cv.take<float>((size_t)rows * x->QKVN);
@@ -345,10 +347,10 @@ void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMa
   const int sn[3] = {c.n_q_heads * d, c.n_kv_heads * d, c.n_kv_heads * d};
   gemm(x, KC_GEMM_QKV, x->a_norm, H, 3, ws, sn, nullptr, nullptr, x->qkv, x->QKVN, M, x->QKVN, H, 0);
   { Scope s(x, KC_ROPE_KV);
-    launch_rope_kv_write(x->qkv, x->QKVN, x->cos_t, x->sin_t, x->q_rot, x->NQD, kc_layer, vc_layer, c.dtype, x->kv,
+    launch_rope_kv_write(x->qkv, x->QKVN, x->cos_t, x->sin_t, x->q_rot, x->NQD, kc_layer, vc_layer, x->kvdtype, x->kv,
                          base_len, c.n_q_heads, rm, x->d_err, x->st); }
   { Scope s(x, KC_ATTN);
-    launch_attn_generic(x->q_rot, x->NQD, kc_layer, vc_layer, c.dtype, x->kv, base_len, anc, c.n_q_heads, x->attn_out,
+    launch_attn_generic(x->q_rot, x->NQD, kc_layer, vc_layer, x->kvdtype, x->kv, base_len, anc, c.n_q_heads, x->attn_out,
                         x->NQD, rm, x->st); }
   gemm1(x, KC_GEMM_WO, x->attn_out, x->NQD, lw.wo, nullptr, xres, H, M, H, x->NQD, 1);
   { Scope s(x, KC_RMSNORM); launch_rmsnorm(xres, H, lw.ffn_norm, c.dtype, c.rms_eps, x->a_norm, H, H, M, x->st); }
@@ -421,7 +423,7 @@ int accept_common(clover_ctx* x, int batch, const int* tree_tokens, const float*
     launch_accept_walk(x->topk_ids, tree_tokens, x->d_first_child, x->d_n_child, t.n, batch, R, n_forced, forced_next,
                        m, acc_idx, new_tokens, next_tok, x->st); }
   { Scope s(x, KC_COMPACT);
-    launch_compact_kv(x->kc, x->vc, c.dtype, x->kv, c.n_layers, x->k_layer_elems, x->v_layer_elems, x->d_seq_len, m,
+    launch_compact_kv(x->kc, x->vc, x->kvdtype, x->kv, c.n_layers, x->k_layer_elems, x->v_layer_elems, x->d_seq_len, m,
                       acc_idx, batch, R, x->st);
     launch_gather_hidden(hidden, acc_idx, m, batch, R, x->H, hid_acc, x->st);
     launch_add_len(x->d_seq_len, m, batch, x->st); }
@@ -553,8 +555,8 @@ int draft_tree(clover_ctx* x, int32_t batch, const float* hid_acc, const int32_t
   run_ad(x, x->w.ad1, hid_acc, x->d_e, M, x->xd);
   { Scope s(x, KC_ROPE_KV); launch_rope_table(x->d_aug_len, nullptr, c.rope_base, c.head_dim, x->cos_t, x->sin_t, rm, x->st); }
   for (int l = 0; l < c.aug_layers; ++l)
-    run_layer(x, x->aug[l], x->xd, rm, M, x->aug_kc + (size_t)l * x->k_layer_elems * x->esz,
-              x->aug_vc + (size_t)l * x->v_layer_elems * x->esz, x->d_aug_len, x->d_anc_chain);
+    run_layer(x, x->aug[l], x->xd, rm, M, x->aug_kc + (size_t)l * x->k_layer_elems * x->kv_esz,
+              x->aug_vc + (size_t)l * x->v_layer_elems * x->kv_esz, x->d_aug_len, x->d_anc_chain);
   { Scope s(x, KC_DRAFT_MISC);
     launch_draft_root(x->xd, next_tok, m, B, R, H, x->d_rootx, x->d_state, tree_tokens, x->st);
     launch_add_len(x->d_aug_len, m, B, x->st); }
@@ -600,8 +602,8 @@ int verify_tree(clover_ctx* x, int32_t batch, const int32_t* tree_tokens, float*
   { Scope s(x, KC_EMBED); launch_embed(x->w.embed, c.dtype, tree_tokens, c.vocab, hidden, H, H, rm, x->st); }
   { Scope s(x, KC_ROPE_KV); launch_rope_table(x->d_seq_len, x->d_depth, c.rope_base, c.head_dim, x->cos_t, x->sin_t, rm, x->st); }
   for (int l = 0; l < c.n_layers; ++l)
-    run_layer(x, x->layers[l], hidden, rm, M, x->kc + (size_t)l * x->k_layer_elems * x->esz,
-              x->vc + (size_t)l * x->v_layer_elems * x->esz, x->d_seq_len, x->d_anc);
+    run_layer(x, x->layers[l], hidden, rm, M, x->kc + (size_t)l * x->k_layer_elems * x->kv_esz,
+              x->vc + (size_t)l * x->v_layer_elems * x->kv_esz, x->d_seq_len, x->d_anc);
   { Scope s(x, KC_RMSNORM); launch_rmsnorm(hidden, H, x->w.final_norm, c.dtype, c.rms_eps, x->a_norm, H, H, M, x->st); }
   gemm1(x, KC_GEMM_LMHEAD, x->a_norm, H, x->w.lm_head, nullptr, logits, c.vocab, M, c.vocab, H, 0);
   return finish(x, "verify_tree");
@@ -663,9 +665,9 @@ int clover_read_kv(clover_ctx* x, int32_t stack, int32_t layer, int32_t b, int32
   const size_t n = (size_t)n_slots * c.n_kv_heads * c.head_dim;
   if (2 * n > (size_t)x->max_rows * c.vocab) return fail(x, CLOVER_E_SHAPE, "clover_read_kv: too many slots at once");
   if (n == 0) return CLOVER_OK;
-  const char* kbase = (stack == 0 ? x->kc : x->aug_kc) + (size_t)layer * x->k_layer_elems * x->esz;
-  const char* vbase = (stack == 0 ? x->vc : x->aug_vc) + (size_t)layer * x->v_layer_elems * x->esz;
-  launch_read_kv(kbase, vbase, c.dtype, x->kv, b, slot0, n_slots, x->z, x->z + n, x->st);
+  const char* kbase = (stack == 0 ? x->kc : x->aug_kc) + (size_t)layer * x->k_layer_elems * x->kv_esz;
+  const char* vbase = (stack == 0 ? x->vc : x->aug_vc) + (size_t)layer * x->v_layer_elems * x->kv_esz;
+  launch_read_kv(kbase, vbase, x->kvdtype, x->kv, b, slot0, n_slots, x->z, x->z + n, x->st);
   hipError_t e = hipMemcpyAsync(k_out_host, x->z, n * sizeof(float), hipMemcpyDeviceToHost, x->st);
   if (e == hipSuccess) e = hipMemcpyAsync(v_out_host, x->z + n, n * sizeof(float), hipMemcpyDeviceToHost, x->st);
   if (e == hipSuccess) e = hipStreamSynchronize(x->st);

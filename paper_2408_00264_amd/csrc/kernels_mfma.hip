@@ -3,14 +3,25 @@
 //   Y[M,N] = X[M,K] * W[N,K]^T     W bf16 row-major (streamed once from HBM), X fp32, fp32 accumulate
 //
 // M is the number of tree rows (tens to a few hundred), so the kernel is bound by reading W.
-// Mapping: v_mfma_f32_16x16x32_bf16 with the WEIGHT rows as the A operand and the activation rows as
-// the B operand.  A wavefront owns two 16-row weight blocks and all M activation rows; each lane
-// loads its 16-byte A fragment straight from global memory (row = lane%16, k = 8*(lane/16)..+7),
-// i.e. every weight byte is read exactly once and goes directly to registers.  The activation
-// chunk is converted to bf16 and staged once per workgroup in LDS, from which every wavefront
-// reads its B fragments.  Split-K partial tiles are combined by the last workgroup to arrive
-// (fixed summation order, so results do not depend on scheduling).
+//
+// * v_mfma_f32_16x16x32_bf16 with the WEIGHT rows as the A operand and the activation rows as the
+//   B operand.  A wavefront owns NF 16-row weight blocks and all M activation rows; each lane loads
+//   its 16-byte A fragments straight from global memory into registers (row = lane%16,
+//   k = 8*(lane/16)..+7): every weight byte is read exactly once.
+// * Activations are fp32.  A random-init 32-layer stack amplifies a bf16 rounding of the
+//   activations about twenty-fold by the last layer, so each activation is split into
+//   hi = bf16(x) and lo = bf16(x - hi) and both halves are multiplied (two MFMAs per fragment):
+//   16 mantissa bits, at no cost in HBM traffic.  The split chunk is staged once per workgroup in LDS.
+// * Weight rows are K*2 bytes apart, a power of two: workgroups that walk K in the same order all
+//   hit the same few HBM channels at the same time.  Each workgroup therefore starts at a different
+//   (rotated) K chunk.
+// * Software pipeline: the weight fragments and the activation chunk of step i+1 are in flight
+//   (registers / second LDS buffer) while step i is multiplied.
+// * Split-K partial tiles are combined by the last workgroup to arrive, in a fixed order, so the
+//   result does not depend on scheduling.
 #include "clover_internal.h"
+
+#include <cstdlib>
 
 namespace clv {
 
@@ -18,11 +29,17 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ unsigned pack_bf16x2(float a, float b) {
-  unsigned ua = __float_as_uint(a), ub = __float_as_uint(b);
-  ua += 0x7FFFu + ((ua >> 16) & 1u);
-  ub += 0x7FFFu + ((ub >> 16) & 1u);
-  return (ua >> 16) | (ub & 0xFFFF0000u);
+__device__ __forceinline__ unsigned bf16_rn_bits(float a) {  // bf16 bits in the low half
+  unsigned u = __float_as_uint(a);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+// split two floats into packed (hi, hi) and (lo, lo) bf16 pairs
+__device__ __forceinline__ void split2(float a, float b, unsigned& hi, unsigned& lo) {
+  const unsigned ha = bf16_rn_bits(a), hb = bf16_rn_bits(b);
+  const float ra = a - __uint_as_float(ha << 16), rb = b - __uint_as_float(hb << 16);
+  hi = ha | (hb << 16);
+  lo = bf16_rn_bits(ra) | (bf16_rn_bits(rb) << 16);
 }
 
 union Frag {
@@ -30,108 +47,184 @@ union Frag {
   bf16x8 v;
 };
 
-template <int MT, int KC>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(MfmaGemm p) {
-  constexpr int LDK = KC + 8;  // row stride in bf16: +16 bytes keeps the 16 lanes of a fragment read on distinct banks
-  constexpr int KS = KC / 32;  // MFMA k-steps per chunk
-  __shared__ __attribute__((aligned(16))) bf16_t xs[MT * 16 * LDK];
+constexpr int GEMM_CW = 4;                          // consumer wavefronts: stream weights, MFMA
+constexpr int GEMM_PW = 2;                          // producer wavefronts: stage the activation chunks
+constexpr int GEMM_THREADS = 64 * (GEMM_CW + GEMM_PW);
+
+template <int MT, int NF, int KC>
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(MfmaGemm p) {
+  constexpr int LDK = KC + 8;      // LDS row stride in bf16 (+16 B: the 16 lanes of a fragment read hit distinct banks)
+  constexpr int KS = KC / 32;      // MFMA k-steps per chunk
+  constexpr int ROWS = MT * 16;
+  constexpr int PLANE = ROWS * LDK;  // one bf16 plane (hi or lo) of one buffer
+  extern __shared__ __attribute__((aligned(16))) bf16_t smem[];  // [2 buffers][hi, lo][ROWS][LDK]
   __shared__ int s_last;
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int l16 = lane & 15, g4 = lane >> 4;
   const int K = p.K, M = p.M;
-  const int pair = blockIdx.x * 4 + wave;
-  const int n_pairs = (p.mode == 2) ? p.N / 16 : p.N / 32;
-  const bool active = pair < n_pairs;
-
-  // weight row pointers of this lane's two A fragments, and the output columns they produce
-  const bf16_t *wa = p.W[0], *wb = p.W[0];
-  int colA = 0, colB = 0;
-  if (active) {
-    if (p.mode == 2) {
-      wa = p.W[0] + (size_t)(pair * 16 + l16) * K;
-      wb = p.W_up + (size_t)(pair * 16 + l16) * K;
-      colA = colB = pair * 16;
-    } else {
-      const int n = pair * 32;
-      int s = 0;
-      if (n >= p.seg_begin[1]) s = 1;
-      if (n >= p.seg_begin[2]) s = 2;
-      wa = p.W[s] + (size_t)(n - p.seg_begin[s] + l16) * K;
-      wb = wa + (size_t)16 * K;
-      colA = n;
-      colB = n + 16;
-    }
-  }
-  wa += g4 * 8;
-  wb += g4 * 8;
-
-  f32x4 acc[2][MT];
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int mb = 0; mb < MT; ++mb) acc[i][mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  const bool producer = wave >= GEMM_CW;
+  const int grp = blockIdx.x * GEMM_CW + wave;
+  const int n_groups = (p.mode == 2) ? p.N / (8 * NF) : p.N / (16 * NF);
+  const bool active = !producer && grp < n_groups;
 
   const int n_chunks = K / KC;
   const int per = (n_chunks + p.splits - 1) / p.splits;
   const int c0 = blockIdx.y * per;
-  const int c1 = min(c0 + per, n_chunks);
+  const int n_it = max(0, min(c0 + per, n_chunks) - c0);
+  const int rot = n_it > 0 ? (int)((blockIdx.x * 5u + blockIdx.y * 3u) % (unsigned)n_it) : 0;
+  auto chunk_k = [&](int i) {
+    int j = i + rot;
+    if (j >= n_it) j -= n_it;
+    return (c0 + j) * KC;
+  };
 
-  for (int c = c0; c < c1; ++c) {
-    const int kc = c * KC;
-    // issue this chunk's weight loads first: they are the long-latency HBM stream
-    Frag fa[KS], fb[KS];
-    if (active) {
+  f32x4 acc[NF][MT];
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        fa[ks].u = __builtin_nontemporal_load((const u32x4*)(wa + kc + ks * 32));
-        fb[ks].u = __builtin_nontemporal_load((const u32x4*)(wb + kc + ks * 32));
+  for (int f = 0; f < NF; ++f)
+#pragma unroll
+    for (int mb = 0; mb < MT; ++mb) acc[f][mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  int col[NF];
+#pragma unroll
+  for (int f = 0; f < NF; ++f) col[f] = 0;
+
+  if (producer) {
+    // ---------------- producer wavefronts: X[:, chunk] -> (hi, lo) bf16 planes in LDS ----------------
+    // Their memory queue holds only these short-latency (L2) loads, so they never wait behind the
+    // long HBM weight stream of the consumers.
+    constexpr int TPR = KC / 8;                    // threads per activation row (8 consecutive k each)
+    constexpr int RPP = (64 * GEMM_PW) / TPR;      // rows per pass
+    constexpr int NPASS = (ROWS + RPP - 1) / RPP;
+    const int ptid = tid - 64 * GEMM_CW;
+    const int srow = ptid / TPR, skk = (ptid % TPR) * 8;
+    auto stage_x = [&](int kc, int buf) {
+      float4 xr[NPASS][2];
+#pragma unroll
+      for (int ps = 0; ps < NPASS; ++ps) {
+        const int r = ps * RPP + srow;
+        if (r < M && r < ROWS) {
+          const float4* src = (const float4*)(p.X + (size_t)r * p.ldx + kc + skk);
+          xr[ps][0] = src[0];
+          xr[ps][1] = src[1];
+        } else {
+          xr[ps][0] = make_float4(0.f, 0.f, 0.f, 0.f);
+          xr[ps][1] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+      }
+      bf16_t* hi = smem + (size_t)buf * 2 * PLANE;
+      bf16_t* lo = hi + PLANE;
+#pragma unroll
+      for (int ps = 0; ps < NPASS; ++ps) {
+        const int r = ps * RPP + srow;
+        if (r < ROWS) {
+          u32x4 h, l;
+          unsigned a, b;
+          split2(xr[ps][0].x, xr[ps][0].y, a, b); h.x = a; l.x = b;
+          split2(xr[ps][0].z, xr[ps][0].w, a, b); h.y = a; l.y = b;
+          split2(xr[ps][1].x, xr[ps][1].y, a, b); h.z = a; l.z = b;
+          split2(xr[ps][1].z, xr[ps][1].w, a, b); h.w = a; l.w = b;
+          *(u32x4*)(hi + r * LDK + skk) = h;
+          *(u32x4*)(lo + r * LDK + skk) = l;
+        }
+      }
+    };
+    if (n_it > 0) {
+      stage_x(chunk_k(0), 0);
+      __syncthreads();
+      for (int i = 0; i < n_it; ++i) {
+        if (i + 1 < n_it) stage_x(chunk_k(i + 1), (i + 1) & 1);
+        __syncthreads();
       }
     }
-    // stage X[:, kc:kc+KC] as bf16: a thread converts 8 consecutive k of one row per pass
-    constexpr int TPR = KC / 8;         // threads per row
-    constexpr int RPP = 256 / TPR;      // rows per pass
+  } else {
+    // ---------------- consumer wavefronts: weight stream + MFMA ----------------
+    // weight row pointer and first output column of each fragment
+    const bf16_t* wrow[NF];
 #pragma unroll
-    for (int r0 = 0; r0 < MT * 16; r0 += RPP) {
-      const int r = r0 + tid / TPR, kk = (tid % TPR) * 8;
-      u32x4 o = {0u, 0u, 0u, 0u};
-      if (r < M) {
-        const float4* src = (const float4*)(p.X + (size_t)r * p.ldx + kc + kk);
-        const float4 v0 = src[0], v1 = src[1];
-        o.x = pack_bf16x2(v0.x, v0.y);
-        o.y = pack_bf16x2(v0.z, v0.w);
-        o.z = pack_bf16x2(v1.x, v1.y);
-        o.w = pack_bf16x2(v1.z, v1.w);
+    for (int f = 0; f < NF; ++f) {
+      wrow[f] = p.W[0];
+      if (active) {
+        if (p.mode == 2) {
+          constexpr int HF = NF / 2 > 0 ? NF / 2 : 1;
+          const int r0 = grp * (8 * NF) + (f % HF) * 16;
+          wrow[f] = ((f < HF) ? p.W[0] : p.W_up) + (size_t)(r0 + l16) * K + g4 * 8;
+          col[f] = r0;
+        } else {
+          const int n = grp * (16 * NF) + f * 16;
+          int s = 0;
+          if (n >= p.seg_begin[1]) s = 1;
+          if (n >= p.seg_begin[2]) s = 2;
+          wrow[f] = p.W[s] + (size_t)(n - p.seg_begin[s] + l16) * K + g4 * 8;
+          col[f] = n;
+        }
       }
-      *(u32x4*)(&xs[r * LDK + kk]) = o;
     }
-    __syncthreads();
-    if (active) {
+    constexpr int RING = 4;        // weight fragments of up to three future chunks are in flight
+    Frag w[RING][NF][KS];
+    auto load_w = [&](int slot, int kc) {
+      if (!active) return;
+#pragma unroll
+      for (int f = 0; f < NF; ++f)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          w[slot][f][ks].u = __builtin_nontemporal_load((const u32x4*)(wrow[f] + kc + ks * 32));
+    };
+    auto compute = [&](int slot, int buf) {
+      if (!active) return;
+      const bf16_t* hi = smem + (size_t)buf * 2 * PLANE + l16 * LDK + g4 * 8;
+      const bf16_t* lo = hi + PLANE;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
         for (int mb = 0; mb < MT; ++mb) {
-          Frag b;
-          b.u = *(const u32x4*)(&xs[(mb * 16 + l16) * LDK + ks * 32 + g4 * 8]);
-          acc[0][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[ks].v, b.v, acc[0][mb], 0, 0, 0);
-          acc[1][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[ks].v, b.v, acc[1][mb], 0, 0, 0);
+          Frag bh, bl;
+          bh.u = *(const u32x4*)(hi + mb * 16 * LDK + ks * 32);
+          bl.u = *(const u32x4*)(lo + mb * 16 * LDK + ks * 32);
+#pragma unroll
+          for (int f = 0; f < NF; ++f) {
+            acc[f][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[slot][f][ks].v, bl.v, acc[f][mb], 0, 0, 0);
+            acc[f][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[slot][f][ks].v, bh.v, acc[f][mb], 0, 0, 0);
+          }
         }
       }
+    };
+    // stage(r, i): multiply chunk i (weights in ring slot r, activations in LDS buffer i&1) while the
+    // weights of chunk i+3 are fetched
+    auto stage = [&](int r, int i) {
+      if (i + 3 < n_it) load_w((r + 3) & 3, chunk_k(i + 3));
+      compute(r, r & 1);
+      __syncthreads();
+    };
+    if (n_it > 0) {
+      load_w(0, chunk_k(0));
+      if (n_it > 1) load_w(1, chunk_k(1));
+      if (n_it > 2) load_w(2, chunk_k(2));
+      __syncthreads();
+      for (int i = 0; i < n_it; i += 4) {
+        stage(0, i);
+        if (i + 1 >= n_it) break;
+        stage(1, i + 1);
+        if (i + 2 >= n_it) break;
+        stage(2, i + 2);
+        if (i + 3 >= n_it) break;
+        stage(3, i + 3);
+      }
     }
-    __syncthreads();
   }
 
   // ---- split-K: publish the partial tile; the last workgroup of this column sums all of them ----
   if (p.splits > 1) {
-    // layout [tile][split][wave][i][mb][lane] of f32x4: a lane re-reads exactly its own positions
+    // layout [tile][split][wave][f][mb][lane] of f32x4: a lane re-reads exactly its own positions
     f32x4* part = (f32x4*)p.partial;
-    const size_t tile_stride = (size_t)p.splits * 4 * 2 * MT * 64;
+    const size_t tile_stride = (size_t)p.splits * 4 * NF * MT * 64;
     const size_t base = (size_t)blockIdx.x * tile_stride;
+    if (!producer) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+      for (int f = 0; f < NF; ++f)
 #pragma unroll
-      for (int mb = 0; mb < MT; ++mb)
-        part[base + ((((size_t)blockIdx.y * 4 + wave) * 2 + i) * MT + mb) * 64 + lane] = acc[i][mb];
+        for (int mb = 0; mb < MT; ++mb)
+          part[base + ((((size_t)blockIdx.y * 4 + wave) * NF + f) * MT + mb) * 64 + lane] = acc[f][mb];
+    }
     __threadfence();
     __syncthreads();
     if (tid == 0) {
@@ -139,19 +232,16 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(MfmaGemm p) {
       s_last = (prev == p.splits - 1) ? 1 : 0;
     }
     __syncthreads();
-    if (!s_last) return;
+    if (!s_last || producer) return;
     __threadfence();
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int f = 0; f < NF; ++f)
 #pragma unroll
       for (int mb = 0; mb < MT; ++mb) {
         f32x4 sum = (f32x4){0.f, 0.f, 0.f, 0.f};
-        for (int s = 0; s < p.splits; ++s) {
-          const f32x4 v = __builtin_nontemporal_load(
-              &part[base + ((((size_t)s * 4 + wave) * 2 + i) * MT + mb) * 64 + lane]);
-          sum += v;
-        }
-        acc[i][mb] = sum;
+        for (int s = 0; s < p.splits; ++s)
+          sum += __builtin_nontemporal_load(&part[base + ((((size_t)s * 4 + wave) * NF + f) * MT + mb) * 64 + lane]);
+        acc[f][mb] = sum;
       }
     if (tid == 0) p.counters[blockIdx.x] = 0;  // ready for the next launch on this stream
   }
@@ -164,24 +254,28 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(MfmaGemm p) {
     if (m >= M) continue;
     float* yrow = p.Y + (size_t)m * p.ldy;
     if (p.mode == 2) {
-      const f32x4 g = acc[0][mb], u = acc[1][mb];
-      float4 o;
-      o.x = g[0] / (1.0f + __expf(-g[0])) * u[0];
-      o.y = g[1] / (1.0f + __expf(-g[1])) * u[1];
-      o.z = g[2] / (1.0f + __expf(-g[2])) * u[2];
-      o.w = g[3] / (1.0f + __expf(-g[3])) * u[3];
-      *(float4*)(yrow + colA + 4 * g4) = o;
+      constexpr int HF = NF / 2 > 0 ? NF / 2 : 1;
+#pragma unroll
+      for (int f = 0; f < HF; ++f) {
+        const f32x4 g = acc[f][mb], u = acc[(f + HF) % NF][mb];
+        float4 o;
+        o.x = g[0] / (1.0f + expf(-g[0])) * u[0];
+        o.y = g[1] / (1.0f + expf(-g[1])) * u[1];
+        o.z = g[2] / (1.0f + expf(-g[2])) * u[2];
+        o.w = g[3] / (1.0f + expf(-g[3])) * u[3];
+        *(float4*)(yrow + col[f] + 4 * g4) = o;
+      }
     } else {
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int col = (i == 0 ? colA : colB) + 4 * g4;
-        f32x4 v = acc[i][mb];
+      for (int f = 0; f < NF; ++f) {
+        const int c = col[f] + 4 * g4;
+        f32x4 v = acc[f][mb];
         if (p.bias) {
-          const bf16_t* bp = p.bias + col;
+          const bf16_t* bp = p.bias + c;
 #pragma unroll
           for (int r = 0; r < 4; ++r) v[r] += __uint_as_float(((unsigned)bp[r]) << 16);
         }
-        float4* dst = (float4*)(yrow + col);
+        float4* dst = (float4*)(yrow + c);
         float4 o = {v[0], v[1], v[2], v[3]};
         if (p.mode == 1) {
           const float4 old = *dst;
@@ -197,46 +291,76 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(MfmaGemm p) {
 // host side
 // ------------------------------------------------------------------------------------------
 static int mt_for(int M) { return M <= 16 ? 1 : M <= 32 ? 2 : M <= 64 ? 4 : M <= 128 ? 8 : 16; }
-static int kc_for(int mt) { return mt <= 4 ? 256 : mt == 8 ? 128 : 64; }
+static int kc_for(int mt) { return mt <= 4 ? 128 : mt == 8 ? 64 : 32; }
+static int env_int(const char* name) {
+  const char* v = getenv(name);
+  return v ? atoi(v) : 0;
+}
 
 bool mfma_gemm_supported(int M, int N, int K, int mode) {
   if (M < 1 || M > 256) return false;
-  if (K % 256 != 0) return false;
-  if (mode == 2) return N % 16 == 0;
-  return N % 32 == 0;
+  if (K % 128 != 0) return false;
+  return N % 16 == 0;
 }
 
+// fragments per wavefront: 2 when the column count allows it, else 1 (mode 2 always pairs gate/up)
+static int nf_for(int N, int mode) {
+  if (mode == 2) return 2;
+  const int forced = env_int("CLOVER_GEMM_NF");
+  if (forced == 1 || forced == 2) return (N % (16 * forced) == 0) ? forced : 1;
+  return (N % 32 == 0 && N >= 8192) ? 2 : 1;
+}
 static int tiles_for(int N, int mode) {
-  const int pairs = (mode == 2) ? N / 16 : N / 32;
-  return (pairs + 3) / 4;
+  const int nf = nf_for(N, mode);
+  const int groups = (mode == 2) ? N / (8 * nf) : N / (16 * nf);
+  return (groups + 3) / 4;
 }
 
 int mfma_gemm_pick_splits(int M, int N, int K, int mode) {
+  const int forced = env_int("CLOVER_GEMM_SPLITS");
+  const int mt = mt_for(M);
+  const int chunks = K / kc_for(mt);
+  if (forced > 0) return std::min(forced, chunks);
   const int tiles = tiles_for(N, mode);
-  const int chunks = K / kc_for(mt_for(M));
   int s = 1;
-  // aim at >= 512 workgroups (two per CU) while keeping at least two chunks per split
-  while (tiles * s < 512 && s * 2 <= chunks / 2 && s < 32) s *= 2;
+  // fill the chip (>= 256 workgroups), keep >= 4 chunks per split for the pipeline, and keep the
+  // fp32 partial tiles (splits * M * 4 bytes per column) below a quarter of the weight bytes (K * 2)
+  while (tiles * s < 256 && (s * 2) * 4 <= chunks && (size_t)(s * 2) * mt * 16 * 4 * 4 <= (size_t)K * 2) s *= 2;
   return s;
 }
 
 size_t mfma_gemm_partial_bytes(int M, int N, int K, int mode, int splits) {
   if (splits <= 1) return 0;
-  return (size_t)tiles_for(N, mode) * splits * 4 * 2 * mt_for(M) * 64 * sizeof(float) * 4;
+  return (size_t)tiles_for(N, mode) * splits * 4 * nf_for(N, mode) * mt_for(M) * 64 * sizeof(float) * 4;
 }
 
 int mfma_gemm_counters(int N, int mode) { return tiles_for(N, mode); }
 
-void launch_gemm_mfma(const MfmaGemm& g, hipStream_t st) {
-  const int mt = mt_for(g.M);
-  dim3 grid(tiles_for(g.N, g.mode), g.splits);
-  switch (mt) {
-    case 1: gemm_mfma_kernel<1, 256><<<grid, 256, 0, st>>>(g); break;
-    case 2: gemm_mfma_kernel<2, 256><<<grid, 256, 0, st>>>(g); break;
-    case 4: gemm_mfma_kernel<4, 256><<<grid, 256, 0, st>>>(g); break;
-    case 8: gemm_mfma_kernel<8, 128><<<grid, 256, 0, st>>>(g); break;
-    default: gemm_mfma_kernel<16, 64><<<grid, 256, 0, st>>>(g); break;
+template <int MT, int NF, int KC>
+static void launch_one(const MfmaGemm& g, dim3 grid, hipStream_t st) {
+  constexpr size_t lds = (size_t)2 * 2 * MT * 16 * (KC + 8) * sizeof(bf16_t);
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipFuncSetAttribute((const void*)gemm_mfma_kernel<MT, NF, KC>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    attr_done = true;
   }
+  gemm_mfma_kernel<MT, NF, KC><<<grid, GEMM_THREADS, lds, st>>>(g);
+}
+
+void launch_gemm_mfma(const MfmaGemm& g, hipStream_t st) {
+  const int mt = mt_for(g.M), nf = nf_for(g.N, g.mode);
+  dim3 grid(tiles_for(g.N, g.mode), g.splits);
+#define CLV_CASE(MT_, KC_)                                              \
+  if (nf == 2) launch_one<MT_, 2, KC_>(g, grid, st);                    \
+  else launch_one<MT_, 1, KC_>(g, grid, st);
+  switch (mt) {
+    case 1: CLV_CASE(1, 128) break;
+    case 2: CLV_CASE(2, 128) break;
+    case 4: CLV_CASE(4, 128) break;
+    case 8: CLV_CASE(8, 64) break;
+    default: CLV_CASE(16, 32) break;
+  }
+#undef CLV_CASE
 }
 
 }  // namespace clv
