@@ -62,10 +62,10 @@ struct clover_ctx {
   float *ad_q, *ad_k, *ad_v, *d_xs, *d_e, *d_cat, *d_g, *d_s, *d_state, *d_rootx, *z;
   void* cand;
   int* topk_ids;
-  float* partial;
+  float* partial;          // split-K partial tiles / plain GEMM outputs of the MFMA path
   size_t partial_bytes;
-  int* counters;
-  int n_counters;
+  float* pl_y;             // planes of draft-side GEMM inputs that no fused producer writes
+  bool fast;               // bf16 model on the MFMA path
   // host-side bounds
   std::vector<int> len_ub, aug_ub;
   int m_upper;
@@ -237,26 +237,32 @@ void carve(clover_ctx* x, char* base, size_t* total) {
   x->z = cv.take<float>((size_t)rows * c.vocab);
   x->cand = cv.take<unsigned long long>((size_t)rows * topk_chunks(c.vocab) * 16);
   x->topk_ids = cv.take<int>((size_t)rows * 16);
-  // split-K scratch of the MFMA GEMM, sized for the largest shape of this model
-  size_t pbytes = 0;
-  int ncount = 1;
-  if (c.dtype == CLOVER_DTYPE_BF16) {
+  // MFMA path: is every GEMM shape of this model supported, and how large can an output with its
+  // split-K partials get?
+  size_t pbytes = 256;
+  bool fast = c.dtype == CLOVER_DTYPE_BF16 && !(c.flags & CLOVER_FLAG_GENERIC);
+  if (fast) {
     std::vector<GemmShape> shapes;
     model_gemm_shapes(c, shapes);
-    const int Mmax = std::min(rows, 256);
+    for (const GemmShape& s : shapes) fast = fast && mfma_gemm_supported(1, s.N, s.K, s.mode);
+    fast = fast && (c.n_kv_heads * d) % 16 == 0;
+  }
+  if (fast) {
+    std::vector<GemmShape> shapes;
+    model_gemm_shapes(c, shapes);
     for (const GemmShape& s : shapes) {
-      if (!mfma_gemm_supported(Mmax, s.N, s.K, s.mode)) continue;
-      ncount = std::max(ncount, mfma_gemm_counters(s.N, s.mode));
-      for (int M = 16; M <= 256; M *= 2) {
-        const int mm = std::min(M, Mmax);
-        pbytes = std::max(pbytes, mfma_gemm_partial_bytes(mm, s.N, s.K, s.mode, mfma_gemm_pick_splits(mm, s.N, s.K, s.mode)));
+      if (s.mode == 2) continue;
+      for (int M = 1; M <= std::min(rows, 256); ++M) {
+        const int sp = mfma_gemm_pick_splits(M, s.N, s.K, s.mode);
+        const size_t mtot = rows <= 256 ? (size_t)M : (size_t)rows;
+        pbytes = std::max(pbytes, (size_t)sp * mtot * s.N * sizeof(float));
       }
     }
   }
+  x->fast = fast;
   x->partial_bytes = pbytes;
-  x->partial = (float*)cv.take<char>(pbytes ? pbytes : 256);
-  x->n_counters = ncount;
-  x->counters = cv.take<int>(ncount);
+  x->partial = (float*)cv.take<char>(pbytes);
+  x->pl_y = cv.take<float>((size_t)rows * 2 * H);
   *total = cv.off;
 }
 
@@ -280,104 +286,188 @@ struct Scope {
 };
 
 // ---- GEMM dispatch ----------------------------------------------------------------------------
-// Y[M, N] = X[M, K] * [W0; W1; W2]^T (row segments of seg_n[] rows) ; mode 2 uses W0 = gate and w_up.
-void gemm(clover_ctx* x, int cls, const float* X, int ldx, int nseg, const void* const* W, const int* seg_n,
-          const void* w_up, const void* bias, float* Y, int ldy, int M, int N, int K, int mode) {
-  Scope sc(x, cls);
-  const bool bf16 = x->cfg.dtype == CLOVER_DTYPE_BF16;
-  bool fast = bf16 && !(x->cfg.flags & CLOVER_FLAG_GENERIC) && mfma_gemm_supported(std::min(M, 256), N, K, mode) &&
-              (ldx % 4 == 0) && (ldy % 4 == 0);
-  for (int s = 0; s < nseg && fast && mode != 2; ++s) fast = (seg_n[s] % 32 == 0);
-  if (fast) {
-    for (int m0 = 0; m0 < M; m0 += 256) {
-      const int mm = std::min(256, M - m0);
-      MfmaGemm g;
-      memset(&g, 0, sizeof(g));
-      g.X = X + (size_t)m0 * ldx; g.ldx = ldx;
-      int off = 0;
-      for (int s = 0; s < 3; ++s) {
-        g.W[s] = (const bf16_t*)(s < nseg ? W[s] : W[nseg - 1]);
-        g.seg_begin[s] = s < nseg ? off : 0x7fffffff;
-        if (s < nseg) off += seg_n[s];
-      }
-      g.seg_begin[0] = 0;
-      g.seg_begin[3] = 0x7fffffff;
-      g.W_up = (const bf16_t*)w_up;
-      g.bias = (const bf16_t*)bias;
-      g.Y = Y + (size_t)m0 * ldy; g.ldy = ldy;
-      g.M = mm; g.N = N; g.K = K; g.mode = mode;
-      g.splits = mfma_gemm_pick_splits(mm, N, K, mode);
-      if (mfma_gemm_partial_bytes(mm, N, K, mode, g.splits) > x->partial_bytes || mfma_gemm_counters(N, mode) > x->n_counters) g.splits = 1;
-      g.partial = x->partial;
-      g.counters = x->counters;
-      launch_gemm_mfma(g, x->st);
-    }
-    return;
-  }
-  const int wd = x->cfg.dtype;
-  if (mode == 2) {
-    launch_gemm_generic(X, ldx, W[0], nullptr, wd, x->tmp_ffn, N, M, N, K, 0, x->st);
-    launch_gemm_generic(X, ldx, w_up, nullptr, wd, Y, ldy, M, N, K, 0, x->st);
-    if (ldy == N) launch_swiglu(x->tmp_ffn, Y, Y, (size_t)M * N, x->st);
-    else for (int r = 0; r < M; ++r) launch_swiglu(x->tmp_ffn + (size_t)r * N, Y + (size_t)r * ldy, Y + (size_t)r * ldy, N, x->st);
-    return;
-  }
-  int off = 0;
-  for (int s = 0; s < nseg; ++s) {
-    const void* b = bias ? (const void*)((const char*)bias + (size_t)off * x->esz) : nullptr;
-    launch_gemm_generic(X, ldx, W[s], b, wd, Y + off, ldy, M, seg_n[s], K, mode, x->st);
-    off += seg_n[s];
-  }
+struct Planes {
+  bf16_t *hi, *lo;
+  int ld;
+};
+// planes view of an fp32 activation buffer of capacity max_rows x K floats (same bytes)
+Planes planes_of(clover_ctx* x, float* buf, int K) {
+  bf16_t* hi = (bf16_t*)buf;
+  return Planes{hi, hi + (size_t)x->max_rows * K, K};
 }
 
-void gemm1(clover_ctx* x, int cls, const float* X, int ldx, const void* W, const void* bias, float* Y, int ldy, int M,
-           int N, int K, int mode) {
+// MFMA path: out[s][M][N] = X * [W0; W1; W2]^T per split s.  Writes into `direct` (leading dimension
+// ld_direct, no split) when given, else into x->partial as [splits][M][N].  Returns the split count.
+int gemm_fast(clover_ctx* x, int cls, Planes X, int nseg, const void* const* W, const int* seg_n, int M, int N, int K,
+              float* direct, int ld_direct) {
+  Scope sc(x, cls);
+  int splits = 1;
+  if (!direct) {
+    splits = mfma_gemm_pick_splits(std::min(M, 256), N, K, 0);
+    while (splits > 1 && (size_t)splits * M * N * sizeof(float) > x->partial_bytes) splits /= 2;
+  }
+  for (int m0 = 0; m0 < M; m0 += 256) {
+    const int mm = std::min(256, M - m0);
+    MfmaGemm g;
+    memset(&g, 0, sizeof(g));
+    g.Xhi = X.hi + (size_t)m0 * X.ld; g.Xlo = X.lo + (size_t)m0 * X.ld; g.ldx = X.ld;
+    int off = 0;
+    for (int s = 0; s < 3; ++s) {
+      g.W[s] = (const bf16_t*)(s < nseg ? W[s] : W[nseg - 1]);
+      g.seg_begin[s] = s < nseg ? off : 0x7fffffff;
+      if (s < nseg) off += seg_n[s];
+    }
+    g.seg_begin[0] = 0;
+    g.seg_begin[3] = 0x7fffffff;
+    if (direct) { g.Y = direct + (size_t)m0 * ld_direct; g.ldy = ld_direct; g.split_stride = 0; }
+    else { g.Y = x->partial + (size_t)m0 * N; g.ldy = N; g.split_stride = (size_t)M * N; }
+    g.M = mm; g.N = N; g.K = K; g.mode = 0; g.splits = splits;
+    launch_gemm_mfma(g, x->st);
+  }
+  return splits;
+}
+int gemm_fast1(clover_ctx* x, int cls, Planes X, const void* W, int M, int N, int K, float* direct = nullptr,
+               int ld_direct = 0) {
   const void* ws[1] = {W};
   const int sn[1] = {N};
-  gemm(x, cls, X, ldx, 1, ws, sn, nullptr, bias, Y, ldy, M, N, K, mode);
+  return gemm_fast(x, cls, X, 1, ws, sn, M, N, K, direct, ld_direct);
+}
+// Y = X W^T + bias through the MFMA path, for the small draft-side linears
+void linear_fast(clover_ctx* x, Planes X, const void* W, const void* bias, float* Y, int ldy, int M, int N, int K) {
+  const int sp = gemm_fast1(x, KC_GEMM_DRAFT, X, W, M, N, K);
+  Scope sc(x, KC_ELTWISE);
+  launch_reduce(x->partial, sp, (size_t)M * N, N, bias, x->cfg.dtype, Y, ldy, M, N, 0, x->st);
+}
+Planes split_to(clover_ctx* x, const float* src, int ld, float* planes_buf, int rows, int K) {
+  Planes P = planes_of(x, planes_buf, K);
+  Scope sc(x, KC_ELTWISE);
+  launch_split_planes(src, ld, P.hi, P.lo, K, rows, K, x->st);
+  return P;
 }
 
-// One LLaMA decoder layer over the rows of `rm` (residual stream x, leading dimension H).
+// generic path: Y = X W^T (+bias), mode 1 adds into Y
+void gemm_generic(clover_ctx* x, int cls, const float* X, int ldx, const void* W, const void* bias, float* Y, int ldy,
+                  int M, int N, int K, int mode) {
+  Scope sc(x, cls);
+  launch_gemm_generic(X, ldx, W, bias, x->cfg.dtype, Y, ldy, M, N, K, mode, x->st);
+}
+
+// One LLaMA decoder layer over the rows of `rm` (residual stream xres, leading dimension H).
+// MFMA path: on entry the planes of a_norm hold RMSNorm(xres) * attn_norm of this layer; on exit they
+// hold RMSNorm(xres) * next_gain (skipped when next_gain is null).  Generic path: norms are computed here.
 void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMap rm, int M, char* kc_layer,
-               char* vc_layer, const int* base_len, const unsigned long long* anc) {
+               char* vc_layer, const int* base_len, const unsigned long long* anc, const void* next_gain) {
   const clover_config& c = x->cfg;
-  const int H = x->H, d = c.head_dim;
-  { Scope s(x, KC_RMSNORM); launch_rmsnorm(xres, H, lw.attn_norm, c.dtype, c.rms_eps, x->a_norm, H, H, M, x->st); }
-  const void* ws[3] = {lw.wq, lw.wk, lw.wv};
+  const int H = x->H, d = c.head_dim, F = c.ffn;
   const int sn[3] = {c.n_q_heads * d, c.n_kv_heads * d, c.n_kv_heads * d};
-  gemm(x, KC_GEMM_QKV, x->a_norm, H, 3, ws, sn, nullptr, nullptr, x->qkv, x->QKVN, M, x->QKVN, H, 0);
+  const void* ws[3] = {lw.wq, lw.wk, lw.wv};
+  if (x->fast) {
+    Planes A = planes_of(x, x->a_norm, 2 * H);
+    A.ld = H;
+    Planes O = planes_of(x, x->attn_out, x->NQD);
+    Planes Hf = planes_of(x, x->h_ffn, F);
+    const int sq = gemm_fast(x, KC_GEMM_QKV, A, 3, ws, sn, M, x->QKVN, H, nullptr, 0);
+    { Scope s(x, KC_ROPE_KV);
+      launch_rope_kv_write(x->partial, x->QKVN, sq, (size_t)M * x->QKVN, x->cos_t, x->sin_t, x->q_rot, x->NQD, kc_layer,
+                           vc_layer, x->kvdtype, x->kv, base_len, c.n_q_heads, rm, x->d_err, x->st); }
+    { Scope s(x, KC_ATTN);
+      launch_attn_generic(x->q_rot, x->NQD, kc_layer, vc_layer, x->kvdtype, x->kv, base_len, anc, c.n_q_heads, nullptr,
+                          x->NQD, O.hi, O.lo, rm, x->st); }
+    const int sw = gemm_fast1(x, KC_GEMM_WO, O, lw.wo, M, H, x->NQD);
+    { Scope s(x, KC_RMSNORM);
+      launch_reduce_add_norm(xres, H, x->partial, sw, (size_t)M * H, H, lw.ffn_norm, c.dtype, c.rms_eps, A.hi, A.lo, H, M,
+                             H, x->st); }
+    { Scope s(x, KC_GEMM_GATEUP);
+      for (int m0 = 0; m0 < M; m0 += 256) {
+        MfmaGemm g;
+        memset(&g, 0, sizeof(g));
+        g.Xhi = A.hi + (size_t)m0 * H; g.Xlo = A.lo + (size_t)m0 * H; g.ldx = H;
+        g.W[0] = g.W[1] = g.W[2] = (const bf16_t*)lw.w_gate;
+        g.W_up = (const bf16_t*)lw.w_up;
+        g.seg_begin[1] = g.seg_begin[2] = g.seg_begin[3] = 0x7fffffff;
+        g.Yhi = Hf.hi + (size_t)m0 * F; g.Ylo = Hf.lo + (size_t)m0 * F; g.ldy = F;
+        g.M = std::min(256, M - m0); g.N = F; g.K = H; g.mode = 2; g.splits = 1;
+        launch_gemm_mfma(g, x->st);
+      } }
+    const int sd = gemm_fast1(x, KC_GEMM_DOWN, Hf, lw.w_down, M, H, F);
+    { Scope s(x, KC_RMSNORM);
+      launch_reduce_add_norm(xres, H, x->partial, sd, (size_t)M * H, H, next_gain, c.dtype, c.rms_eps, A.hi, A.lo, H, M,
+                             H, x->st); }
+    return;
+  }
+  { Scope s(x, KC_RMSNORM); launch_rmsnorm(xres, H, lw.attn_norm, c.dtype, c.rms_eps, x->a_norm, H, H, M, x->st); }
+  { int off = 0;
+    for (int sgm = 0; sgm < 3; ++sgm) {
+      gemm_generic(x, KC_GEMM_QKV, x->a_norm, H, ws[sgm], nullptr, x->qkv + off, x->QKVN, M, sn[sgm], H, 0);
+      off += sn[sgm];
+    } }
   { Scope s(x, KC_ROPE_KV);
-    launch_rope_kv_write(x->qkv, x->QKVN, x->cos_t, x->sin_t, x->q_rot, x->NQD, kc_layer, vc_layer, x->kvdtype, x->kv,
-                         base_len, c.n_q_heads, rm, x->d_err, x->st); }
+    launch_rope_kv_write(x->qkv, x->QKVN, 1, 0, x->cos_t, x->sin_t, x->q_rot, x->NQD, kc_layer, vc_layer, x->kvdtype,
+                         x->kv, base_len, c.n_q_heads, rm, x->d_err, x->st); }
   { Scope s(x, KC_ATTN);
     launch_attn_generic(x->q_rot, x->NQD, kc_layer, vc_layer, x->kvdtype, x->kv, base_len, anc, c.n_q_heads, x->attn_out,
-                        x->NQD, rm, x->st); }
-  gemm1(x, KC_GEMM_WO, x->attn_out, x->NQD, lw.wo, nullptr, xres, H, M, H, x->NQD, 1);
+                        x->NQD, nullptr, nullptr, rm, x->st); }
+  gemm_generic(x, KC_GEMM_WO, x->attn_out, x->NQD, lw.wo, nullptr, xres, H, M, H, x->NQD, 1);
   { Scope s(x, KC_RMSNORM); launch_rmsnorm(xres, H, lw.ffn_norm, c.dtype, c.rms_eps, x->a_norm, H, H, M, x->st); }
-  const void* wg[1] = {lw.w_gate};
-  const int gn[1] = {c.ffn};
-  gemm(x, KC_GEMM_GATEUP, x->a_norm, H, 1, wg, gn, lw.w_up, nullptr, x->h_ffn, c.ffn, M, c.ffn, H, 2);
-  gemm1(x, KC_GEMM_DOWN, x->h_ffn, c.ffn, lw.w_down, nullptr, xres, H, M, H, c.ffn, 1);
+  gemm_generic(x, KC_GEMM_GATEUP, x->a_norm, H, lw.w_gate, nullptr, x->tmp_ffn, F, M, F, H, 0);
+  gemm_generic(x, KC_GEMM_GATEUP, x->a_norm, H, lw.w_up, nullptr, x->h_ffn, F, M, F, H, 0);
+  { Scope s(x, KC_ELTWISE); launch_swiglu(x->tmp_ffn, x->h_ffn, x->h_ffn, (size_t)M * F, x->st); }
+  gemm_generic(x, KC_GEMM_DOWN, x->h_ffn, F, lw.w_down, nullptr, xres, H, M, H, F, 1);
+}
+
+// planes of RMSNorm(src) * gain in the a_norm buffer (MFMA path)
+Planes norm_planes(clover_ctx* x, const float* src, const void* gain, int rows) {
+  const clover_config& c = x->cfg;
+  Planes A = planes_of(x, x->a_norm, 2 * x->H);
+  A.ld = x->H;
+  Scope s(x, KC_RMSNORM);
+  launch_reduce_add_norm(const_cast<float*>(src), x->H, nullptr, 0, 0, 0, gain, c.dtype, c.rms_eps, A.hi, A.lo, x->H, rows,
+                         x->H, x->st);
+  return A;
 }
 
 // Attention Decoder on `rows` contiguous rows: out = x + gate(q(norm(x)), k(y)) * v(y)
 void run_ad(clover_ctx* x, const clover_ad_weights& ad, const float* xin, const float* y, int rows, float* out) {
   const clover_config& c = x->cfg;
   const int H = x->H;
-  { Scope s(x, KC_RMSNORM); launch_rmsnorm(xin, H, ad.norm, c.dtype, c.rms_eps, x->a_norm, H, H, rows, x->st); }
-  gemm1(x, KC_GEMM_DRAFT, x->a_norm, H, ad.wq, ad.bq, x->ad_q, H, rows, H, H, 0);
-  gemm1(x, KC_GEMM_DRAFT, y, H, ad.wk, ad.bk, x->ad_k, H, rows, H, H, 0);
-  gemm1(x, KC_GEMM_DRAFT, y, H, ad.wv, ad.bv, x->ad_v, H, rows, H, H, 0);
+  if (x->fast) {
+    Planes A = norm_planes(x, xin, ad.norm, rows);
+    linear_fast(x, A, ad.wq, ad.bq, x->ad_q, H, rows, H, H);
+    Planes Y = split_to(x, y, H, x->pl_y, rows, H);
+    linear_fast(x, Y, ad.wk, ad.bk, x->ad_k, H, rows, H, H);
+    linear_fast(x, Y, ad.wv, ad.bv, x->ad_v, H, rows, H, H);
+  } else {
+    { Scope s(x, KC_RMSNORM); launch_rmsnorm(xin, H, ad.norm, c.dtype, c.rms_eps, x->a_norm, H, H, rows, x->st); }
+    gemm_generic(x, KC_GEMM_DRAFT, x->a_norm, H, ad.wq, ad.bq, x->ad_q, H, rows, H, H, 0);
+    gemm_generic(x, KC_GEMM_DRAFT, y, H, ad.wk, ad.bk, x->ad_k, H, rows, H, H, 0);
+    gemm_generic(x, KC_GEMM_DRAFT, y, H, ad.wv, ad.bv, x->ad_v, H, rows, H, H, 0);
+  }
   { Scope s(x, KC_AD_GATE);
     launch_ad_gate(xin, H, x->ad_q, x->ad_k, x->ad_v, H, c.ad_heads, out, H, nullptr, 0, rows, x->st); }
+}
+
+// Y = X W^T + bias for a draft-side FC with fp32 input X [rows, K]
+void run_fc(clover_ctx* x, const float* X, int K, const void* W, const void* bias, float* Y, int rows) {
+  const int H = x->H;
+  if (x->fast) {
+    Planes P = split_to(x, X, K, x->pl_y, rows, K);
+    linear_fast(x, P, W, bias, Y, H, rows, H, K);
+  } else {
+    gemm_generic(x, KC_GEMM_DRAFT, X, K, W, bias, Y, H, rows, H, K, 0);
+  }
 }
 
 // logits of `rows` contiguous rows of g through the head norm and the shared LM head, then top-k
 void run_head(clover_ctx* x, const float* g, int rows, int k) {
   const clover_config& c = x->cfg;
   const int H = x->H;
-  { Scope s(x, KC_RMSNORM); launch_rmsnorm(g, H, x->w.head_norm, c.dtype, c.rms_eps, x->a_norm, H, H, rows, x->st); }
-  gemm1(x, KC_GEMM_LMHEAD, x->a_norm, H, x->w.lm_head, nullptr, x->z, c.vocab, rows, c.vocab, H, 0);
+  if (x->fast) {
+    Planes A = norm_planes(x, g, x->w.head_norm, rows);
+    gemm_fast1(x, KC_GEMM_LMHEAD, A, x->w.lm_head, rows, c.vocab, H, x->z, c.vocab);
+  } else {
+    { Scope s(x, KC_RMSNORM); launch_rmsnorm(g, H, x->w.head_norm, c.dtype, c.rms_eps, x->a_norm, H, H, rows, x->st); }
+    gemm_generic(x, KC_GEMM_LMHEAD, x->a_norm, H, x->w.lm_head, nullptr, x->z, c.vocab, rows, c.vocab, H, 0);
+  }
   { Scope s(x, KC_TOPK); launch_topk(x->z, c.vocab, c.vocab, rows, k, x->cand, x->topk_ids, x->st); }
 }
 
@@ -498,7 +588,6 @@ int clover_init(const clover_config* cfg, const clover_weights* w, const clover_
   launch_fill_i32(x->d_seq_len, 0, cfg->max_batch, x->st);
   launch_fill_i32(x->d_aug_len, 0, cfg->max_batch, x->st);
   launch_fill_i32(x->d_err, 0, 1, x->st);
-  launch_fill_i32(x->counters, 0, x->n_counters, x->st);
   rc = upload_tree(x);
   if (rc == CLOVER_OK) rc = finish(x, "init");
   if (rc) { g_err = x->err; delete x; return rc; }
@@ -554,9 +643,11 @@ int draft_tree(clover_ctx* x, int32_t batch, const float* hid_acc, const int32_t
   { Scope s(x, KC_EMBED); launch_embed(x->w.lm_head, c.dtype, next_tok, c.vocab, x->d_e, H, H, rm, x->st); }
   run_ad(x, x->w.ad1, hid_acc, x->d_e, M, x->xd);
   { Scope s(x, KC_ROPE_KV); launch_rope_table(x->d_aug_len, nullptr, c.rope_base, c.head_dim, x->cos_t, x->sin_t, rm, x->st); }
+  if (x->fast) norm_planes(x, x->xd, x->aug[0].attn_norm, M);
   for (int l = 0; l < c.aug_layers; ++l)
     run_layer(x, x->aug[l], x->xd, rm, M, x->aug_kc + (size_t)l * x->k_layer_elems * x->kv_esz,
-              x->aug_vc + (size_t)l * x->v_layer_elems * x->kv_esz, x->d_aug_len, x->d_anc_chain);
+              x->aug_vc + (size_t)l * x->v_layer_elems * x->kv_esz, x->d_aug_len, x->d_anc_chain,
+              l + 1 < c.aug_layers ? x->aug[l + 1].attn_norm : nullptr);
   { Scope s(x, KC_DRAFT_MISC);
     launch_draft_root(x->xd, next_tok, m, B, R, H, x->d_rootx, x->d_state, tree_tokens, x->st);
     launch_add_len(x->d_aug_len, m, B, x->st); }
@@ -568,7 +659,7 @@ int draft_tree(clover_ctx* x, int32_t batch, const float* hid_acc, const int32_t
       if (n_lvl == 0) break;
       const int rows = B * n_lvl;
       if (j == 0) {
-        gemm1(x, KC_GEMM_DRAFT, x->d_rootx, H, x->w.fc0_w, x->w.fc0_b, x->d_g, H, rows, H, H, 0);
+        run_fc(x, x->d_rootx, H, x->w.fc0_w, x->w.fc0_b, x->d_g, rows);
       } else {
         const int* nodes = x->d_lvl_nodes + t.lvl_off[j];
         { Scope s(x, KC_DRAFT_MISC);
@@ -577,7 +668,7 @@ int draft_tree(clover_ctx* x, int32_t batch, const float* hid_acc, const int32_t
         run_ad(x, x->w.ad2, x->d_xs, x->d_e, rows, x->d_s);
         { Scope s(x, KC_DRAFT_MISC);
           launch_draft_scatter_state(x->d_s, nodes, n_lvl, B, R, H, x->d_state, x->d_cat, x->st); }
-        gemm1(x, KC_GEMM_DRAFT, x->d_cat, 2 * H, x->fc_w[j], x->fc_b[j], x->d_g, H, rows, H, 2 * H, 0);
+        run_fc(x, x->d_cat, 2 * H, x->fc_w[j], x->fc_b[j], x->d_g, rows);
       }
       run_head(x, x->d_g, rows, t.kmax[j]);
       { Scope s(x, KC_DRAFT_MISC);
@@ -601,11 +692,19 @@ int verify_tree(clover_ctx* x, int32_t batch, const int32_t* tree_tokens, float*
   const int M = (B - 1) * R + t.n;
   { Scope s(x, KC_EMBED); launch_embed(x->w.embed, c.dtype, tree_tokens, c.vocab, hidden, H, H, rm, x->st); }
   { Scope s(x, KC_ROPE_KV); launch_rope_table(x->d_seq_len, x->d_depth, c.rope_base, c.head_dim, x->cos_t, x->sin_t, rm, x->st); }
+  if (x->fast) norm_planes(x, hidden, x->layers[0].attn_norm, M);
   for (int l = 0; l < c.n_layers; ++l)
     run_layer(x, x->layers[l], hidden, rm, M, x->kc + (size_t)l * x->k_layer_elems * x->kv_esz,
-              x->vc + (size_t)l * x->v_layer_elems * x->kv_esz, x->d_seq_len, x->d_anc);
-  { Scope s(x, KC_RMSNORM); launch_rmsnorm(hidden, H, x->w.final_norm, c.dtype, c.rms_eps, x->a_norm, H, H, M, x->st); }
-  gemm1(x, KC_GEMM_LMHEAD, x->a_norm, H, x->w.lm_head, nullptr, logits, c.vocab, M, c.vocab, H, 0);
+              x->vc + (size_t)l * x->v_layer_elems * x->kv_esz, x->d_seq_len, x->d_anc,
+              l + 1 < c.n_layers ? x->layers[l + 1].attn_norm : x->w.final_norm);
+  if (x->fast) {
+    Planes A = planes_of(x, x->a_norm, 2 * H);
+    A.ld = H;
+    gemm_fast1(x, KC_GEMM_LMHEAD, A, x->w.lm_head, M, c.vocab, H, logits, c.vocab);
+  } else {
+    { Scope s(x, KC_RMSNORM); launch_rmsnorm(hidden, H, x->w.final_norm, c.dtype, c.rms_eps, x->a_norm, H, H, M, x->st); }
+    gemm_generic(x, KC_GEMM_LMHEAD, x->a_norm, H, x->w.lm_head, nullptr, logits, c.vocab, M, c.vocab, H, 0);
+  }
   return finish(x, "verify_tree");
 }
 
@@ -705,11 +804,8 @@ const char* clover_last_global_error(void) { return g_err.c_str(); }
 size_t clover_op_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K) {
   if (M < 1 || N < 1 || K < 1) return 256;
   size_t bytes = 256;
-  const int mm = std::min(M, 256);
-  if (mfma_gemm_supported(mm, N, K, 0)) {
-    const int s = mfma_gemm_pick_splits(mm, N, K, 0);
-    bytes = align256(mfma_gemm_partial_bytes(mm, N, K, 0, s)) + align256((size_t)mfma_gemm_counters(N, 0) * sizeof(int)) + 256;
-  }
+  if (M <= 256 && mfma_gemm_supported(M, N, K, 0))
+    bytes += align256((size_t)M * K * 4) + align256(mfma_gemm_out_bytes(M, N, mfma_gemm_pick_splits(M, N, K, 0)));
   return bytes;
 }
 
@@ -721,21 +817,23 @@ int clover_op_gemm(int32_t path, int32_t dtype, const float* X, const void* W, f
   if (path == 0) {
     launch_gemm_generic(X, K, W, nullptr, dtype, Y, ldy, M, N, K, 0, st);
   } else {
-    if (dtype != CLOVER_DTYPE_BF16 || M > 256 || !mfma_gemm_supported(M, N, K, 0) || (ldy % 4) != 0)
+    if (dtype != CLOVER_DTYPE_BF16 || M > 256 || !mfma_gemm_supported(M, N, K, 0))
       return fail(nullptr, CLOVER_E_SHAPE, "shape not supported by the MFMA GEMM");
     if (scratch_bytes < clover_op_gemm_scratch_bytes(M, N, K)) return fail(nullptr, CLOVER_E_CAPACITY, "scratch too small");
+    bf16_t* hi = (bf16_t*)scratch;
+    bf16_t* lo = hi + (size_t)M * K;
+    float* part = (float*)((char*)scratch + align256((size_t)M * K * 4));
+    launch_split_planes(X, K, hi, lo, K, M, K, st);
     MfmaGemm g;
     memset(&g, 0, sizeof(g));
-    g.X = X; g.ldx = K;
+    g.Xhi = hi; g.Xlo = lo; g.ldx = K;
     g.W[0] = g.W[1] = g.W[2] = (const bf16_t*)W;
     g.seg_begin[0] = 0; g.seg_begin[1] = g.seg_begin[2] = g.seg_begin[3] = 0x7fffffff;
-    g.Y = Y; g.ldy = ldy; g.M = M; g.N = N; g.K = K; g.mode = 0;
+    g.Y = part; g.ldy = N; g.split_stride = (size_t)M * N;
+    g.M = M; g.N = N; g.K = K; g.mode = 0;
     g.splits = mfma_gemm_pick_splits(M, N, K, 0);
-    const size_t pb = align256(mfma_gemm_partial_bytes(M, N, K, 0, g.splits));
-    g.partial = (float*)scratch;
-    g.counters = (int*)((char*)scratch + pb);
-    launch_fill_i32(g.counters, 0, mfma_gemm_counters(N, 0), st);
     launch_gemm_mfma(g, st);
+    launch_reduce(part, g.splits, g.split_stride, N, nullptr, dtype, Y, ldy, M, N, 0, st);
   }
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(nullptr, CLOVER_E_HIP, hipGetErrorString(e));

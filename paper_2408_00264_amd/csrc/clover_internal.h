@@ -34,12 +34,13 @@ void launch_rmsnorm(const float* x, int ldx, const void* gain, int wdtype, float
                     int rows, hipStream_t st);
 void launch_rope_table(const int* base_len, const int* depth /*null: row index*/, float rope_base, int d,
                        float* cos_t, float* sin_t, RowMap rm, hipStream_t st);
-void launch_rope_kv_write(const float* qkv, int ldqkv, const float* cos_t, const float* sin_t, float* q_out, int ldq,
+void launch_rope_kv_write(const float* qkv, int ldqkv, int qkv_splits, size_t qkv_split_stride, const float* cos_t, const float* sin_t, float* q_out, int ldq,
                           void* k_cache, void* v_cache, int kvdtype, KVLayout kv, const int* base_len, int n_q,
                           RowMap rm, int* err_flag, hipStream_t st);
 void launch_attn_generic(const float* q, int ldq, const void* k_cache, const void* v_cache, int kvdtype, KVLayout kv,
                          const int* base_len, const unsigned long long* anc /*[n][2]*/, int n_q, float* out, int ldo,
-                         RowMap rm, hipStream_t st);
+                         bf16_t* out_hi, bf16_t* out_lo /*planes instead of fp32 when non-null*/, RowMap rm,
+                         hipStream_t st);
 // mode 0: Y = X W^T (+bias); mode 1: Y += X W^T (+bias)
 void launch_gemm_generic(const float* X, int ldx, const void* W, const void* bias, int wdtype, float* Y, int ldy,
                          int M, int N, int K, int mode, hipStream_t st);
@@ -81,24 +82,35 @@ void launch_read_kv(const void* k_cache, const void* v_cache, int kvdtype, KVLay
                     float* k_out, float* v_out, hipStream_t st);
 void launch_fill_i32(int* p, int v, int n, hipStream_t st);
 
-// ---- MFMA weight-streaming GEMM (bf16 weights, fp32 activations in, fp32 out) -------------------
+// ---- split-bf16 activation planes and partial-sum consumers ------------------------------------
+// An activation matrix that feeds the MFMA GEMM is stored as two bf16 planes (hi, lo) with
+// hi + lo == x to 16 mantissa bits.
+void launch_split_planes(const float* x, int ldx, bf16_t* hi, bf16_t* lo, int ldo, int rows, int K, hipStream_t st);
+// Y[m,n] (=|+=) sum_s P[s*split_stride + m*ldp + n] (+ bias[n]);  mode 0 store, 1 add
+void launch_reduce(const float* P, int splits, size_t split_stride, int ldp, const void* bias, int wdtype, float* Y,
+                   int ldy, int M, int N, int mode, hipStream_t st);
+// x[m,:] += sum_s P[s][m][:]  (splits may be 0); then, if gain: (hi, lo)[m,:] = split(rmsnorm(x[m,:]) * gain)
+void launch_reduce_add_norm(float* x, int ldx, const float* P, int splits, size_t split_stride, int ldp,
+                            const void* gain, int wdtype, float eps, bf16_t* hi, bf16_t* lo, int ldo, int rows, int H,
+                            hipStream_t st);
+
+// ---- MFMA weight-streaming GEMM (bf16 weights, split-bf16 activations in, fp32 out) -------------
 struct MfmaGemm {
-  const float* X; int ldx;
+  const bf16_t *Xhi, *Xlo; int ldx;   // activation planes [M, K]
   const bf16_t* W[3];      // up to three row-segments (fused QKV); plain GEMM uses W[0]
   int seg_begin[4];        // segment s covers output columns [seg_begin[s], seg_begin[s+1])
   const bf16_t* W_up;      // mode 2: second matrix (W[0] = gate)
-  const bf16_t* bias;      // optional [N]
-  float* Y; int ldy;
+  float* Y; int ldy;       // mode 0: split s writes Y[s*split_stride + m*ldy + n]
+  size_t split_stride;
+  bf16_t *Yhi, *Ylo;       // mode 2: silu(X Wg^T) * (X Wu^T) as planes, leading dimension ldy
   int M, N, K;
-  int mode;                // 0 store, 1 add into Y, 2 Y = silu(X Wg^T) * (X Wu^T)
-  int splits;              // split-K factor (>=1)
-  float* partial;          // scratch for split-K partial tiles
-  int* counters;           // one int per workgroup column, zero before and after each launch
+  int mode;                // 0 partial/plain fp32 store, 2 SwiGLU
+  int splits;              // split-K factor (>=1; 1 for mode 2)
+  int dbg;                 // timing experiments only (CLOVER_GEMM_DBG): 1 no MFMA, 2 no weight loads, 4 no activation loads
 };
 bool mfma_gemm_supported(int M, int N, int K, int mode);
 int mfma_gemm_pick_splits(int M, int N, int K, int mode);
-size_t mfma_gemm_partial_bytes(int M, int N, int K, int mode, int splits);
-int mfma_gemm_counters(int N, int mode);
+size_t mfma_gemm_out_bytes(int M, int N, int splits);
 void launch_gemm_mfma(const MfmaGemm& g, hipStream_t st);
 
 }  // namespace clv

@@ -125,7 +125,8 @@ void launch_rope_table(const int* base_len, const int* depth, float rope_base, i
 // blocks [0, n): one row each (q out, K row); blocks [n, n + vblocks): 32 (head,dim) lines of V^T
 // ------------------------------------------------------------------------------------------
 template <typename KT>
-__global__ void rope_kv_write_kernel(const float* __restrict__ qkv, int ldqkv, const float* __restrict__ cos_t,
+__global__ void rope_kv_write_kernel(const float* __restrict__ qkv, int ldqkv, int nsp, size_t sps,
+                                     const float* __restrict__ cos_t,
                                      const float* __restrict__ sin_t, float* __restrict__ q_out, int ldq,
                                      KT* __restrict__ kc, KT* __restrict__ vc, KVLayout kv,
                                      const int* __restrict__ base_len, int n_q, RowMap rm, int* err_flag) {
@@ -146,7 +147,11 @@ __global__ void rope_kv_write_kernel(const float* __restrict__ qkv, int ldqkv, c
     for (int idx = threadIdx.x; idx < (n_q + n_kv) * half; idx += blockDim.x) {
       const int hh = idx / half, ii = idx - hh * half;
       const float c = cos_t[row * half + ii], s = sin_t[row * half + ii];
-      const float x1 = src[hh * d + ii], x2 = src[hh * d + ii + half];
+      float x1 = src[hh * d + ii], x2 = src[hh * d + ii + half];
+      for (int sp = 1; sp < nsp; ++sp) {   // split-K partials of the QKV projection, fixed order
+        x1 += src[sp * sps + hh * d + ii];
+        x2 += src[sp * sps + hh * d + ii + half];
+      }
       const float o1 = x1 * c - x2 * s, o2 = x2 * c + x1 * s;
       if (hh < n_q) {
         q_out[row * ldq + hh * d + ii] = o1;
@@ -163,22 +168,24 @@ __global__ void rope_kv_write_kernel(const float* __restrict__ qkv, int ldqkv, c
     for (int idx = threadIdx.x; idx < 32 * rm.n; idx += blockDim.x) {
       const int node = idx % rm.n, e = vb * 32 + idx / rm.n;
       if (node >= nv || e >= n_kv * d) continue;
-      const float v = qkv[((size_t)b * rm.R + node) * ldqkv + voff + e];
+      float v = qkv[((size_t)b * rm.R + node) * ldqkv + voff + e];
+      for (int sp = 1; sp < nsp; ++sp) v += qkv[sp * sps + ((size_t)b * rm.R + node) * ldqkv + voff + e];
       stf(vc, ((size_t)b * n_kv * d + e) * kv.max_seq + L + node, v);
     }
   }
 }
 
-void launch_rope_kv_write(const float* qkv, int ldqkv, const float* cos_t, const float* sin_t, float* q_out, int ldq,
+void launch_rope_kv_write(const float* qkv, int ldqkv, int qkv_splits, size_t qkv_split_stride, const float* cos_t,
+                          const float* sin_t, float* q_out, int ldq,
                           void* k_cache, void* v_cache, int kvdtype, KVLayout kv, const int* base_len, int n_q,
                           RowMap rm, int* err_flag, hipStream_t st) {
   const int vblocks = (kv.n_kv * kv.d + 31) / 32;
   dim3 grid(rm.n + vblocks, rm.B);
   if (kvdtype == 0)
-    rope_kv_write_kernel<float><<<grid, 256, 0, st>>>(qkv, ldqkv, cos_t, sin_t, q_out, ldq, (float*)k_cache,
+    rope_kv_write_kernel<float><<<grid, 256, 0, st>>>(qkv, ldqkv, qkv_splits, qkv_split_stride, cos_t, sin_t, q_out, ldq, (float*)k_cache,
                                                       (float*)v_cache, kv, base_len, n_q, rm, err_flag);
   else
-    rope_kv_write_kernel<bf16_t><<<grid, 256, 0, st>>>(qkv, ldqkv, cos_t, sin_t, q_out, ldq, (bf16_t*)k_cache,
+    rope_kv_write_kernel<bf16_t><<<grid, 256, 0, st>>>(qkv, ldqkv, qkv_splits, qkv_split_stride, cos_t, sin_t, q_out, ldq, (bf16_t*)k_cache,
                                                        (bf16_t*)v_cache, kv, base_len, n_q, rm, err_flag);
 }
 
@@ -190,7 +197,7 @@ template <typename KT>
 __global__ void attn_generic_kernel(const float* __restrict__ q, int ldq, const KT* __restrict__ kc,
                                     const KT* __restrict__ vc, KVLayout kv, const int* __restrict__ base_len,
                                     const unsigned long long* __restrict__ anc, int n_q, float* __restrict__ out,
-                                    int ldo, RowMap rm) {
+                                    int ldo, bf16_t* __restrict__ out_hi, bf16_t* __restrict__ out_lo, RowMap rm) {
   __shared__ float qs[128];
   __shared__ float ps[64];
   const int h = blockIdx.x, i = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
@@ -245,20 +252,31 @@ __global__ void attn_generic_kernel(const float* __restrict__ q, int ldq, const 
     }
   }
   const float inv = 1.0f / lrun;
+  if (out_hi) {
+    const float r0 = o0 * inv, r1 = o1 * inv;
+    const bf16_t h0 = f32_to_bf16(r0), h1 = f32_to_bf16(r1);
+    out_hi[row * ldo + h * d + lane] = h0;
+    out_lo[row * ldo + h * d + lane] = f32_to_bf16(r0 - bf16_to_f32(h0));
+    if (d > 64) {
+      out_hi[row * ldo + h * d + 64 + lane] = h1;
+      out_lo[row * ldo + h * d + 64 + lane] = f32_to_bf16(r1 - bf16_to_f32(h1));
+    }
+    return;
+  }
   out[row * ldo + h * d + lane] = o0 * inv;
   if (d > 64) out[row * ldo + h * d + 64 + lane] = o1 * inv;
 }
 
 void launch_attn_generic(const float* q, int ldq, const void* k_cache, const void* v_cache, int kvdtype, KVLayout kv,
-                         const int* base_len, const unsigned long long* anc, int n_q, float* out, int ldo, RowMap rm,
-                         hipStream_t st) {
+                         const int* base_len, const unsigned long long* anc, int n_q, float* out, int ldo,
+                         bf16_t* out_hi, bf16_t* out_lo, RowMap rm, hipStream_t st) {
   dim3 grid(n_q, rm.n, rm.B);
   if (kvdtype == 0)
     attn_generic_kernel<float><<<grid, 64, 0, st>>>(q, ldq, (const float*)k_cache, (const float*)v_cache, kv, base_len,
-                                                    anc, n_q, out, ldo, rm);
+                                                    anc, n_q, out, ldo, out_hi, out_lo, rm);
   else
     attn_generic_kernel<bf16_t><<<grid, 64, 0, st>>>(q, ldq, (const bf16_t*)k_cache, (const bf16_t*)v_cache, kv,
-                                                     base_len, anc, n_q, out, ldo, rm);
+                                                     base_len, anc, n_q, out, ldo, out_hi, out_lo, rm);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -666,6 +684,95 @@ void launch_read_kv(const void* k_cache, const void* v_cache, int kvdtype, KVLay
   else
     read_kv_kernel<bf16_t><<<blocks, 256, 0, st>>>((const bf16_t*)k_cache, (const bf16_t*)v_cache, kv, b, slot0,
                                                    n_slots, k_out, v_out);
+}
+
+// ------------------------------------------------------------------------------------------
+// split-bf16 planes and partial-sum consumers
+// ------------------------------------------------------------------------------------------
+__global__ void split_planes_kernel(const float* __restrict__ x, int ldx, bf16_t* __restrict__ hi,
+                                    bf16_t* __restrict__ lo, int ldo, int K) {
+  const size_t row = blockIdx.y;
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= K) return;
+  const float v = x[row * ldx + c];
+  const bf16_t h = f32_to_bf16(v);
+  hi[row * ldo + c] = h;
+  lo[row * ldo + c] = f32_to_bf16(v - bf16_to_f32(h));
+}
+void launch_split_planes(const float* x, int ldx, bf16_t* hi, bf16_t* lo, int ldo, int rows, int K, hipStream_t st) {
+  if (rows <= 0) return;
+  split_planes_kernel<<<dim3((K + 255) / 256, rows), 256, 0, st>>>(x, ldx, hi, lo, ldo, K);
+}
+
+template <typename WT>
+__global__ void reduce_kernel(const float* __restrict__ P, int splits, size_t sps, int ldp, const WT* __restrict__ bias,
+                              float* __restrict__ Y, int ldy, int N, int mode) {
+  const size_t row = blockIdx.y;
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= N) return;
+  float v = 0.f;
+  for (int s = 0; s < splits; ++s) v += P[s * sps + row * ldp + c];
+  if (bias) v += ldf(bias, c);
+  float* y = Y + row * ldy + c;
+  *y = mode == 1 ? *y + v : v;
+}
+void launch_reduce(const float* P, int splits, size_t split_stride, int ldp, const void* bias, int wdtype, float* Y,
+                   int ldy, int M, int N, int mode, hipStream_t st) {
+  if (M <= 0) return;
+  dim3 grid((N + 255) / 256, M);
+  if (wdtype == 0)
+    reduce_kernel<float><<<grid, 256, 0, st>>>(P, splits, split_stride, ldp, (const float*)bias, Y, ldy, N, mode);
+  else
+    reduce_kernel<bf16_t><<<grid, 256, 0, st>>>(P, splits, split_stride, ldp, (const bf16_t*)bias, Y, ldy, N, mode);
+}
+
+// one block per row: residual add of the split-K partials, then RMSNorm written as planes
+template <typename WT>
+__global__ __launch_bounds__(256) void reduce_add_norm_kernel(float* __restrict__ x, int ldx,
+                                                              const float* __restrict__ P, int splits, size_t sps,
+                                                              int ldp, const WT* __restrict__ gain, float eps,
+                                                              bf16_t* __restrict__ hi, bf16_t* __restrict__ lo,
+                                                              int ldo, int H) {
+  __shared__ float red[4];
+  const size_t row = blockIdx.x;
+  float* xr = x + row * ldx;
+  float ss = 0.f;
+  for (int c = threadIdx.x * 4; c < H; c += 1024) {
+    float4 v = *(const float4*)(xr + c);
+    for (int s = 0; s < splits; ++s) {
+      const float4 q = *(const float4*)(P + s * sps + row * ldp + c);
+      v.x += q.x; v.y += q.y; v.z += q.z; v.w += q.w;
+    }
+    if (splits > 0) *(float4*)(xr + c) = v;
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  if (!gain) return;
+  ss = block_sum_256(ss, red);
+  const float scale = 1.0f / sqrtf(ss / (float)H + eps);
+  for (int c = threadIdx.x * 4; c < H; c += 1024) {
+    const float4 v = *(const float4*)(xr + c);   // written by this same thread above
+    const float o[4] = {v.x * scale * ldf(gain, c), v.y * scale * ldf(gain, c + 1), v.z * scale * ldf(gain, c + 2),
+                        v.w * scale * ldf(gain, c + 3)};
+    bf16_t h[4], l[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      h[r] = f32_to_bf16(o[r]);
+      l[r] = f32_to_bf16(o[r] - bf16_to_f32(h[r]));
+    }
+    *(uint2*)(hi + row * ldo + c) = make_uint2((unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16));
+    *(uint2*)(lo + row * ldo + c) = make_uint2((unsigned)l[0] | ((unsigned)l[1] << 16), (unsigned)l[2] | ((unsigned)l[3] << 16));
+  }
+}
+void launch_reduce_add_norm(float* x, int ldx, const float* P, int splits, size_t split_stride, int ldp,
+                            const void* gain, int wdtype, float eps, bf16_t* hi, bf16_t* lo, int ldo, int rows, int H,
+                            hipStream_t st) {
+  if (rows <= 0) return;
+  if (wdtype == 0)
+    reduce_add_norm_kernel<float><<<rows, 256, 0, st>>>(x, ldx, P, splits, split_stride, ldp, (const float*)gain, eps,
+                                                        hi, lo, ldo, H);
+  else
+    reduce_add_norm_kernel<bf16_t><<<rows, 256, 0, st>>>(x, ldx, P, splits, split_stride, ldp, (const bf16_t*)gain,
+                                                         eps, hi, lo, ldo, H);
 }
 
 }  // namespace clv

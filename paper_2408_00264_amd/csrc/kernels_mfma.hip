@@ -8,17 +8,19 @@
 //   B operand.  A wavefront owns NF 16-row weight blocks and all M activation rows; each lane loads
 //   its 16-byte A fragments straight from global memory into registers (row = lane%16,
 //   k = 8*(lane/16)..+7): every weight byte is read exactly once.
-// * Activations are fp32.  A random-init 32-layer stack amplifies a bf16 rounding of the
-//   activations about twenty-fold by the last layer, so each activation is split into
-//   hi = bf16(x) and lo = bf16(x - hi) and both halves are multiplied (two MFMAs per fragment):
-//   16 mantissa bits, at no cost in HBM traffic.  The split chunk is staged once per workgroup in LDS.
+// * A random-init 32-layer stack amplifies a bf16 rounding of the activations about twenty-fold by
+//   the last layer, so each activation x arrives as two bf16 planes, hi = bf16(x) and
+//   lo = bf16(x - hi), and both halves are multiplied (two MFMAs per fragment): 16 mantissa bits,
+//   at no cost in HBM traffic.  The planes are written once by the kernel that produces x.
+// * Two producer wavefronts copy the activation chunk of step i+1 into LDS while four consumer
+//   wavefronts multiply step i.  The consumers' memory queue holds nothing but the weight stream,
+//   three chunks deep (registers), so they never wait behind a short-latency activation load.
 // * Weight rows are K*2 bytes apart, a power of two: workgroups that walk K in the same order all
 //   hit the same few HBM channels at the same time.  Each workgroup therefore starts at a different
 //   (rotated) K chunk.
-// * Software pipeline: the weight fragments and the activation chunk of step i+1 are in flight
-//   (registers / second LDS buffer) while step i is multiplied.
-// * Split-K partial tiles are combined by the last workgroup to arrive, in a fixed order, so the
-//   result does not depend on scheduling.
+// * Split-K: every split writes its own fp32 partial tile; the kernel that consumes the result
+//   (RoPE, residual add + RMSNorm, bias add) sums the partials in a fixed order.  No atomics, no
+//   in-kernel fences, results independent of scheduling.
 #include "clover_internal.h"
 
 #include <cstdlib>
@@ -58,7 +60,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(MfmaGemm p) {
   constexpr int ROWS = MT * 16;
   constexpr int PLANE = ROWS * LDK;  // one bf16 plane (hi or lo) of one buffer
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];  // [2 buffers][hi, lo][ROWS][LDK]
-  __shared__ int s_last;
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int l16 = lane & 15, g4 = lane >> 4;
@@ -92,40 +93,26 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(MfmaGemm p) {
     // ---------------- producer wavefronts: X[:, chunk] -> (hi, lo) bf16 planes in LDS ----------------
     // Their memory queue holds only these short-latency (L2) loads, so they never wait behind the
     // long HBM weight stream of the consumers.
-    constexpr int TPR = KC / 8;                    // threads per activation row (8 consecutive k each)
-    constexpr int RPP = (64 * GEMM_PW) / TPR;      // rows per pass
-    constexpr int NPASS = (ROWS + RPP - 1) / RPP;
+    constexpr int SLOTS = KC / 8;                  // 16-byte slots per row and plane
+    constexpr int NIT = (2 * ROWS * SLOTS) / (64 * GEMM_PW);
+    static_assert((2 * ROWS * SLOTS) % (64 * GEMM_PW) == 0, "chunk must divide among the producer lanes");
     const int ptid = tid - 64 * GEMM_CW;
-    const int srow = ptid / TPR, skk = (ptid % TPR) * 8;
     auto stage_x = [&](int kc, int buf) {
-      float4 xr[NPASS][2];
+      u32x4 v[NIT];
 #pragma unroll
-      for (int ps = 0; ps < NPASS; ++ps) {
-        const int r = ps * RPP + srow;
-        if (r < M && r < ROWS) {
-          const float4* src = (const float4*)(p.X + (size_t)r * p.ldx + kc + skk);
-          xr[ps][0] = src[0];
-          xr[ps][1] = src[1];
-        } else {
-          xr[ps][0] = make_float4(0.f, 0.f, 0.f, 0.f);
-          xr[ps][1] = make_float4(0.f, 0.f, 0.f, 0.f);
-        }
+      for (int it = 0; it < NIT; ++it) {
+        const int idx = it * (64 * GEMM_PW) + ptid;
+        const int plane = idx / (ROWS * SLOTS), rem = idx % (ROWS * SLOTS);
+        const int r = rem / SLOTS, sl = rem % SLOTS;
+        v[it] = (u32x4){0u, 0u, 0u, 0u};
+        if (r < M && !(p.dbg & 4)) v[it] = *(const u32x4*)((plane ? p.Xlo : p.Xhi) + (size_t)r * p.ldx + kc + sl * 8);
       }
-      bf16_t* hi = smem + (size_t)buf * 2 * PLANE;
-      bf16_t* lo = hi + PLANE;
 #pragma unroll
-      for (int ps = 0; ps < NPASS; ++ps) {
-        const int r = ps * RPP + srow;
-        if (r < ROWS) {
-          u32x4 h, l;
-          unsigned a, b;
-          split2(xr[ps][0].x, xr[ps][0].y, a, b); h.x = a; l.x = b;
-          split2(xr[ps][0].z, xr[ps][0].w, a, b); h.y = a; l.y = b;
-          split2(xr[ps][1].x, xr[ps][1].y, a, b); h.z = a; l.z = b;
-          split2(xr[ps][1].z, xr[ps][1].w, a, b); h.w = a; l.w = b;
-          *(u32x4*)(hi + r * LDK + skk) = h;
-          *(u32x4*)(lo + r * LDK + skk) = l;
-        }
+      for (int it = 0; it < NIT; ++it) {
+        const int idx = it * (64 * GEMM_PW) + ptid;
+        const int plane = idx / (ROWS * SLOTS), rem = idx % (ROWS * SLOTS);
+        const int r = rem / SLOTS, sl = rem % SLOTS;
+        *(u32x4*)(smem + (size_t)(buf * 2 + plane) * PLANE + r * LDK + sl * 8) = v[it];
       }
     };
     if (n_it > 0) {
@@ -162,15 +149,23 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(MfmaGemm p) {
     constexpr int RING = 4;        // weight fragments of up to three future chunks are in flight
     Frag w[RING][NF][KS];
     auto load_w = [&](int slot, int kc) {
-      if (!active) return;
+      if (!active || (p.dbg & 2)) return;
 #pragma unroll
       for (int f = 0; f < NF; ++f)
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-          w[slot][f][ks].u = __builtin_nontemporal_load((const u32x4*)(wrow[f] + kc + ks * 32));
+          w[slot][f][ks].u = (p.dbg & 8) ? *(const u32x4*)(wrow[f] + kc + ks * 32)
+                                         : __builtin_nontemporal_load((const u32x4*)(wrow[f] + kc + ks * 32));
     };
     auto compute = [&](int slot, int buf) {
       if (!active) return;
+      if (p.dbg & 1) {  // keep the loads alive without the matrix work
+#pragma unroll
+        for (int f = 0; f < NF; ++f)
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) acc[f][0][0] += __uint_as_float(w[slot][f][ks].u.x & 0x3f800000u);
+        return;
+      }
       const bf16_t* hi = smem + (size_t)buf * 2 * PLANE + l16 * LDK + g4 * 8;
       const bf16_t* lo = hi + PLANE;
 #pragma unroll
@@ -212,76 +207,34 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(MfmaGemm p) {
     }
   }
 
-  // ---- split-K: publish the partial tile; the last workgroup of this column sums all of them ----
-  if (p.splits > 1) {
-    // layout [tile][split][wave][f][mb][lane] of f32x4: a lane re-reads exactly its own positions
-    f32x4* part = (f32x4*)p.partial;
-    const size_t tile_stride = (size_t)p.splits * 4 * NF * MT * 64;
-    const size_t base = (size_t)blockIdx.x * tile_stride;
-    if (!producer) {
-#pragma unroll
-      for (int f = 0; f < NF; ++f)
-#pragma unroll
-        for (int mb = 0; mb < MT; ++mb)
-          part[base + ((((size_t)blockIdx.y * 4 + wave) * NF + f) * MT + mb) * 64 + lane] = acc[f][mb];
-    }
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-      const int prev = atomicAdd(&p.counters[blockIdx.x], 1);
-      s_last = (prev == p.splits - 1) ? 1 : 0;
-    }
-    __syncthreads();
-    if (!s_last || producer) return;
-    __threadfence();
-#pragma unroll
-    for (int f = 0; f < NF; ++f)
-#pragma unroll
-      for (int mb = 0; mb < MT; ++mb) {
-        f32x4 sum = (f32x4){0.f, 0.f, 0.f, 0.f};
-        for (int s = 0; s < p.splits; ++s)
-          sum += __builtin_nontemporal_load(&part[base + ((((size_t)s * 4 + wave) * NF + f) * MT + mb) * 64 + lane]);
-        acc[f][mb] = sum;
-      }
-    if (tid == 0) p.counters[blockIdx.x] = 0;  // ready for the next launch on this stream
-  }
   if (!active) return;
 
-  // ---- epilogue: lane holds Y[m = mb*16 + l16][col + 4*g4 + 0..3] ----
+  // ---- epilogue: lane holds rows m = mb*16 + l16, columns col + 4*g4 + 0..3 ----
 #pragma unroll
   for (int mb = 0; mb < MT; ++mb) {
     const int m = mb * 16 + l16;
     if (m >= M) continue;
-    float* yrow = p.Y + (size_t)m * p.ldy;
     if (p.mode == 2) {
       constexpr int HF = NF / 2 > 0 ? NF / 2 : 1;
 #pragma unroll
       for (int f = 0; f < HF; ++f) {
         const f32x4 g = acc[f][mb], u = acc[(f + HF) % NF][mb];
-        float4 o;
-        o.x = g[0] / (1.0f + expf(-g[0])) * u[0];
-        o.y = g[1] / (1.0f + expf(-g[1])) * u[1];
-        o.z = g[2] / (1.0f + expf(-g[2])) * u[2];
-        o.w = g[3] / (1.0f + expf(-g[3])) * u[3];
-        *(float4*)(yrow + col[f] + 4 * g4) = o;
+        float o[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o[r] = g[r] / (1.0f + expf(-g[r])) * u[r];
+        unsigned h0, l0, h1, l1;
+        split2(o[0], o[1], h0, l0);
+        split2(o[2], o[3], h1, l1);
+        const size_t off = (size_t)m * p.ldy + col[f] + 4 * g4;
+        *(uint2*)(p.Yhi + off) = make_uint2(h0, h1);
+        *(uint2*)(p.Ylo + off) = make_uint2(l0, l1);
       }
     } else {
+      float* yrow = p.Y + (size_t)blockIdx.y * p.split_stride + (size_t)m * p.ldy;
 #pragma unroll
       for (int f = 0; f < NF; ++f) {
-        const int c = col[f] + 4 * g4;
-        f32x4 v = acc[f][mb];
-        if (p.bias) {
-          const bf16_t* bp = p.bias + c;
-#pragma unroll
-          for (int r = 0; r < 4; ++r) v[r] += __uint_as_float(((unsigned)bp[r]) << 16);
-        }
-        float4* dst = (float4*)(yrow + c);
-        float4 o = {v[0], v[1], v[2], v[3]};
-        if (p.mode == 1) {
-          const float4 old = *dst;
-          o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
-        }
-        *dst = o;
+        const f32x4 v = acc[f][mb];
+        *(float4*)(yrow + col[f] + 4 * g4) = make_float4(v[0], v[1], v[2], v[3]);
       }
     }
   }
@@ -323,18 +276,14 @@ int mfma_gemm_pick_splits(int M, int N, int K, int mode) {
   if (forced > 0) return std::min(forced, chunks);
   const int tiles = tiles_for(N, mode);
   int s = 1;
+  if (mode == 2) return 1;  // the SwiGLU epilogue needs complete sums
   // fill the chip (>= 256 workgroups), keep >= 4 chunks per split for the pipeline, and keep the
   // fp32 partial tiles (splits * M * 4 bytes per column) below a quarter of the weight bytes (K * 2)
-  while (tiles * s < 256 && (s * 2) * 4 <= chunks && (size_t)(s * 2) * mt * 16 * 4 * 4 <= (size_t)K * 2) s *= 2;
+  while (tiles * s < 256 && (s * 2) * 4 <= chunks && (size_t)(s * 2) * M * 4 * 4 <= (size_t)K * 2) s *= 2;
   return s;
 }
 
-size_t mfma_gemm_partial_bytes(int M, int N, int K, int mode, int splits) {
-  if (splits <= 1) return 0;
-  return (size_t)tiles_for(N, mode) * splits * 4 * nf_for(N, mode) * mt_for(M) * 64 * sizeof(float) * 4;
-}
-
-int mfma_gemm_counters(int N, int mode) { return tiles_for(N, mode); }
+size_t mfma_gemm_out_bytes(int M, int N, int splits) { return (size_t)std::max(splits, 1) * M * N * sizeof(float); }
 
 template <int MT, int NF, int KC>
 static void launch_one(const MfmaGemm& g, dim3 grid, hipStream_t st) {
@@ -350,9 +299,11 @@ static void launch_one(const MfmaGemm& g, dim3 grid, hipStream_t st) {
 void launch_gemm_mfma(const MfmaGemm& g, hipStream_t st) {
   const int mt = mt_for(g.M), nf = nf_for(g.N, g.mode);
   dim3 grid(tiles_for(g.N, g.mode), g.splits);
+  MfmaGemm g2 = g;
+  g2.dbg = env_int("CLOVER_GEMM_DBG");
 #define CLV_CASE(MT_, KC_)                                              \
-  if (nf == 2) launch_one<MT_, 2, KC_>(g, grid, st);                    \
-  else launch_one<MT_, 1, KC_>(g, grid, st);
+  if (nf == 2) launch_one<MT_, 2, KC_>(g2, grid, st);                   \
+  else launch_one<MT_, 1, KC_>(g2, grid, st);
   switch (mt) {
     case 1: CLV_CASE(1, 128) break;
     case 2: CLV_CASE(2, 128) break;
