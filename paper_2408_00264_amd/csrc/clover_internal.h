@@ -97,7 +97,7 @@ void launch_reduce_add_norm(float* x, int ldx, const float* P, int splits, size_
 // ---- MFMA weight-streaming GEMM (bf16 weights, split-bf16 activations in, fp32 out) -------------
 struct MfmaGemm {
   const bf16_t *Xhi, *Xlo; int ldx;   // activation planes [M, K]
-  const bf16_t* W[3];      // up to three row-segments (fused QKV); plain GEMM uses W[0]
+  const bf16_t* W[3];      // up to three fragment-major row-segments (fused QKV); plain GEMM uses W[0]
   int seg_begin[4];        // segment s covers output columns [seg_begin[s], seg_begin[s+1])
   const bf16_t* W_up;      // mode 2: second matrix (W[0] = gate)
   float* Y; int ldy;       // mode 0: split s writes Y[s*split_stride + m*ldy + n]
@@ -112,5 +112,27 @@ bool mfma_gemm_supported(int M, int N, int K, int mode);
 int mfma_gemm_pick_splits(int M, int N, int K, int mode);
 size_t mfma_gemm_out_bytes(int M, int N, int splits);
 void launch_gemm_mfma(const MfmaGemm& g, hipStream_t st);
+
+
+// ---- fragment-major weights and the K-slice-resident streaming GEMM (M <= 64) -------------------
+// [N,K] row-major bf16 -> [N/16][K/32][64 lanes][8]: lane l of tile (nb, kt) holds row nb*16 + l%16,
+// columns kt*32 + (l/16)*8 .. +7.  Both MFMA GEMMs read this layout.
+void launch_pack_weight(const void* src, void* dst, int N, int K, hipStream_t st);
+struct StreamGemm {
+  const bf16_t *Xhi, *Xlo; int ldx;   // activation planes [M, K]
+  const bf16_t* W[3];                 // fragment-major weight segments
+  int seg_begin[4];                   // segment s covers output columns [seg_begin[s], seg_begin[s+1])
+  float* Y; int ldy;                  // slice s writes Y[s*split_stride + m*ldy + n]
+  size_t split_stride;
+  int M, N, K;
+  int n_slices, groups;               // filled in by launch_gemm_stream
+};
+bool stream_gemm_supported(int M, int N, int K);
+int stream_gemm_slices(int K);
+size_t stream_gemm_out_bytes(int M, int N, int K);
+void launch_gemm_stream(StreamGemm g, hipStream_t st);
+// (hi, lo)[m, c] = split(silu(sum_s P[s][m][c]) * sum_s P[s][m][F + c])
+void launch_reduce_swiglu(const float* P, int splits, size_t split_stride, int ldp, int F, bf16_t* hi, bf16_t* lo,
+                          int ldo, int rows, hipStream_t st);
 
 }  // namespace clv

@@ -1,13 +1,15 @@
 // Weight-streaming skinny GEMM on the gfx950 matrix cores.
 //
-//   Y[M,N] = X[M,K] * W[N,K]^T     W bf16 row-major (streamed once from HBM), X fp32, fp32 accumulate
+//   Y[M,N] = X[M,K] * W[N,K]^T     W bf16 (streamed once from HBM), X as split-bf16 planes, fp32 accumulate
 //
 // M is the number of tree rows (tens to a few hundred), so the kernel is bound by reading W.
 //
 // * v_mfma_f32_16x16x32_bf16 with the WEIGHT rows as the A operand and the activation rows as the
 //   B operand.  A wavefront owns NF 16-row weight blocks and all M activation rows; each lane loads
-//   its 16-byte A fragments straight from global memory into registers (row = lane%16,
-//   k = 8*(lane/16)..+7): every weight byte is read exactly once.
+//   its 16-byte A fragments straight from global memory into registers.  The weights are stored
+//   fragment-major ([N/16][K/32][64 lanes][8]), so a load instruction reads one contiguous KB and
+//   every weight byte is read exactly once.  This tiled kernel serves M > 64; up to 64 rows the
+//   K-slice-resident kernel is used.
 // * A random-init 32-layer stack amplifies a bf16 rounding of the activations about twenty-fold by
 //   the last layer, so each activation x arrives as two bf16 planes, hi = bf16(x) and
 //   lo = bf16(x - hi), and both halves are multiplied (two MFMAs per fragment): 16 mantissa bits,
@@ -134,14 +136,14 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(MfmaGemm p) {
         if (p.mode == 2) {
           constexpr int HF = NF / 2 > 0 ? NF / 2 : 1;
           const int r0 = grp * (8 * NF) + (f % HF) * 16;
-          wrow[f] = ((f < HF) ? p.W[0] : p.W_up) + (size_t)(r0 + l16) * K + g4 * 8;
+          wrow[f] = ((f < HF) ? p.W[0] : p.W_up) + (size_t)(r0 / 16) * (K / 32) * 512 + lane * 8;
           col[f] = r0;
         } else {
           const int n = grp * (16 * NF) + f * 16;
           int s = 0;
           if (n >= p.seg_begin[1]) s = 1;
           if (n >= p.seg_begin[2]) s = 2;
-          wrow[f] = p.W[s] + (size_t)(n - p.seg_begin[s] + l16) * K + g4 * 8;
+          wrow[f] = p.W[s] + (size_t)((n - p.seg_begin[s]) / 16) * (K / 32) * 512 + lane * 8;
           col[f] = n;
         }
       }
@@ -154,8 +156,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(MfmaGemm p) {
       for (int f = 0; f < NF; ++f)
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-          w[slot][f][ks].u = (p.dbg & 8) ? *(const u32x4*)(wrow[f] + kc + ks * 32)
-                                         : __builtin_nontemporal_load((const u32x4*)(wrow[f] + kc + ks * 32));
+          w[slot][f][ks].u = __builtin_nontemporal_load((const u32x4*)(wrow[f] + (size_t)(kc / 32 + ks) * 512));
     };
     auto compute = [&](int slot, int buf) {
       if (!active) return;

@@ -1,0 +1,251 @@
+// K-slice-resident weight-streaming GEMM for few activation rows (M <= 64) on gfx950, and the
+// fragment-major weight layout both MFMA GEMMs read.
+//
+//   P[s][M,N] = X[M, slice s of K] * W[N, slice s of K]^T        (fp32 partial per K slice)
+//
+// Why this shape.  With M <= 64 the GEMM is bound by streaming W from HBM, and what has to be kept
+// small is everything else that crosses the L2 fabric.  A workgroup is therefore tied to ONE slice of
+// K (512 columns): its activation slice (hi and lo bf16 planes, 64 x 512 x 4 B = 128 KB) is copied
+// into LDS once, and from then on its eight wavefronts do nothing but stream weight fragments
+// (global -> registers, 16 KB in flight per wavefront) and multiply them against the resident slice:
+// no barrier and no activation traffic in the steady state.  Each workgroup walks a contiguous range
+// of 16-row weight blocks; the per-slice partial tiles are summed, in slice order, by whichever
+// kernel consumes the result (RoPE, residual add + RMSNorm, SwiGLU, bias add).
+//
+// Weight layout.  A 16x16x32 MFMA A-fragment takes, per lane, 8 consecutive k of row lane%16 at
+// k-offset 8*(lane/16).  Read from a row-major matrix that is 16 rows x 64 B per load instruction,
+// i.e. every 128-byte line is requested by two different instructions and crosses the L2->L1 fabric
+// twice.  The weights are therefore re-laid out once (at init, into the library's own copy) as
+// [N/16][K/32][64 lanes][8] so that one load instruction reads one contiguous KB.
+#include "clover_internal.h"
+
+#include <algorithm>
+#include <cstdlib>
+
+namespace clv {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+union Frag {
+  u32x4 u;
+  bf16x8 v;
+};
+
+// ------------------------------------------------------------------------------------------
+// row-major [N,K] -> fragment-major [N/16][K/32][64][8]
+// ------------------------------------------------------------------------------------------
+__global__ void pack_weight_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst, int N, int K) {
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // one 16-byte piece each
+  const size_t total = (size_t)N * K / 8;
+  if (idx >= total) return;
+  const int lane = (int)(idx & 63);
+  const size_t tile = idx >> 6;
+  const int KT = K / 32;
+  const size_t nb = tile / KT;
+  const int kt = (int)(tile % KT);
+  const size_t row = nb * 16 + (lane & 15);
+  const int k = kt * 32 + (lane >> 4) * 8;
+  *(u32x4*)(dst + idx * 8) = *(const u32x4*)(src + row * K + k);
+}
+void launch_pack_weight(const void* src, void* dst, int N, int K, hipStream_t st) {
+  const size_t total = (size_t)N * K / 8;
+  pack_weight_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>((const bf16_t*)src, (bf16_t*)dst, N, K);
+}
+
+// ------------------------------------------------------------------------------------------
+// the streaming kernel
+// ------------------------------------------------------------------------------------------
+constexpr int ST_WAVES = 8;
+constexpr int ST_KSL = 512;          // K columns per slice
+constexpr int ST_LDK = ST_KSL + 8;   // LDS row stride (bf16): +16 B spreads the 16 rows of a fragment read over the banks
+constexpr int ST_STAGE = 8;          // 32-column weight tiles per pipeline stage (8 KB per fragment, contiguous)
+
+template <int MT, int NF>
+__global__ __launch_bounds__(ST_WAVES * 64) void gemm_stream_kernel(StreamGemm p) {
+  constexpr int ROWS = MT * 16;
+  constexpr int PLANE = ROWS * ST_LDK;
+  extern __shared__ __attribute__((aligned(16))) bf16_t xs[];  // [hi, lo][ROWS][ST_LDK]
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int l16 = lane & 15, g4 = lane >> 4;
+  const int slice = blockIdx.x % p.n_slices, grp = blockIdx.x / p.n_slices;
+  const int k0 = slice * ST_KSL;
+  const int kt_n = min(ST_KSL, p.K - k0) / 32;  // 32-column tiles in this slice (multiple of ST_STAGE)
+  const int n_st = kt_n / ST_STAGE;
+  const int KT = p.K / 32;
+
+  // units of NF 16-row blocks; this workgroup owns units [u0, u1)
+  const int n_units = p.N / (16 * NF);
+  const int per = (n_units + p.groups - 1) / p.groups;
+  const int u0 = grp * per, u1 = min(n_units, u0 + per);
+  if (u0 >= u1) return;  // whole workgroup
+
+  // ---- activation slice -> LDS (rows >= M are zero) ----
+  {
+    const int slots = kt_n * 4;  // 16-byte pieces per row and plane
+    const int total = 2 * ROWS * slots;
+    for (int idx = tid; idx < total; idx += ST_WAVES * 64) {
+      const int plane = idx / (ROWS * slots), rem = idx % (ROWS * slots);
+      const int r = rem / slots, sl = rem % slots;
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (r < p.M) v = *(const u32x4*)((plane ? p.Xlo : p.Xhi) + (size_t)r * p.ldx + k0 + sl * 8);
+      *(u32x4*)(xs + plane * PLANE + r * ST_LDK + sl * 8) = v;
+    }
+  }
+  __syncthreads();
+
+  // ---- this wavefront's units: u0 + wave, u0 + wave + 8, ...; one item = one stage of one unit ----
+  const int my_units = (u1 - u0 - wave + ST_WAVES - 1) / ST_WAVES;
+  if (my_units <= 0) return;
+  const int n_items = my_units * n_st;
+
+  Frag w[2][NF][ST_STAGE];
+  f32x4 acc[NF][MT];
+#pragma unroll
+  for (int f = 0; f < NF; ++f)
+#pragma unroll
+    for (int mb = 0; mb < MT; ++mb) acc[f][mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  auto frag_base = [&](int unit, int f, int& col) -> const bf16_t* {
+    const int n = (unit * NF + f) * 16;
+    int s = 0;
+    if (n >= p.seg_begin[1]) s = 1;
+    if (n >= p.seg_begin[2]) s = 2;
+    col = n;
+    return p.W[s] + ((size_t)((n - p.seg_begin[s]) / 16) * KT + k0 / 32) * 512 + lane * 8;
+  };
+  auto load = [&](int buf, int item) {
+    const int unit = u0 + wave + (item / n_st) * ST_WAVES, st = item % n_st;
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+      int col;
+      const bf16_t* b = frag_base(unit, f, col) + (size_t)st * ST_STAGE * 512;
+#pragma unroll
+      for (int t = 0; t < ST_STAGE; ++t) w[buf][f][t].u = __builtin_nontemporal_load((const u32x4*)(b + t * 512));
+    }
+  };
+  auto compute = [&](int buf, int item) {
+    const int st = item % n_st;
+    const bf16_t* hi = xs + l16 * ST_LDK + g4 * 8 + st * ST_STAGE * 32;
+    const bf16_t* lo = hi + PLANE;
+#pragma unroll
+    for (int t = 0; t < ST_STAGE; ++t) {
+#pragma unroll
+      for (int mb = 0; mb < MT; ++mb) {
+        Frag bh, bl;
+        bh.u = *(const u32x4*)(hi + mb * 16 * ST_LDK + t * 32);
+        bl.u = *(const u32x4*)(lo + mb * 16 * ST_LDK + t * 32);
+#pragma unroll
+        for (int f = 0; f < NF; ++f) {
+          acc[f][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[buf][f][t].v, bl.v, acc[f][mb], 0, 0, 0);
+          acc[f][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[buf][f][t].v, bh.v, acc[f][mb], 0, 0, 0);
+        }
+      }
+    }
+    if (st == n_st - 1) {  // unit complete: write this slice's partial tile and start over
+      const int unit = u0 + wave + (item / n_st) * ST_WAVES;
+      float* ybase = p.Y + (size_t)slice * p.split_stride;
+#pragma unroll
+      for (int f = 0; f < NF; ++f) {
+        const int col = (unit * NF + f) * 16 + 4 * g4;
+#pragma unroll
+        for (int mb = 0; mb < MT; ++mb) {
+          const int m = mb * 16 + l16;
+          const f32x4 v = acc[f][mb];
+          if (m < p.M) *(float4*)(ybase + (size_t)m * p.ldy + col) = make_float4(v[0], v[1], v[2], v[3]);
+          acc[f][mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        }
+      }
+    }
+  };
+
+  load(0, 0);
+  for (int i = 0; i < n_items; i += 2) {
+    if (i + 1 < n_items) load(1, i + 1);
+    compute(0, i);
+    if (i + 1 >= n_items) break;
+    if (i + 2 < n_items) load(0, i + 2);
+    compute(1, i + 1);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------
+bool stream_gemm_supported(int M, int N, int K) {
+  return M >= 1 && M <= 64 && K % (ST_STAGE * 32) == 0 && N % 32 == 0;
+}
+int stream_gemm_slices(int K) { return (K + ST_KSL - 1) / ST_KSL; }
+size_t stream_gemm_out_bytes(int M, int N, int K) { return (size_t)stream_gemm_slices(K) * M * N * sizeof(float); }
+
+template <int MT, int NF>
+static void launch_stream_one(const StreamGemm& g, int wgs, hipStream_t st) {
+  constexpr size_t lds = (size_t)2 * MT * 16 * ST_LDK * sizeof(bf16_t);
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipFuncSetAttribute((const void*)gemm_stream_kernel<MT, NF>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    attr_done = true;
+  }
+  gemm_stream_kernel<MT, NF><<<wgs, ST_WAVES * 64, lds, st>>>(g);
+}
+
+void launch_gemm_stream(StreamGemm g, hipStream_t st) {
+  g.n_slices = stream_gemm_slices(g.K);
+  const int mt = g.M <= 16 ? 1 : g.M <= 32 ? 2 : 4;
+  // one workgroup per CU: a 64-row slice fills most of the LDS.  Pair fragments (halves the LDS
+  // reads per weight byte) when that still leaves every wavefront a unit.
+  static const int target = [] { const char* v = getenv("CLOVER_STREAM_WGS"); return v ? atoi(v) : 256; }();
+  int groups = std::max(1, target / g.n_slices);
+  int nf = 2;
+  if (g.N / 32 < groups * ST_WAVES) nf = 1;
+  const int n_units = g.N / (16 * nf);
+  groups = std::min(groups, std::max(1, (n_units + ST_WAVES - 1) / ST_WAVES));
+  g.groups = groups;
+  const int wgs = groups * g.n_slices;
+#define CLV_ST(MT_)                                       \
+  if (nf == 2) launch_stream_one<MT_, 2>(g, wgs, st);     \
+  else launch_stream_one<MT_, 1>(g, wgs, st);
+  if (mt == 1) { CLV_ST(1) } else if (mt == 2) { CLV_ST(2) } else { CLV_ST(4) }
+#undef CLV_ST
+}
+
+// ------------------------------------------------------------------------------------------
+// consumer of the fused gate/up projection: h = silu(sum_s P[s][m][c]) * (sum_s P[s][m][F + c]), as planes
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ unsigned rn_bf16(float a) {
+  unsigned u = __float_as_uint(a);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__global__ void reduce_swiglu_kernel(const float* __restrict__ P, int splits, size_t sps, int ldp, int F,
+                                     bf16_t* __restrict__ hi, bf16_t* __restrict__ lo, int ldo) {
+  const size_t row = blockIdx.y;
+  const int c = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (c >= F) return;
+  float4 g = {0.f, 0.f, 0.f, 0.f}, u = {0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < splits; ++s) {
+    const float4 a = *(const float4*)(P + s * sps + row * ldp + c);
+    const float4 b = *(const float4*)(P + s * sps + row * ldp + F + c);
+    g.x += a.x; g.y += a.y; g.z += a.z; g.w += a.w;
+    u.x += b.x; u.y += b.y; u.z += b.z; u.w += b.w;
+  }
+  const float o[4] = {g.x / (1.0f + expf(-g.x)) * u.x, g.y / (1.0f + expf(-g.y)) * u.y,
+                      g.z / (1.0f + expf(-g.z)) * u.z, g.w / (1.0f + expf(-g.w)) * u.w};
+  unsigned h[4], l[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    h[r] = rn_bf16(o[r]);
+    l[r] = rn_bf16(o[r] - __uint_as_float(h[r] << 16));
+  }
+  *(uint2*)(hi + row * ldo + c) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+  *(uint2*)(lo + row * ldo + c) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
+}
+void launch_reduce_swiglu(const float* P, int splits, size_t split_stride, int ldp, int F, bf16_t* hi, bf16_t* lo,
+                          int ldo, int rows, hipStream_t st) {
+  if (rows <= 0) return;
+  reduce_swiglu_kernel<<<dim3((F / 4 + 255) / 256, rows), 256, 0, st>>>(P, splits, split_stride, ldp, F, hi, lo, ldo);
+}
+
+}  // namespace clv
