@@ -52,7 +52,12 @@ struct clover_ctx {
   int R, max_rows, H, QKVN, NQD;
   KVLayout kv;
   size_t k_layer_elems, v_layer_elems, esz, kv_esz;
-  int kvdtype;  // element type of the KV caches (fp32: a random-init 32-layer stack amplifies bf16 cache rounding ~20x)
+  int kvdtype;  // 0: fp32 cache elements; 1: (hi, lo) bf16 planes, same bytes (a random-init 32-layer stack amplifies
+                // plain bf16 cache rounding ~20x, so 16 mantissa bits are kept either way)
+  size_t kv_layer_stride;  // cache elements (of the kvdtype's element type) per layer
+  bool attn_fast;
+  float *o_part, *ml_part;
+  int attn_max_splits;
   // device regions
   int *d_seq_len, *d_aug_len, *d_err;
   int *d_depth, *d_parent, *d_rank, *d_first_child, *d_n_child, *d_lvl_nodes, *d_par_row;
@@ -196,11 +201,11 @@ void carve(clover_ctx* x, char* base, size_t* total) {
   const int B = c.max_batch, R = c.max_nodes, rows = B * R, H = c.hidden, d = c.head_dim;
   const size_t esz = c.dtype == CLOVER_DTYPE_F32 ? 4 : 2;
   x->R = R; x->max_rows = rows; x->H = H; x->esz = esz;
-  x->kvdtype = CLOVER_DTYPE_F32; x->kv_esz = 4;
+  x->kv_esz = 4;  // bytes per cached value in both formats
   x->NQD = c.n_q_heads * d;
   x->QKVN = (c.n_q_heads + 2 * c.n_kv_heads) * d;
-  x->kv = KVLayout{B, c.max_seq, c.n_kv_heads, d};
   x->k_layer_elems = (size_t)B * c.max_seq * c.n_kv_heads * d;
+  x->kv = KVLayout{B, c.max_seq, c.n_kv_heads, d, x->k_layer_elems};
   x->v_layer_elems = x->k_layer_elems;
   x->d_seq_len = cv.take<int>(B);
   x->d_aug_len = cv.take<int>(B);
@@ -271,6 +276,12 @@ void carve(clover_ctx* x, char* base, size_t* total) {
   x->packed_bytes = packed_bytes;
   x->packed = cv.take<char>(packed_bytes ? packed_bytes : 256);
   x->fast = fast;
+  x->kvdtype = fast ? 1 : 0;
+  x->kv_layer_stride = fast ? 2 * x->k_layer_elems : x->k_layer_elems;
+  x->attn_fast = fast && attn_mfma_supported(d, c.n_q_heads, c.n_kv_heads, c.max_seq);
+  x->attn_max_splits = 16;
+  x->o_part = cv.take<float>(x->attn_fast ? (size_t)x->attn_max_splits * rows * x->NQD : 64);
+  x->ml_part = cv.take<float>(x->attn_fast ? (size_t)x->attn_max_splits * rows * c.n_q_heads * 2 : 64);
   x->partial_bytes = pbytes;
   x->partial = (float*)cv.take<char>(pbytes);
   x->pl_y = cv.take<float>((size_t)rows * 2 * H);
@@ -383,7 +394,8 @@ void gemm_generic(clover_ctx* x, int cls, const float* X, int ldx, const void* W
 // MFMA path: on entry the planes of a_norm hold RMSNorm(xres) * attn_norm of this layer; on exit they
 // hold RMSNorm(xres) * next_gain (skipped when next_gain is null).  Generic path: norms are computed here.
 void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMap rm, int M, char* kc_layer,
-               char* vc_layer, const int* base_len, const unsigned long long* anc, const void* next_gain) {
+               char* vc_layer, const int* base_len, const unsigned long long* anc, const void* next_gain,
+               int key_bound) {
   const clover_config& c = x->cfg;
   const int H = x->H, d = c.head_dim, F = c.ffn;
   const int sn[3] = {c.n_q_heads * d, c.n_kv_heads * d, c.n_kv_heads * d};
@@ -398,8 +410,20 @@ void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMa
       launch_rope_kv_write(x->partial, x->QKVN, sq, (size_t)M * x->QKVN, x->cos_t, x->sin_t, x->q_rot, x->NQD, kc_layer,
                            vc_layer, x->kvdtype, x->kv, base_len, c.n_q_heads, rm, x->d_err, x->st); }
     { Scope s(x, KC_ATTN);
-      launch_attn_generic(x->q_rot, x->NQD, kc_layer, vc_layer, x->kvdtype, x->kv, base_len, anc, c.n_q_heads, nullptr,
-                          x->NQD, O.hi, O.lo, rm, x->st); }
+      if (x->attn_fast) {
+        AttnParams ap;
+        memset(&ap, 0, sizeof(ap));
+        ap.q = x->q_rot; ap.ldq = x->NQD;
+        ap.k_hi = (const bf16_t*)kc_layer; ap.k_plane = x->k_layer_elems;
+        ap.v_hi = (const bf16_t*)vc_layer; ap.v_plane = x->v_layer_elems;
+        ap.max_seq = c.max_seq; ap.n_kv = c.n_kv_heads; ap.n_q = c.n_q_heads;
+        ap.base_len = base_len; ap.anc = anc; ap.rm = rm;
+        ap.o_part = x->o_part; ap.ml_part = x->ml_part; ap.rows_total = x->max_rows; ap.max_splits = x->attn_max_splits;
+        launch_attn_mfma(ap, key_bound, O.hi, O.lo, x->NQD, x->st);
+      } else {
+        launch_attn_generic(x->q_rot, x->NQD, kc_layer, vc_layer, x->kvdtype, x->kv, base_len, anc, c.n_q_heads, nullptr,
+                            x->NQD, O.hi, O.lo, rm, x->st);
+      } }
     const int sw = gemm_fast1(x, KC_GEMM_WO, O, lw.wo, M, H, x->NQD);
     { Scope s(x, KC_RMSNORM);
       launch_reduce_add_norm(xres, H, x->partial, sw, (size_t)M * H, H, lw.ffn_norm, c.dtype, c.rms_eps, A.hi, A.lo, H, M,
@@ -548,7 +572,7 @@ int accept_common(clover_ctx* x, int batch, const int* tree_tokens, const float*
     launch_accept_walk(x->topk_ids, tree_tokens, x->d_first_child, x->d_n_child, t.n, batch, R, n_forced, forced_next,
                        m, acc_idx, new_tokens, next_tok, x->st); }
   { Scope s(x, KC_COMPACT);
-    launch_compact_kv(x->kc, x->vc, x->kvdtype, x->kv, c.n_layers, x->k_layer_elems, x->v_layer_elems, x->d_seq_len, m,
+    launch_compact_kv(x->kc, x->vc, x->kvdtype, x->kv, c.n_layers, x->kv_layer_stride, x->kv_layer_stride, x->d_seq_len, m,
                       acc_idx, batch, R, x->st);
     launch_gather_hidden(hidden, acc_idx, m, batch, R, x->H, hid_acc, x->st);
     launch_add_len(x->d_seq_len, m, batch, x->st); }
@@ -624,6 +648,12 @@ int clover_init(const clover_config* cfg, const clover_weights* w, const clover_
   launch_fill_i32(x->d_aug_len, 0, cfg->max_batch, x->st);
   launch_fill_i32(x->d_err, 0, 1, x->st);
   if (x->fast) {
+    // the MFMA attention multiplies masked probabilities (exact zeros) with whatever the cache rows of a
+    // tile hold, so the caches must never contain non-finite garbage
+    hipMemsetAsync(x->kc, 0, x->k_layer_elems * x->kv_esz * cfg->n_layers, x->st);
+    hipMemsetAsync(x->vc, 0, x->v_layer_elems * x->kv_esz * cfg->n_layers, x->st);
+    hipMemsetAsync(x->aug_kc, 0, x->k_layer_elems * x->kv_esz * cfg->aug_layers, x->st);
+    hipMemsetAsync(x->aug_vc, 0, x->v_layer_elems * x->kv_esz * cfg->aug_layers, x->st);
     // private fragment-major copies of every linear weight; the originals are only read here
     // (and, for the LM head, by the draft's embedding gathers)
     char* cur = x->packed;
@@ -697,6 +727,8 @@ int draft_tree(clover_ctx* x, int32_t batch, const float* hid_acc, const int32_t
     if (x->aug_ub[b] + n > c.max_seq) return fail(x, CLOVER_E_CAPACITY, "augmenting-block cache could exceed max_seq");
   const RowMap rm{B, R, n, m};
   const int M = (B - 1) * R + n;
+  int aug_bound = 0;
+  for (int b = 0; b < B; ++b) aug_bound = std::max(aug_bound, x->aug_ub[b] + n);
   // embeddings of the follow-up tokens come from the LM-head rows
   { Scope s(x, KC_EMBED); launch_embed(x->w.lm_head, c.dtype, next_tok, c.vocab, x->d_e, H, H, rm, x->st); }
   run_ad(x, x->w.ad1, hid_acc, x->d_e, M, x->xd);
@@ -705,7 +737,7 @@ int draft_tree(clover_ctx* x, int32_t batch, const float* hid_acc, const int32_t
   for (int l = 0; l < c.aug_layers; ++l)
     run_layer(x, x->aug[l], x->xd, rm, M, x->aug_kc + (size_t)l * x->k_layer_elems * x->kv_esz,
               x->aug_vc + (size_t)l * x->v_layer_elems * x->kv_esz, x->d_aug_len, x->d_anc_chain,
-              l + 1 < c.aug_layers ? x->aug[l + 1].attn_norm : nullptr);
+              l + 1 < c.aug_layers ? x->aug[l + 1].attn_norm : nullptr, aug_bound);
   { Scope s(x, KC_DRAFT_MISC);
     launch_draft_root(x->xd, next_tok, m, B, R, H, x->d_rootx, x->d_state, tree_tokens, x->st);
     launch_add_len(x->d_aug_len, m, B, x->st); }
@@ -748,13 +780,15 @@ int verify_tree(clover_ctx* x, int32_t batch, const int32_t* tree_tokens, float*
     if (x->len_ub[b] + t.n > c.max_seq) return fail(x, CLOVER_E_CAPACITY, "sequence could exceed max_seq (call clover_seq_len to refresh the bound)");
   const RowMap rm{B, R, t.n, nullptr};
   const int M = (B - 1) * R + t.n;
+  int key_bound = 0;
+  for (int b = 0; b < B; ++b) key_bound = std::max(key_bound, x->len_ub[b] + t.n);
   { Scope s(x, KC_EMBED); launch_embed(x->w.embed, c.dtype, tree_tokens, c.vocab, hidden, H, H, rm, x->st); }
   { Scope s(x, KC_ROPE_KV); launch_rope_table(x->d_seq_len, x->d_depth, c.rope_base, c.head_dim, x->cos_t, x->sin_t, rm, x->st); }
   if (x->fast) norm_planes(x, hidden, x->layers[0].attn_norm, M);
   for (int l = 0; l < c.n_layers; ++l)
     run_layer(x, x->layers[l], hidden, rm, M, x->kc + (size_t)l * x->k_layer_elems * x->kv_esz,
               x->vc + (size_t)l * x->v_layer_elems * x->kv_esz, x->d_seq_len, x->d_anc,
-              l + 1 < c.n_layers ? x->layers[l + 1].attn_norm : x->w.final_norm);
+              l + 1 < c.n_layers ? x->layers[l + 1].attn_norm : x->w.final_norm, key_bound);
   if (x->fast) {
     Planes A = planes_of(x, x->a_norm, 2 * H);
     A.ld = H;

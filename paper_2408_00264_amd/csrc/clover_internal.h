@@ -24,7 +24,10 @@ struct RowMap {
 
 struct KVLayout {
   // K: [max_batch][max_seq][n_kv][d]; V (transposed): [max_batch][n_kv][d][max_seq]; one such pair per layer.
+  // kvdtype 0: fp32 elements.  kvdtype 1: each cache is two bf16 planes (hi, then lo `plane` elements
+  // later) with hi + lo == value to 16 mantissa bits -- the operand format of the MFMA attention.
   int max_batch, max_seq, n_kv, d;
+  size_t plane;
 };
 
 // ---- generic (fp32 ALU) kernels; wdtype: 0 fp32, 1 bf16 ---------------------------------------
@@ -113,6 +116,24 @@ int mfma_gemm_pick_splits(int M, int N, int K, int mode);
 size_t mfma_gemm_out_bytes(int M, int N, int splits);
 void launch_gemm_mfma(const MfmaGemm& g, hipStream_t st);
 
+
+// ---- MFMA tree attention (head_dim 128, caches as bf16 planes) ---------------------------------
+struct AttnParams {
+  const float* q; int ldq;               // [rows, n_q*128] fp32, RoPE applied
+  const bf16_t* k_hi; size_t k_plane;    // K planes [B][max_seq][n_kv][128]; lo = hi + k_plane
+  const bf16_t* v_hi; size_t v_plane;    // V^T planes [B][n_kv][128][max_seq]
+  int max_seq, n_kv, n_q;
+  const int* base_len;                   // dev [B]
+  const unsigned long long* anc;         // dev [n][2]
+  RowMap rm;
+  float* o_part;                         // [max_splits][rows_total][n_q][128]
+  float* ml_part;                        // [max_splits][rows_total][n_q][2]
+  int rows_total, max_splits;
+  int tiles_per_split, n_splits;         // filled in by launch_attn_mfma
+};
+bool attn_mfma_supported(int head_dim, int n_q, int n_kv, int max_seq);
+// max_total_keys: host-side upper bound of base_len[b] + rm.n over the batch (sizes the key splits)
+void launch_attn_mfma(AttnParams p, int max_total_keys, bf16_t* out_hi, bf16_t* out_lo, int ldo, hipStream_t st);
 
 // ---- fragment-major weights and the K-slice-resident streaming GEMM (M <= 64) -------------------
 // [N,K] row-major bf16 -> [N/16][K/32][64 lanes][8]: lane l of tile (nb, kt) holds row nb*16 + l%16,

@@ -1,0 +1,306 @@
+// Tree-masked decode attention on the gfx950 matrix cores (head_dim 128).
+//
+// For one sequence and one KV head, the G query heads that share it and the N tree nodes form
+// G*N query rows; they attend to the L cached keys (all visible) and to the N tree keys, of which
+// node u sees exactly those on its own root path (one bit per tree node in anc[u]).
+//
+// Work split: a workgroup = (sequence, KV head, group of 32 nodes, range of 32-key tiles); its G
+// wavefronts are the G query heads.  K and V^T tiles are staged once per workgroup in LDS and
+// shared by the heads; every split writes an un-normalised partial (O, running max, running sum)
+// and a small kernel merges the splits with the usual log-sum-exp weights.
+//
+// MFMA mapping (v_mfma_f32_16x16x32_bf16, D[i][j] += sum_k A[i][k] B[j][k]):
+//   scores   S^T[key][row] : A = K tile  (16 keys x 32 d),  B = Q (16 rows x 32 d)
+//   output   O^T[d][row]   : A = V^T tile (16 d x 32 keys), B = P (16 rows x 32 keys)
+// A lane owns one query row in both products (j = lane%16), so the soft-max statistics and the
+// rescaling of O never leave the lane, and the eight probabilities a lane computes for the keys
+// 8*(lane/16)..+7 of a tile are exactly the B fragment of the second product.
+//
+// Precision: a random-init stack amplifies bf16 rounding ~20x over 32 layers, so Q, K, V and P are
+// all carried as hi + lo bf16 pairs and each product takes three MFMAs (hi*hi, hi*lo, lo*hi).  The
+// caches already hold K and V^T as (hi, lo) planes.
+#include "clover_internal.h"
+
+#include <algorithm>
+
+namespace clv {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+union Frag {
+  u32x4 u;
+  bf16x8 v;
+};
+
+__device__ __forceinline__ unsigned a_rn(float a) {
+  unsigned u = __float_as_uint(a);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ void a_split2(float a, float b, unsigned& hi, unsigned& lo) {
+  const unsigned ha = a_rn(a), hb = a_rn(b);
+  hi = ha | (hb << 16);
+  lo = a_rn(a - __uint_as_float(ha << 16)) | (a_rn(b - __uint_as_float(hb << 16)) << 16);
+}
+
+constexpr int AT_D = 128;         // head dim
+constexpr int AT_TK = 32;         // keys per tile
+constexpr int AT_MB = 2;          // 16-row blocks of nodes per wavefront (32 nodes per workgroup)
+constexpr int AT_KLD = AT_D + 8;  // LDS row strides (bf16) chosen so fragment reads are conflict-free
+constexpr int AT_VLD = AT_TK + 8;
+constexpr int AT_KPLANE = AT_TK * AT_KLD;
+constexpr int AT_VPLANE = AT_D * AT_VLD;
+constexpr int AT_BUF = 2 * AT_KPLANE + 2 * AT_VPLANE;  // one stage: K hi, K lo, V^T hi, V^T lo
+
+template <int G>
+__global__ __launch_bounds__(64 * G) void attn_mfma_kernel(AttnParams p) {
+  extern __shared__ __attribute__((aligned(16))) bf16_t sm[];  // [2 stages][AT_BUF]
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int l16 = lane & 15, g4 = lane >> 4;
+  const int split = blockIdx.x, ng = blockIdx.y / p.n_kv, kvh = blockIdx.y % p.n_kv, b = blockIdx.z;
+  const RowMap& rm = p.rm;
+  const int nv = rm.n_valid ? min(rm.n_valid[b], rm.n) : rm.n;
+  const int L = p.base_len[b];
+  if (ng * 32 >= nv || L + nv > p.max_seq) return;  // whole workgroup
+  const int total = L + nv;
+  const int n_tiles = (total + AT_TK - 1) / AT_TK;
+  const int t0 = split * p.tiles_per_split, t1 = min(n_tiles, t0 + p.tiles_per_split);
+  const int head = kvh * G + wave;
+
+  // ---- Q fragments (scaled by 1/sqrt(d)), ancestor masks ----
+  Frag qh[AT_MB][4], ql[AT_MB][4];
+  unsigned long long a0[AT_MB], a1[AT_MB];
+  const float scale = 0.08838834764831845f;  // 1/sqrt(128)
+#pragma unroll
+  for (int mb = 0; mb < AT_MB; ++mb) {
+    const int node = ng * 32 + mb * 16 + l16;
+    const bool ok = node < nv;
+    a0[mb] = ok ? p.anc[2 * node] : 0ull;
+    a1[mb] = ok ? p.anc[2 * node + 1] : 0ull;
+    const float* qp = p.q + ((size_t)b * rm.R + (ok ? node : 0)) * p.ldq + head * AT_D + g4 * 8;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f), v1 = v0;
+      if (ok) { v0 = *(const float4*)(qp + ks * 32); v1 = *(const float4*)(qp + ks * 32 + 4); }
+      unsigned h, l;
+      a_split2(v0.x * scale, v0.y * scale, h, l); qh[mb][ks].u.x = h; ql[mb][ks].u.x = l;
+      a_split2(v0.z * scale, v0.w * scale, h, l); qh[mb][ks].u.y = h; ql[mb][ks].u.y = l;
+      a_split2(v1.x * scale, v1.y * scale, h, l); qh[mb][ks].u.z = h; ql[mb][ks].u.z = l;
+      a_split2(v1.z * scale, v1.w * scale, h, l); qh[mb][ks].u.w = h; ql[mb][ks].u.w = l;
+    }
+  }
+
+  f32x4 O[8][AT_MB];
+#pragma unroll
+  for (int db = 0; db < 8; ++db)
+#pragma unroll
+    for (int mb = 0; mb < AT_MB; ++mb) O[db][mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  float m_run[AT_MB], l_run[AT_MB];
+#pragma unroll
+  for (int mb = 0; mb < AT_MB; ++mb) { m_run[mb] = -INFINITY; l_run[mb] = 0.f; }
+
+  // ---- staging: 16-byte pieces; K rows are stored in the order the score MFMA consumes them ----
+  constexpr int NT = 64 * G;
+  constexpr int KSLOTS = 2 * AT_TK * 16, VSLOTS = 2 * AT_D * 4;  // both 1024
+  constexpr int KIT = KSLOTS / NT, VIT = VSLOTS / NT;
+  u32x4 kr[KIT], vr[VIT];
+  const bf16_t* kbase = p.k_hi + (size_t)b * p.max_seq * p.n_kv * AT_D + (size_t)kvh * AT_D;
+  const bf16_t* vbase = p.v_hi + ((size_t)b * p.n_kv + kvh) * AT_D * p.max_seq;
+  auto load_tile = [&](int t) {
+#pragma unroll
+    for (int it = 0; it < KIT; ++it) {
+      const int idx = it * NT + tid, plane = idx >> 9, rem = idx & 511, key = rem >> 4, sl = rem & 15;
+      const int j = min(t * AT_TK + key, p.max_seq - 1);
+      kr[it] = *(const u32x4*)(kbase + plane * p.k_plane + (size_t)j * p.n_kv * AT_D + sl * 8);
+    }
+#pragma unroll
+    for (int it = 0; it < VIT; ++it) {
+      const int idx = it * NT + tid, plane = idx >> 9, rem = idx & 511, dr = rem >> 2, sl = rem & 3;
+      const int j = min(t * AT_TK + sl * 8, p.max_seq - 8);
+      vr[it] = *(const u32x4*)(vbase + plane * p.v_plane + (size_t)dr * p.max_seq + j);
+    }
+  };
+  auto store_tile = [&](int buf) {
+    bf16_t* base = sm + buf * AT_BUF;
+#pragma unroll
+    for (int it = 0; it < KIT; ++it) {
+      const int idx = it * NT + tid, plane = idx >> 9, rem = idx & 511, key = rem >> 4, sl = rem & 15;
+      // key k of the tile is row ((k/4)%2)*16 + (k/8)*4 + k%4: sub-tile tt holds keys 8g + 4tt + r at row 4g + r
+      const int row = ((key >> 2) & 1) * 16 + (key >> 3) * 4 + (key & 3);
+      *(u32x4*)(base + plane * AT_KPLANE + row * AT_KLD + sl * 8) = kr[it];
+    }
+#pragma unroll
+    for (int it = 0; it < VIT; ++it) {
+      const int idx = it * NT + tid, plane = idx >> 9, rem = idx & 511, dr = rem >> 2, sl = rem & 3;
+      *(u32x4*)(base + 2 * AT_KPLANE + plane * AT_VPLANE + dr * AT_VLD + sl * 8) = vr[it];
+    }
+  };
+  auto compute = [&](int buf, int t) {
+    const bf16_t* kb = sm + buf * AT_BUF + l16 * AT_KLD + g4 * 8;
+    const bf16_t* vb = sm + buf * AT_BUF + 2 * AT_KPLANE + l16 * AT_VLD + g4 * 8;
+    f32x4 s[2][AT_MB];
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+      for (int mb = 0; mb < AT_MB; ++mb) s[tt][mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        Frag kh, kl;
+        kh.u = *(const u32x4*)(kb + tt * 16 * AT_KLD + ks * 32);
+        kl.u = *(const u32x4*)(kb + AT_KPLANE + tt * 16 * AT_KLD + ks * 32);
+#pragma unroll
+        for (int mb = 0; mb < AT_MB; ++mb) {
+          s[tt][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kl.v, qh[mb][ks].v, s[tt][mb], 0, 0, 0);
+          s[tt][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kh.v, ql[mb][ks].v, s[tt][mb], 0, 0, 0);
+          s[tt][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kh.v, qh[mb][ks].v, s[tt][mb], 0, 0, 0);
+        }
+      }
+    Frag ph[AT_MB], pl[AT_MB];
+#pragma unroll
+    for (int mb = 0; mb < AT_MB; ++mb) {
+      float sv[8];
+      float tmax = -INFINITY;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {  // e-th key of this lane: slot t*32 + 8*g4 + e
+        const int j = t * AT_TK + 8 * g4 + e;
+        bool vis = j < L;
+        if (!vis && j < total) {
+          const int wn = j - L;
+          vis = ((wn < 64 ? (a0[mb] >> wn) : (a1[mb] >> (wn - 64))) & 1ull) != 0ull;
+        }
+        if (a0[mb] == 0ull && a1[mb] == 0ull) vis = false;  // padding row
+        sv[e] = vis ? s[e >> 2][mb][e & 3] : -INFINITY;
+        tmax = fmaxf(tmax, sv[e]);
+      }
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+      const float m_new = fmaxf(m_run[mb], tmax);
+      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+      const float corr = __expf(m_run[mb] - m_safe);  // exp(-inf) = 0 on the first visible tile
+      float pe[8], psum = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { pe[e] = __expf(sv[e] - m_safe); psum += pe[e]; }
+      l_run[mb] = l_run[mb] * corr + psum;
+      m_run[mb] = m_new;
+#pragma unroll
+      for (int db = 0; db < 8; ++db) O[db][mb] *= corr;
+      unsigned h, l;
+      a_split2(pe[0], pe[1], h, l); ph[mb].u.x = h; pl[mb].u.x = l;
+      a_split2(pe[2], pe[3], h, l); ph[mb].u.y = h; pl[mb].u.y = l;
+      a_split2(pe[4], pe[5], h, l); ph[mb].u.z = h; pl[mb].u.z = l;
+      a_split2(pe[6], pe[7], h, l); ph[mb].u.w = h; pl[mb].u.w = l;
+    }
+#pragma unroll
+    for (int db = 0; db < 8; ++db) {
+      Frag vh, vl;
+      vh.u = *(const u32x4*)(vb + db * 16 * AT_VLD);
+      vl.u = *(const u32x4*)(vb + AT_VPLANE + db * 16 * AT_VLD);
+#pragma unroll
+      for (int mb = 0; mb < AT_MB; ++mb) {
+        O[db][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vl.v, ph[mb].v, O[db][mb], 0, 0, 0);
+        O[db][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vh.v, pl[mb].v, O[db][mb], 0, 0, 0);
+        O[db][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vh.v, ph[mb].v, O[db][mb], 0, 0, 0);
+      }
+    }
+  };
+
+  if (t0 < t1) {  // uniform over the workgroup
+    load_tile(t0);
+    store_tile(0);
+    __syncthreads();
+    for (int t = t0; t < t1; ++t) {
+      const int buf = (t - t0) & 1;
+      if (t + 1 < t1) load_tile(t + 1);
+      compute(buf, t);
+      if (t + 1 < t1) store_tile(buf ^ 1);
+      __syncthreads();
+    }
+  }
+
+  // ---- partial result of this split ----
+#pragma unroll
+  for (int mb = 0; mb < AT_MB; ++mb) {
+    const int node = ng * 32 + mb * 16 + l16;
+    float lsum = l_run[mb];
+    lsum += __shfl_xor(lsum, 16, 64);
+    lsum += __shfl_xor(lsum, 32, 64);
+    if (node >= nv) continue;
+    const size_t prow = ((size_t)split * p.rows_total + (size_t)b * rm.R + node) * p.n_q + head;
+#pragma unroll
+    for (int db = 0; db < 8; ++db) {
+      const f32x4 v = O[db][mb];
+      *(float4*)(p.o_part + prow * AT_D + db * 16 + 4 * g4) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+    if (g4 == 0) {
+      p.ml_part[prow * 2] = m_run[mb];
+      p.ml_part[prow * 2 + 1] = lsum;
+    }
+  }
+}
+
+// merge the splits of one (row, head): out = sum_s e^{m_s - M} O_s / sum_s e^{m_s - M} l_s, as planes
+__global__ void attn_merge_kernel(const float* __restrict__ o_part, const float* __restrict__ ml_part, int n_splits,
+                                  int rows_total, int n_q, bf16_t* __restrict__ out_hi, bf16_t* __restrict__ out_lo,
+                                  int ldo, RowMap rm) {
+  const int i = blockIdx.x, b = blockIdx.y, head = blockIdx.z, dd = threadIdx.x;
+  const int nv = rm.n_valid ? min(rm.n_valid[b], rm.n) : rm.n;
+  if (i >= nv) return;
+  const size_t row = (size_t)b * rm.R + i;
+  float M = -INFINITY;
+  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ml_part[(((size_t)s * rows_total + row) * n_q + head) * 2]);
+  float num = 0.f, den = 0.f;
+  for (int s = 0; s < n_splits; ++s) {
+    const size_t pr = ((size_t)s * rows_total + row) * n_q + head;
+    const float ms = ml_part[pr * 2];
+    if (ms == -INFINITY) continue;
+    const float wgt = __expf(ms - M);
+    den += wgt * ml_part[pr * 2 + 1];
+    num += wgt * o_part[pr * AT_D + dd];
+  }
+  const float o = num / den;
+  const unsigned h = a_rn(o);
+  out_hi[row * ldo + head * AT_D + dd] = (bf16_t)h;
+  out_lo[row * ldo + head * AT_D + dd] = (bf16_t)a_rn(o - __uint_as_float(h << 16));
+}
+
+bool attn_mfma_supported(int head_dim, int n_q, int n_kv, int max_seq) {
+  const int g = n_q / n_kv;
+  return head_dim == AT_D && (g == 1 || g == 2 || g == 4 || g == 8) && max_seq % 8 == 0 && max_seq >= 32;
+}
+
+template <int G>
+static void launch_attn_one(const AttnParams& p, dim3 grid, hipStream_t st) {
+  constexpr size_t lds = (size_t)2 * AT_BUF * sizeof(bf16_t);
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipFuncSetAttribute((const void*)attn_mfma_kernel<G>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    attr_done = true;
+  }
+  attn_mfma_kernel<G><<<grid, 64 * G, lds, st>>>(p);
+}
+
+void launch_attn_mfma(AttnParams p, int max_total_keys, bf16_t* out_hi, bf16_t* out_lo, int ldo, hipStream_t st) {
+  const int g = p.n_q / p.n_kv;
+  const int node_groups = (p.rm.n + 31) / 32;
+  const int n_tiles = (max_total_keys + AT_TK - 1) / AT_TK;
+  // enough workgroups to fill the chip twice, at least two tiles per split, within the partial buffer
+  int splits = (512 + p.rm.B * p.n_kv * node_groups - 1) / (p.rm.B * p.n_kv * node_groups);
+  splits = std::max(1, std::min(std::min(splits, p.max_splits), (n_tiles + 1) / 2));
+  p.tiles_per_split = (n_tiles + splits - 1) / splits;
+  p.n_splits = (n_tiles + p.tiles_per_split - 1) / p.tiles_per_split;
+  dim3 grid(p.n_splits, node_groups * p.n_kv, p.rm.B);
+  switch (g) {
+    case 1: launch_attn_one<1>(p, grid, st); break;
+    case 2: launch_attn_one<2>(p, grid, st); break;
+    case 4: launch_attn_one<4>(p, grid, st); break;
+    default: launch_attn_one<8>(p, grid, st); break;
+  }
+  attn_merge_kernel<<<dim3(p.rm.n, p.rm.B, p.n_q), AT_D, 0, st>>>(p.o_part, p.ml_part, p.n_splits, p.rows_total, p.n_q,
+                                                                 out_hi, out_lo, ldo, p.rm);
+}
+
+}  // namespace clv

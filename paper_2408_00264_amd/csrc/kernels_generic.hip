@@ -18,6 +18,22 @@ __device__ __forceinline__ float ldf(const float* p, size_t i) { return p[i]; }
 __device__ __forceinline__ float ldf(const bf16_t* p, size_t i) { return bf16_to_f32(p[i]); }
 __device__ __forceinline__ void stf(float* p, size_t i, float v) { p[i] = v; }
 __device__ __forceinline__ void stf(bf16_t* p, size_t i, float v) { p[i] = f32_to_bf16(v); }
+// KV-cache elements: fp32, or a (hi, lo) pair of bf16 planes `plane` elements apart
+__device__ __forceinline__ float ldkv(const float* p, size_t i, size_t) { return p[i]; }
+__device__ __forceinline__ float ldkv(const bf16_t* p, size_t i, size_t plane) {
+  return bf16_to_f32(p[i]) + bf16_to_f32(p[i + plane]);
+}
+__device__ __forceinline__ void stkv(float* p, size_t i, size_t, float v) { p[i] = v; }
+__device__ __forceinline__ void stkv(bf16_t* p, size_t i, size_t plane, float v) {
+  const bf16_t h = f32_to_bf16(v);
+  p[i] = h;
+  p[i + plane] = f32_to_bf16(v - bf16_to_f32(h));
+}
+__device__ __forceinline__ void mvkv(float* p, size_t dst, size_t src, size_t) { p[dst] = p[src]; }
+__device__ __forceinline__ void mvkv(bf16_t* p, size_t dst, size_t src, size_t plane) {
+  p[dst] = p[src];
+  p[dst + plane] = p[src + plane];
+}
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -158,8 +174,8 @@ __global__ void rope_kv_write_kernel(const float* __restrict__ qkv, int ldqkv, i
         q_out[row * ldq + hh * d + ii + half] = o2;
       } else {
         const size_t base = (((size_t)b * kv.max_seq + slot) * n_kv + (hh - n_q)) * d;
-        stf(kc, base + ii, o1);
-        stf(kc, base + ii + half, o2);
+        stkv(kc, base + ii, kv.plane, o1);
+        stkv(kc, base + ii + half, kv.plane, o2);
       }
     }
   } else {
@@ -170,7 +186,7 @@ __global__ void rope_kv_write_kernel(const float* __restrict__ qkv, int ldqkv, i
       if (node >= nv || e >= n_kv * d) continue;
       float v = qkv[((size_t)b * rm.R + node) * ldqkv + voff + e];
       for (int sp = 1; sp < nsp; ++sp) v += qkv[sp * sps + ((size_t)b * rm.R + node) * ldqkv + voff + e];
-      stf(vc, ((size_t)b * n_kv * d + e) * kv.max_seq + L + node, v);
+      stkv(vc, ((size_t)b * n_kv * d + e) * kv.max_seq + L + node, kv.plane, v);
     }
   }
 }
@@ -228,7 +244,7 @@ __global__ void attn_generic_kernel(const float* __restrict__ q, int ldq, const 
     if (vis) {
       const KT* kr = kc + (((size_t)b * kv.max_seq + s) * n_kv + g) * d;
       float acc = 0.f;
-      for (int c = 0; c < d; ++c) acc += qs[c] * ldf(kr, c);
+      for (int c = 0; c < d; ++c) acc += qs[c] * ldkv(kr, c, kv.plane);
       sc = acc;
     }
     const float mnew = fmaxf(mrun, wave_max(sc));
@@ -246,8 +262,8 @@ __global__ void attn_generic_kernel(const float* __restrict__ q, int ldq, const 
     for (int j = 0; j < jmax; ++j) {
       const float pj = ps[j];
       if (pj != 0.f) {
-        o0 += pj * ldf(vrow0, t * 64 + j);
-        if (d > 64) o1 += pj * ldf(vrow1, t * 64 + j);
+        o0 += pj * ldkv(vrow0, t * 64 + j, kv.plane);
+        if (d > 64) o1 += pj * ldkv(vrow1, t * 64 + j, kv.plane);
       }
     }
   }
@@ -632,8 +648,8 @@ __global__ void compact_kv_kernel(KT* __restrict__ kc, KT* __restrict__ vc, KVLa
   for (int i = 0; i < mb; ++i) {
     const int a = acc_idx[(size_t)b * R + i];
     if (a == i || a < 0 || L + a >= kv.max_seq) continue;
-    kbase[(size_t)(L + i) * width] = kbase[(size_t)(L + a) * width];
-    vbase[L + i] = vbase[L + a];
+    mvkv(kbase, (size_t)(L + i) * width, (size_t)(L + a) * width, kv.plane);
+    mvkv(vbase, L + i, L + a, kv.plane);
   }
 }
 void launch_compact_kv(void* k_cache, void* v_cache, int kvdtype, KVLayout kv, int n_layers, size_t k_layer_elems,
@@ -670,8 +686,8 @@ __global__ void read_kv_kernel(const KT* __restrict__ kc, const KT* __restrict__
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (size_t)n_slots * width) return;
   const int s = (int)(idx / width), col = (int)(idx % width);
-  k_out[idx] = ldf(kc, ((size_t)b * kv.max_seq + slot0 + s) * width + col);
-  v_out[idx] = ldf(vc, ((size_t)b * width + col) * kv.max_seq + slot0 + s);
+  k_out[idx] = ldkv(kc, ((size_t)b * kv.max_seq + slot0 + s) * width + col, kv.plane);
+  v_out[idx] = ldkv(vc, ((size_t)b * width + col) * kv.max_seq + slot0 + s, kv.plane);
 }
 void launch_read_kv(const void* k_cache, const void* v_cache, int kvdtype, KVLayout kv, int b, int slot0, int n_slots,
                     float* k_out, float* v_out, hipStream_t st) {
