@@ -137,15 +137,28 @@ void launch_rope_table(const int* base_len, const int* depth, float rope_base, i
 }
 
 // ------------------------------------------------------------------------------------------
-// RoPE on q and k (half-split pairing), K rows and transposed V columns into the cache.
-// blocks [0, n): one row each (q out, K row); blocks [n, n + vblocks): 32 (head,dim) lines of V^T
+// RoPE on q and k (half-split pairing), K rows and transposed V columns into the cache; sums the
+// split-K partials of the QKV projection on the way (fixed order, eight loads in flight).
+// blocks [0, n*hc): 256 (head, pair) items of one row; then blocks of 8 (head,dim) lines of V^T
 // ------------------------------------------------------------------------------------------
+__device__ __forceinline__ float sum_partials(const float* __restrict__ p, int nsp, size_t sps) {
+  float v = 0.f;
+  for (int s0 = 0; s0 < nsp; s0 += 8) {
+    float q[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) q[j] = (s0 + j < nsp) ? p[(size_t)(s0 + j) * sps] : 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v += q[j];
+  }
+  return v;
+}
+
 template <typename KT>
 __global__ void rope_kv_write_kernel(const float* __restrict__ qkv, int ldqkv, int nsp, size_t sps,
                                      const float* __restrict__ cos_t,
                                      const float* __restrict__ sin_t, float* __restrict__ q_out, int ldq,
                                      KT* __restrict__ kc, KT* __restrict__ vc, KVLayout kv,
-                                     const int* __restrict__ base_len, int n_q, RowMap rm, int* err_flag) {
+                                     const int* __restrict__ base_len, int n_q, RowMap rm, int* err_flag, int hc) {
   const int b = blockIdx.y;
   const int nv = rows_valid(rm, b);
   const int L = base_len[b];
@@ -154,38 +167,34 @@ __global__ void rope_kv_write_kernel(const float* __restrict__ qkv, int ldqkv, i
     if (threadIdx.x == 0 && blockIdx.x == 0) atomicOr(err_flag, 1);
     return;
   }
-  if ((int)blockIdx.x < rm.n) {
-    const int i = blockIdx.x;
+  if ((int)blockIdx.x < rm.n * hc) {
+    const int i = blockIdx.x / hc;
     if (i >= nv) return;
+    const int idx = (blockIdx.x % hc) * 256 + threadIdx.x;
+    if (idx >= (n_q + n_kv) * half) return;
     const size_t row = (size_t)b * rm.R + i;
     const int slot = L + i;
     const float* src = qkv + row * ldqkv;
-    for (int idx = threadIdx.x; idx < (n_q + n_kv) * half; idx += blockDim.x) {
-      const int hh = idx / half, ii = idx - hh * half;
-      const float c = cos_t[row * half + ii], s = sin_t[row * half + ii];
-      float x1 = src[hh * d + ii], x2 = src[hh * d + ii + half];
-      for (int sp = 1; sp < nsp; ++sp) {   // split-K partials of the QKV projection, fixed order
-        x1 += src[sp * sps + hh * d + ii];
-        x2 += src[sp * sps + hh * d + ii + half];
-      }
-      const float o1 = x1 * c - x2 * s, o2 = x2 * c + x1 * s;
-      if (hh < n_q) {
-        q_out[row * ldq + hh * d + ii] = o1;
-        q_out[row * ldq + hh * d + ii + half] = o2;
-      } else {
-        const size_t base = (((size_t)b * kv.max_seq + slot) * n_kv + (hh - n_q)) * d;
-        stkv(kc, base + ii, kv.plane, o1);
-        stkv(kc, base + ii + half, kv.plane, o2);
-      }
+    const int hh = idx / half, ii = idx - hh * half;
+    const float c = cos_t[row * half + ii], s = sin_t[row * half + ii];
+    const float x1 = sum_partials(src + hh * d + ii, nsp, sps);
+    const float x2 = sum_partials(src + hh * d + ii + half, nsp, sps);
+    const float o1 = x1 * c - x2 * s, o2 = x2 * c + x1 * s;
+    if (hh < n_q) {
+      q_out[row * ldq + hh * d + ii] = o1;
+      q_out[row * ldq + hh * d + ii + half] = o2;
+    } else {
+      const size_t base = (((size_t)b * kv.max_seq + slot) * n_kv + (hh - n_q)) * d;
+      stkv(kc, base + ii, kv.plane, o1);
+      stkv(kc, base + ii + half, kv.plane, o2);
     }
   } else {
-    const int vb = blockIdx.x - rm.n;
+    const int vb = blockIdx.x - rm.n * hc;
     const int voff = (n_q + n_kv) * d;
-    for (int idx = threadIdx.x; idx < 32 * rm.n; idx += blockDim.x) {
-      const int node = idx % rm.n, e = vb * 32 + idx / rm.n;
+    for (int idx = threadIdx.x; idx < 8 * rm.n; idx += blockDim.x) {
+      const int node = idx % rm.n, e = vb * 8 + idx / rm.n;
       if (node >= nv || e >= n_kv * d) continue;
-      float v = qkv[((size_t)b * rm.R + node) * ldqkv + voff + e];
-      for (int sp = 1; sp < nsp; ++sp) v += qkv[sp * sps + ((size_t)b * rm.R + node) * ldqkv + voff + e];
+      const float v = sum_partials(qkv + ((size_t)b * rm.R + node) * ldqkv + voff + e, nsp, sps);
       stkv(vc, ((size_t)b * n_kv * d + e) * kv.max_seq + L + node, kv.plane, v);
     }
   }
@@ -195,14 +204,15 @@ void launch_rope_kv_write(const float* qkv, int ldqkv, int qkv_splits, size_t qk
                           const float* sin_t, float* q_out, int ldq,
                           void* k_cache, void* v_cache, int kvdtype, KVLayout kv, const int* base_len, int n_q,
                           RowMap rm, int* err_flag, hipStream_t st) {
-  const int vblocks = (kv.n_kv * kv.d + 31) / 32;
-  dim3 grid(rm.n + vblocks, rm.B);
+  const int vblocks = (kv.n_kv * kv.d + 7) / 8;
+  const int hc = ((n_q + kv.n_kv) * (kv.d / 2) + 255) / 256;
+  dim3 grid(rm.n * hc + vblocks, rm.B);
   if (kvdtype == 0)
     rope_kv_write_kernel<float><<<grid, 256, 0, st>>>(qkv, ldqkv, qkv_splits, qkv_split_stride, cos_t, sin_t, q_out, ldq, (float*)k_cache,
-                                                      (float*)v_cache, kv, base_len, n_q, rm, err_flag);
+                                                      (float*)v_cache, kv, base_len, n_q, rm, err_flag, hc);
   else
     rope_kv_write_kernel<bf16_t><<<grid, 256, 0, st>>>(qkv, ldqkv, qkv_splits, qkv_split_stride, cos_t, sin_t, q_out, ldq, (bf16_t*)k_cache,
-                                                       (bf16_t*)v_cache, kv, base_len, n_q, rm, err_flag);
+                                                       (bf16_t*)v_cache, kv, base_len, n_q, rm, err_flag, hc);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -742,30 +752,41 @@ void launch_reduce(const float* P, int splits, size_t split_stride, int ldp, con
     reduce_kernel<bf16_t><<<grid, 256, 0, st>>>(P, splits, split_stride, ldp, (const bf16_t*)bias, Y, ldy, N, mode);
 }
 
-// one block per row: residual add of the split-K partials, then RMSNorm written as planes
+// one 1024-thread block per row: residual add of the split-K partials (eight loads in flight per
+// thread, summed in split order), then RMSNorm written as planes
 template <typename WT>
-__global__ __launch_bounds__(256) void reduce_add_norm_kernel(float* __restrict__ x, int ldx,
-                                                              const float* __restrict__ P, int splits, size_t sps,
-                                                              int ldp, const WT* __restrict__ gain, float eps,
-                                                              bf16_t* __restrict__ hi, bf16_t* __restrict__ lo,
-                                                              int ldo, int H) {
-  __shared__ float red[4];
+__global__ __launch_bounds__(1024) void reduce_add_norm_kernel(float* __restrict__ x, int ldx,
+                                                               const float* __restrict__ P, int splits, size_t sps,
+                                                               int ldp, const WT* __restrict__ gain, float eps,
+                                                               bf16_t* __restrict__ hi, bf16_t* __restrict__ lo,
+                                                               int ldo, int H) {
+  __shared__ float red[16];
   const size_t row = blockIdx.x;
   float* xr = x + row * ldx;
+  const float* pr = P + row * ldp;
   float ss = 0.f;
-  for (int c = threadIdx.x * 4; c < H; c += 1024) {
+  for (int c = threadIdx.x * 4; c < H; c += 4096) {
     float4 v = *(const float4*)(xr + c);
-    for (int s = 0; s < splits; ++s) {
-      const float4 q = *(const float4*)(P + s * sps + row * ldp + c);
-      v.x += q.x; v.y += q.y; v.z += q.z; v.w += q.w;
+    for (int s0 = 0; s0 < splits; s0 += 8) {
+      float4 q[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        q[j] = (s0 + j < splits) ? *(const float4*)(pr + (size_t)(s0 + j) * sps + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { v.x += q[j].x; v.y += q[j].y; v.z += q[j].z; v.w += q[j].w; }
     }
     if (splits > 0) *(float4*)(xr + c) = v;
     ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
   }
   if (!gain) return;
-  ss = block_sum_256(ss, red);
-  const float scale = 1.0f / sqrtf(ss / (float)H + eps);
-  for (int c = threadIdx.x * 4; c < H; c += 1024) {
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  float tot = 0.f;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) tot += red[w];
+  const float scale = 1.0f / sqrtf(tot / (float)H + eps);
+  for (int c = threadIdx.x * 4; c < H; c += 4096) {
     const float4 v = *(const float4*)(xr + c);   // written by this same thread above
     const float o[4] = {v.x * scale * ldf(gain, c), v.y * scale * ldf(gain, c + 1), v.z * scale * ldf(gain, c + 2),
                         v.w * scale * ldf(gain, c + 3)};
@@ -784,10 +805,10 @@ void launch_reduce_add_norm(float* x, int ldx, const float* P, int splits, size_
                             hipStream_t st) {
   if (rows <= 0) return;
   if (wdtype == 0)
-    reduce_add_norm_kernel<float><<<rows, 256, 0, st>>>(x, ldx, P, splits, split_stride, ldp, (const float*)gain, eps,
+    reduce_add_norm_kernel<float><<<rows, 1024, 0, st>>>(x, ldx, P, splits, split_stride, ldp, (const float*)gain, eps,
                                                         hi, lo, ldo, H);
   else
-    reduce_add_norm_kernel<bf16_t><<<rows, 256, 0, st>>>(x, ldx, P, splits, split_stride, ldp, (const bf16_t*)gain,
+    reduce_add_norm_kernel<bf16_t><<<rows, 1024, 0, st>>>(x, ldx, P, splits, split_stride, ldp, (const bf16_t*)gain,
                                                          eps, hi, lo, ldo, H);
 }
 

@@ -82,24 +82,9 @@ __global__ __launch_bounds__(ST_WAVES * 64) void gemm_stream_kernel(StreamGemm p
   const int u0 = grp * per, u1 = min(n_units, u0 + per);
   if (u0 >= u1) return;  // whole workgroup
 
-  // ---- activation slice -> LDS (rows >= M are zero) ----
-  {
-    const int slots = kt_n * 4;  // 16-byte pieces per row and plane
-    const int total = 2 * ROWS * slots;
-    for (int idx = tid; idx < total; idx += ST_WAVES * 64) {
-      const int plane = idx / (ROWS * slots), rem = idx % (ROWS * slots);
-      const int r = rem / slots, sl = rem % slots;
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (r < p.M) v = *(const u32x4*)((plane ? p.Xlo : p.Xhi) + (size_t)r * p.ldx + k0 + sl * 8);
-      *(u32x4*)(xs + plane * PLANE + r * ST_LDK + sl * 8) = v;
-    }
-  }
-  __syncthreads();
-
   // ---- this wavefront's units: u0 + wave, u0 + wave + 8, ...; one item = one stage of one unit ----
   const int my_units = (u1 - u0 - wave + ST_WAVES - 1) / ST_WAVES;
-  if (my_units <= 0) return;
-  const int n_items = my_units * n_st;
+  const int n_items = max(my_units, 0) * n_st;
 
   Frag w[2][NF][ST_STAGE];
   f32x4 acc[NF][MT];
@@ -126,6 +111,33 @@ __global__ __launch_bounds__(ST_WAVES * 64) void gemm_stream_kernel(StreamGemm p
       for (int t = 0; t < ST_STAGE; ++t) w[buf][f][t].u = __builtin_nontemporal_load((const u32x4*)(b + t * 512));
     }
   };
+  if (n_items > 0) load(0, 0);  // the HBM stream starts before the activation slice is staged
+
+  // ---- activation slice -> LDS (rows >= M are zero); all loads are issued before the first store ----
+  {
+    const int slots = kt_n * 4;  // 16-byte pieces per row and plane
+    const int total = 2 * ROWS * slots;
+    constexpr int XIT = (2 * ROWS * (ST_KSL / 8) + ST_WAVES * 64 - 1) / (ST_WAVES * 64);
+    u32x4 v[XIT];
+#pragma unroll
+    for (int it = 0; it < XIT; ++it) {
+      const int idx = it * (ST_WAVES * 64) + tid;
+      const int plane = idx / (ROWS * slots), rem = idx % (ROWS * slots);
+      const int r = rem / slots, sl = rem % slots;
+      v[it] = (u32x4){0u, 0u, 0u, 0u};
+      if (idx < total && r < p.M) v[it] = *(const u32x4*)((plane ? p.Xlo : p.Xhi) + (size_t)r * p.ldx + k0 + sl * 8);
+    }
+#pragma unroll
+    for (int it = 0; it < XIT; ++it) {
+      const int idx = it * (ST_WAVES * 64) + tid;
+      const int plane = idx / (ROWS * slots), rem = idx % (ROWS * slots);
+      const int r = rem / slots, sl = rem % slots;
+      if (idx < total) *(u32x4*)(xs + plane * PLANE + r * ST_LDK + sl * 8) = v[it];
+    }
+  }
+  __syncthreads();
+  if (n_items == 0) return;
+
   auto compute = [&](int buf, int item) {
     const int st = item % n_st;
     const bf16_t* hi = xs + l16 * ST_LDK + g4 * 8 + st * ST_STAGE * 32;
@@ -161,7 +173,6 @@ __global__ __launch_bounds__(ST_WAVES * 64) void gemm_stream_kernel(StreamGemm p
     }
   };
 
-  load(0, 0);
   for (int i = 0; i < n_items; i += 2) {
     if (i + 1 < n_items) load(1, i + 1);
     compute(0, i);
