@@ -204,7 +204,7 @@ static void launch_stream_one(const StreamGemm& g, int wgs, hipStream_t st) {
 
 void launch_gemm_stream(StreamGemm g, hipStream_t st) {
   g.n_slices = stream_gemm_slices(g.K);
-  const int mt = g.M <= 16 ? 1 : g.M <= 32 ? 2 : 4;
+  const int mt = g.M <= 16 ? 1 : 4;  // 17..32 rows run as 64 (zero rows cost MFMA time only, the kernel is HBM-bound)
   // one workgroup per CU: a 64-row slice fills most of the LDS.  Pair fragments (halves the LDS
   // reads per weight byte) when that still leaves every wavefront a unit.
   static const int target = [] { const char* v = getenv("CLOVER_STREAM_WGS"); return v ? atoi(v) : 256; }();
@@ -218,7 +218,7 @@ void launch_gemm_stream(StreamGemm g, hipStream_t st) {
 #define CLV_ST(MT_)                                       \
   if (nf == 2) launch_stream_one<MT_, 2>(g, wgs, st);     \
   else launch_stream_one<MT_, 1>(g, wgs, st);
-  if (mt == 1) { CLV_ST(1) } else if (mt == 2) { CLV_ST(2) } else { CLV_ST(4) }
+  if (mt == 1) { CLV_ST(1) } else { CLV_ST(4) }
 #undef CLV_ST
 }
 
