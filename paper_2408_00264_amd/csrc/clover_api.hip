@@ -4,6 +4,7 @@
 #include "clover_internal.h"
 
 #include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstring>
 #include <string>
@@ -407,13 +408,16 @@ void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMa
     Planes Hf = planes_of(x, x->h_ffn, F);
     const int sq = gemm_fast(x, KC_GEMM_QKV, A, 3, ws, sn, M, x->QKVN, H, nullptr, 0);
     { Scope s(x, KC_ROPE_KV);
+      Planes Q = planes_of(x, x->q_rot, x->NQD);
       launch_rope_kv_write(x->partial, x->QKVN, sq, (size_t)M * x->QKVN, x->cos_t, x->sin_t, x->q_rot, x->NQD, kc_layer,
-                           vc_layer, x->kvdtype, x->kv, base_len, c.n_q_heads, rm, x->d_err, x->st); }
+                           vc_layer, x->kvdtype, x->kv, base_len, c.n_q_heads, rm, x->d_err,
+                           x->attn_fast ? Q.hi : nullptr, Q.lo, 1.0f / sqrtf((float)d), x->st); }
     { Scope s(x, KC_ATTN);
       if (x->attn_fast) {
         AttnParams ap;
         memset(&ap, 0, sizeof(ap));
-        ap.q = x->q_rot; ap.ldq = x->NQD;
+        Planes Q = planes_of(x, x->q_rot, x->NQD);
+        ap.q_hi = Q.hi; ap.q_lo = Q.lo; ap.ldq = x->NQD;
         ap.k_hi = (const bf16_t*)kc_layer; ap.k_plane = x->k_layer_elems;
         ap.v_hi = (const bf16_t*)vc_layer; ap.v_plane = x->v_layer_elems;
         ap.max_seq = c.max_seq; ap.n_kv = c.n_kv_heads; ap.n_q = c.n_q_heads;
@@ -462,7 +466,7 @@ void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMa
     } }
   { Scope s(x, KC_ROPE_KV);
     launch_rope_kv_write(x->qkv, x->QKVN, 1, 0, x->cos_t, x->sin_t, x->q_rot, x->NQD, kc_layer, vc_layer, x->kvdtype,
-                         x->kv, base_len, c.n_q_heads, rm, x->d_err, x->st); }
+                         x->kv, base_len, c.n_q_heads, rm, x->d_err, nullptr, nullptr, 0.f, x->st); }
   { Scope s(x, KC_ATTN);
     launch_attn_generic(x->q_rot, x->NQD, kc_layer, vc_layer, x->kvdtype, x->kv, base_len, anc, c.n_q_heads, x->attn_out,
                         x->NQD, nullptr, nullptr, rm, x->st); }

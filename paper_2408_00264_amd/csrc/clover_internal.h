@@ -39,7 +39,8 @@ void launch_rope_table(const int* base_len, const int* depth /*null: row index*/
                        float* cos_t, float* sin_t, RowMap rm, hipStream_t st);
 void launch_rope_kv_write(const float* qkv, int ldqkv, int qkv_splits, size_t qkv_split_stride, const float* cos_t, const float* sin_t, float* q_out, int ldq,
                           void* k_cache, void* v_cache, int kvdtype, KVLayout kv, const int* base_len, int n_q,
-                          RowMap rm, int* err_flag, hipStream_t st);
+                          RowMap rm, int* err_flag, bf16_t* q_hi /*null: fp32 q_out*/, bf16_t* q_lo, float q_scale,
+                          hipStream_t st);
 void launch_attn_generic(const float* q, int ldq, const void* k_cache, const void* v_cache, int kvdtype, KVLayout kv,
                          const int* base_len, const unsigned long long* anc /*[n][2]*/, int n_q, float* out, int ldo,
                          bf16_t* out_hi, bf16_t* out_lo /*planes instead of fp32 when non-null*/, RowMap rm,
@@ -119,7 +120,7 @@ void launch_gemm_mfma(const MfmaGemm& g, hipStream_t st);
 
 // ---- MFMA tree attention (head_dim 128, caches as bf16 planes) ---------------------------------
 struct AttnParams {
-  const float* q; int ldq;               // [rows, n_q*128] fp32, RoPE applied
+  const bf16_t *q_hi, *q_lo; int ldq;    // [rows, n_q*128] planes: RoPE applied, scaled by 1/sqrt(128)
   const bf16_t* k_hi; size_t k_plane;    // K planes [B][max_seq][n_kv][128]; lo = hi + k_plane
   const bf16_t* v_hi; size_t v_plane;    // V^T planes [B][n_kv][128][max_seq]
   int max_seq, n_kv, n_q;

@@ -69,26 +69,24 @@ __global__ __launch_bounds__(64 * G) void attn_mfma_kernel(AttnParams p) {
   const int t0 = split * p.tiles_per_split, t1 = min(n_tiles, t0 + p.tiles_per_split);
   const int head = kvh * G + wave;
 
-  // ---- Q fragments (scaled by 1/sqrt(d)), ancestor masks ----
+  // ---- Q fragments (already scaled and split by the RoPE kernel), ancestor masks ----
   Frag qh[AT_MB][4], ql[AT_MB][4];
   unsigned long long a0[AT_MB], a1[AT_MB];
-  const float scale = 0.08838834764831845f;  // 1/sqrt(128)
 #pragma unroll
   for (int mb = 0; mb < AT_MB; ++mb) {
     const int node = ng * 32 + mb * 16 + l16;
     const bool ok = node < nv;
     a0[mb] = ok ? p.anc[2 * node] : 0ull;
     a1[mb] = ok ? p.anc[2 * node + 1] : 0ull;
-    const float* qp = p.q + ((size_t)b * rm.R + (ok ? node : 0)) * p.ldq + head * AT_D + g4 * 8;
+    const size_t qo = ((size_t)b * rm.R + (ok ? node : 0)) * p.ldq + head * AT_D + g4 * 8;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f), v1 = v0;
-      if (ok) { v0 = *(const float4*)(qp + ks * 32); v1 = *(const float4*)(qp + ks * 32 + 4); }
-      unsigned h, l;
-      a_split2(v0.x * scale, v0.y * scale, h, l); qh[mb][ks].u.x = h; ql[mb][ks].u.x = l;
-      a_split2(v0.z * scale, v0.w * scale, h, l); qh[mb][ks].u.y = h; ql[mb][ks].u.y = l;
-      a_split2(v1.x * scale, v1.y * scale, h, l); qh[mb][ks].u.z = h; ql[mb][ks].u.z = l;
-      a_split2(v1.z * scale, v1.w * scale, h, l); qh[mb][ks].u.w = h; ql[mb][ks].u.w = l;
+      qh[mb][ks].u = (u32x4){0u, 0u, 0u, 0u};
+      ql[mb][ks].u = (u32x4){0u, 0u, 0u, 0u};
+      if (ok) {
+        qh[mb][ks].u = *(const u32x4*)(p.q_hi + qo + ks * 32);
+        ql[mb][ks].u = *(const u32x4*)(p.q_lo + qo + ks * 32);
+      }
     }
   }
 

@@ -158,7 +158,8 @@ __global__ void rope_kv_write_kernel(const float* __restrict__ qkv, int ldqkv, i
                                      const float* __restrict__ cos_t,
                                      const float* __restrict__ sin_t, float* __restrict__ q_out, int ldq,
                                      KT* __restrict__ kc, KT* __restrict__ vc, KVLayout kv,
-                                     const int* __restrict__ base_len, int n_q, RowMap rm, int* err_flag, int hc) {
+                                     const int* __restrict__ base_len, int n_q, RowMap rm, int* err_flag, int hc,
+                                     bf16_t* __restrict__ q_hi, bf16_t* __restrict__ q_lo, float q_scale) {
   const int b = blockIdx.y;
   const int nv = rows_valid(rm, b);
   const int L = base_len[b];
@@ -181,8 +182,17 @@ __global__ void rope_kv_write_kernel(const float* __restrict__ qkv, int ldqkv, i
     const float x2 = sum_partials(src + hh * d + ii + half, nsp, sps);
     const float o1 = x1 * c - x2 * s, o2 = x2 * c + x1 * s;
     if (hh < n_q) {
-      q_out[row * ldq + hh * d + ii] = o1;
-      q_out[row * ldq + hh * d + ii + half] = o2;
+      if (q_hi) {  // operand format of the MFMA attention: pre-scaled (hi, lo) bf16 planes
+        const float s1 = o1 * q_scale, s2 = o2 * q_scale;
+        const bf16_t h1 = f32_to_bf16(s1), h2 = f32_to_bf16(s2);
+        q_hi[row * ldq + hh * d + ii] = h1;
+        q_hi[row * ldq + hh * d + ii + half] = h2;
+        q_lo[row * ldq + hh * d + ii] = f32_to_bf16(s1 - bf16_to_f32(h1));
+        q_lo[row * ldq + hh * d + ii + half] = f32_to_bf16(s2 - bf16_to_f32(h2));
+      } else {
+        q_out[row * ldq + hh * d + ii] = o1;
+        q_out[row * ldq + hh * d + ii + half] = o2;
+      }
     } else {
       const size_t base = (((size_t)b * kv.max_seq + slot) * n_kv + (hh - n_q)) * d;
       stkv(kc, base + ii, kv.plane, o1);
@@ -203,16 +213,16 @@ __global__ void rope_kv_write_kernel(const float* __restrict__ qkv, int ldqkv, i
 void launch_rope_kv_write(const float* qkv, int ldqkv, int qkv_splits, size_t qkv_split_stride, const float* cos_t,
                           const float* sin_t, float* q_out, int ldq,
                           void* k_cache, void* v_cache, int kvdtype, KVLayout kv, const int* base_len, int n_q,
-                          RowMap rm, int* err_flag, hipStream_t st) {
+                          RowMap rm, int* err_flag, bf16_t* q_hi, bf16_t* q_lo, float q_scale, hipStream_t st) {
   const int vblocks = (kv.n_kv * kv.d + 7) / 8;
   const int hc = ((n_q + kv.n_kv) * (kv.d / 2) + 255) / 256;
   dim3 grid(rm.n * hc + vblocks, rm.B);
   if (kvdtype == 0)
     rope_kv_write_kernel<float><<<grid, 256, 0, st>>>(qkv, ldqkv, qkv_splits, qkv_split_stride, cos_t, sin_t, q_out, ldq, (float*)k_cache,
-                                                      (float*)v_cache, kv, base_len, n_q, rm, err_flag, hc);
+                                                      (float*)v_cache, kv, base_len, n_q, rm, err_flag, hc, q_hi, q_lo, q_scale);
   else
     rope_kv_write_kernel<bf16_t><<<grid, 256, 0, st>>>(qkv, ldqkv, qkv_splits, qkv_split_stride, cos_t, sin_t, q_out, ldq, (bf16_t*)k_cache,
-                                                       (bf16_t*)v_cache, kv, base_len, n_q, rm, err_flag, hc);
+                                                       (bf16_t*)v_cache, kv, base_len, n_q, rm, err_flag, hc, q_hi, q_lo, q_scale);
 }
 
 // ------------------------------------------------------------------------------------------
