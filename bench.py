@@ -50,7 +50,20 @@ def draft_bytes(shape, n_levels):
     return 2 * w
 
 
-def cpu_baseline(shape, parent, rank, L, sample_layers, store):
+def measured_traffic(config):
+    """HBM bytes per launch of the dominant kernel from the committed counter summary (FETCH_SIZE and
+    WRITE_SIZE passes scaled by a copy of known size); None when no summary covers the workload."""
+    path = os.path.join(ROOT, "profiles", f"traffic_gemm_gate_up_config{config}.txt")
+    try:
+        for line in open(path):
+            if line.strip().startswith("traffic_bytes_per_launch:"):
+                return int(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(shape, parent, rank, L, sample_layers, store, min_seconds):
     """The oracle, as it stands, timed on this host on a bounded sample of the same workload:
     `sample_layers` decoder layers of the verify pass (scaled to all layers), the LM head, the
     acceptance and one full draft_tree, for one sequence with L cached tokens."""
@@ -75,25 +88,33 @@ def cpu_baseline(shape, parent, rank, L, sample_layers, store):
     tokens = rng.integers(0, shape.vocab, N)
     # touch every weight once so conversion to fp32 is outside the timing
     O.verify_tree(W, cfg, seq, tokens[:1], [-1])
-    t0 = time.perf_counter()
-    x = W("embed")[tokens].astype(dt)
     depth = O.tree_depths(parent)
     vis = O.ancestor_matrix(parent)
-    for li in range(sample_layers):
-        x = O.decoder_layer(W, f"layers.{li}.", cfg, x, seq.kv, li, L, L + depth, L + np.arange(N), vis)
-    t1 = time.perf_counter()
-    logits = O.rmsnorm(x, W("final_norm"), cfg.rms_eps) @ W("lm_head").T
-    acc = O.accept_and_compact(cfg, seq, tokens, logits, x, parent)
-    t2 = time.perf_counter()
-    O.draft_tree(W, cfg, seq, acc["hid_acc"], acc["next_tok"], parent, rank)      # warm the draft weights
-    seq.aug_L = L
-    t3 = time.perf_counter()
-    O.draft_tree(W, cfg, seq, acc["hid_acc"], acc["next_tok"], parent, rank)
-    t4 = time.perf_counter()
-    step_s = (t1 - t0) * shape.n_layers / sample_layers + (t2 - t1) + (t4 - t3)
+    t_layers = t_head = t_draft = 0.0
+    reps = 0
+    t_begin = time.perf_counter()
+    while reps < 2 or time.perf_counter() - t_begin < min_seconds:
+        t0 = time.perf_counter()
+        x = W("embed")[tokens].astype(dt)
+        for li in range(sample_layers):
+            x = O.decoder_layer(W, f"layers.{li}.", cfg, x, seq.kv, li, L, L + depth, L + np.arange(N), vis)
+        t1 = time.perf_counter()
+        logits = O.rmsnorm(x, W("final_norm"), cfg.rms_eps) @ W("lm_head").T
+        seq.L = L
+        acc = O.accept_and_compact(cfg, seq, tokens, logits, x, parent)
+        t2 = time.perf_counter()
+        seq.L = seq.aug_L = L
+        O.draft_tree(W, cfg, seq, acc["hid_acc"], acc["next_tok"], parent, rank)
+        t3 = time.perf_counter()
+        if reps:                      # the first repetition warms the draft weights and is not counted
+            t_layers += t1 - t0; t_head += t2 - t1; t_draft += t3 - t2
+        reps += 1
+    n = reps - 1
+    step_s = t_layers / n * shape.n_layers / sample_layers + t_head / n + t_draft / n
     return {"value": N / step_s, "unit": "tree-tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"1 sequence, L={L}, {N}-node tree: {sample_layers} of {shape.n_layers} verify layers timed "
-                      f"({t1 - t0:.2f}s, scaled), LM head + accept ({t2 - t1:.2f}s), full draft_tree ({t4 - t3:.2f}s); "
+            "sample": f"1 sequence, L={L}, {N}-node tree, {n} timed repetitions ({t_layers + t_head + t_draft:.1f}s of "
+                      f"CPU work): {sample_layers} of {shape.n_layers} verify layers ({t_layers / n:.2f}s each time, scaled "
+                      f"to {shape.n_layers}), LM head + accept ({t_head / n:.2f}s), full draft_tree ({t_draft / n:.2f}s); "
                       f"fp32 NumPy", "est_step_ms": step_s * 1e3}
 
 
@@ -107,7 +128,11 @@ def main():
     ap.add_argument("--prompt", type=int, default=0, help="debug: override the prompt length")
     ap.add_argument("--flags", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-layers", type=int, default=2)
+    ap.add_argument("--calib", action="store_true",
+                    help="also launch an elementwise kernel that reads 1 GiB and writes 1 GiB (three times), the "
+                         "known-size reference for scaling hardware byte counters")
+    ap.add_argument("--cpu-sample-layers", type=int, default=8)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time spent on the oracle baseline")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -158,6 +183,13 @@ def main():
             else:
                 g.verify_tree(B); g.accept_and_compact(B); g.draft_tree(B)
 
+    if args.calib:
+        ca = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        cb = torch.empty_like(ca)
+        for _ in range(3):
+            torch.add(ca, 1.0, out=cb)
+        torch.cuda.synchronize()
+        del ca, cb
     run_steps(Wm)
     torch.cuda.synchronize()
     g.seq_len()
@@ -208,13 +240,15 @@ def main():
                        "tree_tokens_per_s": B * N / (float(np.median(ver)) * 1e-3)},
         "draft_hbm": {"algorithmic_bytes": dbytes, "GBps": dbytes / (float(np.median(dra)) * 1e-3) / 1e9},
         "roofline": {"kernel": "gemm_gate_up (fused SwiGLU projection)", "bound": "hbm", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": measured_traffic(args.config) if not (args.layers or args.prompt) else None,
                      "bytes_per_launch": gu_bytes, "avg_launch_ms": gu_avg_ms},
         "kernels": kernels,
     }
     if not args.no_cpu_baseline:
         t0 = time.time()
-        out["cpu_baseline"] = cpu_baseline(shape, parent, rank, int(lens0[0]), min(args.cpu_sample_layers, shape.n_layers), store)
+        out["cpu_baseline"] = cpu_baseline(shape, parent, rank, int(lens0[0]), min(args.cpu_sample_layers, shape.n_layers), store,
+                                           args.cpu_seconds)
         log(f"[bench] cpu baseline in {time.time() - t0:.1f}s")
     print(json.dumps(out), flush=True)
 
