@@ -113,26 +113,24 @@ __global__ __launch_bounds__(ST_WAVES * 64) void gemm_stream_kernel(StreamGemm p
   };
   if (n_items > 0) load(0, 0);  // the HBM stream starts before the activation slice is staged
 
-  // ---- activation slice -> LDS (rows >= M are zero); all loads are issued before the first store ----
+  // ---- activation slice -> LDS (rows >= M are zero); all loads are issued before the first store.
+  // One wavefront instruction moves one row of one plane (64 lanes x 16 B = 512 columns), so the
+  // index arithmetic is shifts only.
   {
-    const int slots = kt_n * 4;  // 16-byte pieces per row and plane
-    const int total = 2 * ROWS * slots;
-    constexpr int XIT = (2 * ROWS * (ST_KSL / 8) + ST_WAVES * 64 - 1) / (ST_WAVES * 64);
+    const int slots = kt_n * 4;  // 16-byte pieces per row and plane (<= 64)
+    constexpr int XIT = 2 * ROWS / ST_WAVES;
     u32x4 v[XIT];
 #pragma unroll
     for (int it = 0; it < XIT; ++it) {
-      const int idx = it * (ST_WAVES * 64) + tid;
-      const int plane = idx / (ROWS * slots), rem = idx % (ROWS * slots);
-      const int r = rem / slots, sl = rem % slots;
+      const int rp = it * ST_WAVES + wave, plane = rp / ROWS, r = rp % ROWS;
       v[it] = (u32x4){0u, 0u, 0u, 0u};
-      if (idx < total && r < p.M) v[it] = *(const u32x4*)((plane ? p.Xlo : p.Xhi) + (size_t)r * p.ldx + k0 + sl * 8);
+      if (lane < slots && r < p.M && !(p.dbg & 1))
+        v[it] = *(const u32x4*)((plane ? p.Xlo : p.Xhi) + (size_t)r * p.ldx + k0 + lane * 8);
     }
 #pragma unroll
     for (int it = 0; it < XIT; ++it) {
-      const int idx = it * (ST_WAVES * 64) + tid;
-      const int plane = idx / (ROWS * slots), rem = idx % (ROWS * slots);
-      const int r = rem / slots, sl = rem % slots;
-      if (idx < total) *(u32x4*)(xs + plane * PLANE + r * ST_LDK + sl * 8) = v[it];
+      const int rp = it * ST_WAVES + wave, plane = rp / ROWS, r = rp % ROWS;
+      if (lane < slots) *(u32x4*)(xs + plane * PLANE + r * ST_LDK + lane * 8) = v[it];
     }
   }
   __syncthreads();
@@ -166,7 +164,7 @@ __global__ __launch_bounds__(ST_WAVES * 64) void gemm_stream_kernel(StreamGemm p
         for (int mb = 0; mb < MT; ++mb) {
           const int m = mb * 16 + l16;
           const f32x4 v = acc[f][mb];
-          if (m < p.M) *(float4*)(ybase + (size_t)m * p.ldy + col) = make_float4(v[0], v[1], v[2], v[3]);
+          if (m < p.M && !(p.dbg & 2)) *(float4*)(ybase + (size_t)m * p.ldy + col) = make_float4(v[0], v[1], v[2], v[3]);
           acc[f][mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
         }
       }
@@ -204,6 +202,8 @@ static void launch_stream_one(const StreamGemm& g, int wgs, hipStream_t st) {
 
 void launch_gemm_stream(StreamGemm g, hipStream_t st) {
   g.n_slices = stream_gemm_slices(g.K);
+  static const int dbg = [] { const char* v = getenv("CLOVER_STREAM_DBG"); return v ? atoi(v) : 0; }();
+  g.dbg = dbg;
   const int mt = g.M <= 16 ? 1 : 4;  // 17..32 rows run as 64 (zero rows cost MFMA time only, the kernel is HBM-bound)
   // one workgroup per CU: a 64-row slice fills most of the LDS.  Pair fragments (halves the LDS
   // reads per weight byte) when that still leaves every wavefront a unit.
