@@ -341,6 +341,7 @@ int gemm_fast(clover_ctx* x, int cls, Planes X, int nseg, const void* const* W, 
     g.seg_begin[3] = 0x7fffffff;
     g.Y = x->partial; g.ldy = N; g.split_stride = (size_t)M * N;
     g.M = M; g.N = N; g.K = K;
+    g.tag = cls == KC_GEMM_GATEUP ? 1 : 0;
     launch_gemm_stream(g, x->st);
     const int sp = stream_gemm_slices(K);
     if (direct) launch_reduce(x->partial, sp, (size_t)M * N, N, nullptr, x->cfg.dtype, direct, ld_direct, M, N, 0, x->st);

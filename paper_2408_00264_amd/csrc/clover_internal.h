@@ -148,6 +148,7 @@ struct StreamGemm {
   size_t split_stride;
   int M, N, K;
   int n_slices, groups;               // filled in by launch_gemm_stream
+  int tag;                            // 1: gate+up projection (selects a separately named instantiation)
   int dbg;                            // timing experiments only (CLOVER_STREAM_DBG): 1 no activation loads, 2 no stores
 };
 bool stream_gemm_supported(int M, int N, int K);

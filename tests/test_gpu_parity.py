@@ -161,6 +161,56 @@ def test_random_tree_and_chain_mask():
     assert ls.max_logit_err <= 1e-4
 
 
+def test_mha_shape_bf16():
+    """Structure of the Vicuna-7B-shaped workload: one query head per KV head, RoPE base 1e4."""
+    _torch()
+    shape = synth.scaled(synth.CONFIGS[2], name="mini-mha", n_layers=2, hidden=512, n_q_heads=4, n_kv_heads=4,
+                         ffn=1280, vocab=4096, tree_k=(4, 3, 2, 2), tree_nodes=24, seed=17)
+    ls = _lockstep(shape, gain_jitter=0.1, max_seq=384)
+    ls.prefill([synth.make_prompts(shape)[0][:131]], chunk=24)
+    for s in range(3):
+        ms = ls.step()
+        say(f"  step {s}: m={ms} max|dlogit|={ls.max_logit_err:.2e} ties={ls.tie_events}")
+    assert ls.max_logit_err <= 3e-2
+
+
+def test_batch8_ragged_32_node_tree():
+    """Structure of the batch-8 workload: 8 ragged sequences x 32-node tree = 256 rows per GEMM."""
+    _torch()
+    shape = synth.scaled(synth.CONFIGS[4], name="mini-b8", n_layers=2, hidden=512, n_q_heads=4, n_kv_heads=2,
+                         ffn=1536, vocab=8192, prompt_len=(16, 200), seed=19)
+    ls = _lockstep(shape, gain_jitter=0.1, batch=8, max_seq=384)
+    prompts = synth.make_prompts(shape)
+    say("batch 8 prompt lengths", [len(p) for p in prompts])
+    ls.prefill(prompts, chunk=32)
+    for s in range(3):
+        ms = ls.step()
+        say(f"  step {s}: m={ms} max|dlogit|={ls.max_logit_err:.2e} ties={ls.tie_events}")
+    assert ls.max_logit_err <= 3e-2
+
+
+def test_long_context_96_node_tree():
+    """Structure of the long-context workload: 96-node tree, draft depth 5, >1000 cached keys (many key
+    tiles and several key splits per attention launch)."""
+    _torch()
+    from tests.parity import truth_hook_factory
+    shape = synth.scaled(synth.CONFIGS[5], name="mini-long", n_layers=2, hidden=512, n_q_heads=4, n_kv_heads=2,
+                         ffn=1536, vocab=8192, prompt_len=(1100, 1100), seed=23)
+    ls = _lockstep(shape, gain_jitter=0.1, max_seq=1536)
+    ls.prefill(synth.make_prompts(shape), chunk=96)
+    want = [6, 2]
+    hook = truth_hook_factory(ls, want)
+    for s in range(len(want)):
+        ties = ls.tie_events
+        ms = ls.step(tree_hook=hook)
+        say(f"  step {s}: want {want[s]} got {ms} max|dlogit|={ls.max_logit_err:.2e} ties={ls.tie_events}")
+        if ls.tie_events == ties:
+            assert ms == [want[s]]
+    ms = ls.step()
+    say(f"  free step: m={ms} max|dlogit|={ls.max_logit_err:.2e}")
+    assert ls.max_logit_err <= 3e-2
+
+
 # ------------------------------------------------------------------------------------------
 # error paths reachable without touching the kernels
 # ------------------------------------------------------------------------------------------
