@@ -201,7 +201,8 @@ const char *clover_last_global_error(void);
 /* Y[M,N] (fp32, leading dimension ldy) = X[M,K] (fp32, ld = K) * W[N,K]^T, W in `dtype`.
  * path 0 = generic fp32-ALU kernel, 1 = MFMA weight-streaming kernels (bf16 only; W is first copied
  * into `scratch` in the library's fragment-major layout), 2 = as 1 but reusing the copy a previous
- * path-1 call with the same W and scratch left behind (times the GEMM alone).
+ * path-1 call with the same W and scratch left behind (times the GEMM alone); 3 = full-K panel
+ * kernel (bf16, M <= 64, K % 256 == 0, N % 16 == 0, ldy % 4 == 0), 4 = as 3 reusing the copy.
  * `scratch` dev, >= clover_op_gemm_scratch_bytes(M,N,K).  Stream as given. */
 size_t clover_op_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K);
 int clover_op_gemm(int32_t path, int32_t dtype, const float *X, const void *W, float *Y, int32_t ldy,

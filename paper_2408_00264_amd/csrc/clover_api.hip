@@ -75,6 +75,7 @@ struct clover_ctx {
   size_t packed_bytes;
   const void* lm_head_pk;
   bool fast;               // bf16 model on the MFMA path
+  bool panel;              // full-K panel GEMM for the gate+up projection and the LM head
   // host-side bounds
   std::vector<int> len_ub, aug_ub;
   int m_upper;
@@ -277,6 +278,7 @@ void carve(clover_ctx* x, char* base, size_t* total) {
   x->packed_bytes = packed_bytes;
   x->packed = cv.take<char>(packed_bytes ? packed_bytes : 256);
   x->fast = fast;
+  x->panel = fast && !getenv("CLOVER_NO_PANEL");
   x->kvdtype = fast ? 1 : 0;
   x->kv_layer_stride = fast ? 2 * x->k_layer_elems : x->k_layer_elems;
   x->attn_fast = fast && attn_mfma_supported(d, c.n_q_heads, c.n_kv_heads, c.max_seq);
@@ -433,7 +435,16 @@ void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMa
     { Scope s(x, KC_RMSNORM);
       launch_reduce_add_norm(xres, H, x->partial, sw, (size_t)M * H, H, lw.ffn_norm, c.dtype, c.rms_eps, A.hi, A.lo, H, M,
                              H, x->st); }
-    if (M <= 64 && stream_gemm_supported(M, 2 * F, H) && stream_gemm_out_bytes(M, 2 * F, H) <= x->partial_bytes) {
+    if (x->panel && panel_gemm_supported(M, F, H, 1)) {
+      Scope s(x, KC_GEMM_GATEUP);
+      PanelGemm g;
+      memset(&g, 0, sizeof(g));
+      g.Xhi = A.hi; g.Xlo = A.lo; g.ldx = H;
+      g.W[0] = (const bf16_t*)lw.w_gate; g.W[1] = (const bf16_t*)lw.w_up;
+      g.Yhi = Hf.hi; g.Ylo = Hf.lo; g.ldo = F;
+      g.M = M; g.N = F; g.K = H; g.epi = 1;
+      launch_gemm_panel(g, x->st);
+    } else if (M <= 64 && stream_gemm_supported(M, 2 * F, H) && stream_gemm_out_bytes(M, 2 * F, H) <= x->partial_bytes) {
       const void* wgu[2] = {lw.w_gate, lw.w_up};
       const int gun[2] = {F, F};
       const int sg = gemm_fast(x, KC_GEMM_GATEUP, A, 2, wgu, gun, M, 2 * F, H, nullptr, 0);
@@ -521,13 +532,30 @@ void run_fc(clover_ctx* x, const float* X, int K, const void* W, const void* bia
   }
 }
 
+// out[rows, vocab] = A * lm_head^T (MFMA path)
+void lm_head_fast(clover_ctx* x, Planes A, int rows, float* out) {
+  const clover_config& c = x->cfg;
+  if (x->panel && rows > 16 && panel_gemm_supported(rows, c.vocab, x->H, 0)) {
+    Scope s(x, KC_GEMM_LMHEAD);
+    PanelGemm g;
+    memset(&g, 0, sizeof(g));
+    g.Xhi = A.hi; g.Xlo = A.lo; g.ldx = A.ld;
+    g.W[0] = g.W[1] = (const bf16_t*)x->lm_head_pk;
+    g.Y = out; g.ldy = c.vocab;
+    g.M = rows; g.N = c.vocab; g.K = x->H; g.epi = 0;
+    launch_gemm_panel(g, x->st);
+    return;
+  }
+  gemm_fast1(x, KC_GEMM_LMHEAD, A, x->lm_head_pk, rows, c.vocab, x->H, out, c.vocab);
+}
+
 // logits of `rows` contiguous rows of g through the head norm and the shared LM head, then top-k
 void run_head(clover_ctx* x, const float* g, int rows, int k) {
   const clover_config& c = x->cfg;
   const int H = x->H;
   if (x->fast) {
     Planes A = norm_planes(x, g, x->w.head_norm, rows);
-    gemm_fast1(x, KC_GEMM_LMHEAD, A, x->lm_head_pk, rows, c.vocab, H, x->z, c.vocab);
+    lm_head_fast(x, A, rows, x->z);
   } else {
     { Scope s(x, KC_RMSNORM); launch_rmsnorm(g, H, x->w.head_norm, c.dtype, c.rms_eps, x->a_norm, H, H, rows, x->st); }
     gemm_generic(x, KC_GEMM_LMHEAD, x->a_norm, H, x->w.lm_head, nullptr, x->z, c.vocab, rows, c.vocab, H, 0);
@@ -797,7 +825,7 @@ int verify_tree(clover_ctx* x, int32_t batch, const int32_t* tree_tokens, float*
   if (x->fast) {
     Planes A = planes_of(x, x->a_norm, 2 * H);
     A.ld = H;
-    gemm_fast1(x, KC_GEMM_LMHEAD, A, x->lm_head_pk, M, c.vocab, H, logits, c.vocab);
+    lm_head_fast(x, A, M, logits);
   } else {
     { Scope s(x, KC_RMSNORM); launch_rmsnorm(hidden, H, x->w.final_norm, c.dtype, c.rms_eps, x->a_norm, H, H, M, x->st); }
     gemm_generic(x, KC_GEMM_LMHEAD, x->a_norm, H, x->w.lm_head, nullptr, logits, c.vocab, M, c.vocab, H, 0);
@@ -926,9 +954,22 @@ int clover_op_gemm(int32_t path, int32_t dtype, const float* X, const void* W, f
     bf16_t* hi = (bf16_t*)((char*)scratch + align256((size_t)N * K * 2));
     bf16_t* lo = hi + (size_t)M * K;
     float* part = (float*)((char*)hi + align256((size_t)M * K * 4));
-    if (path == 1) launch_pack_weight(W, wp, N, K, st);
+    if (path == 1 || path == 3) launch_pack_weight(W, wp, N, K, st);
     launch_split_planes(X, K, hi, lo, K, M, K, st);
     int splits;
+    if (path >= 3) {
+      if (!panel_gemm_supported(M, N, K, 0) || ldy % 4 != 0)
+        return fail(nullptr, CLOVER_E_SHAPE, "shape not supported by the panel GEMM");
+      PanelGemm g;
+      memset(&g, 0, sizeof(g));
+      g.Xhi = hi; g.Xlo = lo; g.ldx = K;
+      g.W[0] = g.W[1] = wp;
+      g.Y = Y; g.ldy = ldy; g.M = M; g.N = N; g.K = K; g.epi = 0;
+      launch_gemm_panel(g, st);
+      const hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return fail(nullptr, CLOVER_E_HIP, hipGetErrorString(e));
+      return CLOVER_OK;
+    }
     if (M <= 64 && stream_gemm_supported(M, N, K)) {
       StreamGemm g;
       memset(&g, 0, sizeof(g));

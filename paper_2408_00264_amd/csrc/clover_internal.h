@@ -159,4 +159,18 @@ void launch_gemm_stream(StreamGemm g, hipStream_t st);
 void launch_reduce_swiglu(const float* P, int splits, size_t split_stride, int ldp, int F, bf16_t* hi, bf16_t* lo,
                           int ldo, int rows, hipStream_t st);
 
+
+// ---- full-K panel GEMM (M <= 64, many output columns): finished results, no K-slice partials ----
+struct PanelGemm {
+  const bf16_t *Xhi, *Xlo; int ldx;   // activation planes [M, K]
+  const bf16_t* W[2];                 // fragment-major; epi 1: W[0] = gate, W[1] = up, each [N, K]
+  float* Y; int ldy;                  // epi 0: fp32 [M, N]
+  bf16_t *Yhi, *Ylo; int ldo;         // epi 1: planes of silu(X W0^T) * (X W1^T), [M, N]
+  int M, N, K;
+  int epi;                            // 0 plain, 1 SwiGLU
+  int dbg;                            // timing experiments only (CLOVER_PANEL_DBG): 1 no activation loads
+};
+bool panel_gemm_supported(int M, int N, int K, int epi);
+void launch_gemm_panel(const PanelGemm& g, hipStream_t st);
+
 }  // namespace clv

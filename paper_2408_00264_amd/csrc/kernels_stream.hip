@@ -21,12 +21,14 @@
 
 #include <algorithm>
 #include <cstdlib>
+#include <type_traits>
 
 namespace clv {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef const u32x4 __attribute__((address_space(1)))* gvec_ptr;  // global (not flat) address: vmcnt only
 
 union Frag {
   u32x4 u;
@@ -70,7 +72,7 @@ __global__ __launch_bounds__(ST_WAVES * 64) void gemm_stream_kernel(StreamGemm p
   constexpr int PLANE = ROWS * ST_LDK;
   extern __shared__ __attribute__((aligned(16))) bf16_t xs[];  // [hi, lo][ROWS][ST_LDK]
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int l16 = lane & 15, g4 = lane >> 4;
   const int slice = blockIdx.x % p.n_slices, grp = blockIdx.x / p.n_slices;
   const int k0 = slice * ST_KSL;
@@ -95,25 +97,33 @@ __global__ __launch_bounds__(ST_WAVES * 64) void gemm_stream_kernel(StreamGemm p
 #pragma unroll
     for (int mb = 0; mb < MT; ++mb) acc[f][mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  auto frag_base = [&](int unit, int f, int& col) -> const bf16_t* {
+  // Segment lookup by arithmetic on scalars held in registers: base = W0 + [n >= b1] * d1 + [n >= b2] * d2
+  // with d1, d2 the pointer differences corrected for the segments' first rows.  (Indexing the
+  // by-value argument struct with a runtime index, or a chain of pointer selects, ends up as a
+  // memory load whose wait also drains the weight loads in flight.)
+  const long long KT512 = (long long)KT * 512;
+  const long long seg_w0 = (long long)p.W[0];
+  const long long seg_d1 = (long long)p.W[1] - (long long)p.W[0] - (long long)(p.seg_begin[1] / 16) * KT512 * 2;
+  const long long seg_d2 = (long long)p.W[2] - (long long)p.W[1] - (long long)((p.seg_begin[2] - p.seg_begin[1]) / 16) * KT512 * 2;
+  const int seg_b1 = p.seg_begin[1], seg_b2 = p.seg_begin[2];
+  auto frag_base = [&](int unit, int f) -> const bf16_t* {
     const int n = (unit * NF + f) * 16;
-    int s = 0;
-    if (n >= p.seg_begin[1]) s = 1;
-    if (n >= p.seg_begin[2]) s = 2;
-    col = n;
-    return p.W[s] + ((size_t)((n - p.seg_begin[s]) / 16) * KT + k0 / 32) * 512 + lane * 8;
+    const long long b = seg_w0 + (seg_d1 & -(long long)(n >= seg_b1)) + (seg_d2 & -(long long)(n >= seg_b2));
+    return (const bf16_t*)b + ((size_t)(n / 16) * KT + k0 / 32) * 512 + lane * 8;
   };
-  auto load = [&](int buf, int item) {
+  auto load = [&](auto bufc, int item) {
+    constexpr int buf = decltype(bufc)::value;
     const int unit = u0 + wave + (item / n_st) * ST_WAVES, st = item % n_st;
 #pragma unroll
     for (int f = 0; f < NF; ++f) {
-      int col;
-      const bf16_t* b = frag_base(unit, f, col) + (size_t)st * ST_STAGE * 512;
+      const bf16_t* b = frag_base(unit, f) + (size_t)st * ST_STAGE * 512;
 #pragma unroll
-      for (int t = 0; t < ST_STAGE; ++t) w[buf][f][t].u = __builtin_nontemporal_load((const u32x4*)(b + t * 512));
+      for (int t = 0; t < ST_STAGE; ++t) w[buf][f][t].u = __builtin_nontemporal_load((gvec_ptr)(b + t * 512));
     }
   };
-  if (n_items > 0) load(0, 0);  // the HBM stream starts before the activation slice is staged
+  constexpr std::integral_constant<int, 0> B0{};
+  constexpr std::integral_constant<int, 1> B1{};
+  if (n_items > 0) load(B0, 0);  // the HBM stream starts before the activation slice is staged
 
   // ---- activation slice -> LDS (rows >= M are zero); all loads are issued before the first store.
   // One wavefront instruction moves one row of one plane (64 lanes x 16 B = 512 columns), so the
@@ -138,7 +148,8 @@ __global__ __launch_bounds__(ST_WAVES * 64) void gemm_stream_kernel(StreamGemm p
   __syncthreads();
   if (n_items == 0) return;
 
-  auto compute = [&](int buf, int item) {
+  auto compute = [&](auto bufc, int item) {
+    constexpr int buf = decltype(bufc)::value;
     const int st = item % n_st;
     const bf16_t* hi = xs + l16 * ST_LDK + g4 * 8 + st * ST_STAGE * 32;
     const bf16_t* lo = hi + PLANE;
@@ -173,12 +184,28 @@ __global__ __launch_bounds__(ST_WAVES * 64) void gemm_stream_kernel(StreamGemm p
     }
   };
 
-  for (int i = 0; i < n_items; i += 2) {
-    if (i + 1 < n_items) load(1, i + 1);
-    compute(0, i);
-    if (i + 1 >= n_items) break;
-    if (i + 2 < n_items) load(0, i + 2);
-    compute(1, i + 1);
+  // Steady state without conditions around the loads, so that the wait before a compute step
+  // counts exactly the loads issued after its buffer and leaves them in flight.
+  int i = 0;
+  // (the scheduling barriers keep the compiler from sinking a buffer's loads below the compute step
+  // they are meant to overlap)
+  for (; i + 2 < n_items; i += 2) {
+    load(B1, i + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(B0, i);
+    __builtin_amdgcn_sched_barrier(0);
+    load(B0, i + 2);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(B1, i + 1);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  if (i + 1 < n_items) {
+    load(B1, i + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(B0, i);
+    compute(B1, i + 1);
+  } else {
+    compute(B0, i);
   }
 }
 

@@ -33,6 +33,9 @@ GEMM_CASES = [
     (1, 1, 64, 6144, 4096), (1, 1, 5, 4096, 8192), (1, 1, 16, 4096, 4096), (1, 1, 24, 1024, 512),
     (1, 1, 96, 4096, 14336), (1, 1, 256, 4096, 4096), (1, 1, 1, 32000, 4096), (1, 1, 130, 8192, 512),
     (1, 1, 64, 160, 256), (1, 1, 64, 28672, 4096), (1, 1, 48, 4096, 1536),
+    # full-K panel kernel: odd block count, ragged rows, one row, LM-head width
+    (3, 1, 64, 28672, 4096), (3, 1, 17, 1040, 768), (3, 1, 5, 4096, 512), (3, 1, 64, 160, 256), (3, 1, 1, 2064, 256),
+    (3, 1, 33, 128256, 4096),
 ]
 
 
