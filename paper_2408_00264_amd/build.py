@@ -30,9 +30,19 @@ def build(verbose: bool = False) -> str:
 
     def compile_one(src: str) -> str:
         obj = os.path.join(BUILD, src.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *FLAGS, "-Rpass-analysis=kernel-resource-usage", "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
-        err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+        lines = r.stderr.splitlines()
+        # a kernel that keeps arrays or spills in scratch memory runs many times slower: say so loudly
+        name = None
+        for l in lines:
+            if "Function Name:" in l:
+                name = l.split("Function Name:")[1].split("[")[0].strip()
+            elif "ScratchSize [bytes/lane]:" in l and name:
+                n = int(l.split("ScratchSize [bytes/lane]:")[1].split("[")[0])
+                if n:
+                    print(f"[build] WARNING: {src}: kernel {name} uses {n} bytes/lane of scratch", file=sys.stderr)
+        err = "\n".join(l for l in lines if "packed-fp32-ops" not in l and "-Rpass-analysis" not in l)
         if r.returncode != 0:
             raise RuntimeError(f"hipcc failed for {src}:\n{err}")
         if verbose and err.strip():

@@ -22,6 +22,7 @@
 #include "clover_internal.h"
 
 #include <algorithm>
+#include <type_traits>
 
 namespace clv {
 
@@ -103,10 +104,12 @@ __global__ __launch_bounds__(64 * G) void attn_mfma_kernel(AttnParams p) {
   constexpr int NT = 64 * G;
   constexpr int KSLOTS = 2 * AT_TK * 16, VSLOTS = 2 * AT_D * 4;  // both 1024
   constexpr int KIT = KSLOTS / NT, VIT = VSLOTS / NT;
-  u32x4 kr[KIT], vr[VIT];
+  // two register sets: while a tile is multiplied, the next one sits in LDS or lands in one set and
+  // the one after it is in flight into the other
+  u32x4 krA[KIT], vrA[VIT], krB[KIT], vrB[VIT];
   const bf16_t* kbase = p.k_hi + (size_t)b * p.max_seq * p.n_kv * AT_D + (size_t)kvh * AT_D;
   const bf16_t* vbase = p.v_hi + ((size_t)b * p.n_kv + kvh) * AT_D * p.max_seq;
-  auto load_tile = [&](int t) {
+  auto load_tile = [&](u32x4 (&kr)[KIT], u32x4 (&vr)[VIT], int t) __attribute__((always_inline)) {
 #pragma unroll
     for (int it = 0; it < KIT; ++it) {
       const int idx = it * NT + tid, plane = idx >> 9, rem = idx & 511, key = rem >> 4, sl = rem & 15;
@@ -120,7 +123,7 @@ __global__ __launch_bounds__(64 * G) void attn_mfma_kernel(AttnParams p) {
       vr[it] = *(const u32x4*)(vbase + plane * p.v_plane + (size_t)dr * p.max_seq + j);
     }
   };
-  auto store_tile = [&](int buf) {
+  auto store_tile = [&](const u32x4 (&kr)[KIT], const u32x4 (&vr)[VIT], int buf) __attribute__((always_inline)) {
     bf16_t* base = sm + buf * AT_BUF;
 #pragma unroll
     for (int it = 0; it < KIT; ++it) {
@@ -135,7 +138,8 @@ __global__ __launch_bounds__(64 * G) void attn_mfma_kernel(AttnParams p) {
       *(u32x4*)(base + 2 * AT_KPLANE + plane * AT_VPLANE + dr * AT_VLD + sl * 8) = vr[it];
     }
   };
-  auto compute = [&](int buf, int t) {
+  auto compute_t = [&](int buf, int t, auto cachedc) __attribute__((always_inline)) {
+    constexpr bool CACHED = decltype(cachedc)::value;  // every key of the tile is a cached token: no tree mask
     const bf16_t* kb = sm + buf * AT_BUF + l16 * AT_KLD + g4 * 8;
     const bf16_t* vb = sm + buf * AT_BUF + 2 * AT_KPLANE + l16 * AT_VLD + g4 * 8;
     f32x4 s[2][AT_MB];
@@ -165,8 +169,8 @@ __global__ __launch_bounds__(64 * G) void attn_mfma_kernel(AttnParams p) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) {  // e-th key of this lane: slot t*32 + 8*g4 + e
         const int j = t * AT_TK + 8 * g4 + e;
-        bool vis = j < L;
-        if (!vis && j < total) {
+        bool vis = CACHED || j < L;
+        if (!CACHED && !vis && j < total) {
           const int wn = j - L;
           vis = ((wn < 64 ? (a0[mb] >> wn) : (a1[mb] >> (wn - 64))) & 1ull) != 0ull;
         }
@@ -206,16 +210,40 @@ __global__ __launch_bounds__(64 * G) void attn_mfma_kernel(AttnParams p) {
     }
   };
 
+  auto compute = [&](int buf, int t) __attribute__((always_inline)) {
+    // (specialised only where the register file has room for both versions)
+    if ((G == 2 || G == 4) && (t + 1) * AT_TK <= L) compute_t(buf, t, std::true_type{});  // uniform
+    else compute_t(buf, t, std::false_type{});
+  };
+
   if (t0 < t1) {  // uniform over the workgroup
-    load_tile(t0);
-    store_tile(0);
-    __syncthreads();
-    for (int t = t0; t < t1; ++t) {
-      const int buf = (t - t0) & 1;
-      if (t + 1 < t1) load_tile(t + 1);
-      compute(buf, t);
-      if (t + 1 < t1) store_tile(buf ^ 1);
+    const int n = t1 - t0;
+    load_tile(krA, vrA, t0);
+    if constexpr (G == 4) {
+      if (n > 1) load_tile(krB, vrB, t0 + 1);
+      store_tile(krA, vrA, 0);
       __syncthreads();
+      for (int i = 0; i < n; i += 2) {
+        // tile i is in LDS buffer 0, tile i+1 in set B (landing), tile i+2 goes to set A
+        if (i + 2 < n) load_tile(krA, vrA, t0 + i + 2);
+        compute(0, t0 + i);
+        if (i + 1 >= n) break;
+        store_tile(krB, vrB, 1);
+        __syncthreads();
+        if (i + 3 < n) load_tile(krB, vrB, t0 + i + 3);
+        compute(1, t0 + i + 1);
+        if (i + 2 < n) store_tile(krA, vrA, 0);
+        __syncthreads();
+      }
+    } else {  // few threads per workgroup: one staging set is all the register file holds
+      store_tile(krA, vrA, 0);
+      __syncthreads();
+      for (int i = 0; i < n; ++i) {
+        if (i + 1 < n) load_tile(krA, vrA, t0 + i + 1);
+        compute(i & 1, t0 + i);
+        if (i + 1 < n) store_tile(krA, vrA, (i & 1) ^ 1);
+        __syncthreads();
+      }
     }
   }
 
@@ -240,29 +268,50 @@ __global__ __launch_bounds__(64 * G) void attn_mfma_kernel(AttnParams p) {
   }
 }
 
-// merge the splits of one (row, head): out = sum_s e^{m_s - M} O_s / sum_s e^{m_s - M} l_s, as planes
-__global__ void attn_merge_kernel(const float* __restrict__ o_part, const float* __restrict__ ml_part, int n_splits,
-                                  int rows_total, int n_q, bf16_t* __restrict__ out_hi, bf16_t* __restrict__ out_lo,
-                                  int ldo, RowMap rm) {
-  const int i = blockIdx.x, b = blockIdx.y, head = blockIdx.z, dd = threadIdx.x;
+// merge the splits of one (row, head): out = sum_s e^{m_s - M} O_s / sum_s e^{m_s - M} l_s, as planes.
+// One thread owns four adjacent channels of one head; the (m, l) pairs and then the partial rows of
+// all splits are loaded as one batch each, so a thread waits for memory twice, not once per split.
+constexpr int MG_HEADS = 8;   // heads per workgroup (32 threads each)
+constexpr int MG_MAXS = 16;   // >= the largest split count the launcher picks
+__global__ __launch_bounds__(MG_HEADS * 32) void attn_merge_kernel(const float* __restrict__ o_part,
+                                                                    const float* __restrict__ ml_part, int n_splits,
+                                                                    int rows_total, int n_q, bf16_t* __restrict__ out_hi,
+                                                                    bf16_t* __restrict__ out_lo, int ldo, RowMap rm) {
+  const int i = blockIdx.x, b = blockIdx.y;
+  const int head = blockIdx.z * MG_HEADS + (threadIdx.x >> 5), d4 = (threadIdx.x & 31) * 4;
   const int nv = rm.n_valid ? min(rm.n_valid[b], rm.n) : rm.n;
-  if (i >= nv) return;
+  if (i >= nv || head >= n_q) return;
   const size_t row = (size_t)b * rm.R + i;
+  const size_t sstride = (size_t)rows_total * n_q;   // (row, head) pairs per split
+  const size_t pr0 = row * n_q + head;
+  float2 ml[MG_MAXS];
+#pragma unroll
+  for (int s = 0; s < MG_MAXS; ++s)
+    ml[s] = s < n_splits ? *(const float2*)(ml_part + (pr0 + s * sstride) * 2) : make_float2(-INFINITY, 0.f);
+  float4 o[MG_MAXS];
+#pragma unroll
+  for (int s = 0; s < MG_MAXS; ++s)
+    o[s] = s < n_splits ? *(const float4*)(o_part + (pr0 + s * sstride) * AT_D + d4) : make_float4(0.f, 0.f, 0.f, 0.f);
   float M = -INFINITY;
-  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ml_part[(((size_t)s * rows_total + row) * n_q + head) * 2]);
-  float num = 0.f, den = 0.f;
-  for (int s = 0; s < n_splits; ++s) {
-    const size_t pr = ((size_t)s * rows_total + row) * n_q + head;
-    const float ms = ml_part[pr * 2];
-    if (ms == -INFINITY) continue;
-    const float wgt = __expf(ms - M);
-    den += wgt * ml_part[pr * 2 + 1];
-    num += wgt * o_part[pr * AT_D + dd];
+#pragma unroll
+  for (int s = 0; s < MG_MAXS; ++s) M = fmaxf(M, ml[s].x);
+  float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+  float den = 0.f;
+#pragma unroll
+  for (int s = 0; s < MG_MAXS; ++s) {  // split order: the sum does not depend on how the loads were batched
+    const float wgt = ml[s].x == -INFINITY ? 0.f : __expf(ml[s].x - M);
+    den += wgt * ml[s].y;
+    num.x += wgt * o[s].x; num.y += wgt * o[s].y; num.z += wgt * o[s].z; num.w += wgt * o[s].w;
   }
-  const float o = num / den;
-  const unsigned h = a_rn(o);
-  out_hi[row * ldo + head * AT_D + dd] = (bf16_t)h;
-  out_lo[row * ldo + head * AT_D + dd] = (bf16_t)a_rn(o - __uint_as_float(h << 16));
+  const float v[4] = {num.x / den, num.y / den, num.z / den, num.w / den};
+  unsigned h[4], l[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    h[r] = a_rn(v[r]);
+    l[r] = a_rn(v[r] - __uint_as_float(h[r] << 16));
+  }
+  *(uint2*)(out_hi + row * ldo + head * AT_D + d4) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+  *(uint2*)(out_lo + row * ldo + head * AT_D + d4) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
 }
 
 bool attn_mfma_supported(int head_dim, int n_q, int n_kv, int max_seq) {
@@ -287,7 +336,7 @@ void launch_attn_mfma(AttnParams p, int max_total_keys, bf16_t* out_hi, bf16_t* 
   const int n_tiles = (max_total_keys + AT_TK - 1) / AT_TK;
   // enough workgroups to fill the chip twice, at least two tiles per split, within the partial buffer
   int splits = (512 + p.rm.B * p.n_kv * node_groups - 1) / (p.rm.B * p.n_kv * node_groups);
-  splits = std::max(1, std::min(std::min(splits, p.max_splits), (n_tiles + 1) / 2));
+  splits = std::max(1, std::min(std::min(splits, std::min(p.max_splits, MG_MAXS)), (n_tiles + 1) / 2));
   p.tiles_per_split = (n_tiles + splits - 1) / splits;
   p.n_splits = (n_tiles + p.tiles_per_split - 1) / p.tiles_per_split;
   dim3 grid(p.n_splits, node_groups * p.n_kv, p.rm.B);
@@ -297,8 +346,8 @@ void launch_attn_mfma(AttnParams p, int max_total_keys, bf16_t* out_hi, bf16_t* 
     case 4: launch_attn_one<4>(p, grid, st); break;
     default: launch_attn_one<8>(p, grid, st); break;
   }
-  attn_merge_kernel<<<dim3(p.rm.n, p.rm.B, p.n_q), AT_D, 0, st>>>(p.o_part, p.ml_part, p.n_splits, p.rows_total, p.n_q,
-                                                                 out_hi, out_lo, ldo, p.rm);
+  attn_merge_kernel<<<dim3(p.rm.n, p.rm.B, (p.n_q + MG_HEADS - 1) / MG_HEADS), MG_HEADS * 32, 0, st>>>(
+      p.o_part, p.ml_part, p.n_splits, p.rows_total, p.n_q, out_hi, out_lo, ldo, p.rm);
 }
 
 }  // namespace clv

@@ -762,7 +762,7 @@ void launch_reduce(const float* P, int splits, size_t split_stride, int ldp, con
     reduce_kernel<bf16_t><<<grid, 256, 0, st>>>(P, splits, split_stride, ldp, (const bf16_t*)bias, Y, ldy, N, mode);
 }
 
-// one 1024-thread block per row: residual add of the split-K partials (eight loads in flight per
+// one 1024-thread block per row: residual add of the split-K partials (sixteen loads in flight per
 // thread, summed in split order), then RMSNorm written as planes
 template <typename WT>
 __global__ __launch_bounds__(1024) void reduce_add_norm_kernel(float* __restrict__ x, int ldx,
@@ -777,13 +777,13 @@ __global__ __launch_bounds__(1024) void reduce_add_norm_kernel(float* __restrict
   float ss = 0.f;
   for (int c = threadIdx.x * 4; c < H; c += 4096) {
     float4 v = *(const float4*)(xr + c);
-    for (int s0 = 0; s0 < splits; s0 += 8) {
-      float4 q[8];
+    for (int s0 = 0; s0 < splits; s0 += 16) {
+      float4 q[16];
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
+      for (int j = 0; j < 16; ++j)
         q[j] = (s0 + j < splits) ? *(const float4*)(pr + (size_t)(s0 + j) * sps + c) : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-      for (int j = 0; j < 8; ++j) { v.x += q[j].x; v.y += q[j].y; v.z += q[j].z; v.w += q[j].w; }
+      for (int j = 0; j < 16; ++j) { v.x += q[j].x; v.y += q[j].y; v.z += q[j].z; v.w += q[j].w; }
     }
     if (splits > 0) *(float4*)(xr + c) = v;
     ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
