@@ -17,12 +17,12 @@ LIB_PATH = os.path.join(_HERE, "libclover.so")
 
 OK, E_NULL, E_CONFIG, E_TREE, E_CAPACITY, E_SHAPE, E_HIP, E_STATE = 0, -1, -2, -3, -4, -5, -6, -7
 DTYPE_F32, DTYPE_BF16 = 0, 1
-FLAG_GENERIC, FLAG_NO_GRAPH = 1, 2
+FLAG_GENERIC, FLAG_NO_GRAPH, FLAG_MEGA = 1, 2, 4
 
 EXPORTS = [
     "clover_workspace_bytes", "clover_init", "clover_destroy", "clover_reset", "clover_set_tree",
     "draft_tree", "verify_tree", "accept_and_compact", "clover_accept_forced", "clover_seq_len",
-    "clover_read_kv", "clover_profile_enable", "clover_profile_collect", "clover_kernel_class_count",
+    "clover_read_kv", "clover_path_info", "clover_profile_phases", "clover_profile_enable", "clover_profile_collect", "clover_kernel_class_count",
     "clover_kernel_class_name", "clover_last_error", "clover_last_global_error",
     "clover_op_gemm_scratch_bytes", "clover_op_gemm",
 ]
@@ -80,6 +80,8 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.clover_accept_forced.argtypes = [vp, i32, i32p, f32p, f32p, i32p, i32p, i32p, i32p, i32p, f32p, i32p]
     lib.clover_seq_len.argtypes = [vp, C.POINTER(C.c_int32)]
     lib.clover_read_kv.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp]
+    lib.clover_path_info.argtypes = [vp]
+    lib.clover_profile_phases.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32), i32, C.POINTER(i32)]
     lib.clover_profile_enable.argtypes = [vp, i32]
     lib.clover_profile_collect.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), i32]
     lib.clover_kernel_class_count.argtypes = []
@@ -244,6 +246,13 @@ class Clover:
                                                 k[s0:].ctypes.data, v[s0:].ctypes.data))
         return k, v
 
+    def path_info(self) -> int:
+        """Bit 0: MFMA path, bit 1: MFMA tree attention, bit 2: persistent phase-program kernel."""
+        v = self.lib.clover_path_info(self.ctx)
+        if v < 0:
+            self._check(v)
+        return v
+
     def profile_enable(self, on: bool) -> None:
         self._check(self.lib.clover_profile_enable(self.ctx, 1 if on else 0))
 
@@ -253,6 +262,15 @@ class Clover:
         cnt = (C.c_int64 * n)()
         self._check(self.lib.clover_profile_collect(self.ctx, ms, cnt, n))
         return {self.lib.clover_kernel_class_name(i).decode(): (ms[i], cnt[i]) for i in range(n)}
+
+    def profile_phases(self) -> List[tuple]:
+        """(class name, microseconds) per phase of the last profiled persistent-kernel launch."""
+        cap = 4096
+        us = (C.c_double * cap)()
+        cls = (C.c_int32 * cap)()
+        n = C.c_int32(0)
+        self._check(self.lib.clover_profile_phases(self.ctx, us, cls, cap, C.byref(n)))
+        return [(self.lib.clover_kernel_class_name(cls[i]).decode(), us[i]) for i in range(n.value)]
 
     # -- call sequences (no arithmetic here) -----------------------------------------------------
     def prefill(self, prompts: List[np.ndarray], parent, rank, chunk: Optional[int] = None) -> None:

@@ -18,7 +18,7 @@ thread_local std::string g_err;
 
 const char* kClassNames[KC_COUNT] = {"embed",     "rmsnorm",     "gemm_qkv",   "rope_kv_write", "tree_attention", "gemm_wo",
                                      "gemm_gate_up", "gemm_down", "gemm_lm_head", "gemm_draft",  "ad_gate",        "topk",
-                                     "draft_misc", "accept_walk", "compact_kv", "eltwise"};
+                                     "draft_misc", "accept_walk", "compact_kv", "eltwise", "layer_stack"};
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -76,6 +76,20 @@ struct clover_ctx {
   const void* lm_head_pk;
   bool fast;               // bf16 model on the MFMA path
   bool panel;              // full-K panel GEMM for the gate+up projection and the LM head
+  // persistent phase-program kernel (one cooperative launch per verify pass)
+  bool mega = false;       // usable for this model on this device
+  bool mega_phases = false;  // debugging / profiling: one launch per phase
+  int mega_grid = 0;
+  long long mega_limit = 0;
+  unsigned mega_seq = 0;   // barriers executed since the counters were zeroed
+  MegaSync* d_sync;
+  MegaPhase* d_prog;
+  int prog_cap;
+  float* d_ss;             // [rows][4] sums of squares of the residual rows
+  long long* d_stamps;     // [prog_cap + 1] phase time stamps of the last profiled launch
+  int wall_khz = 100000;
+  std::vector<MegaPhase> prog_host;   // what d_prog holds
+  std::vector<int> prog_cls;          // kernel class of each phase (per-phase profiling)
   // host-side bounds
   std::vector<int> len_ub, aug_ub;
   int m_upper;
@@ -271,6 +285,8 @@ void carve(clover_ctx* x, char* base, size_t* total) {
         pbytes = std::max(pbytes, (size_t)sp * mtot * s.N * sizeof(float));
       }
     }
+    // the persistent kernel writes up to 8 K-group partials of its QKV / Wo / down projections
+    pbytes = std::max(pbytes, (size_t)8 * std::min(rows, 64) * std::max(x->QKVN, H) * sizeof(float));
     const size_t layer_elems = (size_t)x->QKVN * H + (size_t)H * x->NQD + (size_t)3 * c.ffn * H;
     packed_bytes = 2 * ((size_t)(c.n_layers + c.aug_layers) * layer_elems + (size_t)c.vocab * H + (size_t)7 * H * H +
                         (size_t)(c.draft_depths - 1) * 2 * H * H);
@@ -288,6 +304,11 @@ void carve(clover_ctx* x, char* base, size_t* total) {
   x->partial_bytes = pbytes;
   x->partial = (float*)cv.take<char>(pbytes);
   x->pl_y = cv.take<float>((size_t)rows * 2 * H);
+  x->d_sync = cv.take<MegaSync>(1);
+  x->prog_cap = 2 + 9 * std::max(c.n_layers, c.aug_layers) + 64;
+  x->d_prog = cv.take<MegaPhase>(x->prog_cap);
+  x->d_ss = cv.take<float>((size_t)std::max(rows, 64) * 4);
+  x->d_stamps = cv.take<long long>(x->prog_cap + 1);
   *total = cv.off;
 }
 
@@ -488,6 +509,149 @@ void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMa
   gemm_generic(x, KC_GEMM_GATEUP, x->a_norm, H, lw.w_up, nullptr, x->h_ffn, F, M, F, H, 0);
   { Scope s(x, KC_ELTWISE); launch_swiglu(x->tmp_ffn, x->h_ffn, x->h_ffn, (size_t)M * F, x->st); }
   gemm_generic(x, KC_GEMM_DOWN, x->h_ffn, F, lw.w_down, nullptr, xres, H, M, H, F, 1);
+}
+
+
+// ---- persistent phase-program path ----------------------------------------------------------
+// Is the phase-program kernel usable for this model?  (bf16 MFMA path, head_dim 128, every GEMM shape
+// a multiple of the kernel's tiles, fused weights contiguous in the packed copy.)
+bool mega_model_ok(clover_ctx* x) {
+  const clover_config& c = x->cfg;
+  const int H = x->H, F = c.ffn;
+  if (!x->fast || !x->attn_fast || c.head_dim != 128) return false;
+  if (H % 256 || x->NQD % 256 || F % 256 || x->QKVN % 16 || H % 16 || F % 16 || c.vocab % 16) return false;
+  if (!mega_gemm_supported(64, x->QKVN, H) || !mega_gemm_supported(64, H, x->NQD) || !mega_gemm_supported(64, 2 * F, H) ||
+      !mega_gemm_supported(64, H, F) || !mega_gemm_supported(64, c.vocab, H))
+    return false;
+  auto fused = [&](const clover_layer_weights& l) {
+    const char* q = (const char*)l.wq;
+    return (const char*)l.wk == q + (size_t)x->NQD * H * 2 &&
+           (const char*)l.wv == q + (size_t)(x->NQD + c.n_kv_heads * c.head_dim) * H * 2 &&
+           (const char*)l.w_up == (const char*)l.w_gate + (size_t)F * H * 2;
+  };
+  for (const auto& l : x->layers) if (!fused(l)) return false;
+  for (const auto& l : x->aug) if (!fused(l)) return false;
+  return true;
+}
+
+struct MegaBuilder {
+  clover_ctx* x;
+  int M;
+  std::vector<MegaPhase> prog;
+  std::vector<int> cls;
+  MegaPhase blank() const {
+    static const int dbg = [] { const char* v = getenv("CLOVER_MEGA_DBG"); return v ? atoi(v) : 0; }();
+    MegaPhase p;
+    memset(&p, 0, sizeof(p));
+    p.M = M; p.H = x->H; p.eps = x->cfg.rms_eps; p.dbg = dbg;
+    return p;
+  }
+  void push(const MegaPhase& p, int c) { prog.push_back(p); cls.push_back(c); }
+  // returns the K-group count, 0 if the partial buffer is too small
+  int gemm(int c, Planes X, const void* W, int N, int K, int epi, float* Y, int ldy, Planes out) {
+    MegaPhase p = blank();
+    p.op = MG_OP_GEMM; p.N = N; p.K = K; p.epi = epi;
+    p.KG = mega_pick_kg(N, K, epi, x->mega_grid);
+    p.Xhi = X.hi; p.Xlo = X.lo; p.ldx = X.ld;
+    p.W = (const bf16_t*)W; p.w_bytes = (unsigned)((size_t)(epi == 1 ? 2 * N : N) * K * 2);
+    if (epi == 0) {
+      if ((size_t)p.KG * M * N * sizeof(float) > x->partial_bytes) return 0;
+      p.Y = x->partial; p.ldy = N; p.split_stride = (size_t)M * N;
+    } else if (epi == 2) {
+      p.Y = Y; p.ldy = ldy;
+    } else {
+      p.Yhi = out.hi; p.Ylo = out.lo; p.ldo = out.ld;
+    }
+    p.ss = x->d_ss;
+    push(p, c);
+    return p.KG;
+  }
+  // x (+)= partials of the last epi-0 GEMM; planes of x * gain
+  void reduce(float* xres, int KG, int N, const void* gain, Planes out, const int* tok, const void* table) {
+    MegaPhase p = blank();
+    p.op = MG_OP_REDUCE; p.KG = KG;
+    p.Y = x->partial; p.ldy = N; p.split_stride = (size_t)M * N;
+    p.x = xres; p.gain = (const bf16_t*)gain; p.ss_out = x->d_ss;
+    p.Yhi = out.hi; p.Ylo = out.lo; p.ldo = out.ld;
+    p.tok = tok; p.table = (const bf16_t*)table; p.vocab = x->cfg.vocab;
+    push(p, KC_RMSNORM);
+  }
+};
+
+// One decoder layer as phases.  On entry the planes of a_norm hold xres * attn_norm of this layer and d_ss
+// the sums of squares of xres; on exit they hold xres * next_gain.
+bool mega_layer(MegaBuilder& mb, const clover_layer_weights& lw, float* xres, RowMap rm, char* kc_layer, char* vc_layer,
+                const int* base_len, const unsigned long long* anc, const void* next_gain) {
+  clover_ctx* x = mb.x;
+  const clover_config& c = x->cfg;
+  const int H = x->H, d = c.head_dim, F = c.ffn;
+  Planes A = planes_of(x, x->a_norm, 2 * H);
+  A.ld = H;
+  Planes Q = planes_of(x, x->q_rot, x->NQD);
+  Planes O = planes_of(x, x->attn_out, x->NQD);
+  Planes Hf = planes_of(x, x->h_ffn, F);
+  const Planes none{nullptr, nullptr, 0};
+  const int kq = mb.gemm(KC_GEMM_QKV, A, lw.wq, x->QKVN, H, 0, nullptr, 0, none);
+  if (!kq) return false;
+  MegaPhase p = mb.blank();
+  p.op = MG_OP_ROPE; p.KG = kq;
+  p.Y = x->partial; p.ldy = x->QKVN; p.split_stride = (size_t)mb.M * x->QKVN;
+  p.ss = x->d_ss;
+  p.rm = rm; p.n_q = c.n_q_heads; p.n_kv = c.n_kv_heads; p.max_seq = c.max_seq; p.base_len = base_len; p.err_flag = x->d_err;
+  p.cos_t = x->cos_t; p.sin_t = x->sin_t; p.q_scale = 1.0f / sqrtf((float)d);
+  p.q_hi = Q.hi; p.q_lo = Q.lo; p.ldq = x->NQD;
+  p.k_hi = (bf16_t*)kc_layer; p.k_plane = x->k_layer_elems;
+  p.v_hi = (bf16_t*)vc_layer; p.v_plane = x->v_layer_elems;
+  p.anc = anc;
+  p.o_part = x->o_part; p.ml_part = x->ml_part; p.rows_total = x->max_rows;
+  {
+    const int G = c.n_q_heads / c.n_kv_heads;
+    const int ngw = std::max(1, 8 / G), node_groups = (rm.n + 31) / 32, chunks = (node_groups + ngw - 1) / ngw;
+    p.n_splits = std::max(1, std::min(x->attn_max_splits, x->mega_grid / std::max(1, rm.B * c.n_kv_heads * chunks)));
+  }
+  p.Yhi = O.hi; p.Ylo = O.lo; p.ldo = x->NQD;
+  mb.push(p, KC_ROPE_KV);
+  p.op = MG_OP_ATTN;
+  mb.push(p, KC_ATTN);
+  p.op = MG_OP_MERGE;
+  mb.push(p, KC_ELTWISE);
+  const int kw = mb.gemm(KC_GEMM_WO, O, lw.wo, H, x->NQD, 0, nullptr, 0, none);
+  if (!kw) return false;
+  mb.reduce(xres, kw, H, lw.ffn_norm, A, nullptr, nullptr);
+  mb.gemm(KC_GEMM_GATEUP, A, lw.w_gate, F, H, 1, nullptr, 0, Hf);
+  const int kd = mb.gemm(KC_GEMM_DOWN, Hf, lw.w_down, H, F, 0, nullptr, 0, none);
+  if (!kd) return false;
+  mb.reduce(xres, kd, H, next_gain, A, nullptr, nullptr);
+  return true;
+}
+
+// upload (if it changed) and run a program; one launch, or one launch per phase when profiling by phase
+int mega_run(clover_ctx* x, MegaBuilder& mb, const char* what) {
+  const int n = (int)mb.prog.size();
+  if (n > x->prog_cap) return fail(x, CLOVER_E_CAPACITY, "internal: phase program too long");
+  if (x->prog_host.size() != mb.prog.size() ||
+      memcmp(x->prog_host.data(), mb.prog.data(), mb.prog.size() * sizeof(MegaPhase)) != 0) {
+    // the previous program may still be running: the copy is stream-ordered behind it
+    hipError_t e = hipMemcpyAsync(x->d_prog, mb.prog.data(), mb.prog.size() * sizeof(MegaPhase), hipMemcpyHostToDevice, x->st);
+    if (e == hipSuccess) e = hipStreamSynchronize(x->st);  // pageable source: make sure it was consumed
+    if (e != hipSuccess) return fail(x, CLOVER_E_HIP, std::string(what) + ": program upload: " + hipGetErrorString(e));
+    x->prog_host = mb.prog;
+    x->prog_cls = mb.cls;
+  }
+  hipError_t e = hipSuccess;
+  if (x->mega_phases) {
+    for (int p = 0; p < n && e == hipSuccess; ++p) {
+      Scope sc(x, x->prog_cls[p]);
+      e = launch_mega(x->d_prog, p, p + 1, x->d_sync, x->mega_seq, x->mega_limit, x->d_err, nullptr, x->mega_grid, x->st);
+    }
+  } else {
+    Scope sc(x, KC_MEGA);
+    e = launch_mega(x->d_prog, 0, n, x->d_sync, x->mega_seq, x->mega_limit, x->d_err, x->prof ? x->d_stamps : nullptr,
+                    x->mega_grid, x->st);
+    x->mega_seq += (unsigned)(n - 1);
+  }
+  if (e != hipSuccess) return fail(x, CLOVER_E_HIP, std::string(what) + ": cooperative launch: " + hipGetErrorString(e));
+  return CLOVER_OK;
 }
 
 // planes of RMSNorm(src) * gain in the a_norm buffer (MFMA path)
@@ -708,6 +872,14 @@ int clover_init(const clover_config* cfg, const clover_weights* w, const clover_
     pack(x->w.fc0_w, H, H);
     for (int j = 1; j < cfg->draft_depths; ++j) pack(x->fc_w[j], H, 2 * H);
     if ((size_t)(cur - x->packed) > x->packed_bytes) { delete x; return fail(nullptr, CLOVER_E_CAPACITY, "internal: packed weights overflow"); }
+    hipMemsetAsync(x->d_sync, 0, sizeof(MegaSync), x->st);
+    x->mega_seq = 0;
+    x->mega_grid = ((cfg->flags & CLOVER_FLAG_MEGA) || getenv("CLOVER_MEGA")) ? mega_grid_size() : 0;
+    x->mega = x->mega_grid > 0 && mega_model_ok(x) && mega_barrier_timeout_ticks(&x->mega_limit) == 0;
+    x->mega_phases = getenv("CLOVER_MEGA_PHASES") != nullptr;
+    { int dev = 0, khz = 0;
+      if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && khz > 0)
+        x->wall_khz = khz; }
   }
   rc = upload_tree(x);
   if (rc == CLOVER_OK) rc = finish(x, "init");
@@ -730,6 +902,10 @@ int clover_reset(clover_ctx* x) {
   launch_fill_i32(x->d_seq_len, 0, x->cfg.max_batch, x->st);
   launch_fill_i32(x->d_aug_len, 0, x->cfg.max_batch, x->st);
   launch_fill_i32(x->d_err, 0, 1, x->st);
+  if (x->fast) {
+    hipMemsetAsync(x->d_sync, 0, sizeof(MegaSync), x->st);
+    x->mega_seq = 0;
+  }
   std::fill(x->len_ub.begin(), x->len_ub.end(), 0);
   std::fill(x->aug_ub.begin(), x->aug_ub.end(), 0);
   x->m_upper = x->cfg.max_nodes;
@@ -815,6 +991,30 @@ int verify_tree(clover_ctx* x, int32_t batch, const int32_t* tree_tokens, float*
   const int M = (B - 1) * R + t.n;
   int key_bound = 0;
   for (int b = 0; b < B; ++b) key_bound = std::max(key_bound, x->len_ub[b] + t.n);
+  if (x->mega && M <= 64) {
+    // the whole pass as one phase program: embedding, the layers, final norm scale + LM head
+    { Scope s(x, KC_ROPE_KV); launch_rope_table(x->d_seq_len, x->d_depth, c.rope_base, c.head_dim, x->cos_t, x->sin_t, rm, x->st); }
+    MegaBuilder mb{x, M};
+    Planes A = planes_of(x, x->a_norm, 2 * H);
+    A.ld = H;
+    mb.reduce(hidden, 0, H, x->layers[0].attn_norm, A, tree_tokens, x->w.embed);
+    mb.cls.back() = KC_EMBED;
+    bool ok = true;
+    for (int l = 0; l < c.n_layers && ok; ++l)
+      ok = mega_layer(mb, x->layers[l], hidden, rm, x->kc + (size_t)l * x->k_layer_elems * x->kv_esz,
+                      x->vc + (size_t)l * x->v_layer_elems * x->kv_esz, x->d_seq_len, x->d_anc,
+                      l + 1 < c.n_layers ? x->layers[l + 1].attn_norm : x->w.final_norm);
+    if (ok) {
+      mb.gemm(KC_GEMM_LMHEAD, A, x->lm_head_pk, c.vocab, H, 2, logits, c.vocab, Planes{nullptr, nullptr, 0});
+      {  // timing experiment only: phases that do nothing (cost of a bare barrier inside this kernel)
+        static const int n_empty = [] { const char* v = getenv("CLOVER_MEGA_EMPTY"); return v ? atoi(v) : 0; }();
+        for (int i = 0; i < n_empty && (int)mb.prog.size() < x->prog_cap; ++i) mb.push(mb.blank(), KC_DRAFT_MISC);
+      }
+      rc = mega_run(x, mb, "verify_tree");
+      if (rc) return rc;
+      return finish(x, "verify_tree");
+    }
+  }
   { Scope s(x, KC_EMBED); launch_embed(x->w.embed, c.dtype, tree_tokens, c.vocab, hidden, H, H, rm, x->st); }
   { Scope s(x, KC_ROPE_KV); launch_rope_table(x->d_seq_len, x->d_depth, c.rope_base, c.head_dim, x->cos_t, x->sin_t, rm, x->st); }
   if (x->fast) norm_planes(x, hidden, x->layers[0].attn_norm, M);
@@ -874,6 +1074,7 @@ int clover_seq_len(clover_ctx* x, int32_t* out_host) {
   if (e == hipSuccess) e = hipStreamSynchronize(x->st);
   if (e != hipSuccess) return fail(x, CLOVER_E_HIP, std::string("clover_seq_len: ") + hipGetErrorString(e));
   for (int b = 0; b < B; ++b) { x->len_ub[b] = out_host[b]; x->aug_ub[b] = aug[b]; }
+  if (err & 2) return fail(x, CLOVER_E_STATE, "a grid barrier of the persistent kernel timed out; results are invalid (clover_reset clears the state)");
   if (err) return fail(x, CLOVER_E_STATE, "a kernel refused to write past max_seq");
   return CLOVER_OK;
 }
@@ -917,6 +1118,28 @@ int clover_profile_collect(clover_ctx* x, double* ms, int64_t* launches, int32_t
     x->prof_pool.push_back(ev);
   }
   x->prof_events.clear();
+  return CLOVER_OK;
+}
+
+int clover_path_info(clover_ctx* x) {
+  if (!x) return CLOVER_E_NULL;
+  return (x->fast ? 1 : 0) | (x->attn_fast ? 2 : 0) | (x->mega ? 4 : 0);
+}
+
+int clover_profile_phases(clover_ctx* x, double* us_by_phase, int32_t* class_by_phase, int32_t max_phases, int32_t* n_out) {
+  if (!x || !us_by_phase || !class_by_phase || !n_out) return fail(x, CLOVER_E_NULL, "null argument");
+  const int n = (int)x->prog_host.size();
+  *n_out = n;
+  if (n == 0 || !x->mega) return CLOVER_OK;
+  if (max_phases < n) return fail(x, CLOVER_E_SHAPE, "max_phases too small");
+  std::vector<long long> t(n + 1);
+  hipError_t e = hipMemcpyAsync(t.data(), x->d_stamps, (n + 1) * sizeof(long long), hipMemcpyDeviceToHost, x->st);
+  if (e == hipSuccess) e = hipStreamSynchronize(x->st);
+  if (e != hipSuccess) return fail(x, CLOVER_E_HIP, std::string("clover_profile_phases: ") + hipGetErrorString(e));
+  for (int p = 0; p < n; ++p) {
+    us_by_phase[p] = (double)(t[p + 1] - t[p]) * 1e3 / (double)x->wall_khz;
+    class_by_phase[p] = x->prog_cls[p];
+  }
   return CLOVER_OK;
 }
 

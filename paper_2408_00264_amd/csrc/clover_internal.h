@@ -12,7 +12,7 @@ typedef unsigned short bf16_t;  // raw bfloat16 bit pattern
 
 enum KernelClass {
   KC_EMBED = 0, KC_RMSNORM, KC_GEMM_QKV, KC_ROPE_KV, KC_ATTN, KC_GEMM_WO, KC_GEMM_GATEUP, KC_GEMM_DOWN,
-  KC_GEMM_LMHEAD, KC_GEMM_DRAFT, KC_AD_GATE, KC_TOPK, KC_DRAFT_MISC, KC_ACCEPT, KC_COMPACT, KC_ELTWISE,
+  KC_GEMM_LMHEAD, KC_GEMM_DRAFT, KC_AD_GATE, KC_TOPK, KC_DRAFT_MISC, KC_ACCEPT, KC_COMPACT, KC_ELTWISE, KC_MEGA,
   KC_COUNT
 };
 
@@ -172,5 +172,46 @@ struct PanelGemm {
 };
 bool panel_gemm_supported(int M, int N, int K, int epi);
 void launch_gemm_panel(const PanelGemm& g, hipStream_t st);
+
+// ---- persistent phase-program kernel (M <= 64 rows, bf16 weights, head_dim 128) -------------------
+// One cooperative launch walks phases [p_begin, p_end) of a program with a grid-wide barrier between
+// them.  Every pointer is a device pointer; buffers written in one phase and read in a later one must
+// not be touched by anything else while the launch runs.
+enum MegaOp { MG_OP_GEMM = 1, MG_OP_REDUCE, MG_OP_ROPE, MG_OP_ATTN, MG_OP_MERGE };
+struct MegaSync {
+  unsigned xcount[8 * 64];  // arrivals per XCD group (workgroup % 8), one counter per 256 bytes
+  unsigned top;             // XCD groups that have completed a barrier
+  unsigned abort;           // sticky: a barrier timed out
+  unsigned pad[62];
+};
+struct MegaPhase {
+  int op, M;                                   // M: rows b*R + i of the row map, <= 64
+  // GEMM: out = X[M,K] * W[N,K]^T
+  int N, K, KG, epi;                           // KG K-groups (1, 2, 4, 8); epi 0: fp32 partial per K-group,
+                                               // 1: SwiGLU planes (N = F; W = gate rows, then up rows), 2: fp32 out
+  const bf16_t *Xhi, *Xlo; int ldx;            // activation planes
+  const bf16_t* W; unsigned w_bytes;           // fragment-major weights
+  float* Y; int ldy; size_t split_stride;      // GEMM out (epi 0: K-group g at Y + g*split_stride); partials in for REDUCE / ROPE
+  bf16_t *Yhi, *Ylo; int ldo;                  // planes out (GEMM epi 1, REDUCE, MERGE)
+  const float* ss; int H; float eps;           // [row][4] sums of squares of the row the input planes came from:
+                                               // epi 1 / 2 and ROPE scale by rsqrt(sum / H + eps) (the RMSNorm scale)
+  // REDUCE: x[g,:] = (tok ? table[tok[g]] : x[g,:]) + sum of KG partials; planes of x*gain; ss_out
+  float* x; const bf16_t* gain; float* ss_out; const int* tok; const bf16_t* table; int vocab;
+  // ROPE / ATTN / MERGE
+  RowMap rm; int n_q, n_kv, max_seq; const int* base_len; int* err_flag;
+  const float *cos_t, *sin_t; float q_scale;
+  bf16_t *q_hi, *q_lo; int ldq;
+  bf16_t* k_hi; size_t k_plane; bf16_t* v_hi; size_t v_plane;   // caches of this layer (lo plane = hi + plane)
+  const unsigned long long* anc;
+  float *o_part, *ml_part; int rows_total, n_splits;
+  int dbg;                                     // timing experiments only (CLOVER_MEGA_DBG), 0 in normal use
+};
+int mega_grid_size();   // workgroups of a launch on the current device; 0: cooperative launch not available
+int mega_barrier_timeout_ticks(long long* out);
+int mega_pick_kg(int N, int K, int epi, int grid);
+bool mega_gemm_supported(int M, int N, int K);
+// stamps: null, or dev [n_phases + 1] wall-clock ticks (phase starts as seen by workgroup 0, then the end)
+hipError_t launch_mega(const MegaPhase* prog_dev, int p_begin, int p_end, MegaSync* sync, unsigned seq_base,
+                       long long limit_ticks, int* err_flag, long long* stamps, int grid, hipStream_t st);
 
 }  // namespace clv

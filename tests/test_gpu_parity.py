@@ -116,11 +116,13 @@ def test_config1_gain_jitter_injected_accept_lengths():
     assert max(got) == 4 and min(got) == 1
 
 
-@pytest.mark.parametrize("flags", [clover.FLAG_GENERIC, 0], ids=["generic", "mfma"])
+@pytest.mark.parametrize("flags", [clover.FLAG_GENERIC, 0, clover.FLAG_MEGA], ids=["generic", "mfma_kernels", "mfma_persistent"])
 def test_mini_bf16(flags):
     _torch()
     from tests.parity import truth_hook_factory
     ls = _lockstep(MINI, flags=flags, gain_jitter=0.1, max_seq=512)
+    # the three variants must really run three different sets of kernels
+    assert ls.gpu.path_info() == {clover.FLAG_GENERIC: 0, 0: 3, clover.FLAG_MEGA: 7}[flags]
     prompts = [synth.make_prompts(MINI, seed=3)[0][:150]]
     say(f"mini bf16 flags={flags}: prefill 150 tokens in chunks of 24")
     ls.prefill(prompts, chunk=24)
@@ -246,6 +248,7 @@ def test_config3_full_size_step():
     shape = synth.CONFIGS[3]
     say("config 3 full size: generating weights, prefilling 1024 tokens on both sides")
     ls = _lockstep(shape, max_seq=1024 + 3 * 64 + 64)
+    assert ls.gpu.path_info() & 3 == 3   # MFMA GEMMs and MFMA attention, as bench.py runs it
     ls.ocfg.dtype = np.float32
     ls.W = __import__("oracle.clover2_oracle", fromlist=["x"]).Weights(ls.store.get_f32, np.float32)
     ls.seqs = [__import__("oracle.clover2_oracle", fromlist=["x"]).SeqState(ls.ocfg)]
