@@ -201,7 +201,8 @@ const char *clover_kernel_class_name(int32_t cls);
 
 /* Which kernels this context runs: bit 0 = MFMA path (bf16 model), bit 1 = MFMA tree attention,
  * bit 2 = persistent phase-program kernel for passes of at most 64 rows (one cooperative launch per
- * verify_tree instead of one kernel per operation).  Negative: error code. */
+ * verify_tree instead of one kernel per operation), bit 3 = that kernel shards heads and FFN columns over
+ * the XCDs (head and FFN counts divide by 8).  Negative: error code. */
 int clover_path_info(clover_ctx *ctx);
 
 /* Message of the last error on this context ("" if none); valid until the next call. */

@@ -81,7 +81,11 @@ struct clover_ctx {
   bool mega_phases = false;  // debugging / profiling: one launch per phase
   int mega_grid = 0;
   long long mega_limit = 0;
-  unsigned mega_seq = 0;   // barriers executed since the counters were zeroed
+  bool mega_shard = false;   // head groups and FFN slices divide by the 8 XCDs: XCD-local chains
+  unsigned mega_seq = 0;   // grid barriers executed since the counters were zeroed
+  unsigned mega_lseq = 0;  // XCD-local barriers executed since then
+  float* d_lbuf;           // 8 per-XCD scratch regions (QKV partials, attention partials)
+  size_t lbuf_stride;      // floats per region
   MegaSync* d_sync;
   MegaPhase* d_prog;
   int prog_cap;
@@ -305,10 +309,20 @@ void carve(clover_ctx* x, char* base, size_t* total) {
   x->partial = (float*)cv.take<char>(pbytes);
   x->pl_y = cv.take<float>((size_t)rows * 2 * H);
   x->d_sync = cv.take<MegaSync>(1);
-  x->prog_cap = 2 + 9 * std::max(c.n_layers, c.aug_layers) + 64;
+  x->prog_cap = 2 + 9 * std::max(c.n_layers, c.aug_layers);
   x->d_prog = cv.take<MegaPhase>(x->prog_cap);
   x->d_ss = cv.take<float>((size_t)std::max(rows, 64) * 4);
   x->d_stamps = cv.take<long long>(x->prog_cap + 1);
+  {
+    // per-XCD scratch of the sharded persistent kernel: QKV partials [<= 8 K groups][64 rows][its columns], then
+    // the attention partial outputs and (max, sum) pairs of its query heads
+    const int r64 = std::min(rows, 64);
+    const size_t nq8 = (size_t)(c.n_q_heads + 7) / 8, nkv8 = (size_t)(c.n_kv_heads + 7) / 8;
+    const size_t qkv = (size_t)8 * r64 * (nq8 + 2 * nkv8) * d;
+    const size_t op = (size_t)16 * rows * nq8 * d, ml = (size_t)16 * rows * nq8 * 2;
+    x->lbuf_stride = (qkv + op + ml + 3 * 64 + 63) / 64 * 64;
+    x->d_lbuf = cv.take<float>(fast ? 8 * x->lbuf_stride : 64);
+  }
   *total = cv.off;
 }
 
@@ -539,21 +553,34 @@ struct MegaBuilder {
   int M;
   std::vector<MegaPhase> prog;
   std::vector<int> cls;
+  int n_global = 0, n_local = 0;  // barriers so far, by kind
   MegaPhase blank() const {
     static const int dbg = [] { const char* v = getenv("CLOVER_MEGA_DBG"); return v ? atoi(v) : 0; }();
     MegaPhase p;
     memset(&p, 0, sizeof(p));
     p.M = M; p.H = x->H; p.eps = x->cfg.rms_eps; p.dbg = dbg;
+    p.wt = 1;
     return p;
   }
-  void push(const MegaPhase& p, int c) { prog.push_back(p); cls.push_back(c); }
-  // returns the K-group count, 0 if the partial buffer is too small
-  int gemm(int c, Planes X, const void* W, int N, int K, int epi, float* Y, int ldy, Planes out) {
+  // `local`: the barrier in front of the phase is XCD-local (all its inputs were produced on the same XCD)
+  void push(MegaPhase p, int c, bool local = false) {
+    p.sync = local ? 1 : 0;
+    if (!prog.empty()) p.bar_ord = local ? ++n_local : ++n_global;
+    prog.push_back(p);
+    cls.push_back(c);
+  }
+  MegaPhase gemm_desc(Planes X, const void* W, int N, int K, int epi) const {
     MegaPhase p = blank();
-    p.op = MG_OP_GEMM; p.N = N; p.K = K; p.epi = epi;
-    p.KG = mega_pick_kg(N, K, epi, x->mega_grid);
+    p.op = MG_OP_GEMM; p.N = N; p.K = K; p.epi = epi; p.KG = 1;
     p.Xhi = X.hi; p.Xlo = X.lo; p.ldx = X.ld;
     p.W = (const bf16_t*)W; p.w_bytes = (unsigned)((size_t)(epi == 1 ? 2 * N : N) * K * 2);
+    p.ss = x->d_ss;
+    return p;
+  }
+  // unsharded GEMM; returns the K-group count, 0 if the partial buffer is too small
+  int gemm(int c, Planes X, const void* W, int N, int K, int epi, float* Y, int ldy, Planes out) {
+    MegaPhase p = gemm_desc(X, W, N, K, epi);
+    p.KG = mega_pick_kg(N, K, epi, x->mega_grid);
     if (epi == 0) {
       if ((size_t)p.KG * M * N * sizeof(float) > x->partial_bytes) return 0;
       p.Y = x->partial; p.ldy = N; p.split_stride = (size_t)M * N;
@@ -562,11 +589,10 @@ struct MegaBuilder {
     } else {
       p.Yhi = out.hi; p.Ylo = out.lo; p.ldo = out.ld;
     }
-    p.ss = x->d_ss;
     push(p, c);
     return p.KG;
   }
-  // x (+)= partials of the last epi-0 GEMM; planes of x * gain
+  // x (+)= KG partials [k][M][N] in the shared partial buffer; planes of x * gain
   void reduce(float* xres, int KG, int N, const void* gain, Planes out, const int* tok, const void* table) {
     MegaPhase p = blank();
     p.op = MG_OP_REDUCE; p.KG = KG;
@@ -578,24 +604,55 @@ struct MegaBuilder {
   }
 };
 
+// boundaries that split n_stages 256-column stages over the 8 XCDs as evenly as whole stages allow
+void stage_bounds(int n_stages, int (&b)[9]) {
+  for (int i = 0; i <= 8; ++i) b[i] = (int)((long long)i * n_stages / 8);
+}
+
 // One decoder layer as phases.  On entry the planes of a_norm hold xres * attn_norm of this layer and d_ss
 // the sums of squares of xres; on exit they hold xres * next_gain.
 bool mega_layer(MegaBuilder& mb, const clover_layer_weights& lw, float* xres, RowMap rm, char* kc_layer, char* vc_layer,
                 const int* base_len, const unsigned long long* anc, const void* next_gain) {
   clover_ctx* x = mb.x;
   const clover_config& c = x->cfg;
-  const int H = x->H, d = c.head_dim, F = c.ffn;
+  const int H = x->H, d = c.head_dim, F = c.ffn, M = mb.M;
+  const bool sh = x->mega_shard;
   Planes A = planes_of(x, x->a_norm, 2 * H);
   A.ld = H;
   Planes Q = planes_of(x, x->q_rot, x->NQD);
   Planes O = planes_of(x, x->attn_out, x->NQD);
   Planes Hf = planes_of(x, x->h_ffn, F);
   const Planes none{nullptr, nullptr, 0};
-  const int kq = mb.gemm(KC_GEMM_QKV, A, lw.wq, x->QKVN, H, 0, nullptr, 0, none);
-  if (!kq) return false;
+  const int nq8 = c.n_q_heads / 8, nkv8 = c.n_kv_heads / 8, nw = x->mega_grid / 8;
+  const int G = c.n_q_heads / c.n_kv_heads;
+  const int ngw = std::max(1, 8 / G), node_groups = (rm.n + 31) / 32, chunks = (node_groups + ngw - 1) / ngw;
+
+  // ---- QKV projection ----
+  int kq, ldq_part;
+  size_t sps_q;
+  if (sh) {
+    MegaPhase p = mb.gemm_desc(A, lw.wq, x->QKVN, H, 0);
+    p.shard = 1; p.wt = 0;
+    const int lb = (nq8 + 2 * nkv8) * 8;  // 16-column blocks per XCD
+    int kgl = 8;
+    while (kgl > 1 && (kgl > H / 256 || (long long)lb * kgl > (long long)8 * nw || nw % kgl)) kgl >>= 1;
+    p.KG = kgl;
+    p.seg_base[0] = 0; p.seg_base[1] = x->NQD / 16; p.seg_base[2] = (x->NQD + c.n_kv_heads * d) / 16;
+    for (int i = 0; i <= 8; ++i) { p.seg_bnd[0][i] = i * nq8 * 8; p.seg_bnd[1][i] = p.seg_bnd[2][i] = i * nkv8 * 8; }
+    p.ldy = lb * 16; p.split_stride = (size_t)M * p.ldy;
+    p.lbuf = x->d_lbuf; p.lbuf_stride = x->lbuf_stride;
+    mb.push(p, KC_GEMM_QKV);
+    kq = kgl; ldq_part = p.ldy; sps_q = p.split_stride;
+  } else {
+    kq = mb.gemm(KC_GEMM_QKV, A, lw.wq, x->QKVN, H, 0, nullptr, 0, none);
+    if (!kq) return false;
+    ldq_part = x->QKVN; sps_q = (size_t)M * x->QKVN;
+  }
+
+  // ---- RoPE + KV write, attention, merge ----
   MegaPhase p = mb.blank();
   p.op = MG_OP_ROPE; p.KG = kq;
-  p.Y = x->partial; p.ldy = x->QKVN; p.split_stride = (size_t)mb.M * x->QKVN;
+  p.Y = x->partial; p.ldy = ldq_part; p.split_stride = sps_q;
   p.ss = x->d_ss;
   p.rm = rm; p.n_q = c.n_q_heads; p.n_kv = c.n_kv_heads; p.max_seq = c.max_seq; p.base_len = base_len; p.err_flag = x->d_err;
   p.cos_t = x->cos_t; p.sin_t = x->sin_t; p.q_scale = 1.0f / sqrtf((float)d);
@@ -604,24 +661,59 @@ bool mega_layer(MegaBuilder& mb, const clover_layer_weights& lw, float* xres, Ro
   p.v_hi = (bf16_t*)vc_layer; p.v_plane = x->v_layer_elems;
   p.anc = anc;
   p.o_part = x->o_part; p.ml_part = x->ml_part; p.rows_total = x->max_rows;
-  {
-    const int G = c.n_q_heads / c.n_kv_heads;
-    const int ngw = std::max(1, 8 / G), node_groups = (rm.n + 31) / 32, chunks = (node_groups + ngw - 1) / ngw;
+  p.Yhi = O.hi; p.Ylo = O.lo; p.ldo = x->NQD;
+  if (sh) {
+    p.shard = 1; p.wt = 0;
+    p.lbuf = x->d_lbuf; p.lbuf_stride = x->lbuf_stride;
+    const size_t qkv_floats = ((size_t)8 * std::min(x->max_rows, 64) * (nq8 + 2 * nkv8) * d + 63) / 64 * 64;
+    p.lo_off = qkv_floats;
+    p.lml_off = qkv_floats + ((size_t)16 * x->max_rows * nq8 * d + 63) / 64 * 64;
+    p.n_splits = std::max(1, std::min(16, nw / std::max(1, rm.B * nkv8 * chunks)));
+  } else {
     p.n_splits = std::max(1, std::min(x->attn_max_splits, x->mega_grid / std::max(1, rm.B * c.n_kv_heads * chunks)));
   }
-  p.Yhi = O.hi; p.Ylo = O.lo; p.ldo = x->NQD;
-  mb.push(p, KC_ROPE_KV);
+  mb.push(p, KC_ROPE_KV, sh);
   p.op = MG_OP_ATTN;
-  mb.push(p, KC_ATTN);
+  mb.push(p, KC_ATTN, sh);
   p.op = MG_OP_MERGE;
-  mb.push(p, KC_ELTWISE);
-  const int kw = mb.gemm(KC_GEMM_WO, O, lw.wo, H, x->NQD, 0, nullptr, 0, none);
-  if (!kw) return false;
-  mb.reduce(xres, kw, H, lw.ffn_norm, A, nullptr, nullptr);
-  mb.gemm(KC_GEMM_GATEUP, A, lw.w_gate, F, H, 1, nullptr, 0, Hf);
-  const int kd = mb.gemm(KC_GEMM_DOWN, Hf, lw.w_down, H, F, 0, nullptr, 0, none);
-  if (!kd) return false;
-  mb.reduce(xres, kd, H, next_gain, A, nullptr, nullptr);
+  mb.push(p, KC_ELTWISE, sh);
+
+  // ---- output projection, residual ----
+  if (sh) {
+    MegaPhase g = mb.gemm_desc(O, lw.wo, H, x->NQD, 0);
+    g.shard = 2; g.wt = 1; g.KG = 8;
+    stage_bounds(x->NQD / 256, g.ks_bnd);
+    g.Y = x->partial; g.ldy = H; g.split_stride = (size_t)M * H;
+    mb.push(g, KC_GEMM_WO, true);
+    mb.reduce(xres, 8, H, lw.ffn_norm, A, nullptr, nullptr);
+  } else {
+    const int kw = mb.gemm(KC_GEMM_WO, O, lw.wo, H, x->NQD, 0, nullptr, 0, none);
+    if (!kw) return false;
+    mb.reduce(xres, kw, H, lw.ffn_norm, A, nullptr, nullptr);
+  }
+
+  // ---- FFN ----
+  if (sh) {
+    MegaPhase g = mb.gemm_desc(A, lw.w_gate, F, H, 1);
+    g.shard = 1; g.wt = 0; g.KG = 1;
+    int fb[9];
+    stage_bounds(F / 256, fb);
+    for (int i = 0; i <= 8; ++i) g.seg_bnd[0][i] = fb[i] * 16;
+    g.Yhi = Hf.hi; g.Ylo = Hf.lo; g.ldo = F;
+    g.lbuf = x->d_lbuf; g.lbuf_stride = x->lbuf_stride;
+    mb.push(g, KC_GEMM_GATEUP);
+    MegaPhase dn = mb.gemm_desc(Hf, lw.w_down, H, F, 0);
+    dn.shard = 2; dn.wt = 1; dn.KG = 8;
+    for (int i = 0; i <= 8; ++i) dn.ks_bnd[i] = fb[i];
+    dn.Y = x->partial; dn.ldy = H; dn.split_stride = (size_t)M * H;
+    mb.push(dn, KC_GEMM_DOWN, true);
+    mb.reduce(xres, 8, H, next_gain, A, nullptr, nullptr);
+  } else {
+    mb.gemm(KC_GEMM_GATEUP, A, lw.w_gate, F, H, 1, nullptr, 0, Hf);
+    const int kd = mb.gemm(KC_GEMM_DOWN, Hf, lw.w_down, H, F, 0, nullptr, 0, none);
+    if (!kd) return false;
+    mb.reduce(xres, kd, H, next_gain, A, nullptr, nullptr);
+  }
   return true;
 }
 
@@ -642,13 +734,15 @@ int mega_run(clover_ctx* x, MegaBuilder& mb, const char* what) {
   if (x->mega_phases) {
     for (int p = 0; p < n && e == hipSuccess; ++p) {
       Scope sc(x, x->prog_cls[p]);
-      e = launch_mega(x->d_prog, p, p + 1, x->d_sync, x->mega_seq, x->mega_limit, x->d_err, nullptr, x->mega_grid, x->st);
+      e = launch_mega(x->d_prog, p, p + 1, x->d_sync, x->mega_seq, x->mega_lseq, x->mega_limit, x->d_err, nullptr, 0,
+                      x->mega_grid, x->st);
     }
   } else {
     Scope sc(x, KC_MEGA);
-    e = launch_mega(x->d_prog, 0, n, x->d_sync, x->mega_seq, x->mega_limit, x->d_err, x->prof ? x->d_stamps : nullptr,
-                    x->mega_grid, x->st);
-    x->mega_seq += (unsigned)(n - 1);
+    e = launch_mega(x->d_prog, 0, n, x->d_sync, x->mega_seq, x->mega_lseq, x->mega_limit, x->d_err,
+                    x->prof ? x->d_stamps : nullptr, mb.n_global > 0 ? 1 : 0, x->mega_grid, x->st);
+    x->mega_seq += (unsigned)mb.n_global;
+    x->mega_lseq += (unsigned)mb.n_local;
   }
   if (e != hipSuccess) return fail(x, CLOVER_E_HIP, std::string(what) + ": cooperative launch: " + hipGetErrorString(e));
   return CLOVER_OK;
@@ -877,6 +971,10 @@ int clover_init(const clover_config* cfg, const clover_weights* w, const clover_
     x->mega_grid = ((cfg->flags & CLOVER_FLAG_MEGA) || getenv("CLOVER_MEGA")) ? mega_grid_size() : 0;
     x->mega = x->mega_grid > 0 && mega_model_ok(x) && mega_barrier_timeout_ticks(&x->mega_limit) == 0;
     x->mega_phases = getenv("CLOVER_MEGA_PHASES") != nullptr;
+    x->mega_lseq = 0;
+    // XCD sharding: head groups, their attention-output columns and the FFN stages must divide by the 8 XCDs
+    x->mega_shard = x->mega && !getenv("CLOVER_MEGA_NOSHARD") && cfg->n_q_heads % 8 == 0 && cfg->n_kv_heads % 8 == 0 &&
+                    (x->NQD / 8) % 256 == 0 && cfg->ffn / 256 >= 8 && x->mega_grid % 8 == 0 && x->mega_grid >= 64;
     { int dev = 0, khz = 0;
       if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && khz > 0)
         x->wall_khz = khz; }
@@ -905,6 +1003,7 @@ int clover_reset(clover_ctx* x) {
   if (x->fast) {
     hipMemsetAsync(x->d_sync, 0, sizeof(MegaSync), x->st);
     x->mega_seq = 0;
+    x->mega_lseq = 0;
   }
   std::fill(x->len_ub.begin(), x->len_ub.end(), 0);
   std::fill(x->aug_ub.begin(), x->aug_ub.end(), 0);
@@ -1006,10 +1105,6 @@ int verify_tree(clover_ctx* x, int32_t batch, const int32_t* tree_tokens, float*
                       l + 1 < c.n_layers ? x->layers[l + 1].attn_norm : x->w.final_norm);
     if (ok) {
       mb.gemm(KC_GEMM_LMHEAD, A, x->lm_head_pk, c.vocab, H, 2, logits, c.vocab, Planes{nullptr, nullptr, 0});
-      {  // timing experiment only: phases that do nothing (cost of a bare barrier inside this kernel)
-        static const int n_empty = [] { const char* v = getenv("CLOVER_MEGA_EMPTY"); return v ? atoi(v) : 0; }();
-        for (int i = 0; i < n_empty && (int)mb.prog.size() < x->prog_cap; ++i) mb.push(mb.blank(), KC_DRAFT_MISC);
-      }
       rc = mega_run(x, mb, "verify_tree");
       if (rc) return rc;
       return finish(x, "verify_tree");
@@ -1074,7 +1169,8 @@ int clover_seq_len(clover_ctx* x, int32_t* out_host) {
   if (e == hipSuccess) e = hipStreamSynchronize(x->st);
   if (e != hipSuccess) return fail(x, CLOVER_E_HIP, std::string("clover_seq_len: ") + hipGetErrorString(e));
   for (int b = 0; b < B; ++b) { x->len_ub[b] = out_host[b]; x->aug_ub[b] = aug[b]; }
-  if (err & 2) return fail(x, CLOVER_E_STATE, "a grid barrier of the persistent kernel timed out; results are invalid (clover_reset clears the state)");
+  if (err & 2) return fail(x, CLOVER_E_STATE, "a barrier of the persistent kernel timed out; results are invalid (clover_reset clears the state)");
+  if (err & 4) return fail(x, CLOVER_E_STATE, "workgroups i and i + 8 of the persistent kernel did not share an XCD; sharded results are invalid");
   if (err) return fail(x, CLOVER_E_STATE, "a kernel refused to write past max_seq");
   return CLOVER_OK;
 }
@@ -1123,7 +1219,7 @@ int clover_profile_collect(clover_ctx* x, double* ms, int64_t* launches, int32_t
 
 int clover_path_info(clover_ctx* x) {
   if (!x) return CLOVER_E_NULL;
-  return (x->fast ? 1 : 0) | (x->attn_fast ? 2 : 0) | (x->mega ? 4 : 0);
+  return (x->fast ? 1 : 0) | (x->attn_fast ? 2 : 0) | (x->mega ? 4 : 0) | (x->mega_shard ? 8 : 0);
 }
 
 int clover_profile_phases(clover_ctx* x, double* us_by_phase, int32_t* class_by_phase, int32_t max_phases, int32_t* n_out) {

@@ -174,27 +174,47 @@ bool panel_gemm_supported(int M, int N, int K, int epi);
 void launch_gemm_panel(const PanelGemm& g, hipStream_t st);
 
 // ---- persistent phase-program kernel (M <= 64 rows, bf16 weights, head_dim 128) -------------------
-// One cooperative launch walks phases [p_begin, p_end) of a program with a grid-wide barrier between
-// them.  Every pointer is a device pointer; buffers written in one phase and read in a later one must
-// not be touched by anything else while the launch runs.
+// One cooperative launch walks phases [p_begin, p_end) of a program with a barrier before each phase
+// after the first.  Every pointer is a device pointer; buffers written in one phase and read in a later
+// one must not be touched by anything else while the launch runs.
+//
+// XCD sharding (shard != 0).  Workgroups with the same index modulo 8 run on the same XCD and share its
+// L2.  When the head and FFN counts divide by 8, XCD x owns head group x and FFN slice x for the whole
+// layer: QKV columns -> RoPE -> attention -> merge -> its K slice of the output projection, and gate/up
+// columns -> SwiGLU -> its K slice of the down projection.  Inside such a chain data passes through the
+// XCD's own L2 (plain stores, an L1 invalidate, an XCD-local barrier of ~1 us); only the two residual
+// sums per layer cross XCDs (write-through stores, L2 invalidate, grid barrier of ~4 us).
 enum MegaOp { MG_OP_GEMM = 1, MG_OP_REDUCE, MG_OP_ROPE, MG_OP_ATTN, MG_OP_MERGE };
 struct MegaSync {
-  unsigned xcount[8 * 64];  // arrivals per XCD group (workgroup % 8), one counter per 256 bytes
-  unsigned top;             // XCD groups that have completed a barrier
+  unsigned xcount[8 * 64];  // grid barrier: arrivals per XCD group (workgroup % 8), one counter per 256 bytes
+  unsigned lcount[8 * 64];  // XCD-local barriers: arrivals per XCD group
+  unsigned top;             // grid barrier: XCD groups that have completed it
   unsigned abort;           // sticky: a barrier timed out
-  unsigned pad[62];
+  unsigned off_tag;         // (launch tag << 3) | (XCC id - workgroup index) mod 8 of workgroup 0: must hold for every workgroup
+  unsigned pad[61];
 };
 struct MegaPhase {
   int op, M;                                   // M: rows b*R + i of the row map, <= 64
+  int sync;                                    // barrier before this phase: 0 grid-wide, 1 XCD-local
+  int bar_ord;                                 // 1-based ordinal of that barrier among the program's barriers of its kind
+  int wt;                                      // 1: outputs are written through (read on other XCDs), 0: plain stores
+  int shard;                                   // 0: work spread over all workgroups; GEMM 1: column-sharded, 2: K-sharded;
+                                               // ROPE / ATTN / MERGE 1: XCD x handles head group x
   // GEMM: out = X[M,K] * W[N,K]^T
-  int N, K, KG, epi;                           // KG K-groups (1, 2, 4, 8); epi 0: fp32 partial per K-group,
-                                               // 1: SwiGLU planes (N = F; W = gate rows, then up rows), 2: fp32 out
+  int N, K, KG, epi;                           // KG K-groups (shard 0: 1, 2, 4, 8 over the XCDs; shard 1: local groups);
+                                               // epi 0: fp32 partial per K-group, 1: SwiGLU planes (N = F; W = gate rows,
+                                               // then up rows), 2: fp32 out
   const bf16_t *Xhi, *Xlo; int ldx;            // activation planes
   const bf16_t* W; unsigned w_bytes;           // fragment-major weights
   float* Y; int ldy; size_t split_stride;      // GEMM out (epi 0: K-group g at Y + g*split_stride); partials in for REDUCE / ROPE
   bf16_t *Yhi, *Ylo; int ldo;                  // planes out (GEMM epi 1, REDUCE, MERGE)
   const float* ss; int H; float eps;           // [row][4] sums of squares of the row the input planes came from:
                                                // epi 1 / 2 and ROPE scale by rsqrt(sum / H + eps) (the RMSNorm scale)
+  int seg_base[3], seg_bnd[3][9];              // shard 1: XCD x owns the 16-column blocks seg_base[s] + [seg_bnd[s][x], seg_bnd[s][x+1])
+  int ks_bnd[9];                               // shard 2: XCD x owns the 256-column K stages [ks_bnd[x], ks_bnd[x+1])
+  float* lbuf; size_t lbuf_stride;             // shard 1: XCD x's private scratch = lbuf + x*lbuf_stride (floats): QKV partials
+                                               // [KG][M][ldy] with LOCAL column indices, then the attention partials
+  size_t lo_off, lml_off;                      // float offsets of the attention partial outputs / (max, sum) pairs in it
   // REDUCE: x[g,:] = (tok ? table[tok[g]] : x[g,:]) + sum of KG partials; planes of x*gain; ss_out
   float* x; const bf16_t* gain; float* ss_out; const int* tok; const bf16_t* table; int vocab;
   // ROPE / ATTN / MERGE
@@ -203,7 +223,7 @@ struct MegaPhase {
   bf16_t *q_hi, *q_lo; int ldq;
   bf16_t* k_hi; size_t k_plane; bf16_t* v_hi; size_t v_plane;   // caches of this layer (lo plane = hi + plane)
   const unsigned long long* anc;
-  float *o_part, *ml_part; int rows_total, n_splits;
+  float *o_part, *ml_part; int rows_total, n_splits;            // shard 0 partial outputs; n_splits in both modes
   int dbg;                                     // timing experiments only (CLOVER_MEGA_DBG), 0 in normal use
 };
 int mega_grid_size();   // workgroups of a launch on the current device; 0: cooperative launch not available
@@ -211,7 +231,10 @@ int mega_barrier_timeout_ticks(long long* out);
 int mega_pick_kg(int N, int K, int epi, int grid);
 bool mega_gemm_supported(int M, int N, int K);
 // stamps: null, or dev [n_phases + 1] wall-clock ticks (phase starts as seen by workgroup 0, then the end)
-hipError_t launch_mega(const MegaPhase* prog_dev, int p_begin, int p_end, MegaSync* sync, unsigned seq_base,
-                       long long limit_ticks, int* err_flag, long long* stamps, int grid, hipStream_t st);
+// gseq_base / lseq_base: grid-wide / XCD-local barriers executed since the counters were zeroed
+// check_xcd: compare every workgroup's XCD placement with workgroup 0's at the end (needs a grid barrier in the range)
+hipError_t launch_mega(const MegaPhase* prog_dev, int p_begin, int p_end, MegaSync* sync, unsigned gseq_base,
+                       unsigned lseq_base, long long limit_ticks, int* err_flag, long long* stamps, int check_xcd,
+                       int grid, hipStream_t st);
 
 }  // namespace clv

@@ -6,18 +6,24 @@
 // boundary costs ~4.5 us of drain, cache write-back and dispatch during which no weight bytes move.
 // Inside one kernel a barrier costs ~2.5 us and, more important, does not stop the memory pipeline.
 //
-// Coherence without cache flushes.  The eight XCDs have private L2 caches, so data a workgroup
-// writes for the next phase must not stay dirty in its L2, and a reader must not hit a stale line:
-//   * every store whose value another workgroup reads later in the same launch is a write-through
-//     store at agent scope (buffer_store ... sc1);
-//   * the barrier is relaxed agent-scope atomics on per-XCD counters plus one top counter; the
-//     workgroup-scope release before it waits for the write-through stores to be acknowledged;
-//   * after the barrier one thread per workgroup executes an agent-scope acquire fence
-//     (buffer_inv sc1), so the plain loads of the next phase miss in L1/L2 and may then be cached
-//     again, which is what lets the 32 workgroups of an XCD share one activation slice.
-// No L2 write-back (buffer_wbl2) is ever needed: nothing dirty is left behind.
+// Coherence without cache flushes.  The eight XCDs have private L2 caches.
+//   * Data another XCD reads later in the launch is stored write-through at agent scope
+//     (buffer_store ... sc1); before reading it, after the grid barrier, one thread per workgroup executes
+//     an agent-scope acquire (buffer_inv sc1), so plain loads miss in L1/L2 and may then be cached again --
+//     which is what lets the 32 workgroups of an XCD share one activation slice.  No L2 write-back
+//     (buffer_wbl2) is ever needed: nothing another XCD reads is left dirty.
+//   * Data only workgroups of the SAME XCD read (sharded phases) is stored plainly into that XCD's L2; an
+//     XCD-local barrier (one counter per XCD) and an L1 invalidate (buffer_inv sc0) are enough.  Such
+//     buffers are private to one XCD for the whole launch, cache line by cache line, so no other L2 ever
+//     holds a copy that could be written back over them.
+//   * Barriers are relaxed agent-scope atomics; the workgroup-scope release in front waits for the
+//     stores to be acknowledged.  Grid barrier: per-XCD counters plus one top counter (~4 us); XCD-local
+//     barrier: the per-XCD counter alone (~1 us).
+// Workgroups i and i + 8 share an XCD because the dispatcher hands consecutive workgroups to consecutive
+// XCDs; every launch checks this against the hardware's XCC id register and raises the error flag if it
+// does not hold (sharded results would then be invalid).
 //
-// The barrier's spin is bounded (wall clock); on expiry a sticky abort flag makes every later
+// The spin of every barrier is bounded (wall clock); on expiry a sticky abort flag makes every later
 // barrier and launch return at once, and the error flag word reports it to the host.
 #include "clover_internal.h"
 
@@ -68,124 +74,186 @@ __device__ __forceinline__ void split2(float a, float b, unsigned& hi, unsigned&
   hi = ha | (hb << 16);
   lo = rn_bf16(a - bf16_f32(ha)) | (rn_bf16(b - bf16_f32(hb)) << 16);
 }
-// Write-through stores (the value is read by other workgroups after the next barrier).  The buffer
-// resource is built from a wavefront-uniform base pointer and the lane's position goes into the byte
-// offset (< 4 GB): a resource that differed per lane would be issued one lane at a time.
+// Stores of a phase's results.  wt: write-through at agent scope (readers on other XCDs after a grid
+// barrier); else plain stores into this XCD's L2 (readers on this XCD after an XCD-local barrier).  The
+// buffer resource is built from a wavefront-uniform base pointer and the lane's position goes into the
+// byte offset (< 4 GB): a resource that differed per lane would be issued one lane at a time.
 struct WtBuf {
   __amdgpu_buffer_rsrc_t r;
-  __device__ __forceinline__ explicit WtBuf(const void* base) : r(rsrc_of(base, 0xFFFFFFFFu)) {}
+  bool wt;
+  __device__ __forceinline__ WtBuf(const void* base, int write_through) : r(rsrc_of(base, 0xFFFFFFFFu)), wt(write_through != 0) {}
   __device__ __forceinline__ void st128(size_t byte_off, f32x4 v) const {
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, (unsigned)byte_off, 0, AUX_SC1);
+    if (wt) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, (unsigned)byte_off, 0, AUX_SC1);
+    else __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, (unsigned)byte_off, 0, 0);
   }
   __device__ __forceinline__ void st64(size_t byte_off, u32x2 v) const {
-    __builtin_amdgcn_raw_buffer_store_b64(v, r, (unsigned)byte_off, 0, AUX_SC1);
+    if (wt) __builtin_amdgcn_raw_buffer_store_b64(v, r, (unsigned)byte_off, 0, AUX_SC1);
+    else __builtin_amdgcn_raw_buffer_store_b64(v, r, (unsigned)byte_off, 0, 0);
   }
   __device__ __forceinline__ void st32(size_t byte_off, unsigned v) const {
-    __builtin_amdgcn_raw_buffer_store_b32(v, r, (unsigned)byte_off, 0, AUX_SC1);
+    if (wt) __builtin_amdgcn_raw_buffer_store_b32(v, r, (unsigned)byte_off, 0, AUX_SC1);
+    else __builtin_amdgcn_raw_buffer_store_b32(v, r, (unsigned)byte_off, 0, 0);
   }
   __device__ __forceinline__ void st16(size_t byte_off, unsigned v) const {
-    __builtin_amdgcn_raw_buffer_store_b16((unsigned short)v, r, (unsigned)byte_off, 0, AUX_SC1);
+    if (wt) __builtin_amdgcn_raw_buffer_store_b16((unsigned short)v, r, (unsigned)byte_off, 0, AUX_SC1);
+    else __builtin_amdgcn_raw_buffer_store_b16((unsigned short)v, r, (unsigned)byte_off, 0, 0);
   }
 };
 
 // ------------------------------------------------------------------------------------------
-// grid barrier
+// barriers
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ bool mg_aborted(MegaSync* s) {
   return __hip_atomic_load(&s->abort, __ATOMIC_RELAXED, MG_AGENT) != 0u;
 }
 
-// The barrier comes in two halves so that a phase can put independent memory requests between them.
-// `seq`: number of this barrier since the counters were last zeroed (1-based, the same in every workgroup).
-__device__ __forceinline__ void barrier_arrive(MegaSync* s, unsigned seq) {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this wave's write-through stores are acknowledged
+// A barrier comes in two halves so that a phase can put independent memory requests between them.
+// local: only the workgroups of this XCD group (blockIdx.x % 8) meet.  `seq`: number of this barrier among
+// the barriers of its kind since the counters were zeroed (1-based, the same in every workgroup).
+struct Barrier {
+  MegaSync* s;
+  long long limit_ticks;
+  int* err_flag;
+  bool no_inv;  // timing experiment only
+};
+__device__ __forceinline__ void barrier_arrive(const Barrier& b, bool local, unsigned seq) {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this wave's stores are acknowledged (L2, or memory if write-through)
   __syncthreads();
-  if (threadIdx.x == 0 && !mg_aborted(s)) {
-    const unsigned n = gridDim.x, wg = blockIdx.x;
-    const unsigned x = wg & 7u;
-    const unsigned per = (n + 7u - x) / 8u;  // workgroups with wg % 8 == x
-    const unsigned old = __hip_atomic_fetch_add(&s->xcount[x * 64], 1u, __ATOMIC_RELAXED, MG_AGENT);
-    if (old + 1u == seq * per) __hip_atomic_fetch_add(&s->top, 1u, __ATOMIC_RELAXED, MG_AGENT);
+  if (threadIdx.x == 0 && !mg_aborted(b.s)) {
+    const unsigned n = gridDim.x, x = blockIdx.x & 7u;
+    const unsigned per = (n + 7u - x) / 8u;  // workgroups with blockIdx.x % 8 == x
+    if (local) {
+      __hip_atomic_fetch_add(&b.s->lcount[x * 64], 1u, __ATOMIC_RELAXED, MG_AGENT);
+    } else {
+      const unsigned old = __hip_atomic_fetch_add(&b.s->xcount[x * 64], 1u, __ATOMIC_RELAXED, MG_AGENT);
+      if (old + 1u == seq * per) __hip_atomic_fetch_add(&b.s->top, 1u, __ATOMIC_RELAXED, MG_AGENT);
+    }
   }
 }
-__device__ __forceinline__ void barrier_wait(MegaSync* s, unsigned seq, long long limit_ticks, int* err_flag,
-                                             bool no_inv = false) {
+__device__ __forceinline__ void barrier_wait(const Barrier& b, bool local, unsigned seq) {
   if (threadIdx.x == 0) {
-    if (!mg_aborted(s)) {
-      const unsigned n = gridDim.x, groups = n < 8u ? n : 8u;
-      const unsigned target = seq * groups;
+    if (!mg_aborted(b.s)) {
+      const unsigned n = gridDim.x, x = blockIdx.x & 7u;
+      const unsigned* ctr = local ? &b.s->lcount[x * 64] : &b.s->top;
+      const unsigned target = local ? seq * ((n + 7u - x) / 8u) : seq * (n < 8u ? n : 8u);
       const long long t0 = wall_clock64();
-      while ((int)(__hip_atomic_load(&s->top, __ATOMIC_RELAXED, MG_AGENT) - target) < 0) {
+      while ((int)(__hip_atomic_load(ctr, __ATOMIC_RELAXED, MG_AGENT) - target) < 0) {
         __builtin_amdgcn_s_sleep(1);
-        if (wall_clock64() - t0 > limit_ticks) {
-          __hip_atomic_store(&s->abort, 1u, __ATOMIC_RELAXED, MG_AGENT);
-          atomicOr(err_flag, 2);
+        if (wall_clock64() - t0 > b.limit_ticks) {
+          __hip_atomic_store(&b.s->abort, 1u, __ATOMIC_RELAXED, MG_AGENT);
+          atomicOr(b.err_flag, 2);
           break;
         }
-        if (mg_aborted(s)) break;
+        if (mg_aborted(b.s)) break;
       }
     }
-    if (!no_inv) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // drop L1/L2 lines other XCDs may have rewritten
+    if (!b.no_inv) {
+      if (local) asm volatile("buffer_inv sc0" ::: "memory");   // this CU's L1 only: the data is in this XCD's L2
+      else __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");    // L1 and the L2 lines other XCDs may have rewritten
+    }
   }
   __syncthreads();
-}
-__device__ __forceinline__ void grid_barrier(MegaSync* s, unsigned seq, long long limit_ticks, int* err_flag,
-                                             bool no_inv = false) {
-  barrier_arrive(s, seq);
-  barrier_wait(s, seq, limit_ticks, err_flag, no_inv);
 }
 
 // ------------------------------------------------------------------------------------------
-// GEMM phase:  out = X[M,K] * W[N,K]^T  for the K range of this workgroup's K group
+// GEMM phase:  out = X[M,K] * W[N,K]^T
 //
-// Workgroup -> (K group kg, column group ng); workgroups of one XCD (wg % 8) share kg, so the
-// activation stages they all read are L2 hits after the first.  A workgroup finishes its column
-// blocks in passes of MG_PASS_BLOCKS; in a pass wavefront (uw, kp) owns MG_NFW fragments and the
-// k-tiles kp*MG_CH.. of every 256-column stage, streams its weights global -> registers one stage
-// ahead and reads the activation fragments from the double-buffered LDS stage.  The k-parts are
-// added through LDS after the last stage.
+// Three mappings of (K range, 16-column blocks) onto workgroups (x = workgroup % 8, the XCD group;
+// j = workgroup / 8):
+//   shard 0  K group kg = x % KG over the whole grid: the workgroups of an XCD share the activation
+//            stages they read (L2 hits after the first); every column block has KG partial results.
+//   shard 1  XCD x owns a set of column blocks (its heads, its FFN slice) over all of K, split again
+//            into KG local K groups among its workgroups; partial results stay in this XCD.
+//   shard 2  XCD x owns a K slice (the columns it produced itself in the previous phase) for ALL
+//            column blocks; partial result x goes to the grid-wide residual sum.
+// A workgroup finishes its column blocks in passes of MG_PASS_BLOCKS; in a pass wavefront (uw, kp)
+// owns MG_NFW fragments and the k-tiles kp*MG_CH.. of every 256-column stage, streams its weights
+// global -> registers two stages ahead and reads the activation fragments from the double-buffered
+// LDS stage.  The k-parts are added through LDS after the last stage.
 // ------------------------------------------------------------------------------------------
-constexpr int MG_NBUF = 3;           // register buffers of weight fragments: loads run two stages ahead
-constexpr int MG_NPRE = MG_NBUF - 1;  // stages whose weights can be requested before the previous phase's barrier
+constexpr int MG_NBUF = 2;           // register buffers of weight fragments: loads run MG_NBUF - 1 stages ahead (more in
+                                     // flight only lengthens the queue in front of the latency-critical activation loads)
+constexpr int MG_NPRE = MG_NBUF - 1;  // stages whose weights are requested before the previous phase's barrier
 
 typedef Frag WBuf[MG_NFW][MG_CH];
 
-// where a workgroup / wavefront stands in a GEMM phase
+// where a workgroup stands in a GEMM phase
 struct GemmPlan {
-  int kg, s_begin, s_end, b_begin, b_end;  // K group, its stages, this workgroup's column blocks
+  int kg;                      // index of the partial result this workgroup contributes to
+  int s_begin, s_end;          // its K stages
+  int b_begin, b_end;          // its column blocks (shard 1: indices into the XCD's local block list)
   int n_blocks, KT, cb_per_pass, cb_per_wave;
-  bool idle;                               // nothing to do (whole workgroup)
+  int rot;                     // rotation of the stage order
+  bool idle;                   // nothing to do (whole workgroup)
 };
 __device__ __forceinline__ GemmPlan gemm_plan(const MegaPhase& ph) {
   GemmPlan g;
   const int nwg = gridDim.x, wg = blockIdx.x;
+  const int x = wg & 7, j = wg >> 3, nw = nwg >> 3;  // XCD group, index and count of workgroups in it
   const int KG = ph.KG;
-  const int xcd = wg & 7, j = wg >> 3;
-  g.kg = xcd % KG;
-  const int NG = nwg / KG;
-  const int ng = xcd / KG + (8 / KG) * j;
   g.KT = ph.K / 32;
   const int NS = ph.K / MG_KST;
-  g.s_begin = (int)((long long)g.kg * NS / KG);
-  g.s_end = (int)((long long)(g.kg + 1) * NS / KG);
   g.n_blocks = ph.N / 16;  // epi 1: blocks of F (each a gate and an up fragment)
-  g.b_begin = (int)((long long)ng * g.n_blocks / NG);
-  g.b_end = (int)((long long)(ng + 1) * g.n_blocks / NG);
+  int part, parts, kgi, kgs, nb;
+  if (ph.shard == 0) {
+    kgi = x % KG; kgs = KG;
+    parts = nwg / KG; part = x / KG + (8 / KG) * j;
+    nb = g.n_blocks;
+    g.s_begin = (int)((long long)kgi * NS / kgs);
+    g.s_end = (int)((long long)(kgi + 1) * NS / kgs);
+    g.kg = kgi;
+  } else if (ph.shard == 1) {
+    kgi = j % KG; kgs = KG;
+    parts = nw / KG; part = j / KG;
+    nb = 0;
+#pragma unroll
+    for (int sgm = 0; sgm < 3; ++sgm) nb += ph.seg_bnd[sgm][x + 1] - ph.seg_bnd[sgm][x];
+    g.s_begin = (int)((long long)kgi * NS / kgs);
+    g.s_end = (int)((long long)(kgi + 1) * NS / kgs);
+    g.kg = kgi;
+    if (part >= parts) nb = 0;  // workgroups beyond parts * KG have no share
+  } else {
+    parts = nw; part = j;
+    nb = g.n_blocks;
+    g.s_begin = ph.ks_bnd[x];
+    g.s_end = ph.ks_bnd[x + 1];
+    g.kg = x;
+  }
+  g.b_begin = (int)((long long)part * nb / parts);
+  g.b_end = (int)((long long)(part + 1) * nb / parts);
   g.cb_per_pass = ph.epi == 1 ? MG_PASS_BLOCKS / 2 : MG_PASS_BLOCKS;  // column blocks per pass
   g.cb_per_wave = ph.epi == 1 ? MG_NFW / 2 : MG_NFW;
   g.idle = g.b_begin >= g.b_end || g.s_begin >= g.s_end;
+  // Workgroups walk their stages in rotated order: every weight block has the same power-of-two size, and
+  // walking them in lock-step would keep all workgroups on the same few HBM channels at any moment.
+  g.rot = g.idle ? 0 : j % (g.s_end - g.s_begin);
   return g;
 }
+// column block index -> block row of W (shard 1: the XCD's local list -> global block)
+__device__ __forceinline__ int gemm_global_block(const MegaPhase& ph, int lb) {
+  if (ph.shard != 1) return lb;
+  const int x = blockIdx.x & 7;
+  int gb = 0, cum = 0;
+#pragma unroll
+  for (int sgm = 0; sgm < 3; ++sgm) {
+    const int lo = ph.seg_bnd[sgm][x], len = ph.seg_bnd[sgm][x + 1] - lo;
+    if (lb >= cum && lb < cum + len) gb = ph.seg_base[sgm] + lo + (lb - cum);
+    cum += len;
+  }
+  return gb;
+}
 // fragments of wavefront (uw, kp) in the pass that starts at column block p0: byte offset of fragment f
-// at stage 0 (k-tile kp*MG_CH), out of range for a missing fragment; cbk: its column block or -1
+// at stage 0 (k-tile kp*MG_CH), out of range for a missing fragment; cbk: its column block (the index
+// of gemm_plan's range) or -1; gbk: the same block's row in W
 __device__ __forceinline__ void gemm_frags(const MegaPhase& ph, const GemmPlan& g, int p0, int uw, int kp, int lane,
-                                           unsigned (&wof)[MG_NFW], int (&cbk)[MG_NFW]) {
+                                           unsigned (&wof)[MG_NFW], int (&cbk)[MG_NFW], int (&gbk)[MG_NFW]) {
 #pragma unroll
   for (int f = 0; f < MG_NFW; ++f) {
     const int cb = p0 + uw * g.cb_per_wave + (ph.epi == 1 ? f / 2 : f);
     const bool live = !g.idle && cb < min(g.b_end, p0 + g.cb_per_pass);
     cbk[f] = live ? cb : -1;
-    const int wrow = (ph.epi == 1 && (f & 1)) ? cb + g.n_blocks : cb;  // up fragments follow the gate matrix
+    gbk[f] = live ? gemm_global_block(ph, cb) : 0;
+    const int wrow = (ph.epi == 1 && (f & 1)) ? gbk[f] + g.n_blocks : gbk[f];  // up fragments follow the gate matrix
     wof[f] = live ? ((unsigned)wrow * (unsigned)g.KT + (unsigned)(kp * MG_CH)) * 1024u + (unsigned)lane * 16u : 0xFFFFFF00u;
   }
 }
@@ -207,9 +275,8 @@ __device__ __forceinline__ void gemm_load_w(const __amdgpu_buffer_rsrc_t rw, con
 // MG_NPRE stages have been requested: they do not depend on the previous phase, so the HBM stream keeps
 // running while the workgroups wait for each other.
 template <int MT>
-__device__ __forceinline__ void gemm_phase(const MegaPhase& ph, const int tid, bf16_t* xs, MegaSync* sync,
-                                           const unsigned barrier_seq /* 0: no barrier */, const long long limit_ticks,
-                                           int* err_flag, long long* stamp) {
+__device__ __forceinline__ void gemm_phase(const MegaPhase& ph, const int tid, bf16_t* xs, const Barrier& bar,
+                                           const unsigned barrier_seq /* 0: no barrier */, long long* stamp) {
   constexpr int ROWS = MT * 16;
   constexpr int PLANE = ROWS * MG_LDK;
   constexpr int BUF = 2 * PLANE;
@@ -218,16 +285,15 @@ __device__ __forceinline__ void gemm_phase(const MegaPhase& ph, const int tid, b
   const int wave = tid >> 6, lane = tid & 63;
   const int l16 = lane & 15, g4 = lane >> 4;
   const int uw = wave / MG_KW, kp = wave % MG_KW;
+  const bool local_bar = ph.sync != 0;
   const GemmPlan g = gemm_plan(ph);
   if (g.idle) {  // whole workgroup
-    if (barrier_seq) grid_barrier(sync, barrier_seq, limit_ticks, err_flag, (ph.dbg & 8) != 0);
+    if (barrier_seq) { barrier_arrive(bar, local_bar, barrier_seq); barrier_wait(bar, local_bar, barrier_seq); }
     if (stamp && blockIdx.x == 0 && threadIdx.x == 0) *stamp = wall_clock64();
     return;
   }
   const int kg = g.kg, s_begin = g.s_begin, ns = g.s_end - g.s_begin, epi = ph.epi;
-  // Workgroups walk their stages in rotated order: every weight block has the same power-of-two size, and
-  // walking them in lock-step would keep all workgroups on the same few HBM channels at any moment.
-  const int rot = (int)(blockIdx.x >> 3) % ns;
+  const int rot = g.rot;
   auto stage_of = [&](int i) { const int r = i + rot; return s_begin + (r >= ns ? r - ns : r); };  // i < ns
 
   const __amdgpu_buffer_rsrc_t rw = rsrc_of(ph.W, ph.w_bytes);
@@ -239,8 +305,8 @@ __device__ __forceinline__ void gemm_phase(const MegaPhase& ph, const int tid, b
 
   for (int p0 = g.b_begin; p0 < g.b_end; p0 += g.cb_per_pass) {
     unsigned wof[MG_NFW];
-    int cbk[MG_NFW];
-    gemm_frags(ph, g, p0, uw, kp, lane, wof, cbk);
+    int cbk[MG_NFW], gbk[MG_NFW];
+    gemm_frags(ph, g, p0, uw, kp, lane, wof, cbk, gbk);
     WBuf w[MG_NBUF];
     f32x4 acc[MG_NFW][MT];
 #pragma unroll
@@ -291,11 +357,11 @@ __device__ __forceinline__ void gemm_phase(const MegaPhase& ph, const int tid, b
     // ---- prologue: the first MG_NPRE stages of weights, the previous phase's barrier (first pass), the
     // first activation stage ----
     const bool first = p0 == g.b_begin;
-    if (first && barrier_seq) barrier_arrive(sync, barrier_seq);  // (its store wait must not see the loads below)
+    if (first && barrier_seq) barrier_arrive(bar, local_bar, barrier_seq);  // (its store wait must not see the loads below)
 #pragma unroll
     for (int i = 0; i < MG_NPRE; ++i) gemm_load_w(rw, wof, cbk, stage_of(i), i < ns && !(dbg & 4), w[i]);
     if (first) {
-      if (barrier_seq) barrier_wait(sync, barrier_seq, limit_ticks, err_flag, (dbg & 8) != 0);
+      if (barrier_seq) barrier_wait(bar, local_bar, barrier_seq);
       if (stamp && blockIdx.x == 0 && threadIdx.x == 0) *stamp = wall_clock64();
     }
     x_load(0);
@@ -316,8 +382,8 @@ __device__ __forceinline__ void gemm_phase(const MegaPhase& ph, const int tid, b
     };
     for (int i = 0; i < ns; i += MG_NBUF) {
       stage(std::integral_constant<int, 0>{}, i);
-      if (i + 1 < ns) stage(std::integral_constant<int, 1>{}, i + 1);
-      if (i + 2 < ns) stage(std::integral_constant<int, 2>{}, i + 2);
+      if (i + 1 < ns) stage(std::integral_constant<int, 1 % MG_NBUF>{}, i + 1);
+      if (MG_NBUF > 2 && i + 2 < ns) stage(std::integral_constant<int, 2 % MG_NBUF>{}, i + 2);
     }
     // (the last stage's barrier also frees the stage buffers)
 
@@ -347,7 +413,8 @@ __device__ __forceinline__ void gemm_phase(const MegaPhase& ph, const int tid, b
     // ---- epilogue: lane holds rows mb*16 + l16, columns 4*g4.. of each fragment ----
     if (kp == 0) {
       if (epi == 0) {
-        const WtBuf wy(ph.Y);
+        // shard 1: this XCD's private partial buffer, indexed by the XCD's local columns
+        const WtBuf wy(ph.shard == 1 ? ph.lbuf + (size_t)(blockIdx.x & 7) * ph.lbuf_stride : ph.Y, ph.wt);
         const size_t ybase = (size_t)kg * ph.split_stride;
 #pragma unroll
         for (int f = 0; f < MG_NFW; ++f) {
@@ -360,7 +427,7 @@ __device__ __forceinline__ void gemm_phase(const MegaPhase& ph, const int tid, b
           }
         }
       } else {
-        const WtBuf wh(ph.Yhi), wl(ph.Ylo);
+        const WtBuf wh(ph.Yhi, ph.wt), wl(ph.Ylo, ph.wt);
 #pragma unroll
         for (int mb = 0; mb < MT; ++mb) {
           const int m = mb * 16 + l16;
@@ -371,7 +438,7 @@ __device__ __forceinline__ void gemm_phase(const MegaPhase& ph, const int tid, b
 #pragma unroll
             for (int f = 0; f < MG_NFW; f += 2) {
               if (cbk[f] < 0) continue;
-              const int col = cbk[f] * 16 + 4 * g4;
+              const int col = gbk[f] * 16 + 4 * g4;
               float o[4];
 #pragma unroll
               for (int r = 0; r < 4; ++r) {
@@ -389,7 +456,7 @@ __device__ __forceinline__ void gemm_phase(const MegaPhase& ph, const int tid, b
 #pragma unroll
             for (int f = 0; f < MG_NFW; ++f) {
               if (cbk[f] < 0) continue;
-              const int col = cbk[f] * 16 + 4 * g4;
+              const int col = gbk[f] * 16 + 4 * g4;
               const f32x4 v = acc[f][mb] * sc;
               *(float4*)(ph.Y + (size_t)m * ph.ldy + col) = make_float4(v[0], v[1], v[2], v[3]);
             }
@@ -410,7 +477,7 @@ __device__ __forceinline__ void reduce_phase(const MegaPhase& ph, const int tid,
   const int lane = tid & 63, wave = tid >> 6;
   const int H = ph.H, Q = H / 4;
   const int n_items = ph.M * 4;
-  const WtBuf wx(ph.x), wh(ph.Yhi), wl(ph.Ylo), wss(ph.ss_out);
+  const WtBuf wx(ph.x, 1), wh(ph.Yhi, 1), wl(ph.Ylo, 1), wss(ph.ss_out, 1);  // read by every XCD
   for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
     const int g = item >> 2, q = item & 3;
     float ssq = 0.f;
@@ -461,6 +528,31 @@ __device__ __forceinline__ void reduce_phase(const MegaPhase& ph, const int tid,
 // Wavefront items: (row, q or k head) with one rotation pair per lane, then (sequence, 8 V^T lines)
 // with one tree node per lane.
 // ------------------------------------------------------------------------------------------
+// the heads this workgroup's XCD group handles in the RoPE / attention / merge phases, where the workgroup
+// stands among the workgroups that share them, and the buffers the three phases hand results over in
+struct HeadShare {
+  int q0, nq, kv0, nkv;   // first / number of query heads and of KV heads
+  int widx, nwork;        // index / number of the workgroups sharing these heads
+  const float* qkv;       // QKV partials [KG][M][ldy]: columns = (nq q heads, nkv k heads, nkv v heads) x 128
+  float *o_part, *ml_part;  // [split][rows_total][nq][128] and [split][rows_total][nq][2]
+};
+__device__ __forceinline__ HeadShare head_share(const MegaPhase& ph) {
+  HeadShare h;
+  if (ph.shard) {
+    const int x = blockIdx.x & 7;
+    h.nq = ph.n_q / 8; h.nkv = ph.n_kv / 8;
+    h.q0 = x * h.nq; h.kv0 = x * h.nkv;
+    h.widx = blockIdx.x >> 3; h.nwork = gridDim.x >> 3;
+    float* base = ph.lbuf + (size_t)x * ph.lbuf_stride;
+    h.qkv = base; h.o_part = base + ph.lo_off; h.ml_part = base + ph.lml_off;
+  } else {
+    h.nq = ph.n_q; h.nkv = ph.n_kv; h.q0 = 0; h.kv0 = 0;
+    h.widx = blockIdx.x; h.nwork = gridDim.x;
+    h.qkv = ph.Y; h.o_part = ph.o_part; h.ml_part = ph.ml_part;
+  }
+  return h;
+}
+
 __device__ __forceinline__ float row_scale(const float* ss, int g, int H, float eps) {
   const float4 q = *(const float4*)(ss + (size_t)g * 4);
   return 1.0f / sqrtf((q.x + q.y + q.z + q.w) / (float)H + eps);
@@ -468,28 +560,29 @@ __device__ __forceinline__ float row_scale(const float* ss, int g, int H, float 
 
 __device__ __forceinline__ void rope_phase(const MegaPhase& ph, const int tid) {
   const int lane = tid & 63;
-  const int gw = blockIdx.x * MG_WAVES + (tid >> 6), n_gw = gridDim.x * MG_WAVES;
+  const HeadShare hs = head_share(ph);
+  const int gw = hs.widx * MG_WAVES + (tid >> 6), n_gw = hs.nwork * MG_WAVES;
   const RowMap rm = ph.rm;
-  const int d = 128, half = 64, n_q = ph.n_q, n_kv = ph.n_kv;
-  const int heads = n_q + n_kv;
+  const int d = 128, half = 64, n_kv = ph.n_kv;
+  const int heads = hs.nq + hs.nkv;
   const int qk_items = rm.B * rm.n * heads;
-  const int v_chunks = n_kv * d / 8;
+  const int v_chunks = hs.nkv * d / 8;
   const int n_items = qk_items + rm.B * v_chunks;
   const int voff = heads * d;
-  const WtBuf wqh(ph.q_hi), wql(ph.q_lo), wk(ph.k_hi), wv(ph.v_hi);
+  const WtBuf wqh(ph.q_hi, ph.wt), wql(ph.q_lo, ph.wt), wk(ph.k_hi, ph.wt), wv(ph.v_hi, ph.wt);
   for (int item = gw; item < n_items; item += n_gw) {
     if (item < qk_items) {
-      const int hh = item % heads, bi = item / heads, i = bi % rm.n, b = bi / rm.n;
+      const int li = item % heads, bi = item / heads, i = bi % rm.n, b = bi / rm.n;
       const int nv = rm.n_valid ? min(rm.n_valid[b], rm.n) : rm.n;
       const int L = ph.base_len[b];
       if (L + nv > ph.max_seq) {
-        if (lane == 0 && i == 0 && hh == 0) atomicOr(ph.err_flag, 1);
+        if (lane == 0 && i == 0 && li == 0) atomicOr(ph.err_flag, 1);
         continue;
       }
       if (i >= nv) continue;
       const int g = b * rm.R + i;
       const float sc = row_scale(ph.ss, g, ph.H, ph.eps);
-      const float* src = ph.Y + (size_t)g * ph.ldy + hh * d + lane;
+      const float* src = hs.qkv + (size_t)g * ph.ldy + li * d + lane;
       float a1[8], a2[8];
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
@@ -500,29 +593,30 @@ __device__ __forceinline__ void rope_phase(const MegaPhase& ph, const int tid) {
 #pragma unroll
       for (int k = 0; k < 8; ++k) { x1 += a1[k]; x2 += a2[k]; }
       x1 *= sc; x2 *= sc;
-      const float c = ph.cos_t[(size_t)g * half + lane], s = ph.sin_t[(size_t)g * half + lane];
-      const float qs = hh < n_q ? ph.q_scale : 1.0f;  // queries are stored pre-scaled by 1/sqrt(d)
-      const float o1 = (x1 * c - x2 * s) * qs, o2 = (x2 * c + x1 * s) * qs;
+      const float c = ph.cos_t[(size_t)g * half + lane], sn = ph.sin_t[(size_t)g * half + lane];
+      const bool is_q = li < hs.nq;  // wavefront-uniform
+      const float qs = is_q ? ph.q_scale : 1.0f;  // queries are stored pre-scaled by 1/sqrt(d)
+      const float o1 = (x1 * c - x2 * sn) * qs, o2 = (x2 * c + x1 * sn) * qs;
       const unsigned h1 = rn_bf16(o1), h2 = rn_bf16(o2);
       const unsigned l1 = rn_bf16(o1 - bf16_f32(h1)), l2 = rn_bf16(o2 - bf16_f32(h2));
-      if (hh < n_q) {  // wavefront-uniform
-        const size_t o = ((size_t)g * ph.ldq + hh * d + lane) * 2;
+      if (is_q) {
+        const size_t o = ((size_t)g * ph.ldq + (hs.q0 + li) * d + lane) * 2;
         wqh.st16(o, h1); wqh.st16(o + half * 2, h2);
         wql.st16(o, l1); wql.st16(o + half * 2, l2);
       } else {
-        const size_t o = ((((size_t)b * ph.max_seq + (L + i)) * n_kv + (hh - n_q)) * d + lane) * 2;
+        const size_t o = ((((size_t)b * ph.max_seq + (L + i)) * n_kv + (hs.kv0 + li - hs.nq)) * d + lane) * 2;
         wk.st16(o, h1); wk.st16(o + half * 2, h2);
         wk.st16(o + ph.k_plane * 2, l1); wk.st16(o + ph.k_plane * 2 + half * 2, l2);
       }
     } else {
-      const int vi = item - qk_items, b = vi / v_chunks, e0 = (vi % v_chunks) * 8;
+      const int vi = item - qk_items, b = vi / v_chunks, e0 = (vi % v_chunks) * 8;  // e0: first of 8 V^T lines of this share
       const int nv = rm.n_valid ? min(rm.n_valid[b], rm.n) : rm.n;
       const int L = ph.base_len[b];
       if (L + nv > ph.max_seq) continue;
       for (int i = lane; i < nv; i += 64) {
         const int g = b * rm.R + i;
         const float sc = row_scale(ph.ss, g, ph.H, ph.eps);
-        const float* src = ph.Y + (size_t)g * ph.ldy + voff + e0;
+        const float* src = hs.qkv + (size_t)g * ph.ldy + voff + e0;
         float4 va = {0.f, 0.f, 0.f, 0.f}, vb = {0.f, 0.f, 0.f, 0.f};
         float4 p0[8], p1[8];
 #pragma unroll
@@ -539,7 +633,7 @@ __device__ __forceinline__ void rope_phase(const MegaPhase& ph, const int tid) {
         const float v[8] = {va.x * sc, va.y * sc, va.z * sc, va.w * sc, vb.x * sc, vb.y * sc, vb.z * sc, vb.w * sc};
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          const size_t o = (((size_t)b * n_kv * d + e0 + e) * ph.max_seq + L + i) * 2;
+          const size_t o = ((((size_t)b * n_kv + hs.kv0) * d + e0 + e) * ph.max_seq + L + i) * 2;
           const unsigned h = rn_bf16(v[e]);
           wv.st16(o, h);
           wv.st16(o + ph.v_plane * 2, rn_bf16(v[e] - bf16_f32(h)));
@@ -572,15 +666,16 @@ __device__ __forceinline__ void attn_phase(const MegaPhase& ph, const int tid, b
   const int wave = tid >> 6, lane = tid & 63;
   const int l16 = lane & 15, g4 = lane >> 4;
   const RowMap rm = ph.rm;
-  const int n_kv = ph.n_kv, n_q = ph.n_q;
+  const HeadShare hs = head_share(ph);
+  const int n_kv = ph.n_kv;
   const int node_groups = (rm.n + 31) / 32;
   const int chunks = (node_groups + NGW - 1) / NGW;
-  const int n_items = rm.B * n_kv * chunks * ph.n_splits;
-  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+  const int n_items = rm.B * hs.nkv * chunks * ph.n_splits;
+  for (int item = hs.widx; item < n_items; item += hs.nwork) {
     const int split = item % ph.n_splits;
     int r = item / ph.n_splits;
     const int ck = r % chunks; r /= chunks;
-    const int kvh = r % n_kv, b = r / n_kv;
+    const int kvh = hs.kv0 + r % hs.nkv, b = r / hs.nkv;
     const int nv = rm.n_valid ? min(rm.n_valid[b], rm.n) : rm.n;
     const int L = ph.base_len[b];
     if (ck * NGW * 32 >= nv || L + nv > ph.max_seq) continue;  // whole workgroup
@@ -745,7 +840,7 @@ __device__ __forceinline__ void attn_phase(const MegaPhase& ph, const int tid, b
     }
 
     // ---- partial result of this split (write-through: the merge phase runs in other workgroups) ----
-    const WtBuf wo(ph.o_part), wml(ph.ml_part);
+    const WtBuf wo(hs.o_part, ph.wt), wml(hs.ml_part, ph.wt);
     if (active) {
 #pragma unroll
       for (int mb = 0; mb < AT_MB; ++mb) {
@@ -754,7 +849,7 @@ __device__ __forceinline__ void attn_phase(const MegaPhase& ph, const int tid, b
         lsum += __shfl_xor(lsum, 16, 64);
         lsum += __shfl_xor(lsum, 32, 64);
         if (node >= nv) continue;
-        const size_t prow = ((size_t)split * ph.rows_total + (size_t)b * rm.R + node) * n_q + head;
+        const size_t prow = ((size_t)split * ph.rows_total + (size_t)b * rm.R + node) * hs.nq + (head - hs.q0);
 #pragma unroll
         for (int db = 0; db < 8; ++db) wo.st128((prow * AT_D + db * 16 + 4 * g4) * 4, O[db][mb]);
         if (g4 == 0) {
@@ -770,18 +865,19 @@ __device__ __forceinline__ void attn_phase(const MegaPhase& ph, const int tid, b
 // Item = (row, group of 16 heads); 32 threads per head, four channels each.
 __device__ __forceinline__ void merge_phase(const MegaPhase& ph, const int tid) {
   const RowMap rm = ph.rm;
-  const int n_q = ph.n_q;
-  const int hgroups = (n_q + 15) / 16;
+  const HeadShare hs = head_share(ph);
+  const int hgroups = (hs.nq + 15) / 16;
   const int n_items = rm.B * rm.n * hgroups;
-  const WtBuf wh(ph.Yhi), wl(ph.Ylo);
-  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+  const WtBuf wh(ph.Yhi, ph.wt), wl(ph.Ylo, ph.wt);
+  for (int item = hs.widx; item < n_items; item += hs.nwork) {
     const int hg = item % hgroups, bi = item / hgroups, i = bi % rm.n, b = bi / rm.n;
     const int nv = rm.n_valid ? min(rm.n_valid[b], rm.n) : rm.n;
-    const int head = hg * 16 + (tid >> 5), d4 = (tid & 31) * 4;
-    if (i >= nv || head >= n_q || ph.base_len[b] + nv > ph.max_seq) continue;
+    const int hl = hg * 16 + (tid >> 5), d4 = (tid & 31) * 4;  // head within the share
+    if (i >= nv || hl >= hs.nq || ph.base_len[b] + nv > ph.max_seq) continue;
+    const int head = hs.q0 + hl;
     const size_t row = (size_t)b * rm.R + i;
-    const size_t sstride = (size_t)ph.rows_total * n_q;
-    const size_t pr0 = row * n_q + head;
+    const size_t sstride = (size_t)ph.rows_total * hs.nq;
+    const size_t pr0 = row * hs.nq + hl;
     const int n_tiles = (ph.base_len[b] + nv + AT_TK - 1) / AT_TK;
     const int tps = attn_tiles_per_split(n_tiles, ph.n_splits);
     const int ns = (n_tiles + tps - 1) / tps;  // splits that hold a result
@@ -791,8 +887,8 @@ __device__ __forceinline__ void merge_phase(const MegaPhase& ph, const int tid) 
 #pragma unroll
     for (int k = 0; k < MG_MAX_SPLITS; ++k) {
       const bool in = k < ns;
-      ml[k] = in ? *(const float2*)(ph.ml_part + (pr0 + k * sstride) * 2) : make_float2(-INFINITY, 0.f);
-      o[k] = in ? *(const float4*)(ph.o_part + (pr0 + k * sstride) * AT_D + d4) : make_float4(0.f, 0.f, 0.f, 0.f);
+      ml[k] = in ? *(const float2*)(hs.ml_part + (pr0 + k * sstride) * 2) : make_float2(-INFINITY, 0.f);
+      o[k] = in ? *(const float4*)(hs.o_part + (pr0 + k * sstride) * AT_D + d4) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
     float M = -INFINITY;
 #pragma unroll
@@ -820,16 +916,29 @@ static_assert((size_t)MG_UW * (MG_KW - 1) * MG_NFW * 4 * 64 * 16 <= MG_LDS_BYTES
 
 // stamps (optional): wall-clock ticks at which workgroup 0 started phase p (stamps[p]) and left the last one
 __global__ __launch_bounds__(MG_NT) void mega_kernel(const MegaPhase* __restrict__ prog, int p_begin, int p_end,
-                                                     MegaSync* sync, unsigned seq_base, long long limit_ticks,
-                                                     int* err_flag, long long* stamps) {
+                                                     MegaSync* sync, unsigned gseq_base, unsigned lseq_base,
+                                                     long long limit_ticks, int* err_flag, long long* stamps,
+                                                     int check_xcd /* the program has a grid barrier */) {
   extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
   __shared__ float redbuf[MG_WAVES];
   if (mg_aborted(sync)) return;  // a previous launch timed out in a barrier: the counters are not trustworthy
+  // Workgroups i and i + 8 must share an XCD: (XCC id - workgroup index) mod 8 is then one value for the
+  // whole grid.  Workgroup 0 publishes its own, tagged with this launch's barrier count; at the end (behind
+  // at least one grid barrier) every workgroup compares.
+  const unsigned xcc_off = (__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) - blockIdx.x) & 7u;  // HW_REG_XCC_ID, 4 bits
+  const unsigned xcc_tag = (gseq_base << 3);
+  if (blockIdx.x == 0 && threadIdx.x == 0) __hip_atomic_store(&sync->off_tag, xcc_tag | xcc_off, __ATOMIC_RELAXED, MG_AGENT);
+  Barrier bar{sync, limit_ticks, err_flag, false};
   for (int p = p_begin; p < p_end; ++p) {
     const MegaPhase& ph = prog[p];
     // barrier between phase p - 1 and phase p (a GEMM phase takes it itself, behind its first weight loads)
-    const unsigned bseq = p > p_begin ? seq_base + (unsigned)(p - p_begin) : 0u;
-    if (bseq && ph.op != MG_OP_GEMM) grid_barrier(sync, bseq, limit_ticks, err_flag, (ph.dbg & 8) != 0);  // (dbg: timing experiment only)
+    const bool local = ph.sync != 0;
+    const unsigned bseq = p > p_begin ? (local ? lseq_base : gseq_base) + (unsigned)ph.bar_ord : 0u;
+    bar.no_inv = (ph.dbg & 8) != 0;
+    if (bseq && ph.op != MG_OP_GEMM) {
+      barrier_arrive(bar, local, bseq);
+      barrier_wait(bar, local, bseq);
+    }
     if (stamps && blockIdx.x == 0 && threadIdx.x == 0 && ph.op != MG_OP_GEMM) stamps[p] = wall_clock64();
     // The thread index enters every phase through a value the compiler cannot see through: otherwise
     // it hoists each phase's index arithmetic out of this loop and keeps (spills) all of it across
@@ -838,9 +947,7 @@ __global__ __launch_bounds__(MG_NT) void mega_kernel(const MegaPhase* __restrict
     asm volatile("v_mov_b32 %0, 0" : "=v"(zero));
     const int tid = (int)threadIdx.x + zero;
     switch (ph.op) {
-      case MG_OP_GEMM:
-        gemm_phase<4>(ph, tid, lds, sync, bseq, limit_ticks, err_flag, stamps ? stamps + p : nullptr);
-        break;
+      case MG_OP_GEMM: gemm_phase<4>(ph, tid, lds, bar, bseq, stamps ? stamps + p : nullptr); break;
       case MG_OP_REDUCE: reduce_phase(ph, tid, redbuf); break;
       case MG_OP_ROPE: rope_phase(ph, tid); break;
       case MG_OP_ATTN:
@@ -856,6 +963,10 @@ __global__ __launch_bounds__(MG_NT) void mega_kernel(const MegaPhase* __restrict
     }
   }
   if (stamps && blockIdx.x == 0 && threadIdx.x == 0) stamps[p_end] = wall_clock64();
+  if (check_xcd && threadIdx.x == 0) {
+    const unsigned v = __hip_atomic_load(&sync->off_tag, __ATOMIC_RELAXED, MG_AGENT);
+    if ((v & ~7u) == xcc_tag && (v & 7u) != xcc_off) atomicOr(err_flag, 4);
+  }
 }
 
 }  // namespace
@@ -897,10 +1008,11 @@ int mega_barrier_timeout_ticks(long long* out) {
   return 0;
 }
 
-hipError_t launch_mega(const MegaPhase* prog_dev, int p_begin, int p_end, MegaSync* sync, unsigned seq_base,
-                       long long limit_ticks, int* err_flag, long long* stamps, int grid, hipStream_t st) {
-  void* args[] = {(void*)&prog_dev, (void*)&p_begin, (void*)&p_end, (void*)&sync, (void*)&seq_base, (void*)&limit_ticks,
-                  (void*)&err_flag, (void*)&stamps};
+hipError_t launch_mega(const MegaPhase* prog_dev, int p_begin, int p_end, MegaSync* sync, unsigned gseq_base,
+                       unsigned lseq_base, long long limit_ticks, int* err_flag, long long* stamps, int check_xcd,
+                       int grid, hipStream_t st) {
+  void* args[] = {(void*)&prog_dev, (void*)&p_begin, (void*)&p_end, (void*)&sync, (void*)&gseq_base, (void*)&lseq_base,
+                  (void*)&limit_ticks, (void*)&err_flag, (void*)&stamps, (void*)&check_xcd};
   return hipLaunchCooperativeKernel((const void*)mega_kernel, dim3(grid), dim3(MG_NT), args, (unsigned)MG_LDS_BYTES, st);
 }
 

@@ -179,6 +179,31 @@ def test_mha_shape_bf16():
     assert ls.max_logit_err <= 3e-2
 
 
+@pytest.mark.parametrize("n_kv", [8, 16], ids=["gqa2", "mha"])
+def test_persistent_kernel_xcd_sharded(n_kv):
+    """The persistent kernel with heads and FFN columns sharded over the 8 XCDs (head counts divisible by 8):
+    QKV -> RoPE -> attention -> merge -> output projection and gate/up -> down chained inside one XCD."""
+    _torch()
+    from tests.parity import truth_hook_factory
+    shape = synth.scaled(synth.CONFIGS[3], name="mini-shard", n_layers=2, hidden=512, n_q_heads=16, n_kv_heads=n_kv,
+                         ffn=2304, vocab=4096, tree_k=(4, 3, 2, 2), tree_nodes=40, seed=29 + n_kv)
+    ls = _lockstep(shape, flags=clover.FLAG_MEGA, gain_jitter=0.1, max_seq=512)
+    assert ls.gpu.path_info() == 15
+    ls.prefill([synth.make_prompts(shape)[0][:201]], chunk=48)
+    want = [4, 1, 3]
+    hook = truth_hook_factory(ls, want)
+    for s in range(len(want)):
+        ties = ls.tie_events
+        ms = ls.step(tree_hook=hook)
+        say(f"  step {s}: want {want[s]} got {ms} max|dlogit|={ls.max_logit_err:.2e} ties={ls.tie_events}")
+        if ls.tie_events == ties:
+            assert ms == [want[s]]
+    ms = ls.step()
+    say(f"  free step: m={ms} max|dlogit|={ls.max_logit_err:.2e}")
+    assert ls.max_logit_err <= 3e-2
+    assert ls.gpu.seq_len()[0] > 201          # (also reads the device error flags: barrier time-out, XCD placement)
+
+
 def test_batch8_ragged_32_node_tree():
     """Structure of the batch-8 workload: 8 ragged sequences x 32-node tree = 256 rows per GEMM."""
     _torch()
