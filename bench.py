@@ -63,6 +63,21 @@ def measured_traffic(kernel, config):
     return None
 
 
+def traced_avg_ms(kernel, config):
+    """Average duration of the dominant kernel in the committed rocprofv3 --kernel-trace --stats summary of this
+    workload (None if there is none).  HIP events around a launch also see its dispatch latency (a few microseconds
+    more); the roofline figure uses the event-timed duration measured in this run."""
+    path = os.path.join(ROOT, "profiles", f"spec_step_config{config}_kernel_trace.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) >= 5 and kernel in line:
+                return float(f[2]) * 1e-3
+    except (OSError, ValueError):
+        pass
+    return None
+
+
 def cpu_baseline(shape, parent, rank, L, sample_layers, store, min_seconds):
     """The oracle, as it stands, timed on this host on a bounded sample of the same workload:
     `sample_layers` decoder layers of the verify pass (scaled to all layers), the LM head, the
@@ -232,12 +247,14 @@ def main():
         dom_ms, dom_n = prof["layer_stack"]
         dom_bytes = vbytes
         traffic_key = "mega_kernel"
+        trace_name = "mega_kernel"
     else:
         # dominant kernel: the fused gate/up projection (largest weight stream of a layer)
         dom_name = "gemm_gate_up (fused SwiGLU projection)"
         dom_ms, dom_n = prof["gemm_gate_up"]
         dom_bytes = 2 * 2 * shape.ffn * shape.hidden
         traffic_key = "gemm_gate_up"
+        trace_name = "gemm_panel_kernel<4, 2, 1, 2>"
     dom_avg_ms = dom_ms / max(dom_n, 1)
     achieved = dom_bytes / (dom_avg_ms * 1e-3) / 1e9 if dom_n else 0.0
     by_cls = {}
@@ -263,7 +280,9 @@ def main():
         "roofline": {"kernel": dom_name, "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic(traffic_key, args.config) if not (args.layers or args.prompt) else None,
-                     "bytes_per_launch": dom_bytes, "avg_launch_ms": dom_avg_ms},
+                     "bytes_per_launch": dom_bytes, "avg_launch_ms": dom_avg_ms,
+                     "kernel_trace_avg_launch_ms": traced_avg_ms(trace_name, args.config)
+                     if not (args.layers or args.prompt) else None},
         "kernels": kernels,
     }
     if by_cls:
