@@ -359,8 +359,9 @@ Planes planes_of(clover_ctx* x, float* buf, int K) {
 // MFMA path: out[s][M][N] = X * [W0; W1; W2]^T per split s.  Writes into `direct` (leading dimension
 // ld_direct, no split) when given, else into x->partial as [splits][M][N].  Returns the split count.
 int gemm_fast(clover_ctx* x, int cls, Planes X, int nseg, const void* const* W, const int* seg_n, int M, int N, int K,
-              float* direct, int ld_direct) {
+              float* direct, int ld_direct, float* part = nullptr /* where the K-slice partials go (stream path) */) {
   Scope sc(x, cls);
+  if (!part) part = x->partial;
   int segb[4] = {0, 0x7fffffff, 0x7fffffff, 0x7fffffff};
   const bf16_t* ws[3];
   {
@@ -376,12 +377,12 @@ int gemm_fast(clover_ctx* x, int cls, Planes X, int nseg, const void* const* W, 
     g.Xhi = X.hi; g.Xlo = X.lo; g.ldx = X.ld;
     for (int s = 0; s < 3; ++s) { g.W[s] = ws[s]; g.seg_begin[s] = segb[s]; }
     g.seg_begin[3] = 0x7fffffff;
-    g.Y = x->partial; g.ldy = N; g.split_stride = (size_t)M * N;
+    g.Y = part; g.ldy = N; g.split_stride = (size_t)M * N;
     g.M = M; g.N = N; g.K = K;
     g.tag = cls == KC_GEMM_GATEUP ? 1 : 0;
     launch_gemm_stream(g, x->st);
     const int sp = stream_gemm_slices(K);
-    if (direct) launch_reduce(x->partial, sp, (size_t)M * N, N, nullptr, x->cfg.dtype, direct, ld_direct, M, N, 0, x->st);
+    if (direct) launch_reduce(part, sp, (size_t)M * N, N, nullptr, x->cfg.dtype, direct, ld_direct, M, N, 0, x->st);
     return direct ? 1 : sp;
   }
   int splits = 1;
@@ -821,6 +822,40 @@ void run_head(clover_ctx* x, const float* g, int rows, int k) {
   { Scope s(x, KC_TOPK); launch_topk(x->z, c.vocab, c.vocab, rows, k, x->cand, x->topk_ids, x->st); }
 }
 
+// Can draft_tree take the fused route for `rows` GEMM rows?  (K-slice GEMMs for every draft linear, at most 8 slices
+// for the Attention Decoder's projections, room for the q and the k|v partials side by side.)
+bool draft_fused_ok(clover_ctx* x, int rows) {
+  const int H = x->H;
+  if (!x->fast || rows < 1 || rows > 64 || getenv("CLOVER_DRAFT_UNFUSED")) return false;
+  if (!ad_gate_fused_supported(H, x->cfg.ad_heads)) return false;
+  if (!stream_gemm_supported(rows, H, H) || !stream_gemm_supported(rows, 2 * H, H) || !stream_gemm_supported(rows, H, 2 * H) ||
+      !stream_gemm_supported(rows, x->cfg.vocab, H))
+    return false;
+  const int sH = stream_gemm_slices(H);
+  if (sH > 8) return false;
+  const size_t need = std::max((size_t)sH * rows * 3 * H, std::max((size_t)stream_gemm_slices(2 * H) * rows * H,
+                                                                    (size_t)sH * rows * x->cfg.vocab)) * sizeof(float);
+  return need <= x->partial_bytes;
+}
+
+// Attention Decoder on the fused route: planes A = RMSNorm(x)*norm (rows, ld H), Y = y (rows, ld H) are in place;
+// q and k|v projections leave their K-slice partials side by side, the gate kernel does the rest.
+void run_ad_fused(clover_ctx* x, const clover_ad_weights& ad, Planes A, Planes Y, int rows, AdGateArgs g) {
+  const int H = x->H, sH = stream_gemm_slices(H);
+  float* Pq = x->partial;
+  float* Pkv = x->partial + (size_t)sH * rows * H;
+  gemm_fast1(x, KC_GEMM_DRAFT, A, ad.wq, rows, H, H, nullptr, 0);
+  const void* wkv[2] = {ad.wk, ad.wv};
+  const int nkv[2] = {H, H};
+  gemm_fast(x, KC_GEMM_DRAFT, Y, 2, wkv, nkv, rows, 2 * H, H, nullptr, 0, Pkv);
+  g.Pq = Pq; g.Sq = sH; g.sps_q = (size_t)rows * H;
+  g.Pkv = Pkv; g.Skv = sH; g.sps_kv = (size_t)rows * 2 * H;
+  g.bq = ad.bq; g.bk = ad.bk; g.bv = ad.bv;
+  g.H = H; g.heads = x->cfg.ad_heads; g.eps = x->cfg.rms_eps;
+  Scope sc(x, KC_AD_GATE);
+  launch_ad_gate_fused(g, rows, x->st);
+}
+
 int upload_tree(clover_ctx* x) {
   const TreeHost& t = x->tree;
   const int n = t.n;
@@ -1037,18 +1072,44 @@ int draft_tree(clover_ctx* x, int32_t batch, const float* hid_acc, const int32_t
   const int M = (B - 1) * R + n;
   int aug_bound = 0;
   for (int b = 0; b < B; ++b) aug_bound = std::max(aug_bound, x->aug_ub[b] + n);
+  int max_lvl_rows = B;
+  if (t.max_depth <= c.draft_depths)
+    for (int j = 0; j < t.max_depth; ++j) max_lvl_rows = std::max(max_lvl_rows, B * (t.lvl_off[j + 1] - t.lvl_off[j]));
+  const bool fused = draft_fused_ok(x, M) && draft_fused_ok(x, max_lvl_rows);
+  Planes A = planes_of(x, x->a_norm, 2 * H);
+  A.ld = H;
+  Planes Y = planes_of(x, x->pl_y, 2 * H);
+  Y.ld = H;
+  Planes Cc = planes_of(x, x->d_cat, 2 * H);   // [state ; embedding] rows of the per-depth FC
+  if (fused) {
+    // embeddings of the follow-up tokens come from the LM-head rows; AD1 over (hidden state, embedding)
+    { Scope s(x, KC_DRAFT_MISC);
+      launch_draft_pre(hid_acc, next_tok, x->w.ad1.norm, c.rms_eps, x->w.lm_head, c.vocab, H, rm, A.hi, A.lo, Y.hi, Y.lo, x->st); }
+    AdGateArgs g;
+    memset(&g, 0, sizeof(g));
+    g.x = hid_acc; g.ldx = H; g.out = x->xd; g.ldo = H;
+    g.gain = x->aug[0].attn_norm; g.n_hi = A.hi; g.n_lo = A.lo;   // planes for the Augmenting Block's first layer
+    run_ad_fused(x, x->w.ad1, A, Y, M, g);
+    { Scope s(x, KC_ROPE_KV); launch_rope_table(x->d_aug_len, nullptr, c.rope_base, c.head_dim, x->cos_t, x->sin_t, rm, x->st); }
+  } else {
   // embeddings of the follow-up tokens come from the LM-head rows
   { Scope s(x, KC_EMBED); launch_embed(x->w.lm_head, c.dtype, next_tok, c.vocab, x->d_e, H, H, rm, x->st); }
   run_ad(x, x->w.ad1, hid_acc, x->d_e, M, x->xd);
   { Scope s(x, KC_ROPE_KV); launch_rope_table(x->d_aug_len, nullptr, c.rope_base, c.head_dim, x->cos_t, x->sin_t, rm, x->st); }
   if (x->fast) norm_planes(x, x->xd, x->aug[0].attn_norm, M);
+  }
   for (int l = 0; l < c.aug_layers; ++l)
     run_layer(x, x->aug[l], x->xd, rm, M, x->aug_kc + (size_t)l * x->k_layer_elems * x->kv_esz,
               x->aug_vc + (size_t)l * x->v_layer_elems * x->kv_esz, x->d_aug_len, x->d_anc_chain,
               l + 1 < c.aug_layers ? x->aug[l + 1].attn_norm : nullptr, aug_bound);
-  { Scope s(x, KC_DRAFT_MISC);
+  if (fused) {
+    Scope s(x, KC_DRAFT_MISC);
+    launch_draft_root_fused(x->xd, next_tok, m, B, R, H, x->d_state, tree_tokens, Y.hi, Y.lo, x->d_aug_len, x->st);
+  } else {
+    Scope s(x, KC_DRAFT_MISC);
     launch_draft_root(x->xd, next_tok, m, B, R, H, x->d_rootx, x->d_state, tree_tokens, x->st);
-    launch_add_len(x->d_aug_len, m, B, x->st); }
+    launch_add_len(x->d_aug_len, m, B, x->st);
+  }
   for (int b = 0; b < B; ++b) x->aug_ub[b] += n;
   // expansion, level by level; a tree deeper than the head (e.g. a prompt chain) is not expanded
   if (t.max_depth <= c.draft_depths) {
@@ -1056,6 +1117,44 @@ int draft_tree(clover_ctx* x, int32_t batch, const float* hid_acc, const int32_t
       const int n_lvl = t.lvl_off[j + 1] - t.lvl_off[j];
       if (n_lvl == 0) break;
       const int rows = B * n_lvl;
+      if (fused) {
+        // depth j: (AD2 over the parent's state and the node's token embedding, then) FC_j; the FC's K-slice partials
+        // and bias go straight into the head norm; the LM head's partials go straight into the ranking
+        int sp;
+        if (j == 0) {
+          sp = gemm_fast1(x, KC_GEMM_DRAFT, Y, x->w.fc0_w, rows, H, H);
+        } else {
+          const int* nodes = x->d_lvl_nodes + t.lvl_off[j];
+          { Scope s(x, KC_DRAFT_MISC);
+            launch_draft_level(x->d_state, tree_tokens, nodes, x->d_parent, n_lvl, B, R, H, x->w.lm_head, c.vocab,
+                               x->w.ad2.norm, c.rms_eps, A.hi, A.lo, Y.hi, Y.lo, Cc.hi, Cc.lo, x->st); }
+          AdGateArgs g;
+          memset(&g, 0, sizeof(g));
+          g.x = x->d_state; g.ldx = H; g.out = x->d_state; g.ldo = H;
+          g.nodes = nodes; g.parent = x->d_parent; g.n_lvl = n_lvl; g.R = R; g.m = m;
+          g.c_hi = Cc.hi; g.c_lo = Cc.lo; g.ldc = 2 * H;
+          run_ad_fused(x, x->w.ad2, A, Y, rows, g);
+          Planes C2 = Cc;
+          C2.ld = 2 * H;
+          sp = gemm_fast1(x, KC_GEMM_DRAFT, C2, x->fc_w[j], rows, H, 2 * H);
+        }
+        { Scope s(x, KC_RMSNORM);
+          launch_reduce_add_norm(x->d_g, H, x->partial, sp, (size_t)rows * H, H, x->w.head_norm, c.dtype, c.rms_eps, A.hi,
+                                 A.lo, H, rows, H, x->st, j == 0 ? x->w.fc0_b : x->fc_b[j]); }
+        if (x->panel && rows > 16 && panel_gemm_supported(rows, c.vocab, H, 0)) {
+          lm_head_fast(x, A, rows, x->z);
+          Scope s(x, KC_TOPK);
+          launch_topk(x->z, c.vocab, c.vocab, rows, t.kmax[j], x->cand, x->topk_ids, x->st);
+        } else {
+          const int spv = gemm_fast1(x, KC_GEMM_LMHEAD, A, x->lm_head_pk, rows, c.vocab, H);
+          Scope s(x, KC_TOPK);
+          launch_topk(x->partial, c.vocab, c.vocab, rows, t.kmax[j], x->cand, x->topk_ids, x->st, spv, (size_t)rows * c.vocab);
+        }
+        { Scope s(x, KC_DRAFT_MISC);
+          launch_draft_assign(x->topk_ids, x->d_par_row, x->d_rank, t.node_off[j + 1], t.node_off[j + 2], n_lvl, B, R, m,
+                              tree_tokens, x->st); }
+        continue;
+      }
       if (j == 0) {
         run_fc(x, x->d_rootx, H, x->w.fc0_w, x->w.fc0_b, x->d_g, rows);
       } else {

@@ -55,7 +55,9 @@ void launch_ad_gate(const float* x, int ldx, const float* q, const float* k, con
 // top-k of each row of z[rows, V] by (value desc, id asc); k <= CLOVER_MAX_RANK.
 // cand: scratch [rows][chunks][16] of (float,int) pairs; out_ids [rows][16]; chunks = topk_chunks(V).
 int topk_chunks(int V);
-void launch_topk(const float* z, int ldz, int V, int rows, int k, void* cand, int* out_ids, hipStream_t st);
+// z may be given as `splits` partial tiles z[s*split_stride + row*ldz + id] that are summed on the fly (1: plain)
+void launch_topk(const float* z, int ldz, int V, int rows, int k, void* cand, int* out_ids, hipStream_t st, int splits = 1,
+                 size_t split_stride = 0);
 
 // ---- draft-tree bookkeeping -------------------------------------------------------------------
 // gather for level rows: row (b,r) <- node u = lvl_nodes[r]; xs = state[b][parent(u)], e = lm_head[token[b][u]]
@@ -94,9 +96,10 @@ void launch_split_planes(const float* x, int ldx, bf16_t* hi, bf16_t* lo, int ld
 void launch_reduce(const float* P, int splits, size_t split_stride, int ldp, const void* bias, int wdtype, float* Y,
                    int ldy, int M, int N, int mode, hipStream_t st);
 // x[m,:] += sum_s P[s][m][:]  (splits may be 0); then, if gain: (hi, lo)[m,:] = split(rmsnorm(x[m,:]) * gain)
+// bias non-null: x[m,:] = bias + sum_s P[s][m][:] (the old x is not read)
 void launch_reduce_add_norm(float* x, int ldx, const float* P, int splits, size_t split_stride, int ldp,
                             const void* gain, int wdtype, float eps, bf16_t* hi, bf16_t* lo, int ldo, int rows, int H,
-                            hipStream_t st);
+                            hipStream_t st, const void* bias = nullptr);
 
 // ---- MFMA weight-streaming GEMM (bf16 weights, split-bf16 activations in, fp32 out) -------------
 struct MfmaGemm {
@@ -172,6 +175,34 @@ struct PanelGemm {
 };
 bool panel_gemm_supported(int M, int N, int K, int epi);
 void launch_gemm_panel(const PanelGemm& g, hipStream_t st);
+
+// ---- fused bookkeeping kernels of the draft head (MFMA path, bf16 weights) ----------------------
+// planes of RMSNorm(hid[row]) * gain -> (a_hi, a_lo) and of the embedding of tok[row] -> (y_hi, y_lo), rows of `rm`
+void launch_draft_pre(const float* hid, const int* tok, const void* gain, float eps, const void* table, int vocab, int H,
+                      RowMap rm, bf16_t* a_hi, bf16_t* a_lo, bf16_t* y_hi, bf16_t* y_lo, hipStream_t st);
+// Attention-Decoder gate reading the q and (k|v) GEMMs' K-slice partials and adding the biases itself
+struct AdGateArgs {
+  const float* x; int ldx;                    // residual input rows
+  const float* Pq; int Sq; size_t sps_q;      // [Sq][M][H], Sq <= 8
+  const float* Pkv; int Skv; size_t sps_kv;   // [Skv][M][2H]: k columns, then v columns, Skv <= 8
+  const void *bq, *bk, *bv;                   // bf16 [H]
+  int H, heads;
+  const int *nodes, *parent; int n_lvl, R;    // nodes null: row g -> row g; else g = b*n_lvl + r, u = nodes[r]: row b*R+parent[u] -> row b*R+u
+  const int* m;                               // with nodes: sequences with m[b] < 1 are skipped (null: none)
+  float* out; int ldo;
+  const void* gain; float eps; bf16_t *n_hi, *n_lo;   // gain non-null: planes of RMSNorm(result)*gain, row g, ld H
+  bf16_t *c_hi, *c_lo; int ldc;               // non-null: planes of the result, row g
+};
+bool ad_gate_fused_supported(int H, int heads);
+void launch_ad_gate_fused(const AdGateArgs& a, int rows, hipStream_t st);
+// root state/token from the last accepted row, its planes (row b, ld H), aug_len[b] += m[b]
+void launch_draft_root_fused(const float* a, const int* next_tok, const int* m, int B, int R, int H, float* state,
+                             int* tokens, bf16_t* y_hi, bf16_t* y_lo, int* aug_len, hipStream_t st);
+// per internal node r of one depth (u = nodes[r]): planes of RMSNorm(state[parent(u)]) * gain (row b*n_lvl + r, ld H),
+// planes of the embedding of tokens[u] in (y_hi, y_lo) (ld H) and in the second half of (c_hi, c_lo) (ld 2H)
+void launch_draft_level(const float* state, const int* tokens, const int* nodes, const int* parent, int n_lvl, int B,
+                        int R, int H, const void* table, int vocab, const void* gain, float eps, bf16_t* a_hi,
+                        bf16_t* a_lo, bf16_t* y_hi, bf16_t* y_lo, bf16_t* c_hi, bf16_t* c_lo, hipStream_t st);
 
 // ---- persistent phase-program kernel (M <= 64 rows, bf16 weights, head_dim 128) -------------------
 // One cooperative launch walks phases [p_begin, p_end) of a program with a barrier before each phase

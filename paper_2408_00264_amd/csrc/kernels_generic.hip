@@ -453,14 +453,24 @@ constexpr int TOPK_EPT = TOPK_CHUNK / 256;
 int topk_chunks(int V) { return (V + TOPK_CHUNK - 1) / TOPK_CHUNK; }
 
 __global__ __launch_bounds__(256) void topk_stage1_kernel(const float* __restrict__ z, int ldz, int V, int k,
-                                                          unsigned long long* __restrict__ cand) {
+                                                          unsigned long long* __restrict__ cand, int splits,
+                                                          size_t sps) {
   __shared__ unsigned long long red[4];
   const int chunk = blockIdx.x, row = blockIdx.y, chunks = gridDim.x;
   unsigned long long key[TOPK_EPT];
 #pragma unroll
   for (int e = 0; e < TOPK_EPT; ++e) {
     const int id = chunk * TOPK_CHUNK + e * 256 + threadIdx.x;
-    key[e] = id < V ? topk_key(z[(size_t)row * ldz + id], id) : 0ull;
+    float v = 0.f;
+    if (id < V) {
+      float q[8];
+#pragma unroll
+      for (int s = 0; s < 8; ++s) q[s] = s < splits ? z[s * sps + (size_t)row * ldz + id] : 0.f;  // one batch of loads
+#pragma unroll
+      for (int s = 0; s < 8; ++s) v += q[s];  // split order, as the reduce kernel
+      for (int s = 8; s < splits; ++s) v += z[s * sps + (size_t)row * ldz + id];
+    }
+    key[e] = id < V ? topk_key(v, id) : 0ull;
   }
   for (int r = 0; r < k; ++r) {
     unsigned long long best = 0ull;
@@ -497,10 +507,11 @@ __global__ __launch_bounds__(256) void topk_stage2_kernel(const unsigned long lo
   }
 }
 
-void launch_topk(const float* z, int ldz, int V, int rows, int k, void* cand, int* out_ids, hipStream_t st) {
+void launch_topk(const float* z, int ldz, int V, int rows, int k, void* cand, int* out_ids, hipStream_t st, int splits,
+                 size_t split_stride) {
   if (rows <= 0) return;
   const int chunks = topk_chunks(V);  // chunks * k <= 2048 is checked at init (vocab <= 262144)
-  topk_stage1_kernel<<<dim3(chunks, rows), 256, 0, st>>>(z, ldz, V, k, (unsigned long long*)cand);
+  topk_stage1_kernel<<<dim3(chunks, rows), 256, 0, st>>>(z, ldz, V, k, (unsigned long long*)cand, splits, split_stride);
   topk_stage2_kernel<<<rows, 256, 0, st>>>((const unsigned long long*)cand, chunks, k, out_ids);
 }
 
@@ -769,14 +780,15 @@ __global__ __launch_bounds__(1024) void reduce_add_norm_kernel(float* __restrict
                                                                const float* __restrict__ P, int splits, size_t sps,
                                                                int ldp, const WT* __restrict__ gain, float eps,
                                                                bf16_t* __restrict__ hi, bf16_t* __restrict__ lo,
-                                                               int ldo, int H) {
+                                                               int ldo, int H, const WT* __restrict__ bias) {
   __shared__ float red[16];
   const size_t row = blockIdx.x;
   float* xr = x + row * ldx;
   const float* pr = P + row * ldp;
   float ss = 0.f;
   for (int c = threadIdx.x * 4; c < H; c += 4096) {
-    float4 v = *(const float4*)(xr + c);
+    float4 v = bias ? make_float4(ldf(bias, c), ldf(bias, c + 1), ldf(bias, c + 2), ldf(bias, c + 3))
+                    : *(const float4*)(xr + c);
     for (int s0 = 0; s0 < splits; s0 += 16) {
       float4 q[16];
 #pragma unroll
@@ -785,7 +797,7 @@ __global__ __launch_bounds__(1024) void reduce_add_norm_kernel(float* __restrict
 #pragma unroll
       for (int j = 0; j < 16; ++j) { v.x += q[j].x; v.y += q[j].y; v.z += q[j].z; v.w += q[j].w; }
     }
-    if (splits > 0) *(float4*)(xr + c) = v;
+    if (splits > 0 || bias) *(float4*)(xr + c) = v;
     ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
   }
   if (!gain) return;
@@ -812,14 +824,14 @@ __global__ __launch_bounds__(1024) void reduce_add_norm_kernel(float* __restrict
 }
 void launch_reduce_add_norm(float* x, int ldx, const float* P, int splits, size_t split_stride, int ldp,
                             const void* gain, int wdtype, float eps, bf16_t* hi, bf16_t* lo, int ldo, int rows, int H,
-                            hipStream_t st) {
+                            hipStream_t st, const void* bias) {
   if (rows <= 0) return;
   if (wdtype == 0)
     reduce_add_norm_kernel<float><<<rows, 1024, 0, st>>>(x, ldx, P, splits, split_stride, ldp, (const float*)gain, eps,
-                                                        hi, lo, ldo, H);
+                                                        hi, lo, ldo, H, (const float*)bias);
   else
     reduce_add_norm_kernel<bf16_t><<<rows, 1024, 0, st>>>(x, ldx, P, splits, split_stride, ldp, (const bf16_t*)gain,
-                                                         eps, hi, lo, ldo, H);
+                                                         eps, hi, lo, ldo, H, (const bf16_t*)bias);
 }
 
 }  // namespace clv
