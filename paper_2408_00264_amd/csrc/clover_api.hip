@@ -76,6 +76,7 @@ struct clover_ctx {
   const void* lm_head_pk;
   bool fast;               // bf16 model on the MFMA path
   bool panel;              // full-K panel GEMM for the gate+up projection and the LM head
+  int row_batch_max = 64;  // passes of up to this many rows run through the <= 64-row GEMM kernels, in batches of 64
   // persistent phase-program kernel (one cooperative launch per verify pass)
   bool mega = false;       // usable for this model on this device
   bool mega_phases = false;  // debugging / profiling: one launch per phase
@@ -289,6 +290,15 @@ void carve(clover_ctx* x, char* base, size_t* total) {
         pbytes = std::max(pbytes, (size_t)sp * mtot * s.N * sizeof(float));
       }
     }
+    // 65..256 rows in batches of 64 through the K-slice kernel: partial tiles of the whole pass
+    if (rows > 64 && !getenv("CLOVER_NO_ROW_BATCH")) {
+      std::vector<GemmShape> shp;
+      model_gemm_shapes(c, shp);
+      const int rb = std::min(rows, 256);
+      for (const GemmShape& g : shp)
+        if (g.mode != 2 && g.N != c.vocab && g.N != 2 * c.ffn && stream_gemm_supported(64, g.N, g.K))
+          pbytes = std::max(pbytes, stream_gemm_out_bytes(rb, g.N, g.K));
+    }
     // the persistent kernel writes up to 8 K-group partials of its QKV / Wo / down projections
     pbytes = std::max(pbytes, (size_t)8 * std::min(rows, 64) * std::max(x->QKVN, H) * sizeof(float));
     const size_t layer_elems = (size_t)x->QKVN * H + (size_t)H * x->NQD + (size_t)3 * c.ffn * H;
@@ -299,6 +309,7 @@ void carve(clover_ctx* x, char* base, size_t* total) {
   x->packed = cv.take<char>(packed_bytes ? packed_bytes : 256);
   x->fast = fast;
   x->panel = fast && !getenv("CLOVER_NO_PANEL");
+  x->row_batch_max = (fast && !getenv("CLOVER_NO_ROW_BATCH")) ? 256 : 64;
   x->kvdtype = fast ? 1 : 0;
   x->kv_layer_stride = fast ? 2 * x->k_layer_elems : x->k_layer_elems;
   x->attn_fast = fast && attn_mfma_supported(d, c.n_q_heads, c.n_kv_heads, c.max_seq);
@@ -371,16 +382,22 @@ int gemm_fast(clover_ctx* x, int cls, Planes X, int nseg, const void* const* W, 
       if (s < nseg) { segb[s] = off; off += seg_n[s]; }
     }
   }
-  if (M <= 64 && stream_gemm_supported(M, N, K) && stream_gemm_out_bytes(M, N, K) <= x->partial_bytes) {
-    StreamGemm g;
-    memset(&g, 0, sizeof(g));
-    g.Xhi = X.hi; g.Xlo = X.lo; g.ldx = X.ld;
-    for (int s = 0; s < 3; ++s) { g.W[s] = ws[s]; g.seg_begin[s] = segb[s]; }
-    g.seg_begin[3] = 0x7fffffff;
-    g.Y = part; g.ldy = N; g.split_stride = (size_t)M * N;
-    g.M = M; g.N = N; g.K = K;
-    g.tag = cls == KC_GEMM_GATEUP ? 1 : 0;
-    launch_gemm_stream(g, x->st);
+  // Up to 64 rows: the K-slice kernel.  65..256 rows: the same kernel over batches of 64 rows -- the weights are
+  // streamed once per batch, which still beats the tiled kernel (each of its wavefronts multiplies ALL rows and is
+  // bound by the LDS reads of the activations).
+  if (M <= x->row_batch_max && stream_gemm_supported(std::min(M, 64), N, K) &&
+      stream_gemm_out_bytes(M, N, K) <= x->partial_bytes) {
+    for (int m0 = 0; m0 < M; m0 += 64) {
+      StreamGemm g;
+      memset(&g, 0, sizeof(g));
+      g.Xhi = X.hi + (size_t)m0 * X.ld; g.Xlo = X.lo + (size_t)m0 * X.ld; g.ldx = X.ld;
+      for (int s = 0; s < 3; ++s) { g.W[s] = ws[s]; g.seg_begin[s] = segb[s]; }
+      g.seg_begin[3] = 0x7fffffff;
+      g.Y = part + (size_t)m0 * N; g.ldy = N; g.split_stride = (size_t)M * N;
+      g.M = std::min(64, M - m0); g.N = N; g.K = K;
+      g.tag = cls == KC_GEMM_GATEUP ? 1 : 0;
+      launch_gemm_stream(g, x->st);
+    }
     const int sp = stream_gemm_slices(K);
     if (direct) launch_reduce(part, sp, (size_t)M * N, N, nullptr, x->cfg.dtype, direct, ld_direct, M, N, 0, x->st);
     return direct ? 1 : sp;
@@ -471,15 +488,17 @@ void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMa
     { Scope s(x, KC_RMSNORM);
       launch_reduce_add_norm(xres, H, x->partial, sw, (size_t)M * H, H, lw.ffn_norm, c.dtype, c.rms_eps, A.hi, A.lo, H, M,
                              H, x->st); }
-    if (x->panel && panel_gemm_supported(M, F, H, 1)) {
+    if (x->panel && M <= x->row_batch_max && panel_gemm_supported(std::min(M, 64), F, H, 1)) {
       Scope s(x, KC_GEMM_GATEUP);
-      PanelGemm g;
-      memset(&g, 0, sizeof(g));
-      g.Xhi = A.hi; g.Xlo = A.lo; g.ldx = H;
-      g.W[0] = (const bf16_t*)lw.w_gate; g.W[1] = (const bf16_t*)lw.w_up;
-      g.Yhi = Hf.hi; g.Ylo = Hf.lo; g.ldo = F;
-      g.M = M; g.N = F; g.K = H; g.epi = 1;
-      launch_gemm_panel(g, x->st);
+      for (int m0 = 0; m0 < M; m0 += 64) {  // (more than 64 rows: batches of 64, see gemm_fast)
+        PanelGemm g;
+        memset(&g, 0, sizeof(g));
+        g.Xhi = A.hi + (size_t)m0 * H; g.Xlo = A.lo + (size_t)m0 * H; g.ldx = H;
+        g.W[0] = (const bf16_t*)lw.w_gate; g.W[1] = (const bf16_t*)lw.w_up;
+        g.Yhi = Hf.hi + (size_t)m0 * F; g.Ylo = Hf.lo + (size_t)m0 * F; g.ldo = F;
+        g.M = std::min(64, M - m0); g.N = F; g.K = H; g.epi = 1;
+        launch_gemm_panel(g, x->st);
+      }
     } else if (M <= 64 && stream_gemm_supported(M, 2 * F, H) && stream_gemm_out_bytes(M, 2 * F, H) <= x->partial_bytes) {
       const void* wgu[2] = {lw.w_gate, lw.w_up};
       const int gun[2] = {F, F};
@@ -794,15 +813,17 @@ void run_fc(clover_ctx* x, const float* X, int K, const void* W, const void* bia
 // out[rows, vocab] = A * lm_head^T (MFMA path)
 void lm_head_fast(clover_ctx* x, Planes A, int rows, float* out) {
   const clover_config& c = x->cfg;
-  if (x->panel && rows > 16 && panel_gemm_supported(rows, c.vocab, x->H, 0)) {
+  if (x->panel && rows <= x->row_batch_max && panel_gemm_supported(std::min(rows, 64), c.vocab, x->H, 0)) {
     Scope s(x, KC_GEMM_LMHEAD);
-    PanelGemm g;
-    memset(&g, 0, sizeof(g));
-    g.Xhi = A.hi; g.Xlo = A.lo; g.ldx = A.ld;
-    g.W[0] = g.W[1] = (const bf16_t*)x->lm_head_pk;
-    g.Y = out; g.ldy = c.vocab;
-    g.M = rows; g.N = c.vocab; g.K = x->H; g.epi = 0;
-    launch_gemm_panel(g, x->st);
+    for (int m0 = 0; m0 < rows; m0 += 64) {  // (more than 64 rows: batches of 64, see gemm_fast)
+      PanelGemm g;
+      memset(&g, 0, sizeof(g));
+      g.Xhi = A.hi + (size_t)m0 * A.ld; g.Xlo = A.lo + (size_t)m0 * A.ld; g.ldx = A.ld;
+      g.W[0] = g.W[1] = (const bf16_t*)x->lm_head_pk;
+      g.Y = out + (size_t)m0 * c.vocab; g.ldy = c.vocab;
+      g.M = std::min(64, rows - m0); g.N = c.vocab; g.K = x->H; g.epi = 0;
+      launch_gemm_panel(g, x->st);
+    }
     return;
   }
   gemm_fast1(x, KC_GEMM_LMHEAD, A, x->lm_head_pk, rows, c.vocab, x->H, out, c.vocab);
@@ -1141,7 +1162,7 @@ int draft_tree(clover_ctx* x, int32_t batch, const float* hid_acc, const int32_t
         { Scope s(x, KC_RMSNORM);
           launch_reduce_add_norm(x->d_g, H, x->partial, sp, (size_t)rows * H, H, x->w.head_norm, c.dtype, c.rms_eps, A.hi,
                                  A.lo, H, rows, H, x->st, j == 0 ? x->w.fc0_b : x->fc_b[j]); }
-        if (x->panel && rows > 16 && panel_gemm_supported(rows, c.vocab, H, 0)) {
+        if (x->panel && panel_gemm_supported(std::min(rows, 64), c.vocab, H, 0)) {
           lm_head_fast(x, A, rows, x->z);
           Scope s(x, KC_TOPK);
           launch_topk(x->z, c.vocab, c.vocab, rows, t.kmax[j], x->cand, x->topk_ids, x->st);
