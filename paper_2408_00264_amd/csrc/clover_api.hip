@@ -382,6 +382,23 @@ int gemm_fast(clover_ctx* x, int cls, Planes X, int nseg, const void* const* W, 
       if (s < nseg) { segb[s] = off; off += seg_n[s]; }
     }
   }
+  // Long K into a narrow output (the down projection): K ranges of the panel kernel, a few partials instead of
+  // one per 512 columns
+  if (x->panel && !direct && nseg == 1 && M <= x->row_batch_max) {
+    const int kp = panel_gemm_pick_k_parts(std::min(M, 64), N, K);
+    if (kp > 1 && (size_t)kp * M * N * sizeof(float) <= x->partial_bytes) {
+      for (int m0 = 0; m0 < M; m0 += 64) {
+        PanelGemm g;
+        memset(&g, 0, sizeof(g));
+        g.Xhi = X.hi + (size_t)m0 * X.ld; g.Xlo = X.lo + (size_t)m0 * X.ld; g.ldx = X.ld;
+        g.W[0] = g.W[1] = ws[0];
+        g.Y = part + (size_t)m0 * N; g.ldy = N; g.k_parts = kp; g.split_stride = (size_t)M * N;
+        g.M = std::min(64, M - m0); g.N = N; g.K = K; g.epi = 0;
+        launch_gemm_panel(g, x->st);
+      }
+      return kp;
+    }
+  }
   // Up to 64 rows: the K-slice kernel.  65..256 rows: the same kernel over batches of 64 rows -- the weights are
   // streamed once per batch, which still beats the tiled kernel (each of its wavefronts multiplies ALL rows and is
   // bound by the LDS reads of the activations).
@@ -1371,6 +1388,7 @@ size_t clover_op_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K) {
   if (M <= 256 && mfma_gemm_supported(M, N, K, 0)) {
     size_t out = mfma_gemm_out_bytes(M, N, mfma_gemm_pick_splits(M, N, K, 0));
     if (stream_gemm_supported(M, N, K)) out = std::max(out, stream_gemm_out_bytes(M, N, K));
+    out = std::max(out, (size_t)std::max(panel_gemm_pick_k_parts(M, N, K), 0) * M * N * sizeof(float));
     bytes += align256((size_t)M * K * 4) + align256(out) + align256((size_t)N * K * 2);
   }
   return bytes;
@@ -1393,7 +1411,7 @@ int clover_op_gemm(int32_t path, int32_t dtype, const float* X, const void* W, f
     bf16_t* hi = (bf16_t*)((char*)scratch + align256((size_t)N * K * 2));
     bf16_t* lo = hi + (size_t)M * K;
     float* part = (float*)((char*)hi + align256((size_t)M * K * 4));
-    if (path == 1 || path == 3) launch_pack_weight(W, wp, N, K, st);
+    if (path & 1) launch_pack_weight(W, wp, N, K, st);
     launch_split_planes(X, K, hi, lo, K, M, K, st);
     int splits;
     if (path >= 3) {
@@ -1404,7 +1422,15 @@ int clover_op_gemm(int32_t path, int32_t dtype, const float* X, const void* W, f
       g.Xhi = hi; g.Xlo = lo; g.ldx = K;
       g.W[0] = g.W[1] = wp;
       g.Y = Y; g.ldy = ldy; g.M = M; g.N = N; g.K = K; g.epi = 0;
-      launch_gemm_panel(g, st);
+      if (path >= 5) {  // K ranges into partials, then the reduction every consumer of partials performs
+        const int kp = panel_gemm_pick_k_parts(M, N, K);
+        if (kp < 2) return fail(nullptr, CLOVER_E_SHAPE, "shape not supported by the K-range panel GEMM");
+        g.Y = part; g.ldy = N; g.k_parts = kp; g.split_stride = (size_t)M * N;
+        launch_gemm_panel(g, st);
+        launch_reduce(part, kp, (size_t)M * N, N, nullptr, dtype, Y, ldy, M, N, 0, st);
+      } else {
+        launch_gemm_panel(g, st);
+      }
       const hipError_t e = hipGetLastError();
       if (e != hipSuccess) return fail(nullptr, CLOVER_E_HIP, hipGetErrorString(e));
       return CLOVER_OK;

@@ -171,9 +171,12 @@ struct PanelGemm {
   bf16_t *Yhi, *Ylo; int ldo;         // epi 1: planes of silu(X W0^T) * (X W1^T), [M, N]
   int M, N, K;
   int epi;                            // 0 plain, 1 SwiGLU
+  int k_parts; size_t split_stride;   // epi 0 only: K is cut into k_parts ranges, range r writes Y + r * split_stride
   int dbg;                            // timing experiments only (CLOVER_PANEL_DBG): 1 no activation loads
 };
 bool panel_gemm_supported(int M, int N, int K, int epi);
+// how many K ranges make the plain panel GEMM fill the chip for a NARROW output (0: not worth it)
+int panel_gemm_pick_k_parts(int M, int N, int K);
 void launch_gemm_panel(const PanelGemm& g, hipStream_t st);
 
 // ---- fused bookkeeping kernels of the draft head (MFMA path, bf16 weights) ----------------------

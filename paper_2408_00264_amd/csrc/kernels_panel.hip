@@ -71,7 +71,8 @@ __global__ __launch_bounds__(PN_WAVES * 64) void gemm_panel_kernel(PanelGemm p) 
   const int l16 = lane & 15, g4 = lane >> 4;
   const int uw = wave / KW, kp = wave % KW;
   const int KT = p.K / 32;
-  const int NS = p.K / PN_KST;
+  const int NS = p.K / PN_KST / p.k_parts;      // stages of this workgroup's K range
+  const int ks0 = blockIdx.y * NS;              // its first stage
   // Workgroups start at different K stages: all weight blocks have the same power-of-two size, and
   // walking them in lock-step would keep every workgroup on the same few HBM channels.
   const int rot = (p.dbg & 2) ? 0 : blockIdx.x % NS;
@@ -103,7 +104,7 @@ __global__ __launch_bounds__(PN_WAVES * 64) void gemm_panel_kernel(PanelGemm p) 
 
   auto load_w = [&](auto bufc, int s) {
     constexpr int buf = decltype(bufc)::value;
-    const int ks = (s + rot) % NS;
+    const int ks = ks0 + (s + rot) % NS;
     const size_t off = (size_t)(ks * 8 + kp * CH) * 512;
 #pragma unroll
     for (int f = 0; f < PN_NFW; ++f)
@@ -112,7 +113,7 @@ __global__ __launch_bounds__(PN_WAVES * 64) void gemm_panel_kernel(PanelGemm p) 
   };
   u32x4 xv[XIT];
   auto x_load = [&](int s) {
-    const int ks = (s + rot) % NS;
+    const int ks = ks0 + (s + rot) % NS;
 #pragma unroll
     for (int it = 0; it < XIT; ++it) {
       const int idx = it * (PN_WAVES * 64) + tid;
@@ -229,7 +230,7 @@ __global__ __launch_bounds__(PN_WAVES * 64) void gemm_panel_kernel(PanelGemm p) 
       for (int mb = 0; mb < MT; ++mb) {
         const int m = mb * 16 + l16;
         const f32x4 v = acc[f][mb];
-        if (m < p.M) *(float4*)(p.Y + (size_t)m * p.ldy + col) = make_float4(v[0], v[1], v[2], v[3]);
+        if (m < p.M) *(float4*)(p.Y + blockIdx.y * p.split_stride + (size_t)m * p.ldy + col) = make_float4(v[0], v[1], v[2], v[3]);
       }
     }
   }
@@ -243,7 +244,7 @@ void launch_panel_one(const PanelGemm& g, int wgs, hipStream_t st) {
     hipFuncSetAttribute((const void*)gemm_panel_kernel<MT, KW, EPI, NBUF>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_done = true;
   }
-  gemm_panel_kernel<MT, KW, EPI, NBUF><<<wgs, PN_WAVES * 64, lds, st>>>(g);
+  gemm_panel_kernel<MT, KW, EPI, NBUF><<<dim3(wgs, g.k_parts), PN_WAVES * 64, lds, st>>>(g);
 }
 
 }  // namespace
@@ -255,12 +256,35 @@ bool panel_gemm_supported(int M, int N, int K, int epi) {
   return true;
 }
 
+// Narrow outputs (N = hidden) have too few 16-column blocks to give every CU a full-K panel, so K
+// is cut into ranges and each range writes its own fp32 partial, as the K-slice kernel does -- but
+// with 4 blocks x 2 k-parts per workgroup a range is several thousand columns long, i.e. a handful
+// of partials instead of one per 512 columns (K = 14336: 8 instead of 28, 21 MB less to write and
+// read back per call).  Picks the largest divisor of the stage count that keeps the grid within
+// one workgroup per CU; 0 when that leaves CUs idle or ranges shorter than 4 stages.
+int panel_gemm_pick_k_parts(int M, int N, int K) {
+  if (!panel_gemm_supported(M, N, K, 0) || N % 32 != 0) return 0;
+  const int wgs_n = (N / 32 + 3) / 4, NS = K / PN_KST;
+  int best = 0;
+  for (int d = 1; d <= NS; ++d)
+    if (NS % d == 0 && wgs_n * d <= 256 && NS / d >= 4) best = d;
+  return (best > 1 && wgs_n * best >= 224) ? best : 0;
+}
+
 void launch_gemm_panel(const PanelGemm& g_in, hipStream_t st) {
   static const int dbg = [] { const char* v = getenv("CLOVER_PANEL_DBG"); return v ? atoi(v) : 0; }();
   PanelGemm g = g_in;
   g.dbg = dbg;
   const int n_blocks = g.N / 16;
   const bool small = g.M <= 16;
+  if (g.epi == 0 && g.k_parts > 1) {
+    // K ranges: 4 units of two blocks x 2 k-parts per workgroup
+    const int wgs = ((n_blocks + 1) / 2 + 3) / 4;
+    if (small) launch_panel_one<1, 2, 0, 2>(g, wgs, st);
+    else launch_panel_one<4, 2, 0, 2>(g, wgs, st);
+    return;
+  }
+  g.k_parts = 1; g.split_stride = 0;
   if (g.epi == 1) {
     // gate+up: 4 units x 2 k-parts per workgroup (896 blocks -> 224 workgroups for F = 14336)
     const int wgs = (n_blocks + 3) / 4;

@@ -36,6 +36,8 @@ GEMM_CASES = [
     # full-K panel kernel: odd block count, ragged rows, one row, LM-head width
     (3, 1, 64, 28672, 4096), (3, 1, 17, 1040, 768), (3, 1, 5, 4096, 512), (3, 1, 64, 160, 256), (3, 1, 1, 2064, 256),
     (3, 1, 33, 128256, 4096),
+    # panel kernel over K ranges (the down projection's shape): full and ragged rows, one row
+    (5, 1, 64, 4096, 14336), (5, 1, 37, 4096, 14336), (5, 1, 1, 4096, 14336), (5, 1, 16, 4096, 8192),
 ]
 
 
