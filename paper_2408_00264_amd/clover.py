@@ -62,7 +62,7 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     global _lib
     if _lib is not None and path is None:
         return _lib
-    p = path or LIB_PATH
+    p = path or os.environ.get("CLOVER_LIBRARY") or LIB_PATH   # CLOVER_LIBRARY: another build of the same sources
     if not os.path.exists(p):
         raise RuntimeError(f"{p} is missing: build it with `python -m paper_2408_00264_amd.build` "
                            "(there is no CPU fallback)")

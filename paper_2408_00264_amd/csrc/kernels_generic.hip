@@ -210,10 +210,112 @@ __global__ void rope_kv_write_kernel(const float* __restrict__ qkv, int ldqkv, i
   }
 }
 
+// The same operation for the MFMA path's formats (q as pre-scaled bf16 planes, bf16-plane caches), vectorised:
+// a thread of the first blocks rotates four adjacent pairs of one head (float4 loads of every partial, issued
+// before anything else is waited for; 8-byte plane stores); the last blocks transpose 64 nodes x 32 channels of V
+// through LDS so that the partials are read along the channels and V^T is written along the nodes.
+__device__ __forceinline__ void planes4(bf16_t* hi, bf16_t* lo, size_t off, const float (&o)[4]) {
+  unsigned h[4], l[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const bf16_t hb = f32_to_bf16(o[r]);
+    h[r] = hb;
+    l[r] = f32_to_bf16(o[r] - bf16_to_f32(hb));
+  }
+  *(uint2*)(hi + off) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+  *(uint2*)(lo + off) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
+}
+__device__ __forceinline__ float4 sum_partials4(const float* __restrict__ p, int nsp, size_t sps) {
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int s0 = 0; s0 < nsp; s0 += 8) {
+    float4 q[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) q[j] = (s0 + j < nsp) ? *(const float4*)(p + (size_t)(s0 + j) * sps) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { v.x += q[j].x; v.y += q[j].y; v.z += q[j].z; v.w += q[j].w; }
+  }
+  return v;
+}
+__global__ __launch_bounds__(256) void rope_kv_planes_kernel(const float* __restrict__ qkv, int ldqkv, int nsp, size_t sps,
+                                                             const float* __restrict__ cos_t, const float* __restrict__ sin_t,
+                                                             bf16_t* __restrict__ kc, bf16_t* __restrict__ vc, KVLayout kv,
+                                                             const int* __restrict__ base_len, int n_q, RowMap rm,
+                                                             int* err_flag, int qk_blocks, bf16_t* __restrict__ q_hi,
+                                                             bf16_t* __restrict__ q_lo, int ldq, float q_scale) {
+  __shared__ float tile[64][33];
+  const int b = blockIdx.y, tid = threadIdx.x;
+  const int d = kv.d, half = d / 2, n_kv = kv.n_kv;
+  if ((int)blockIdx.x < qk_blocks) {
+    const int quads = half / 4, per_row = (n_q + n_kv) * quads;
+    const int idx = blockIdx.x * 256 + tid;
+    const int i = idx / per_row, rem = idx - i * per_row, hh = rem / quads, ii = (rem - hh * quads) * 4;
+    const size_t row = (size_t)b * rm.R + min(i, rm.n - 1);
+    const float* src = qkv + row * ldqkv + hh * d + ii;
+    const float4 x1 = sum_partials4(src, nsp, sps), x2 = sum_partials4(src + half, nsp, sps);
+    const float4 c = *(const float4*)(cos_t + row * half + ii), s = *(const float4*)(sin_t + row * half + ii);
+    const int nv = rows_valid(rm, b), L = base_len[b];
+    if (L + nv > kv.max_seq) {  // would overrun the cache: refuse, flag
+      if (tid == 0 && blockIdx.x == 0) atomicOr(err_flag, 1);
+      return;
+    }
+    if (i >= nv) return;
+    float o1[4] = {x1.x * c.x - x2.x * s.x, x1.y * c.y - x2.y * s.y, x1.z * c.z - x2.z * s.z, x1.w * c.w - x2.w * s.w};
+    float o2[4] = {x2.x * c.x + x1.x * s.x, x2.y * c.y + x1.y * s.y, x2.z * c.z + x1.z * s.z, x2.w * c.w + x1.w * s.w};
+    if (hh < n_q) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) { o1[r] *= q_scale; o2[r] *= q_scale; }
+      planes4(q_hi, q_lo, row * ldq + hh * d + ii, o1);
+      planes4(q_hi, q_lo, row * ldq + hh * d + ii + half, o2);
+    } else {
+      const size_t base = (((size_t)b * kv.max_seq + L + i) * n_kv + (hh - n_q)) * d + ii;
+      planes4(kc, kc + kv.plane, base, o1);
+      planes4(kc, kc + kv.plane, base + half, o2);
+    }
+  } else {
+    const int n_eb = n_kv * d / 32;
+    const int vblk = blockIdx.x - qk_blocks, eb = vblk % n_eb, nb0 = (vblk / n_eb) * 64;
+    const int voff = (n_q + n_kv) * d + eb * 32;
+    float4 v[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int f = tid + 256 * j, node = min(nb0 + f / 8, rm.n - 1), e4 = (f % 8) * 4;
+      v[j] = sum_partials4(qkv + ((size_t)b * rm.R + node) * ldqkv + voff + e4, nsp, sps);
+    }
+    const int nv = rows_valid(rm, b), L = base_len[b];
+    if (L + nv > kv.max_seq) return;  // (flagged by the first block)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int f = tid + 256 * j, e4 = (f % 8) * 4;
+      tile[f / 8][e4] = v[j].x; tile[f / 8][e4 + 1] = v[j].y; tile[f / 8][e4 + 2] = v[j].z; tile[f / 8][e4 + 3] = v[j].w;
+    }
+    __syncthreads();
+    const int nl = tid % 64, node = nb0 + nl;
+    if (node >= nv) return;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int e = tid / 64 + 4 * j;
+      const float val = tile[nl][e];
+      const size_t at = ((size_t)b * n_kv * d + eb * 32 + e) * kv.max_seq + L + node;
+      const bf16_t hb = f32_to_bf16(val);
+      vc[at] = hb;
+      vc[at + kv.plane] = f32_to_bf16(val - bf16_to_f32(hb));
+    }
+  }
+}
+
 void launch_rope_kv_write(const float* qkv, int ldqkv, int qkv_splits, size_t qkv_split_stride, const float* cos_t,
                           const float* sin_t, float* q_out, int ldq,
                           void* k_cache, void* v_cache, int kvdtype, KVLayout kv, const int* base_len, int n_q,
                           RowMap rm, int* err_flag, bf16_t* q_hi, bf16_t* q_lo, float q_scale, hipStream_t st) {
+  if (kvdtype == 1 && q_hi && kv.d % 32 == 0 && ldqkv % 4 == 0 && qkv_split_stride % 4 == 0 && ldq % 4 == 0) {
+    const int per_row = (n_q + kv.n_kv) * (kv.d / 8);
+    const int qk_blocks = (rm.n * per_row + 255) / 256;
+    const int v_blocks = (kv.n_kv * kv.d / 32) * ((rm.n + 63) / 64);
+    rope_kv_planes_kernel<<<dim3(qk_blocks + v_blocks, rm.B), 256, 0, st>>>(
+        qkv, ldqkv, qkv_splits, qkv_split_stride, cos_t, sin_t, (bf16_t*)k_cache, (bf16_t*)v_cache, kv, base_len, n_q, rm,
+        err_flag, qk_blocks, q_hi, q_lo, ldq, q_scale);
+    return;
+  }
   const int vblocks = (kv.n_kv * kv.d + 7) / 8;
   const int hc = ((n_q + kv.n_kv) * (kv.d / 2) + 255) / 256;
   dim3 grid(rm.n * hc + vblocks, rm.B);
@@ -774,7 +876,8 @@ void launch_reduce(const float* P, int splits, size_t split_stride, int ldp, con
 }
 
 // one 1024-thread block per row: residual add of the split-K partials (sixteen loads in flight per
-// thread, summed in split order), then RMSNorm written as planes
+// thread, summed in split order), then RMSNorm written as planes.  A thread keeps its (up to two)
+// float4 of the new row in registers across the block-wide sum of squares; wider rows re-read them.
 template <typename WT>
 __global__ __launch_bounds__(1024) void reduce_add_norm_kernel(float* __restrict__ x, int ldx,
                                                                const float* __restrict__ P, int splits, size_t sps,
@@ -786,7 +889,7 @@ __global__ __launch_bounds__(1024) void reduce_add_norm_kernel(float* __restrict
   float* xr = x + row * ldx;
   const float* pr = P + row * ldp;
   float ss = 0.f;
-  for (int c = threadIdx.x * 4; c < H; c += 4096) {
+  auto new_row = [&](int c) -> float4 {
     float4 v = bias ? make_float4(ldf(bias, c), ldf(bias, c + 1), ldf(bias, c + 2), ldf(bias, c + 3))
                     : *(const float4*)(xr + c);
     for (int s0 = 0; s0 < splits; s0 += 16) {
@@ -799,7 +902,20 @@ __global__ __launch_bounds__(1024) void reduce_add_norm_kernel(float* __restrict
     }
     if (splits > 0 || bias) *(float4*)(xr + c) = v;
     ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    return v;
+  };
+  auto gain4 = [&](int c) { return make_float4(ldf(gain, c), ldf(gain, c + 1), ldf(gain, c + 2), ldf(gain, c + 3)); };
+  const int c0 = threadIdx.x * 4;
+  float4 keep[2], gn[2];
+#pragma unroll
+  for (int it = 0; it < 2; ++it) {  // (static indices: the two kept pieces live in registers)
+    const int c = c0 + it * 4096;
+    if (c < H) {
+      if (gain) gn[it] = gain4(c);
+      keep[it] = new_row(c);
+    }
   }
+  for (int c = c0 + 8192; c < H; c += 4096) new_row(c);
   if (!gain) return;
   ss = wave_sum(ss);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
@@ -808,10 +924,8 @@ __global__ __launch_bounds__(1024) void reduce_add_norm_kernel(float* __restrict
 #pragma unroll
   for (int w = 0; w < 16; ++w) tot += red[w];
   const float scale = 1.0f / sqrtf(tot / (float)H + eps);
-  for (int c = threadIdx.x * 4; c < H; c += 4096) {
-    const float4 v = *(const float4*)(xr + c);   // written by this same thread above
-    const float o[4] = {v.x * scale * ldf(gain, c), v.y * scale * ldf(gain, c + 1), v.z * scale * ldf(gain, c + 2),
-                        v.w * scale * ldf(gain, c + 3)};
+  auto emit = [&](int c, float4 v, float4 g4) {
+    const float o[4] = {v.x * scale * g4.x, v.y * scale * g4.y, v.z * scale * g4.z, v.w * scale * g4.w};
     bf16_t h[4], l[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -820,7 +934,13 @@ __global__ __launch_bounds__(1024) void reduce_add_norm_kernel(float* __restrict
     }
     *(uint2*)(hi + row * ldo + c) = make_uint2((unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16));
     *(uint2*)(lo + row * ldo + c) = make_uint2((unsigned)l[0] | ((unsigned)l[1] << 16), (unsigned)l[2] | ((unsigned)l[3] << 16));
+  };
+#pragma unroll
+  for (int it = 0; it < 2; ++it) {
+    const int c = c0 + it * 4096;
+    if (c < H) emit(c, keep[it], gn[it]);
   }
+  for (int c = c0 + 8192; c < H; c += 4096) emit(c, *(const float4*)(xr + c), gain4(c));  // written by this same thread above
 }
 void launch_reduce_add_norm(float* x, int ldx, const float* P, int splits, size_t split_stride, int ldp,
                             const void* gain, int wdtype, float eps, bf16_t* hi, bf16_t* lo, int ldo, int rows, int H,

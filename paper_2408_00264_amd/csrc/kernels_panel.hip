@@ -75,7 +75,8 @@ __global__ __launch_bounds__(PN_WAVES * 64) void gemm_panel_kernel(PanelGemm p) 
   const int ks0 = blockIdx.y * NS;              // its first stage
   // Workgroups start at different K stages: all weight blocks have the same power-of-two size, and
   // walking them in lock-step would keep every workgroup on the same few HBM channels.
-  const int rot = (p.dbg & 2) ? 0 : blockIdx.x % NS;
+  // (a launch of more than one workgroup per CU staggers by itself, and measured faster unrotated)
+  const int rot = ((p.dbg & 2) || gridDim.x * gridDim.y > 256) ? 0 : blockIdx.x % NS;
   const int n_blocks = p.N / 16;                // 16-column blocks of the output
   // EPI 1: unit = one 16-column block (fragments: gate rows, up rows); EPI 0: unit = two adjacent blocks
   const int unit = blockIdx.x * UW + uw;
