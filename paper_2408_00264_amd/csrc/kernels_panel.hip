@@ -72,14 +72,19 @@ __global__ __launch_bounds__(PN_WAVES * 64) void gemm_panel_kernel(PanelGemm p) 
   const int uw = wave / KW, kp = wave % KW;
   const int KT = p.K / 32;
   const int NS = p.K / PN_KST / p.k_parts;      // stages of this workgroup's K range
-  const int ks0 = blockIdx.y * NS;              // its first stage
+  // K range = workgroup id % k_parts: workgroups are dealt to the 8 XCDs round-robin, so with 8 ranges
+  // every XCD's L2 holds ONE range of the activations instead of all of them (K = 14336: the whole
+  // 3.7 MB matrix would not stay in a 4 MB L2 beside the weight stream and was fetched again and again)
+  const int part = p.k_parts > 1 ? (int)blockIdx.x % p.k_parts : 0;
+  const int wg = p.k_parts > 1 ? (int)blockIdx.x / p.k_parts : (int)blockIdx.x;
+  const int ks0 = part * NS;                    // its first stage
   // Workgroups start at different K stages: all weight blocks have the same power-of-two size, and
   // walking them in lock-step would keep every workgroup on the same few HBM channels.
   // (a launch of more than one workgroup per CU staggers by itself, and measured faster unrotated)
-  const int rot = ((p.dbg & 2) || gridDim.x * gridDim.y > 256) ? 0 : blockIdx.x % NS;
+  const int rot = ((p.dbg & 2) || gridDim.x > 256) ? 0 : wg % NS;
   const int n_blocks = p.N / 16;                // 16-column blocks of the output
   // EPI 1: unit = one 16-column block (fragments: gate rows, up rows); EPI 0: unit = two adjacent blocks
-  const int unit = blockIdx.x * UW + uw;
+  const int unit = wg * UW + uw;
   int nb[PN_NFW];
   const bf16_t* wbase[PN_NFW];
   bool live;
@@ -231,7 +236,7 @@ __global__ __launch_bounds__(PN_WAVES * 64) void gemm_panel_kernel(PanelGemm p) 
       for (int mb = 0; mb < MT; ++mb) {
         const int m = mb * 16 + l16;
         const f32x4 v = acc[f][mb];
-        if (m < p.M) *(float4*)(p.Y + blockIdx.y * p.split_stride + (size_t)m * p.ldy + col) = make_float4(v[0], v[1], v[2], v[3]);
+        if (m < p.M) *(float4*)(p.Y + part * p.split_stride + (size_t)m * p.ldy + col) = make_float4(v[0], v[1], v[2], v[3]);
       }
     }
   }
@@ -245,7 +250,7 @@ void launch_panel_one(const PanelGemm& g, int wgs, hipStream_t st) {
     hipFuncSetAttribute((const void*)gemm_panel_kernel<MT, KW, EPI, NBUF>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_done = true;
   }
-  gemm_panel_kernel<MT, KW, EPI, NBUF><<<dim3(wgs, g.k_parts), PN_WAVES * 64, lds, st>>>(g);
+  gemm_panel_kernel<MT, KW, EPI, NBUF><<<wgs * g.k_parts, PN_WAVES * 64, lds, st>>>(g);
 }
 
 }  // namespace
