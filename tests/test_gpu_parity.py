@@ -181,6 +181,20 @@ def test_mha_shape_bf16():
     assert ls.max_logit_err <= 3e-2
 
 
+@pytest.mark.parametrize("bf16", [False, True], ids=["fp32", "bf16"])
+def test_paper_size_head_two_aug_layers_five_depths(bf16):
+    """The draft head at the paper's size (Sec. 3.3, 4.1): two augmenting layers, five depths (FC_1..FC_4)."""
+    _torch()
+    shape = synth.scaled(MINI if bf16 else TINY, name="paper-head", aug_layers=2, draft_depths=5,
+                         tree_k=(3, 2, 2, 2, 1), tree_nodes=20, seed=23)
+    ls = _lockstep(shape, gain_jitter=0.1, max_seq=256)
+    ls.prefill([synth.make_prompts(shape)[0][:47]], chunk=20)
+    for s in range(4):
+        ms = ls.step()
+        say(f"  step {s}: m={ms} max|dlogit|={ls.max_logit_err:.2e} ties={ls.tie_events}")
+    assert ls.max_logit_err <= (3e-2 if bf16 else 1e-4)
+
+
 @pytest.mark.parametrize("n_kv", [8, 16], ids=["gqa2", "mha"])
 def test_persistent_kernel_xcd_sharded(n_kv):
     """The persistent kernel with heads and FFN columns sharded over the 8 XCDs (head counts divisible by 8):

@@ -119,6 +119,24 @@ def test_p3_speculative_equals_plain_greedy_config1():
     assert seq.L == seq.aug_L == len(prompt) + sum(ms)
 
 
+def test_p3_paper_size_head_two_aug_layers_five_depths():
+    """The head at the paper's size (Sec. 3.3 and 4.1: two augmenting layers, five heads): still lossless,
+    and both caches advance together."""
+    shape = synth.scaled(TINY, name="tiny-paper-head", aug_layers=2, draft_depths=5, tree_k=(3, 2, 2, 2, 1),
+                         tree_nodes=20, seed=23)
+    ws, cfg, W = make(shape=shape, gain_jitter=0.0, max_seq=200)
+    parent, rank = synth.tree_for(shape)
+    depth = [0] * len(parent)
+    for u in range(1, len(parent)):
+        depth[u] = depth[parent[u]] + 1
+    assert len(parent) == 20 and max(depth) == 5
+    prompt = synth.make_prompts(shape)[0][:40]
+    emitted, ms, seq = O.speculative_generate(W, cfg, prompt, parent, rank, steps=4, chunk=16)
+    ref, _ = _plain(W, cfg, prompt, len(emitted))
+    assert emitted == ref
+    assert seq.L == seq.aug_L == len(prompt) + sum(ms)
+
+
 @pytest.mark.parametrize("pattern", ["deep", "mixed", "none"])
 def test_p3_p4_injected_trees(pattern):
     """Trees built from the true continuation with controlled corruption: accept
