@@ -305,3 +305,31 @@ def test_config3_full_size_step():
         if ls.tie_events == ties:
             assert ms == [want[s]]
     assert ls.max_logit_err <= 3e-2
+
+
+def test_config2_full_size_step():
+    """The Vicuna-7B-shaped workload at full size (32 layers, 32 MHA heads, FFN 11008, vocab 32000, RoPE base 1e4,
+    64-node tree over a 512-token prompt): its shapes take other launch routes than the LLaMA3 one (K = 11008 ends
+    in a 256-column slice, 688 gate/up column blocks, one query head per KV head)."""
+    _torch()
+    from tests.parity import truth_hook_factory
+    O = __import__("oracle.clover2_oracle", fromlist=["x"])
+    shape = synth.CONFIGS[2]
+    say("config 2 full size: generating weights, prefilling 512 tokens on both sides")
+    ls = _lockstep(shape, max_seq=512 + 3 * 64 + 64)
+    assert ls.gpu.path_info() & 3 == 3
+    ls.ocfg.dtype = np.float32
+    ls.W = O.Weights(ls.store.get_f32, np.float32)
+    ls.seqs = [O.SeqState(ls.ocfg)]
+    ls.prefill(synth.make_prompts(shape), chunk=64)
+    say(f"  prefill ok, tie events {ls.tie_events}")
+    want = [2, 1]
+    hook = truth_hook_factory(ls, want)
+    for s in range(len(want)):
+        ties = ls.tie_events
+        ms = ls.step(tree_hook=hook)
+        say(f"  step {s}: want {want[s]} got {ms} max|dlogit|={ls.max_logit_err:.3e} "
+            f"max|dhidden|={ls.max_hidden_err:.3e} ties={ls.tie_events}")
+        if ls.tie_events == ties:
+            assert ms == [want[s]]
+    assert ls.max_logit_err <= 3e-2
