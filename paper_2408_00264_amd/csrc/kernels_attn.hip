@@ -62,13 +62,42 @@ __global__ __launch_bounds__(64 * G) void attn_mfma_kernel(AttnParams p) {
   const int l16 = lane & 15, g4 = lane >> 4;
   const int split = blockIdx.x, ng = blockIdx.y / p.n_kv, kvh = blockIdx.y % p.n_kv, b = blockIdx.z;
   const RowMap& rm = p.rm;
+  const int t0 = split * p.tiles_per_split;
+  const int head = kvh * G + wave;
+
+  // ---- staging: 16-byte pieces; K rows are stored in the order the score MFMA consumes them ----
+  constexpr int NT = 64 * G;
+  constexpr int KSLOTS = 2 * AT_TK * 16, VSLOTS = 2 * AT_D * 4;  // both 1024
+  constexpr int KIT = KSLOTS / NT, VIT = VSLOTS / NT;
+  // two register sets: while a tile is multiplied, the next one sits in LDS or lands in one set and
+  // the one after it is in flight into the other
+  u32x4 krA[KIT], vrA[VIT], krB[KIT], vrB[VIT];
+  const bf16_t* kbase = p.k_hi + (size_t)b * p.max_seq * p.n_kv * AT_D + (size_t)kvh * AT_D;
+  const bf16_t* vbase = p.v_hi + ((size_t)b * p.n_kv + kvh) * AT_D * p.max_seq;
+  auto load_tile = [&](u32x4 (&kr)[KIT], u32x4 (&vr)[VIT], int t) __attribute__((always_inline)) {
+#pragma unroll
+    for (int it = 0; it < KIT; ++it) {
+      const int idx = it * NT + tid, plane = idx >> 9, rem = idx & 511, key = rem >> 4, sl = rem & 15;
+      const int j = min(t * AT_TK + key, p.max_seq - 1);
+      kr[it] = *(const u32x4*)(kbase + plane * p.k_plane + (size_t)j * p.n_kv * AT_D + sl * 8);
+    }
+#pragma unroll
+    for (int it = 0; it < VIT; ++it) {
+      const int idx = it * NT + tid, plane = idx >> 9, rem = idx & 511, dr = rem >> 2, sl = rem & 3;
+      const int j = min(t * AT_TK + sl * 8, p.max_seq - 8);
+      vr[it] = *(const u32x4*)(vbase + plane * p.v_plane + (size_t)dr * p.max_seq + j);
+    }
+  };
+  // The first key tile is requested before anything else is waited for (its addresses need no memory:
+  // keys past the cache are clamped and masked later), so its HBM latency overlaps the loads of the lengths,
+  // the masks and Q.
+  load_tile(krA, vrA, t0);
   const int nv = rm.n_valid ? min(rm.n_valid[b], rm.n) : rm.n;
   const int L = p.base_len[b];
   if (ng * 32 >= nv || L + nv > p.max_seq) return;  // whole workgroup
   const int total = L + nv;
   const int n_tiles = (total + AT_TK - 1) / AT_TK;
-  const int t0 = split * p.tiles_per_split, t1 = min(n_tiles, t0 + p.tiles_per_split);
-  const int head = kvh * G + wave;
+  const int t1 = min(n_tiles, t0 + p.tiles_per_split);
 
   // ---- Q fragments (already scaled and split by the RoPE kernel), ancestor masks ----
   Frag qh[AT_MB][4], ql[AT_MB][4];
@@ -100,29 +129,6 @@ __global__ __launch_bounds__(64 * G) void attn_mfma_kernel(AttnParams p) {
 #pragma unroll
   for (int mb = 0; mb < AT_MB; ++mb) { m_run[mb] = -INFINITY; l_run[mb] = 0.f; }
 
-  // ---- staging: 16-byte pieces; K rows are stored in the order the score MFMA consumes them ----
-  constexpr int NT = 64 * G;
-  constexpr int KSLOTS = 2 * AT_TK * 16, VSLOTS = 2 * AT_D * 4;  // both 1024
-  constexpr int KIT = KSLOTS / NT, VIT = VSLOTS / NT;
-  // two register sets: while a tile is multiplied, the next one sits in LDS or lands in one set and
-  // the one after it is in flight into the other
-  u32x4 krA[KIT], vrA[VIT], krB[KIT], vrB[VIT];
-  const bf16_t* kbase = p.k_hi + (size_t)b * p.max_seq * p.n_kv * AT_D + (size_t)kvh * AT_D;
-  const bf16_t* vbase = p.v_hi + ((size_t)b * p.n_kv + kvh) * AT_D * p.max_seq;
-  auto load_tile = [&](u32x4 (&kr)[KIT], u32x4 (&vr)[VIT], int t) __attribute__((always_inline)) {
-#pragma unroll
-    for (int it = 0; it < KIT; ++it) {
-      const int idx = it * NT + tid, plane = idx >> 9, rem = idx & 511, key = rem >> 4, sl = rem & 15;
-      const int j = min(t * AT_TK + key, p.max_seq - 1);
-      kr[it] = *(const u32x4*)(kbase + plane * p.k_plane + (size_t)j * p.n_kv * AT_D + sl * 8);
-    }
-#pragma unroll
-    for (int it = 0; it < VIT; ++it) {
-      const int idx = it * NT + tid, plane = idx >> 9, rem = idx & 511, dr = rem >> 2, sl = rem & 3;
-      const int j = min(t * AT_TK + sl * 8, p.max_seq - 8);
-      vr[it] = *(const u32x4*)(vbase + plane * p.v_plane + (size_t)dr * p.max_seq + j);
-    }
-  };
   auto store_tile = [&](const u32x4 (&kr)[KIT], const u32x4 (&vr)[VIT], int buf) __attribute__((always_inline)) {
     bf16_t* base = sm + buf * AT_BUF;
 #pragma unroll
@@ -218,7 +224,6 @@ __global__ __launch_bounds__(64 * G) void attn_mfma_kernel(AttnParams p) {
 
   if (t0 < t1) {  // uniform over the workgroup
     const int n = t1 - t0;
-    load_tile(krA, vrA, t0);
     if constexpr (G == 4) {
       if (n > 1) load_tile(krB, vrB, t0 + 1);
       store_tile(krA, vrA, 0);
