@@ -76,7 +76,8 @@ struct clover_ctx {
   const void* lm_head_pk;
   bool fast;               // bf16 model on the MFMA path
   bool panel;              // full-K panel GEMM for the gate+up projection and the LM head
-  int row_batch_max = 64;  // passes of up to this many rows run through the <= 64-row GEMM kernels, in batches of 64
+  int row_batch_max = 64;
+  int row_batch = 64;      // rows per weight pass for passes of more than 64 rows: 128 when the panel kernel may take them  // passes of up to this many rows run through the <= 64-row GEMM kernels, in batches of 64
   // persistent phase-program kernel (one cooperative launch per verify pass)
   bool mega = false;       // usable for this model on this device
   bool mega_phases = false;  // debugging / profiling: one launch per phase
@@ -310,6 +311,7 @@ void carve(clover_ctx* x, char* base, size_t* total) {
   x->fast = fast;
   x->panel = fast && !getenv("CLOVER_NO_PANEL");
   x->row_batch_max = (fast && !getenv("CLOVER_NO_ROW_BATCH")) ? 256 : 64;
+  x->row_batch = (x->panel && !getenv("CLOVER_ROW_BATCH_64")) ? 128 : 64;
   x->kvdtype = fast ? 1 : 0;
   x->kv_layer_stride = fast ? 2 * x->k_layer_elems : x->k_layer_elems;
   x->attn_fast = fast && attn_mfma_supported(d, c.n_q_heads, c.n_kv_heads, c.max_seq);
@@ -383,17 +385,21 @@ int gemm_fast(clover_ctx* x, int cls, Planes X, int nseg, const void* const* W, 
     }
   }
   // Long K into a narrow output (the down projection): K ranges of the panel kernel, a few partials instead of
-  // one per 512 columns
-  if (x->panel && !direct && nseg == 1 && M <= x->row_batch_max) {
-    const int kp = panel_gemm_pick_k_parts(std::min(M, 64), N, K);
+  // one per 512 columns.  Passes of more than 64 rows take this route for every GEMM it supports, in batches of
+  // 128 rows (one weight pass per batch), including the three-segment QKV when the packed copies are adjacent.
+  if (x->panel && !direct && M <= x->row_batch_max) {
+    const int bm = M > 64 ? x->row_batch : 64;
+    bool adjacent = true;
+    for (int s = 1; s < nseg; ++s) adjacent = adjacent && ws[s] == ws[s - 1] + (size_t)seg_n[s - 1] * K;
+    const int kp = (nseg == 1 || (bm > 64 && adjacent)) ? panel_gemm_pick_k_parts(std::min(M, bm), N, K) : 0;
     if (kp > 1 && (size_t)kp * M * N * sizeof(float) <= x->partial_bytes) {
-      for (int m0 = 0; m0 < M; m0 += 64) {
+      for (int m0 = 0; m0 < M; m0 += bm) {
         PanelGemm g;
         memset(&g, 0, sizeof(g));
         g.Xhi = X.hi + (size_t)m0 * X.ld; g.Xlo = X.lo + (size_t)m0 * X.ld; g.ldx = X.ld;
         g.W[0] = g.W[1] = ws[0];
         g.Y = part + (size_t)m0 * N; g.ldy = N; g.k_parts = kp; g.split_stride = (size_t)M * N;
-        g.M = std::min(64, M - m0); g.N = N; g.K = K; g.epi = 0;
+        g.M = std::min(bm, M - m0); g.N = N; g.K = K; g.epi = 0;
         launch_gemm_panel(g, x->st);
       }
       return kp;
@@ -507,13 +513,14 @@ void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMa
                              H, x->st); }
     if (x->panel && M <= x->row_batch_max && panel_gemm_supported(std::min(M, 64), F, H, 1)) {
       Scope s(x, KC_GEMM_GATEUP);
-      for (int m0 = 0; m0 < M; m0 += 64) {  // (more than 64 rows: batches of 64, see gemm_fast)
+      const int bm = (M > 64 && panel_gemm_supported(std::min(M, x->row_batch), F, H, 1)) ? x->row_batch : 64;
+      for (int m0 = 0; m0 < M; m0 += bm) {  // (more than 64 rows: one weight pass per batch, see gemm_fast)
         PanelGemm g;
         memset(&g, 0, sizeof(g));
         g.Xhi = A.hi + (size_t)m0 * H; g.Xlo = A.lo + (size_t)m0 * H; g.ldx = H;
         g.W[0] = (const bf16_t*)lw.w_gate; g.W[1] = (const bf16_t*)lw.w_up;
         g.Yhi = Hf.hi + (size_t)m0 * F; g.Ylo = Hf.lo + (size_t)m0 * F; g.ldo = F;
-        g.M = std::min(64, M - m0); g.N = F; g.K = H; g.epi = 1;
+        g.M = std::min(bm, M - m0); g.N = F; g.K = H; g.epi = 1;
         launch_gemm_panel(g, x->st);
       }
     } else if (M <= 64 && stream_gemm_supported(M, 2 * F, H) && stream_gemm_out_bytes(M, 2 * F, H) <= x->partial_bytes) {
@@ -832,13 +839,14 @@ void lm_head_fast(clover_ctx* x, Planes A, int rows, float* out) {
   const clover_config& c = x->cfg;
   if (x->panel && rows <= x->row_batch_max && panel_gemm_supported(std::min(rows, 64), c.vocab, x->H, 0)) {
     Scope s(x, KC_GEMM_LMHEAD);
-    for (int m0 = 0; m0 < rows; m0 += 64) {  // (more than 64 rows: batches of 64, see gemm_fast)
+    const int bm = (rows > 64 && panel_gemm_supported(std::min(rows, x->row_batch), c.vocab, x->H, 0)) ? x->row_batch : 64;
+    for (int m0 = 0; m0 < rows; m0 += bm) {  // (more than 64 rows: one weight pass per batch, see gemm_fast)
       PanelGemm g;
       memset(&g, 0, sizeof(g));
       g.Xhi = A.hi + (size_t)m0 * A.ld; g.Xlo = A.lo + (size_t)m0 * A.ld; g.ldx = A.ld;
       g.W[0] = g.W[1] = (const bf16_t*)x->lm_head_pk;
       g.Y = out + (size_t)m0 * c.vocab; g.ldy = c.vocab;
-      g.M = std::min(64, rows - m0); g.N = c.vocab; g.K = x->H; g.epi = 0;
+      g.M = std::min(bm, rows - m0); g.N = c.vocab; g.K = x->H; g.epi = 0;
       launch_gemm_panel(g, x->st);
     }
     return;

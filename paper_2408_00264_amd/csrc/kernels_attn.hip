@@ -22,6 +22,7 @@
 #include "clover_internal.h"
 
 #include <algorithm>
+#include <cstdlib>
 #include <type_traits>
 
 namespace clv {
@@ -339,8 +340,10 @@ void launch_attn_mfma(AttnParams p, int max_total_keys, bf16_t* out_hi, bf16_t* 
   const int g = p.n_q / p.n_kv;
   const int node_groups = (p.rm.n + 31) / 32;
   const int n_tiles = (max_total_keys + AT_TK - 1) / AT_TK;
-  // enough workgroups to fill the chip twice, at least two tiles per split, within the partial buffer
-  int splits = (512 + p.rm.B * p.n_kv * node_groups - 1) / (p.rm.B * p.n_kv * node_groups);
+  // about one workgroup per CU (two on a CU do not overlap: a CU finishes one key tile per ~4 us either way, so a
+  // launch of 1.5 workgroups per CU takes as long as one of 2), at least two tiles per split, within the partial buffer
+  static const int target = [] { const char* v = getenv("CLOVER_ATTN_WGS"); return v ? atoi(v) : 256; }();
+  int splits = std::max(1, target / (p.rm.B * p.n_kv * node_groups));
   splits = std::max(1, std::min(std::min(splits, std::min(p.max_splits, MG_MAXS)), (n_tiles + 1) / 2));
   p.tiles_per_split = (n_tiles + splits - 1) / splits;
   p.n_splits = (n_tiles + p.tiles_per_split - 1) / p.tiles_per_split;

@@ -14,6 +14,10 @@
 // affordable only because few workgroups share the weights' columns, which is why the narrow
 // GEMMs (N <= 6144) stay with the K-slice kernel.
 //
+// A third use cuts K into ranges (k_parts > 1, EPI 0): a narrow output with a long K (the down projection)
+// has too few column blocks for full-K panels on every CU, so each range writes a partial [M,N] tile that the
+// consumer adds -- a few partials of several thousand columns each instead of one per 512 columns.
+//
 // Work split inside a workgroup of 8 wavefronts: UW = 8 / KW column units x KW parts of each
 // stage's 8 k-tiles.  A wavefront keeps NFW = 2 weight fragments (16 output columns each; for EPI 1
 // the gate and the up fragment of the same columns) against all 64 rows, streams its weights
@@ -40,7 +44,6 @@ union Frag {
 
 constexpr int PN_WAVES = 8;
 constexpr int PN_KST = 256;           // K columns per activation stage (8 k-tiles of 32)
-constexpr int PN_LDK = PN_KST + 8;    // LDS row stride (bf16): +16 B spreads a fragment read over the banks
 constexpr int PN_NFW = 2;
 
 __device__ __forceinline__ unsigned rn_bf16(float a) {
@@ -57,21 +60,24 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-template <int MT, int KW, int EPI, int NBUF>
+template <int MT, int KW, int EPI, int NBUF, int KST>
 __global__ __launch_bounds__(PN_WAVES * 64) void gemm_panel_kernel(PanelGemm p) {
   constexpr int ROWS = MT * 16;
+  constexpr int PN_LDK = KST + 8;               // LDS row stride (bf16): +16 B spreads a fragment read over the banks
+  constexpr int TILES = KST / 32;               // k-tiles per stage
+  constexpr int SL = KST / 8;                   // 16-byte pieces per row and stage
   constexpr int PLANE = ROWS * PN_LDK;          // bf16 elements per plane of one stage buffer
   constexpr int BUF = 2 * PLANE;                // hi and lo
   constexpr int UW = PN_WAVES / KW;             // column units per workgroup
-  constexpr int CH = 8 / KW;                    // k-tiles per wavefront and stage
-  constexpr int XIT = 2 * ROWS * (PN_KST / 8) / (PN_WAVES * 64);  // 16-byte pieces per thread and stage
+  constexpr int CH = TILES / KW;                   // k-tiles per wavefront and stage
+  constexpr int XIT = 2 * ROWS * SL / (PN_WAVES * 64);  // 16-byte pieces per thread and stage
   extern __shared__ __attribute__((aligned(16))) bf16_t xs[];      // [2 buffers][hi, lo][ROWS][PN_LDK]
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int l16 = lane & 15, g4 = lane >> 4;
   const int uw = wave / KW, kp = wave % KW;
   const int KT = p.K / 32;
-  const int NS = p.K / PN_KST / p.k_parts;      // stages of this workgroup's K range
+  const int NS = p.K / KST / p.k_parts;      // stages of this workgroup's K range
   // K range = workgroup id % k_parts: workgroups are dealt to the 8 XCDs round-robin, so with 8 ranges
   // every XCD's L2 holds ONE range of the activations instead of all of them (K = 14336: the whole
   // 3.7 MB matrix would not stay in a 4 MB L2 beside the weight stream and was fetched again and again)
@@ -111,7 +117,7 @@ __global__ __launch_bounds__(PN_WAVES * 64) void gemm_panel_kernel(PanelGemm p) 
   auto load_w = [&](auto bufc, int s) {
     constexpr int buf = decltype(bufc)::value;
     const int ks = ks0 + (s + rot) % NS;
-    const size_t off = (size_t)(ks * 8 + kp * CH) * 512;
+    const size_t off = (size_t)(ks * TILES + kp * CH) * 512;
 #pragma unroll
     for (int f = 0; f < PN_NFW; ++f)
 #pragma unroll
@@ -123,9 +129,9 @@ __global__ __launch_bounds__(PN_WAVES * 64) void gemm_panel_kernel(PanelGemm p) 
 #pragma unroll
     for (int it = 0; it < XIT; ++it) {
       const int idx = it * (PN_WAVES * 64) + tid;
-      const int rp = idx >> 5, sl = idx & 31, plane = rp / ROWS, r = rp % ROWS;
+      const int rp = idx / SL, sl = idx % SL, plane = rp / ROWS, r = rp % ROWS;
       // always load (row clamped), then zero the padding rows: no branch around a load
-      const bf16_t* src = (plane ? p.Xlo : p.Xhi) + (size_t)min(r, p.M - 1) * p.ldx + ks * PN_KST + sl * 8;
+      const bf16_t* src = (plane ? p.Xlo : p.Xhi) + (size_t)min(r, p.M - 1) * p.ldx + ks * KST + sl * 8;
       const u32x4 v = *(const u32x4*)src;
       xv[it] = r < p.M ? v : (u32x4){0u, 0u, 0u, 0u};
     }
@@ -134,7 +140,7 @@ __global__ __launch_bounds__(PN_WAVES * 64) void gemm_panel_kernel(PanelGemm p) 
 #pragma unroll
     for (int it = 0; it < XIT; ++it) {
       const int idx = it * (PN_WAVES * 64) + tid;
-      const int rp = idx >> 5, sl = idx & 31, plane = rp / ROWS, r = rp % ROWS;
+      const int rp = idx / SL, sl = idx % SL, plane = rp / ROWS, r = rp % ROWS;
       *(u32x4*)(xs + b * BUF + plane * PLANE + r * PN_LDK + sl * 8) = xv[it];
     }
   };
@@ -242,22 +248,25 @@ __global__ __launch_bounds__(PN_WAVES * 64) void gemm_panel_kernel(PanelGemm p) 
   }
 }
 
-template <int MT, int KW, int EPI, int NBUF>
+template <int MT, int KW, int EPI, int NBUF, int KST = PN_KST>
 void launch_panel_one(const PanelGemm& g, int wgs, hipStream_t st) {
-  constexpr size_t lds = (size_t)2 * 2 * MT * 16 * PN_LDK * sizeof(bf16_t);
+  constexpr size_t lds = (size_t)2 * 2 * MT * 16 * (KST + 8) * sizeof(bf16_t);
+  static_assert(lds <= 160 * 1024, "stage buffers exceed the LDS");
   static bool attr_done = false;
   if (!attr_done) {
-    hipFuncSetAttribute((const void*)gemm_panel_kernel<MT, KW, EPI, NBUF>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipFuncSetAttribute((const void*)gemm_panel_kernel<MT, KW, EPI, NBUF, KST>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_done = true;
   }
-  gemm_panel_kernel<MT, KW, EPI, NBUF><<<wgs * g.k_parts, PN_WAVES * 64, lds, st>>>(g);
+  gemm_panel_kernel<MT, KW, EPI, NBUF, KST><<<wgs * g.k_parts, PN_WAVES * 64, lds, st>>>(g);
 }
 
 }  // namespace
 
-// N: output columns (EPI 1: the FFN width F, with W[0] = gate and W[1] = up, each [F, K])
+// N: output columns (EPI 1: the FFN width F, with W[0] = gate and W[1] = up, each [F, K]).
+// Up to 64 rows: 256-column stages.  65..128 rows: eight row blocks per wavefront and 128-column stages (the two stage
+// buffers of 128 rows would not fit the LDS otherwise); twice the matrix work per weight byte, still one pass over W.
 bool panel_gemm_supported(int M, int N, int K, int epi) {
-  if (M < 1 || M > 64 || K % PN_KST != 0 || N % 16 != 0) return false;
+  if (M < 1 || M > 128 || K % (M > 64 ? 128 : PN_KST) != 0 || N % 16 != 0) return false;
   if (epi == 0) return N % 4 == 0;
   return true;
 }
@@ -267,14 +276,15 @@ bool panel_gemm_supported(int M, int N, int K, int epi) {
 // with 4 blocks x 2 k-parts per workgroup a range is several thousand columns long, i.e. a handful
 // of partials instead of one per 512 columns (K = 14336: 8 instead of 28, 21 MB less to write and
 // read back per call).  Picks the largest divisor of the stage count that keeps the grid within
-// one workgroup per CU; 0 when that leaves CUs idle or ranges shorter than 4 stages.
+// one workgroup per CU; 0 when that leaves CUs idle or ranges shorter than 4 stages.  (More than 64 rows:
+// there is no K-slice kernel to fall back to, so three quarters of the CUs are accepted.)
 int panel_gemm_pick_k_parts(int M, int N, int K) {
   if (!panel_gemm_supported(M, N, K, 0) || N % 32 != 0) return 0;
-  const int wgs_n = (N / 32 + 3) / 4, NS = K / PN_KST;
+  const int wgs_n = (N / 32 + 3) / 4, NS = K / (M > 64 ? 128 : PN_KST);
   int best = 0;
   for (int d = 1; d <= NS; ++d)
     if (NS % d == 0 && wgs_n * d <= 256 && NS / d >= 4) best = d;
-  return (best > 1 && wgs_n * best >= 224) ? best : 0;
+  return (best > 1 && wgs_n * best >= (M > 64 ? 160 : 224)) ? best : 0;
 }
 
 void launch_gemm_panel(const PanelGemm& g_in, hipStream_t st) {
@@ -282,11 +292,12 @@ void launch_gemm_panel(const PanelGemm& g_in, hipStream_t st) {
   PanelGemm g = g_in;
   g.dbg = dbg;
   const int n_blocks = g.N / 16;
-  const bool small = g.M <= 16;
+  const bool small = g.M <= 16, big = g.M > 64;
   if (g.epi == 0 && g.k_parts > 1) {
     // K ranges: 4 units of two blocks x 2 k-parts per workgroup
     const int wgs = ((n_blocks + 1) / 2 + 3) / 4;
     if (small) launch_panel_one<1, 2, 0, 2>(g, wgs, st);
+    else if (big) launch_panel_one<8, 2, 0, 2, 128>(g, wgs, st);
     else launch_panel_one<4, 2, 0, 2>(g, wgs, st);
     return;
   }
@@ -295,12 +306,14 @@ void launch_gemm_panel(const PanelGemm& g_in, hipStream_t st) {
     // gate+up: 4 units x 2 k-parts per workgroup (896 blocks -> 224 workgroups for F = 14336)
     const int wgs = (n_blocks + 3) / 4;
     if (small) launch_panel_one<1, 2, 1, 2>(g, wgs, st);
+    else if (big) launch_panel_one<8, 2, 1, 2, 128>(g, wgs, st);
     else launch_panel_one<4, 2, 1, 2>(g, wgs, st);
   } else {
     // plain: 8 units of two blocks per workgroup
     const int units = (n_blocks + 1) / 2;
     const int wgs = (units + 7) / 8;
     if (small) launch_panel_one<1, 1, 0, 2>(g, wgs, st);
+    else if (big) launch_panel_one<8, 1, 0, 2, 128>(g, wgs, st);
     else launch_panel_one<4, 1, 0, 2>(g, wgs, st);
   }
 }

@@ -38,6 +38,9 @@ GEMM_CASES = [
     (3, 1, 33, 128256, 4096),
     # panel kernel over K ranges (the down projection's shape): full and ragged rows, one row
     (5, 1, 64, 4096, 14336), (5, 1, 37, 4096, 14336), (5, 1, 1, 4096, 14336), (5, 1, 16, 4096, 8192),
+    # 65..128 rows in one weight pass (eight row blocks, 128-column stages): plain, odd rows, K ranges
+    (3, 1, 128, 4096, 1024), (3, 1, 97, 28672, 4096), (5, 1, 96, 4096, 14336), (5, 1, 128, 6144, 4096),
+    (5, 1, 65, 4096, 4096),
 ]
 
 
