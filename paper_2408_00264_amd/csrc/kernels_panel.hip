@@ -297,7 +297,7 @@ void launch_gemm_panel(const PanelGemm& g_in, hipStream_t st) {
     // K ranges: 4 units of two blocks x 2 k-parts per workgroup
     const int wgs = ((n_blocks + 1) / 2 + 3) / 4;
     if (small) launch_panel_one<1, 2, 0, 2>(g, wgs, st);
-    else if (big) launch_panel_one<8, 2, 0, 2, 128>(g, wgs, st);
+    else if (big) launch_panel_one<8, 2, 0, 3, 128>(g, wgs, st);  // (4 KB stages: a third buffer in flight measured 8 % faster)
     else launch_panel_one<4, 2, 0, 2>(g, wgs, st);
     return;
   }
@@ -306,7 +306,7 @@ void launch_gemm_panel(const PanelGemm& g_in, hipStream_t st) {
     // gate+up: 4 units x 2 k-parts per workgroup (896 blocks -> 224 workgroups for F = 14336)
     const int wgs = (n_blocks + 3) / 4;
     if (small) launch_panel_one<1, 2, 1, 2>(g, wgs, st);
-    else if (big) launch_panel_one<8, 2, 1, 2, 128>(g, wgs, st);
+    else if (big) launch_panel_one<8, 2, 1, 3, 128>(g, wgs, st);
     else launch_panel_one<4, 2, 1, 2>(g, wgs, st);
   } else {
     // plain: 8 units of two blocks per workgroup
