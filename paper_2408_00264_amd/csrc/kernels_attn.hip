@@ -49,25 +49,27 @@ __device__ __forceinline__ void a_split2(float a, float b, unsigned& hi, unsigne
 
 constexpr int AT_D = 128;         // head dim
 constexpr int AT_TK = 32;         // keys per tile
-constexpr int AT_MB = 2;          // 16-row blocks of nodes per wavefront (32 nodes per workgroup)
+// (WM, a template parameter: wavefronts per query head; a workgroup always covers 32 nodes, a wavefront 32 / WM)
 constexpr int AT_KLD = AT_D + 8;  // LDS row strides (bf16) chosen so fragment reads are conflict-free
 constexpr int AT_VLD = AT_TK + 8;
 constexpr int AT_KPLANE = AT_TK * AT_KLD;
 constexpr int AT_VPLANE = AT_D * AT_VLD;
 constexpr int AT_BUF = 2 * AT_KPLANE + 2 * AT_VPLANE;  // one stage: K hi, K lo, V^T hi, V^T lo
 
-template <int G>
-__global__ __launch_bounds__(64 * G) void attn_mfma_kernel(AttnParams p) {
+template <int G, int WM>
+__global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
+  constexpr int AT_MB = 2 / WM;     // 16-row blocks of nodes per wavefront
   extern __shared__ __attribute__((aligned(16))) bf16_t sm[];  // [2 stages][AT_BUF]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int l16 = lane & 15, g4 = lane >> 4;
   const int split = blockIdx.x, ng = blockIdx.y / p.n_kv, kvh = blockIdx.y % p.n_kv, b = blockIdx.z;
   const RowMap& rm = p.rm;
   const int t0 = split * p.tiles_per_split;
-  const int head = kvh * G + wave;
+  const int head = kvh * G + wave % G;
+  const int nsub = (wave / G) * AT_MB * 16;   // this wavefront's first node within the workgroup's 32
 
   // ---- staging: 16-byte pieces; K rows are stored in the order the score MFMA consumes them ----
-  constexpr int NT = 64 * G;
+  constexpr int NT = 64 * G * WM;
   constexpr int KSLOTS = 2 * AT_TK * 16, VSLOTS = 2 * AT_D * 4;  // both 1024
   constexpr int KIT = KSLOTS / NT, VIT = VSLOTS / NT;
   // two register sets: while a tile is multiplied, the next one sits in LDS or lands in one set and
@@ -105,7 +107,7 @@ __global__ __launch_bounds__(64 * G) void attn_mfma_kernel(AttnParams p) {
   unsigned long long a0[AT_MB], a1[AT_MB];
 #pragma unroll
   for (int mb = 0; mb < AT_MB; ++mb) {
-    const int node = ng * 32 + mb * 16 + l16;
+    const int node = ng * 32 + nsub + mb * 16 + l16;
     const bool ok = node < nv;
     a0[mb] = ok ? p.anc[2 * node] : 0ull;
     a1[mb] = ok ? p.anc[2 * node + 1] : 0ull;
@@ -219,13 +221,13 @@ __global__ __launch_bounds__(64 * G) void attn_mfma_kernel(AttnParams p) {
 
   auto compute = [&](int buf, int t) __attribute__((always_inline)) {
     // (specialised only where the register file has room for both versions)
-    if ((G == 2 || G == 4) && (t + 1) * AT_TK <= L) compute_t(buf, t, std::true_type{});  // uniform
+    if ((G == 2 || G == 4 || WM == 2) && (t + 1) * AT_TK <= L) compute_t(buf, t, std::true_type{});  // uniform
     else compute_t(buf, t, std::false_type{});
   };
 
   if (t0 < t1) {  // uniform over the workgroup
     const int n = t1 - t0;
-    if constexpr (G == 4) {
+    if constexpr (G * WM >= 4) {
       if (n > 1) load_tile(krB, vrB, t0 + 1);
       store_tile(krA, vrA, 0);
       __syncthreads();
@@ -256,7 +258,7 @@ __global__ __launch_bounds__(64 * G) void attn_mfma_kernel(AttnParams p) {
   // ---- partial result of this split ----
 #pragma unroll
   for (int mb = 0; mb < AT_MB; ++mb) {
-    const int node = ng * 32 + mb * 16 + l16;
+    const int node = ng * 32 + nsub + mb * 16 + l16;
     float lsum = l_run[mb];
     lsum += __shfl_xor(lsum, 16, 64);
     lsum += __shfl_xor(lsum, 32, 64);
@@ -325,15 +327,15 @@ bool attn_mfma_supported(int head_dim, int n_q, int n_kv, int max_seq) {
   return head_dim == AT_D && (g == 1 || g == 2 || g == 4 || g == 8) && max_seq % 8 == 0 && max_seq >= 32;
 }
 
-template <int G>
+template <int G, int WM>
 static void launch_attn_one(const AttnParams& p, dim3 grid, hipStream_t st) {
   constexpr size_t lds = (size_t)2 * AT_BUF * sizeof(bf16_t);
   static bool attr_done = false;
   if (!attr_done) {
-    hipFuncSetAttribute((const void*)attn_mfma_kernel<G>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipFuncSetAttribute((const void*)attn_mfma_kernel<G, WM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_done = true;
   }
-  attn_mfma_kernel<G><<<grid, 64 * G, lds, st>>>(p);
+  attn_mfma_kernel<G, WM><<<grid, 64 * G * WM, lds, st>>>(p);
 }
 
 void launch_attn_mfma(AttnParams p, int max_total_keys, bf16_t* out_hi, bf16_t* out_lo, int ldo, hipStream_t st) {
@@ -348,11 +350,14 @@ void launch_attn_mfma(AttnParams p, int max_total_keys, bf16_t* out_hi, bf16_t* 
   p.tiles_per_split = (n_tiles + splits - 1) / splits;
   p.n_splits = (n_tiles + p.tiles_per_split - 1) / p.tiles_per_split;
   dim3 grid(p.n_splits, node_groups * p.n_kv, p.rm.B);
+  // Two wavefronts per head (16 nodes each) share a SIMD, so one's matrix products overlap the other's soft-max
+  // arithmetic, and both share the staged K / V^T tile.
+  static const int wm1 = getenv("CLOVER_ATTN_WM1") != nullptr;
   switch (g) {
-    case 1: launch_attn_one<1>(p, grid, st); break;
-    case 2: launch_attn_one<2>(p, grid, st); break;
-    case 4: launch_attn_one<4>(p, grid, st); break;
-    default: launch_attn_one<8>(p, grid, st); break;
+    case 1: if (wm1) launch_attn_one<1, 1>(p, grid, st); else launch_attn_one<1, 2>(p, grid, st); break;
+    case 2: if (wm1) launch_attn_one<2, 1>(p, grid, st); else launch_attn_one<2, 2>(p, grid, st); break;
+    case 4: if (wm1) launch_attn_one<4, 1>(p, grid, st); else launch_attn_one<4, 2>(p, grid, st); break;
+    default: launch_attn_one<8, 1>(p, grid, st); break;
   }
   attn_merge_kernel<<<dim3(p.rm.n, p.rm.B, (p.n_q + MG_HEADS - 1) / MG_HEADS), MG_HEADS * 32, 0, st>>>(
       p.o_part, p.ml_part, p.n_splits, p.rows_total, p.n_q, out_hi, out_lo, ldo, p.rm);
