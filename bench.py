@@ -254,7 +254,7 @@ def main():
         dom_ms, dom_n = prof["gemm_gate_up"]
         dom_bytes = 2 * 2 * shape.ffn * shape.hidden
         traffic_key = "gemm_gate_up"
-        trace_name = "gemm_panel_kernel<4, 2, 1, 2>"
+        trace_name = "gemm_panel_kernel<4, 2, 1, 2, 256>"
     dom_avg_ms = dom_ms / max(dom_n, 1)
     achieved = dom_bytes / (dom_avg_ms * 1e-3) / 1e9 if dom_n else 0.0
     by_cls = {}

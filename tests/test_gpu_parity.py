@@ -185,6 +185,22 @@ def test_mha_shape_bf16():
 
 
 @pytest.mark.parametrize("bf16", [False, True], ids=["fp32", "bf16"])
+def test_single_node_tree_is_plain_decoding(bf16):
+    """Degenerate tree: the root alone.  Every step verifies one row, accepts it and emits the target's next token,
+    i.e. plain greedy decoding through the same three calls (the draft head still has to advance its own cache)."""
+    _torch()
+    shape = MINI if bf16 else TINY
+    parent, rank = np.array([-1]), np.array([0])
+    ls = _lockstep(shape, gain_jitter=0.1, tree=(parent, rank), max_seq=128, max_nodes=16)
+    ls.prefill([synth.make_prompts(shape, seed=5)[0][:19]], chunk=8)
+    for s in range(5):
+        ms = ls.step()
+        assert ms == [1]
+    assert ls.max_logit_err <= (3e-2 if bf16 else 1e-4)
+    assert ls.gpu.seq_len()[0] == 19 + 5
+
+
+@pytest.mark.parametrize("bf16", [False, True], ids=["fp32", "bf16"])
 def test_paper_size_head_two_aug_layers_five_depths(bf16):
     """The draft head at the paper's size (Sec. 3.3, 4.1): two augmenting layers, five depths (FC_1..FC_4)."""
     _torch()
