@@ -352,3 +352,27 @@ def test_config2_full_size_step():
         if ls.tie_events == ties:
             assert ms == [want[s]]
     assert ls.max_logit_err <= 3e-2
+
+
+@pytest.mark.parametrize("cfg", [4, 5], ids=["batch8_256_rows", "tree96_depth5"])
+def test_full_width_two_layers(cfg):
+    """Configs 4 and 5 at their real widths (H 4096, FFN 14336, vocab 128256, 32/8 heads) with two layers and short
+    prompts, so that the oracle stays quick: passes of 96 and 256 rows take the 128-row routes of the real shapes
+    (QKV, Wo and down over K ranges of the panel kernel, gate+up and LM head full-K), which the small models above
+    are too narrow for."""
+    _torch()
+    O = __import__("oracle.clover2_oracle", fromlist=["x"])
+    base = synth.CONFIGS[cfg]
+    shape = synth.scaled(base, name=f"wide-{cfg}", n_layers=2, prompt_len=(24, 90) if cfg == 4 else (150, 150), seed=31 + cfg)
+    ls = _lockstep(shape, batch=shape.batch, max_seq=384)
+    assert ls.gpu.path_info() & 3 == 3
+    ls.ocfg.dtype = np.float32
+    ls.W = O.Weights(ls.store.get_f32, np.float32)
+    ls.seqs = [O.SeqState(ls.ocfg) for _ in range(shape.batch)]
+    prompts = synth.make_prompts(shape)
+    say(f"config {cfg} widths, 2 layers: prompt lengths {[len(p) for p in prompts]}")
+    ls.prefill(prompts, chunk=len(synth.tree_for(shape)[0]))
+    for s in range(2):
+        ms = ls.step()
+        say(f"  step {s}: m={ms} max|dlogit|={ls.max_logit_err:.3e} ties={ls.tie_events}")
+    assert ls.max_logit_err <= 3e-2
