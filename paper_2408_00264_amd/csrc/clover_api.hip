@@ -400,6 +400,7 @@ int gemm_fast(clover_ctx* x, int cls, Planes X, int nseg, const void* const* W, 
         g.W[0] = g.W[1] = ws[0];
         g.Y = part + (size_t)m0 * N; g.ldy = N; g.k_parts = kp; g.split_stride = (size_t)M * N;
         g.M = std::min(bm, M - m0); g.N = N; g.K = K; g.epi = 0;
+        g.rows128 = bm > 64;   // a short last batch keeps the form the ranges were picked for
         launch_gemm_panel(g, x->st);
       }
       return kp;

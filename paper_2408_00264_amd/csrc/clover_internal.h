@@ -172,6 +172,7 @@ struct PanelGemm {
   int M, N, K;
   int epi;                            // 0 plain, 1 SwiGLU
   int k_parts; size_t split_stride;   // epi 0 only: K is cut into k_parts ranges, range r writes Y + r * split_stride
+  int rows128;                        // use the 65..128-row form whatever M is (k_parts was picked for its stage width)
   int dbg;                            // timing experiments only (CLOVER_PANEL_DBG): 1 no activation loads
 };
 bool panel_gemm_supported(int M, int N, int K, int epi);

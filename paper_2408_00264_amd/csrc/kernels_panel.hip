@@ -292,7 +292,7 @@ void launch_gemm_panel(const PanelGemm& g_in, hipStream_t st) {
   PanelGemm g = g_in;
   g.dbg = dbg;
   const int n_blocks = g.N / 16;
-  const bool small = g.M <= 16, big = g.M > 64;
+  const bool big = g.M > 64 || g.rows128, small = g.M <= 16 && !big;
   if (g.epi == 0 && g.k_parts > 1) {
     // K ranges: 4 units of two blocks x 2 k-parts per workgroup
     const int wgs = ((n_blocks + 1) / 2 + 3) / 4;

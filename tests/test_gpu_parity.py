@@ -354,8 +354,8 @@ def test_config2_full_size_step():
     assert ls.max_logit_err <= 3e-2
 
 
-@pytest.mark.parametrize("cfg", [4, 5], ids=["batch8_256_rows", "tree96_depth5"])
-def test_full_width_two_layers(cfg):
+@pytest.mark.parametrize("cfg,batch", [(4, 8), (4, 5), (5, 1)], ids=["batch8_256_rows", "batch5_160_rows", "tree96_depth5"])
+def test_full_width_two_layers(cfg, batch):
     """Configs 4 and 5 at their real widths (H 4096, FFN 14336, vocab 128256, 32/8 heads) with two layers and short
     prompts, so that the oracle stays quick: passes of 96 and 256 rows take the 128-row routes of the real shapes
     (QKV, Wo and down over K ranges of the panel kernel, gate+up and LM head full-K), which the small models above
@@ -363,7 +363,9 @@ def test_full_width_two_layers(cfg):
     _torch()
     O = __import__("oracle.clover2_oracle", fromlist=["x"])
     base = synth.CONFIGS[cfg]
-    shape = synth.scaled(base, name=f"wide-{cfg}", n_layers=2, prompt_len=(24, 90) if cfg == 4 else (150, 150), seed=31 + cfg)
+    # (160 rows: a full 128-row batch followed by a short one)
+    shape = synth.scaled(base, name=f"wide-{cfg}-{batch}", n_layers=2, batch=batch,
+                         prompt_len=(24, 90) if cfg == 4 else (150, 150), seed=31 + cfg + batch)
     ls = _lockstep(shape, batch=shape.batch, max_seq=384)
     assert ls.gpu.path_info() & 3 == 3
     ls.ocfg.dtype = np.float32
