@@ -30,13 +30,14 @@ def log(*a):
 
 def verify_bytes(shape, B, N, L_sum):
     """Algorithmic HBM bytes of one verify_tree: every target weight once (2 bytes each), the
-    cached K/V rows read once, the new K/V rows written once (4 bytes per cached value: the
-    caches hold a bf16 hi/lo pair per value)."""
+    cached K/V rows read once and the new K/V rows written once at 2 bytes per value (a bf16 cache:
+    what the method needs; this library's caches hold a bf16 hi/lo pair, i.e. it moves 4, which is
+    its own cost and does not count towards the achieved rate)."""
     H, d = shape.hidden, shape.head_dim
     nq, nkv, F, V = shape.n_q_heads, shape.n_kv_heads, shape.ffn, shape.vocab
     per_layer = (nq * d * H) + 2 * (nkv * d * H) + (H * nq * d) + 3 * F * H
     weights = 2 * (shape.n_layers * per_layer + V * H)
-    kv_row = 2 * nkv * d * 4
+    kv_row = 2 * nkv * d * 2
     kv_read = shape.n_layers * kv_row * (L_sum + B * N)
     kv_write = shape.n_layers * kv_row * B * N
     return weights + kv_read + kv_write
