@@ -496,3 +496,52 @@ def test_bf16_rounding_bits():
     np.testing.assert_array_equal(synth._f32_to_bf16_bits_np(r), t)
     big = np.random.default_rng(1).standard_normal(1 << 20).astype(np.float32)
     np.testing.assert_array_equal(synth.f32_to_bf16_bits(big), synth._f32_to_bf16_bits_np(big))
+
+
+# ---------------------------------------------------------------- cost figures the paper states
+def _golden(name):
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "draft_cost_ratios.txt")
+    for line in open(path):
+        f = line.split()
+        if f and f[0] == name:
+            return float(f[1]), float(f[2])
+    raise KeyError(name)
+
+
+def test_draft_head_cost_matches_the_papers_figures():
+    """Which weight matrices the oracle's draft step actually multiplies by, priced at the paper's two model shapes,
+    against the two cost statements of Sec. 3.3 (tests/golden/draft_cost_ratios.txt).  A different reading of the head
+    (an output projection inside the Attention Decoder, an FC over the state alone, per-depth Attention Decoders that
+    also project the embedding twice, an augmenting block that is not a decoder layer) moves the ratio out of range."""
+    ws, cfg, W0 = make(gain_jitter=0.0, max_seq=64)
+    used = []
+    W = O.Weights(lambda n: (used.append(n), ws.get_f32(n))[1], np.float64, cache=False)
+    seq = O.SeqState(cfg)
+    rng = np.random.default_rng(3)
+    hid = rng.standard_normal((2, TINY.hidden))
+    # root with one child: AD1, augmenting block, head 0 only
+    O.draft_tree(W, cfg, seq, hid, [5, 9], [-1, 0], [0, 0])
+    first = list(used)
+    used.clear()
+    # a chain root -> a -> b: the second call adds exactly ONE regressive update (node a has a child)
+    seq2 = O.SeqState(cfg)
+    O.draft_tree(W, cfg, seq2, hid, [5, 9], [-1, 0, 1], [0, 0, 0])
+    extra = list(used)
+    for n in first:
+        extra.remove(n)
+    mats = lambda names: sorted(n for n in names if len(ws.shapes[n]) == 2 and n not in ("lm_head", "embed"))
+    update = mats(extra)
+    assert update == ["ad2.wk", "ad2.wq", "ad2.wv", "fc.1.w"], update
+    aug = [n for n in mats(first) if n.startswith("aug.")]
+    layer_names = sorted(f"aug.0.{k}" for k, v in synth.layer_tensor_shapes(TINY).items() if len(v) == 2)
+    assert aug == layer_names
+    want, tol = _golden("aug_block_in_decoder_layers")
+    assert abs(len(aug) / len(layer_names) / TINY.aug_layers - want) <= tol
+    want, tol = _golden("decoder_layer_over_per_depth_update")
+    for c in (2, 3):                       # the paper's two targets: Vicuna-7B and LLaMA3-8B shapes
+        shapes = synth.weight_shapes(synth.CONFIGS[c])
+        size = lambda n: int(np.prod(shapes[n]))
+        layer = sum(size(f"layers.0.{k}") for k, v in synth.layer_tensor_shapes(synth.CONFIGS[c]).items() if len(v) == 2)
+        upd = sum(size(n) for n in update)
+        assert abs(layer / upd - want) <= tol, (c, layer / upd)
