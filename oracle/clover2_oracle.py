@@ -29,7 +29,8 @@ verify == every root-to-leaf path run alone; speculative greedy == plain greedy;
 compacted KV == KV of a fresh prefill; identity-style draft head reproduces the
 target's logits; Attention-Decoder algebra; HF `LlamaForCausalLM` and
 `scaled_dot_product_attention` cross-checks; top-k and the accept walk against
-brute force.  Parity unpinned against printed values: the paper prints no worked
+brute force; the matrices a regressive update and the Augmenting Block multiply
+by, priced against the cost figures of Sec. 3.3.  Parity unpinned against printed values: the paper prints no worked
 numeric example, so draft-head numerics beyond those special cases follow from
 the listed readings only.
 """

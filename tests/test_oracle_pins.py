@@ -9,6 +9,7 @@ P5 identity-style draft head (limit of the init table, Appendix A.2) reproduces 
 P6 Attention-Decoder algebra                        (Appendix A.3)
 P7 HF LlamaForCausalLM / SDPA cross-checks          (library special case)
 P8 ranking and accept walk vs brute force
+P9 matrices used by one regressive update / the Augmenting Block vs the cost figures of Sec. 3.3
 """
 import itertools
 
