@@ -17,10 +17,13 @@ What is computed, and where the paper defines it
 * Draft head wiring (Sec. 3, Sec. 3.1, 3.2, 3.3, "Other details"): AD1 merges
   the target's last-block hidden state with the embedding of the token that
   followed it; the Augmenting Block (decoder layers with their own KV cache)
-  runs on that; head 0 is a plain FC; every later depth is AD2 on the parent's
-  state and the parent's token embedding, then an FC over [state ; embedding];
-  an RMSNorm precedes the shared LM head; token embeddings are rows of the LM
-  head weight.
+  runs on that; head 0 is a plain FC on the block's last row.  For a node u of
+  depth >= 1 that has children: s_u = AD2(x = s_parent(u), y = emb(tok_u)), i.e.
+  the state handed down by u's parent (the root hands down the block's last
+  row) and the embedding of u's OWN token; then FC_j over [s_u ; emb(tok_u)],
+  an RMSNorm and the shared LM head give the logits whose ranked ids become
+  u's children.  s_u (not the FC's output) is what u hands down (Sec. 3.2).
+  Token embeddings are rows of the LM head weight.
 * Greedy verification (Sec. 2.1; Table 1 caption, temperature 0): walk from the
   root, descend while a child carries the target's argmax, emit one bonus token.
 
@@ -30,9 +33,11 @@ compacted KV == KV of a fresh prefill; identity-style draft head reproduces the
 target's logits; Attention-Decoder algebra; HF `LlamaForCausalLM` and
 `scaled_dot_product_attention` cross-checks; top-k and the accept walk against
 brute force; the matrices a regressive update and the Augmenting Block multiply
-by, priced against the cost figures of Sec. 3.3.  Parity unpinned against printed values: the paper prints no worked
-numeric example, so draft-head numerics beyond those special cases follow from
-the listed readings only.
+by, priced against the cost figures of Sec. 3.3; the draft wiring (which token
+embedding and whose state AD1 / AD2 / FC_j receive, what is handed down) against
+a closed form in the tokens alone for additive Attention Decoders, a pin that
+planted wiring mistakes are shown to fail.  The paper prints no worked numeric
+example, so no pin compares against printed values.
 """
 from __future__ import annotations
 

@@ -10,6 +10,8 @@ P6 Attention-Decoder algebra                        (Appendix A.3)
 P7 HF LlamaForCausalLM / SDPA cross-checks          (library special case)
 P8 ranking and accept walk vs brute force
 P9 matrices used by one regressive update / the Augmenting Block vs the cost figures of Sec. 3.3
+P10 draft wiring in closed form (additive Attention Decoders): which token and whose state each step receives;
+    the pin is shown to fail on planted wiring mistakes (mutants of the oracle's source, CPU only)
 """
 import itertools
 
@@ -546,3 +548,114 @@ def test_draft_head_cost_matches_the_papers_figures():
         layer = sum(size(f"layers.0.{k}") for k, v in synth.layer_tensor_shapes(synth.CONFIGS[c]).items() if len(v) == 2)
         upd = sum(size(n) for n in update)
         assert abs(layer / upd - want) <= tol, (c, layer / upd)
+
+
+# ---------------------------------------------------------------- P10: the draft head's wiring (Sec. 3.1, 3.2, App. A.3)
+def _additive_overrides(shape, rng):
+    """A head whose result has a closed form in the tokens alone.  Both Attention Decoders get Wq = Wk = 0 and
+    bq = bk = one non-zero vector (every head's cosine is exactly 1), Wv = I, bv = 0: AD(x, y) = x + y.  The
+    augmenting layer keeps its attention but projects to zero (Wo = W_down = 0), so it returns its input and only
+    fills its cache.  FC_j = [2I | 0] without bias, head-norm gains 1."""
+    H = shape.hidden
+    z = lambda *s: np.zeros(s, np.float32)
+    c = (0.5 + rng.random(H)).astype(np.float32)
+    ov = {}
+    for ad in ("ad1", "ad2"):
+        ov[f"{ad}.wq"] = z(H, H); ov[f"{ad}.wk"] = z(H, H)
+        ov[f"{ad}.bq"] = c; ov[f"{ad}.bk"] = c
+        ov[f"{ad}.wv"] = np.eye(H, dtype=np.float32); ov[f"{ad}.bv"] = z(H)
+    for l in range(shape.aug_layers):
+        ov[f"aug.{l}.wo"] = z(H, shape.n_q_heads * shape.head_dim)
+        ov[f"aug.{l}.w_down"] = z(H, shape.ffn)
+    for j in range(1, shape.draft_depths):
+        w = z(H, 2 * H)
+        w[:, :H] = 2.0 * np.eye(H)
+        ov[f"fc.{j}.w"] = w; ov[f"fc.{j}.b"] = z(H)
+    ov["head_norm"] = np.ones(H, np.float32)
+    return ov
+
+
+def _wiring_pin(draft_tree_fn):
+    """Runs `draft_tree_fn` on the additive head and checks every returned logit vector and the augmenting block's
+    cached V rows against values computed here from the tokens alone:
+        s_root = h_{m-1} + E[n_{m-1}]                       (AD1 pairs row i with the token that followed it)
+        s_u    = s_root + sum of E[tok_w] over the nodes w != root on the path root -> u   (AD2 chains the STATE,
+                 and adds the node's OWN token embedding)
+        z_root = W_lm RMSNorm(FC0 s_root + b0),   z_u = W_lm RMSNorm(2 s_u)
+        V_aug[i] = Wv_aug RMSNorm(h_i + E[n_i]; attn_norm)   (no rotation on V: shows the pairing of every row)
+    with E = rows of the LM-head weight."""
+    rng = np.random.default_rng(41)
+    shape = TINY
+    ws, cfg, W = make(shape=shape, gain_jitter=0.1, overrides=_additive_overrides(shape, rng), max_seq=64)
+    parent, rank = synth.tree_for(shape)
+    n, H, m = len(parent), shape.hidden, 3
+    hid = rng.standard_normal((m, H))
+    nxt = [int(t) for t in rng.integers(0, shape.vocab, m)]
+    seq = O.SeqState(cfg)
+    tokens, zs = draft_tree_fn(W, cfg, seq, hid, nxt, parent, rank)
+    lm = ws.get_f32("lm_head").astype(np.float64)
+    rms = lambda v: v / np.sqrt(np.mean(v * v) + shape.rms_eps)
+    kids = O.children_of(parent)
+    assert tokens[0] == nxt[-1]
+    s_root = hid[m - 1] + lm[nxt[m - 1]]
+    checked_deep = 0
+    for u in range(n):
+        if not kids[u]:
+            continue
+        s = s_root.copy()
+        w = u
+        while w > 0:                          # explicit walk up the path, own token of every node on it
+            s += lm[int(tokens[w])]
+            w = int(parent[w])
+        if u == 0:
+            g = ws.get_f32("fc0.w").astype(np.float64) @ s + ws.get_f32("fc0.b").astype(np.float64)
+        else:
+            g = 2.0 * s
+            checked_deep += int(parent[u] != 0)
+        np.testing.assert_allclose(zs[u], lm @ rms(g), atol=1e-9, err_msg=f"node {u}")
+        # children carry the ranked ids of exactly these logits
+        order = sorted(range(shape.vocab), key=lambda i: (-zs[u][i], i))
+        for c in kids[u]:
+            assert tokens[c] == order[rank[c]]
+    assert checked_deep >= 1                  # a node whose parent is not the root: chaining is exercised
+    wv = ws.get_f32("aug.0.wv").astype(np.float64)
+    gain = ws.get_f32("aug.0.attn_norm").astype(np.float64)
+    for i in range(m):
+        want = wv @ (rms(hid[i] + lm[nxt[i]]) * gain)
+        np.testing.assert_allclose(seq.aug_kv.v[0, i].reshape(-1), want, atol=1e-9, err_msg=f"aug V row {i}")
+    assert seq.aug_L == m
+
+
+def test_p10_draft_wiring_closed_form():
+    _wiring_pin(O.draft_tree)
+
+
+def _mutant(replacements):
+    """draft_tree with one line of its source replaced (a planted wiring mistake), compiled beside the oracle."""
+    import inspect
+    src = inspect.getsource(O.draft_tree)
+    for old, new in replacements:
+        assert src.count(old) == 1, old
+        src = src.replace(old, new)
+    ns = dict(vars(O))
+    exec(compile(src, "<mutant draft_tree>", "exec"), ns)
+    return ns["draft_tree"]
+
+
+@pytest.mark.parametrize("name,replacements", [
+    # AD2 / FC_j fed the PARENT's token embedding instead of the node's own
+    ("parent_token", [("e = emb(tokens[node])", "e = emb(tokens[int(parent[node])])")]),
+    # the FC's output handed to the next depth instead of the Attention Decoder's state
+    ("chain_fc_output", [("expand(node, W(\"lm_head\") @ rmsnorm(g, W(\"head_norm\"), cfg.rms_eps))\n    return",
+                          "state[node] = g\n        expand(node, W(\"lm_head\") @ rmsnorm(g, W(\"head_norm\"), cfg.rms_eps))\n    return")]),
+    # AD1 pairs hidden row i with the token of row i-1 (shifted pairing)
+    ("ad1_shifted_pairing", [("emb(next_tok))", "emb(np.roll(next_tok, 1)))")]),
+    # AD2 takes the ROOT's state instead of the parent's
+    ("root_state", [("state[int(parent[node])][None, :]", "state[0][None, :]")]),
+    # only an EARLIER accepted row is paired with the wrong token (visible in the augmenting block's cache alone)
+    ("ad1_earlier_row_mispaired", [("emb(next_tok))", "emb(np.array([next_tok[0], next_tok[0], next_tok[2]])))")]),
+], ids=lambda v: v if isinstance(v, str) else "")
+def test_p10_pin_detects_planted_wiring_mistakes(name, replacements):
+    mutant = _mutant(replacements)
+    with pytest.raises(AssertionError):
+        _wiring_pin(mutant)
