@@ -230,7 +230,6 @@ def main():
     run_steps(K)
     torch.cuda.synchronize()
     prof = g.profile_collect()
-    phases = g.profile_phases()       # the last verify pass, phase by phase, if it ran as one persistent launch
     g.profile_enable(False)
     g.seq_len()
     ver = np.array([e[0].elapsed_time(e[1]) for e in events])
@@ -241,27 +240,14 @@ def main():
     n_levels = D
     dbytes = draft_bytes(shape, n_levels)
     kernels = {k: {"ms_per_step": v[0] / K, "launches_per_step": v[1] / K} for k, v in prof.items() if v[1]}
-    persistent = bool(g.path_info() & 4) and B * N <= 64 and prof.get("layer_stack", (0, 0))[1] > 0
-    if persistent:
-        # dominant kernel: the persistent kernel that runs the whole verify pass (all layers + LM head)
-        dom_name = "mega_kernel (verify_tree as one persistent launch: embedding, all layers, LM head)"
-        dom_ms, dom_n = prof["layer_stack"]
-        dom_bytes = vbytes
-        traffic_key = "mega_kernel"
-        trace_name = "mega_kernel"
-    else:
-        # dominant kernel: the fused gate/up projection (largest weight stream of a layer)
-        dom_name = "gemm_gate_up (fused SwiGLU projection)"
-        dom_ms, dom_n = prof["gemm_gate_up"]
-        dom_bytes = 2 * 2 * shape.ffn * shape.hidden
-        traffic_key = "gemm_gate_up"
-        trace_name = "gemm_panel_kernel<4, 2, 1, 2, 256>"
+    # dominant kernel: the fused gate/up projection (largest weight stream of a layer)
+    dom_name = "gemm_gate_up (fused SwiGLU projection)"
+    dom_ms, dom_n = prof["gemm_gate_up"]
+    dom_bytes = 2 * 2 * shape.ffn * shape.hidden
+    traffic_key = "gemm_gate_up"
+    trace_name = "gemm_panel_kernel<4, 2, 1, 2, 256>"
     dom_avg_ms = dom_ms / max(dom_n, 1)
     achieved = dom_bytes / (dom_avg_ms * 1e-3) / 1e9 if dom_n else 0.0
-    by_cls = {}
-    for name, us in phases:
-        t, n = by_cls.get(name, (0.0, 0))
-        by_cls[name] = (t + us, n + 1)
     out = {
         "metric": "verified tree-tokens/s over the whole speculative step (draft_tree + verify_tree + accept_and_compact)",
         "value": B * N / (ms_per_step * 1e-3), "unit": "tree-tokens/s", "n_gpus": 1, "steps": K, "warmup": Wm,
@@ -286,8 +272,6 @@ def main():
                      if not (args.layers or args.prompt) else None},
         "kernels": kernels,
     }
-    if by_cls:
-        out["verify_phases"] = {k: {"us_per_pass": round(v[0], 1), "phases": v[1]} for k, v in by_cls.items()}
     if not args.no_cpu_baseline:
         t0 = time.time()
         out["cpu_baseline"] = cpu_baseline(shape, parent, rank, int(lens0[0]), min(args.cpu_sample_layers, shape.n_layers), store,

@@ -43,10 +43,7 @@ enum {
 
 enum { CLOVER_DTYPE_F32 = 0, CLOVER_DTYPE_BF16 = 1 };
 enum {
-  CLOVER_FLAG_GENERIC = 1,   /* use the plain fp32-ALU kernels everywhere (no MFMA path) */
-  CLOVER_FLAG_NO_GRAPH = 2,  /* never replay captured HIP graphs */
-  CLOVER_FLAG_MEGA = 4       /* run passes of at most 64 rows as ONE persistent phase-program kernel (cooperative
-                                launch, grid-wide barriers between the operations) instead of one kernel per operation */
+  CLOVER_FLAG_GENERIC = 1    /* use the plain fp32-ALU kernels everywhere (no MFMA path) */
 };
 #define CLOVER_MAX_NODES 128 /* upper bound on max_nodes (ancestor masks are 2 x 64 bit) */
 #define CLOVER_MAX_DEPTH 8   /* upper bound on draft_depths */
@@ -185,24 +182,16 @@ int clover_read_kv(clover_ctx *ctx, int32_t stack, int32_t layer, int32_t b, int
                    float *k_out_host, float *v_out_host);
 
 /* Per-kernel-class timing with HIP events on the library's stream.  While enabled, every launch
- * is bracketed by two events (and HIP graphs are not used).  collect synchronises, adds up the
+ * is bracketed by two events.  collect synchronises, adds up the
  * elapsed milliseconds and launch counts per class since the last collect, and clears them.
  * Class names: clover_kernel_class_name(i), i < clover_kernel_class_count(). */
 int clover_profile_enable(clover_ctx *ctx, int32_t on);
 int clover_profile_collect(clover_ctx *ctx, double *ms_by_class, int64_t *launches_by_class, int32_t n_classes);
 int clover_kernel_class_count(void);
-/* Phase times of the most recent persistent-kernel launch made while profiling was enabled: duration in
- * microseconds (including the barrier that ends the phase, as seen by workgroup 0) and kernel class of
- * each phase, in program order.  *n_out = number of phases (0 if the persistent kernel is not in use);
- * synchronises.  HOST arrays of max_phases entries. */
-int clover_profile_phases(clover_ctx *ctx, double *us_by_phase, int32_t *class_by_phase, int32_t max_phases,
-                          int32_t *n_out);
 const char *clover_kernel_class_name(int32_t cls);
 
-/* Which kernels this context runs: bit 0 = MFMA path (bf16 model), bit 1 = MFMA tree attention,
- * bit 2 = persistent phase-program kernel for passes of at most 64 rows (one cooperative launch per
- * verify_tree instead of one kernel per operation), bit 3 = that kernel shards heads and FFN columns over
- * the XCDs (head and FFN counts divide by 8).  Negative: error code. */
+/* Which kernels this context runs: bit 0 = MFMA path (bf16 model), bit 1 = MFMA tree attention.
+ * Negative: error code. */
 int clover_path_info(clover_ctx *ctx);
 
 /* Message of the last error on this context ("" if none); valid until the next call. */

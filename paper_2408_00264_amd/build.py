@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libclover.so")
-SOURCES = ["kernels_generic.hip", "kernels_mfma.hip", "kernels_stream.hip", "kernels_panel.hip", "kernels_attn.hip", "kernels_mega.hip", "kernels_draft.hip", "clover_api.hip"]
+SOURCES = ["kernels_generic.hip", "kernels_mfma.hip", "kernels_stream.hip", "kernels_panel.hip", "kernels_attn.hip", "kernels_draft.hip", "clover_api.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-value", "-I", os.path.join(ROOT, "include")]
 
@@ -23,14 +23,21 @@ def _hipcc() -> str:
     return "hipcc"
 
 
-def build(verbose: bool = False) -> str:
-    os.makedirs(BUILD, exist_ok=True)
+def build(verbose: bool = False, ablate: bool = False, out: str = "") -> str:
+    """Compile every source and link the library.  `ablate` adds -DCLOVER_ABLATE (kernel-tuning builds that read
+    CLOVER_* environment switches; never the shipped library) and needs an explicit `out` path."""
+    if ablate and not out:
+        raise ValueError("an ablation build must not overwrite the shipped library: pass out=<path>")
+    build_dir = BUILD + ("_ablate" if ablate else "")
+    lib_path = out or LIB
+    flags = FLAGS + (["-DCLOVER_ABLATE"] if ablate else [])
+    os.makedirs(build_dir, exist_ok=True)
     hipcc = _hipcc()
     srcs = [s for s in SOURCES if os.path.exists(os.path.join(CSRC, s))]
 
     def compile_one(src: str) -> str:
-        obj = os.path.join(BUILD, src.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, "-Rpass-analysis=kernel-resource-usage", "-c", os.path.join(CSRC, src), "-o", obj]
+        obj = os.path.join(build_dir, src.replace(".hip", ".o"))
+        cmd = [hipcc, *flags, "-Rpass-analysis=kernel-resource-usage", "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         lines = r.stderr.splitlines()
         # a kernel that keeps arrays or spills in scratch memory runs many times slower: say so loudly
@@ -51,12 +58,17 @@ def build(verbose: bool = False) -> str:
 
     with ThreadPoolExecutor(max_workers=4) as ex:
         objs = list(ex.map(compile_one, srcs))
-    r = subprocess.run([hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *objs],
+    r = subprocess.run([hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", lib_path, *objs],
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
-    return LIB
+    return lib_path
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import argparse
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--ablate", action="store_true", help="tuning build that reads CLOVER_* switches (needs --out)")
+    ap.add_argument("--out", default="")
+    a = ap.parse_args()
+    print(build(verbose=True, ablate=a.ablate, out=a.out))

@@ -17,12 +17,12 @@ LIB_PATH = os.path.join(_HERE, "libclover.so")
 
 OK, E_NULL, E_CONFIG, E_TREE, E_CAPACITY, E_SHAPE, E_HIP, E_STATE = 0, -1, -2, -3, -4, -5, -6, -7
 DTYPE_F32, DTYPE_BF16 = 0, 1
-FLAG_GENERIC, FLAG_NO_GRAPH, FLAG_MEGA = 1, 2, 4
+FLAG_GENERIC = 1
 
 EXPORTS = [
     "clover_workspace_bytes", "clover_init", "clover_destroy", "clover_reset", "clover_set_tree",
     "draft_tree", "verify_tree", "accept_and_compact", "clover_accept_forced", "clover_seq_len",
-    "clover_read_kv", "clover_path_info", "clover_profile_phases", "clover_profile_enable", "clover_profile_collect", "clover_kernel_class_count",
+    "clover_read_kv", "clover_path_info", "clover_profile_enable", "clover_profile_collect", "clover_kernel_class_count",
     "clover_kernel_class_name", "clover_last_error", "clover_last_global_error",
     "clover_op_gemm_scratch_bytes", "clover_op_gemm",
 ]
@@ -62,7 +62,7 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     global _lib
     if _lib is not None and path is None:
         return _lib
-    p = path or os.environ.get("CLOVER_LIBRARY") or LIB_PATH   # CLOVER_LIBRARY: another build of the same sources
+    p = path or LIB_PATH
     if not os.path.exists(p):
         raise RuntimeError(f"{p} is missing: build it with `python -m paper_2408_00264_amd.build` "
                            "(there is no CPU fallback)")
@@ -81,7 +81,6 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.clover_seq_len.argtypes = [vp, C.POINTER(C.c_int32)]
     lib.clover_read_kv.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp]
     lib.clover_path_info.argtypes = [vp]
-    lib.clover_profile_phases.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32), i32, C.POINTER(i32)]
     lib.clover_profile_enable.argtypes = [vp, i32]
     lib.clover_profile_collect.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), i32]
     lib.clover_kernel_class_count.argtypes = []
@@ -96,8 +95,8 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.clover_op_gemm.argtypes = [i32, i32, vp, vp, vp, i32, i32, i32, i32, vp, C.c_size_t, vp]
     for n in EXPORTS:
         getattr(lib, n)  # every declared symbol must be exported
-    if path is None:
-        _lib = lib
+    if _lib is None:
+        _lib = lib          # the first library loaded serves the whole process
     return lib
 
 
@@ -247,7 +246,7 @@ class Clover:
         return k, v
 
     def path_info(self) -> int:
-        """Bit 0: MFMA path, bit 1: MFMA tree attention, bit 2: persistent phase-program kernel."""
+        """Bit 0: MFMA path, bit 1: MFMA tree attention."""
         v = self.lib.clover_path_info(self.ctx)
         if v < 0:
             self._check(v)
@@ -262,15 +261,6 @@ class Clover:
         cnt = (C.c_int64 * n)()
         self._check(self.lib.clover_profile_collect(self.ctx, ms, cnt, n))
         return {self.lib.clover_kernel_class_name(i).decode(): (ms[i], cnt[i]) for i in range(n)}
-
-    def profile_phases(self) -> List[tuple]:
-        """(class name, microseconds) per phase of the last profiled persistent-kernel launch."""
-        cap = 4096
-        us = (C.c_double * cap)()
-        cls = (C.c_int32 * cap)()
-        n = C.c_int32(0)
-        self._check(self.lib.clover_profile_phases(self.ctx, us, cls, cap, C.byref(n)))
-        return [(self.lib.clover_kernel_class_name(cls[i]).decode(), us[i]) for i in range(n.value)]
 
     # -- call sequences (no arithmetic here) -----------------------------------------------------
     def prefill(self, prompts: List[np.ndarray], parent, rank, chunk: Optional[int] = None) -> None:

@@ -12,13 +12,27 @@
 
 using namespace clv;
 
+#ifdef CLOVER_ABLATE
+#include <cstdlib>
+#include <map>
+namespace clv {
+int tune_int(const char* name, int dflt) {
+  static std::map<std::string, int> seen;   // read once per process
+  auto it = seen.find(name);
+  if (it != seen.end()) return it->second;
+  const char* v = getenv(name);
+  return seen[name] = v ? atoi(v) : dflt;
+}
+}  // namespace clv
+#endif
+
 namespace {
 
 thread_local std::string g_err;
 
 const char* kClassNames[KC_COUNT] = {"embed",     "rmsnorm",     "gemm_qkv",   "rope_kv_write", "tree_attention", "gemm_wo",
                                      "gemm_gate_up", "gemm_down", "gemm_lm_head", "gemm_draft",  "ad_gate",        "topk",
-                                     "draft_misc", "accept_walk", "compact_kv", "eltwise", "layer_stack"};
+                                     "draft_misc", "accept_walk", "compact_kv", "eltwise"};
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -78,24 +92,6 @@ struct clover_ctx {
   bool panel;              // full-K panel GEMM for the gate+up projection and the LM head
   int row_batch_max = 64;
   int row_batch = 64;      // rows per weight pass for passes of more than 64 rows: 128 when the panel kernel may take them  // passes of up to this many rows run through the <= 64-row GEMM kernels, in batches of 64
-  // persistent phase-program kernel (one cooperative launch per verify pass)
-  bool mega = false;       // usable for this model on this device
-  bool mega_phases = false;  // debugging / profiling: one launch per phase
-  int mega_grid = 0;
-  long long mega_limit = 0;
-  bool mega_shard = false;   // head groups and FFN slices divide by the 8 XCDs: XCD-local chains
-  unsigned mega_seq = 0;   // grid barriers executed since the counters were zeroed
-  unsigned mega_lseq = 0;  // XCD-local barriers executed since then
-  float* d_lbuf;           // 8 per-XCD scratch regions (QKV partials, attention partials)
-  size_t lbuf_stride;      // floats per region
-  MegaSync* d_sync;
-  MegaPhase* d_prog;
-  int prog_cap;
-  float* d_ss;             // [rows][4] sums of squares of the residual rows
-  long long* d_stamps;     // [prog_cap + 1] phase time stamps of the last profiled launch
-  int wall_khz = 100000;
-  std::vector<MegaPhase> prog_host;   // what d_prog holds
-  std::vector<int> prog_cls;          // kernel class of each phase (per-phase profiling)
   // host-side bounds
   std::vector<int> len_ub, aug_ub;
   int m_upper;
@@ -292,7 +288,7 @@ void carve(clover_ctx* x, char* base, size_t* total) {
       }
     }
     // 65..256 rows in batches of 64 through the K-slice kernel: partial tiles of the whole pass
-    if (rows > 64 && !getenv("CLOVER_NO_ROW_BATCH")) {
+    if (rows > 64 && !tune_int("CLOVER_NO_ROW_BATCH", 0)) {
       std::vector<GemmShape> shp;
       model_gemm_shapes(c, shp);
       const int rb = std::min(rows, 256);
@@ -300,8 +296,6 @@ void carve(clover_ctx* x, char* base, size_t* total) {
         if (g.mode != 2 && g.N != c.vocab && g.N != 2 * c.ffn && stream_gemm_supported(64, g.N, g.K))
           pbytes = std::max(pbytes, stream_gemm_out_bytes(rb, g.N, g.K));
     }
-    // the persistent kernel writes up to 8 K-group partials of its QKV / Wo / down projections
-    pbytes = std::max(pbytes, (size_t)8 * std::min(rows, 64) * std::max(x->QKVN, H) * sizeof(float));
     const size_t layer_elems = (size_t)x->QKVN * H + (size_t)H * x->NQD + (size_t)3 * c.ffn * H;
     packed_bytes = 2 * ((size_t)(c.n_layers + c.aug_layers) * layer_elems + (size_t)c.vocab * H + (size_t)7 * H * H +
                         (size_t)(c.draft_depths - 1) * 2 * H * H);
@@ -309,9 +303,9 @@ void carve(clover_ctx* x, char* base, size_t* total) {
   x->packed_bytes = packed_bytes;
   x->packed = cv.take<char>(packed_bytes ? packed_bytes : 256);
   x->fast = fast;
-  x->panel = fast && !getenv("CLOVER_NO_PANEL");
-  x->row_batch_max = (fast && !getenv("CLOVER_NO_ROW_BATCH")) ? 256 : 64;
-  x->row_batch = (x->panel && !getenv("CLOVER_ROW_BATCH_64")) ? 128 : 64;
+  x->panel = fast && !tune_int("CLOVER_NO_PANEL", 0);
+  x->row_batch_max = (fast && !tune_int("CLOVER_NO_ROW_BATCH", 0)) ? 256 : 64;
+  x->row_batch = (x->panel && !tune_int("CLOVER_ROW_BATCH_64", 0)) ? 128 : 64;
   x->kvdtype = fast ? 1 : 0;
   x->kv_layer_stride = fast ? 2 * x->k_layer_elems : x->k_layer_elems;
   x->attn_fast = fast && attn_mfma_supported(d, c.n_q_heads, c.n_kv_heads, c.max_seq);
@@ -321,21 +315,6 @@ void carve(clover_ctx* x, char* base, size_t* total) {
   x->partial_bytes = pbytes;
   x->partial = (float*)cv.take<char>(pbytes);
   x->pl_y = cv.take<float>((size_t)rows * 2 * H);
-  x->d_sync = cv.take<MegaSync>(1);
-  x->prog_cap = 2 + 9 * std::max(c.n_layers, c.aug_layers);
-  x->d_prog = cv.take<MegaPhase>(x->prog_cap);
-  x->d_ss = cv.take<float>((size_t)std::max(rows, 64) * 4);
-  x->d_stamps = cv.take<long long>(x->prog_cap + 1);
-  {
-    // per-XCD scratch of the sharded persistent kernel: QKV partials [<= 8 K groups][64 rows][its columns], then
-    // the attention partial outputs and (max, sum) pairs of its query heads
-    const int r64 = std::min(rows, 64);
-    const size_t nq8 = (size_t)(c.n_q_heads + 7) / 8, nkv8 = (size_t)(c.n_kv_heads + 7) / 8;
-    const size_t qkv = (size_t)8 * r64 * (nq8 + 2 * nkv8) * d;
-    const size_t op = (size_t)16 * rows * nq8 * d, ml = (size_t)16 * rows * nq8 * 2;
-    x->lbuf_stride = (qkv + op + ml + 3 * 64 + 63) / 64 * 64;
-    x->d_lbuf = cv.take<float>(fast ? 8 * x->lbuf_stride : 64);
-  }
   *total = cv.off;
 }
 
@@ -571,228 +550,6 @@ void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMa
 }
 
 
-// ---- persistent phase-program path ----------------------------------------------------------
-// Is the phase-program kernel usable for this model?  (bf16 MFMA path, head_dim 128, every GEMM shape
-// a multiple of the kernel's tiles, fused weights contiguous in the packed copy.)
-bool mega_model_ok(clover_ctx* x) {
-  const clover_config& c = x->cfg;
-  const int H = x->H, F = c.ffn;
-  if (!x->fast || !x->attn_fast || c.head_dim != 128) return false;
-  if (H % 256 || x->NQD % 256 || F % 256 || x->QKVN % 16 || H % 16 || F % 16 || c.vocab % 16) return false;
-  if (!mega_gemm_supported(64, x->QKVN, H) || !mega_gemm_supported(64, H, x->NQD) || !mega_gemm_supported(64, 2 * F, H) ||
-      !mega_gemm_supported(64, H, F) || !mega_gemm_supported(64, c.vocab, H))
-    return false;
-  auto fused = [&](const clover_layer_weights& l) {
-    const char* q = (const char*)l.wq;
-    return (const char*)l.wk == q + (size_t)x->NQD * H * 2 &&
-           (const char*)l.wv == q + (size_t)(x->NQD + c.n_kv_heads * c.head_dim) * H * 2 &&
-           (const char*)l.w_up == (const char*)l.w_gate + (size_t)F * H * 2;
-  };
-  for (const auto& l : x->layers) if (!fused(l)) return false;
-  for (const auto& l : x->aug) if (!fused(l)) return false;
-  return true;
-}
-
-struct MegaBuilder {
-  clover_ctx* x;
-  int M;
-  std::vector<MegaPhase> prog;
-  std::vector<int> cls;
-  int n_global = 0, n_local = 0;  // barriers so far, by kind
-  MegaPhase blank() const {
-    static const int dbg = [] { const char* v = getenv("CLOVER_MEGA_DBG"); return v ? atoi(v) : 0; }();
-    MegaPhase p;
-    memset(&p, 0, sizeof(p));
-    p.M = M; p.H = x->H; p.eps = x->cfg.rms_eps; p.dbg = dbg;
-    p.wt = 1;
-    return p;
-  }
-  // `local`: the barrier in front of the phase is XCD-local (all its inputs were produced on the same XCD)
-  void push(MegaPhase p, int c, bool local = false) {
-    p.sync = local ? 1 : 0;
-    if (!prog.empty()) p.bar_ord = local ? ++n_local : ++n_global;
-    prog.push_back(p);
-    cls.push_back(c);
-  }
-  MegaPhase gemm_desc(Planes X, const void* W, int N, int K, int epi) const {
-    MegaPhase p = blank();
-    p.op = MG_OP_GEMM; p.N = N; p.K = K; p.epi = epi; p.KG = 1;
-    p.Xhi = X.hi; p.Xlo = X.lo; p.ldx = X.ld;
-    p.W = (const bf16_t*)W; p.w_bytes = (unsigned)((size_t)(epi == 1 ? 2 * N : N) * K * 2);
-    p.ss = x->d_ss;
-    return p;
-  }
-  // unsharded GEMM; returns the K-group count, 0 if the partial buffer is too small
-  int gemm(int c, Planes X, const void* W, int N, int K, int epi, float* Y, int ldy, Planes out) {
-    MegaPhase p = gemm_desc(X, W, N, K, epi);
-    p.KG = mega_pick_kg(N, K, epi, x->mega_grid);
-    if (epi == 0) {
-      if ((size_t)p.KG * M * N * sizeof(float) > x->partial_bytes) return 0;
-      p.Y = x->partial; p.ldy = N; p.split_stride = (size_t)M * N;
-    } else if (epi == 2) {
-      p.Y = Y; p.ldy = ldy;
-    } else {
-      p.Yhi = out.hi; p.Ylo = out.lo; p.ldo = out.ld;
-    }
-    push(p, c);
-    return p.KG;
-  }
-  // x (+)= KG partials [k][M][N] in the shared partial buffer; planes of x * gain
-  void reduce(float* xres, int KG, int N, const void* gain, Planes out, const int* tok, const void* table) {
-    MegaPhase p = blank();
-    p.op = MG_OP_REDUCE; p.KG = KG;
-    p.Y = x->partial; p.ldy = N; p.split_stride = (size_t)M * N;
-    p.x = xres; p.gain = (const bf16_t*)gain; p.ss_out = x->d_ss;
-    p.Yhi = out.hi; p.Ylo = out.lo; p.ldo = out.ld;
-    p.tok = tok; p.table = (const bf16_t*)table; p.vocab = x->cfg.vocab;
-    push(p, KC_RMSNORM);
-  }
-};
-
-// boundaries that split n_stages 256-column stages over the 8 XCDs as evenly as whole stages allow
-void stage_bounds(int n_stages, int (&b)[9]) {
-  for (int i = 0; i <= 8; ++i) b[i] = (int)((long long)i * n_stages / 8);
-}
-
-// One decoder layer as phases.  On entry the planes of a_norm hold xres * attn_norm of this layer and d_ss
-// the sums of squares of xres; on exit they hold xres * next_gain.
-bool mega_layer(MegaBuilder& mb, const clover_layer_weights& lw, float* xres, RowMap rm, char* kc_layer, char* vc_layer,
-                const int* base_len, const unsigned long long* anc, const void* next_gain) {
-  clover_ctx* x = mb.x;
-  const clover_config& c = x->cfg;
-  const int H = x->H, d = c.head_dim, F = c.ffn, M = mb.M;
-  const bool sh = x->mega_shard;
-  Planes A = planes_of(x, x->a_norm, 2 * H);
-  A.ld = H;
-  Planes Q = planes_of(x, x->q_rot, x->NQD);
-  Planes O = planes_of(x, x->attn_out, x->NQD);
-  Planes Hf = planes_of(x, x->h_ffn, F);
-  const Planes none{nullptr, nullptr, 0};
-  const int nq8 = c.n_q_heads / 8, nkv8 = c.n_kv_heads / 8, nw = x->mega_grid / 8;
-  const int G = c.n_q_heads / c.n_kv_heads;
-  const int ngw = std::max(1, 8 / G), node_groups = (rm.n + 31) / 32, chunks = (node_groups + ngw - 1) / ngw;
-
-  // ---- QKV projection ----
-  int kq, ldq_part;
-  size_t sps_q;
-  if (sh) {
-    MegaPhase p = mb.gemm_desc(A, lw.wq, x->QKVN, H, 0);
-    p.shard = 1; p.wt = 0;
-    const int lb = (nq8 + 2 * nkv8) * 8;  // 16-column blocks per XCD
-    int kgl = 8;
-    while (kgl > 1 && (kgl > H / 256 || (long long)lb * kgl > (long long)8 * nw || nw % kgl)) kgl >>= 1;
-    p.KG = kgl;
-    p.seg_base[0] = 0; p.seg_base[1] = x->NQD / 16; p.seg_base[2] = (x->NQD + c.n_kv_heads * d) / 16;
-    for (int i = 0; i <= 8; ++i) { p.seg_bnd[0][i] = i * nq8 * 8; p.seg_bnd[1][i] = p.seg_bnd[2][i] = i * nkv8 * 8; }
-    p.ldy = lb * 16; p.split_stride = (size_t)M * p.ldy;
-    p.lbuf = x->d_lbuf; p.lbuf_stride = x->lbuf_stride;
-    mb.push(p, KC_GEMM_QKV);
-    kq = kgl; ldq_part = p.ldy; sps_q = p.split_stride;
-  } else {
-    kq = mb.gemm(KC_GEMM_QKV, A, lw.wq, x->QKVN, H, 0, nullptr, 0, none);
-    if (!kq) return false;
-    ldq_part = x->QKVN; sps_q = (size_t)M * x->QKVN;
-  }
-
-  // ---- RoPE + KV write, attention, merge ----
-  MegaPhase p = mb.blank();
-  p.op = MG_OP_ROPE; p.KG = kq;
-  p.Y = x->partial; p.ldy = ldq_part; p.split_stride = sps_q;
-  p.ss = x->d_ss;
-  p.rm = rm; p.n_q = c.n_q_heads; p.n_kv = c.n_kv_heads; p.max_seq = c.max_seq; p.base_len = base_len; p.err_flag = x->d_err;
-  p.cos_t = x->cos_t; p.sin_t = x->sin_t; p.q_scale = 1.0f / sqrtf((float)d);
-  p.q_hi = Q.hi; p.q_lo = Q.lo; p.ldq = x->NQD;
-  p.k_hi = (bf16_t*)kc_layer; p.k_plane = x->k_layer_elems;
-  p.v_hi = (bf16_t*)vc_layer; p.v_plane = x->v_layer_elems;
-  p.anc = anc;
-  p.o_part = x->o_part; p.ml_part = x->ml_part; p.rows_total = x->max_rows;
-  p.Yhi = O.hi; p.Ylo = O.lo; p.ldo = x->NQD;
-  if (sh) {
-    p.shard = 1; p.wt = 0;
-    p.lbuf = x->d_lbuf; p.lbuf_stride = x->lbuf_stride;
-    const size_t qkv_floats = ((size_t)8 * std::min(x->max_rows, 64) * (nq8 + 2 * nkv8) * d + 63) / 64 * 64;
-    p.lo_off = qkv_floats;
-    p.lml_off = qkv_floats + ((size_t)16 * x->max_rows * nq8 * d + 63) / 64 * 64;
-    p.n_splits = std::max(1, std::min(16, nw / std::max(1, rm.B * nkv8 * chunks)));
-  } else {
-    p.n_splits = std::max(1, std::min(x->attn_max_splits, x->mega_grid / std::max(1, rm.B * c.n_kv_heads * chunks)));
-  }
-  mb.push(p, KC_ROPE_KV, sh);
-  p.op = MG_OP_ATTN;
-  mb.push(p, KC_ATTN, sh);
-  p.op = MG_OP_MERGE;
-  mb.push(p, KC_ELTWISE, sh);
-
-  // ---- output projection, residual ----
-  if (sh) {
-    MegaPhase g = mb.gemm_desc(O, lw.wo, H, x->NQD, 0);
-    g.shard = 2; g.wt = 1; g.KG = 8;
-    stage_bounds(x->NQD / 256, g.ks_bnd);
-    g.Y = x->partial; g.ldy = H; g.split_stride = (size_t)M * H;
-    mb.push(g, KC_GEMM_WO, true);
-    mb.reduce(xres, 8, H, lw.ffn_norm, A, nullptr, nullptr);
-  } else {
-    const int kw = mb.gemm(KC_GEMM_WO, O, lw.wo, H, x->NQD, 0, nullptr, 0, none);
-    if (!kw) return false;
-    mb.reduce(xres, kw, H, lw.ffn_norm, A, nullptr, nullptr);
-  }
-
-  // ---- FFN ----
-  if (sh) {
-    MegaPhase g = mb.gemm_desc(A, lw.w_gate, F, H, 1);
-    g.shard = 1; g.wt = 0; g.KG = 1;
-    int fb[9];
-    stage_bounds(F / 256, fb);
-    for (int i = 0; i <= 8; ++i) g.seg_bnd[0][i] = fb[i] * 16;
-    g.Yhi = Hf.hi; g.Ylo = Hf.lo; g.ldo = F;
-    g.lbuf = x->d_lbuf; g.lbuf_stride = x->lbuf_stride;
-    mb.push(g, KC_GEMM_GATEUP);
-    MegaPhase dn = mb.gemm_desc(Hf, lw.w_down, H, F, 0);
-    dn.shard = 2; dn.wt = 1; dn.KG = 8;
-    for (int i = 0; i <= 8; ++i) dn.ks_bnd[i] = fb[i];
-    dn.Y = x->partial; dn.ldy = H; dn.split_stride = (size_t)M * H;
-    mb.push(dn, KC_GEMM_DOWN, true);
-    mb.reduce(xres, 8, H, next_gain, A, nullptr, nullptr);
-  } else {
-    mb.gemm(KC_GEMM_GATEUP, A, lw.w_gate, F, H, 1, nullptr, 0, Hf);
-    const int kd = mb.gemm(KC_GEMM_DOWN, Hf, lw.w_down, H, F, 0, nullptr, 0, none);
-    if (!kd) return false;
-    mb.reduce(xres, kd, H, next_gain, A, nullptr, nullptr);
-  }
-  return true;
-}
-
-// upload (if it changed) and run a program; one launch, or one launch per phase when profiling by phase
-int mega_run(clover_ctx* x, MegaBuilder& mb, const char* what) {
-  const int n = (int)mb.prog.size();
-  if (n > x->prog_cap) return fail(x, CLOVER_E_CAPACITY, "internal: phase program too long");
-  if (x->prog_host.size() != mb.prog.size() ||
-      memcmp(x->prog_host.data(), mb.prog.data(), mb.prog.size() * sizeof(MegaPhase)) != 0) {
-    // the previous program may still be running: the copy is stream-ordered behind it
-    hipError_t e = hipMemcpyAsync(x->d_prog, mb.prog.data(), mb.prog.size() * sizeof(MegaPhase), hipMemcpyHostToDevice, x->st);
-    if (e == hipSuccess) e = hipStreamSynchronize(x->st);  // pageable source: make sure it was consumed
-    if (e != hipSuccess) return fail(x, CLOVER_E_HIP, std::string(what) + ": program upload: " + hipGetErrorString(e));
-    x->prog_host = mb.prog;
-    x->prog_cls = mb.cls;
-  }
-  hipError_t e = hipSuccess;
-  if (x->mega_phases) {
-    for (int p = 0; p < n && e == hipSuccess; ++p) {
-      Scope sc(x, x->prog_cls[p]);
-      e = launch_mega(x->d_prog, p, p + 1, x->d_sync, x->mega_seq, x->mega_lseq, x->mega_limit, x->d_err, nullptr, 0,
-                      x->mega_grid, x->st);
-    }
-  } else {
-    Scope sc(x, KC_MEGA);
-    e = launch_mega(x->d_prog, 0, n, x->d_sync, x->mega_seq, x->mega_lseq, x->mega_limit, x->d_err,
-                    x->prof ? x->d_stamps : nullptr, mb.n_global > 0 ? 1 : 0, x->mega_grid, x->st);
-    x->mega_seq += (unsigned)mb.n_global;
-    x->mega_lseq += (unsigned)mb.n_local;
-  }
-  if (e != hipSuccess) return fail(x, CLOVER_E_HIP, std::string(what) + ": cooperative launch: " + hipGetErrorString(e));
-  return CLOVER_OK;
-}
-
 // planes of RMSNorm(src) * gain in the a_norm buffer (MFMA path)
 Planes norm_planes(clover_ctx* x, const float* src, const void* gain, int rows) {
   const clover_config& c = x->cfg;
@@ -873,7 +630,7 @@ void run_head(clover_ctx* x, const float* g, int rows, int k) {
 // for the Attention Decoder's projections, room for the q and the k|v partials side by side.)
 bool draft_fused_ok(clover_ctx* x, int rows) {
   const int H = x->H;
-  if (!x->fast || rows < 1 || rows > 64 || getenv("CLOVER_DRAFT_UNFUSED")) return false;
+  if (!x->fast || rows < 1 || rows > 64 || tune_int("CLOVER_DRAFT_UNFUSED", 0)) return false;
   if (!ad_gate_fused_supported(H, x->cfg.ad_heads)) return false;
   if (!stream_gemm_supported(rows, H, H) || !stream_gemm_supported(rows, 2 * H, H) || !stream_gemm_supported(rows, H, 2 * H) ||
       !stream_gemm_supported(rows, x->cfg.vocab, H))
@@ -1048,18 +805,6 @@ int clover_init(const clover_config* cfg, const clover_weights* w, const clover_
     pack(x->w.fc0_w, H, H);
     for (int j = 1; j < cfg->draft_depths; ++j) pack(x->fc_w[j], H, 2 * H);
     if ((size_t)(cur - x->packed) > x->packed_bytes) { delete x; return fail(nullptr, CLOVER_E_CAPACITY, "internal: packed weights overflow"); }
-    hipMemsetAsync(x->d_sync, 0, sizeof(MegaSync), x->st);
-    x->mega_seq = 0;
-    x->mega_grid = ((cfg->flags & CLOVER_FLAG_MEGA) || getenv("CLOVER_MEGA")) ? mega_grid_size() : 0;
-    x->mega = x->mega_grid > 0 && mega_model_ok(x) && mega_barrier_timeout_ticks(&x->mega_limit) == 0;
-    x->mega_phases = getenv("CLOVER_MEGA_PHASES") != nullptr;
-    x->mega_lseq = 0;
-    // XCD sharding: head groups, their attention-output columns and the FFN stages must divide by the 8 XCDs
-    x->mega_shard = x->mega && !getenv("CLOVER_MEGA_NOSHARD") && cfg->n_q_heads % 8 == 0 && cfg->n_kv_heads % 8 == 0 &&
-                    (x->NQD / 8) % 256 == 0 && cfg->ffn / 256 >= 8 && x->mega_grid % 8 == 0 && x->mega_grid >= 64;
-    { int dev = 0, khz = 0;
-      if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && khz > 0)
-        x->wall_khz = khz; }
   }
   rc = upload_tree(x);
   if (rc == CLOVER_OK) rc = finish(x, "init");
@@ -1082,11 +827,6 @@ int clover_reset(clover_ctx* x) {
   launch_fill_i32(x->d_seq_len, 0, x->cfg.max_batch, x->st);
   launch_fill_i32(x->d_aug_len, 0, x->cfg.max_batch, x->st);
   launch_fill_i32(x->d_err, 0, 1, x->st);
-  if (x->fast) {
-    hipMemsetAsync(x->d_sync, 0, sizeof(MegaSync), x->st);
-    x->mega_seq = 0;
-    x->mega_lseq = 0;
-  }
   std::fill(x->len_ub.begin(), x->len_ub.end(), 0);
   std::fill(x->aug_ub.begin(), x->aug_ub.end(), 0);
   x->m_upper = x->cfg.max_nodes;
@@ -1236,26 +976,6 @@ int verify_tree(clover_ctx* x, int32_t batch, const int32_t* tree_tokens, float*
   const int M = (B - 1) * R + t.n;
   int key_bound = 0;
   for (int b = 0; b < B; ++b) key_bound = std::max(key_bound, x->len_ub[b] + t.n);
-  if (x->mega && M <= 64) {
-    // the whole pass as one phase program: embedding, the layers, final norm scale + LM head
-    { Scope s(x, KC_ROPE_KV); launch_rope_table(x->d_seq_len, x->d_depth, c.rope_base, c.head_dim, x->cos_t, x->sin_t, rm, x->st); }
-    MegaBuilder mb{x, M};
-    Planes A = planes_of(x, x->a_norm, 2 * H);
-    A.ld = H;
-    mb.reduce(hidden, 0, H, x->layers[0].attn_norm, A, tree_tokens, x->w.embed);
-    mb.cls.back() = KC_EMBED;
-    bool ok = true;
-    for (int l = 0; l < c.n_layers && ok; ++l)
-      ok = mega_layer(mb, x->layers[l], hidden, rm, x->kc + (size_t)l * x->k_layer_elems * x->kv_esz,
-                      x->vc + (size_t)l * x->v_layer_elems * x->kv_esz, x->d_seq_len, x->d_anc,
-                      l + 1 < c.n_layers ? x->layers[l + 1].attn_norm : x->w.final_norm);
-    if (ok) {
-      mb.gemm(KC_GEMM_LMHEAD, A, x->lm_head_pk, c.vocab, H, 2, logits, c.vocab, Planes{nullptr, nullptr, 0});
-      rc = mega_run(x, mb, "verify_tree");
-      if (rc) return rc;
-      return finish(x, "verify_tree");
-    }
-  }
   { Scope s(x, KC_EMBED); launch_embed(x->w.embed, c.dtype, tree_tokens, c.vocab, hidden, H, H, rm, x->st); }
   { Scope s(x, KC_ROPE_KV); launch_rope_table(x->d_seq_len, x->d_depth, c.rope_base, c.head_dim, x->cos_t, x->sin_t, rm, x->st); }
   if (x->fast) norm_planes(x, hidden, x->layers[0].attn_norm, M);
@@ -1315,8 +1035,6 @@ int clover_seq_len(clover_ctx* x, int32_t* out_host) {
   if (e == hipSuccess) e = hipStreamSynchronize(x->st);
   if (e != hipSuccess) return fail(x, CLOVER_E_HIP, std::string("clover_seq_len: ") + hipGetErrorString(e));
   for (int b = 0; b < B; ++b) { x->len_ub[b] = out_host[b]; x->aug_ub[b] = aug[b]; }
-  if (err & 2) return fail(x, CLOVER_E_STATE, "a barrier of the persistent kernel timed out; results are invalid (clover_reset clears the state)");
-  if (err & 4) return fail(x, CLOVER_E_STATE, "workgroups i and i + 8 of the persistent kernel did not share an XCD; sharded results are invalid");
   if (err) return fail(x, CLOVER_E_STATE, "a kernel refused to write past max_seq");
   return CLOVER_OK;
 }
@@ -1365,24 +1083,7 @@ int clover_profile_collect(clover_ctx* x, double* ms, int64_t* launches, int32_t
 
 int clover_path_info(clover_ctx* x) {
   if (!x) return CLOVER_E_NULL;
-  return (x->fast ? 1 : 0) | (x->attn_fast ? 2 : 0) | (x->mega ? 4 : 0) | (x->mega_shard ? 8 : 0);
-}
-
-int clover_profile_phases(clover_ctx* x, double* us_by_phase, int32_t* class_by_phase, int32_t max_phases, int32_t* n_out) {
-  if (!x || !us_by_phase || !class_by_phase || !n_out) return fail(x, CLOVER_E_NULL, "null argument");
-  const int n = (int)x->prog_host.size();
-  *n_out = n;
-  if (n == 0 || !x->mega) return CLOVER_OK;
-  if (max_phases < n) return fail(x, CLOVER_E_SHAPE, "max_phases too small");
-  std::vector<long long> t(n + 1);
-  hipError_t e = hipMemcpyAsync(t.data(), x->d_stamps, (n + 1) * sizeof(long long), hipMemcpyDeviceToHost, x->st);
-  if (e == hipSuccess) e = hipStreamSynchronize(x->st);
-  if (e != hipSuccess) return fail(x, CLOVER_E_HIP, std::string("clover_profile_phases: ") + hipGetErrorString(e));
-  for (int p = 0; p < n; ++p) {
-    us_by_phase[p] = (double)(t[p + 1] - t[p]) * 1e3 / (double)x->wall_khz;
-    class_by_phase[p] = x->prog_cls[p];
-  }
-  return CLOVER_OK;
+  return (x->fast ? 1 : 0) | (x->attn_fast ? 2 : 0);
 }
 
 int clover_kernel_class_count(void) { return KC_COUNT; }

@@ -12,7 +12,7 @@ typedef unsigned short bf16_t;  // raw bfloat16 bit pattern
 
 enum KernelClass {
   KC_EMBED = 0, KC_RMSNORM, KC_GEMM_QKV, KC_ROPE_KV, KC_ATTN, KC_GEMM_WO, KC_GEMM_GATEUP, KC_GEMM_DOWN,
-  KC_GEMM_LMHEAD, KC_GEMM_DRAFT, KC_AD_GATE, KC_TOPK, KC_DRAFT_MISC, KC_ACCEPT, KC_COMPACT, KC_ELTWISE, KC_MEGA,
+  KC_GEMM_LMHEAD, KC_GEMM_DRAFT, KC_AD_GATE, KC_TOPK, KC_DRAFT_MISC, KC_ACCEPT, KC_COMPACT, KC_ELTWISE,
   KC_COUNT
 };
 
@@ -113,7 +113,7 @@ struct MfmaGemm {
   int M, N, K;
   int mode;                // 0 partial/plain fp32 store, 2 SwiGLU
   int splits;              // split-K factor (>=1; 1 for mode 2)
-  int dbg;                 // timing experiments only (CLOVER_GEMM_DBG): 1 no MFMA, 2 no weight loads, 4 no activation loads
+  int dbg;                 // ablation builds only: 1 no MFMA, 2 no weight loads, 4 no activation loads
 };
 bool mfma_gemm_supported(int M, int N, int K, int mode);
 int mfma_gemm_pick_splits(int M, int N, int K, int mode);
@@ -152,7 +152,7 @@ struct StreamGemm {
   int M, N, K;
   int n_slices, groups;               // filled in by launch_gemm_stream
   int tag;                            // 1: gate+up projection (selects a separately named instantiation)
-  int dbg;                            // timing experiments only (CLOVER_STREAM_DBG): 1 no activation loads, 2 no stores
+  int dbg;                            // ablation builds only: 1 no activation loads, 2 no stores
 };
 bool stream_gemm_supported(int M, int N, int K);
 int stream_gemm_slices(int K);
@@ -173,7 +173,7 @@ struct PanelGemm {
   int epi;                            // 0 plain, 1 SwiGLU
   int k_parts; size_t split_stride;   // epi 0 only: K is cut into k_parts ranges, range r writes Y + r * split_stride
   int rows128;                        // use the 65..128-row form whatever M is (k_parts was picked for its stage width)
-  int dbg;                            // timing experiments only (CLOVER_PANEL_DBG): 1 no activation loads
+  int dbg;                            // ablation builds only: 1 no activation loads, 2 no stage rotation
 };
 bool panel_gemm_supported(int M, int N, int K, int epi);
 // how many K ranges make the plain panel GEMM fill the chip for a NARROW output (0: not worth it)
@@ -208,68 +208,16 @@ void launch_draft_level(const float* state, const int* tokens, const int* nodes,
                         int R, int H, const void* table, int vocab, const void* gain, float eps, bf16_t* a_hi,
                         bf16_t* a_lo, bf16_t* y_hi, bf16_t* y_lo, bf16_t* c_hi, bf16_t* c_lo, hipStream_t st);
 
-// ---- persistent phase-program kernel (M <= 64 rows, bf16 weights, head_dim 128) -------------------
-// One cooperative launch walks phases [p_begin, p_end) of a program with a barrier before each phase
-// after the first.  Every pointer is a device pointer; buffers written in one phase and read in a later
-// one must not be touched by anything else while the launch runs.
-//
-// XCD sharding (shard != 0).  Workgroups with the same index modulo 8 run on the same XCD and share its
-// L2.  When the head and FFN counts divide by 8, XCD x owns head group x and FFN slice x for the whole
-// layer: QKV columns -> RoPE -> attention -> merge -> its K slice of the output projection, and gate/up
-// columns -> SwiGLU -> its K slice of the down projection.  Inside such a chain data passes through the
-// XCD's own L2 (plain stores, an L1 invalidate, an XCD-local barrier of ~1 us); only the two residual
-// sums per layer cross XCDs (write-through stores, L2 invalidate, grid barrier of ~4 us).
-enum MegaOp { MG_OP_GEMM = 1, MG_OP_REDUCE, MG_OP_ROPE, MG_OP_ATTN, MG_OP_MERGE };
-struct MegaSync {
-  unsigned xcount[8 * 64];  // grid barrier: arrivals per XCD group (workgroup % 8), one counter per 256 bytes
-  unsigned lcount[8 * 64];  // XCD-local barriers: arrivals per XCD group
-  unsigned top;             // grid barrier: XCD groups that have completed it
-  unsigned abort;           // sticky: a barrier timed out
-  unsigned off_tag;         // (launch tag << 3) | (XCC id - workgroup index) mod 8 of workgroup 0: must hold for every workgroup
-  unsigned pad[61];
-};
-struct MegaPhase {
-  int op, M;                                   // M: rows b*R + i of the row map, <= 64
-  int sync;                                    // barrier before this phase: 0 grid-wide, 1 XCD-local
-  int bar_ord;                                 // 1-based ordinal of that barrier among the program's barriers of its kind
-  int wt;                                      // 1: outputs are written through (read on other XCDs), 0: plain stores
-  int shard;                                   // 0: work spread over all workgroups; GEMM 1: column-sharded, 2: K-sharded;
-                                               // ROPE / ATTN / MERGE 1: XCD x handles head group x
-  // GEMM: out = X[M,K] * W[N,K]^T
-  int N, K, KG, epi;                           // KG K-groups (shard 0: 1, 2, 4, 8 over the XCDs; shard 1: local groups);
-                                               // epi 0: fp32 partial per K-group, 1: SwiGLU planes (N = F; W = gate rows,
-                                               // then up rows), 2: fp32 out
-  const bf16_t *Xhi, *Xlo; int ldx;            // activation planes
-  const bf16_t* W; unsigned w_bytes;           // fragment-major weights
-  float* Y; int ldy; size_t split_stride;      // GEMM out (epi 0: K-group g at Y + g*split_stride); partials in for REDUCE / ROPE
-  bf16_t *Yhi, *Ylo; int ldo;                  // planes out (GEMM epi 1, REDUCE, MERGE)
-  const float* ss; int H; float eps;           // [row][4] sums of squares of the row the input planes came from:
-                                               // epi 1 / 2 and ROPE scale by rsqrt(sum / H + eps) (the RMSNorm scale)
-  int seg_base[3], seg_bnd[3][9];              // shard 1: XCD x owns the 16-column blocks seg_base[s] + [seg_bnd[s][x], seg_bnd[s][x+1])
-  int ks_bnd[9];                               // shard 2: XCD x owns the 256-column K stages [ks_bnd[x], ks_bnd[x+1])
-  float* lbuf; size_t lbuf_stride;             // shard 1: XCD x's private scratch = lbuf + x*lbuf_stride (floats): QKV partials
-                                               // [KG][M][ldy] with LOCAL column indices, then the attention partials
-  size_t lo_off, lml_off;                      // float offsets of the attention partial outputs / (max, sum) pairs in it
-  // REDUCE: x[g,:] = (tok ? table[tok[g]] : x[g,:]) + sum of KG partials; planes of x*gain; ss_out
-  float* x; const bf16_t* gain; float* ss_out; const int* tok; const bf16_t* table; int vocab;
-  // ROPE / ATTN / MERGE
-  RowMap rm; int n_q, n_kv, max_seq; const int* base_len; int* err_flag;
-  const float *cos_t, *sin_t; float q_scale;
-  bf16_t *q_hi, *q_lo; int ldq;
-  bf16_t* k_hi; size_t k_plane; bf16_t* v_hi; size_t v_plane;   // caches of this layer (lo plane = hi + plane)
-  const unsigned long long* anc;
-  float *o_part, *ml_part; int rows_total, n_splits;            // shard 0 partial outputs; n_splits in both modes
-  int dbg;                                     // timing experiments only (CLOVER_MEGA_DBG), 0 in normal use
-};
-int mega_grid_size();   // workgroups of a launch on the current device; 0: cooperative launch not available
-int mega_barrier_timeout_ticks(long long* out);
-int mega_pick_kg(int N, int K, int epi, int grid);
-bool mega_gemm_supported(int M, int N, int K);
-// stamps: null, or dev [n_phases + 1] wall-clock ticks (phase starts as seen by workgroup 0, then the end)
-// gseq_base / lseq_base: grid-wide / XCD-local barriers executed since the counters were zeroed
-// check_xcd: compare every workgroup's XCD placement with workgroup 0's at the end (needs a grid barrier in the range)
-hipError_t launch_mega(const MegaPhase* prog_dev, int p_begin, int p_end, MegaSync* sync, unsigned gseq_base,
-                       unsigned lseq_base, long long limit_ticks, int* err_flag, long long* stamps, int check_xcd,
-                       int grid, hipStream_t st);
+// ---- tuning knobs -------------------------------------------------------------------------------
+// The shipped library reads no environment variable: every knob is its default.  A build with
+// -DCLOVER_ABLATE (kernel-tuning experiments only) reads CLOVER_<NAME> once per process instead, and only
+// such a build honours the `dbg` fields of the GEMM descriptors (ablations that skip loads or stores).
+#ifdef CLOVER_ABLATE
+int tune_int(const char* name, int dflt);
+#define CLV_DBG(p, bit) ((p).dbg & (bit))
+#else
+inline int tune_int(const char*, int dflt) { return dflt; }
+#define CLV_DBG(p, bit) 0
+#endif
 
 }  // namespace clv

@@ -344,7 +344,7 @@ void launch_attn_mfma(AttnParams p, int max_total_keys, bf16_t* out_hi, bf16_t* 
   const int n_tiles = (max_total_keys + AT_TK - 1) / AT_TK;
   // about one workgroup per CU (two on a CU do not overlap: a CU finishes one key tile per ~4 us either way, so a
   // launch of 1.5 workgroups per CU takes as long as one of 2), at least two tiles per split, within the partial buffer
-  static const int target = [] { const char* v = getenv("CLOVER_ATTN_WGS"); return v ? atoi(v) : 256; }();
+  const int target = tune_int("CLOVER_ATTN_WGS", 256);
   int splits = std::max(1, target / (p.rm.B * p.n_kv * node_groups));
   splits = std::max(1, std::min(std::min(splits, std::min(p.max_splits, MG_MAXS)), (n_tiles + 1) / 2));
   p.tiles_per_split = (n_tiles + splits - 1) / splits;
@@ -352,7 +352,7 @@ void launch_attn_mfma(AttnParams p, int max_total_keys, bf16_t* out_hi, bf16_t* 
   dim3 grid(p.n_splits, node_groups * p.n_kv, p.rm.B);
   // Two wavefronts per head (16 nodes each) share a SIMD, so one's matrix products overlap the other's soft-max
   // arithmetic, and both share the staged K / V^T tile.
-  static const int wm1 = getenv("CLOVER_ATTN_WM1") != nullptr;
+  const int wm1 = tune_int("CLOVER_ATTN_WM1", 0);
   switch (g) {
     case 1: if (wm1) launch_attn_one<1, 1>(p, grid, st); else launch_attn_one<1, 2>(p, grid, st); break;
     case 2: if (wm1) launch_attn_one<2, 1>(p, grid, st); else launch_attn_one<2, 2>(p, grid, st); break;

@@ -107,7 +107,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(MfmaGemm p) {
         const int plane = idx / (ROWS * SLOTS), rem = idx % (ROWS * SLOTS);
         const int r = rem / SLOTS, sl = rem % SLOTS;
         v[it] = (u32x4){0u, 0u, 0u, 0u};
-        if (r < M && !(p.dbg & 4)) v[it] = *(const u32x4*)((plane ? p.Xlo : p.Xhi) + (size_t)r * p.ldx + kc + sl * 8);
+        if (r < M && !CLV_DBG(p, 4)) v[it] = *(const u32x4*)((plane ? p.Xlo : p.Xhi) + (size_t)r * p.ldx + kc + sl * 8);
       }
 #pragma unroll
       for (int it = 0; it < NIT; ++it) {
@@ -151,7 +151,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(MfmaGemm p) {
     constexpr int RING = 4;        // weight fragments of up to three future chunks are in flight
     Frag w[RING][NF][KS];
     auto load_w = [&](int slot, int kc) {
-      if (!active || (p.dbg & 2)) return;
+      if (!active || CLV_DBG(p, 2)) return;
 #pragma unroll
       for (int f = 0; f < NF; ++f)
 #pragma unroll
@@ -160,7 +160,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(MfmaGemm p) {
     };
     auto compute = [&](int slot, int buf) {
       if (!active) return;
-      if (p.dbg & 1) {  // keep the loads alive without the matrix work
+      if (CLV_DBG(p, 1)) {  // keep the loads alive without the matrix work
 #pragma unroll
         for (int f = 0; f < NF; ++f)
 #pragma unroll
@@ -246,10 +246,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(MfmaGemm p) {
 // ------------------------------------------------------------------------------------------
 static int mt_for(int M) { return M <= 16 ? 1 : M <= 32 ? 2 : M <= 64 ? 4 : M <= 128 ? 8 : 16; }
 static int kc_for(int mt) { return mt <= 4 ? 128 : mt == 8 ? 64 : 32; }
-static int env_int(const char* name) {
-  const char* v = getenv(name);
-  return v ? atoi(v) : 0;
-}
 
 bool mfma_gemm_supported(int M, int N, int K, int mode) {
   if (M < 1 || M > 256) return false;
@@ -260,7 +256,7 @@ bool mfma_gemm_supported(int M, int N, int K, int mode) {
 // fragments per wavefront: 2 when the column count allows it, else 1 (mode 2 always pairs gate/up)
 static int nf_for(int N, int mode) {
   if (mode == 2) return 2;
-  const int forced = env_int("CLOVER_GEMM_NF");
+  const int forced = tune_int("CLOVER_GEMM_NF", 0);
   if (forced == 1 || forced == 2) return (N % (16 * forced) == 0) ? forced : 1;
   return (N % 32 == 0 && N >= 8192) ? 2 : 1;
 }
@@ -271,7 +267,7 @@ static int tiles_for(int N, int mode) {
 }
 
 int mfma_gemm_pick_splits(int M, int N, int K, int mode) {
-  const int forced = env_int("CLOVER_GEMM_SPLITS");
+  const int forced = tune_int("CLOVER_GEMM_SPLITS", 0);
   const int mt = mt_for(M);
   const int chunks = K / kc_for(mt);
   if (forced > 0) return std::min(forced, chunks);
@@ -301,7 +297,7 @@ void launch_gemm_mfma(const MfmaGemm& g, hipStream_t st) {
   const int mt = mt_for(g.M), nf = nf_for(g.N, g.mode);
   dim3 grid(tiles_for(g.N, g.mode), g.splits);
   MfmaGemm g2 = g;
-  g2.dbg = env_int("CLOVER_GEMM_DBG");
+  g2.dbg = tune_int("CLOVER_GEMM_DBG", 0);
 #define CLV_CASE(MT_, KC_)                                              \
   if (nf == 2) launch_one<MT_, 2, KC_>(g2, grid, st);                   \
   else launch_one<MT_, 1, KC_>(g2, grid, st);

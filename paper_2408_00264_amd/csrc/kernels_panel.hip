@@ -87,7 +87,7 @@ __global__ __launch_bounds__(PN_WAVES * 64) void gemm_panel_kernel(PanelGemm p) 
   // Workgroups start at different K stages: all weight blocks have the same power-of-two size, and
   // walking them in lock-step would keep every workgroup on the same few HBM channels.
   // (a launch of more than one workgroup per CU staggers by itself, and measured faster unrotated)
-  const int rot = ((p.dbg & 2) || gridDim.x > 256) ? 0 : wg % NS;
+  const int rot = (CLV_DBG(p, 2) || gridDim.x > 256) ? 0 : wg % NS;
   const int n_blocks = p.N / 16;                // 16-column blocks of the output
   // EPI 1: unit = one 16-column block (fragments: gate rows, up rows); EPI 0: unit = two adjacent blocks
   const int unit = wg * UW + uw;
@@ -288,9 +288,8 @@ int panel_gemm_pick_k_parts(int M, int N, int K) {
 }
 
 void launch_gemm_panel(const PanelGemm& g_in, hipStream_t st) {
-  static const int dbg = [] { const char* v = getenv("CLOVER_PANEL_DBG"); return v ? atoi(v) : 0; }();
   PanelGemm g = g_in;
-  g.dbg = dbg;
+  g.dbg = tune_int("CLOVER_PANEL_DBG", 0);
   const int n_blocks = g.N / 16;
   const bool big = g.M > 64 || g.rows128, small = g.M <= 16 && !big;
   if (g.epi == 0 && g.k_parts > 1) {

@@ -137,7 +137,7 @@ __global__ __launch_bounds__(ST_WAVES * 64) void gemm_stream_kernel(StreamGemm p
     for (int it = 0; it < XIT; ++it) {
       const int rp = it * ST_WAVES + wave, plane = rp / ROWS, r = rp % ROWS;
       v[it] = (u32x4){0u, 0u, 0u, 0u};
-      if (lane < slots && r < p.M && !(p.dbg & 1))
+      if (lane < slots && r < p.M && !CLV_DBG(p, 1))
         v[it] = *(const u32x4*)((plane ? p.Xlo : p.Xhi) + (size_t)r * p.ldx + k0 + lane * 8);
     }
 #pragma unroll
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(ST_WAVES * 64) void gemm_stream_kernel(StreamGemm p
         for (int mb = 0; mb < MT; ++mb) {
           const int m = mb * 16 + l16;
           const f32x4 v = acc[f][mb];
-          if (m < p.M && !(p.dbg & 2)) *(float4*)(ybase + (size_t)m * p.ldy + col) = make_float4(v[0], v[1], v[2], v[3]);
+          if (m < p.M && !CLV_DBG(p, 2)) *(float4*)(ybase + (size_t)m * p.ldy + col) = make_float4(v[0], v[1], v[2], v[3]);
           acc[f][mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
         }
       }
@@ -232,12 +232,11 @@ static void launch_stream_one(const StreamGemm& g, int wgs, hipStream_t st) {
 
 void launch_gemm_stream(StreamGemm g, hipStream_t st) {
   g.n_slices = stream_gemm_slices(g.K);
-  static const int dbg = [] { const char* v = getenv("CLOVER_STREAM_DBG"); return v ? atoi(v) : 0; }();
-  g.dbg = dbg;
+  g.dbg = tune_int("CLOVER_STREAM_DBG", 0);
   const int mt = g.M <= 16 ? 1 : 4;  // 17..32 rows run as 64 (zero rows cost MFMA time only, the kernel is HBM-bound)
   // one workgroup per CU: a 64-row slice fills most of the LDS.  Pair fragments (halves the LDS
   // reads per weight byte) when that still leaves every wavefront a unit.
-  static const int target = [] { const char* v = getenv("CLOVER_STREAM_WGS"); return v ? atoi(v) : 256; }();
+  const int target = tune_int("CLOVER_STREAM_WGS", 256);
   int groups = std::max(1, target / g.n_slices);
   int nf = 2;
   if (g.N / 32 < groups * ST_WAVES) nf = 1;

@@ -104,3 +104,13 @@ def test_null_context_calls(lib):
     assert lib.clover_kernel_class_count() >= 10
     assert lib.clover_kernel_class_name(0) == b"embed"
     assert lib.clover_op_gemm(0, 0, None, None, None, 4, 1, 4, 4, None, 0, None) == clover.E_NULL
+
+
+def test_shipped_library_reads_no_environment_switch(lib):
+    """The library's behaviour must not depend on the environment: the shipped build neither imports getenv nor
+    carries the name of a CLOVER_* switch (those exist only in -DCLOVER_ABLATE tuning builds)."""
+    import subprocess
+    blob = open(clover.LIB_PATH, "rb").read()
+    assert b"CLOVER_" not in blob
+    syms = subprocess.run(["nm", "-D", clover.LIB_PATH], capture_output=True, text=True).stdout
+    assert "getenv" not in syms
