@@ -11,7 +11,9 @@
  *  - Arguments are validated on the host before anything is launched.
  *  - "dev" pointers are device (HBM) addresses, "host" pointers are ordinary host memory.
  *  - The library allocates no device memory: KV caches, lengths and all scratch live in the
- *    caller's workspace; weights are borrowed for the lifetime of the context.
+ *    caller's workspace; weights are borrowed for the lifetime of the context.  For bf16 models the
+ *    workspace also holds the library's own copy of every linear weight in MFMA-fragment order
+ *    (+1x the weight bytes); the originals are then read only by the embedding gathers.
  *  - Calls enqueue work on the stream given at init and return without synchronising, unless
  *    stated otherwise.  A HIP error found while launching is returned as CLOVER_E_HIP.
  *  - Model tensors (weights, norm gains, biases) are in the model dtype (fp32 or bf16 bit
@@ -53,7 +55,9 @@ enum {
 typedef struct {
   int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
   float rope_base, rms_eps;
-  int32_t dtype;         /* CLOVER_DTYPE_*: type of every model tensor and of the KV caches */
+  int32_t dtype;         /* CLOVER_DTYPE_*: type of every model tensor.  KV caches: fp32 elements for fp32 models;
+                            for bf16 models each cached value is a pair of bf16 numbers (hi + lo, 16 mantissa bits,
+                            4 bytes): twice the bytes of a plain bf16 cache, the price of the 3e-2 logit bound */
   int32_t aug_layers;    /* decoder layers in the Augmenting Block (Sec. 3.3) */
   int32_t ad_heads;      /* heads of the Attention Decoder's cosine gate (Appendix A.3) */
   int32_t draft_depths;  /* D: deepest tree level the draft head can fill (FC_0 .. FC_{D-1}) */
@@ -180,6 +184,22 @@ int clover_seq_len(clover_ctx *ctx, int32_t *out_host);
  * to host as fp32 [n_slots, n_kv, d].  stack 0 = target, 1 = augmenting block. */
 int clover_read_kv(clover_ctx *ctx, int32_t stack, int32_t layer, int32_t b, int32_t slot0, int32_t n_slots,
                    float *k_out_host, float *v_out_host);
+
+/* Test helper (synchronises): the mirror of clover_read_kv.  Writes n_slots cache rows of one layer and sequence
+ * from host fp32 [n_slots, n_kv, d] (stored in the cache's own format).  Lengths are not changed. */
+int clover_write_kv(clover_ctx *ctx, int32_t stack, int32_t layer, int32_t b, int32_t slot0, int32_t n_slots,
+                    const float *k_in_host, const float *v_in_host);
+
+/* Test helper (synchronises): declare the first len_host[b] slots of the target cache and the first
+ * aug_len_host[b] slots of the augmenting block's cache of every sequence valid (after a prompt of L tokens the
+ * target holds L rows and the block L - 1: its last row arrives with the next draft_tree).  HOST int32 [max_batch]. */
+int clover_set_seq_len(clover_ctx *ctx, const int32_t *len_host, const int32_t *aug_len_host);
+
+/* Test helper: while dev_out is non-null every draft_tree also copies the draft logits it ranks (Sec. 3.2: the
+ * shared LM head after FC_j) to dev_out, fp32: the rows of depth j start at batch * (number of internal nodes
+ * shallower than j) * V, row (b, r) of that depth at ((b * n_j) + r) * V, r-th internal node of the depth in
+ * index order.  Depths that would not fit capacity_floats are skipped.  null switches it off. */
+int clover_capture_draft_logits(clover_ctx *ctx, float *dev_out, size_t capacity_floats);
 
 /* Per-kernel-class timing with HIP events on the library's stream.  While enabled, every launch
  * is bracketed by two events.  collect synchronises, adds up the

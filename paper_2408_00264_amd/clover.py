@@ -22,7 +22,7 @@ FLAG_GENERIC = 1
 EXPORTS = [
     "clover_workspace_bytes", "clover_init", "clover_destroy", "clover_reset", "clover_set_tree",
     "draft_tree", "verify_tree", "accept_and_compact", "clover_accept_forced", "clover_seq_len",
-    "clover_read_kv", "clover_path_info", "clover_profile_enable", "clover_profile_collect", "clover_kernel_class_count",
+    "clover_read_kv", "clover_write_kv", "clover_set_seq_len", "clover_capture_draft_logits", "clover_path_info", "clover_profile_enable", "clover_profile_collect", "clover_kernel_class_count",
     "clover_kernel_class_name", "clover_last_error", "clover_last_global_error",
     "clover_op_gemm_scratch_bytes", "clover_op_gemm",
 ]
@@ -80,6 +80,9 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.clover_accept_forced.argtypes = [vp, i32, i32p, f32p, f32p, i32p, i32p, i32p, i32p, i32p, f32p, i32p]
     lib.clover_seq_len.argtypes = [vp, C.POINTER(C.c_int32)]
     lib.clover_read_kv.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp]
+    lib.clover_write_kv.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp]
+    lib.clover_set_seq_len.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+    lib.clover_capture_draft_logits.argtypes = [vp, vp, C.c_size_t]
     lib.clover_path_info.argtypes = [vp]
     lib.clover_profile_enable.argtypes = [vp, i32]
     lib.clover_profile_collect.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), i32]
@@ -244,6 +247,32 @@ class Clover:
             self._check(self.lib.clover_read_kv(self.ctx, stack, layer, b, slot0 + s0, n,
                                                 k[s0:].ctypes.data, v[s0:].ctypes.data))
         return k, v
+
+    def write_kv(self, stack: int, layer: int, b: int, slot0: int, k: np.ndarray, v: np.ndarray) -> None:
+        k = np.ascontiguousarray(k, dtype=np.float32)
+        v = np.ascontiguousarray(v, dtype=np.float32)
+        nkv, d = self.shape.n_kv_heads, self.shape.head_dim
+        n_slots = k.shape[0]
+        per_call = max(1, (self.B * self.R * self.V // 2) // (nkv * d))   # staging area of the library
+        for s0 in range(0, n_slots, per_call):
+            n = min(per_call, n_slots - s0)
+            self._check(self.lib.clover_write_kv(self.ctx, stack, layer, b, slot0 + s0, n,
+                                                 k[s0:].ctypes.data, v[s0:].ctypes.data))
+
+    def set_seq_len(self, lens, aug_lens) -> None:
+        a = (C.c_int32 * self.B)(*[int(v) for v in lens])
+        b = (C.c_int32 * self.B)(*[int(v) for v in aug_lens])
+        self._check(self.lib.clover_set_seq_len(self.ctx, a, b))
+
+    def capture_draft_logits(self, on: bool = True):
+        """Device buffer [batch * internal nodes, V] that every later draft_tree fills (None: off)."""
+        if not on:
+            self._check(self.lib.clover_capture_draft_logits(self.ctx, None, 0))
+            self.draft_logits = None
+            return None
+        self.draft_logits = self.torch.zeros(self.B * self.R, self.V, dtype=self.torch.float32, device=self.dev)
+        self._check(self.lib.clover_capture_draft_logits(self.ctx, self._p(self.draft_logits), self.draft_logits.numel()))
+        return self.draft_logits
 
     def path_info(self) -> int:
         """Bit 0: MFMA path, bit 1: MFMA tree attention."""

@@ -92,6 +92,8 @@ struct clover_ctx {
   bool panel;              // full-K panel GEMM for the gate+up projection and the LM head
   int row_batch_max = 64;
   int row_batch = 64;      // rows per weight pass for passes of more than 64 rows: 128 when the panel kernel may take them  // passes of up to this many rows run through the <= 64-row GEMM kernels, in batches of 64
+  float* draft_capture = nullptr;   // test hook: device buffer that receives every depth's draft logits
+  size_t draft_capture_floats = 0;
   // host-side bounds
   std::vector<int> len_ub, aug_ub;
   int m_upper;
@@ -660,6 +662,15 @@ void run_ad_fused(clover_ctx* x, const clover_ad_weights& ad, Planes A, Planes Y
   launch_ad_gate_fused(g, rows, x->st);
 }
 
+// test hook: copy the logits of the depth-j internal nodes (rows x vocab in x->z) behind those of the shallower depths
+void capture_draft_logits(clover_ctx* x, int j, int rows) {
+  if (!x->draft_capture) return;
+  const size_t V = (size_t)x->cfg.vocab;
+  const size_t off = (size_t)(rows / std::max(1, x->tree.lvl_off[j + 1] - x->tree.lvl_off[j])) * x->tree.lvl_off[j] * V;
+  if (off + (size_t)rows * V > x->draft_capture_floats) return;
+  hipMemcpyAsync(x->draft_capture + off, x->z, (size_t)rows * V * sizeof(float), hipMemcpyDeviceToDevice, x->st);
+}
+
 int upload_tree(clover_ctx* x) {
   const TreeHost& t = x->tree;
   const int n = t.n;
@@ -930,10 +941,15 @@ int draft_tree(clover_ctx* x, int32_t batch, const float* hid_acc, const int32_t
                                  A.lo, H, rows, H, x->st, j == 0 ? x->w.fc0_b : x->fc_b[j]); }
         if (x->panel && panel_gemm_supported(std::min(rows, 64), c.vocab, H, 0)) {
           lm_head_fast(x, A, rows, x->z);
+          capture_draft_logits(x, j, rows);
           Scope s(x, KC_TOPK);
           launch_topk(x->z, c.vocab, c.vocab, rows, t.kmax[j], x->cand, x->topk_ids, x->st);
         } else {
           const int spv = gemm_fast1(x, KC_GEMM_LMHEAD, A, x->lm_head_pk, rows, c.vocab, H);
+          if (x->draft_capture) {
+            launch_reduce(x->partial, spv, (size_t)rows * c.vocab, c.vocab, nullptr, c.dtype, x->z, c.vocab, rows, c.vocab, 0, x->st);
+            capture_draft_logits(x, j, rows);
+          }
           Scope s(x, KC_TOPK);
           launch_topk(x->partial, c.vocab, c.vocab, rows, t.kmax[j], x->cand, x->topk_ids, x->st, spv, (size_t)rows * c.vocab);
         }
@@ -955,6 +971,7 @@ int draft_tree(clover_ctx* x, int32_t batch, const float* hid_acc, const int32_t
         run_fc(x, x->d_cat, 2 * H, x->fc_w[j], x->fc_b[j], x->d_g, rows);
       }
       run_head(x, x->d_g, rows, t.kmax[j]);
+      capture_draft_logits(x, j, rows);
       { Scope s(x, KC_DRAFT_MISC);
         launch_draft_assign(x->topk_ids, x->d_par_row, x->d_rank, t.node_off[j + 1], t.node_off[j + 2], n_lvl, B, R, m,
                             tree_tokens, x->st); }
@@ -1057,6 +1074,50 @@ int clover_read_kv(clover_ctx* x, int32_t stack, int32_t layer, int32_t b, int32
   if (e == hipSuccess) e = hipMemcpyAsync(v_out_host, x->z + n, n * sizeof(float), hipMemcpyDeviceToHost, x->st);
   if (e == hipSuccess) e = hipStreamSynchronize(x->st);
   if (e != hipSuccess) return fail(x, CLOVER_E_HIP, std::string("clover_read_kv: ") + hipGetErrorString(e));
+  return CLOVER_OK;
+}
+
+int clover_write_kv(clover_ctx* x, int32_t stack, int32_t layer, int32_t b, int32_t slot0, int32_t n_slots,
+                    const float* k_in_host, const float* v_in_host) {
+  if (!x || !k_in_host || !v_in_host) return fail(x, CLOVER_E_NULL, "null argument");
+  const clover_config& c = x->cfg;
+  const int nl = stack == 0 ? c.n_layers : c.aug_layers;
+  if (stack < 0 || stack > 1 || layer < 0 || layer >= nl || b < 0 || b >= c.max_batch || slot0 < 0 || n_slots < 0 ||
+      slot0 + n_slots > c.max_seq)
+    return fail(x, CLOVER_E_SHAPE, "clover_write_kv: index out of range");
+  const size_t n = (size_t)n_slots * c.n_kv_heads * c.head_dim;
+  if (2 * n > (size_t)x->max_rows * c.vocab) return fail(x, CLOVER_E_SHAPE, "clover_write_kv: too many slots at once");
+  if (n == 0) return CLOVER_OK;
+  char* kbase = (stack == 0 ? x->kc : x->aug_kc) + (size_t)layer * x->k_layer_elems * x->kv_esz;
+  char* vbase = (stack == 0 ? x->vc : x->aug_vc) + (size_t)layer * x->v_layer_elems * x->kv_esz;
+  hipError_t e = hipMemcpyAsync(x->z, k_in_host, n * sizeof(float), hipMemcpyHostToDevice, x->st);
+  if (e == hipSuccess) e = hipMemcpyAsync(x->z + n, v_in_host, n * sizeof(float), hipMemcpyHostToDevice, x->st);
+  if (e == hipSuccess) {
+    launch_write_kv(kbase, vbase, x->kvdtype, x->kv, b, slot0, n_slots, x->z, x->z + n, x->st);
+    e = hipStreamSynchronize(x->st);   // the host arrays and the staging area are free again on return
+  }
+  if (e != hipSuccess) return fail(x, CLOVER_E_HIP, std::string("clover_write_kv: ") + hipGetErrorString(e));
+  return CLOVER_OK;
+}
+
+int clover_set_seq_len(clover_ctx* x, const int32_t* len_host, const int32_t* aug_len_host) {
+  if (!x || !len_host || !aug_len_host) return fail(x, CLOVER_E_NULL, "null argument");
+  const int B = x->cfg.max_batch;
+  for (int b = 0; b < B; ++b)
+    if (len_host[b] < 0 || len_host[b] > x->cfg.max_seq || aug_len_host[b] < 0 || aug_len_host[b] > x->cfg.max_seq)
+      return fail(x, CLOVER_E_CAPACITY, "clover_set_seq_len: length outside [0, max_seq]");
+  hipError_t e = hipMemcpyAsync(x->d_seq_len, len_host, B * sizeof(int), hipMemcpyHostToDevice, x->st);
+  if (e == hipSuccess) e = hipMemcpyAsync(x->d_aug_len, aug_len_host, B * sizeof(int), hipMemcpyHostToDevice, x->st);
+  if (e == hipSuccess) e = hipStreamSynchronize(x->st);
+  if (e != hipSuccess) return fail(x, CLOVER_E_HIP, std::string("clover_set_seq_len: ") + hipGetErrorString(e));
+  for (int b = 0; b < B; ++b) { x->len_ub[b] = len_host[b]; x->aug_ub[b] = aug_len_host[b]; }
+  return CLOVER_OK;
+}
+
+int clover_capture_draft_logits(clover_ctx* x, float* dev_out, size_t capacity_floats) {
+  if (!x) return CLOVER_E_NULL;
+  x->draft_capture = dev_out;
+  x->draft_capture_floats = dev_out ? capacity_floats : 0;
   return CLOVER_OK;
 }
 

@@ -86,6 +86,8 @@ void launch_gather_hidden(const float* hidden, const int* acc_idx, const int* m,
                           hipStream_t st);
 void launch_read_kv(const void* k_cache, const void* v_cache, int kvdtype, KVLayout kv, int b, int slot0, int n_slots,
                     float* k_out, float* v_out, hipStream_t st);
+void launch_write_kv(void* k_cache, void* v_cache, int kvdtype, KVLayout kv, int b, int slot0, int n_slots,
+                     const float* k_in, const float* v_in, hipStream_t st);
 void launch_fill_i32(int* p, int v, int n, hipStream_t st);
 
 // ---- split-bf16 activation planes and partial-sum consumers ------------------------------------

@@ -835,6 +835,28 @@ void launch_read_kv(const void* k_cache, const void* v_cache, int kvdtype, KVLay
                                                    n_slots, k_out, v_out);
 }
 
+template <typename KT>
+__global__ void write_kv_kernel(KT* __restrict__ kc, KT* __restrict__ vc, KVLayout kv, int b, int slot0, int n_slots,
+                                const float* __restrict__ k_in, const float* __restrict__ v_in) {
+  const int width = kv.n_kv * kv.d;
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (size_t)n_slots * width) return;
+  const int s = (int)(idx / width), col = (int)(idx % width);
+  stkv(kc, ((size_t)b * kv.max_seq + slot0 + s) * width + col, kv.plane, k_in[idx]);
+  stkv(vc, ((size_t)b * width + col) * kv.max_seq + slot0 + s, kv.plane, v_in[idx]);
+}
+void launch_write_kv(void* k_cache, void* v_cache, int kvdtype, KVLayout kv, int b, int slot0, int n_slots,
+                     const float* k_in, const float* v_in, hipStream_t st) {
+  const size_t n = (size_t)n_slots * kv.n_kv * kv.d;
+  if (n == 0) return;
+  const unsigned blocks = (unsigned)((n + 255) / 256);
+  if (kvdtype == 0)
+    write_kv_kernel<float><<<blocks, 256, 0, st>>>((float*)k_cache, (float*)v_cache, kv, b, slot0, n_slots, k_in, v_in);
+  else
+    write_kv_kernel<bf16_t><<<blocks, 256, 0, st>>>((bf16_t*)k_cache, (bf16_t*)v_cache, kv, b, slot0, n_slots, k_in,
+                                                    v_in);
+}
+
 // ------------------------------------------------------------------------------------------
 // split-bf16 planes and partial-sum consumers
 // ------------------------------------------------------------------------------------------

@@ -57,6 +57,14 @@ class Lockstep:
         self.tie_events = 0
         self.max_logit_err = 0.0
         self.max_hidden_err = 0.0
+        self.max_draft_logit_err = 0.0
+        self.max_kv_err = 0.0
+        # tolerances: logits as the target states them; K/V rows and hidden states are not bounded by it, the
+        # bounds below are what 16 mantissa bits through the stack give with a wide margin (a lost low plane
+        # of the split-bf16 cache alone is ~2^-9 |x| ~ 1e-2 and fails them)
+        self.kv_atol = 2e-3 if shape.bf16 else 1e-4
+        self.hidden_atol = 1e-2 if shape.bf16 else 1e-4
+        self.gpu.capture_draft_logits(True)
 
     # ------------------------------------------------------------------------------------
     def _check_draft(self, b: int, gpu_tokens: np.ndarray, parent, rank) -> None:
@@ -66,6 +74,24 @@ class Lockstep:
                                 forced_tokens=gpu_tokens)
         assert int(gpu_tokens[0]) == int(acc["next_tok"][-1]), "root token"
         kids = O.children_of(parent)
+        # every draft logit the GPU ranked, element by element (internal nodes in index order are grouped by depth)
+        cap = self.gpu.draft_logits
+        if cap is not None and zs:
+            depth = O.tree_depths(parent)
+            internal = sorted(zs)
+            by_depth: Dict[int, List[int]] = {}
+            for u in internal:
+                by_depth.setdefault(int(depth[u]), []).append(u)
+            start = 0
+            for j in sorted(by_depth):
+                nodes = by_depth[j]
+                base = self.B * start + b * len(nodes)
+                got = cap[base:base + len(nodes)].cpu().numpy()
+                for r, u in enumerate(nodes):
+                    err = float(np.abs(got[r] - zs[u]).max())
+                    self.max_draft_logit_err = max(self.max_draft_logit_err, err)
+                    assert err <= self.tol, f"seq {b} node {u} (depth {j}): draft logits max-abs error {err:.3e}"
+                start += len(nodes)
         for u, z in zs.items():
             need = 1 + max(rank[c] for c in kids[u])
             top = O.ranked_ids(z, need)
@@ -116,9 +142,55 @@ class Lockstep:
             assert seq.aug_L == seq.L
             self.compare_kv(b, 0, seq.L)
 
+    def seed_cache(self, lengths: List[int], seed: int) -> None:
+        """Instead of a prefill: the state right after a prompt of lengths[b] tokens, with seeded random cache rows
+        (N(0, 0.6) keys and values, each a sum of two bf16 numbers so that both sides hold identical values): L rows
+        in the target cache, L - 1 in the augmenting block's, and one seeded (hidden state, next token) hand-off
+        row per sequence, on which the draft head then runs on both sides."""
+        g, torch = self.gpu, self.gpu.torch
+        nkv, d = self.shape.n_kv_heads, self.shape.head_dim
+
+        def two_bf16(a: np.ndarray) -> np.ndarray:
+            hi = synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(a))
+            lo = synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(a - hi))
+            return hi + lo
+
+        hid = np.zeros((self.B, self.R, self.shape.hidden), np.float32)
+        nxt = np.zeros((self.B, self.R), np.int32)
+        for b, L in enumerate(lengths):
+            rng = np.random.default_rng([seed, b])
+            seq = self.seqs[b]
+            for stack, n_layers, kv in ((0, self.shape.n_layers, seq.kv), (1, self.shape.aug_layers, seq.aug_kv)):
+                rows = L - stack
+                for l in range(n_layers):
+                    k = two_bf16((rng.standard_normal((rows, nkv, d), dtype=np.float32) * 0.6).astype(np.float32))
+                    v = two_bf16((rng.standard_normal((rows, nkv, d), dtype=np.float32) * 0.6).astype(np.float32))
+                    kv.k[l, :rows] = k
+                    kv.v[l, :rows] = v
+                    g.write_kv(stack, l, b, 0, k, v)
+            seq.L, seq.aug_L = L, L - 1
+            hid[b, 0] = rng.standard_normal(self.shape.hidden, dtype=np.float32)
+            nxt[b, 0] = int(rng.integers(0, self.shape.vocab))
+            self.acc[b] = dict(m=1, path=[0], new_tokens=[int(nxt[b, 0])], hid_acc=hid[b, :1].astype(np.float64),
+                               next_tok=[int(nxt[b, 0])])
+        full = list(lengths) + [0] * (self.B - len(lengths))
+        g.set_seq_len(full, [max(v - 1, 0) for v in full])
+        g.hid_acc.copy_(torch.from_numpy(hid))
+        g.next_tok.copy_(torch.from_numpy(nxt))
+        g.m.copy_(torch.from_numpy(np.ones(self.B, np.int32)))
+        g.draft_tree(len(lengths))
+        torch.cuda.synchronize()
+        toks = g.tree_tokens.cpu().numpy()
+        lens = g.seq_len()
+        for b, L in enumerate(lengths):
+            assert lens[b] == L
+            self._check_draft(b, toks[b, :len(self.parent)], self.parent, self.rank)
+            assert self.seqs[b].aug_L == L
+            self.compare_kv(b, L - 1, L, stacks=(1,))
+
     def compare_kv(self, b: int, slot0: int, slot1: int, atol: Optional[float] = None, stacks=(0, 1)) -> None:
         """Target and augmenting-block cache rows [slot0, slot1) against the oracle's."""
-        atol = atol if atol is not None else (4e-2 if self.shape.bf16 else 1e-4)
+        atol = atol if atol is not None else self.kv_atol
         if slot1 <= slot0:
             return
         seq = self.seqs[b]
@@ -129,6 +201,7 @@ class Lockstep:
                 k, v = self.gpu.read_kv(stack, l, b, slot0, slot1 - slot0)
                 ek = np.abs(k - kv.k[l, slot0:slot1]).max()
                 ev = np.abs(v - kv.v[l, slot0:slot1]).max()
+                self.max_kv_err = max(self.max_kv_err, float(ek), float(ev))
                 assert ek <= atol and ev <= atol, f"KV stack {stack} layer {l} seq {b}: |dK| {ek:.3e} |dV| {ev:.3e}"
 
     def step(self, tree_hook: Optional[Callable[[int, np.ndarray], np.ndarray]] = None,
@@ -163,11 +236,13 @@ class Lockstep:
             self.max_logit_err = max(self.max_logit_err, le)
             self.max_hidden_err = max(self.max_hidden_err, he)
             assert le <= self.tol, f"seq {b}: logits max-abs error {le:.3e} > {self.tol}"
+            assert he <= self.hidden_atol, f"seq {b}: hidden-state max-abs error {he:.3e} > {self.hidden_atol}"
             # uncompacted tree rows of the cache (read back before the GPU compacted them)
-            atol = 4e-2 if self.shape.bf16 else 1e-4
+            atol = self.kv_atol
             for l in range(self.shape.n_layers):
                 ek = np.abs(pre_kv[b][l][0] - seq.kv.k[l, seq.L:seq.L + N]).max()
                 ev = np.abs(pre_kv[b][l][1] - seq.kv.v[l, seq.L:seq.L + N]).max()
+                self.max_kv_err = max(self.max_kv_err, float(ek), float(ev))
                 assert ek <= atol and ev <= atol, f"tree KV rows layer {l} seq {b}: |dK| {ek:.3e} |dV| {ev:.3e}"
             # acceptance: the GPU's implied argmax at each visited node must be (near-)optimal for the oracle
             mb = int(m[b])

@@ -252,6 +252,73 @@ def test_long_context_96_node_tree():
 
 
 # ------------------------------------------------------------------------------------------
+# acceptance and compaction on crafted logits: overlapping moves, a sibling search, a late child
+# ------------------------------------------------------------------------------------------
+CRAFTED = [
+    # parent array, accepted path it must produce
+    ([-1, 0, 1, 2], [0, 1, 2, 3]),                  # chain accepted whole: every move is the identity, m = D + 1
+    ([-1, 0, 0, 1, 1, 2, 2], [0, 2, 5]),            # slot L+1 <- L+2, slot L+2 <- L+5: a destination is an earlier source
+    ([-1, 0, 0, 0, 0, 1], [0, 4]),                  # the last of four siblings
+    ([-1, 0, 0, 1, 2, 2, 4, 5, 5], [0, 2, 5, 8]),   # moves 2->1, 5->2, 8->3
+]
+
+
+@pytest.mark.parametrize("bf16", [False, True], ids=["fp32", "bf16"])
+@pytest.mark.parametrize("case", range(len(CRAFTED)))
+def test_accept_and_compact_crafted_paths(bf16, case):
+    torch = _torch()
+    O = __import__("oracle.clover2_oracle", fromlist=["x"])
+    shape = MINI if bf16 else TINY
+    parent, want_path = CRAFTED[case]
+    parent = np.asarray(parent, np.int32)
+    n = len(parent)
+    kids = O.children_of(parent)
+    rank = np.zeros(n, np.int32)
+    for u in range(n):
+        for i, c in enumerate(kids[u]):
+            rank[c] = i
+    say(f"crafted accept: parent {parent.tolist()} path {want_path} bf16={bf16}")
+    ls = _lockstep(shape, gain_jitter=0.1, tree=(parent, rank), max_seq=128, max_nodes=16)
+    g = ls.gpu
+    ls.prefill([synth.make_prompts(shape, seed=40 + case)[0][:23]], chunk=8)
+    L = int(g.seq_len()[0])
+    tokens = np.zeros((1, g.R), np.int32)
+    tokens[0, :n] = 100 + 7 * np.arange(n)                      # distinct ids
+    tokens[0, 0] = int(g.tree_tokens[0, 0].item())              # the root stays the hand-off token
+    g.tree_tokens.copy_(torch.from_numpy(tokens))
+    g.verify_tree(1)
+    torch.cuda.synchronize()
+    seq = ls.seqs[0]
+    o_hidden, o_logits = O.verify_tree(ls.W, ls.ocfg, seq, tokens[0, :n], parent)     # fills the oracle's tree rows
+    pre = [g.read_kv(0, l, 0, L, n) for l in range(shape.n_layers)]
+    hidden = g.hidden.cpu().numpy()
+    # one-hot logits that walk exactly want_path and then emit `bonus`
+    bonus = 77
+    logits = np.zeros((n, shape.vocab), np.float32)
+    logits[:, 3] = 1.0                                          # off-path nodes point at a token nobody carries
+    for i, u in enumerate(want_path):
+        logits[u, 3] = 0.0
+        logits[u, tokens[0, want_path[i + 1]] if i + 1 < len(want_path) else bonus] = 5.0
+    g.logits[0, :n].copy_(torch.from_numpy(logits))
+    g.accept_and_compact(1)
+    torch.cuda.synchronize()
+    m = int(g.m[0].item())
+    acc = O.accept_and_compact(ls.ocfg, seq, tokens[0, :n], logits.astype(np.float64), o_hidden, parent)
+    assert acc["path"] == want_path                             # the crafted case means what it says
+    assert m == len(want_path)
+    assert g.acc_idx[0, :m].cpu().tolist() == want_path
+    assert g.new_tokens[0, :m].cpu().tolist() == acc["new_tokens"] == [int(tokens[0, u]) for u in want_path[1:]] + [bonus]
+    assert g.next_tok[0, :m].cpu().tolist() == acc["next_tok"]
+    assert int(g.seq_len()[0]) == L + m == seq.L
+    np.testing.assert_array_equal(g.hid_acc[0, :m].cpu().numpy(), hidden[0, want_path])
+    for l in range(shape.n_layers):
+        k2, v2 = g.read_kv(0, l, 0, L, m)
+        np.testing.assert_array_equal(k2, pre[l][0][want_path])  # the moves carry bits, in an order that keeps sources intact
+        np.testing.assert_array_equal(v2, pre[l][1][want_path])
+    ls.compare_kv(0, L, L + m, stacks=(0,))                      # and the compacted rows are the oracle's
+
+
+# ------------------------------------------------------------------------------------------
 # error paths reachable without touching the kernels
 # ------------------------------------------------------------------------------------------
 def test_capacity_and_shape_errors():
@@ -352,4 +419,59 @@ def test_full_width_two_layers(cfg, batch):
     for s in range(2):
         ms = ls.step()
         say(f"  step {s}: m={ms} max|dlogit|={ls.max_logit_err:.3e} ties={ls.tie_events}")
+    assert ls.max_logit_err <= 3e-2
+
+
+# ------------------------------------------------------------------------------------------
+# the long-context and the ragged batch-8 workloads at their real widths AND their real cache lengths
+# ------------------------------------------------------------------------------------------
+def _seeded(cfg, lengths, seed, max_seq, n_layers=2):
+    O = __import__("oracle.clover2_oracle", fromlist=["x"])
+    base = synth.CONFIGS[cfg]
+    shape = synth.scaled(base, name=f"wide-{cfg}-seeded", n_layers=n_layers, batch=len(lengths), seed=seed)
+    ls = _lockstep(shape, batch=len(lengths), max_seq=max_seq)
+    assert ls.gpu.path_info() & 3 == 3
+    ls.ocfg.dtype = np.float32
+    ls.W = O.Weights(ls.store.get_f32, np.float32)
+    ls.seqs = [O.SeqState(ls.ocfg) for _ in lengths]
+    ls.seed_cache(lengths, seed)
+    return ls
+
+
+def test_config5_8192_cached_keys_96_node_tree():
+    """The long-context workload at its real size except for the layer count: H 4096, 32/8 heads, vocab 128256,
+    8192 cached keys (seeded rows written straight into both caches), 96-node tree of depth 5: the attention runs
+    its full split arithmetic (several hundred key tiles over the key splits, three node groups), every logit,
+    tree K/V row and draft logit is compared with the oracle, and two steps accept 4 and 2 nodes."""
+    _torch()
+    from tests.parity import truth_hook_factory
+    say("config 5 widths, 2 layers, 8192 seeded cache rows")
+    ls = _seeded(5, [8192], seed=51, max_seq=8192 + 4 * 96)
+    want = [4, 2]
+    hook = truth_hook_factory(ls, want)
+    for s in range(len(want)):
+        ties = ls.tie_events
+        ms = ls.step(tree_hook=hook)
+        say(f"  step {s}: want {want[s]} got {ms} max|dlogit|={ls.max_logit_err:.3e} max|dhidden|={ls.max_hidden_err:.3e} "
+            f"max|dKV|={ls.max_kv_err:.3e} max|ddraft|={ls.max_draft_logit_err:.3e} ties={ls.tie_events}")
+        if ls.tie_events == ties:
+            assert ms == [want[s]]
+    assert ls.max_logit_err <= 3e-2
+
+
+def test_config4_ragged_256_to_2048_cached_keys():
+    """The batch-8 workload at its real widths and cache lengths (the recipe's eight lengths, uniform in
+    [256, 2048]), 32-node trees, 256 rows per pass, 2 layers."""
+    _torch()
+    from tests.parity import truth_hook_factory
+    lengths = [len(p) for p in synth.make_prompts(synth.CONFIGS[4])]
+    assert len(lengths) == 8 and min(lengths) >= 256 and max(lengths) <= 2048
+    say(f"config 4 widths, 2 layers, seeded cache rows, lengths {lengths}")
+    ls = _seeded(4, lengths, seed=41, max_seq=2048 + 4 * 32)
+    want = [3, 1]
+    hook = truth_hook_factory(ls, want)
+    for s in range(len(want)):
+        ms = ls.step(tree_hook=hook)
+        say(f"  step {s}: want {want[s]} got {ms} max|dlogit|={ls.max_logit_err:.3e} max|dhidden|={ls.max_hidden_err:.3e} "
+            f"max|dKV|={ls.max_kv_err:.3e} max|ddraft|={ls.max_draft_logit_err:.3e} ties={ls.tie_events}")
     assert ls.max_logit_err <= 3e-2
