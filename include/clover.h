@@ -233,6 +233,17 @@ size_t clover_op_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K);
 int clover_op_gemm(int32_t path, int32_t dtype, const float *X, const void *W, float *Y, int32_t ldy,
                    int32_t M, int32_t N, int32_t K, void *scratch, size_t scratch_bytes, void *hip_stream);
 
+/* clover_op_gemm for callers that cannot allocate device memory (code under HIP-graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the scratch is a fixed device array inside the library, one per GPU,
+ * CLOVER_STATIC_SCRATCH_BYTES long, held until the process ends.  Same arguments and results as clover_op_gemm
+ * for path 0, 1, 3 or 5 (the weight copy is always made: the array keeps only the LAST call's contents).
+ * CLOVER_E_CAPACITY when clover_op_gemm_scratch_bytes(M, N, K) exceeds the array; CLOVER_E_SHAPE for the
+ * copy-reusing paths.  Allocates nothing.  All calls on one GPU share the array: calls that overlap on one
+ * GPU (different streams or threads) race. */
+#define CLOVER_STATIC_SCRATCH_BYTES (32u << 20)
+int clover_op_gemm_static(int32_t path, int32_t dtype, const float *X, const void *W, float *Y, int32_t ldy,
+                          int32_t M, int32_t N, int32_t K, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -18,13 +18,14 @@ LIB_PATH = os.path.join(_HERE, "libclover.so")
 OK, E_NULL, E_CONFIG, E_TREE, E_CAPACITY, E_SHAPE, E_HIP, E_STATE = 0, -1, -2, -3, -4, -5, -6, -7
 DTYPE_F32, DTYPE_BF16 = 0, 1
 FLAG_GENERIC = 1
+STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = [
     "clover_workspace_bytes", "clover_init", "clover_destroy", "clover_reset", "clover_set_tree",
     "draft_tree", "verify_tree", "accept_and_compact", "clover_accept_forced", "clover_seq_len",
     "clover_read_kv", "clover_write_kv", "clover_set_seq_len", "clover_capture_draft_logits", "clover_path_info", "clover_profile_enable", "clover_profile_collect", "clover_kernel_class_count",
     "clover_kernel_class_name", "clover_last_error", "clover_last_global_error",
-    "clover_op_gemm_scratch_bytes", "clover_op_gemm",
+    "clover_op_gemm_scratch_bytes", "clover_op_gemm", "clover_op_gemm_static",
 ]
 
 
@@ -96,6 +97,7 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.clover_op_gemm_scratch_bytes.argtypes = [i32, i32, i32]
     lib.clover_op_gemm_scratch_bytes.restype = C.c_size_t
     lib.clover_op_gemm.argtypes = [i32, i32, vp, vp, vp, i32, i32, i32, i32, vp, C.c_size_t, vp]
+    lib.clover_op_gemm_static.argtypes = [i32, i32, vp, vp, vp, i32, i32, i32, i32, vp]
     for n in EXPORTS:
         getattr(lib, n)  # every declared symbol must be exported
     if _lib is None:

@@ -30,6 +30,16 @@ namespace {
 
 thread_local std::string g_err;
 
+int op_gemm_impl(int32_t path, int32_t dtype, const float* X, const void* W, float* Y, int32_t ldy, int32_t M,
+                 int32_t N, int32_t K, void* scratch, size_t scratch_bytes, void* hip_stream);
+
+// Scratch of clover_op_gemm_static: one copy per GPU, held until the process ends.  In host code the name below is
+// only a handle for hipGetSymbolAddress; every use goes through the per-device address looked up once.
+__device__ __align__(256) unsigned char g_static_scratch[CLOVER_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+void* g_static_scratch_ptr[kMaxDevices] = {};
+int static_scratch_ptr(void** out);
+
 const char* kClassNames[KC_COUNT] = {"embed",     "rmsnorm",     "gemm_qkv",   "rope_kv_write", "tree_attention", "gemm_wo",
                                      "gemm_gate_up", "gemm_down", "gemm_lm_head", "gemm_draft",  "ad_gate",        "topk",
                                      "draft_misc", "accept_walk", "compact_kv", "eltwise"};
@@ -720,6 +730,24 @@ int accept_common(clover_ctx* x, int batch, const int* tree_tokens, const float*
   return finish(x, "accept");
 }
 
+int static_scratch_ptr(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) { g_err = std::string("hipGetDevice: ") + hipGetErrorString(e); return CLOVER_E_HIP; }
+  if (dev < 0 || dev >= kMaxDevices) { g_err = "device index beyond the static scratch table"; return CLOVER_E_SHAPE; }
+  if (!g_static_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch));
+    if (e != hipSuccess || !p) {
+      g_err = std::string("hipGetSymbolAddress(static scratch): ") + hipGetErrorString(e);
+      return CLOVER_E_HIP;
+    }
+    g_static_scratch_ptr[dev] = p;
+  }
+  *out = g_static_scratch_ptr[dev];
+  return CLOVER_OK;
+}
+
 }  // namespace
 
 // ================================================================================================
@@ -1167,6 +1195,26 @@ size_t clover_op_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K) {
 
 int clover_op_gemm(int32_t path, int32_t dtype, const float* X, const void* W, float* Y, int32_t ldy, int32_t M,
                    int32_t N, int32_t K, void* scratch, size_t scratch_bytes, void* hip_stream) {
+  return op_gemm_impl(path, dtype, X, W, Y, ldy, M, N, K, scratch, scratch_bytes, hip_stream);
+}
+
+int clover_op_gemm_static(int32_t path, int32_t dtype, const float* X, const void* W, float* Y, int32_t ldy, int32_t M,
+                          int32_t N, int32_t K, void* hip_stream) {
+  if (path != 0 && path != 1 && path != 3 && path != 5)
+    return fail(nullptr, CLOVER_E_SHAPE, "clover_op_gemm_static: path must be 0, 1, 3 or 5 (the shared buffer keeps no copy between calls)");
+  if (M >= 1 && N >= 1 && K >= 1 && clover_op_gemm_scratch_bytes(M, N, K) > CLOVER_STATIC_SCRATCH_BYTES)
+    return fail(nullptr, CLOVER_E_CAPACITY, "clover_op_gemm_static: M, N, K need more than CLOVER_STATIC_SCRATCH_BYTES of scratch");
+  void* ptr = nullptr;
+  const int rc = static_scratch_ptr(&ptr);
+  if (rc) return rc;
+  return op_gemm_impl(path, dtype, X, W, Y, ldy, M, N, K, ptr, CLOVER_STATIC_SCRATCH_BYTES, hip_stream);
+}
+
+}  // extern "C"
+
+namespace {
+int op_gemm_impl(int32_t path, int32_t dtype, const float* X, const void* W, float* Y, int32_t ldy, int32_t M,
+                 int32_t N, int32_t K, void* scratch, size_t scratch_bytes, void* hip_stream) {
   if (!X || !W || !Y || !scratch) return fail(nullptr, CLOVER_E_NULL, "null argument");
   if (M < 1 || N < 1 || K < 1 || ldy < N) return fail(nullptr, CLOVER_E_SHAPE, "bad GEMM shape");
   hipStream_t st = (hipStream_t)hip_stream;
@@ -1233,4 +1281,4 @@ int clover_op_gemm(int32_t path, int32_t dtype, const float* X, const void* W, f
   return CLOVER_OK;
 }
 
-}  // extern "C"
+}  // namespace
