@@ -143,6 +143,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="debug: override the number of target layers")
     ap.add_argument("--prompt", type=int, default=0, help="debug: override the prompt length")
     ap.add_argument("--flags", type=int, default=0)
+    ap.add_argument("--library", default="", help="load another build of libclover.so (reported in the JSON line)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib", action="store_true",
                     help="also launch an elementwise kernel that reads 1 GiB and writes 1 GiB (three times), the "
@@ -157,6 +158,8 @@ def main():
 
     import torch
     from paper_2408_00264_amd import clover, synth
+    if args.library:
+        clover.load_library(os.path.abspath(args.library))
 
     if not torch.cuda.is_available():
         log("bench.py: no GPU visible")

@@ -36,15 +36,17 @@ union Frag {
   bf16x8 v;
 };
 
-__device__ __forceinline__ unsigned a_rn(float a) {
-  unsigned u = __float_as_uint(a);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return u >> 16;
-}
+// float -> bf16 (round to nearest even) through the hardware conversion (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ unsigned a_rn(float a) { return (unsigned)__builtin_bit_cast(unsigned short, (__bf16)a); }
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+// (a, b) -> packed hi pair and packed lo pair, hi + lo == value to 16 mantissa bits: six instructions per pair
 __device__ __forceinline__ void a_split2(float a, float b, unsigned& hi, unsigned& lo) {
-  const unsigned ha = a_rn(a), hb = a_rn(b);
-  hi = ha | (hb << 16);
-  lo = a_rn(a - __uint_as_float(ha << 16)) | (a_rn(b - __uint_as_float(hb << 16)) << 16);
+  const f32x2_t v = {a, b};
+  const bf16x2_t h = __builtin_convertvector(v, bf16x2_t);
+  const bf16x2_t l = __builtin_convertvector(v - __builtin_convertvector(h, f32x2_t), bf16x2_t);
+  hi = __builtin_bit_cast(unsigned, h);
+  lo = __builtin_bit_cast(unsigned, l);
 }
 
 constexpr int AT_D = 128;         // head dim
@@ -197,8 +199,11 @@ __global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
       for (int e = 0; e < 8; ++e) { pe[e] = __expf(sv[e] - m_safe); psum += pe[e]; }
       l_run[mb] = l_run[mb] * corr + psum;
       m_run[mb] = m_new;
+      // the running maximum rarely moves after the first tiles: rescale only when some row of the wavefront needs it
+      if (__builtin_amdgcn_ballot_w64(corr != 1.0f) != 0ull) {
 #pragma unroll
-      for (int db = 0; db < 8; ++db) O[db][mb] *= corr;
+        for (int db = 0; db < 8; ++db) O[db][mb] *= corr;
+      }
       unsigned h, l;
       a_split2(pe[0], pe[1], h, l); ph[mb].u.x = h; pl[mb].u.x = l;
       a_split2(pe[2], pe[3], h, l); ph[mb].u.y = h; pl[mb].u.y = l;

@@ -22,11 +22,8 @@ namespace clv {
 
 namespace {
 
-__device__ __forceinline__ unsigned rn_bf16(float a) {
-  unsigned u = __float_as_uint(a);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return u >> 16;
-}
+// float -> bf16 (round to nearest even) through the hardware conversion (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ unsigned rn_bf16(float a) { return (unsigned)__builtin_bit_cast(unsigned short, (__bf16)a); }
 __device__ __forceinline__ float bf16f(bf16_t b) { return __uint_as_float((unsigned)b << 16); }
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

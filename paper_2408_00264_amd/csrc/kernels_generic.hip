@@ -9,11 +9,8 @@ namespace clv {
 // small device helpers
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ float bf16_to_f32(bf16_t u) { return __uint_as_float(((unsigned)u) << 16); }
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-  unsigned u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);  // round to nearest even (inputs are finite)
-  return (bf16_t)(u >> 16);
-}
+// round to nearest even through the hardware conversion (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) { return __builtin_bit_cast(unsigned short, (__bf16)f); }
 __device__ __forceinline__ float ldf(const float* p, size_t i) { return p[i]; }
 __device__ __forceinline__ float ldf(const bf16_t* p, size_t i) { return bf16_to_f32(p[i]); }
 __device__ __forceinline__ void stf(float* p, size_t i, float v) { p[i] = v; }

@@ -46,11 +46,8 @@ constexpr int PN_WAVES = 8;
 constexpr int PN_KST = 256;           // K columns per activation stage (8 k-tiles of 32)
 constexpr int PN_NFW = 2;
 
-__device__ __forceinline__ unsigned rn_bf16(float a) {
-  unsigned u = __float_as_uint(a);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return u >> 16;
-}
+// float -> bf16 (round to nearest even) through the hardware conversion (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ unsigned rn_bf16(float a) { return (unsigned)__builtin_bit_cast(unsigned short, (__bf16)a); }
 
 template <int I, int N, class F>
 __device__ __forceinline__ void static_for(F&& f) {
@@ -132,7 +129,8 @@ __global__ __launch_bounds__(PN_WAVES * 64) void gemm_panel_kernel(PanelGemm p) 
       const int rp = idx / SL, sl = idx % SL, plane = rp / ROWS, r = rp % ROWS;
       // always load (row clamped), then zero the padding rows: no branch around a load
       const bf16_t* src = (plane ? p.Xlo : p.Xhi) + (size_t)min(r, p.M - 1) * p.ldx + ks * KST + sl * 8;
-      const u32x4 v = *(const u32x4*)src;
+      u32x4 v = (u32x4){0u, 0u, 0u, 0u};
+      if (!CLV_DBG(p, 1)) v = *(const u32x4*)src;
       xv[it] = r < p.M ? v : (u32x4){0u, 0u, 0u, 0u};
     }
   };
@@ -146,6 +144,13 @@ __global__ __launch_bounds__(PN_WAVES * 64) void gemm_panel_kernel(PanelGemm p) 
   };
   auto compute = [&](auto bufc, int b) {
     constexpr int buf = decltype(bufc)::value;
+    if (CLV_DBG(p, 4)) {  // keep the weight loads alive without LDS reads and matrix work
+#pragma unroll
+      for (int f = 0; f < PN_NFW; ++f)
+#pragma unroll
+        for (int t = 0; t < CH; ++t) acc[f][0][0] += __uint_as_float(w[buf][f][t].u.x & 0x3f800000u);
+      return;
+    }
     const bf16_t* hi = xs + b * BUF + l16 * PN_LDK + g4 * 8 + kp * CH * 32;
     const bf16_t* lo = hi + PLANE;
 #pragma unroll
@@ -186,7 +191,7 @@ __global__ __launch_bounds__(PN_WAVES * 64) void gemm_panel_kernel(PanelGemm p) 
     compute(std::integral_constant<int, I>{}, s & 1);
     __builtin_amdgcn_sched_barrier(0);
     if (FULL || s + 1 < NS) x_store((s + 1) & 1);
-    __syncthreads();
+    if (!CLV_DBG(p, 8)) __syncthreads();
   };
   int s0 = 0;
   for (; s0 + 2 * NBUF - 2 < NS; s0 += NBUF)
@@ -242,7 +247,11 @@ __global__ __launch_bounds__(PN_WAVES * 64) void gemm_panel_kernel(PanelGemm p) 
       for (int mb = 0; mb < MT; ++mb) {
         const int m = mb * 16 + l16;
         const f32x4 v = acc[f][mb];
-        if (m < p.M) *(float4*)(p.Y + part * p.split_stride + (size_t)m * p.ldy + col) = make_float4(v[0], v[1], v[2], v[3]);
+        if (m < p.M) {
+          float4* dst = (float4*)(p.Y + part * p.split_stride + (size_t)m * p.ldy + col);
+          if (CLV_DBG(p, 16)) __builtin_nontemporal_store(v, (f32x4*)dst);
+          else *dst = make_float4(v[0], v[1], v[2], v[3]);
+        }
       }
     }
   }

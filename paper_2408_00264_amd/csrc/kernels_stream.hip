@@ -178,7 +178,11 @@ __global__ __launch_bounds__(ST_WAVES * 64) void gemm_stream_kernel(StreamGemm p
         for (int mb = 0; mb < MT; ++mb) {
           const int m = mb * 16 + l16;
           const f32x4 v = acc[f][mb];
-          if (m < p.M && !CLV_DBG(p, 2)) *(float4*)(ybase + (size_t)m * p.ldy + col) = make_float4(v[0], v[1], v[2], v[3]);
+          if (m < p.M && !CLV_DBG(p, 2)) {
+            float4* dst = (float4*)(ybase + (size_t)m * p.ldy + col);
+            if (CLV_DBG(p, 4)) __builtin_nontemporal_store(v, (f32x4*)dst);
+            else *dst = make_float4(v[0], v[1], v[2], v[3]);
+          }
           acc[f][mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
         }
       }
@@ -255,11 +259,8 @@ void launch_gemm_stream(StreamGemm g, hipStream_t st) {
 // ------------------------------------------------------------------------------------------
 // consumer of the fused gate/up projection: h = silu(sum_s P[s][m][c]) * (sum_s P[s][m][F + c]), as planes
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ unsigned rn_bf16(float a) {
-  unsigned u = __float_as_uint(a);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return u >> 16;
-}
+// float -> bf16 (round to nearest even) through the hardware conversion (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ unsigned rn_bf16(float a) { return (unsigned)__builtin_bit_cast(unsigned short, (__bf16)a); }
 __global__ void reduce_swiglu_kernel(const float* __restrict__ P, int splits, size_t sps, int ldp, int F,
                                      bf16_t* __restrict__ hi, bf16_t* __restrict__ lo, int ldo) {
   const size_t row = blockIdx.y;
