@@ -6,11 +6,13 @@ on one MI355X.  Prints ONE JSON line.
 
 A "step" is one pass of the whole hot path over one batch of synthetic input (weights and KV
 cache resident in HBM, prompt prefilled before the timed region).  The default workload is the
-LLaMA3-8B-shaped batch-1 configuration (64-node tree over 1024 cached tokens).
+LLaMA3-8B-shaped batch-1 configuration (64-node tree over 1024 cached tokens); --config 4 and 5
+run the ragged batch-8 and the long-context workloads.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -22,10 +24,17 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+def layer_params(shape):
+    H, d = shape.hidden, shape.head_dim
+    nq, nkv, F = shape.n_q_heads, shape.n_kv_heads, shape.ffn
+    return {"gemm_qkv": (nq + 2 * nkv) * d * H, "gemm_wo": H * nq * d, "gemm_gate_up": 2 * F * H, "gemm_down": H * F}
 
 
 def verify_bytes(shape, B, N, L_sum):
@@ -33,50 +42,50 @@ def verify_bytes(shape, B, N, L_sum):
     cached K/V rows read once and the new K/V rows written once at 2 bytes per value (a bf16 cache:
     what the method needs; this library's caches hold a bf16 hi/lo pair, i.e. it moves 4, which is
     its own cost and does not count towards the achieved rate)."""
-    H, d = shape.hidden, shape.head_dim
-    nq, nkv, F, V = shape.n_q_heads, shape.n_kv_heads, shape.ffn, shape.vocab
-    per_layer = (nq * d * H) + 2 * (nkv * d * H) + (H * nq * d) + 3 * F * H
-    weights = 2 * (shape.n_layers * per_layer + V * H)
-    kv_row = 2 * nkv * d * 2
+    weights = 2 * (shape.n_layers * sum(layer_params(shape).values()) + shape.vocab * shape.hidden)
+    kv_row = 2 * shape.n_kv_heads * shape.head_dim * 2
     kv_read = shape.n_layers * kv_row * (L_sum + B * N)
     kv_write = shape.n_layers * kv_row * B * N
     return weights + kv_read + kv_write
 
 
 def draft_bytes(shape, n_levels):
-    H, d = shape.hidden, shape.head_dim
-    nq, nkv, F, V = shape.n_q_heads, shape.n_kv_heads, shape.ffn, shape.vocab
-    per_layer = (nq * d * H) + 2 * (nkv * d * H) + (H * nq * d) + 3 * F * H
-    w = 3 * H * H + shape.aug_layers * per_layer + H * H + (n_levels - 1) * (3 * H * H + 2 * H * H) + n_levels * V * H
+    H = shape.hidden
+    w = 3 * H * H + shape.aug_layers * sum(layer_params(shape).values()) + H * H + \
+        (n_levels - 1) * (3 * H * H + 2 * H * H) + n_levels * shape.vocab * H
     return 2 * w
 
 
-def measured_traffic(kernel, config):
-    """HBM bytes per launch of the dominant kernel from the committed counter summary (FETCH_SIZE and
-    WRITE_SIZE passes scaled by a copy of known size); None when no summary covers the workload."""
-    path = os.path.join(ROOT, "profiles", f"traffic_{kernel}_config{config}.txt")
+def source_fingerprint():
+    """sha256 over the kernel sources: a committed profile summary is used only while it was taken from THESE
+    sources (it records the fingerprint it was measured with)."""
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2408_00264_amd", "csrc")
+    for n in sorted(os.listdir(csrc)):
+        if n.endswith((".hip", ".h")):
+            h.update(n.encode())
+            h.update(open(os.path.join(csrc, n), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def profile_value(path, key, fingerprint):
+    """`key: value` from a committed profile summary, or None when the file is missing, does not carry the key, or
+    was measured with other kernel sources than the ones in this tree."""
     try:
-        for line in open(path):
-            if line.strip().startswith("traffic_bytes_per_launch:"):
-                return int(line.split(":")[1])
+        text = open(os.path.join(ROOT, "profiles", path)).read()
     except OSError:
-        pass
-    return None
-
-
-def traced_avg_ms(kernel, config):
-    """Average duration of the dominant kernel in the committed rocprofv3 --kernel-trace --stats summary of this
-    workload (None if there is none).  HIP events around a launch also see its dispatch latency (a few microseconds
-    more); the roofline figure uses the event-timed duration measured in this run."""
-    path = os.path.join(ROOT, "profiles", f"spec_step_config{config}_kernel_trace.txt")
+        return None
+    vals = {}
+    for line in text.splitlines():
+        if ":" in line:
+            k, v = line.split(":", 1)
+            vals[k.strip()] = v.strip()
+    if vals.get("source_fingerprint") != fingerprint or key not in vals:
+        return None
     try:
-        for line in open(path):
-            f = line.split()
-            if len(f) >= 5 and kernel in line:
-                return float(f[2]) * 1e-3
-    except (OSError, ValueError):
-        pass
-    return None
+        return float(vals[key])
+    except ValueError:
+        return None
 
 
 def cpu_baseline(shape, parent, rank, L, sample_layers, store, min_seconds):
@@ -139,7 +148,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3, choices=[2, 3, 4, 5])
     ap.add_argument("--layers", type=int, default=0, help="debug: override the number of target layers")
     ap.add_argument("--prompt", type=int, default=0, help="debug: override the prompt length")
     ap.add_argument("--flags", type=int, default=0)
@@ -154,6 +163,13 @@ def main():
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
             "(the speculative step of one sequence batch lives on one device)")
+        sys.exit(2)
+    # The shipped library reads no environment variable; a tuning build does.  A number measured with a switch set
+    # must not pass for the default path: refuse unless another library was named explicitly, and report the set.
+    switches = sorted(k for k in os.environ if k.startswith("CLOVER_"))
+    if switches and not args.library:
+        log(f"bench.py: environment switches {switches} are set; unset them (the shipped library ignores them, a "
+            "tuning build named with --library would not)")
         sys.exit(2)
 
     import torch
@@ -226,8 +242,8 @@ def main():
     run_steps(K, events)
     torch.cuda.synchronize()
     lens2 = g.seq_len()
-    # ---- third pass with the library's event pairs around every kernel class (these add gaps
-    # between the kernels, so only the per-class sums of this pass are used) ----
+    # ---- third pass with the library's HIP-event pairs around every kernel class, recorded on the library's own
+    # stream (these add gaps between the kernels, so only the per-class sums of this pass are used) ----
     g.profile_enable(True)
     torch.cuda.synchronize()
     run_steps(K)
@@ -240,17 +256,48 @@ def main():
     dra = np.array([e[2].elapsed_time(e[3]) for e in events])
     L_sum = int(lens1[:B].sum())
     vbytes = verify_bytes(shape, B, N, L_sum)
-    n_levels = D
-    dbytes = draft_bytes(shape, n_levels)
+    dbytes = draft_bytes(shape, D)
     kernels = {k: {"ms_per_step": v[0] / K, "launches_per_step": v[1] / K} for k, v in prof.items() if v[1]}
-    # dominant kernel: the fused gate/up projection (largest weight stream of a layer)
-    dom_name = "gemm_gate_up (fused SwiGLU projection)"
+    ver_med = float(np.median(ver))
+
+    # ---- per kernel class: bytes the class has to move per call and what it reached.  More than 64 rows run as
+    # row batches of 128, each batch a launch of its own that streams the weights once; the class timer brackets
+    # all batches of one call, so a class's rate is against ONE pass over its weights. ----
+    rows = B * N
+    passes = (rows + 127) // 128 if rows > 64 else 1
+    lp = layer_params(shape)
+    classes = {}
+    for name, params in list(lp.items()) + [("gemm_lm_head", shape.vocab * shape.hidden)]:
+        if name in prof and prof[name][1]:
+            ms = prof[name][0] / prof[name][1]
+            classes[name] = {"weight_bytes": 2 * params, "avg_call_ms": ms, "weight_passes": passes,
+                             "GBps": 2 * params / (ms * 1e-3) / 1e9, "frac": 2 * params / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    # tree attention: K/V rows of the cached tokens and the tree nodes of one layer; the library's cache holds
+    # 4 bytes per value (bf16 hi/lo pair), the method needs 2
+    if "tree_attention" in prof and prof["tree_attention"][1]:
+        ms = prof["tree_attention"][0] / prof["tree_attention"][1]
+        kv_vals = 2 * shape.n_kv_heads * shape.head_dim * (L_sum + B * N)
+        classes["tree_attention"] = {"kv_bytes_algorithmic": 2 * kv_vals, "kv_bytes_stored": 4 * kv_vals, "avg_call_ms": ms,
+                                     "GBps_algorithmic": 2 * kv_vals / (ms * 1e-3) / 1e9,
+                                     "GBps_stored": 4 * kv_vals / (ms * 1e-3) / 1e9,
+                                     "frac": 2 * kv_vals / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                     "note": "attention kernel + the merge of its key splits"}
+
+    # dominant kernel: the fused gate/up projection (largest weight stream of a layer); one launch = one pass over
+    # both weight matrices for up to 128 rows
+    dom_name = "gemm_gate_up (fused SwiGLU projection, one launch = one pass over both weight matrices)"
     dom_ms, dom_n = prof["gemm_gate_up"]
-    dom_bytes = 2 * 2 * shape.ffn * shape.hidden
-    traffic_key = "gemm_gate_up"
-    trace_name = "gemm_panel_kernel<4, 2, 1, 2, 256>"
-    dom_avg_ms = dom_ms / max(dom_n, 1)
+    dom_bytes = 2 * lp["gemm_gate_up"]
+    dom_avg_ms = dom_ms / max(dom_n, 1) / passes
     achieved = dom_bytes / (dom_avg_ms * 1e-3) / 1e9 if dom_n else 0.0
+    rows_per_launch = (rows + passes - 1) // passes
+    issued_tflops = 2 * 2 * rows_per_launch * lp["gemm_gate_up"] / (dom_avg_ms * 1e-3) / 1e12   # hi and lo planes
+    fp = source_fingerprint()
+    default_workload = not (args.layers or args.prompt or args.library or args.flags)
+    traffic = profile_value(f"traffic_gemm_gate_up_config{args.config}.txt", "traffic_bytes_per_launch", fp) \
+        if default_workload else None
+    trace_us = profile_value(f"spec_step_config{args.config}_kernel_trace.txt", "gate_up_avg_us", fp) \
+        if default_workload else None
     out = {
         "metric": "verified tree-tokens/s over the whole speculative step (draft_tree + verify_tree + accept_and_compact)",
         "value": B * N / (ms_per_step * 1e-3), "unit": "tree-tokens/s", "n_gpus": 1, "steps": K, "warmup": Wm,
@@ -258,21 +305,27 @@ def main():
         "dtype": "bf16" if shape.bf16 else "f32", "data": "synthetic",
         "config": {"workload": f"config {args.config}: {shape.name}, batch {B}, {N}-node tree, "
                                f"cached lengths {lens1[:B].tolist()}, {shape.n_layers} layers",
-                   "accepted_per_step": float((lens2[:B] - lens1[:B]).sum()) / (K * B)},
-        "calls_ms": {"verify_tree": {"median": float(np.median(ver)), "p10": float(np.percentile(ver, 10)),
+                   "accepted_per_step": float((lens2[:B] - lens1[:B]).sum()) / (K * B),
+                   "library": os.path.abspath(args.library) if args.library else "shipped",
+                   "env_switches": switches},
+        "calls_ms": {"verify_tree": {"median": ver_med, "p10": float(np.percentile(ver, 10)),
                                      "p90": float(np.percentile(ver, 90))},
                      "accept_and_compact": {"median": float(np.median(acc))},
                      "draft_tree": {"median": float(np.median(dra))}},
-        "verify_hbm": {"algorithmic_bytes": vbytes, "GBps": vbytes / (float(np.median(ver)) * 1e-3) / 1e9,
-                       "frac_of_peak": vbytes / (float(np.median(ver)) * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                       "tree_tokens_per_s": B * N / (float(np.median(ver)) * 1e-3)},
+        "verify_hbm": {"algorithmic_bytes": vbytes, "GBps": vbytes / (ver_med * 1e-3) / 1e9,
+                       "frac_of_peak": vbytes / (ver_med * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       "tree_tokens_per_s": B * N / (ver_med * 1e-3),
+                       "weight_passes_per_gemm": passes},
         "draft_hbm": {"algorithmic_bytes": dbytes, "GBps": dbytes / (float(np.median(dra)) * 1e-3) / 1e9},
         "roofline": {"kernel": dom_name, "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": measured_traffic(traffic_key, args.config) if not (args.layers or args.prompt) else None,
+                     "traffic": int(traffic) if traffic else None,
                      "bytes_per_launch": dom_bytes, "avg_launch_ms": dom_avg_ms,
-                     "kernel_trace_avg_launch_ms": traced_avg_ms(trace_name, args.config)
-                     if not (args.layers or args.prompt) else None},
+                     "rows_per_launch": rows_per_launch,
+                     "mfma_issued_TFLOPs": issued_tflops, "mfma_frac_of_bf16_peak": issued_tflops / MFMA_BF16_PEAK_TFLOPS,
+                     "kernel_trace_avg_launch_ms": trace_us * 1e-3 if trace_us else None,
+                     "source_fingerprint": fp},
+        "kernel_classes": classes,
         "kernels": kernels,
     }
     if not args.no_cpu_baseline:

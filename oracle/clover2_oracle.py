@@ -36,7 +36,9 @@ brute force; the matrices a regressive update and the Augmenting Block multiply
 by, priced against the cost figures of Sec. 3.3; the draft wiring (which token
 embedding and whose state AD1 / AD2 / FC_j receive, what is handed down) against
 a closed form in the tokens alone for additive Attention Decoders, a pin that
-planted wiring mistakes are shown to fail.  The paper prints no worked numeric
+planted wiring mistakes are shown to fail; the dynamic (score-pruned) tree
+against brute force over every prefix of the full static tree, normalisation of
+its scores, and the lossless property.  The paper prints no worked numeric
 example, so no pin compares against printed values.
 """
 from __future__ import annotations
@@ -324,6 +326,107 @@ def draft_tree(W: Weights, cfg: OracleConfig, seq: SeqState, hid_acc: np.ndarray
         g = W(f"fc.{j}.w") @ np.concatenate([s, e]) + W(f"fc.{j}.b")
         expand(node, W("lm_head") @ rmsnorm(g, W("head_norm"), cfg.rms_eps))
     return tokens, zs
+
+
+def log_softmax(z: np.ndarray) -> np.ndarray:
+    z = z - z.max()
+    return z - np.log(np.exp(z).sum())
+
+
+def draft_tree_dynamic(W: Weights, cfg: OracleConfig, seq: SeqState, hid_acc: np.ndarray, next_tok: Sequence[int],
+                       topk: int, frontier: int, n_nodes: int, follow: Optional[dict] = None) -> dict:
+    """Score-pruned dynamic tree (Sec. 4.1: the tree is constructed the way EAGLE constructs it; the reading
+    taken here is the expand-and-rerank scheme below).
+
+    Same draft head as `draft_tree` (AD1, Augmenting Block, head 0, regressive AD2/FC_j updates, shared LM
+    head), but the topology is chosen per call from the draft's own probabilities:
+      * a candidate's score is the sum of the draft log-probabilities (log-softmax of its parent's logits at
+        its token) along its root path; the root has score 0;
+      * the root expands into its `topk` most probable tokens (ids by value descending, id ascending);
+      * at every depth j = 1 .. D-1 the `frontier` best candidates of that depth (score descending, older
+        candidate first) are expanded, each into its `topk` most probable tokens;
+      * of all candidates the n_nodes - 1 best (score descending, shallower first, older first) form the
+        tree together with the root; a child never outscores its parent, so the set is closed under parents;
+      * nodes are numbered breadth-first: by depth, then by the parent's number, then by rank under the parent.
+    Candidates are numbered in creation order: 0 = root, depth-1 candidates in rank order, then for each
+    depth the children of the expanded candidates in (expansion order, rank) order.
+
+    `follow` = dict(tokens=[per candidate], frontier=[[candidate ids per depth 1..D-1]], keep=[candidate ids])
+    makes the oracle take those decisions instead of its own (tests follow a tolerated near-tie choice of the
+    other side); every score and logit returned is still the oracle's own.
+
+    Returns dict(tokens, parent, rank [n_nodes]; cand_token, cand_parent, cand_depth, cand_rank, cand_score
+    [per candidate]; frontier [[ids]]; keep [candidate id of every tree node]; logits {candidate id: z})."""
+    m = hid_acc.shape[0]
+    next_tok = np.asarray(next_tok, dtype=np.int64)
+    assert m >= 1 and len(next_tok) == m and topk >= 1 and frontier >= 1 and n_nodes >= 1
+    D = cfg.draft_depths
+    lm = W("lm_head")
+    emb = lambda t: lm[np.asarray(t, dtype=np.int64)].astype(cfg.dtype)
+    u = attention_decoder(W, "ad1.", cfg, hid_acc.astype(cfg.dtype), emb(next_tok))
+    L0 = seq.aug_L
+    assert L0 + m <= cfg.max_seq
+    pos = L0 + np.arange(m)
+    causal = np.tril(np.ones((m, m), dtype=bool))
+    a = u
+    for li in range(cfg.aug_layers):
+        a = decoder_layer(W, f"aug.{li}.", cfg, a, seq.aug_kv, li, L0, pos, pos, causal)
+    seq.aug_L = L0 + m
+
+    c_tok, c_par, c_dep, c_rank, c_score = [int(next_tok[m - 1])], [-1], [0], [0], [0.0]
+    state: Dict[int, np.ndarray] = {0: a[m - 1]}
+    zs: Dict[int, np.ndarray] = {}
+    fronts: List[List[int]] = []
+
+    def expand(c: int, z: np.ndarray) -> None:
+        zs[c] = z
+        lp = log_softmax(z.astype(np.float64))
+        top = ranked_ids(z, topk)
+        for i in range(topk):
+            cid = len(c_tok)
+            t = int(top[i]) if follow is None else int(follow["tokens"][cid])
+            c_tok.append(t); c_par.append(c); c_dep.append(c_dep[c] + 1); c_rank.append(i)
+            c_score.append(c_score[c] + float(lp[t]))
+
+    g = W("fc0.w") @ state[0] + W("fc0.b")
+    expand(0, W("lm_head") @ rmsnorm(g, W("head_norm"), cfg.rms_eps))
+    for j in range(1, D):
+        level = [c for c in range(len(c_tok)) if c_dep[c] == j]
+        if follow is None:
+            chosen = sorted(level, key=lambda c: (-c_score[c], c))[:frontier]
+        else:
+            chosen = [int(c) for c in follow["frontier"][j - 1]]
+            assert all(c_dep[c] == j for c in chosen) and len(set(chosen)) == len(chosen) <= frontier
+        fronts.append(chosen)
+        for c in chosen:
+            e = emb(c_tok[c])
+            s = attention_decoder(W, "ad2.", cfg, state[c_par[c]][None, :], e[None, :])[0]
+            state[c] = s
+            g = W(f"fc.{j}.w") @ np.concatenate([s, e]) + W(f"fc.{j}.b")
+            expand(c, W("lm_head") @ rmsnorm(g, W("head_norm"), cfg.rms_eps))
+
+    cands = list(range(1, len(c_tok)))
+    assert len(cands) >= n_nodes - 1, "fewer candidates than tree nodes"
+    if follow is None:
+        keep = [0] + sorted(cands, key=lambda c: (-c_score[c], c_dep[c], c))[:n_nodes - 1]
+    else:
+        keep = [int(c) for c in follow["keep"]]
+        assert keep[0] == 0 and len(set(keep)) == len(keep) == n_nodes
+    kept = set(keep)
+    assert all(c == 0 or c_par[c] in kept for c in keep), "selection is not closed under parents"
+    # breadth-first numbering: by depth, then the parent's number, then the rank under the parent
+    number: Dict[int, int] = {0: 0}
+    order = [0]
+    for j in range(1, D + 1):
+        level = sorted((c for c in keep if c_dep[c] == j), key=lambda c: (number[c_par[c]], c_rank[c]))
+        for c in level:
+            number[c] = len(order)
+            order.append(c)
+    tokens = np.asarray([c_tok[c] for c in order], dtype=np.int64)
+    parent = np.asarray([-1] + [number[c_par[c]] for c in order[1:]], dtype=np.int64)
+    rank = np.asarray([c_rank[c] for c in order], dtype=np.int64)
+    return dict(tokens=tokens, parent=parent, rank=rank, cand_token=c_tok, cand_parent=c_par, cand_depth=c_dep,
+                cand_rank=c_rank, cand_score=c_score, frontier=fronts, keep=order, logits=zs)
 
 
 def accept_greedy(tokens: Sequence[int], logits: np.ndarray, parent: Sequence[int],

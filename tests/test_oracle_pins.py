@@ -659,3 +659,149 @@ def test_p10_pin_detects_planted_wiring_mistakes(name, replacements):
     mutant = _mutant(replacements)
     with pytest.raises(AssertionError):
         _wiring_pin(mutant)
+
+
+# ---------------------------------------------------------------- P11: the dynamic (score-pruned) tree, Sec. 4.1
+def _full_static_tree(k, D):
+    """Complete k-ary tree of depth D in breadth-first order with ranks 0..k-1 under every parent."""
+    parent, rank, depth = [-1], [0], [0]
+    level = [0]
+    for _ in range(D):
+        nxt = []
+        for u in level:
+            for i in range(k):
+                parent.append(u); rank.append(i); depth.append(depth[u] + 1)
+                nxt.append(len(parent) - 1)
+        level = nxt
+    return np.asarray(parent), np.asarray(rank), np.asarray(depth)
+
+
+def _path_key(parent, rank, u):
+    out = []
+    while u > 0:
+        out.append(int(rank[u])); u = int(parent[u])
+    return tuple(out[::-1])
+
+
+def _dynamic_case(seed=5, m=2):
+    ws, cfg, W = make(gain_jitter=0.1, max_seq=64)
+    rng = np.random.default_rng(seed)
+    hid = rng.standard_normal((m, TINY.hidden))
+    nxt = [int(t) for t in rng.integers(0, TINY.vocab, m)]
+    return ws, cfg, W, hid, nxt
+
+
+def _brute_scores(W, cfg, hid, nxt, k, D):
+    """Cumulative draft log-probability of EVERY node of the complete k-ary tree, from the static-tree oracle's
+    logits (pinned by P5/P10) and a log-softmax written out here."""
+    parent, rank, depth = _full_static_tree(k, D)
+    seq = O.SeqState(cfg)
+    tokens, zs = O.draft_tree(W, cfg, seq, hid, nxt, parent, rank)
+    score = np.zeros(len(parent))
+    for u in range(1, len(parent)):
+        z = zs[int(parent[u])].astype(np.float64)
+        lse = np.log(np.sum(np.exp(z - z.max()))) + z.max()
+        score[u] = score[parent[u]] + z[tokens[u]] - lse
+    return parent, rank, depth, tokens, score
+
+
+def test_p11_dynamic_tree_is_the_best_prefixes_of_the_full_tree():
+    """No frontier pruning (every candidate of a depth is expanded): the dynamic tree must be exactly the
+    n_nodes - 1 most probable prefixes among ALL prefixes of the complete tree, found here by brute force."""
+    k, D, N = 3, TINY.draft_depths, 14
+    ws, cfg, W, hid, nxt = _dynamic_case()
+    parent, rank, depth, tokens, score = _brute_scores(W, cfg, hid, nxt, k, D)
+    order = sorted(range(1, len(parent)), key=lambda u: (-score[u], depth[u], u))[:N - 1]
+    want = {_path_key(parent, rank, u): int(tokens[u]) for u in order}
+    dyn = O.draft_tree_dynamic(W, cfg, O.SeqState(cfg), hid, nxt, topk=k, frontier=k ** D, n_nodes=N)
+    got = {_path_key(dyn["parent"], dyn["rank"], u): int(dyn["tokens"][u]) for u in range(1, N)}
+    assert got == want
+    assert dyn["tokens"][0] == nxt[-1] and len(dyn["tokens"]) == N
+    # scores reported per candidate equal the brute-force ones
+    by_path = {_path_key(parent, rank, u): score[u] for u in range(1, len(parent))}
+    for c in range(1, len(dyn["cand_token"])):
+        path, w = [], c
+        while w > 0:
+            path.append(dyn["cand_rank"][w]); w = dyn["cand_parent"][w]
+        assert abs(dyn["cand_score"][c] - by_path[tuple(path[::-1])]) < 1e-9
+
+
+def test_p11_frontier_pruning_bruteforce():
+    """frontier = 2: at every depth only the two best candidates (among the children of the previous frontier)
+    are expanded; checked against the complete tree's brute-force scores."""
+    k, D, N, K = 3, TINY.draft_depths, 10, 2
+    ws, cfg, W, hid, nxt = _dynamic_case(seed=6, m=1)
+    parent, rank, depth, tokens, score = _brute_scores(W, cfg, hid, nxt, k, D)
+    kids = O.children_of(parent)
+    alive = list(kids[0])                       # generated candidates of the current depth
+    generated = list(alive)
+    for j in range(1, D):
+        front = sorted(alive, key=lambda u: (-score[u], u))[:K]
+        alive = [c for u in front for c in kids[u]]
+        generated += alive
+    keep = sorted(generated, key=lambda u: (-score[u], depth[u], u))[:N - 1]
+    want = {_path_key(parent, rank, u): int(tokens[u]) for u in keep}
+    dyn = O.draft_tree_dynamic(W, cfg, O.SeqState(cfg), hid, nxt, topk=k, frontier=K, n_nodes=N)
+    got = {_path_key(dyn["parent"], dyn["rank"], u): int(dyn["tokens"][u]) for u in range(1, N)}
+    assert got == want
+    assert len(dyn["cand_token"]) == 1 + k + (D - 1) * K * k
+
+
+def test_p11_scores_are_normalised_log_probabilities():
+    """topk = whole vocabulary on a tiny head: the exp(score) of all depth-1 candidates sum to 1, and those of
+    the children of any expanded candidate sum to that candidate's own probability."""
+    shape = synth.scaled(TINY, name="tiny-v32", vocab=32, seed=3)
+    ws, cfg, W = make(shape=shape, gain_jitter=0.1, max_seq=32)
+    rng = np.random.default_rng(1)
+    hid = rng.standard_normal((1, shape.hidden))
+    dyn = O.draft_tree_dynamic(W, cfg, O.SeqState(cfg), hid, [7], topk=32, frontier=3, n_nodes=20)
+    sc, par, dep = np.asarray(dyn["cand_score"]), np.asarray(dyn["cand_parent"]), np.asarray(dyn["cand_depth"])
+    assert abs(np.exp(sc[dep == 1]).sum() - 1.0) < 1e-12
+    for front in dyn["frontier"]:
+        for c in front:
+            assert abs(np.exp(sc[par == c]).sum() - np.exp(sc[c])) < 1e-12
+    assert len({dyn["cand_token"][c] for c in range(len(sc)) if par[c] == 0}) == 32   # all distinct tokens
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_p11_dynamic_tree_invariants(seed):
+    ws, cfg, W, hid, nxt = _dynamic_case(seed=10 + seed, m=3)
+    N = 16
+    dyn = O.draft_tree_dynamic(W, cfg, O.SeqState(cfg), hid, nxt, topk=4, frontier=3, n_nodes=N)
+    parent, rank, toks = dyn["parent"], dyn["rank"], dyn["tokens"]
+    assert parent[0] == -1 and all(0 <= parent[u] < u for u in range(1, N))
+    assert all(parent[u] >= parent[u - 1] for u in range(2, N))                  # breadth-first: children contiguous
+    depth = O.tree_depths(parent)
+    assert list(depth) == sorted(depth) and depth.max() <= TINY.draft_depths
+    kids = O.children_of(parent)
+    for u in range(N):
+        assert [int(rank[c]) for c in kids[u]] == sorted({int(rank[c]) for c in kids[u]})   # distinct, ascending
+        assert len({int(toks[c]) for c in kids[u]}) == len(kids[u])
+    sc = {n: dyn["cand_score"][c] for n, c in enumerate(dyn["keep"])}
+    assert all(sc[u] <= sc[int(parent[u])] + 1e-12 for u in range(1, N))         # a child never outscores its parent
+    # every kept candidate beats every candidate that was left out
+    left = [c for c in range(1, len(dyn["cand_token"])) if c not in set(dyn["keep"])]
+    assert min(sc[u] for u in range(1, N)) >= max(dyn["cand_score"][c] for c in left) - 1e-12
+    # follow mode reproduces the same tree from the recorded decisions
+    again = O.draft_tree_dynamic(W, cfg, O.SeqState(cfg), hid, nxt, topk=4, frontier=3, n_nodes=N,
+                                 follow=dict(tokens=dyn["cand_token"], frontier=dyn["frontier"], keep=dyn["keep"]))
+    np.testing.assert_array_equal(again["tokens"], toks)
+    np.testing.assert_array_equal(again["parent"], parent)
+
+
+def test_p11_dynamic_tree_is_lossless():
+    """Greedy speculative decoding with a dynamic tree per step emits the plain greedy text (Sec. 2.1)."""
+    ws, cfg, W = make(gain_jitter=0.0, max_seq=200)
+    prompt = synth.make_prompts(TINY, seed=9)[0][:24]
+    seq = O.SeqState(cfg)
+    acc, _ = O.prefill(W, cfg, seq, prompt, 16, [-1], [0])
+    emitted = [acc["new_tokens"][-1]]
+    seq.aug_L -= acc["m"]                             # the last chunk's rows are drafted again below (same values)
+    for step in range(6):
+        dyn = O.draft_tree_dynamic(W, cfg, seq, acc["hid_acc"], acc["next_tok"], topk=3, frontier=3, n_nodes=12)
+        hidden, logits = O.verify_tree(W, cfg, seq, dyn["tokens"], dyn["parent"])
+        acc = O.accept_and_compact(cfg, seq, dyn["tokens"], logits, hidden, dyn["parent"])
+        emitted.extend(acc["new_tokens"])
+        assert seq.aug_L == seq.L - acc["m"]          # the augmenting block catches up in the next draft call
+    ref, _ = O.plain_greedy(W, cfg, prompt, len(emitted))
+    assert emitted == ref
