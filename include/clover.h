@@ -130,6 +130,25 @@ int clover_reset(clover_ctx *ctx);
  * n_nodes <= max_nodes.  Synchronises the stream. */
 int clover_set_tree(clover_ctx *ctx, const clover_tree *tree);
 
+/* Dynamic (score-pruned) tree (Sec. 4.1: the tree is constructed from the draft's own probabilities).  After this
+ * call draft_tree chooses a new topology for every sequence and call, and verify_tree / accept_and_compact use
+ * it: a candidate's score is the sum of the draft log-probabilities along its root path; the root expands into
+ * its `topk` most probable tokens; at every depth 1 .. draft_depths-1 the `frontier` best candidates are expanded
+ * the same way; the n_nodes - 1 best of all candidates (score descending, shallower first, older first) and the
+ * root form the tree, numbered breadth-first.  Ties go to the lower token id / older candidate.  At most 256
+ * candidates (1 + topk + (draft_depths-1) * frontier * topk), topk <= 16, frontier <= 64.  clover_set_tree returns
+ * to a static tree.  Synchronises the stream. */
+int clover_set_dynamic_tree(clover_ctx *ctx, int32_t n_nodes, int32_t topk, int32_t frontier);
+
+/* Test helper (synchronises): the dynamic tree of sequence b as the last draft_tree left it.  HOST arrays:
+ * parent, rank, keep [n_nodes] (keep = candidate number of every tree node); cand_token, cand_score, cand_parent
+ * [256] (candidates in creation order: 0 = root, depth-1 candidates by rank, then per depth the children of the
+ * expanded candidates in (expansion order, rank) order); frontier [CLOVER_MAX_DEPTH * 64]: the candidates
+ * expanded at depth j, best first, at [j * 64 ...). */
+int clover_read_dynamic_tree(clover_ctx *ctx, int32_t b, int32_t *parent_out, int32_t *rank_out, int32_t *keep_out,
+                             int32_t *cand_token_out, float *cand_score_out, int32_t *cand_parent_out,
+                             int32_t *frontier_out);
+
 /* Draft head (Sec. 3; Sec. 3.1-3.3; Appendix A.3).  For every sequence b < batch with
  * m[b] >= 1: rows i < m[b] pair hid_acc[b,i] (target hidden state before the final norm) with
  * next_tok[b,i] (the token that followed it; the last is the new root).  AD1 and the Augmenting
@@ -198,7 +217,8 @@ int clover_set_seq_len(clover_ctx *ctx, const int32_t *len_host, const int32_t *
 /* Test helper: while dev_out is non-null every draft_tree also copies the draft logits it ranks (Sec. 3.2: the
  * shared LM head after FC_j) to dev_out, fp32: the rows of depth j start at batch * (number of internal nodes
  * shallower than j) * V, row (b, r) of that depth at ((b * n_j) + r) * V, r-th internal node of the depth in
- * index order.  Depths that would not fit capacity_floats are skipped.  null switches it off. */
+ * index order (dynamic tree: r-th expanded candidate of the depth, best first).  Depths that would not fit
+ * capacity_floats are skipped.  null switches it off. */
 int clover_capture_draft_logits(clover_ctx *ctx, float *dev_out, size_t capacity_floats);
 
 /* Per-kernel-class timing with HIP events on the library's stream.  While enabled, every launch

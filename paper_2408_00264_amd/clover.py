@@ -23,7 +23,7 @@ STATIC_SCRATCH_BYTES = 32 << 20
 EXPORTS = [
     "clover_workspace_bytes", "clover_init", "clover_destroy", "clover_reset", "clover_set_tree",
     "draft_tree", "verify_tree", "accept_and_compact", "clover_accept_forced", "clover_seq_len",
-    "clover_read_kv", "clover_write_kv", "clover_set_seq_len", "clover_capture_draft_logits", "clover_path_info", "clover_profile_enable", "clover_profile_collect", "clover_kernel_class_count",
+    "clover_read_kv", "clover_write_kv", "clover_set_seq_len", "clover_capture_draft_logits", "clover_set_dynamic_tree", "clover_read_dynamic_tree", "clover_path_info", "clover_profile_enable", "clover_profile_collect", "clover_kernel_class_count",
     "clover_kernel_class_name", "clover_last_error", "clover_last_global_error",
     "clover_op_gemm_scratch_bytes", "clover_op_gemm", "clover_op_gemm_static",
 ]
@@ -84,6 +84,8 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.clover_write_kv.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp]
     lib.clover_set_seq_len.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.clover_capture_draft_logits.argtypes = [vp, vp, C.c_size_t]
+    lib.clover_set_dynamic_tree.argtypes = [vp, i32, i32, i32]
+    lib.clover_read_dynamic_tree.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.clover_path_info.argtypes = [vp]
     lib.clover_profile_enable.argtypes = [vp, i32]
     lib.clover_profile_collect.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), i32]
@@ -276,6 +278,22 @@ class Clover:
         self._check(self.lib.clover_capture_draft_logits(self.ctx, self._p(self.draft_logits), self.draft_logits.numel()))
         return self.draft_logits
 
+    def set_dynamic_tree(self, n_nodes: int, topk: int, frontier: int) -> None:
+        self._check(self.lib.clover_set_dynamic_tree(self.ctx, n_nodes, topk, frontier))
+        self.n_nodes = n_nodes
+        self.dyn = (n_nodes, topk, frontier)
+
+    def read_dynamic_tree(self, b: int) -> dict:
+        n = self.dyn[0]
+        parent = np.zeros(n, np.int32); rank = np.zeros(n, np.int32); keep = np.zeros(n, np.int32)
+        ctok = np.zeros(256, np.int32); cscore = np.zeros(256, np.float32); cpar = np.zeros(256, np.int32)
+        front = np.zeros(8 * 64, np.int32)
+        self._check(self.lib.clover_read_dynamic_tree(self.ctx, b, parent.ctypes.data, rank.ctypes.data, keep.ctypes.data,
+                                                      ctok.ctypes.data, cscore.ctypes.data, cpar.ctypes.data,
+                                                      front.ctypes.data))
+        return dict(parent=parent, rank=rank, keep=keep, cand_token=ctok, cand_score=cscore, cand_parent=cpar,
+                    frontier=front.reshape(8, 64))
+
     def path_info(self) -> int:
         """Bit 0: MFMA path, bit 1: MFMA tree attention."""
         v = self.lib.clover_path_info(self.ctx)
@@ -294,7 +312,8 @@ class Clover:
         return {self.lib.clover_kernel_class_name(i).decode(): (ms[i], cnt[i]) for i in range(n)}
 
     # -- call sequences (no arithmetic here) -----------------------------------------------------
-    def prefill(self, prompts: List[np.ndarray], parent, rank, chunk: Optional[int] = None) -> None:
+    def prefill(self, prompts: List[np.ndarray], parent, rank, chunk: Optional[int] = None,
+                dynamic: Optional[tuple] = None) -> None:
         """Feed prompts as chain-shaped trees of at most `chunk` tokens per call; afterwards
         `tree_tokens` holds the first draft tree and m/hid_acc/next_tok the hand-off state.
         Ragged batches are right-aligned in chunk time: a shorter prompt starts in a later call
@@ -327,7 +346,10 @@ class Clover:
             self.verify_tree(B)
             self.accept_forced(B)
             if ci == n_chunks - 1:
-                self.set_tree(parent, rank)
+                if dynamic is not None:
+                    self.set_dynamic_tree(*dynamic)      # (n_nodes, topk, frontier): a new topology per draft call
+                else:
+                    self.set_tree(parent, rank)
             self.draft_tree(B)
 
     def step(self, batch: int) -> None:

@@ -102,6 +102,11 @@ struct clover_ctx {
   bool panel;              // full-K panel GEMM for the gate+up projection and the LM head
   int row_batch_max = 64;
   int row_batch = 64;      // rows per weight pass for passes of more than 64 rows: 128 when the panel kernel may take them  // passes of up to this many rows run through the <= 64-row GEMM kernels, in batches of 64
+  // dynamic (score-pruned) tree: candidates, frontiers and the per-sequence topology tables
+  bool dyn_on = false;
+  DynTree dyn{};
+  float *topk_vals, *topk_lse, *topk_aux;
+  float* dyn_state;        // [B][DYN_MAX_CAND][H] draft states of the expanded candidates
   float* draft_capture = nullptr;   // test hook: device buffer that receives every depth's draft logits
   size_t draft_capture_floats = 0;
   // host-side bounds
@@ -275,6 +280,21 @@ void carve(clover_ctx* x, char* base, size_t* total) {
   x->z = cv.take<float>((size_t)rows * c.vocab);
   x->cand = cv.take<unsigned long long>((size_t)rows * topk_chunks(c.vocab) * 16);
   x->topk_ids = cv.take<int>((size_t)rows * 16);
+  x->topk_vals = cv.take<float>((size_t)rows * 16);
+  x->topk_lse = cv.take<float>((size_t)rows);
+  x->topk_aux = cv.take<float>((size_t)rows * topk_chunks(c.vocab) * 2);
+  x->dyn.cand_tok = cv.take<int>((size_t)B * DYN_MAX_CAND);
+  x->dyn.cand_score = cv.take<float>((size_t)B * DYN_MAX_CAND);
+  x->dyn.cand_par = cv.take<int>((size_t)B * DYN_MAX_CAND);
+  x->dyn.frontier = cv.take<int>((size_t)B * CLOVER_MAX_DEPTH * DYN_MAX_FRONT);
+  x->dyn.t_parent = cv.take<int>((size_t)rows);
+  x->dyn.t_rank = cv.take<int>((size_t)rows);
+  x->dyn.t_depth = cv.take<int>((size_t)rows);
+  x->dyn.t_first_child = cv.take<int>((size_t)rows);
+  x->dyn.t_n_child = cv.take<int>((size_t)rows);
+  x->dyn.t_keep = cv.take<int>((size_t)rows);
+  x->dyn.t_anc = cv.take<unsigned long long>((size_t)rows * 2);
+  x->dyn_state = cv.take<float>((size_t)B * DYN_MAX_CAND * H);
   // MFMA path: is every GEMM shape of this model supported, and how large can an output with its
   // split-K partials get?
   size_t pbytes = 256;
@@ -467,7 +487,7 @@ void gemm_generic(clover_ctx* x, int cls, const float* X, int ldx, const void* W
 // hold RMSNorm(xres) * next_gain (skipped when next_gain is null).  Generic path: norms are computed here.
 void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMap rm, int M, char* kc_layer,
                char* vc_layer, const int* base_len, const unsigned long long* anc, const void* next_gain,
-               int key_bound) {
+               int key_bound, int anc_stride = 0 /* nodes per sequence in a per-sequence mask table */) {
   const clover_config& c = x->cfg;
   const int H = x->H, d = c.head_dim, F = c.ffn;
   const int sn[3] = {c.n_q_heads * d, c.n_kv_heads * d, c.n_kv_heads * d};
@@ -492,12 +512,12 @@ void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMa
         ap.k_hi = (const bf16_t*)kc_layer; ap.k_plane = x->k_layer_elems;
         ap.v_hi = (const bf16_t*)vc_layer; ap.v_plane = x->v_layer_elems;
         ap.max_seq = c.max_seq; ap.n_kv = c.n_kv_heads; ap.n_q = c.n_q_heads;
-        ap.base_len = base_len; ap.anc = anc; ap.rm = rm;
+        ap.base_len = base_len; ap.anc = anc; ap.anc_stride = anc_stride; ap.rm = rm;
         ap.o_part = x->o_part; ap.ml_part = x->ml_part; ap.rows_total = x->max_rows; ap.max_splits = x->attn_max_splits;
         launch_attn_mfma(ap, key_bound, O.hi, O.lo, x->NQD, x->st);
       } else {
         launch_attn_generic(x->q_rot, x->NQD, kc_layer, vc_layer, x->kvdtype, x->kv, base_len, anc, c.n_q_heads, nullptr,
-                            x->NQD, O.hi, O.lo, rm, x->st);
+                            x->NQD, O.hi, O.lo, rm, x->st, anc_stride);
       } }
     const int sw = gemm_fast1(x, KC_GEMM_WO, O, lw.wo, M, H, x->NQD);
     { Scope s(x, KC_RMSNORM);
@@ -552,7 +572,7 @@ void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMa
                          x->kv, base_len, c.n_q_heads, rm, x->d_err, nullptr, nullptr, 0.f, x->st); }
   { Scope s(x, KC_ATTN);
     launch_attn_generic(x->q_rot, x->NQD, kc_layer, vc_layer, x->kvdtype, x->kv, base_len, anc, c.n_q_heads, x->attn_out,
-                        x->NQD, nullptr, nullptr, rm, x->st); }
+                        x->NQD, nullptr, nullptr, rm, x->st, anc_stride); }
   gemm_generic(x, KC_GEMM_WO, x->attn_out, x->NQD, lw.wo, nullptr, xres, H, M, H, x->NQD, 1);
   { Scope s(x, KC_RMSNORM); launch_rmsnorm(xres, H, lw.ffn_norm, c.dtype, c.rms_eps, x->a_norm, H, H, M, x->st); }
   gemm_generic(x, KC_GEMM_GATEUP, x->a_norm, H, lw.w_gate, nullptr, x->tmp_ffn, F, M, F, H, 0);
@@ -625,7 +645,7 @@ void lm_head_fast(clover_ctx* x, Planes A, int rows, float* out) {
 }
 
 // logits of `rows` contiguous rows of g through the head norm and the shared LM head, then top-k
-void run_head(clover_ctx* x, const float* g, int rows, int k) {
+void run_head(clover_ctx* x, const float* g, int rows, int k /* 0: logits only, left in x->z */) {
   const clover_config& c = x->cfg;
   const int H = x->H;
   if (x->fast) {
@@ -635,7 +655,7 @@ void run_head(clover_ctx* x, const float* g, int rows, int k) {
     { Scope s(x, KC_RMSNORM); launch_rmsnorm(g, H, x->w.head_norm, c.dtype, c.rms_eps, x->a_norm, H, H, rows, x->st); }
     gemm_generic(x, KC_GEMM_LMHEAD, x->a_norm, H, x->w.lm_head, nullptr, x->z, c.vocab, rows, c.vocab, H, 0);
   }
-  { Scope s(x, KC_TOPK); launch_topk(x->z, c.vocab, c.vocab, rows, k, x->cand, x->topk_ids, x->st); }
+  if (k > 0) { Scope s(x, KC_TOPK); launch_topk(x->z, c.vocab, c.vocab, rows, k, x->cand, x->topk_ids, x->st); }
 }
 
 // Can draft_tree take the fused route for `rows` GEMM rows?  (K-slice GEMMs for every draft linear, at most 8 slices
@@ -676,9 +696,73 @@ void run_ad_fused(clover_ctx* x, const clover_ad_weights& ad, Planes A, Planes Y
 void capture_draft_logits(clover_ctx* x, int j, int rows) {
   if (!x->draft_capture) return;
   const size_t V = (size_t)x->cfg.vocab;
-  const size_t off = (size_t)(rows / std::max(1, x->tree.lvl_off[j + 1] - x->tree.lvl_off[j])) * x->tree.lvl_off[j] * V;
+  size_t off;
+  if (x->dyn_on) {   // rows of depth j start behind the rows of the shallower depths: batch * (F[0] + .. + F[j-1]) rows
+    int before = 0;
+    for (int i = 0; i < j; ++i) before += x->dyn.F[i];
+    off = (size_t)(rows / std::max(1, x->dyn.F[j])) * before * V;
+  } else {
+    off = (size_t)(rows / std::max(1, x->tree.lvl_off[j + 1] - x->tree.lvl_off[j])) * x->tree.lvl_off[j] * V;
+  }
   if (off + (size_t)rows * V > x->draft_capture_floats) return;
   hipMemcpyAsync(x->draft_capture + off, x->z, (size_t)rows * V * sizeof(float), hipMemcpyDeviceToDevice, x->st);
+}
+
+// Dynamic tree: expansion depth by depth (the root state and token are in candidate 0), then the selection.
+// Depth j expands F[j] candidates per sequence; their logits go through a log-softmax so that scores add up
+// along a path.
+void draft_expand_dynamic(clover_ctx* x, int B, const int* m, int* tree_tokens, bool fused, Planes A, Planes Y, Planes Cc) {
+  const clover_config& c = x->cfg;
+  const DynTree& t = x->dyn;
+  const int H = x->H, C = t.C, ns = CLOVER_MAX_DEPTH * DYN_MAX_FRONT;
+  for (int j = 0; j < t.D; ++j) {
+    const int n_lvl = t.F[j], rows = B * n_lvl;
+    const int* nodes = t.frontier + (size_t)j * DYN_MAX_FRONT;
+    if (fused) {
+      int sp;
+      if (j == 0) {
+        sp = gemm_fast1(x, KC_GEMM_DRAFT, Y, x->w.fc0_w, rows, H, H);
+      } else {
+        { Scope s(x, KC_DRAFT_MISC);
+          launch_draft_level(x->dyn_state, t.cand_tok, nodes, t.cand_par, n_lvl, B, C, H, x->w.lm_head, c.vocab,
+                             x->w.ad2.norm, c.rms_eps, A.hi, A.lo, Y.hi, Y.lo, Cc.hi, Cc.lo, x->st, ns, C); }
+        AdGateArgs g;
+        memset(&g, 0, sizeof(g));
+        g.x = x->dyn_state; g.ldx = H; g.out = x->dyn_state; g.ldo = H;
+        g.nodes = nodes; g.parent = t.cand_par; g.n_lvl = n_lvl; g.R = C; g.m = m;
+        g.nodes_stride = ns; g.parent_stride = C;
+        g.c_hi = Cc.hi; g.c_lo = Cc.lo; g.ldc = 2 * H;
+        run_ad_fused(x, x->w.ad2, A, Y, rows, g);
+        Planes C2 = Cc;
+        C2.ld = 2 * H;
+        sp = gemm_fast1(x, KC_GEMM_DRAFT, C2, x->fc_w[j], rows, H, 2 * H);
+      }
+      { Scope s(x, KC_RMSNORM);
+        launch_reduce_add_norm(x->d_g, H, x->partial, sp, (size_t)rows * H, H, x->w.head_norm, c.dtype, c.rms_eps, A.hi,
+                               A.lo, H, rows, H, x->st, j == 0 ? x->w.fc0_b : x->fc_b[j]); }
+      lm_head_fast(x, A, rows, x->z);
+    } else {
+      if (j == 0) {
+        run_fc(x, x->d_rootx, H, x->w.fc0_w, x->w.fc0_b, x->d_g, rows);
+      } else {
+        { Scope s(x, KC_DRAFT_MISC);
+          launch_draft_gather(x->dyn_state, t.cand_tok, nodes, t.cand_par, n_lvl, B, C, H, x->w.lm_head, c.dtype, c.vocab,
+                              x->d_xs, x->d_e, x->d_cat, x->st, ns, C); }
+        run_ad(x, x->w.ad2, x->d_xs, x->d_e, rows, x->d_s);
+        { Scope s(x, KC_DRAFT_MISC);
+          launch_draft_scatter_state(x->d_s, nodes, n_lvl, B, C, H, x->dyn_state, x->d_cat, x->st, ns); }
+        run_fc(x, x->d_cat, 2 * H, x->fc_w[j], x->fc_b[j], x->d_g, rows);
+      }
+      run_head(x, x->d_g, rows, 0);
+    }
+    capture_draft_logits(x, j, rows);
+    { Scope s(x, KC_TOPK);
+      launch_topk_lse(x->z, c.vocab, c.vocab, rows, t.topk, x->cand, x->topk_aux, x->topk_ids, x->topk_vals, x->topk_lse, x->st); }
+    { Scope s(x, KC_DRAFT_MISC);
+      launch_dyn_assign(t, j, B, x->topk_ids, x->topk_vals, x->topk_lse, m, x->st);
+      if (j + 1 < t.D) launch_dyn_frontier(t, j + 1, B, m, x->st); }
+  }
+  { Scope s(x, KC_DRAFT_MISC); launch_dyn_finalize(t, B, x->R, m, tree_tokens, x->st); }
 }
 
 int upload_tree(clover_ctx* x) {
@@ -717,11 +801,13 @@ int accept_common(clover_ctx* x, int batch, const int* tree_tokens, const float*
                   int* next_tok) {
   const clover_config& c = x->cfg;
   const TreeHost& t = x->tree;
-  const int R = x->R, M = (batch - 1) * R + t.n;
+  const int n_nodes = x->dyn_on ? x->dyn.N : t.n;
+  const int R = x->R, M = (batch - 1) * R + n_nodes;
   { Scope s(x, KC_TOPK); launch_topk(logits, c.vocab, c.vocab, M, 1, x->cand, x->topk_ids, x->st); }
   { Scope s(x, KC_ACCEPT);
-    launch_accept_walk(x->topk_ids, tree_tokens, x->d_first_child, x->d_n_child, t.n, batch, R, n_forced, forced_next,
-                       m, acc_idx, new_tokens, next_tok, x->st); }
+    launch_accept_walk(x->topk_ids, tree_tokens, x->dyn_on ? x->dyn.t_first_child : x->d_first_child,
+                       x->dyn_on ? x->dyn.t_n_child : x->d_n_child, n_nodes, batch, R, n_forced, forced_next,
+                       m, acc_idx, new_tokens, next_tok, x->st, x->dyn_on ? R : 0); }
   { Scope s(x, KC_COMPACT);
     launch_compact_kv(x->kc, x->vc, x->kvdtype, x->kv, c.n_layers, x->kv_layer_stride, x->kv_layer_stride, x->d_seq_len, m,
                       acc_idx, batch, R, x->st);
@@ -881,7 +967,60 @@ int clover_set_tree(clover_ctx* x, const clover_tree* tree) {
   hipError_t e = hipStreamSynchronize(x->st);  // kernels in flight still read the old tables
   if (e != hipSuccess) return fail(x, CLOVER_E_HIP, hipGetErrorString(e));
   x->tree = std::move(th);
+  x->dyn_on = false;
   return upload_tree(x);
+}
+
+int clover_set_dynamic_tree(clover_ctx* x, int32_t n_nodes, int32_t topk, int32_t frontier) {
+  if (!x) return CLOVER_E_NULL;
+  const clover_config& c = x->cfg;
+  if (n_nodes < 1 || n_nodes > c.max_nodes) return fail(x, CLOVER_E_TREE, "n_nodes outside [1, max_nodes]");
+  if (topk < 1 || topk > CLOVER_MAX_RANK) return fail(x, CLOVER_E_TREE, "topk outside [1, 16]");
+  if (frontier < 1 || frontier > DYN_MAX_FRONT || frontier > c.max_nodes)
+    return fail(x, CLOVER_E_TREE, "frontier outside [1, min(64, max_nodes)]");
+  DynTree t = x->dyn;   // keeps the workspace pointers
+  t.D = c.draft_depths; t.topk = topk; t.N = n_nodes;
+  t.off[0] = 0; t.off[1] = 1; t.F[0] = 1;
+  int n_cand = topk;                               // candidates of depth 1
+  for (int j = 1; j <= t.D; ++j) {
+    t.off[j + 1] = t.off[j] + n_cand;
+    if (n_cand > DYN_MAX_CAND) return fail(x, CLOVER_E_TREE, "more than 256 candidates in one depth");
+    t.F[j] = std::min(frontier, n_cand);
+    n_cand = t.F[j] * topk;
+  }
+  t.C = t.off[t.D + 1];
+  if (t.C > DYN_MAX_CAND) return fail(x, CLOVER_E_TREE, "more than 256 candidates: lower topk, frontier or draft_depths");
+  if (t.C < n_nodes) return fail(x, CLOVER_E_TREE, "fewer candidates than tree nodes");
+  hipError_t e = hipStreamSynchronize(x->st);  // kernels in flight still read the old tables
+  if (e != hipSuccess) return fail(x, CLOVER_E_HIP, hipGetErrorString(e));
+  x->dyn = t;
+  x->dyn_on = true;
+  return CLOVER_OK;
+}
+
+int clover_read_dynamic_tree(clover_ctx* x, int32_t b, int32_t* parent_out, int32_t* rank_out, int32_t* keep_out,
+                             int32_t* cand_token_out, float* cand_score_out, int32_t* cand_parent_out,
+                             int32_t* frontier_out) {
+  if (!x || !parent_out || !rank_out || !keep_out || !cand_token_out || !cand_score_out || !cand_parent_out || !frontier_out)
+    return fail(x, CLOVER_E_NULL, "null argument");
+  if (!x->dyn_on) return fail(x, CLOVER_E_TREE, "no dynamic tree is set");
+  if (b < 0 || b >= x->cfg.max_batch) return fail(x, CLOVER_E_SHAPE, "sequence index out of range");
+  const DynTree& t = x->dyn;
+  const size_t ro = (size_t)b * x->R, co = (size_t)b * t.C;
+  hipError_t e = hipSuccess;
+  auto down = [&](void* dst, const void* src, size_t bytes) {
+    if (e == hipSuccess) e = hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToHost, x->st);
+  };
+  down(parent_out, t.t_parent + ro, t.N * sizeof(int));
+  down(rank_out, t.t_rank + ro, t.N * sizeof(int));
+  down(keep_out, t.t_keep + ro, t.N * sizeof(int));
+  down(cand_token_out, t.cand_tok + co, t.C * sizeof(int));
+  down(cand_score_out, t.cand_score + co, t.C * sizeof(float));
+  down(cand_parent_out, t.cand_par + co, t.C * sizeof(int));
+  down(frontier_out, t.frontier + (size_t)b * CLOVER_MAX_DEPTH * DYN_MAX_FRONT, CLOVER_MAX_DEPTH * DYN_MAX_FRONT * sizeof(int));
+  if (e == hipSuccess) e = hipStreamSynchronize(x->st);
+  if (e != hipSuccess) return fail(x, CLOVER_E_HIP, std::string("clover_read_dynamic_tree: ") + hipGetErrorString(e));
+  return CLOVER_OK;
 }
 
 int draft_tree(clover_ctx* x, int32_t batch, const float* hid_acc, const int32_t* next_tok, const int32_t* m,
@@ -899,7 +1038,9 @@ int draft_tree(clover_ctx* x, int32_t batch, const float* hid_acc, const int32_t
   int aug_bound = 0;
   for (int b = 0; b < B; ++b) aug_bound = std::max(aug_bound, x->aug_ub[b] + n);
   int max_lvl_rows = B;
-  if (t.max_depth <= c.draft_depths)
+  if (x->dyn_on)
+    for (int j = 0; j < x->dyn.D; ++j) max_lvl_rows = std::max(max_lvl_rows, B * x->dyn.F[j]);
+  else if (t.max_depth <= c.draft_depths)
     for (int j = 0; j < t.max_depth; ++j) max_lvl_rows = std::max(max_lvl_rows, B * (t.lvl_off[j + 1] - t.lvl_off[j]));
   const bool fused = draft_fused_ok(x, M) && draft_fused_ok(x, max_lvl_rows);
   Planes A = planes_of(x, x->a_norm, 2 * H);
@@ -928,15 +1069,24 @@ int draft_tree(clover_ctx* x, int32_t batch, const float* hid_acc, const int32_t
     run_layer(x, x->aug[l], x->xd, rm, M, x->aug_kc + (size_t)l * x->k_layer_elems * x->kv_esz,
               x->aug_vc + (size_t)l * x->v_layer_elems * x->kv_esz, x->d_aug_len, x->d_anc_chain,
               l + 1 < c.aug_layers ? x->aug[l + 1].attn_norm : nullptr, aug_bound);
-  if (fused) {
+  {
+    // root state and token: node 0 of the static tree, candidate 0 of the dynamic one
+    float* root_state = x->dyn_on ? x->dyn_state : x->d_state;
+    int* root_tok = x->dyn_on ? x->dyn.cand_tok : tree_tokens;
+    const int Rs = x->dyn_on ? x->dyn.C : R;
     Scope s(x, KC_DRAFT_MISC);
-    launch_draft_root_fused(x->xd, next_tok, m, B, R, H, x->d_state, tree_tokens, Y.hi, Y.lo, x->d_aug_len, x->st);
-  } else {
-    Scope s(x, KC_DRAFT_MISC);
-    launch_draft_root(x->xd, next_tok, m, B, R, H, x->d_rootx, x->d_state, tree_tokens, x->st);
-    launch_add_len(x->d_aug_len, m, B, x->st);
+    if (fused) {
+      launch_draft_root_fused(x->xd, next_tok, m, B, R, H, root_state, root_tok, Y.hi, Y.lo, x->d_aug_len, x->st, Rs);
+    } else {
+      launch_draft_root(x->xd, next_tok, m, B, R, H, x->d_rootx, root_state, root_tok, x->st, Rs);
+      launch_add_len(x->d_aug_len, m, B, x->st);
+    }
   }
   for (int b = 0; b < B; ++b) x->aug_ub[b] += n;
+  if (x->dyn_on) {
+    draft_expand_dynamic(x, B, m, tree_tokens, fused, A, Y, Cc);
+    return finish(x, "draft_tree");
+  }
   // expansion, level by level; a tree deeper than the head (e.g. a prompt chain) is not expanded
   if (t.max_depth <= c.draft_depths) {
     for (int j = 0; j < t.max_depth; ++j) {
@@ -1015,19 +1165,25 @@ int verify_tree(clover_ctx* x, int32_t batch, const int32_t* tree_tokens, float*
   const clover_config& c = x->cfg;
   const TreeHost& t = x->tree;
   const int B = batch, R = x->R, H = x->H;
+  const int n_nodes = x->dyn_on ? x->dyn.N : t.n;
+  // topology tables: one static tree for all sequences, or the tables draft_tree wrote per sequence
+  const int* depth_tab = x->dyn_on ? x->dyn.t_depth : x->d_depth;
+  const unsigned long long* anc_tab = x->dyn_on ? x->dyn.t_anc : x->d_anc;
+  const int topo_stride = x->dyn_on ? R : 0;
   for (int b = 0; b < B; ++b)
-    if (x->len_ub[b] + t.n > c.max_seq) return fail(x, CLOVER_E_CAPACITY, "sequence could exceed max_seq (call clover_seq_len to refresh the bound)");
-  const RowMap rm{B, R, t.n, nullptr};
-  const int M = (B - 1) * R + t.n;
+    if (x->len_ub[b] + n_nodes > c.max_seq) return fail(x, CLOVER_E_CAPACITY, "sequence could exceed max_seq (call clover_seq_len to refresh the bound)");
+  const RowMap rm{B, R, n_nodes, nullptr};
+  const int M = (B - 1) * R + n_nodes;
   int key_bound = 0;
-  for (int b = 0; b < B; ++b) key_bound = std::max(key_bound, x->len_ub[b] + t.n);
+  for (int b = 0; b < B; ++b) key_bound = std::max(key_bound, x->len_ub[b] + n_nodes);
   { Scope s(x, KC_EMBED); launch_embed(x->w.embed, c.dtype, tree_tokens, c.vocab, hidden, H, H, rm, x->st); }
-  { Scope s(x, KC_ROPE_KV); launch_rope_table(x->d_seq_len, x->d_depth, c.rope_base, c.head_dim, x->cos_t, x->sin_t, rm, x->st); }
+  { Scope s(x, KC_ROPE_KV);
+    launch_rope_table(x->d_seq_len, depth_tab, c.rope_base, c.head_dim, x->cos_t, x->sin_t, rm, x->st, topo_stride); }
   if (x->fast) norm_planes(x, hidden, x->layers[0].attn_norm, M);
   for (int l = 0; l < c.n_layers; ++l)
     run_layer(x, x->layers[l], hidden, rm, M, x->kc + (size_t)l * x->k_layer_elems * x->kv_esz,
-              x->vc + (size_t)l * x->v_layer_elems * x->kv_esz, x->d_seq_len, x->d_anc,
-              l + 1 < c.n_layers ? x->layers[l + 1].attn_norm : x->w.final_norm, key_bound);
+              x->vc + (size_t)l * x->v_layer_elems * x->kv_esz, x->d_seq_len, anc_tab,
+              l + 1 < c.n_layers ? x->layers[l + 1].attn_norm : x->w.final_norm, key_bound, topo_stride);
   if (x->fast) {
     Planes A = planes_of(x, x->a_norm, 2 * H);
     A.ld = H;
@@ -1048,7 +1204,7 @@ int accept_and_compact(clover_ctx* x, int32_t batch, const int32_t* tree_tokens,
   if (rc) return rc;
   rc = accept_common(x, batch, tree_tokens, logits, hidden, nullptr, nullptr, m, acc_idx, new_tokens, hid_acc, next_tok);
   if (rc) return rc;
-  x->m_upper = std::min(x->tree.max_depth + 1, x->R);
+  x->m_upper = std::min((x->dyn_on ? x->dyn.D : x->tree.max_depth) + 1, x->R);
   for (int b = 0; b < batch; ++b) x->len_ub[b] += x->m_upper;
   return CLOVER_OK;
 }
@@ -1061,7 +1217,7 @@ int clover_accept_forced(clover_ctx* x, int32_t batch, const int32_t* tree_token
     return fail(x, CLOVER_E_NULL, "null argument");
   int rc = check_batch(x, batch);
   if (rc) return rc;
-  if (!x->tree.is_chain) return fail(x, CLOVER_E_TREE, "clover_accept_forced needs a chain-shaped tree");
+  if (x->dyn_on || !x->tree.is_chain) return fail(x, CLOVER_E_TREE, "clover_accept_forced needs a chain-shaped tree");
   rc = accept_common(x, batch, tree_tokens, logits, hidden, n_rows, forced_next, m, acc_idx, new_tokens, hid_acc, next_tok);
   if (rc) return rc;
   x->m_upper = x->tree.n;

@@ -6,6 +6,8 @@
 #include <stdint.h>
 #include <stddef.h>
 
+#include "../../include/clover.h"
+
 namespace clv {
 
 typedef unsigned short bf16_t;  // raw bfloat16 bit pattern
@@ -35,8 +37,9 @@ void launch_embed(const void* table, int wdtype, const int* tok, int vocab, floa
                   RowMap rm, hipStream_t st);
 void launch_rmsnorm(const float* x, int ldx, const void* gain, int wdtype, float eps, float* out, int ldo, int H,
                     int rows, hipStream_t st);
+// depth_stride: 0 when all sequences share one tree, else the per-sequence stride of the depth table
 void launch_rope_table(const int* base_len, const int* depth /*null: row index*/, float rope_base, int d,
-                       float* cos_t, float* sin_t, RowMap rm, hipStream_t st);
+                       float* cos_t, float* sin_t, RowMap rm, hipStream_t st, int depth_stride = 0);
 void launch_rope_kv_write(const float* qkv, int ldqkv, int qkv_splits, size_t qkv_split_stride, const float* cos_t, const float* sin_t, float* q_out, int ldq,
                           void* k_cache, void* v_cache, int kvdtype, KVLayout kv, const int* base_len, int n_q,
                           RowMap rm, int* err_flag, bf16_t* q_hi /*null: fp32 q_out*/, bf16_t* q_lo, float q_scale,
@@ -44,7 +47,7 @@ void launch_rope_kv_write(const float* qkv, int ldqkv, int qkv_splits, size_t qk
 void launch_attn_generic(const float* q, int ldq, const void* k_cache, const void* v_cache, int kvdtype, KVLayout kv,
                          const int* base_len, const unsigned long long* anc /*[n][2]*/, int n_q, float* out, int ldo,
                          bf16_t* out_hi, bf16_t* out_lo /*planes instead of fp32 when non-null*/, RowMap rm,
-                         hipStream_t st);
+                         hipStream_t st, int anc_stride = 0 /*nodes per sequence in a per-sequence mask table, 0: shared*/);
 // mode 0: Y = X W^T (+bias); mode 1: Y += X W^T (+bias)
 void launch_gemm_generic(const float* X, int ldx, const void* W, const void* bias, int wdtype, float* Y, int ldy,
                          int M, int N, int K, int mode, hipStream_t st);
@@ -61,15 +64,18 @@ void launch_topk(const float* z, int ldz, int V, int rows, int k, void* cand, in
 
 // ---- draft-tree bookkeeping -------------------------------------------------------------------
 // gather for level rows: row (b,r) <- node u = lvl_nodes[r]; xs = state[b][parent(u)], e = lm_head[token[b][u]]
+// (nodes_stride / parent_stride: per-sequence strides of the index tables, 0 when all sequences share them)
 void launch_draft_gather(const float* state, const int* tokens, const int* lvl_nodes, const int* parent, int n_lvl,
                          int B, int R, int H, const void* lm_head, int wdtype, int vocab, float* xs, float* e,
-                         float* cat /*[rows,2H], second half <- e*/, hipStream_t st);
+                         float* cat /*[rows,2H], second half <- e*/, hipStream_t st, int nodes_stride = 0,
+                         int parent_stride = 0);
 // state[b][u] <- s rows (also first half of cat)
 void launch_draft_scatter_state(const float* s, const int* lvl_nodes, int n_lvl, int B, int R, int H, float* state,
-                                float* cat, hipStream_t st);
+                                float* cat, hipStream_t st, int nodes_stride = 0);
 // root rows: xs_root[b] = a[b][m[b]-1]; state[b][0] = same; tokens[b][0] = next_tok[b][m[b]-1]
+// (Rs: row stride of state and tokens when it differs from R, the stride of a and next_tok)
 void launch_draft_root(const float* a, const int* next_tok, const int* m, int B, int R, int H, float* root_x,
-                       float* state, int* tokens, hipStream_t st);
+                       float* state, int* tokens, hipStream_t st, int Rs = 0);
 // tokens[b][c] = ids[(b*n_par + par_row[c])*16 + rank[c]] for children c in [c0,c1); skipped when m[b] < 1
 void launch_draft_assign(const int* ids, const int* par_row, const int* rank, int c0, int c1, int n_par, int B, int R,
                          const int* m, int* tokens, hipStream_t st);
@@ -78,7 +84,7 @@ void launch_add_len(int* len, const int* m, int B, hipStream_t st);
 // ---- accept / compact -------------------------------------------------------------------------
 void launch_accept_walk(const int* argmax, const int* tokens, const int* first_child, const int* n_child, int n_nodes,
                         int B, int R, const int* n_forced, const int* forced_next, int* m, int* acc_idx,
-                        int* new_tokens, int* next_tok, hipStream_t st);
+                        int* new_tokens, int* next_tok, hipStream_t st, int child_stride = 0);
 void launch_compact_kv(void* k_cache, void* v_cache, int kvdtype, KVLayout kv, int n_layers, size_t k_layer_elems,
                        size_t v_layer_elems, const int* len, const int* m, const int* acc_idx, int B, int R,
                        hipStream_t st);
@@ -131,6 +137,7 @@ struct AttnParams {
   int max_seq, n_kv, n_q;
   const int* base_len;                   // dev [B]
   const unsigned long long* anc;         // dev [n][2]
+  int anc_stride;                        // nodes per sequence in a per-sequence mask table, 0: one table for all
   RowMap rm;
   float* o_part;                         // [max_splits][rows_total][n_q][128]
   float* ml_part;                        // [max_splits][rows_total][n_q][2]
@@ -194,6 +201,7 @@ struct AdGateArgs {
   const void *bq, *bk, *bv;                   // bf16 [H]
   int H, heads;
   const int *nodes, *parent; int n_lvl, R;    // nodes null: row g -> row g; else g = b*n_lvl + r, u = nodes[r]: row b*R+parent[u] -> row b*R+u
+  int nodes_stride, parent_stride;            // per-sequence strides of nodes / parent (0: shared by all sequences)
   const int* m;                               // with nodes: sequences with m[b] < 1 are skipped (null: none)
   float* out; int ldo;
   const void* gain; float eps; bf16_t *n_hi, *n_lo;   // gain non-null: planes of RMSNorm(result)*gain, row g, ld H
@@ -203,12 +211,34 @@ bool ad_gate_fused_supported(int H, int heads);
 void launch_ad_gate_fused(const AdGateArgs& a, int rows, hipStream_t st);
 // root state/token from the last accepted row, its planes (row b, ld H), aug_len[b] += m[b]
 void launch_draft_root_fused(const float* a, const int* next_tok, const int* m, int B, int R, int H, float* state,
-                             int* tokens, bf16_t* y_hi, bf16_t* y_lo, int* aug_len, hipStream_t st);
+                             int* tokens, bf16_t* y_hi, bf16_t* y_lo, int* aug_len, hipStream_t st, int Rs = 0);
 // per internal node r of one depth (u = nodes[r]): planes of RMSNorm(state[parent(u)]) * gain (row b*n_lvl + r, ld H),
 // planes of the embedding of tokens[u] in (y_hi, y_lo) (ld H) and in the second half of (c_hi, c_lo) (ld 2H)
 void launch_draft_level(const float* state, const int* tokens, const int* nodes, const int* parent, int n_lvl, int B,
                         int R, int H, const void* table, int vocab, const void* gain, float eps, bf16_t* a_hi,
-                        bf16_t* a_lo, bf16_t* y_hi, bf16_t* y_lo, bf16_t* c_hi, bf16_t* c_lo, hipStream_t st);
+                        bf16_t* a_lo, bf16_t* y_hi, bf16_t* y_lo, bf16_t* c_hi, bf16_t* c_lo, hipStream_t st,
+                        int nodes_stride = 0, int parent_stride = 0);
+
+// ---- dynamic (score-pruned) draft tree ----------------------------------------------------------
+constexpr int DYN_MAX_CAND = 256;    // candidates per sequence, the root included
+constexpr int DYN_MAX_FRONT = 64;    // candidates expanded per depth
+struct DynTree {
+  int C, D, topk, N;                       // candidates, depths, children per expansion, tree nodes
+  int off[CLOVER_MAX_DEPTH + 2];           // candidates of depth j are [off[j], off[j + 1])
+  int F[CLOVER_MAX_DEPTH + 1];             // candidates expanded at depth j (F[0] = 1: the root)
+  int* cand_tok; float* cand_score; int* cand_par;   // dev [B][C]
+  int* frontier;                           // dev [B][CLOVER_MAX_DEPTH][DYN_MAX_FRONT]: expanded candidates, best first
+  int *t_parent, *t_rank, *t_depth, *t_first_child, *t_n_child, *t_keep;   // dev [B][R]: the tree as verified
+  unsigned long long* t_anc;               // dev [B][R][2]
+};
+// per row of z[rows, V]: ids and values of the k best entries (value descending, id ascending) and the row's
+// log-sum-exp.  cand: [rows][chunks][16] 64-bit keys, aux: [rows][chunks][2] floats, chunks = ceil(V / 2048)
+void launch_topk_lse(const float* z, int ldz, int V, int rows, int k, void* cand, float* aux, int* out_ids,
+                     float* out_vals, float* out_lse, hipStream_t st);
+void launch_dyn_assign(const DynTree& t, int j, int B, const int* ids, const float* vals, const float* lse, const int* m,
+                       hipStream_t st);
+void launch_dyn_frontier(const DynTree& t, int j, int B, const int* m, hipStream_t st);
+void launch_dyn_finalize(const DynTree& t, int B, int R, const int* m, int* tree_tokens, hipStream_t st);
 
 // ---- tuning knobs -------------------------------------------------------------------------------
 // The shipped library reads no environment variable: every knob is its default.  A build with

@@ -111,8 +111,8 @@ __global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
   for (int mb = 0; mb < AT_MB; ++mb) {
     const int node = ng * 32 + nsub + mb * 16 + l16;
     const bool ok = node < nv;
-    a0[mb] = ok ? p.anc[2 * node] : 0ull;
-    a1[mb] = ok ? p.anc[2 * node + 1] : 0ull;
+    a0[mb] = ok ? p.anc[2 * ((size_t)b * p.anc_stride + node)] : 0ull;
+    a1[mb] = ok ? p.anc[2 * ((size_t)b * p.anc_stride + node) + 1] : 0ull;
     const size_t qo = ((size_t)b * rm.R + (ok ? node : 0)) * p.ldq + head * AT_D + g4 * 8;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {

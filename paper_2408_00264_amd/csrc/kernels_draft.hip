@@ -103,6 +103,7 @@ struct AdGate {
   const bf16_t *bq, *bk, *bv;
   int H, heads;
   const int *nodes, *parent; int n_lvl, R;
+  int nodes_stride, parent_stride;
   const int* m;
   float* out; int ldo;
   const bf16_t* gain; float eps;
@@ -120,9 +121,9 @@ __global__ __launch_bounds__(512) void ad_gate_fused_kernel(AdGate p) {
   const int g = blockIdx.x;
   size_t xin = g, xout = g;
   if (p.nodes) {
-    const int r = g % p.n_lvl, b = g / p.n_lvl, u = p.nodes[r];
+    const int r = g % p.n_lvl, b = g / p.n_lvl, u = p.nodes[(size_t)b * p.nodes_stride + r];
     if (p.m && p.m[b] < 1) return;  // whole block
-    xin = (size_t)b * p.R + p.parent[u];
+    xin = (size_t)b * p.R + p.parent[(size_t)b * p.parent_stride + u];
     xout = (size_t)b * p.R + u;
   }
   const int H = p.H, lanes_per_head = H / p.heads / 4;  // power of two, <= 64
@@ -186,17 +187,18 @@ __global__ __launch_bounds__(512) void ad_gate_fused_kernel(AdGate p) {
 __global__ __launch_bounds__(256) void draft_root_fused_kernel(const float* __restrict__ a, const int* __restrict__ next_tok,
                                                                const int* __restrict__ m, int R, int H,
                                                                float* __restrict__ state, int* __restrict__ tokens,
-                                                               bf16_t* y_hi, bf16_t* y_lo, int* __restrict__ aug_len) {
+                                                               bf16_t* y_hi, bf16_t* y_lo, int* __restrict__ aug_len,
+                                                               int Rs) {
   const int b = blockIdx.x;
   const int mb = min(m[b], R);
   for (int c = threadIdx.x * 4; c < H; c += 1024) {
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
     if (mb >= 1) v = *(const float4*)(a + ((size_t)b * R + mb - 1) * H + c);
-    *(float4*)(state + ((size_t)b * R) * H + c) = v;
+    *(float4*)(state + ((size_t)b * Rs) * H + c) = v;
     store_planes4(y_hi, y_lo, (size_t)b * H + c, v.x, v.y, v.z, v.w);
   }
   if (threadIdx.x == 0) {
-    if (mb >= 1) tokens[(size_t)b * R] = next_tok[(size_t)b * R + mb - 1];
+    if (mb >= 1) tokens[(size_t)b * Rs] = next_tok[(size_t)b * R + mb - 1];
     aug_len[b] += max(m[b], 0);
   }
 }
@@ -207,10 +209,11 @@ __global__ __launch_bounds__(256) void draft_level_kernel(const float* __restric
                                                           int n_lvl, int R, int H, const bf16_t* __restrict__ table,
                                                           int vocab, const bf16_t* __restrict__ gain, float eps,
                                                           bf16_t* a_hi, bf16_t* a_lo, bf16_t* y_hi, bf16_t* y_lo,
-                                                          bf16_t* c_hi, bf16_t* c_lo) {
+                                                          bf16_t* c_hi, bf16_t* c_lo, int nodes_stride,
+                                                          int parent_stride) {
   __shared__ float red[4];
   const int r = blockIdx.x, b = blockIdx.y;
-  const int u = nodes[r], p = parent[u];
+  const int u = nodes[(size_t)b * nodes_stride + r], p = parent[(size_t)b * parent_stride + u];
   int t = tokens[(size_t)b * R + u];
   t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);
   const size_t row = (size_t)b * n_lvl + r;
@@ -243,6 +246,7 @@ void launch_ad_gate_fused(const AdGateArgs& a, int rows, hipStream_t st) {
   p.bq = (const bf16_t*)a.bq; p.bk = (const bf16_t*)a.bk; p.bv = (const bf16_t*)a.bv;
   p.H = a.H; p.heads = a.heads;
   p.nodes = a.nodes; p.parent = a.parent; p.n_lvl = a.n_lvl; p.R = a.R; p.m = a.m;
+  p.nodes_stride = a.nodes_stride; p.parent_stride = a.parent_stride;
   p.out = a.out; p.ldo = a.ldo;
   p.gain = (const bf16_t*)a.gain; p.eps = a.eps; p.n_hi = a.n_hi; p.n_lo = a.n_lo;
   p.c_hi = a.c_hi; p.c_lo = a.c_lo; p.ldc = a.ldc;
@@ -250,16 +254,18 @@ void launch_ad_gate_fused(const AdGateArgs& a, int rows, hipStream_t st) {
 }
 
 void launch_draft_root_fused(const float* a, const int* next_tok, const int* m, int B, int R, int H, float* state,
-                             int* tokens, bf16_t* y_hi, bf16_t* y_lo, int* aug_len, hipStream_t st) {
-  draft_root_fused_kernel<<<B, 256, 0, st>>>(a, next_tok, m, R, H, state, tokens, y_hi, y_lo, aug_len);
+                             int* tokens, bf16_t* y_hi, bf16_t* y_lo, int* aug_len, hipStream_t st, int Rs) {
+  draft_root_fused_kernel<<<B, 256, 0, st>>>(a, next_tok, m, R, H, state, tokens, y_hi, y_lo, aug_len, Rs ? Rs : R);
 }
 
 void launch_draft_level(const float* state, const int* tokens, const int* nodes, const int* parent, int n_lvl, int B,
                         int R, int H, const void* table, int vocab, const void* gain, float eps, bf16_t* a_hi,
-                        bf16_t* a_lo, bf16_t* y_hi, bf16_t* y_lo, bf16_t* c_hi, bf16_t* c_lo, hipStream_t st) {
+                        bf16_t* a_lo, bf16_t* y_hi, bf16_t* y_lo, bf16_t* c_hi, bf16_t* c_lo, hipStream_t st,
+                        int nodes_stride, int parent_stride) {
   if (n_lvl <= 0) return;
   draft_level_kernel<<<dim3(n_lvl, B), 256, 0, st>>>(state, tokens, nodes, parent, n_lvl, R, H, (const bf16_t*)table, vocab,
-                                                     (const bf16_t*)gain, eps, a_hi, a_lo, y_hi, y_lo, c_hi, c_lo);
+                                                     (const bf16_t*)gain, eps, a_hi, a_lo, y_hi, y_lo, c_hi, c_lo,
+                                                     nodes_stride, parent_stride);
 }
 
 }  // namespace clv

@@ -115,10 +115,11 @@ void launch_rmsnorm(const float* x, int ldx, const void* gain, int wdtype, float
 // rotary tables: row (b,i) sits at position base_len[b] + (depth ? depth[i] : i)
 // ------------------------------------------------------------------------------------------
 __global__ void rope_table_kernel(const int* __restrict__ base_len, const int* __restrict__ depth, float rope_base,
-                                  int d, float* __restrict__ cos_t, float* __restrict__ sin_t, RowMap rm) {
+                                  int d, float* __restrict__ cos_t, float* __restrict__ sin_t, RowMap rm,
+                                  int depth_stride) {
   const int b = blockIdx.y, i = blockIdx.x, half = d / 2;
   const size_t row = (size_t)b * rm.R + i;
-  const int pos = base_len[b] + (depth ? depth[i] : i);
+  const int pos = base_len[b] + (depth ? depth[(size_t)b * depth_stride + i] : i);
   for (int c = threadIdx.x; c < half; c += blockDim.x) {
     const double inv = pow((double)rope_base, -2.0 * (double)c / (double)d);
     const double ang = (double)pos * inv;
@@ -128,9 +129,9 @@ __global__ void rope_table_kernel(const int* __restrict__ base_len, const int* _
 }
 
 void launch_rope_table(const int* base_len, const int* depth, float rope_base, int d, float* cos_t, float* sin_t,
-                       RowMap rm, hipStream_t st) {
+                       RowMap rm, hipStream_t st, int depth_stride) {
   dim3 grid(rm.n, rm.B);
-  rope_table_kernel<<<grid, 64, 0, st>>>(base_len, depth, rope_base, d, cos_t, sin_t, rm);
+  rope_table_kernel<<<grid, 64, 0, st>>>(base_len, depth, rope_base, d, cos_t, sin_t, rm, depth_stride);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -332,7 +333,8 @@ template <typename KT>
 __global__ void attn_generic_kernel(const float* __restrict__ q, int ldq, const KT* __restrict__ kc,
                                     const KT* __restrict__ vc, KVLayout kv, const int* __restrict__ base_len,
                                     const unsigned long long* __restrict__ anc, int n_q, float* __restrict__ out,
-                                    int ldo, bf16_t* __restrict__ out_hi, bf16_t* __restrict__ out_lo, RowMap rm) {
+                                    int ldo, bf16_t* __restrict__ out_hi, bf16_t* __restrict__ out_lo, RowMap rm,
+                                    int anc_stride) {
   __shared__ float qs[128];
   __shared__ float ps[64];
   const int h = blockIdx.x, i = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
@@ -342,7 +344,7 @@ __global__ void attn_generic_kernel(const float* __restrict__ q, int ldq, const 
   const int L = base_len[b];
   if (L + nv > kv.max_seq) return;
   const size_t row = (size_t)b * rm.R + i;
-  const unsigned long long a0 = anc[2 * i], a1 = anc[2 * i + 1];
+  const unsigned long long a0 = anc[2 * ((size_t)b * anc_stride + i)], a1 = anc[2 * ((size_t)b * anc_stride + i) + 1];
   const int g = h / (n_q / n_kv);
   const float scale = 1.0f / sqrtf((float)d);
   for (int c = lane; c < d; c += 64) qs[c] = q[row * ldq + h * d + c] * scale;
@@ -404,14 +406,14 @@ __global__ void attn_generic_kernel(const float* __restrict__ q, int ldq, const 
 
 void launch_attn_generic(const float* q, int ldq, const void* k_cache, const void* v_cache, int kvdtype, KVLayout kv,
                          const int* base_len, const unsigned long long* anc, int n_q, float* out, int ldo,
-                         bf16_t* out_hi, bf16_t* out_lo, RowMap rm, hipStream_t st) {
+                         bf16_t* out_hi, bf16_t* out_lo, RowMap rm, hipStream_t st, int anc_stride) {
   dim3 grid(n_q, rm.n, rm.B);
   if (kvdtype == 0)
     attn_generic_kernel<float><<<grid, 64, 0, st>>>(q, ldq, (const float*)k_cache, (const float*)v_cache, kv, base_len,
-                                                    anc, n_q, out, ldo, out_hi, out_lo, rm);
+                                                    anc, n_q, out, ldo, out_hi, out_lo, rm, anc_stride);
   else
     attn_generic_kernel<bf16_t><<<grid, 64, 0, st>>>(q, ldq, (const bf16_t*)k_cache, (const bf16_t*)v_cache, kv,
-                                                     base_len, anc, n_q, out, ldo, out_hi, out_lo, rm);
+                                                     base_len, anc, n_q, out, ldo, out_hi, out_lo, rm, anc_stride);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -621,9 +623,9 @@ template <typename WT>
 __global__ void draft_gather_kernel(const float* __restrict__ state, const int* __restrict__ tokens,
                                     const int* __restrict__ lvl_nodes, const int* __restrict__ parent, int n_lvl,
                                     int R, int H, const WT* __restrict__ lm_head, int vocab, float* __restrict__ xs,
-                                    float* __restrict__ e, float* __restrict__ cat) {
+                                    float* __restrict__ e, float* __restrict__ cat, int nodes_stride, int parent_stride) {
   const int r = blockIdx.x, b = blockIdx.y;
-  const int u = lvl_nodes[r], p = parent[u];
+  const int u = lvl_nodes[(size_t)b * nodes_stride + r], p = parent[(size_t)b * parent_stride + u];
   int t = tokens[(size_t)b * R + u];
   t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);
   const size_t row = (size_t)b * n_lvl + r;
@@ -636,21 +638,22 @@ __global__ void draft_gather_kernel(const float* __restrict__ state, const int* 
 }
 void launch_draft_gather(const float* state, const int* tokens, const int* lvl_nodes, const int* parent, int n_lvl,
                          int B, int R, int H, const void* lm_head, int wdtype, int vocab, float* xs, float* e,
-                         float* cat, hipStream_t st) {
+                         float* cat, hipStream_t st, int nodes_stride, int parent_stride) {
   if (n_lvl <= 0) return;
   dim3 grid(n_lvl, B);
   if (wdtype == 0)
     draft_gather_kernel<float><<<grid, 256, 0, st>>>(state, tokens, lvl_nodes, parent, n_lvl, R, H,
-                                                     (const float*)lm_head, vocab, xs, e, cat);
+                                                     (const float*)lm_head, vocab, xs, e, cat, nodes_stride, parent_stride);
   else
     draft_gather_kernel<bf16_t><<<grid, 256, 0, st>>>(state, tokens, lvl_nodes, parent, n_lvl, R, H,
-                                                      (const bf16_t*)lm_head, vocab, xs, e, cat);
+                                                      (const bf16_t*)lm_head, vocab, xs, e, cat, nodes_stride, parent_stride);
 }
 
 __global__ void draft_scatter_state_kernel(const float* __restrict__ s, const int* __restrict__ lvl_nodes, int n_lvl,
-                                           int R, int H, float* __restrict__ state, float* __restrict__ cat) {
+                                           int R, int H, float* __restrict__ state, float* __restrict__ cat,
+                                           int nodes_stride) {
   const int r = blockIdx.x, b = blockIdx.y;
-  const int u = lvl_nodes[r];
+  const int u = lvl_nodes[(size_t)b * nodes_stride + r];
   const size_t row = (size_t)b * n_lvl + r;
   for (int c = threadIdx.x; c < H; c += blockDim.x) {
     const float v = s[row * H + c];
@@ -659,26 +662,26 @@ __global__ void draft_scatter_state_kernel(const float* __restrict__ s, const in
   }
 }
 void launch_draft_scatter_state(const float* s, const int* lvl_nodes, int n_lvl, int B, int R, int H, float* state,
-                                float* cat, hipStream_t st) {
+                                float* cat, hipStream_t st, int nodes_stride) {
   if (n_lvl <= 0) return;
-  draft_scatter_state_kernel<<<dim3(n_lvl, B), 256, 0, st>>>(s, lvl_nodes, n_lvl, R, H, state, cat);
+  draft_scatter_state_kernel<<<dim3(n_lvl, B), 256, 0, st>>>(s, lvl_nodes, n_lvl, R, H, state, cat, nodes_stride);
 }
 
 __global__ void draft_root_kernel(const float* __restrict__ a, const int* __restrict__ next_tok,
                                   const int* __restrict__ m, int R, int H, float* __restrict__ root_x,
-                                  float* __restrict__ state, int* __restrict__ tokens) {
+                                  float* __restrict__ state, int* __restrict__ tokens, int Rs) {
   const int b = blockIdx.x;
   const int mb = min(m[b], R);
   for (int c = threadIdx.x; c < H; c += blockDim.x) {
     const float v = mb >= 1 ? a[((size_t)b * R + mb - 1) * H + c] : 0.f;
     root_x[(size_t)b * H + c] = v;
-    state[((size_t)b * R) * H + c] = v;
+    state[((size_t)b * Rs) * H + c] = v;
   }
-  if (threadIdx.x == 0 && mb >= 1) tokens[(size_t)b * R] = next_tok[(size_t)b * R + mb - 1];
+  if (threadIdx.x == 0 && mb >= 1) tokens[(size_t)b * Rs] = next_tok[(size_t)b * R + mb - 1];
 }
 void launch_draft_root(const float* a, const int* next_tok, const int* m, int B, int R, int H, float* root_x,
-                       float* state, int* tokens, hipStream_t st) {
-  draft_root_kernel<<<B, 256, 0, st>>>(a, next_tok, m, R, H, root_x, state, tokens);
+                       float* state, int* tokens, hipStream_t st, int Rs) {
+  draft_root_kernel<<<B, 256, 0, st>>>(a, next_tok, m, R, H, root_x, state, tokens, Rs ? Rs : R);
 }
 
 __global__ void draft_assign_kernel(const int* __restrict__ ids, const int* __restrict__ par_row,
@@ -717,10 +720,12 @@ __global__ void accept_walk_kernel(const int* __restrict__ argmax, const int* __
                                    int B, int R, const int* __restrict__ n_forced,
                                    const int* __restrict__ forced_next, int* __restrict__ m,
                                    int* __restrict__ acc_idx, int* __restrict__ new_tokens,
-                                   int* __restrict__ next_tok) {
+                                   int* __restrict__ next_tok, int child_stride) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= B) return;
   const size_t o = (size_t)b * R;
+  first_child += (size_t)b * child_stride;
+  n_child += (size_t)b * child_stride;
   int len, bonus;
   if (n_forced) {
     len = min(max(n_forced[b], 0), n_nodes);
@@ -755,9 +760,9 @@ __global__ void accept_walk_kernel(const int* __restrict__ argmax, const int* __
 }
 void launch_accept_walk(const int* argmax, const int* tokens, const int* first_child, const int* n_child, int n_nodes,
                         int B, int R, const int* n_forced, const int* forced_next, int* m, int* acc_idx,
-                        int* new_tokens, int* next_tok, hipStream_t st) {
+                        int* new_tokens, int* next_tok, hipStream_t st, int child_stride) {
   accept_walk_kernel<<<(B + 63) / 64, 64, 0, st>>>(argmax, tokens, first_child, n_child, n_nodes, B, R, n_forced,
-                                                   forced_next, m, acc_idx, new_tokens, next_tok);
+                                                   forced_next, m, acc_idx, new_tokens, next_tok, child_stride);
 }
 
 // ------------------------------------------------------------------------------------------

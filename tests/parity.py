@@ -40,8 +40,9 @@ def bfs_tree_random(rng, n, max_depth, max_kids=4):
 class Lockstep:
     def __init__(self, shape, parent, rank, max_seq: int, flags: int = 0, gain_jitter: float = 0.0,
                  oracle_dtype=np.float64, max_nodes: Optional[int] = None, batch: int = 1,
-                 overrides: Optional[Dict[str, np.ndarray]] = None):
+                 overrides: Optional[Dict[str, np.ndarray]] = None, dynamic: Optional[tuple] = None):
         self.shape = shape
+        self.dyn = dynamic                  # (n_nodes, topk, frontier): score-pruned tree, new topology per draft call
         self.parent = np.asarray(parent, np.int32)
         self.rank = np.asarray(rank, np.int32)
         self.tol = 3e-2 if shape.bf16 else 1e-4
@@ -53,6 +54,8 @@ class Lockstep:
         self.dev_w = clover.upload_weights(self.store)
         self.gpu = clover.Clover(shape, self.dev_w, self.parent, self.rank, batch, max_seq, self.R, flags)
         self.seqs = [O.SeqState(self.ocfg) for _ in range(batch)]
+        self.parents = [self.parent for _ in range(batch)]      # topology per sequence (differs with a dynamic tree)
+        self.score_tol = 5e-3 if shape.bf16 else 1e-4           # cumulative draft log-probabilities (up to D terms)
         self.acc: List[dict] = [None] * batch
         self.tie_events = 0
         self.max_logit_err = 0.0
@@ -66,9 +69,15 @@ class Lockstep:
         self.hidden_atol = 1e-2 if shape.bf16 else 1e-4
         self.gpu.capture_draft_logits(True)
 
+    @property
+    def n_nodes(self) -> int:
+        return self.dyn[0] if self.dyn is not None else len(self.parent)
+
     # ------------------------------------------------------------------------------------
     def _check_draft(self, b: int, gpu_tokens: np.ndarray, parent, rank) -> None:
         """Oracle draft for sequence b on the oracle's own hand-off state, following the GPU's tokens."""
+        if self.dyn is not None:
+            return self._check_draft_dynamic(b, gpu_tokens)
         acc = self.acc[b]
         toks, zs = O.draft_tree(self.W, self.ocfg, self.seqs[b], acc["hid_acc"], acc["next_tok"], parent, rank,
                                 forced_tokens=gpu_tokens)
@@ -105,9 +114,81 @@ class Lockstep:
                                              f"{int(gpu_tokens[c])} vs oracle {want}, oracle logit gap {gap:.3e}")
                     self.tie_events += 1
 
+    def _check_draft_dynamic(self, b: int, gpu_tokens: np.ndarray) -> None:
+        """Dynamic tree: the oracle follows the GPU's decisions (candidate tokens, expanded candidates, kept set)
+        and every decision must be (near-)optimal under the ORACLE's logits and scores; the breadth-first
+        numbering that follows from the kept set must be identical."""
+        n_nodes, topk, front = self.dyn
+        gt = self.gpu.read_dynamic_tree(b)
+        D = self.shape.draft_depths
+        F, n_cand = [1], topk
+        for j in range(1, D):
+            F.append(min(front, n_cand)); n_cand = F[-1] * topk
+        C = 1 + topk + sum(F[j] * topk for j in range(1, D))
+        follow = dict(tokens=[int(t) for t in gt["cand_token"][:C]],
+                      frontier=[[int(c) for c in gt["frontier"][j][:F[j]]] for j in range(1, D)],
+                      keep=[int(c) for c in gt["keep"]])
+        acc = self.acc[b]
+        assert follow["tokens"][0] == int(acc["next_tok"][-1]) == int(gpu_tokens[0]), "root token"
+        dyn = O.draft_tree_dynamic(self.W, self.ocfg, self.seqs[b], acc["hid_acc"], acc["next_tok"], topk, front, n_nodes,
+                                   follow=follow)
+        score = np.asarray(dyn["cand_score"]); par = np.asarray(dyn["cand_parent"]); dep = np.asarray(dyn["cand_depth"])
+        # (1) tokens of every expansion against the oracle's ranking of that candidate's logits (tie zone allowed)
+        for c, z in dyn["logits"].items():
+            kids = [k for k in range(C) if par[k] == c and k != 0]
+            got = [follow["tokens"][k] for k in kids]
+            assert len(set(got)) == len(got) == topk, f"candidate {c}: children {got}"
+            top = O.ranked_ids(z, topk)
+            for i, k in enumerate(kids):
+                if got[i] != int(top[i]):
+                    gap = abs(float(z[int(top[i])]) - float(z[got[i]]))
+                    assert gap <= self.tol, f"seq {b} candidate {k}: token {got[i]} vs oracle {int(top[i])}, gap {gap:.3e}"
+                    self.tie_events += 1
+        # (2) scores
+        err = float(np.abs(gt["cand_score"][1:C] - score[1:C]).max())
+        self.max_score_err = max(getattr(self, "max_score_err", 0.0), err)
+        assert err <= self.score_tol, f"seq {b}: cumulative draft log-probabilities differ by {err:.3e}"
+        # (3) expanded candidates per depth: none left out that beats a chosen one by more than the tolerance
+        for j in range(1, D):
+            level = [c for c in range(C) if dep[c] == j]
+            chosen = follow["frontier"][j - 1]
+            out = [c for c in level if c not in set(chosen)]
+            if out:
+                slack = max(score[c] for c in out) - min(score[c] for c in chosen)
+                assert slack <= 2 * self.score_tol, f"seq {b} depth {j}: a left-out candidate beats an expanded one by {slack:.3e}"
+                self.tie_events += int(slack > 0)
+            order = [score[c] for c in chosen]
+            assert all(order[i] >= order[i + 1] - 2 * self.score_tol for i in range(len(order) - 1)), "frontier order"
+        # (4) kept set
+        kept = set(follow["keep"])
+        left = [c for c in range(1, C) if c not in kept]
+        if left:
+            slack = max(score[c] for c in left) - min(score[c] for c in kept if c != 0)
+            assert slack <= 2 * self.score_tol, f"seq {b}: a left-out candidate beats a kept one by {slack:.3e}"
+            self.tie_events += int(slack > 0)
+        # numbering: fully determined by the kept set
+        np.testing.assert_array_equal(dyn["keep"], gt["keep"])
+        np.testing.assert_array_equal(dyn["parent"], gt["parent"])
+        np.testing.assert_array_equal(dyn["rank"], gt["rank"])
+        np.testing.assert_array_equal(dyn["tokens"], gpu_tokens[:n_nodes])
+        self.parents[b] = np.asarray(dyn["parent"], np.int32)
+        # (5) every draft logit the GPU ranked
+        cap = self.gpu.draft_logits
+        if cap is not None:
+            start = 0
+            for j in range(D):
+                nodes = [0] if j == 0 else follow["frontier"][j - 1]
+                base = self.B * start + b * len(nodes)
+                got = cap[base:base + len(nodes)].cpu().numpy()
+                for r, c in enumerate(nodes):
+                    e = float(np.abs(got[r] - dyn["logits"][c]).max())
+                    self.max_draft_logit_err = max(self.max_draft_logit_err, e)
+                    assert e <= self.tol, f"seq {b} candidate {c} (depth {j}): draft logits max-abs error {e:.3e}"
+                start += len(nodes)
+
     def prefill(self, prompts: List[np.ndarray], chunk: int) -> None:
         g = self.gpu
-        g.prefill(prompts, self.parent, self.rank, chunk)
+        g.prefill(prompts, self.parent, self.rank, chunk, dynamic=self.dyn)
         g.torch.cuda.synchronize()
         toks = g.tree_tokens.cpu().numpy()
         lens = g.seq_len()
@@ -138,7 +219,7 @@ class Lockstep:
                     O.draft_tree(self.W, self.ocfg, seq, acc["hid_acc"], acc["next_tok"], [-1], [0])
             self.acc[b] = acc
             assert lens[b] == seq.L == len(p), (lens[b], seq.L, len(p))
-            self._check_draft(b, toks[b, :len(self.parent)], self.parent, self.rank)
+            self._check_draft(b, toks[b, :self.n_nodes], self.parent, self.rank)
             assert seq.aug_L == seq.L
             self.compare_kv(b, 0, seq.L)
 
@@ -184,7 +265,7 @@ class Lockstep:
         lens = g.seq_len()
         for b, L in enumerate(lengths):
             assert lens[b] == L
-            self._check_draft(b, toks[b, :len(self.parent)], self.parent, self.rank)
+            self._check_draft(b, toks[b, :self.n_nodes], self.parent, self.rank)
             assert self.seqs[b].aug_L == L
             self.compare_kv(b, L - 1, L, stacks=(1,))
 
@@ -207,7 +288,8 @@ class Lockstep:
     def step(self, tree_hook: Optional[Callable[[int, np.ndarray], np.ndarray]] = None,
              check_compaction_bits: bool = True) -> List[int]:
         """One speculative step on both sides; returns the accepted lengths."""
-        g, B, N = self.gpu, self.B, len(self.parent)
+        g, B = self.gpu, self.B
+        N = self.dyn[0] if self.dyn is not None else len(self.parent)
         torch = g.torch
         if tree_hook is not None:
             t = g.tree_tokens.cpu().numpy()
@@ -230,7 +312,7 @@ class Lockstep:
         for b in range(B):
             seq = self.seqs[b]
             assert seq.L == L_before[b]
-            o_hidden, o_logits = O.verify_tree(self.W, self.ocfg, seq, tokens[b, :N], self.parent)
+            o_hidden, o_logits = O.verify_tree(self.W, self.ocfg, seq, tokens[b, :N], self.parents[b])
             le = float(np.abs(logits[b, :N] - o_logits).max())
             he = float(np.abs(hidden[b, :N] - o_hidden).max())
             self.max_logit_err = max(self.max_logit_err, le)
@@ -259,7 +341,7 @@ class Lockstep:
                     assert gap <= self.tol, f"seq {b} node {u}: gpu argmax {t} vs oracle {best}, gap {gap:.3e}"
                     override[u] = t
                     self.tie_events += 1
-            acc = O.accept_and_compact(self.ocfg, seq, tokens[b, :N], o_logits, o_hidden, self.parent, override)
+            acc = O.accept_and_compact(self.ocfg, seq, tokens[b, :N], o_logits, o_hidden, self.parents[b], override)
             assert acc["path"] == path, f"seq {b}: accepted path gpu {path} oracle {acc['path']}"
             assert acc["new_tokens"] == [int(t) for t in new_tokens[b, :mb]]
             assert acc["next_tok"] == [int(t) for t in next_tok[b, :mb]]
@@ -288,13 +370,15 @@ def truth_hook_factory(ls: Lockstep, want: List[int]):
     """tree_hook that plants the target's true greedy continuation (computed by the oracle from
     its current state, token by token) down one root path for want[step]-1 levels and wrong
     tokens elsewhere (random-init drafts almost never match on their own)."""
-    parent = ls.parent
-    kids = O.children_of(parent)
-    n = len(parent)
-    height = np.zeros(n, dtype=np.int64)
-    for u in range(n - 1, 0, -1):
-        height[parent[u]] = max(height[parent[u]], height[u] + 1)
     state = {"step": 0}
+
+    def shape_of(b: int):
+        parent = ls.parents[b]
+        n = len(parent)
+        height = np.zeros(n, dtype=np.int64)
+        for u in range(n - 1, 0, -1):
+            height[parent[u]] = max(height[parent[u]], height[u] + 1)
+        return O.children_of(parent), n, height
 
     def continuation(seq, root: int, k: int) -> List[int]:
         c = O.SeqState(ls.ocfg)
@@ -309,6 +393,7 @@ def truth_hook_factory(ls: Lockstep, want: List[int]):
         return out
 
     def hook(b: int, tokens: np.ndarray) -> np.ndarray:
+        kids, n, height = shape_of(b)
         w = want[state["step"]]
         truth = continuation(ls.seqs[b], int(tokens[0]), max(w, 1))
         rng = np.random.default_rng(1000 * state["step"] + b)

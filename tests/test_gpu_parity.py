@@ -83,11 +83,11 @@ def test_op_gemm(path, dtype, M, N, K):
 # ------------------------------------------------------------------------------------------
 # whole calls, lock-step with the oracle
 # ------------------------------------------------------------------------------------------
-def _lockstep(shape, flags=0, gain_jitter=0.0, batch=1, max_seq=256, tree=None, max_nodes=None):
+def _lockstep(shape, flags=0, gain_jitter=0.0, batch=1, max_seq=256, tree=None, max_nodes=None, dynamic=None):
     from tests.parity import Lockstep
     parent, rank = tree if tree is not None else synth.tree_for(shape)
     return Lockstep(shape, parent, rank, max_seq, flags=flags, gain_jitter=gain_jitter, batch=batch,
-                    max_nodes=max_nodes)
+                    max_nodes=max_nodes, dynamic=dynamic)
 
 
 def test_config1_fp32_eight_steps():
@@ -249,6 +249,72 @@ def test_long_context_96_node_tree():
     ms = ls.step()
     say(f"  free step: m={ms} max|dlogit|={ls.max_logit_err:.2e}")
     assert ls.max_logit_err <= 3e-2
+
+
+# ------------------------------------------------------------------------------------------
+# dynamic (score-pruned) tree: a new topology per sequence and step (Sec. 4.1)
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("case", ["fp32", "fp32_generic_batch2", "bf16", "bf16_generic"])
+def test_dynamic_tree(case):
+    _torch()
+    from tests.parity import truth_hook_factory
+    bf16 = case.startswith("bf16")
+    shape = MINI if bf16 else TINY
+    batch = 2 if "batch2" in case else 1
+    if batch > 1:
+        shape = synth.scaled(shape, batch=batch, prompt_len=(20, 40), seed=61)
+    flags = clover.FLAG_GENERIC if "generic" in case else 0
+    dyn = (24, 4, 4) if bf16 else (16, 4, 3)          # (tree nodes, children per expansion, expansions per depth)
+    ls = _lockstep(shape, flags=flags, gain_jitter=0.1, batch=batch, max_seq=384, max_nodes=32, dynamic=dyn)
+    prompts = synth.make_prompts(shape, seed=33) if batch > 1 else [synth.make_prompts(shape, seed=33)[0][:45]]
+    say(f"dynamic tree {case}: {dyn}, prompts {[len(p) for p in prompts]}")
+    ls.prefill(prompts, chunk=16)
+    want = [3, 1, 2, 4] if bf16 else [3, 1, 2]
+    hook = truth_hook_factory(ls, want)
+    for s in range(len(want)):
+        ties = ls.tie_events
+        ms = ls.step(tree_hook=hook)
+        say(f"  step {s}: want {want[s]} got {ms} parents {ls.parents[0].tolist()} max|dlogit|={ls.max_logit_err:.2e} "
+            f"max|dscore|={ls.max_score_err:.2e} ties={ls.tie_events}")
+        if ls.tie_events == ties:
+            assert all(mb <= want[s] for mb in ms) and max(ms) >= 1   # the tree of a step may be shallower than asked
+    for s in range(3):
+        ms = ls.step()
+        say(f"  free step {s}: m={ms} max|dlogit|={ls.max_logit_err:.2e} max|ddraft|={ls.max_draft_logit_err:.2e}")
+    assert ls.max_logit_err <= (3e-2 if bf16 else 1e-4)
+
+
+def test_dynamic_tree_full_width():
+    """The LLaMA3-8B-shaped workload's widths (2 layers) with a 64-node dynamic tree: 8 children per expansion,
+    8 expansions per depth, 201 candidates per step."""
+    _torch()
+    O = __import__("oracle.clover2_oracle", fromlist=["x"])
+    shape = synth.scaled(synth.CONFIGS[3], name="wide-dynamic", n_layers=2, prompt_len=(100, 100), seed=71)
+    ls = _lockstep(shape, max_seq=512, dynamic=(64, 8, 8))
+    ls.ocfg.dtype = np.float32
+    ls.W = O.Weights(ls.store.get_f32, np.float32)
+    ls.seqs = [O.SeqState(ls.ocfg)]
+    ls.prefill(synth.make_prompts(shape), chunk=64)
+    for s in range(2):
+        ms = ls.step()
+        say(f"  step {s}: m={ms} depth of tree {int(__import__('oracle.clover2_oracle', fromlist=['x']).tree_depths(ls.parents[0]).max())} "
+            f"max|dlogit|={ls.max_logit_err:.2e} max|dscore|={ls.max_score_err:.2e} ties={ls.tie_events}")
+    assert ls.max_logit_err <= 3e-2
+
+
+def test_dynamic_tree_argument_errors():
+    _torch()
+    ls = _lockstep(TINY, max_seq=128, max_nodes=32)
+    g = ls.gpu
+    for args, code in [((33, 4, 3), clover.E_TREE), ((16, 17, 3), clover.E_TREE), ((16, 4, 65), clover.E_TREE),
+                       ((16, 16, 16), clover.E_TREE),      # 1 + 16 + 2 * 16 * 16 candidates > 256
+                       ((32, 2, 1), clover.E_TREE)]:       # 1 + 2 + 2 * 2 = 7 candidates < 32 nodes
+        with pytest.raises(clover.CloverError) as e:
+            g.set_dynamic_tree(*args)
+        assert e.value.code == code, args
+    g.set_dynamic_tree(16, 4, 3)
+    with pytest.raises(clover.CloverError):
+        g.accept_forced(1)                                  # prompt chunks need the chain tree
 
 
 # ------------------------------------------------------------------------------------------
