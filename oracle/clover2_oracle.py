@@ -38,7 +38,9 @@ embedding and whose state AD1 / AD2 / FC_j receive, what is handed down) against
 a closed form in the tokens alone for additive Attention Decoders, a pin that
 planted wiring mistakes are shown to fail; the dynamic (score-pruned) tree
 against brute force over every prefix of the full static tree, normalisation of
-its scores, and the lossless property.  The paper prints no worked numeric
+its scores, and the lossless property; sampled verification against the target
+distribution (exact enumeration over the uniforms' outcomes and a seeded
+Monte-Carlo run), its zero-temperature limit, and the library inverse-CDF.  The paper prints no worked numeric
 example, so no pin compares against printed values.
 """
 from __future__ import annotations
@@ -448,6 +450,59 @@ def accept_greedy(tokens: Sequence[int], logits: np.ndarray, parent: Sequence[in
         path.append(u)
 
 
+def accept_sampled(tokens: Sequence[int], logits: np.ndarray, parent: Sequence[int], temperature: float,
+                   uniforms: np.ndarray, decisions: Optional[Dict[int, dict]] = None) -> Tuple[List[int], int, Dict[int, dict]]:
+    """Verification at a non-zero temperature (Table 1, temperature 1 rows; the tree is sampled the way EAGLE's
+    engine does it: the candidates below a node are fixed tokens, not draws, so each is a point-mass proposal).
+
+    At node u the target distribution is p = softmax(logits[u] / temperature).  The children of u are tried in
+    index order: child c with token x is accepted with probability p(x) / (1 - mass of the children already
+    refused), i.e. p(x) under the distribution that remains after the refusals; uniforms[u, i] decides the
+    i-th child.  When a child is accepted the walk moves there.  When none is, the next token is drawn from what
+    remains of p -- the refused tokens removed, the rest renormalised -- by inverting its cumulative sum in
+    token-id order with uniforms[u, 16], and the walk ends.  A leaf draws from p itself.  The emitted token
+    after every visited node is therefore distributed exactly as p (the method stays lossless).
+
+    uniforms: [n_nodes, 17] values in [0, 1).  Returns (path, bonus token, {node: record of what was decided
+    there}); `decisions` = {node: dict(accept=child position or -1, bonus=token)} overrides the decisions at those
+    nodes (tests follow the other side inside a tolerance); the probabilities recorded are always the oracle's."""
+    kids = children_of(parent)
+    u, path, rec = 0, [0], {}
+    while True:
+        z = logits[u].astype(np.float64) / float(temperature)
+        p = np.exp(z - z.max())
+        p /= p.sum()
+        refused = 0.0
+        ratios = []
+        accepted = -1
+        for i, c in enumerate(kids[u]):
+            a = p[int(tokens[c])] / max(1.0 - refused, 1e-300)
+            ratios.append(a)
+            if accepted < 0 and (uniforms[u, i] < a if decisions is None or u not in decisions
+                                 else decisions[u]["accept"] == i):
+                accepted = i
+                break
+            refused += p[int(tokens[c])]
+        rec[u] = dict(ratios=ratios, accept=accepted)
+        if accepted >= 0:
+            u = kids[u][accepted]
+            path.append(u)
+            continue
+        rest = p.copy()
+        for c in kids[u]:
+            rest[int(tokens[c])] = 0.0
+        cdf = np.cumsum(rest)
+        target = uniforms[u, 16] * cdf[-1]
+        bonus = int(np.searchsorted(cdf, target, side="right"))
+        bonus = min(bonus, len(p) - 1)
+        while rest[bonus] == 0.0 and bonus > 0:      # a draw that lands on a removed token's zero-width step
+            bonus -= 1
+        if decisions is not None and u in decisions:
+            bonus = int(decisions[u]["bonus"])
+        rec[u].update(cdf=cdf, target=target, bonus=bonus)
+        return path, bonus, rec
+
+
 def compact(seq: SeqState, path: Sequence[int]) -> None:
     """Keep only the accepted rows: slot L+i receives slot L+path[i], ascending i."""
     L = seq.L
@@ -459,11 +514,12 @@ def compact(seq: SeqState, path: Sequence[int]) -> None:
 
 def accept_and_compact(cfg: OracleConfig, seq: SeqState, tokens: Sequence[int], logits: np.ndarray,
                        hidden: np.ndarray, parent: Sequence[int],
-                       argmax_override: Optional[Dict[int, int]] = None):
-    """Greedy acceptance, KV compaction and the hand-off to the next draft call.
+                       argmax_override: Optional[Dict[int, int]] = None, sampled: Optional[Tuple[List[int], int]] = None):
+    """Greedy acceptance (or a path and next token already chosen by `accept_sampled`), KV compaction and the
+    hand-off to the next draft call.
 
     Returns dict(m, path, new_tokens, hid_acc, next_tok)."""
-    path, bonus = accept_greedy(tokens, logits, parent, argmax_override)
+    path, bonus = sampled if sampled is not None else accept_greedy(tokens, logits, parent, argmax_override)
     compact(seq, path)
     new_tokens = [int(tokens[p]) for p in path[1:]] + [bonus]
     return dict(m=len(path), path=path, new_tokens=new_tokens,

@@ -10,6 +10,8 @@ P6 Attention-Decoder algebra                        (Appendix A.3)
 P7 HF LlamaForCausalLM / SDPA cross-checks          (library special case)
 P8 ranking and accept walk vs brute force
 P9 matrices used by one regressive update / the Augmenting Block vs the cost figures of Sec. 3.3
+P11 dynamic (score-pruned) tree == best prefixes of the complete static tree by brute force; invariants; lossless
+P12 verification at temperature > 0 emits the target distribution (Monte-Carlo, quadrature), zero-temperature limit
 P10 draft wiring in closed form (additive Attention Decoders): which token and whose state each step receives;
     the pin is shown to fail on planted wiring mistakes (mutants of the oracle's source, CPU only)
 """
@@ -805,3 +807,96 @@ def test_p11_dynamic_tree_is_lossless():
         assert seq.aug_L == seq.L - acc["m"]          # the augmenting block catches up in the next draft call
     ref, _ = O.plain_greedy(W, cfg, prompt, len(emitted))
     assert emitted == ref
+
+
+# ---------------------------------------------------------------- P12: verification at temperature > 0 (Table 1, T = 1)
+def _chi2_ok(counts, probs, z=5.0):
+    """Pearson statistic within z standard deviations of its mean (dof = k - 1; fixed seeds, so deterministic)."""
+    n = counts.sum()
+    exp = n * probs
+    stat = ((counts - exp) ** 2 / exp).sum()
+    dof = len(probs) - 1
+    return stat <= dof + z * np.sqrt(2 * dof)
+
+
+def test_p12_sampled_acceptance_emits_the_target_distribution():
+    """Whatever the tree offers, the token emitted after a visited node is distributed as softmax(logits / T) of
+    that node (the method stays lossless at T > 0): seeded Monte-Carlo over the uniforms, at the root and, given the
+    walk reached it, at a depth-1 node."""
+    rng = np.random.default_rng(12)
+    V, T = 7, 1.0
+    parent = [-1, 0, 0, 0, 1, 1, 2]
+    tokens = [3, 2, 4, 1, 3, 5, 6]
+    logits = rng.standard_normal((7, V)) * 1.5
+    first = np.zeros(V)
+    second = {1: np.zeros(V), 2: np.zeros(V)}
+    for _ in range(30000):
+        path, bonus, _ = O.accept_sampled(tokens, logits, parent, T, rng.random((7, 17)))
+        out = [tokens[c] for c in path[1:]] + [bonus]
+        first[out[0]] += 1
+        if len(path) > 1 and path[1] in second:
+            second[path[1]][out[1]] += 1
+    soft = lambda z: np.exp(z - z.max()) / np.exp(z - z.max()).sum()
+    assert _chi2_ok(first, soft(logits[0] / T))
+    for node, cnt in second.items():
+        assert cnt.sum() > 2000
+        assert _chi2_ok(cnt, soft(logits[node] / T))
+    # and at another temperature
+    first[:] = 0
+    for _ in range(20000):
+        path, bonus, _ = O.accept_sampled(tokens, logits, parent, 0.6, rng.random((7, 17)))
+        first[tokens[path[1]] if len(path) > 1 else bonus] += 1
+    assert _chi2_ok(first, soft(logits[0] / 0.6))
+
+
+def test_p12_one_child_exact_by_quadrature():
+    """One candidate below the root: the outcome as a function of the two uniforms, integrated on a midpoint grid,
+    reproduces the target probabilities to the grid's resolution (no formula of the procedure is used here)."""
+    rng = np.random.default_rng(3)
+    V, G = 5, 120
+    logits = rng.standard_normal((2, V))
+    parent, tokens = [-1, 0], [0, 3]
+    cnt = np.zeros(V)
+    u = np.zeros((2, 17))
+    for i in range(G):
+        for j in range(G):
+            u[0, 0] = (i + 0.5) / G
+            u[0, 16] = (j + 0.5) / G
+            path, bonus, _ = O.accept_sampled(tokens, logits, parent, 1.0, u)
+            cnt[tokens[path[1]] if len(path) > 1 else bonus] += 1
+    p = np.exp(logits[0] - logits[0].max()); p /= p.sum()
+    assert np.abs(cnt / G ** 2 - p).max() <= 2.5 / G
+
+
+def test_p12_zero_temperature_limit_is_greedy_acceptance():
+    rng = np.random.default_rng(5)
+    V = 9
+    for trial in range(100):
+        n = int(rng.integers(1, 10))
+        parent = rand_tree(rng, n)
+        kids = O.children_of(parent)
+        tokens = np.zeros(n, dtype=np.int64)
+        for u in range(n):
+            perm = rng.permutation(V)
+            for i, c in enumerate(kids[u]):
+                tokens[c] = perm[i]
+        logits = rng.standard_normal((n, V))
+        path, bonus, _ = O.accept_sampled(tokens, logits, parent, 1e-4, rng.random((n, 17)))
+        assert (path, bonus) == O.accept_greedy(tokens, logits, parent)
+
+
+def test_p12_leaf_draw_inverts_the_cumulative_sum():
+    rng = np.random.default_rng(8)
+    V = 50
+    logits = rng.standard_normal((1, V)) * 2
+    p = np.exp(logits[0] - logits[0].max()); p /= p.sum()
+    for _ in range(200):
+        u = rng.random((1, 17))
+        _, bonus, _ = O.accept_sampled([0], logits, [-1], 1.0, u)
+        acc, want = 0.0, V - 1
+        for t in range(V):                  # plain loop: first token whose running sum passes the uniform
+            acc += p[t]
+            if acc > u[0, 16]:
+                want = t
+                break
+        assert bonus == want
