@@ -185,6 +185,19 @@ int accept_and_compact(clover_ctx *ctx, int32_t batch, const int32_t *tree_token
                        const float *hidden, int32_t *m, int32_t *acc_idx, int32_t *new_tokens,
                        float *hid_acc, int32_t *next_tok);
 
+/* Verification at a temperature > 0 (Table 1, temperature 1 rows) and cache compaction.  Per sequence, starting
+ * at the root: with p = softmax(logits[node] / temperature) the children of the node are tried in index order and
+ * child i is accepted when uniforms[b, node, i] < p(its token) / (1 - p-mass of the children already refused); the
+ * walk then moves to it.  When none is accepted (or the node is a leaf) the next token is drawn from what is left
+ * of p (the refused tokens removed) by inverting its cumulative sum in token-id order with uniforms[b, node, 16],
+ * and the walk ends.  Every emitted token is then distributed exactly as the target model's own sample.
+ *   temperature dev-independent scalar > 0
+ *   uniforms    dev in fp32 [batch, max_nodes, 17], values in [0, 1): the caller's random numbers
+ * Everything else as accept_and_compact. */
+int accept_and_compact_sampled(clover_ctx *ctx, int32_t batch, const int32_t *tree_tokens, const float *logits,
+                               const float *hidden, float temperature, const float *uniforms, int32_t *m,
+                               int32_t *acc_idx, int32_t *new_tokens, float *hid_acc, int32_t *next_tok);
+
 /* Prompt hand-off for a chain-shaped tree (the prefill phase of Sec. 1 run as chunks of plain
  * decoding): accept nodes 0..n_rows[b]-1 of sequence b unconditionally (n_rows[b] = 0 leaves
  * the sequence untouched).  The token after the last row is forced_next[b], or the target's

@@ -22,7 +22,7 @@ STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = [
     "clover_workspace_bytes", "clover_init", "clover_destroy", "clover_reset", "clover_set_tree",
-    "draft_tree", "verify_tree", "accept_and_compact", "clover_accept_forced", "clover_seq_len",
+    "draft_tree", "verify_tree", "accept_and_compact", "accept_and_compact_sampled", "clover_accept_forced", "clover_seq_len",
     "clover_read_kv", "clover_write_kv", "clover_set_seq_len", "clover_capture_draft_logits", "clover_set_dynamic_tree", "clover_read_dynamic_tree", "clover_path_info", "clover_profile_enable", "clover_profile_collect", "clover_kernel_class_count",
     "clover_kernel_class_name", "clover_last_error", "clover_last_global_error",
     "clover_op_gemm_scratch_bytes", "clover_op_gemm", "clover_op_gemm_static",
@@ -78,6 +78,7 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.draft_tree.argtypes = [vp, i32, f32p, i32p, i32p, i32p]
     lib.verify_tree.argtypes = [vp, i32, i32p, f32p, f32p]
     lib.accept_and_compact.argtypes = [vp, i32, i32p, f32p, f32p, i32p, i32p, i32p, f32p, i32p]
+    lib.accept_and_compact_sampled.argtypes = [vp, i32, i32p, f32p, f32p, C.c_float, f32p, i32p, i32p, i32p, f32p, i32p]
     lib.clover_accept_forced.argtypes = [vp, i32, i32p, f32p, f32p, i32p, i32p, i32p, i32p, i32p, f32p, i32p]
     lib.clover_seq_len.argtypes = [vp, C.POINTER(C.c_int32)]
     lib.clover_read_kv.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp]
@@ -228,6 +229,14 @@ class Clover:
         self._check(self.lib.accept_and_compact(self.ctx, batch, self._p(self.tree_tokens), self._p(self.logits),
                                                 self._p(self.hidden), self._p(self.m), self._p(self.acc_idx),
                                                 self._p(self.new_tokens), self._p(self.hid_acc), self._p(self.next_tok)))
+
+    def accept_and_compact_sampled(self, batch: int, temperature: float, uniforms) -> None:
+        """uniforms: device fp32 tensor [batch, max_nodes, 17] of the caller's random numbers in [0, 1)."""
+        assert tuple(uniforms.shape) == (self.B, self.R, 17) and uniforms.dtype == self.torch.float32
+        self._check(self.lib.accept_and_compact_sampled(self.ctx, batch, self._p(self.tree_tokens), self._p(self.logits),
+                                                        self._p(self.hidden), C.c_float(temperature), self._p(uniforms),
+                                                        self._p(self.m), self._p(self.acc_idx), self._p(self.new_tokens),
+                                                        self._p(self.hid_acc), self._p(self.next_tok)))
 
     def accept_forced(self, batch: int) -> None:
         self._check(self.lib.clover_accept_forced(self.ctx, batch, self._p(self.tree_tokens), self._p(self.logits),

@@ -798,16 +798,28 @@ int check_batch(clover_ctx* x, int batch) {
 
 int accept_common(clover_ctx* x, int batch, const int* tree_tokens, const float* logits, const float* hidden,
                   const int* n_forced, const int* forced_next, int* m, int* acc_idx, int* new_tokens, float* hid_acc,
-                  int* next_tok) {
+                  int* next_tok, float temperature = 0.f, const float* uniforms = nullptr) {
   const clover_config& c = x->cfg;
   const TreeHost& t = x->tree;
   const int n_nodes = x->dyn_on ? x->dyn.N : t.n;
   const int R = x->R, M = (batch - 1) * R + n_nodes;
+  const int* fc_tab = x->dyn_on ? x->dyn.t_first_child : x->d_first_child;
+  const int* nc_tab = x->dyn_on ? x->dyn.t_n_child : x->d_n_child;
+  if (uniforms) {
+    // temperature > 0: per-row log-sum-exp of logits / T, then the sampled walk
+    const float inv_t = 1.0f / temperature;
+    { Scope s(x, KC_TOPK);
+      launch_topk_lse(logits, c.vocab, c.vocab, M, 1, x->cand, x->topk_aux, x->topk_ids, x->topk_vals, x->topk_lse, x->st, inv_t); }
+    { Scope s(x, KC_ACCEPT);
+      launch_accept_sample(logits, c.vocab, x->topk_lse, inv_t, tree_tokens, fc_tab, nc_tab, x->dyn_on ? R : 0, batch, R,
+                           uniforms, m, acc_idx, new_tokens, next_tok, x->st); }
+  } else {
   { Scope s(x, KC_TOPK); launch_topk(logits, c.vocab, c.vocab, M, 1, x->cand, x->topk_ids, x->st); }
   { Scope s(x, KC_ACCEPT);
     launch_accept_walk(x->topk_ids, tree_tokens, x->dyn_on ? x->dyn.t_first_child : x->d_first_child,
                        x->dyn_on ? x->dyn.t_n_child : x->d_n_child, n_nodes, batch, R, n_forced, forced_next,
                        m, acc_idx, new_tokens, next_tok, x->st, x->dyn_on ? R : 0); }
+  }
   { Scope s(x, KC_COMPACT);
     launch_compact_kv(x->kc, x->vc, x->kvdtype, x->kv, c.n_layers, x->kv_layer_stride, x->kv_layer_stride, x->d_seq_len, m,
                       acc_idx, batch, R, x->st);
@@ -1203,6 +1215,22 @@ int accept_and_compact(clover_ctx* x, int32_t batch, const int32_t* tree_tokens,
   int rc = check_batch(x, batch);
   if (rc) return rc;
   rc = accept_common(x, batch, tree_tokens, logits, hidden, nullptr, nullptr, m, acc_idx, new_tokens, hid_acc, next_tok);
+  if (rc) return rc;
+  x->m_upper = std::min((x->dyn_on ? x->dyn.D : x->tree.max_depth) + 1, x->R);
+  for (int b = 0; b < batch; ++b) x->len_ub[b] += x->m_upper;
+  return CLOVER_OK;
+}
+
+int accept_and_compact_sampled(clover_ctx* x, int32_t batch, const int32_t* tree_tokens, const float* logits,
+                               const float* hidden, float temperature, const float* uniforms, int32_t* m,
+                               int32_t* acc_idx, int32_t* new_tokens, float* hid_acc, int32_t* next_tok) {
+  if (!x || !tree_tokens || !logits || !hidden || !uniforms || !m || !acc_idx || !new_tokens || !hid_acc || !next_tok)
+    return fail(x, CLOVER_E_NULL, "null argument");
+  int rc = check_batch(x, batch);
+  if (rc) return rc;
+  if (!(temperature > 0.f) || !(temperature < 1e6f)) return fail(x, CLOVER_E_SHAPE, "temperature must be positive (use accept_and_compact for temperature 0)");
+  rc = accept_common(x, batch, tree_tokens, logits, hidden, nullptr, nullptr, m, acc_idx, new_tokens, hid_acc, next_tok,
+                     temperature, uniforms);
   if (rc) return rc;
   x->m_upper = std::min((x->dyn_on ? x->dyn.D : x->tree.max_depth) + 1, x->R);
   for (int b = 0; b < batch; ++b) x->len_ub[b] += x->m_upper;

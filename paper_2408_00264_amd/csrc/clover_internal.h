@@ -233,8 +233,13 @@ struct DynTree {
 };
 // per row of z[rows, V]: ids and values of the k best entries (value descending, id ascending) and the row's
 // log-sum-exp.  cand: [rows][chunks][16] 64-bit keys, aux: [rows][chunks][2] floats, chunks = ceil(V / 2048)
+// (scale: every value is multiplied by it first -- an inverse temperature)
 void launch_topk_lse(const float* z, int ldz, int V, int rows, int k, void* cand, float* aux, int* out_ids,
-                     float* out_vals, float* out_lse, hipStream_t st);
+                     float* out_vals, float* out_lse, hipStream_t st, float scale = 1.0f);
+// verification at a temperature > 0: lse[row] = log-sum-exp of logits[row] * inv_temp; uniforms [B][R][17]
+void launch_accept_sample(const float* logits, int V, const float* lse, float inv_temp, const int* tokens,
+                          const int* first_child, const int* n_child, int child_stride, int B, int R,
+                          const float* uniforms, int* m, int* acc_idx, int* new_tokens, int* next_tok, hipStream_t st);
 void launch_dyn_assign(const DynTree& t, int j, int B, const int* ids, const float* vals, const float* lse, const int* m,
                        hipStream_t st);
 void launch_dyn_frontier(const DynTree& t, int j, int B, const int* m, hipStream_t st);

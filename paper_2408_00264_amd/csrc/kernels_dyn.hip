@@ -65,7 +65,7 @@ constexpr int DY_EPT = DY_CHUNK / 256;
 // exp(value - maximum) (the pieces of the row's log-sum-exp)
 __global__ __launch_bounds__(256) void topk_lse_stage1_kernel(const float* __restrict__ z, int ldz, int V, int k,
                                                               unsigned long long* __restrict__ cand,
-                                                              float* __restrict__ aux) {
+                                                              float* __restrict__ aux, float scale) {
   __shared__ unsigned long long red[4];
   __shared__ float fred[4];
   const int chunk = blockIdx.x, row = blockIdx.y, chunks = gridDim.x;
@@ -75,7 +75,7 @@ __global__ __launch_bounds__(256) void topk_lse_stage1_kernel(const float* __res
 #pragma unroll
   for (int e = 0; e < DY_EPT; ++e) {
     const int id = chunk * DY_CHUNK + e * 256 + threadIdx.x;
-    val[e] = id < V ? z[(size_t)row * ldz + id] : -INFINITY;
+    val[e] = id < V ? z[(size_t)row * ldz + id] * scale : -INFINITY;
     key[e] = id < V ? d_key(val[e], id) : 0ull;
     mx = fmaxf(mx, val[e]);
   }
@@ -253,13 +253,117 @@ __global__ __launch_bounds__(DYN_MAX_CAND) void dyn_finalize_kernel(DynTree t, i
   }
 }
 
+// Verification at a temperature > 0 (one 1024-thread workgroup per sequence).  Thread 0 walks the tree: at node u
+// with p = softmax(logits[u] / T), the children are tried in index order, child i accepted when
+// uniforms[u][i] < p(token) / (1 - mass of the children already refused).  When none is accepted (or u is a leaf)
+// the whole workgroup draws the next token from what is left of p (refused tokens removed) by inverting its
+// cumulative sum in token order with uniforms[u][16]; sums are carried in double precision.
+constexpr int SAMPLE_THREADS = 1024;
+__global__ __launch_bounds__(SAMPLE_THREADS) void accept_sample_kernel(
+    const float* __restrict__ logits, int V, const float* __restrict__ lse, float inv_temp, const int* __restrict__ tokens,
+    const int* __restrict__ first_child, const int* __restrict__ n_child, int child_stride, int R,
+    const float* __restrict__ uniforms, int* __restrict__ m, int* __restrict__ acc_idx, int* __restrict__ new_tokens,
+    int* __restrict__ next_tok) {
+  __shared__ int s_u, s_len, s_nk, s_kid_tok[CLOVER_MAX_RANK], s_pick;
+  __shared__ double s_part[SAMPLE_THREADS / 64], s_total;
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const size_t o = (size_t)b * R;
+  first_child += (size_t)b * child_stride;
+  n_child += (size_t)b * child_stride;
+  if (tid == 0) {
+    int u = 0, len = 1;
+    acc_idx[o] = 0;
+    for (;;) {
+      const float* zr = logits + (o + u) * (size_t)V;
+      const float l = lse[o + u];
+      const int c0 = first_child[u], nk = min(n_child[u], CLOVER_MAX_RANK);
+      double refused = 0.0;
+      int accepted = -1;
+      for (int i = 0; i < nk; ++i) {
+        const int x = tokens[o + c0 + i];
+        const double px = (x >= 0 && x < V) ? exp((double)(zr[x] * inv_temp) - (double)l) : 0.0;
+        const double a = px / fmax(1.0 - refused, 1e-300);
+        if ((double)uniforms[(o + u) * 17 + i] < a) { accepted = c0 + i; break; }
+        refused += px;
+      }
+      if (accepted < 0 || len >= R) break;
+      u = accepted;
+      acc_idx[o + len++] = u;
+    }
+    s_u = u; s_len = len;
+    const int nk = min(n_child[u], CLOVER_MAX_RANK);
+    s_nk = nk;
+    for (int i = 0; i < nk; ++i) s_kid_tok[i] = tokens[o + first_child[u] + i];
+    s_pick = V - 1;
+  }
+  __syncthreads();
+  const int u = s_u, nk = s_nk;
+  const float* zr = logits + (o + u) * (size_t)V;
+  const double l = (double)lse[o + u];
+  // each thread owns a contiguous range of token ids
+  const int per = (V + SAMPLE_THREADS - 1) / SAMPLE_THREADS;
+  const int t0 = tid * per, t1 = min(V, t0 + per);
+  auto rest = [&](int t) -> double {
+    for (int i = 0; i < nk; ++i)
+      if (s_kid_tok[i] == t) return 0.0;
+    return exp((double)(zr[t] * inv_temp) - l);
+  };
+  double mine = 0.0;
+  for (int t = t0; t < t1; ++t) mine += rest(t);
+  // inclusive scan over the threads: wavefront scan, then the wavefront totals
+  double incl = mine;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const double v = __shfl_up(incl, d, 64);
+    if ((tid & 63) >= d) incl += v;
+  }
+  if ((tid & 63) == 63) s_part[tid >> 6] = incl;
+  __syncthreads();
+  if (tid == 0) {
+    double run = 0.0;
+    for (int w = 0; w < SAMPLE_THREADS / 64; ++w) { const double v = s_part[w]; s_part[w] = run; run += v; }
+    s_total = run;
+  }
+  __syncthreads();
+  const double before = s_part[tid >> 6] + incl - mine;      // mass of all smaller token ids
+  const double target = (double)uniforms[(o + u) * 17 + 16] * s_total;
+  if (mine > 0.0 && before <= target && target < before + mine) {
+    double run = before;
+    int pick = t1 - 1;
+    for (int t = t0; t < t1; ++t) {
+      run += rest(t);
+      if (run > target) { pick = t; break; }
+    }
+    s_pick = pick;   // exactly one thread's range contains the target
+  }
+  __syncthreads();
+  if (tid == 0) {
+    const int len = s_len, bonus = s_pick;
+    for (int j = 1; j < len; ++j) {
+      const int t = tokens[o + acc_idx[o + j]];
+      new_tokens[o + j - 1] = t;
+      next_tok[o + j - 1] = t;
+    }
+    new_tokens[o + len - 1] = bonus;
+    next_tok[o + len - 1] = bonus;
+    m[b] = len;
+  }
+}
+
 }  // namespace
 
+void launch_accept_sample(const float* logits, int V, const float* lse, float inv_temp, const int* tokens,
+                          const int* first_child, const int* n_child, int child_stride, int B, int R,
+                          const float* uniforms, int* m, int* acc_idx, int* new_tokens, int* next_tok, hipStream_t st) {
+  accept_sample_kernel<<<B, SAMPLE_THREADS, 0, st>>>(logits, V, lse, inv_temp, tokens, first_child, n_child, child_stride, R,
+                                                     uniforms, m, acc_idx, new_tokens, next_tok);
+}
+
 void launch_topk_lse(const float* z, int ldz, int V, int rows, int k, void* cand, float* aux, int* out_ids,
-                     float* out_vals, float* out_lse, hipStream_t st) {
+                     float* out_vals, float* out_lse, hipStream_t st, float scale) {
   if (rows <= 0) return;
   const int chunks = (V + DY_CHUNK - 1) / DY_CHUNK;
-  topk_lse_stage1_kernel<<<dim3(chunks, rows), 256, 0, st>>>(z, ldz, V, k, (unsigned long long*)cand, aux);
+  topk_lse_stage1_kernel<<<dim3(chunks, rows), 256, 0, st>>>(z, ldz, V, k, (unsigned long long*)cand, aux, scale);
   topk_lse_stage2_kernel<<<rows, 256, 0, st>>>((const unsigned long long*)cand, aux, chunks, k, out_ids, out_vals, out_lse);
 }
 void launch_dyn_assign(const DynTree& t, int j, int B, const int* ids, const float* vals, const float* lse, const int* m,

@@ -186,6 +186,44 @@ class Lockstep:
                     assert e <= self.tol, f"seq {b} candidate {c} (depth {j}): draft logits max-abs error {e:.3e}"
                 start += len(nodes)
 
+    def _follow_sampled(self, b: int, tokens, o_logits, o_hidden, gpu_path, gpu_bonus, temperature, uni) -> dict:
+        """Sampled verification: the oracle runs on the same uniforms; where the GPU decided otherwise, its decision
+        must lie within the tolerance of the oracle's own threshold (an acceptance ratio, or a step of the cumulative
+        sum), and the oracle then follows it."""
+        parent = self.parents[b]
+        kids = O.children_of(parent)
+        path, bonus, rec = O.accept_sampled(tokens, o_logits, parent, temperature, uni)
+        if path != gpu_path or bonus != gpu_bonus:
+            # relative slack of a probability computed from logits that may differ by `tol`
+            slack = np.expm1(2 * self.tol / temperature)
+            decisions = {}
+            for i, u in enumerate(gpu_path):
+                nxt = gpu_path[i + 1] if i + 1 < len(gpu_path) else -1
+                decisions[u] = dict(accept=kids[u].index(nxt) if nxt >= 0 else -1, bonus=gpu_bonus)
+            path2, bonus2, rec2 = O.accept_sampled(tokens, o_logits, parent, temperature, uni, decisions=decisions)
+            assert path2 == gpu_path and bonus2 == gpu_bonus
+            for u in gpu_path:                      # every forced decision must be a near-threshold one
+                r = rec2[u]
+                for i, a in enumerate(r["ratios"]):
+                    took = r["accept"] == i
+                    natural = uni[u, i] < a
+                    if took != natural:
+                        assert abs(uni[u, i] - a) <= slack * a + 1e-7, \
+                            f"seq {b} node {u} child {i}: uniform {uni[u, i]:.6f} vs ratio {a:.6f}"
+                        self.tie_events += 1
+                    if took:
+                        break
+                if "cdf" in r:
+                    cdf, target, t = r["cdf"], r["target"], gpu_bonus
+                    lo = cdf[t - 1] if t > 0 else 0.0
+                    d = slack * cdf[-1] + 1e-7
+                    assert cdf[t] > lo, f"seq {b} node {u}: the GPU drew token {t}, which has no probability left"
+                    if not (lo <= target < cdf[t]):
+                        assert lo - d <= target <= cdf[t] + d, f"seq {b} node {u}: drawn token {t} outside its step"
+                        self.tie_events += 1
+            path, bonus = path2, bonus2
+        return O.accept_and_compact(self.ocfg, self.seqs[b], tokens, o_logits, o_hidden, parent, sampled=(path, bonus))
+
     def prefill(self, prompts: List[np.ndarray], chunk: int) -> None:
         g = self.gpu
         g.prefill(prompts, self.parent, self.rank, chunk, dynamic=self.dyn)
@@ -286,8 +324,9 @@ class Lockstep:
                 assert ek <= atol and ev <= atol, f"KV stack {stack} layer {l} seq {b}: |dK| {ek:.3e} |dV| {ev:.3e}"
 
     def step(self, tree_hook: Optional[Callable[[int, np.ndarray], np.ndarray]] = None,
-             check_compaction_bits: bool = True) -> List[int]:
-        """One speculative step on both sides; returns the accepted lengths."""
+             check_compaction_bits: bool = True, sampled: Optional[tuple] = None) -> List[int]:
+        """One speculative step on both sides; returns the accepted lengths.  sampled = (temperature, seed) verifies
+        at that temperature with seeded uniforms handed to both sides."""
         g, B = self.gpu, self.B
         N = self.dyn[0] if self.dyn is not None else len(self.parent)
         torch = g.torch
@@ -303,7 +342,12 @@ class Lockstep:
         logits = g.logits.cpu().numpy()
         hidden = g.hidden.cpu().numpy()
         pre_kv = [[g.read_kv(0, l, b, int(L_before[b]), N) for l in range(self.shape.n_layers)] for b in range(B)]
-        g.accept_and_compact(B)
+        uni = None
+        if sampled is not None:
+            uni = np.random.default_rng([int(sampled[1]), 17]).random((B, g.R, 17), dtype=np.float32)
+            g.accept_and_compact_sampled(B, float(sampled[0]), torch.from_numpy(uni).to(g.dev))
+        else:
+            g.accept_and_compact(B)
         torch.cuda.synchronize()
         m = g.m.cpu().numpy(); acc_idx = g.acc_idx.cpu().numpy(); new_tokens = g.new_tokens.cpu().numpy()
         next_tok = g.next_tok.cpu().numpy(); hid_acc = g.hid_acc.cpu().numpy()
@@ -330,6 +374,21 @@ class Lockstep:
             mb = int(m[b])
             path = [int(a) for a in acc_idx[b, :mb]]
             assert mb >= 1 and path[0] == 0
+            if sampled is not None:
+                acc = self._follow_sampled(b, tokens[b, :N], o_logits, o_hidden, path, int(new_tokens[b, mb - 1]),
+                                           float(sampled[0]), uni[b].astype(np.float64))
+                assert acc["new_tokens"] == [int(t) for t in new_tokens[b, :mb]]
+                assert acc["next_tok"] == [int(t) for t in next_tok[b, :mb]]
+                assert L_after[b] == seq.L
+                np.testing.assert_array_equal(hid_acc[b, :mb], hidden[b, path])
+                if check_compaction_bits:
+                    for l in range(self.shape.n_layers):
+                        k2, v2 = g.read_kv(0, l, b, int(L_before[b]), mb)
+                        np.testing.assert_array_equal(k2, pre_kv[b][l][0][path])
+                        np.testing.assert_array_equal(v2, pre_kv[b][l][1][path])
+                self.acc[b] = acc
+                ms.append(mb)
+                continue
             implied = {}
             for i, u in enumerate(path):
                 implied[u] = int(tokens[b, path[i + 1]]) if i + 1 < mb else int(new_tokens[b, mb - 1])

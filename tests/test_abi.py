@@ -25,7 +25,8 @@ def test_header_symbols_exported(lib):
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = set(re.findall(r"\b([a-z_][a-z0-9_]*)\s*\(", text))
     names -= {"defined"}
-    declared = {n for n in names if n.startswith("clover_") or n in ("draft_tree", "verify_tree", "accept_and_compact")}
+    declared = {n for n in names if n.startswith("clover_") or
+                n in ("draft_tree", "verify_tree", "accept_and_compact", "accept_and_compact_sampled")}
     assert {"clover_init", "draft_tree", "verify_tree", "accept_and_compact"} <= declared
     for n in declared:
         assert hasattr(lib, n), n

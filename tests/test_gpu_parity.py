@@ -299,6 +299,10 @@ def test_dynamic_tree_full_width():
         ms = ls.step()
         say(f"  step {s}: m={ms} depth of tree {int(__import__('oracle.clover2_oracle', fromlist=['x']).tree_depths(ls.parents[0]).max())} "
             f"max|dlogit|={ls.max_logit_err:.2e} max|dscore|={ls.max_score_err:.2e} ties={ls.tie_events}")
+    # and verification at a temperature over the full vocabulary (the draw inverts a 128256-entry cumulative sum)
+    for s, temp in enumerate([1.0, 0.05, 1.0]):
+        ms = ls.step(sampled=(temp, 300 + s))
+        say(f"  sampled step T={temp}: m={ms} ties={ls.tie_events}")
     assert ls.max_logit_err <= 3e-2
 
 
@@ -315,6 +319,84 @@ def test_dynamic_tree_argument_errors():
     g.set_dynamic_tree(16, 4, 3)
     with pytest.raises(clover.CloverError):
         g.accept_forced(1)                                  # prompt chunks need the chain tree
+
+
+# ------------------------------------------------------------------------------------------
+# verification at a temperature > 0 (Table 1, temperature 1 rows)
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("case", ["fp32", "bf16", "bf16_dynamic_tree"])
+def test_sampled_verification(case):
+    """Same seeded uniforms on both sides: identical walks and draws (threshold cases within tolerance), the
+    compaction and the hand-off that follow, over several steps; a low temperature makes acceptances frequent
+    when the tree carries the target's favourite continuation, temperature 1 exercises the draw from the rest."""
+    _torch()
+    from tests.parity import truth_hook_factory
+    bf16 = case.startswith("bf16")
+    shape = MINI if bf16 else TINY
+    dyn = (24, 4, 4) if case.endswith("dynamic_tree") else None
+    ls = _lockstep(shape, gain_jitter=0.1, max_seq=384, max_nodes=32, dynamic=dyn)
+    ls.prefill([synth.make_prompts(shape, seed=52)[0][:41]], chunk=16)
+    want = [4, 3, 2, 4, 3, 4]
+    hook = truth_hook_factory(ls, want)
+    seen = []
+    for s, temp in enumerate([0.02, 0.05, 1.0, 0.02, 0.3, 1.0]):
+        ms = ls.step(tree_hook=hook, sampled=(temp, 100 + s))
+        say(f"  step {s}: T={temp} planted {want[s]} accepted {ms} ties={ls.tie_events}")
+        seen.append(ms[0])
+    assert max(seen) >= 2 and min(seen) == 1            # both outcomes occurred
+    for s in range(4):
+        ms = ls.step(sampled=(1.0, 200 + s))
+    assert ls.max_logit_err <= (3e-2 if bf16 else 1e-4)
+
+
+def test_sampled_verification_crafted():
+    """Crafted logits through the C ABI: probabilities 0.5 / 0.25 / 0.25 over three tokens at the root, two of them
+    offered as children; the uniforms decide exactly which branch is taken."""
+    torch = _torch()
+    shape = TINY
+    parent = np.asarray([-1, 0, 0, 1], np.int32)
+    rank = np.asarray([0, 0, 1, 0], np.int32)
+    ls = _lockstep(shape, tree=(parent, rank), max_seq=128, max_nodes=16)
+    g = ls.gpu
+    ls.prefill([synth.make_prompts(shape, seed=77)[0][:17]], chunk=8)
+    toks = np.zeros((1, g.R), np.int32)
+    toks[0, :4] = [int(g.tree_tokens[0, 0].item()), 11, 22, 33]
+    base = np.full((4, shape.vocab), -1e4, np.float32)
+    base[0, [11, 22, 44]] = np.log([0.5, 0.25, 0.25])       # root: child tokens 11 (p .5), 22 (p .25); 44 not offered
+    base[1, [33, 55]] = np.log([0.5, 0.5])                  # node 1: child token 33 (p .5)
+    base[2, 66] = 0.0                                       # node 2 (leaf): 66 with certainty
+    base[3, [70, 71]] = np.log([0.25, 0.75])                # node 3 (leaf)
+    cases = [  # uniforms at (node, slot) -> expected path, next token
+        ({(0, 0): 0.49, (1, 0): 0.49, (3, 16): 0.24}, [0, 1, 3], 70),
+        ({(0, 0): 0.49, (1, 0): 0.49, (3, 16): 0.26}, [0, 1, 3], 71),
+        ({(0, 0): 0.49, (1, 0): 0.51, (1, 16): 0.9}, [0, 1], 55),
+        ({(0, 0): 0.51, (0, 1): 0.49, (2, 16): 0.3}, [0, 2], 66),     # 22 accepted with 0.25 / (1 - 0.5) = 0.5
+        ({(0, 0): 0.51, (0, 1): 0.51, (0, 16): 0.7}, [0], 44),        # both refused: only 44 is left
+    ]
+    for uni_set, want_path, want_tok in cases:
+        g.tree_tokens.copy_(torch.from_numpy(toks))
+        g.verify_tree(1)                                     # K/V rows for the compaction that follows
+        g.logits[0, :4].copy_(torch.from_numpy(base))
+        uni = np.full((1, g.R, 17), 0.999, np.float32)
+        for (node, slot), v in uni_set.items():
+            uni[0, node, slot] = v
+        L = int(g.seq_len()[0])
+        g.accept_and_compact_sampled(1, 1.0, torch.from_numpy(uni).to(g.dev))
+        torch.cuda.synchronize()
+        m = int(g.m[0].item())
+        assert g.acc_idx[0, :m].cpu().tolist() == want_path, (uni_set, g.acc_idx[0, :m].cpu().tolist())
+        assert int(g.new_tokens[0, m - 1].item()) == want_tok
+        assert g.new_tokens[0, :m - 1].cpu().tolist() == [int(toks[0, u]) for u in want_path[1:]]
+        assert int(g.seq_len()[0]) == L + m
+        # the same decisions from the oracle's procedure on the same numbers
+        O = __import__("oracle.clover2_oracle", fromlist=["x"])
+        path, bonus, _ = O.accept_sampled(toks[0, :4], base.astype(np.float64), parent, 1.0, uni[0].astype(np.float64))
+        assert (path, bonus) == (want_path, want_tok)
+        # keep the draft head's cache in step with the target's
+        g.draft_tree(1)
+    with pytest.raises(clover.CloverError) as e:
+        g.accept_and_compact_sampled(1, 0.0, torch.from_numpy(uni).to(g.dev))
+    assert e.value.code == clover.E_SHAPE
 
 
 # ------------------------------------------------------------------------------------------
