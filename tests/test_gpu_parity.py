@@ -229,6 +229,22 @@ def test_batch8_ragged_32_node_tree():
     assert ls.max_logit_err <= 3e-2
 
 
+def test_batch12_384_rows():
+    """More than 8 sequences and more than 256 rows per pass (12 ragged sequences x 32-node tree = 384 rows): the GEMMs
+    run as several row batches, attention and acceptance per sequence."""
+    _torch()
+    shape = synth.scaled(synth.CONFIGS[4], name="mini-b12", n_layers=2, hidden=512, n_q_heads=4, n_kv_heads=2,
+                         ffn=1536, vocab=8192, batch=12, prompt_len=(10, 120), seed=43)
+    ls = _lockstep(shape, gain_jitter=0.1, batch=12, max_seq=256)
+    prompts = synth.make_prompts(shape)
+    say("batch 12 prompt lengths", [len(p) for p in prompts])
+    ls.prefill(prompts, chunk=32)
+    for s in range(2):
+        ms = ls.step()
+        say(f"  step {s}: m={ms} max|dlogit|={ls.max_logit_err:.2e} ties={ls.tie_events}")
+    assert ls.max_logit_err <= 3e-2
+
+
 def test_long_context_96_node_tree():
     """Structure of the long-context workload: 96-node tree, draft depth 5, >1000 cached keys (many key
     tiles and several key splits per attention launch)."""
