@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libclover.so")
-SOURCES = ["kernels_generic.hip", "kernels_mfma.hip", "kernels_stream.hip", "kernels_panel.hip", "kernels_attn.hip", "kernels_draft.hip", "kernels_dyn.hip", "clover_api.hip"]
+SOURCES = ["kernels_generic.hip", "kernels_mfma.hip", "kernels_stream.hip", "kernels_panel.hip", "kernels_tile.hip", "kernels_attn.hip", "kernels_draft.hip", "kernels_dyn.hip", "clover_api.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-value", "-I", os.path.join(ROOT, "include")]
 

@@ -100,6 +100,7 @@ struct clover_ctx {
   const void* lm_head_pk;
   bool fast;               // bf16 model on the MFMA path
   bool panel;              // full-K panel GEMM for the gate+up projection and the LM head
+  int tile_min = 129;      // passes of at least this many rows (up to 256) take the tiled GEMM: one weight pass
   int row_batch_max = 64;
   int row_batch = 64;      // rows per weight pass for passes of more than 64 rows: 128 when the panel kernel may take them  // passes of up to this many rows run through the <= 64-row GEMM kernels, in batches of 64
   // dynamic (score-pruned) tree: candidates, frontiers and the per-sequence topology tables
@@ -319,6 +320,15 @@ void carve(clover_ctx* x, char* base, size_t* total) {
         pbytes = std::max(pbytes, (size_t)sp * mtot * s.N * sizeof(float));
       }
     }
+    // 129..256 rows through the tiled kernel over K ranges: partial tiles of the whole pass
+    if (rows > 64) {
+      std::vector<GemmShape> shp;
+      model_gemm_shapes(c, shp);
+      const int rb = std::min(rows, 256);
+      for (const GemmShape& g : shp)
+        if (g.mode != 2 && tile_gemm_supported(rb, g.N, g.K, 0))
+          pbytes = std::max(pbytes, (size_t)tile_gemm_pick_k_parts(rb, g.N, g.K) * rb * g.N * sizeof(float));
+    }
     // 65..256 rows in batches of 64 through the K-slice kernel: partial tiles of the whole pass
     if (rows > 64 && !tune_int("CLOVER_NO_ROW_BATCH", 0)) {
       std::vector<GemmShape> shp;
@@ -338,6 +348,7 @@ void carve(clover_ctx* x, char* base, size_t* total) {
   x->panel = fast && !tune_int("CLOVER_NO_PANEL", 0);
   x->row_batch_max = (fast && !tune_int("CLOVER_NO_ROW_BATCH", 0)) ? 256 : 64;
   x->row_batch = (x->panel && !tune_int("CLOVER_ROW_BATCH_64", 0)) ? 128 : 64;
+  x->tile_min = fast ? tune_int("CLOVER_TILE_MIN", 129) : 1 << 30;
   x->kvdtype = fast ? 1 : 0;
   x->kv_layer_stride = fast ? 2 * x->k_layer_elems : x->k_layer_elems;
   x->attn_fast = fast && attn_mfma_supported(d, c.n_q_heads, c.n_kv_heads, c.max_seq);
@@ -393,6 +404,22 @@ int gemm_fast(clover_ctx* x, int cls, Planes X, int nseg, const void* const* W, 
     for (int s = 0; s < 3; ++s) {
       ws[s] = (const bf16_t*)(s < nseg ? W[s] : W[nseg - 1]);
       if (s < nseg) { segb[s] = off; off += seg_n[s]; }
+    }
+  }
+  // Many rows (tile_min..256): the tiled kernel, one pass over the weights for all rows; narrow outputs over K ranges.
+  if (!direct && M >= x->tile_min && M <= 256 && tile_gemm_supported(M, N, K, 0)) {
+    bool adjacent = true;
+    for (int s = 1; s < nseg; ++s) adjacent = adjacent && ws[s] == ws[s - 1] + (size_t)seg_n[s - 1] * K;
+    const int kp = tile_gemm_pick_k_parts(M, N, K);
+    if (adjacent && (size_t)kp * M * N * sizeof(float) <= x->partial_bytes) {
+      TileGemm g;
+      memset(&g, 0, sizeof(g));
+      g.Xhi = X.hi; g.Xlo = X.lo; g.ldx = X.ld;
+      g.W[0] = g.W[1] = ws[0];
+      g.Y = part; g.ldy = N; g.k_parts = kp; g.split_stride = (size_t)M * N;
+      g.M = M; g.N = N; g.K = K; g.epi = 0;
+      launch_gemm_tile(g, x->st);
+      return kp;
     }
   }
   // Long K into a narrow output (the down projection): K ranges of the panel kernel, a few partials instead of
@@ -523,7 +550,16 @@ void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMa
     { Scope s(x, KC_RMSNORM);
       launch_reduce_add_norm(xres, H, x->partial, sw, (size_t)M * H, H, lw.ffn_norm, c.dtype, c.rms_eps, A.hi, A.lo, H, M,
                              H, x->st); }
-    if (x->panel && M <= x->row_batch_max && panel_gemm_supported(std::min(M, 64), F, H, 1)) {
+    if (M >= x->tile_min && M <= 256 && tile_gemm_supported(M, F, H, 1)) {
+      Scope s(x, KC_GEMM_GATEUP);
+      TileGemm g;
+      memset(&g, 0, sizeof(g));
+      g.Xhi = A.hi; g.Xlo = A.lo; g.ldx = H;
+      g.W[0] = (const bf16_t*)lw.w_gate; g.W[1] = (const bf16_t*)lw.w_up;
+      g.Yhi = Hf.hi; g.Ylo = Hf.lo; g.ldo = F;
+      g.M = M; g.N = F; g.K = H; g.epi = 1; g.k_parts = 1;
+      launch_gemm_tile(g, x->st);
+    } else if (x->panel && M <= x->row_batch_max && panel_gemm_supported(std::min(M, 64), F, H, 1)) {
       Scope s(x, KC_GEMM_GATEUP);
       const int bm = (M > 64 && panel_gemm_supported(std::min(M, x->row_batch), F, H, 1)) ? x->row_batch : 64;
       for (int m0 = 0; m0 < M; m0 += bm) {  // (more than 64 rows: one weight pass per batch, see gemm_fast)
@@ -627,6 +663,16 @@ void run_fc(clover_ctx* x, const float* X, int K, const void* W, const void* bia
 // out[rows, vocab] = A * lm_head^T (MFMA path)
 void lm_head_fast(clover_ctx* x, Planes A, int rows, float* out) {
   const clover_config& c = x->cfg;
+  if (rows >= x->tile_min && rows <= 256 && tile_gemm_supported(rows, c.vocab, x->H, 0)) {
+    Scope s(x, KC_GEMM_LMHEAD);
+    TileGemm g;
+    memset(&g, 0, sizeof(g));
+    g.Xhi = A.hi; g.Xlo = A.lo; g.ldx = A.ld;
+    g.W[0] = g.W[1] = (const bf16_t*)x->lm_head_pk;
+    g.Y = out; g.ldy = c.vocab; g.M = rows; g.N = c.vocab; g.K = x->H; g.epi = 0; g.k_parts = 1;
+    launch_gemm_tile(g, x->st);
+    return;
+  }
   if (x->panel && rows <= x->row_batch_max && panel_gemm_supported(std::min(rows, 64), c.vocab, x->H, 0)) {
     Scope s(x, KC_GEMM_LMHEAD);
     const int bm = (rows > 64 && panel_gemm_supported(std::min(rows, x->row_batch), c.vocab, x->H, 0)) ? x->row_batch : 64;
@@ -1372,6 +1418,7 @@ size_t clover_op_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K) {
     size_t out = mfma_gemm_out_bytes(M, N, mfma_gemm_pick_splits(M, N, K, 0));
     if (stream_gemm_supported(M, N, K)) out = std::max(out, stream_gemm_out_bytes(M, N, K));
     out = std::max(out, (size_t)std::max(panel_gemm_pick_k_parts(M, N, K), 0) * M * N * sizeof(float));
+    if (tile_gemm_supported(M, N, K, 0)) out = std::max(out, (size_t)tile_gemm_pick_k_parts(M, N, K) * M * N * sizeof(float));
     bytes += align256((size_t)M * K * 4) + align256(out) + align256((size_t)N * K * 2);
   }
   return bytes;
@@ -1417,6 +1464,21 @@ int op_gemm_impl(int32_t path, int32_t dtype, const float* X, const void* W, flo
     if (path & 1) launch_pack_weight(W, wp, N, K, st);
     launch_split_planes(X, K, hi, lo, K, M, K, st);
     int splits;
+    if (path == 7) {   // tiled kernel over K ranges, then the sum of the ranges
+      if (!tile_gemm_supported(M, N, K, 0)) return fail(nullptr, CLOVER_E_SHAPE, "shape not supported by the tiled GEMM");
+      const int kp = tile_gemm_pick_k_parts(M, N, K);
+      TileGemm g;
+      memset(&g, 0, sizeof(g));
+      g.Xhi = hi; g.Xlo = lo; g.ldx = K;
+      g.W[0] = g.W[1] = wp;
+      g.Y = part; g.ldy = N; g.k_parts = kp; g.split_stride = (size_t)M * N;
+      g.M = M; g.N = N; g.K = K; g.epi = 0;
+      launch_gemm_tile(g, st);
+      launch_reduce(part, kp, (size_t)M * N, N, nullptr, dtype, Y, ldy, M, N, 0, st);
+      const hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return fail(nullptr, CLOVER_E_HIP, hipGetErrorString(e));
+      return CLOVER_OK;
+    }
     if (path >= 3) {
       if (!panel_gemm_supported(M, N, K, 0) || ldy % 4 != 0)
         return fail(nullptr, CLOVER_E_SHAPE, "shape not supported by the panel GEMM");

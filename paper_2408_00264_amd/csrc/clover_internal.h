@@ -189,6 +189,21 @@ bool panel_gemm_supported(int M, int N, int K, int epi);
 int panel_gemm_pick_k_parts(int M, int N, int K);
 void launch_gemm_panel(const PanelGemm& g, hipStream_t st);
 
+// ---- tiled GEMM for 65..256 rows: one weight pass, wavefronts tile rows x columns ------------------
+struct TileGemm {
+  const bf16_t *Xhi, *Xlo; int ldx;   // activation planes [M, K]
+  const bf16_t* W[2];                 // fragment-major; epi 1: W[0] = gate, W[1] = up, each [N, K]
+  float* Y; int ldy;                  // epi 0: fp32 [M, N]; range r of K writes Y + r * split_stride
+  bf16_t *Yhi, *Ylo; int ldo;         // epi 1: planes of silu(X W0^T) * (X W1^T), [M, N]
+  int M, N, K;
+  int epi;                            // 0 plain, 1 SwiGLU
+  int k_parts; size_t split_stride;   // epi 0 only
+  int dbg;                            // ablation builds only: 1 no activation staging, 2 no LDS reads, 4 no weight loads, 8 no barrier
+};
+bool tile_gemm_supported(int M, int N, int K, int epi);
+int tile_gemm_pick_k_parts(int M, int N, int K);
+void launch_gemm_tile(const TileGemm& g, hipStream_t st);
+
 // ---- fused bookkeeping kernels of the draft head (MFMA path, bf16 weights) ----------------------
 // planes of RMSNorm(hid[row]) * gain -> (a_hi, a_lo) and of the embedding of tok[row] -> (y_hi, y_lo), rows of `rm`
 void launch_draft_pre(const float* hid, const int* tok, const void* gain, float eps, const void* table, int vocab, int H,
