@@ -73,6 +73,28 @@ def test_p1_chain_equals_sequential_decoding():
     np.testing.assert_allclose(a.kv.v[:, :16], b.kv.v[:, :16], atol=1e-10)
 
 
+def test_p1_prefill_state_does_not_depend_on_the_chunking():
+    """Sec. 1 (prefill, then decode) with Sec. 3.1 / 3.3: whatever the pass size, a prompt leaves the same target
+    cache, the same augmenting-block cache (position i paired with token i+1, also across pass boundaries) and the
+    same first draft tree.  The GPU's prefill call is compared with the oracle at a different pass size on this basis."""
+    ws, cfg, W = make()
+    parent, rank = synth.tree_for(TINY)
+    prompt = np.random.default_rng(5).integers(0, TINY.vocab, 23)
+    outs = []
+    for chunk in (1, 5, 23):
+        seq = O.SeqState(cfg)
+        acc, (tokens, zs) = O.prefill(W, cfg, seq, prompt, chunk, parent, rank)
+        assert seq.L == 23 and seq.aug_L == 23
+        outs.append((seq, tokens, acc["new_tokens"][-1]))
+    ref = outs[-1]
+    for seq, tokens, first in outs[:-1]:
+        assert first == ref[2] and list(tokens) == list(ref[1])
+        np.testing.assert_allclose(seq.kv.k[:, :23], ref[0].kv.k[:, :23], atol=1e-10)
+        np.testing.assert_allclose(seq.kv.v[:, :23], ref[0].kv.v[:, :23], atol=1e-10)
+        np.testing.assert_allclose(seq.aug_kv.k[:, :23], ref[0].aug_kv.k[:, :23], atol=1e-10)
+        np.testing.assert_allclose(seq.aug_kv.v[:, :23], ref[0].aug_kv.v[:, :23], atol=1e-10)
+
+
 # ---------------------------------------------------------------- P2
 @pytest.mark.parametrize("seed", [0, 1])
 def test_p2_tree_equals_each_path_alone(seed):
