@@ -50,6 +50,7 @@ enum {
 #define CLOVER_MAX_NODES 128 /* upper bound on max_nodes (ancestor masks are 2 x 64 bit) */
 #define CLOVER_MAX_DEPTH 8   /* upper bound on draft_depths */
 #define CLOVER_MAX_RANK 16   /* ranks are < 16 */
+#define CLOVER_MAX_PREFILL_ROWS 256 /* upper bound on prefill_rows: one weight pass of the many-row GEMM */
 
 /* Model + capacity description.  Plain data, copied at init. */
 typedef struct {
@@ -63,6 +64,8 @@ typedef struct {
   int32_t draft_depths;  /* D: deepest tree level the draft head can fill (FC_0 .. FC_{D-1}) */
   int32_t max_batch, max_seq, max_nodes;
   int32_t flags;         /* CLOVER_FLAG_* */
+  int32_t prefill_rows;  /* prompt rows clover_prefill processes per pass (0: max_batch * max_nodes); the row buffers
+                            of the workspace are sized for max(max_batch * max_nodes, prefill_rows).  At most 256. */
 } clover_config;
 
 /* Static tree topology (Sec. 2.1: candidates merged on common prefixes form a tree).
@@ -207,6 +210,26 @@ int accept_and_compact_sampled(clover_ctx *ctx, int32_t batch, const int32_t *tr
 int clover_accept_forced(clover_ctx *ctx, int32_t batch, const int32_t *tree_tokens, const float *logits,
                          const float *hidden, const int32_t *n_rows, const int32_t *forced_next,
                          int32_t *m, int32_t *acc_idx, int32_t *new_tokens, float *hid_acc, int32_t *next_tok);
+
+/* Prefill of one sequence (Sec. 1: the prefill phase that precedes the decode phase; Sec. 3.1, 3.3: the
+ * Augmenting Block sees every earlier position paired with its follow-up token).  The n prompt tokens run through
+ * the target in passes of up to prefill_rows rows -- every GEMM one weight pass over all rows of the pass, causal
+ * attention over the cache and the pass's own rows, K/V written in place at slots len .. len+n-1 -- and the
+ * LM head runs on the LAST row only.  The draft side pairs position i with token i+1 for i < n-1 (Attention
+ * Decoder 1, then the Augmenting Block, causal over its own cache): n-1 rows appended there.  Afterwards
+ * len[b] += n; the caller picks the first generated token g from logits_last (next_tok_out holds the
+ * argmax, ties to the lower id), and a draft_tree call with m[b] = 1, hid_acc[b,0] = hid_last,
+ * next_tok[b,0] = g completes the hand-off exactly as after accept_and_compact.
+ *   b            sequence index, 0 <= b < max_batch
+ *   tokens       dev in  int32 [n]
+ *   n            number of prompt tokens, >= 1; len[b] + n <= max_seq
+ *   logits_last  dev out fp32 [vocab]: target logits after the last prompt token
+ *   hid_last     dev out fp32 [hidden]: its pre-final-norm hidden state
+ *   next_tok_out dev out int32 [1], may be null
+ * Enqueues on the context's stream; does not synchronise.  Errors: CLOVER_E_NULL, CLOVER_E_SHAPE (b, n),
+ * CLOVER_E_CAPACITY (max_seq). */
+int clover_prefill(clover_ctx *ctx, int32_t b, const int32_t *tokens, int32_t n, float *logits_last,
+                   float *hid_last, int32_t *next_tok_out);
 
 /* Synchronise and read the target cache lengths into out_host[max_batch]; refreshes the
  * host-side bound used by the capacity check.  Returns CLOVER_E_STATE if a device guard fired. */

@@ -22,7 +22,7 @@ STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = [
     "clover_workspace_bytes", "clover_init", "clover_destroy", "clover_reset", "clover_set_tree",
-    "draft_tree", "verify_tree", "accept_and_compact", "accept_and_compact_sampled", "clover_accept_forced", "clover_seq_len",
+    "draft_tree", "verify_tree", "accept_and_compact", "accept_and_compact_sampled", "clover_accept_forced", "clover_prefill", "clover_seq_len",
     "clover_read_kv", "clover_write_kv", "clover_set_seq_len", "clover_capture_draft_logits", "clover_set_dynamic_tree", "clover_read_dynamic_tree", "clover_path_info", "clover_profile_enable", "clover_profile_collect", "clover_kernel_class_count",
     "clover_kernel_class_name", "clover_last_error", "clover_last_global_error",
     "clover_op_gemm_scratch_bytes", "clover_op_gemm", "clover_op_gemm_static",
@@ -33,7 +33,7 @@ class Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "vocab")] + \
                [("rope_base", C.c_float), ("rms_eps", C.c_float)] + \
                [(n, C.c_int32) for n in ("dtype", "aug_layers", "ad_heads", "draft_depths", "max_batch", "max_seq",
-                                         "max_nodes", "flags")]
+                                         "max_nodes", "flags", "prefill_rows")]
 
 
 class Tree(C.Structure):
@@ -114,12 +114,12 @@ class CloverError(RuntimeError):
         self.code = code
 
 
-def make_config(shape, max_batch: int, max_seq: int, max_nodes: int, flags: int = 0) -> Config:
+def make_config(shape, max_batch: int, max_seq: int, max_nodes: int, flags: int = 0, prefill_rows: int = 0) -> Config:
     """Config from a synth.ModelShape-like object."""
     return Config(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn,
                   shape.vocab, float(shape.rope_base), float(shape.rms_eps),
                   DTYPE_BF16 if shape.bf16 else DTYPE_F32, shape.aug_layers, shape.ad_heads or shape.n_q_heads,
-                  shape.draft_depths, max_batch, max_seq, max_nodes, flags)
+                  shape.draft_depths, max_batch, max_seq, max_nodes, flags, prefill_rows)
 
 
 def _tree_struct(parent: Sequence[int], rank: Sequence[int]):
@@ -133,13 +133,13 @@ class Clover:
     """One library context plus the torch-owned device buffers of a speculative loop."""
 
     def __init__(self, shape, weights: Dict[str, "object"], parent, rank, max_batch: int, max_seq: int,
-                 max_nodes: int, flags: int = 0, device: str = "cuda:0"):
+                 max_nodes: int, flags: int = 0, device: str = "cuda:0", prefill_rows: int = 0):
         import torch
         self.torch = torch
         self.lib = load_library()
         self.shape = shape
         self.dev = torch.device(device)
-        self.cfg = make_config(shape, max_batch, max_seq, max_nodes, flags)
+        self.cfg = make_config(shape, max_batch, max_seq, max_nodes, flags, prefill_rows)
         self.B, self.R, self.H, self.V = max_batch, max_nodes, shape.hidden, shape.vocab
         self._w = weights                       # name -> device tensor (kept alive: the library borrows them)
         ptr = lambda n: C.c_void_p(weights[n].data_ptr())
@@ -360,6 +360,27 @@ class Clover:
                 else:
                     self.set_tree(parent, rank)
             self.draft_tree(B)
+
+    def prefill_prompt(self, b: int, tokens) -> None:
+        """clover_prefill for sequence b: `tokens` is a device int32 tensor; the last row's logits, hidden state
+        and argmax go to logits[b, 0], hid_acc[b, 0] and next_tok[b, 0]; m[b] is not touched."""
+        self._check(self.lib.clover_prefill(self.ctx, C.c_int32(b), C.c_void_p(tokens.data_ptr()), C.c_int32(tokens.numel()),
+                                            C.c_void_p(self.logits[b, 0].data_ptr()), C.c_void_p(self.hid_acc[b, 0].data_ptr()),
+                                            C.c_void_p(self.next_tok[b, 0].data_ptr())))
+
+    def prefill_prompts(self, prompts: List[np.ndarray], parent, rank, dynamic: Optional[tuple] = None) -> None:
+        """Prefill every prompt with clover_prefill (greedy first token), then one draft_tree call: the same
+        hand-off state as `prefill` leaves."""
+        torch = self.torch
+        B = len(prompts)
+        for b, p in enumerate(prompts):
+            self.prefill_prompt(b, torch.from_numpy(np.ascontiguousarray(p, dtype=np.int32)).to(self.dev))
+        self.m.fill_(1)
+        if dynamic is not None:
+            self.set_dynamic_tree(*dynamic)
+        else:
+            self.set_tree(parent, rank)
+        self.draft_tree(B)
 
     def step(self, batch: int) -> None:
         self.verify_tree(batch)

@@ -113,6 +113,7 @@ struct clover_ctx {
   // host-side bounds
   std::vector<int> len_ub, aug_ub;
   int m_upper;
+  bool only_prefills;   // no accept call since init / reset: every pending hand-off has m = 1
   // profiling
   bool prof = false;
   std::vector<ProfEvent> prof_events;
@@ -139,6 +140,7 @@ int check_config(const clover_config* c, std::string& why) {
   if (c->draft_depths < 1 || c->draft_depths > CLOVER_MAX_DEPTH) return bad("draft_depths out of range");
   if (c->max_batch < 1 || c->max_batch > 1024) return bad("max_batch out of range");
   if (c->max_nodes < 1 || c->max_nodes > CLOVER_MAX_NODES) return bad("max_nodes must be in [1, 128]");
+  if (c->prefill_rows < 0 || c->prefill_rows > CLOVER_MAX_PREFILL_ROWS) return bad("prefill_rows must be in [0, 256]");
   if (c->max_seq < c->max_nodes) return bad("max_seq smaller than max_nodes");
   if (!(c->rope_base > 1.f) || !(c->rms_eps > 0.f)) return bad("rope_base must be > 1 and rms_eps > 0");
   return CLOVER_OK;
@@ -234,7 +236,8 @@ void model_gemm_shapes(const clover_config& c, std::vector<GemmShape>& v) {
 void carve(clover_ctx* x, char* base, size_t* total) {
   const clover_config& c = x->cfg;
   Carver cv{base};
-  const int B = c.max_batch, R = c.max_nodes, rows = B * R, H = c.hidden, d = c.head_dim;
+  const int B = c.max_batch, R = c.max_nodes, H = c.hidden, d = c.head_dim;
+  const int rows = std::max(B * R, c.prefill_rows);   // row capacity of every activation buffer
   const size_t esz = c.dtype == CLOVER_DTYPE_F32 ? 4 : 2;
   x->R = R; x->max_rows = rows; x->H = H; x->esz = esz;
   x->kv_esz = 4;  // bytes per cached value in both formats
@@ -849,6 +852,7 @@ int accept_common(clover_ctx* x, int batch, const int* tree_tokens, const float*
   const TreeHost& t = x->tree;
   const int n_nodes = x->dyn_on ? x->dyn.N : t.n;
   const int R = x->R, M = (batch - 1) * R + n_nodes;
+  x->only_prefills = false;
   const int* fc_tab = x->dyn_on ? x->dyn.t_first_child : x->d_first_child;
   const int* nc_tab = x->dyn_on ? x->dyn.t_n_child : x->d_n_child;
   if (uniforms) {
@@ -948,6 +952,7 @@ int clover_init(const clover_config* cfg, const clover_weights* w, const clover_
   x->len_ub.assign(cfg->max_batch, 0);
   x->aug_ub.assign(cfg->max_batch, 0);
   x->m_upper = cfg->max_nodes;
+  x->only_prefills = true;
   // chain masks for the Augmenting Block's causal rows: row i sees new rows 0..i
   std::vector<unsigned long long> chain((size_t)2 * cfg->max_nodes, 0ull);
   for (int u = 0; u < cfg->max_nodes; ++u) {
@@ -1013,6 +1018,7 @@ int clover_reset(clover_ctx* x) {
   std::fill(x->len_ub.begin(), x->len_ub.end(), 0);
   std::fill(x->aug_ub.begin(), x->aug_ub.end(), 0);
   x->m_upper = x->cfg.max_nodes;
+  x->only_prefills = true;
   return finish(x, "reset");
 }
 
@@ -1297,6 +1303,77 @@ int clover_accept_forced(clover_ctx* x, int32_t batch, const int32_t* tree_token
   x->m_upper = x->tree.n;
   for (int b = 0; b < batch; ++b) x->len_ub[b] += x->tree.n;
   return CLOVER_OK;
+}
+
+int clover_prefill(clover_ctx* x, int32_t b, const int32_t* tokens, int32_t n, float* logits_last, float* hid_last,
+                   int32_t* next_tok_out) {
+  if (!x || !tokens || !logits_last || !hid_last) return fail(x, CLOVER_E_NULL, "null argument");
+  const clover_config& c = x->cfg;
+  if (b < 0 || b >= c.max_batch) return fail(x, CLOVER_E_SHAPE, "sequence index out of range");
+  if (n < 1) return fail(x, CLOVER_E_SHAPE, "a prompt has at least one token");
+  if (x->len_ub[b] + n > c.max_seq || x->aug_ub[b] + n - 1 > c.max_seq)
+    return fail(x, CLOVER_E_CAPACITY, "prompt would exceed max_seq (call clover_seq_len to refresh the bound)");
+  const int H = x->H;
+  const int P = std::min(x->max_rows, CLOVER_MAX_PREFILL_ROWS);   // rows per pass
+  // this sequence's part of the caches (both planes of a split cache move by the same element count) and lengths
+  const size_t seq_bytes = (size_t)c.max_seq * c.n_kv_heads * c.head_dim * (x->kvdtype ? 2 : 4);
+  int* len_b = x->d_seq_len + b;
+  int* aug_len_b = x->d_aug_len + b;
+  float* xres = x->d_xs;   // residual stream of the pass (the draft head's staging buffers are idle here)
+  for (int c0 = 0; c0 < n; c0 += P) {
+    const int M = std::min(P, n - c0);
+    const bool last = c0 + M == n;
+    const RowMap rm{1, P, M, nullptr};
+    // ---- target: embedding, layers with causal attention (no mask table: a chain), K/V in place ----
+    { Scope s(x, KC_EMBED); launch_embed(x->w.embed, c.dtype, tokens + c0, c.vocab, xres, H, H, rm, x->st); }
+    { Scope s(x, KC_ROPE_KV); launch_rope_table(len_b, nullptr, c.rope_base, c.head_dim, x->cos_t, x->sin_t, rm, x->st); }
+    if (x->fast) norm_planes(x, xres, x->layers[0].attn_norm, M);
+    const int key_bound = x->len_ub[b] + M;
+    for (int l = 0; l < c.n_layers; ++l)
+      run_layer(x, x->layers[l], xres, rm, M, x->kc + (size_t)l * x->k_layer_elems * x->kv_esz + b * seq_bytes,
+                x->vc + (size_t)l * x->v_layer_elems * x->kv_esz + b * seq_bytes, len_b, nullptr,
+                l + 1 < c.n_layers ? x->layers[l + 1].attn_norm : x->w.final_norm, key_bound);
+    { Scope s(x, KC_DRAFT_MISC); launch_add_scalar(len_b, M, x->st); }
+    x->len_ub[b] += M;
+    if (last) {
+      // LM head on the last row only; its hidden state is the hand-off row
+      if (x->fast) {
+        Planes A = planes_of(x, x->a_norm, 2 * H);
+        A.ld = H;
+        A.hi += (size_t)(M - 1) * H;
+        A.lo += (size_t)(M - 1) * H;
+        lm_head_fast(x, A, 1, logits_last);
+      } else {
+        { Scope s(x, KC_RMSNORM);
+          launch_rmsnorm(xres + (size_t)(M - 1) * H, H, x->w.final_norm, c.dtype, c.rms_eps, x->a_norm, H, H, 1, x->st); }
+        gemm_generic(x, KC_GEMM_LMHEAD, x->a_norm, H, x->w.lm_head, nullptr, logits_last, c.vocab, 1, c.vocab, H, 0);
+      }
+      hipMemcpyAsync(hid_last, xres + (size_t)(M - 1) * H, (size_t)H * sizeof(float), hipMemcpyDeviceToDevice, x->st);
+      if (next_tok_out) {
+        { Scope s(x, KC_TOPK); launch_topk(logits_last, c.vocab, c.vocab, 1, 1, x->cand, x->topk_ids, x->st); }
+        hipMemcpyAsync(next_tok_out, x->topk_ids, sizeof(int), hipMemcpyDeviceToDevice, x->st);
+      }
+    }
+    // ---- draft side: position i pairs with token i+1 (all but the prompt's last position, whose follow-up token
+    // does not exist yet): Attention Decoder 1, then the Augmenting Block over its own cache ----
+    const int Md = last ? M - 1 : M;
+    if (Md > 0) {
+      const RowMap rd{1, P, Md, nullptr};
+      { Scope s(x, KC_EMBED); launch_embed(x->w.lm_head, c.dtype, tokens + c0 + 1, c.vocab, x->d_e, H, H, rd, x->st); }
+      run_ad(x, x->w.ad1, xres, x->d_e, Md, x->xd);
+      { Scope s(x, KC_ROPE_KV); launch_rope_table(aug_len_b, nullptr, c.rope_base, c.head_dim, x->cos_t, x->sin_t, rd, x->st); }
+      if (x->fast) norm_planes(x, x->xd, x->aug[0].attn_norm, Md);
+      const int aug_bound = x->aug_ub[b] + Md;
+      for (int l = 0; l < c.aug_layers; ++l)
+        run_layer(x, x->aug[l], x->xd, rd, Md, x->aug_kc + (size_t)l * x->k_layer_elems * x->kv_esz + b * seq_bytes,
+                  x->aug_vc + (size_t)l * x->v_layer_elems * x->kv_esz + b * seq_bytes, aug_len_b, nullptr,
+                  l + 1 < c.aug_layers ? x->aug[l + 1].attn_norm : nullptr, aug_bound);
+      { Scope s(x, KC_DRAFT_MISC); launch_add_scalar(aug_len_b, Md, x->st); }
+      x->aug_ub[b] += Md;
+    }
+  }
+  if (x->only_prefills) x->m_upper = 1;
+  return finish(x, "clover_prefill");
 }
 
 int clover_seq_len(clover_ctx* x, int32_t* out_host) {

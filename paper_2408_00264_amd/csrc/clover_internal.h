@@ -80,6 +80,7 @@ void launch_draft_root(const float* a, const int* next_tok, const int* m, int B,
 void launch_draft_assign(const int* ids, const int* par_row, const int* rank, int c0, int c1, int n_par, int B, int R,
                          const int* m, int* tokens, hipStream_t st);
 void launch_add_len(int* len, const int* m, int B, hipStream_t st);
+void launch_add_scalar(int* p, int v, hipStream_t st);   // *p += v
 
 // ---- accept / compact -------------------------------------------------------------------------
 void launch_accept_walk(const int* argmax, const int* tokens, const int* first_child, const int* n_child, int n_nodes,

@@ -2,7 +2,9 @@
 //
 // For one sequence and one KV head, the G query heads that share it and the N tree nodes form
 // G*N query rows; they attend to the L cached keys (all visible) and to the N tree keys, of which
-// node u sees exactly those on its own root path (one bit per tree node in anc[u]).
+// node u sees exactly those on its own root path (one bit per tree node in anc[u]).  Without a mask table
+// (anc == null) the nodes form a chain of any length -- a prompt chunk: node u sees tree keys 0..u, and the key tiles
+// behind a node group's last row are skipped.
 //
 // Work split: a workgroup = (sequence, KV head, group of 32 nodes, range of 32-key tiles); its G
 // wavefronts are the G query heads.  K and V^T tiles are staged once per workgroup in LDS and
@@ -101,7 +103,8 @@ __global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
   const int L = p.base_len[b];
   if (ng * 32 >= nv || L + nv > p.max_seq) return;  // whole workgroup
   const int total = L + nv;
-  const int n_tiles = (total + AT_TK - 1) / AT_TK;
+  const bool chain = p.anc == nullptr;
+  const int n_tiles = ((chain ? min(total, L + ng * 32 + 32) : total) + AT_TK - 1) / AT_TK;
   const int t1 = min(n_tiles, t0 + p.tiles_per_split);
 
   // ---- Q fragments (already scaled and split by the RoPE kernel), ancestor masks ----
@@ -111,8 +114,8 @@ __global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
   for (int mb = 0; mb < AT_MB; ++mb) {
     const int node = ng * 32 + nsub + mb * 16 + l16;
     const bool ok = node < nv;
-    a0[mb] = ok ? p.anc[2 * ((size_t)b * p.anc_stride + node)] : 0ull;
-    a1[mb] = ok ? p.anc[2 * ((size_t)b * p.anc_stride + node) + 1] : 0ull;
+    a0[mb] = !ok ? 0ull : chain ? ~0ull : p.anc[2 * ((size_t)b * p.anc_stride + node)];
+    a1[mb] = !ok ? 0ull : chain ? ~0ull : p.anc[2 * ((size_t)b * p.anc_stride + node) + 1];
     const size_t qo = ((size_t)b * rm.R + (ok ? node : 0)) * p.ldq + head * AT_D + g4 * 8;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
@@ -183,7 +186,8 @@ __global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
         bool vis = CACHED || j < L;
         if (!CACHED && !vis && j < total) {
           const int wn = j - L;
-          vis = ((wn < 64 ? (a0[mb] >> wn) : (a1[mb] >> (wn - 64))) & 1ull) != 0ull;
+          if (chain) vis = wn <= ng * 32 + nsub + mb * 16 + l16;
+          else vis = ((wn < 64 ? (a0[mb] >> wn) : (a1[mb] >> (wn - 64))) & 1ull) != 0ull;
         }
         if (a0[mb] == 0ull && a1[mb] == 0ull) vis = false;  // padding row
         sv[e] = vis ? s[e >> 2][mb][e & 3] : -INFINITY;

@@ -328,6 +328,7 @@ void launch_rope_kv_write(const float* qkv, int ldqkv, int qkv_splits, size_t qk
 // ------------------------------------------------------------------------------------------
 // tree-masked attention, one wavefront per (row, q head).  Keys: cached slots [0,L) all visible,
 // then the rm.n new rows at slots L+w, visible iff bit w of the row's ancestor mask is set.
+// anc == null: the rows form a chain (row i sees new rows 0..i), any number of rows.
 // ------------------------------------------------------------------------------------------
 template <typename KT>
 __global__ void attn_generic_kernel(const float* __restrict__ q, int ldq, const KT* __restrict__ kc,
@@ -344,7 +345,9 @@ __global__ void attn_generic_kernel(const float* __restrict__ q, int ldq, const 
   const int L = base_len[b];
   if (L + nv > kv.max_seq) return;
   const size_t row = (size_t)b * rm.R + i;
-  const unsigned long long a0 = anc[2 * ((size_t)b * anc_stride + i)], a1 = anc[2 * ((size_t)b * anc_stride + i) + 1];
+  const bool chain = anc == nullptr;
+  const unsigned long long a0 = chain ? 0ull : anc[2 * ((size_t)b * anc_stride + i)];
+  const unsigned long long a1 = chain ? 0ull : anc[2 * ((size_t)b * anc_stride + i) + 1];
   const int g = h / (n_q / n_kv);
   const float scale = 1.0f / sqrtf((float)d);
   for (int c = lane; c < d; c += 64) qs[c] = q[row * ldq + h * d + c] * scale;
@@ -359,7 +362,7 @@ __global__ void attn_generic_kernel(const float* __restrict__ q, int ldq, const 
     bool vis = s < L;
     if (!vis && s < total) {
       const int w = s - L;
-      vis = ((w < 64 ? (a0 >> w) : (a1 >> (w - 64))) & 1ull) != 0ull;
+      vis = chain ? w <= i : ((w < 64 ? (a0 >> w) : (a1 >> (w - 64))) & 1ull) != 0ull;
     }
     float sc = -INFINITY;
     if (vis) {
@@ -703,6 +706,9 @@ __global__ void add_len_kernel(int* __restrict__ len, const int* __restrict__ m,
   if (b < B) len[b] += max(m[b], 0);
 }
 void launch_add_len(int* len, const int* m, int B, hipStream_t st) { add_len_kernel<<<(B + 63) / 64, 64, 0, st>>>(len, m, B); }
+
+__global__ void add_scalar_kernel(int* __restrict__ p, int v) { *p += v; }
+void launch_add_scalar(int* p, int v, hipStream_t st) { add_scalar_kernel<<<1, 1, 0, st>>>(p, v); }
 
 __global__ void fill_i32_kernel(int* p, int v, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;

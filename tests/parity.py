@@ -40,7 +40,8 @@ def bfs_tree_random(rng, n, max_depth, max_kids=4):
 class Lockstep:
     def __init__(self, shape, parent, rank, max_seq: int, flags: int = 0, gain_jitter: float = 0.0,
                  oracle_dtype=np.float64, max_nodes: Optional[int] = None, batch: int = 1,
-                 overrides: Optional[Dict[str, np.ndarray]] = None, dynamic: Optional[tuple] = None):
+                 overrides: Optional[Dict[str, np.ndarray]] = None, dynamic: Optional[tuple] = None,
+                 prefill_rows: int = 0):
         self.shape = shape
         self.dyn = dynamic                  # (n_nodes, topk, frontier): score-pruned tree, new topology per draft call
         self.parent = np.asarray(parent, np.int32)
@@ -52,7 +53,8 @@ class Lockstep:
         self.B = batch
         self.R = max_nodes or len(parent)
         self.dev_w = clover.upload_weights(self.store)
-        self.gpu = clover.Clover(shape, self.dev_w, self.parent, self.rank, batch, max_seq, self.R, flags)
+        self.gpu = clover.Clover(shape, self.dev_w, self.parent, self.rank, batch, max_seq, self.R, flags,
+                                 prefill_rows=prefill_rows)
         self.seqs = [O.SeqState(self.ocfg) for _ in range(batch)]
         self.parents = [self.parent for _ in range(batch)]      # topology per sequence (differs with a dynamic tree)
         self.score_tol = 5e-3 if shape.bf16 else 1e-4           # cumulative draft log-probabilities (up to D terms)
@@ -227,12 +229,22 @@ class Lockstep:
     def prefill(self, prompts: List[np.ndarray], chunk: int) -> None:
         g = self.gpu
         g.prefill(prompts, self.parent, self.rank, chunk, dynamic=self.dyn)
+        self._check_prefill(prompts, chunk)
+
+    def prefill_prompts(self, prompts: List[np.ndarray], oracle_chunk: int = 64) -> None:
+        """The library's own prefill call (many-row passes, causal attention, LM head on the last row only) against
+        the oracle's chunked chain prefill: the state after a prompt does not depend on how it was chunked."""
+        g = self.gpu
+        g.prefill_prompts(prompts, self.parent, self.rank, dynamic=self.dyn)
+        self._check_prefill(prompts, oracle_chunk, last_row=True)
+
+    def _check_prefill(self, prompts: List[np.ndarray], chunk: int, last_row: bool = False) -> None:
+        g = self.gpu
         g.torch.cuda.synchronize()
         toks = g.tree_tokens.cpu().numpy()
         lens = g.seq_len()
         for b, p in enumerate(prompts):
-            # oracle prefill, chunked the same way (right-aligned ragged first chunk does not matter
-            # to the result: a chain is plain decoding whatever the chunking)
+            # oracle prefill in chunks (a chain is plain decoding whatever the chunking)
             seq = self.seqs[b]
             n_chunks_b = (len(p) + chunk - 1) // chunk
             acc = None
@@ -250,6 +262,16 @@ class Lockstep:
                         assert gap <= self.tol, f"prefill bonus token: gpu {gpu_bonus} oracle {best} gap {gap:.3e}"
                         self.tie_events += 1
                     nxt_eff = gpu_bonus
+                    if last_row:
+                        # the prefill call hands back the last row's logits and hidden state: element by element
+                        got = g.logits[b, 0].cpu().numpy()
+                        err = float(np.abs(got - logits[len(part) - 1]).max())
+                        self.max_logit_err = max(self.max_logit_err, err)
+                        assert err <= self.tol, f"seq {b}: last-row logits max-abs error {err:.3e}"
+                        herr = float(np.abs(g.hid_acc[b, 0].cpu().numpy() - hidden[len(part) - 1]).max())
+                        self.max_hidden_err = max(self.max_hidden_err, herr)
+                        assert herr <= self.hidden_atol, f"seq {b}: last-row hidden state max-abs error {herr:.3e}"
+                        assert int(g.next_tok[b, 0]) == gpu_bonus
                 else:
                     nxt_eff = nxt
                 acc = O.accept_forced(seq, part, logits, hidden, len(part), nxt_eff)

@@ -34,7 +34,7 @@ def test_header_symbols_exported(lib):
 
 
 def test_struct_layout_matches_header():
-    assert C.sizeof(clover.Config) == 17 * 4
+    assert C.sizeof(clover.Config) == 18 * 4
     assert C.sizeof(clover.LayerWeights) == 9 * 8
     assert C.sizeof(clover.ADWeights) == 7 * 8
     assert C.sizeof(clover.Weights) == 8 * (4 + 7 + 7 + 1 + 2 + 2 + 1)
@@ -61,6 +61,10 @@ def test_workspace_bytes_and_config_errors(lib):
     assert lib.clover_workspace_bytes(C.byref(bad), C.byref(n)) == clover.E_CONFIG
     bad = _cfg(); bad.dtype = 5
     assert lib.clover_workspace_bytes(C.byref(bad), C.byref(n)) == clover.E_CONFIG
+    bad = _cfg(); bad.prefill_rows = 257
+    assert lib.clover_workspace_bytes(C.byref(bad), C.byref(n)) == clover.E_CONFIG
+    wide = _cfg(); wide.prefill_rows = 256     # row buffers sized for the prefill passes
+    assert lib.clover_workspace_bytes(C.byref(wide), C.byref(n)) == 0 and n.value > small
     # LLaMA3-8B-shaped batch-1 context: the fragment-major copy of every linear weight (16.1 GB, as large as
     # the weights themselves) plus a few hundred MB of caches and activations
     big = clover.make_config(synth.CONFIGS[3], 1, 2048, 64)

@@ -86,11 +86,12 @@ def test_op_gemm(path, dtype, M, N, K):
 # ------------------------------------------------------------------------------------------
 # whole calls, lock-step with the oracle
 # ------------------------------------------------------------------------------------------
-def _lockstep(shape, flags=0, gain_jitter=0.0, batch=1, max_seq=256, tree=None, max_nodes=None, dynamic=None):
+def _lockstep(shape, flags=0, gain_jitter=0.0, batch=1, max_seq=256, tree=None, max_nodes=None, dynamic=None,
+              prefill_rows=0):
     from tests.parity import Lockstep
     parent, rank = tree if tree is not None else synth.tree_for(shape)
     return Lockstep(shape, parent, rank, max_seq, flags=flags, gain_jitter=gain_jitter, batch=batch,
-                    max_nodes=max_nodes, dynamic=dynamic)
+                    max_nodes=max_nodes, dynamic=dynamic, prefill_rows=prefill_rows)
 
 
 def test_config1_fp32_eight_steps():
@@ -587,6 +588,81 @@ def test_full_width_two_layers(cfg, batch):
         ms = ls.step()
         say(f"  step {s}: m={ms} max|dlogit|={ls.max_logit_err:.3e} ties={ls.tie_events}")
     assert ls.max_logit_err <= 3e-2
+
+
+# ------------------------------------------------------------------------------------------
+# the prefill call: many-row passes with causal attention, LM head on the last row only (Sec. 1, 3.1, 3.3)
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("flags,prefill_rows,lengths", [
+    (0, 128, [300, 77]),                       # 128 + 128 + 44 rows; a prompt shorter than one pass
+    (0, 256, [600, 1]),                        # 256 + 256 + 88 rows; a one-token prompt (no draft-side row)
+    (0, 0, [50, 24]),                          # no extra capacity: passes of max_batch * max_nodes = 48 rows
+    (clover.FLAG_GENERIC, 96, [200, 96]),      # the plain fp32 kernels; a prompt of exactly one pass
+], ids=["mfma_128", "mfma_256", "mfma_default_rows", "generic_96"])
+def test_prefill_call_mini_bf16(flags, prefill_rows, lengths):
+    _torch()
+    shape = synth.scaled(MINI, batch=2, seed=41)
+    ls = _lockstep(shape, flags=flags, gain_jitter=0.1, batch=2, max_seq=768, prefill_rows=prefill_rows)
+    rng = np.random.default_rng(7)
+    prompts = [rng.integers(0, shape.vocab, size=n).astype(np.int32) for n in lengths]
+    say(f"prefill call, flags={flags}, rows per pass {prefill_rows or 48}: prompts {lengths}")
+    ls.prefill_prompts(prompts, oracle_chunk=64)
+    say(f"  after prefill: max|dlogit|={ls.max_logit_err:.2e} max|dKV|={ls.max_kv_err:.2e} max|dhid|={ls.max_hidden_err:.2e}")
+    for s in range(3):
+        ms = ls.step()
+        say(f"  step {s}: m={ms} max|dlogit|={ls.max_logit_err:.2e} ties={ls.tie_events}")
+    assert ls.max_logit_err <= 3e-2
+
+
+def test_prefill_call_config1_fp32():
+    _torch()
+    ls = _lockstep(TINY, max_seq=256, prefill_rows=40)
+    prompts = synth.make_prompts(TINY)
+    say("config 1: prefill call, 64 tokens in passes of 40 rows")
+    ls.prefill_prompts(prompts, oracle_chunk=16)
+    for s in range(4):
+        ms = ls.step()
+        say(f"  step {s}: m={ms} max|dlogit|={ls.max_logit_err:.2e}")
+    assert ls.max_logit_err <= 1e-4
+
+
+def test_prefill_call_full_width_two_layers():
+    """The prefill call at the LLaMA3-8B widths (two layers): a 600-token prompt in passes of 256 rows through the
+    many-row GEMM, causal attention over eight node groups, then two speculative steps on top."""
+    _torch()
+    O = __import__("oracle.clover2_oracle", fromlist=["x"])
+    shape = synth.scaled(synth.CONFIGS[3], name="wide-3-prefill", n_layers=2, seed=43)
+    ls = _lockstep(shape, max_seq=768, prefill_rows=256)
+    assert ls.gpu.path_info() & 3 == 3
+    ls.ocfg.dtype = np.float32
+    ls.W = O.Weights(ls.store.get_f32, np.float32)
+    ls.seqs = [O.SeqState(ls.ocfg)]
+    rng = np.random.default_rng(9)
+    prompts = [rng.integers(0, shape.vocab, size=600).astype(np.int32)]
+    ls.prefill_prompts(prompts, oracle_chunk=128)
+    say(f"  after prefill: max|dlogit|={ls.max_logit_err:.2e} max|dKV|={ls.max_kv_err:.2e} max|dhid|={ls.max_hidden_err:.2e}")
+    for s in range(2):
+        ms = ls.step()
+        say(f"  step {s}: m={ms} max|dlogit|={ls.max_logit_err:.3e} ties={ls.tie_events}")
+    assert ls.max_logit_err <= 3e-2
+
+
+def test_prefill_call_argument_errors():
+    _torch()
+    torch = _torch()
+    ls = _lockstep(MINI, max_seq=128, prefill_rows=64)
+    g = ls.gpu
+    toks = torch.zeros(200, dtype=torch.int32, device=g.dev)
+    out = [C.c_void_p(t.data_ptr()) for t in (g.logits[0, 0], g.hid_acc[0, 0], g.next_tok[0, 0])]
+    assert g.lib.clover_prefill(g.ctx, 1, C.c_void_p(toks.data_ptr()), 10, *out) == clover.E_SHAPE      # sequence 1 of 1
+    assert g.lib.clover_prefill(g.ctx, 0, None, 10, *out) == clover.E_NULL
+    assert g.lib.clover_prefill(g.ctx, 0, C.c_void_p(toks.data_ptr()), 0, *out) == clover.E_SHAPE       # empty prompt
+    with pytest.raises(clover.CloverError) as e:
+        g.prefill_prompt(0, toks[:129])
+    assert e.value.code == clover.E_CAPACITY
+    with pytest.raises(clover.CloverError) as e:
+        clover.Clover(MINI, ls.dev_w, ls.parent, ls.rank, 1, 128, 24, prefill_rows=257)
+    assert e.value.code == clover.E_CONFIG
 
 
 # ------------------------------------------------------------------------------------------
