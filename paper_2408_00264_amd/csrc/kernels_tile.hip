@@ -218,6 +218,276 @@ void launch_tile_one(const TileGemm& g, int wgs, hipStream_t st) {
   gemm_tile_kernel<MQ, EPI><<<wgs, MQ * TL_NW * 64, lds, st>>>(g);
 }
 
+
+// ------------------------------------------------------------------------------------------
+// Wide form: workgroup tile 128 rows x 256 columns, four wavefronts (one per SIMD), wavefront tile 128 x 64.
+//
+// Why.  In the 256 x 128 form above a compute unit moves, per 64-column K stage, 64 KB of activations and 64 KB of
+// weight fragments through its vector L1 (every weight fragment is fetched by the four wavefronts of the four row
+// quarters): at 64 B/clk that is exactly as long as the stage's 2048 matrix-pipe cycles, so nothing overlaps for
+// free.  A 128 x 256 tile needs half the activation rows per column and lets every wavefront own its columns:
+// per stage 32 KB of activations + 32 KB of weight fragments (each fetched once) pass the L1, the LDS serves 128 KB of
+// fragment reads and takes 32 KB of stores (62 % of the stage).  One wavefront per SIMD has the 512-register budget
+// that the software pipeline needs: 128 accumulators, two sets of 16 activation fragments (the next k-tile's
+// fragments are read from the LDS while this one is multiplied), a ring of four k-tiles of weight fragments in
+// flight, one stage of activations on its way from global memory to the LDS.  Three stage buffers: the stage two
+// ahead is stored while the next one is already being read, one barrier per stage.
+// Rows beyond 128 are a second workgroup on the same columns; it is placed next to the first one on the same XCD
+// (workgroup ids 8 apart) so that one of the two finds the weight fragments in that XCD's L2.
+// ------------------------------------------------------------------------------------------
+constexpr int TW_ROWS = 128;          // rows per workgroup
+constexpr int TW_NW = 4;              // wavefronts, 64 output columns each
+constexpr int TW_PLANE = TW_ROWS * TL_LDK;
+constexpr int TW_BUF = 2 * TW_PLANE;  // hi and lo plane of one stage
+constexpr int TW_NBUF = 3;
+constexpr int TW_XIT = 2 * TW_ROWS * (TL_KST / 8) / (TW_NW * 64);   // 16-byte pieces per thread and stage (= 8)
+
+template <int EPI>
+__global__ __launch_bounds__(TW_NW * 64) void gemm_tile_wide_kernel(TileGemm p) {
+  extern __shared__ __attribute__((aligned(16))) bf16_t xs[];   // [3 buffers][hi, lo][128][TL_LDK]
+  constexpr int NT = TW_NW * 64;
+  const int tid = threadIdx.x, wn = tid >> 6, lane = tid & 63;
+  const int l16 = lane & 15, g4 = lane >> 4;
+  const int KT = p.K / 32;
+  // workgroup id -> (row half, column tile, K range): ids 8 apart share an XCD, so the two row halves of a tile are
+  // the neighbours (2j, 2j + 1) in that XCD's own order
+  const int halves = p.M > TW_ROWS ? 2 : 1;
+  int rh = 0, unit = (int)blockIdx.x;
+  if (halves == 2) {
+    const int xcd = (int)blockIdx.x & 7, j = (int)blockIdx.x >> 3;
+    rh = j & 1;
+    unit = (j >> 1) * 8 + xcd;
+  }
+  if (unit >= p.n_units) return;   // (grid rounded up to whole XCD rows; uniform over the workgroup)
+  const int part = unit % p.k_parts, tile = unit / p.k_parts;
+  const int NS = p.K / TL_KST / p.k_parts;             // stages of this workgroup's K range
+  const int ks0 = part * NS;
+  const int row0 = rh * TW_ROWS;
+
+  const bf16_t* wbase[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    int nb;
+    if (EPI == 1) {   // 32 columns of F per wavefront: blocks 0,1 gate rows, blocks 2,3 the up rows of the same columns
+      nb = min((tile * TW_NW + wn) * 2 + (c & 1), p.N / 16 - 1);
+      wbase[c] = p.W[c >> 1] + (size_t)nb * KT * 512 + lane * 8;
+    } else {
+      nb = min((tile * TW_NW + wn) * 4 + c, p.N / 16 - 1);
+      wbase[c] = p.W[0] + (size_t)nb * KT * 512 + lane * 8;
+    }
+  }
+
+  f32x4 acc[4][8];   // [column block][row block]
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+#pragma unroll
+    for (int rb = 0; rb < 8; ++rb) acc[c][rb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  constexpr int RING = 4;
+  Frag w[RING][4];      // [k-tile modulo 4][column block]
+  Frag xa[8], xb[8];    // activation fragments of row blocks 0..3 / 4..7 of a k-tile: [row block][hi, lo]
+  u32x4 xv[TW_XIT];
+  const int n_kt = NS * 2;
+
+  auto load_w = [&](auto tc, int kt) {
+    constexpr int t = decltype(tc)::value;
+    const size_t off = (size_t)(ks0 * 2 + kt) * 512;
+    if (CLV_DBG(p, 4) && kt > 3) return;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) w[t][c].u = __builtin_nontemporal_load((const u32x4*)(wbase[c] + off));
+  };
+  // rows past M read row M - 1 again: an output row depends on its own activation row only, and the epilogue
+  // never stores rows >= M, so their accumulators may hold anything
+  const bf16_t* xsrc[TW_XIT];
+#pragma unroll
+  for (int it = 0; it < TW_XIT; ++it) {
+    const int idx = it * NT + tid;
+    const int rp = idx / (TL_KST / 8), sl = idx % (TL_KST / 8), plane = rp / TW_ROWS, r = rp % TW_ROWS;
+    xsrc[it] = (plane ? p.Xlo : p.Xhi) + (size_t)min(row0 + r, p.M - 1) * p.ldx + ks0 * TL_KST + sl * 8;
+  }
+  auto x_load = [&](int s) {
+    if (CLV_DBG(p, 1) && s > 1) return;
+#pragma unroll
+    for (int it = 0; it < TW_XIT; ++it) xv[it] = *(const u32x4*)(xsrc[it] + s * TL_KST);
+  };
+  auto x_store = [&](int b) {
+    if (CLV_DBG(p, 16)) return;
+#pragma unroll
+    for (int it = 0; it < TW_XIT; ++it) {
+      const int idx = it * NT + tid;
+      const int rp = idx / (TL_KST / 8), sl = idx % (TL_KST / 8), plane = rp / TW_ROWS, r = rp % TW_ROWS;
+      *(u32x4*)(xs + b * TW_BUF + plane * TW_PLANE + r * TL_LDK + sl * 8) = xv[it];
+    }
+  };
+  // fragments of row blocks 4 q .. 4 q + 3 of k-tile `half` of the stage in buffer b
+  auto frag_load = [&](Frag (&xf)[8], int b, int half, int q) {
+    const bf16_t* hi = xs + b * TW_BUF + (q * 64 + l16) * TL_LDK + g4 * 8 + half * 32;
+    if (CLV_DBG(p, 2)) return;
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb) {
+      xf[2 * rb].u = *(const u32x4*)(hi + rb * 16 * TL_LDK);
+      xf[2 * rb + 1].u = *(const u32x4*)(hi + TW_PLANE + rb * 16 * TL_LDK);
+    }
+  };
+  // 32 matrix instructions: row blocks 4 q .. 4 q + 3 (fragments xf) against the four weight fragments of ring slot t
+  auto mult = [&](auto tc, auto qc, const Frag (&xf)[8]) {
+    constexpr int t = decltype(tc)::value, q = decltype(qc)::value;
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) acc[c][4 * q + rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[t][c].v, xf[2 * rb + 1].v, acc[c][4 * q + rb], 0, 0, 0);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) acc[c][4 * q + rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[t][c].v, xf[2 * rb].v, acc[c][4 * q + rb], 0, 0, 0);
+    }
+  };
+
+  // ---- prologue: weight ring, stages 0 and 1 in the LDS, stage 2 in registers, the first fragments ----
+  load_w(std::integral_constant<int, 0>{}, 0);
+  if (n_kt > 1) load_w(std::integral_constant<int, 1>{}, 1);
+  if (n_kt > 2) load_w(std::integral_constant<int, 2>{}, 2);
+  x_load(0);
+  x_store(0);
+  if (NS > 1) { x_load(1); x_store(1); }
+  if (NS > 2) x_load(2);
+  __syncthreads();
+  frag_load(xa, 0, 0, 0);
+
+  // One stage = two k-tiles = four groups of 32 matrix instructions (row blocks 0..3 / 4..7 of each k-tile); while
+  // one group is multiplied the next group's fragments are read from the LDS into the other fragment set.  Around
+  // them: the activations of stage st + 2 (in registers since the previous stage) go to the LDS and stage st + 3 is
+  // requested (first group), the weights of k-tiles 2 st + 3 and 2 st + 4 are requested (second and third group).
+  // With one wavefront per SIMD nothing else hides the issue of these instructions, so in the FULL stages (every
+  // load unconditional: straight-line code) the group barriers spread them between the matrix instructions.
+  constexpr int G_MFMA = 0x008, G_VMEM = 0x020, G_DSR = 0x100, G_DSW = 0x200;
+  using Q0 = std::integral_constant<int, 0>;
+  using Q1 = std::integral_constant<int, 1>;
+  auto stage = [&](auto w0, auto w1, auto w3, auto fullc, int st, int b /* st % 3 */) {
+    // w0, w1: ring slots of this stage's k-tiles; w3: slot of k-tile 2 st + 3; k-tile 2 st + 4 reuses w0
+    constexpr bool FULL = decltype(fullc)::value;
+    const int b1 = b == TW_NBUF - 1 ? 0 : b + 1, b2 = b1 == TW_NBUF - 1 ? 0 : b1 + 1;
+    // group 0
+    if (FULL || st + 2 < NS) x_store(b2);
+    if (FULL || st + 3 < NS) x_load(st + 3);
+    frag_load(xb, b, 0, 1);
+    mult(w0, Q0{}, xa);
+    if constexpr (FULL) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        __builtin_amdgcn_sched_group_barrier(G_MFMA, 1, 0); __builtin_amdgcn_sched_group_barrier(G_DSW, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(G_MFMA, 1, 0); __builtin_amdgcn_sched_group_barrier(G_DSR, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(G_MFMA, 1, 0); __builtin_amdgcn_sched_group_barrier(G_VMEM, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(G_MFMA, 8, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // group 1
+    if (FULL || 2 * st + 3 < n_kt) load_w(w3, 2 * st + 3);
+    frag_load(xa, b, 1, 0);
+    mult(w0, Q1{}, xb);
+    if constexpr (FULL) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        __builtin_amdgcn_sched_group_barrier(G_MFMA, 2, 0); __builtin_amdgcn_sched_group_barrier(G_DSR, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(G_MFMA, 2, 0); __builtin_amdgcn_sched_group_barrier(G_DSR, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(G_MFMA, 1, 0); __builtin_amdgcn_sched_group_barrier(G_VMEM, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(G_MFMA, 12, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // group 2
+    if (FULL || 2 * st + 4 < n_kt) load_w(w0, 2 * st + 4);
+    frag_load(xb, b, 1, 1);
+    mult(w1, Q0{}, xa);
+    if constexpr (FULL) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        __builtin_amdgcn_sched_group_barrier(G_MFMA, 2, 0); __builtin_amdgcn_sched_group_barrier(G_DSR, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(G_MFMA, 2, 0); __builtin_amdgcn_sched_group_barrier(G_DSR, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(G_MFMA, 1, 0); __builtin_amdgcn_sched_group_barrier(G_VMEM, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(G_MFMA, 12, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // group 3
+    if (FULL || st + 1 < NS) frag_load(xa, b1, 0, 0);
+    mult(w1, Q1{}, xb);
+    if constexpr (FULL) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { __builtin_amdgcn_sched_group_barrier(G_MFMA, 3, 0); __builtin_amdgcn_sched_group_barrier(G_DSR, 1, 0); }
+      __builtin_amdgcn_sched_group_barrier(G_MFMA, 8, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (!CLV_DBG(p, 8)) __syncthreads();
+  };
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  using I2 = std::integral_constant<int, 2>;
+  using I3 = std::integral_constant<int, 3>;
+  int st = 0, b = 0;
+  for (; st + 4 < NS; st += 2) {   // two stages = four k-tiles per iteration: static ring slots
+    stage(I0{}, I1{}, I3{}, std::true_type{}, st, b);
+    b = b == TW_NBUF - 1 ? 0 : b + 1;
+    stage(I2{}, I3{}, I1{}, std::true_type{}, st + 1, b);
+    b = b == TW_NBUF - 1 ? 0 : b + 1;
+  }
+  for (; st < NS; st += 2) {
+    stage(I0{}, I1{}, I3{}, std::false_type{}, st, b);
+    b = b == TW_NBUF - 1 ? 0 : b + 1;
+    if (st + 1 < NS) stage(I2{}, I3{}, I1{}, std::false_type{}, st + 1, b);
+    b = b == TW_NBUF - 1 ? 0 : b + 1;
+  }
+
+  // ---- epilogue: lane holds rows rb*16 + l16 of the tile, columns 4*g4 .. 4*g4+3 of each block ----
+  if (EPI == 1) {
+    const int fblock = (tile * TW_NW + wn) * 2;
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      if ((fblock + c) * 16 >= p.N) continue;
+      const int col = (fblock + c) * 16 + 4 * g4;
+#pragma unroll
+      for (int rb = 0; rb < 8; ++rb) {
+        const int m = row0 + rb * 16 + l16;
+        if (m >= p.M) continue;
+        unsigned h[4], l[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float g = acc[c][rb][r], u = acc[c + 2][rb][r];
+          const float o = g / (1.0f + expf(-g)) * u;
+          h[r] = t_rn(o);
+          l[r] = t_rn(o - __uint_as_float(h[r] << 16));
+        }
+        *(uint2*)(p.Yhi + (size_t)m * p.ldo + col) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+        *(uint2*)(p.Ylo + (size_t)m * p.ldo + col) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
+      }
+    }
+  } else {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int blk = (tile * TW_NW + wn) * 4 + c;
+      if (blk * 16 >= p.N) continue;
+      const int col = blk * 16 + 4 * g4;
+#pragma unroll
+      for (int rb = 0; rb < 8; ++rb) {
+        const int m = row0 + rb * 16 + l16;
+        const f32x4 v = acc[c][rb];
+        if (m < p.M) *(float4*)(p.Y + part * p.split_stride + (size_t)m * p.ldy + col) = make_float4(v[0], v[1], v[2], v[3]);
+      }
+    }
+  }
+}
+
+template <int EPI>
+void launch_tile_wide(const TileGemm& g, int wgs, hipStream_t st) {
+  constexpr size_t lds = (size_t)TW_NBUF * TW_BUF * sizeof(bf16_t);
+  static_assert(lds <= 160 * 1024, "stage buffers exceed the LDS");
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipFuncSetAttribute((const void*)gemm_tile_wide_kernel<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    attr_done = true;
+  }
+  gemm_tile_wide_kernel<EPI><<<wgs, TW_NW * 64, lds, st>>>(g);
+}
+
 }  // namespace
 
 // N: output columns (EPI 1: the FFN width F with W[0] = gate, W[1] = up, each [F, K]); k_parts divides K / 64
@@ -235,10 +505,28 @@ int tile_gemm_pick_k_parts(int M, int N, int K) {
   return best;
 }
 
+// wide form: column tiles of 256 (epi 1: 128 columns of F), one or two row halves
+int tile_wide_pick_k_parts(int M, int N, int K) {
+  const int tiles = (N / 16 + 15) / 16 * (M > TW_ROWS ? 2 : 1), NS = K / TL_KST;
+  int best = 1;
+  for (int d = 1; d <= NS; ++d)
+    if (NS % d == 0 && tiles * d <= 256 && NS / d >= 8) best = d;
+  return best;
+}
+
 void launch_gemm_tile(const TileGemm& g_in, hipStream_t st) {
   TileGemm g = g_in;
   g.dbg = tune_int("CLOVER_TILE_DBG", 0);
   if (g.k_parts < 1 || g.epi == 1) g.k_parts = 1;
+  if (g.wide) {
+    const int blocks = g.N / 16;
+    const int tiles = g.epi == 1 ? (blocks + 7) / 8 : (blocks + 15) / 16;
+    g.n_units = tiles * g.k_parts;
+    const int wgs = g.M > TW_ROWS ? (g.n_units + 7) / 8 * 8 * 2 : g.n_units;
+    if (g.epi == 1) launch_tile_wide<1>(g, wgs, st);
+    else launch_tile_wide<0>(g, wgs, st);
+    return;
+  }
   const int blocks = g.N / 16;
   const int tiles = g.epi == 1 ? (blocks + 3) / 4 : (blocks + 7) / 8;   // 64 columns of F (gate + up) or 128 columns
   const int wgs = tiles * g.k_parts;

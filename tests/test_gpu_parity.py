@@ -44,6 +44,9 @@ GEMM_CASES = [
     # tiled kernel (one weight pass for up to 256 rows): full, ragged rows in every 64-row quarter, narrow and odd widths
     (7, 1, 256, 4096, 4096), (7, 1, 160, 6144, 4096), (7, 1, 97, 4096, 14336), (7, 1, 33, 1040, 512), (7, 1, 200, 8208, 1024),
     (7, 1, 256, 28672, 4096),
+    # its 128-row x 256-column form: two row halves, a ragged second half, one half only, odd widths, K ranges, one stage
+    (9, 1, 256, 4096, 4096), (9, 1, 160, 6144, 4096), (9, 1, 129, 4096, 14336), (9, 1, 97, 1040, 512), (9, 1, 200, 8208, 1024),
+    (9, 1, 256, 28672, 4096), (9, 1, 255, 512, 128), (9, 1, 256, 2064, 384),
 ]
 
 
