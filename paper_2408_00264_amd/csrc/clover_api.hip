@@ -101,6 +101,7 @@ struct clover_ctx {
   bool fast;               // bf16 model on the MFMA path
   bool panel;              // full-K panel GEMM for the gate+up projection and the LM head
   int tile_wide = 1;       // 129..256 rows: the 128 x 256 form of the tiled GEMM
+  int tile_min_kp = 65;    // narrow outputs over K ranges take the tiled GEMM's 128 x 256 form from this many rows on
   int tile_min = 129;      // passes of at least this many rows (up to 256) take the tiled GEMM: one weight pass
   int row_batch_max = 64;
   int row_batch = 64;      // rows per weight pass for passes of more than 64 rows: 128 when the panel kernel may take them  // passes of up to this many rows run through the <= 64-row GEMM kernels, in batches of 64
@@ -355,6 +356,7 @@ void carve(clover_ctx* x, char* base, size_t* total) {
   x->row_batch = (x->panel && !tune_int("CLOVER_ROW_BATCH_64", 0)) ? 128 : 64;
   x->tile_min = fast ? tune_int("CLOVER_TILE_MIN", 129) : 1 << 30;
   x->tile_wide = tune_int("CLOVER_TILE_WIDE", 1);
+  x->tile_min_kp = fast && x->tile_wide ? tune_int("CLOVER_TILE_MIN_KP", 65) : 1 << 30;
   x->kvdtype = fast ? 1 : 0;
   x->kv_layer_stride = fast ? 2 * x->k_layer_elems : x->k_layer_elems;
   x->attn_fast = fast && attn_mfma_supported(d, c.n_q_heads, c.n_kv_heads, c.max_seq);
@@ -412,8 +414,9 @@ int gemm_fast(clover_ctx* x, int cls, Planes X, int nseg, const void* const* W, 
       if (s < nseg) { segb[s] = off; off += seg_n[s]; }
     }
   }
-  // Many rows (tile_min..256): the tiled kernel, one pass over the weights for all rows; narrow outputs over K ranges.
-  if (!direct && M >= x->tile_min && M <= 256 && tile_gemm_supported(M, N, K, 0)) {
+  // Many rows (65..256: this route writes partials over K ranges, where the tiled kernel's 128-row form already beats
+  // the panel kernel's K-range form from 65 rows on): one pass over the weights for all rows.
+  if (!direct && M >= std::min(x->tile_min, x->tile_min_kp) && M <= 256 && tile_gemm_supported(M, N, K, 0)) {
     bool adjacent = true;
     for (int s = 1; s < nseg; ++s) adjacent = adjacent && ws[s] == ws[s - 1] + (size_t)seg_n[s - 1] * K;
     const int kp = x->tile_wide ? tile_wide_pick_k_parts(M, N, K) : tile_gemm_pick_k_parts(M, N, K);
