@@ -122,6 +122,38 @@ def ancestor_matrix(parent: Sequence[int]) -> np.ndarray:
     return a
 
 
+def interval_labels(parent: Sequence[int]):
+    """Linear-size tree mask (Appendix A.1: the mask relation is confirmed by numerical comparison instead of a
+    2-D matrix; the paper's figure is not available, this is the reading taken): two integers per node from a
+    depth-first numbering, enter[u] = the step at which u is first visited (children in index order),
+    exit[u] = the largest enter value inside u's subtree.  Then w is u or an ancestor of u exactly when
+    enter[w] <= enter[u] <= exit[w]."""
+    n = len(parent)
+    kids = children_of(parent)
+    enter = np.zeros(n, dtype=np.int64)
+    exit_ = np.zeros(n, dtype=np.int64)
+    clock = 0
+    stack = [(0, 0)]           # (node, index of the next child to visit)
+    enter[0] = 0
+    while stack:
+        u, i = stack.pop()
+        if i < len(kids[u]):
+            stack.append((u, i + 1))
+            c = kids[u][i]
+            clock += 1
+            enter[c] = clock
+            stack.append((c, 0))
+        else:
+            exit_[u] = clock
+    return enter, exit_
+
+
+def mask_from_intervals(enter: np.ndarray, exit_: np.ndarray) -> np.ndarray:
+    """The 2-D tree mask rebuilt from the interval labels: A[u, w] = enter[w] <= enter[u] <= exit[w]."""
+    e = np.asarray(enter)
+    return (e[None, :] <= e[:, None]) & (e[:, None] <= np.asarray(exit_)[None, :])
+
+
 def children_of(parent: Sequence[int]) -> List[List[int]]:
     ch: List[List[int]] = [[] for _ in parent]
     for u in range(1, len(parent)):

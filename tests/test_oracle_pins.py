@@ -922,3 +922,45 @@ def test_p12_leaf_draw_inverts_the_cumulative_sum():
                 want = t
                 break
         assert bonus == want
+
+
+# ---------------------------------------------------------------- P13: linear-size tree mask (Appendix A.1)
+def test_p13_interval_labels_rebuild_the_tree_mask():
+    """The two-integers-per-node labels give exactly the 2-D tree mask (built independently by walking parent
+    pointers), for random trees, a chain and a star; plus what a depth-first numbering fixes: enter is a permutation
+    of 0..n-1 with the root first, exit - enter + 1 is the subtree size, a chain's intervals are nested and a star's
+    leaves are single points."""
+    rng = np.random.default_rng(3)
+    trees = [rand_tree(rng, n) for n in (2, 5, 16, 64, 96, 200)]
+    trees.append(np.arange(-1, 40))                       # chain
+    trees.append(np.array([-1] + [0] * 30))               # star
+    trees.append(np.asarray(synth.tree_for(synth.CONFIGS[5])[0]))
+    for parent in trees:
+        n = len(parent)
+        enter, exit_ = O.interval_labels(parent)
+        walked = np.zeros((n, n), dtype=bool)             # by parent pointers, not through the oracle's own matrix
+        for u in range(n):
+            w = u
+            while w >= 0:
+                walked[u, w] = True
+                w = int(parent[w])
+        assert np.array_equal(O.mask_from_intervals(enter, exit_), walked)
+        assert np.array_equal(O.ancestor_matrix(parent), walked)
+        assert sorted(enter.tolist()) == list(range(n)) and enter[0] == 0 and exit_[0] == n - 1
+        size = walked.sum(axis=0)                          # nodes that have w on their path = subtree size of w
+        assert np.array_equal(exit_ - enter + 1, size)
+    enter, exit_ = O.interval_labels(np.arange(-1, 39))   # a chain of 40 nodes
+    assert np.array_equal(enter, np.arange(40)) and np.all(exit_ == 39)
+    enter, exit_ = O.interval_labels(np.array([-1] + [0] * 30))
+    assert np.array_equal(enter[1:], exit_[1:])
+
+
+def test_p13_a_wrong_comparison_is_caught():
+    """Planted mistakes in the comparison (strict instead of inclusive, exit of the wrong node) break the mask."""
+    parent = rand_tree(np.random.default_rng(4), 24)
+    enter, exit_ = O.interval_labels(parent)
+    good = O.ancestor_matrix(parent)
+    e = enter
+    strict = (e[None, :] < e[:, None]) & (e[:, None] <= exit_[None, :])
+    swapped = (e[None, :] <= e[:, None]) & (e[:, None] <= exit_[:, None])
+    assert not np.array_equal(strict, good) and not np.array_equal(swapped, good)
