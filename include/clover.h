@@ -45,9 +45,15 @@ enum {
 
 enum { CLOVER_DTYPE_F32 = 0, CLOVER_DTYPE_BF16 = 1 };
 enum {
-  CLOVER_FLAG_GENERIC = 1    /* use the plain fp32-ALU kernels everywhere (no MFMA path) */
+  CLOVER_FLAG_GENERIC = 1,       /* use the plain fp32-ALU kernels everywhere (no MFMA path) */
+  CLOVER_FLAG_INTERVAL_MASK = 2  /* tree attention decides "is key w on the root path of query u" from two integers per
+                                    node instead of a bit set per node: the linear-size tree mask of Appendix A.1, read
+                                    as the interval labels of a depth-first numbering (w is u or an ancestor of u iff
+                                    enter[w] <= enter[u] <= exit[w]).  Same results; lifts max_nodes to 256. */
 };
-#define CLOVER_MAX_NODES 128 /* upper bound on max_nodes (ancestor masks are 2 x 64 bit) */
+#define CLOVER_MAX_NODES 128 /* upper bound on max_nodes with the bit-set mask (2 x 64 bit per node) */
+#define CLOVER_MAX_NODES_INTERVAL 256 /* upper bound on max_nodes with CLOVER_FLAG_INTERVAL_MASK (static trees; a
+                                         dynamic tree still has at most 128 nodes) */
 #define CLOVER_MAX_DEPTH 8   /* upper bound on draft_depths */
 #define CLOVER_MAX_RANK 16   /* ranks are < 16 */
 #define CLOVER_MAX_PREFILL_ROWS 256 /* upper bound on prefill_rows: one weight pass of the many-row GEMM */

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libclover.so")
 OK, E_NULL, E_CONFIG, E_TREE, E_CAPACITY, E_SHAPE, E_HIP, E_STATE = 0, -1, -2, -3, -4, -5, -6, -7
 DTYPE_F32, DTYPE_BF16 = 0, 1
 FLAG_GENERIC = 1
+FLAG_INTERVAL_MASK = 2      # linear-size tree mask (two integers per node); lifts max_nodes to 256
 STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = [

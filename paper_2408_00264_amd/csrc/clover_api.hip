@@ -54,7 +54,8 @@ struct TreeHost {
   std::vector<int> par_row;             // per node: index of its parent within the parent's depth group
   std::vector<int> node_off;            // [max_depth+2]: nodes of depth j are [node_off[j], node_off[j+1])
   std::vector<int> kmax;                // per depth j: 1 + max rank among children of depth-j nodes
-  std::vector<unsigned long long> anc;  // [n][2]
+  std::vector<unsigned long long> anc;  // [n][2] (all zero for trees of more than 128 nodes: those use the labels)
+  std::vector<int> iv;                  // [n][2] interval labels: enter, exit of a depth-first numbering
   bool is_chain = false;
 };
 
@@ -86,7 +87,9 @@ struct clover_ctx {
   // device regions
   int *d_seq_len, *d_aug_len, *d_err;
   int *d_depth, *d_parent, *d_rank, *d_first_child, *d_n_child, *d_lvl_nodes, *d_par_row;
-  unsigned long long *d_anc, *d_anc_chain;
+  unsigned long long* d_anc;
+  int* d_iv;               // interval labels of the static tree [R][2]
+  bool interval;           // CLOVER_FLAG_INTERVAL_MASK: tree attention reads the labels instead of the bit sets
   char *kc, *vc, *aug_kc, *aug_vc;
   float *xd, *a_norm, *qkv, *q_rot, *attn_out, *h_ffn, *tmp_ffn, *cos_t, *sin_t;
   float *ad_q, *ad_k, *ad_v, *d_xs, *d_e, *d_cat, *d_g, *d_s, *d_state, *d_rootx, *z;
@@ -141,7 +144,8 @@ int check_config(const clover_config* c, std::string& why) {
   if (c->aug_layers < 1 || c->aug_layers > 8) return bad("aug_layers must be in [1, 8]");
   if (c->draft_depths < 1 || c->draft_depths > CLOVER_MAX_DEPTH) return bad("draft_depths out of range");
   if (c->max_batch < 1 || c->max_batch > 1024) return bad("max_batch out of range");
-  if (c->max_nodes < 1 || c->max_nodes > CLOVER_MAX_NODES) return bad("max_nodes must be in [1, 128]");
+  if (c->max_nodes < 1 || c->max_nodes > ((c->flags & CLOVER_FLAG_INTERVAL_MASK) ? CLOVER_MAX_NODES_INTERVAL : CLOVER_MAX_NODES))
+    return bad("max_nodes must be in [1, 128] (in [1, 256] with CLOVER_FLAG_INTERVAL_MASK)");
   if (c->prefill_rows < 0 || c->prefill_rows > CLOVER_MAX_PREFILL_ROWS) return bad("prefill_rows must be in [0, 256]");
   if (c->max_seq < c->max_nodes) return bad("max_seq smaller than max_nodes");
   if (!(c->rope_base > 1.f) || !(c->rms_eps > 0.f)) return bad("rope_base must be > 1 and rms_eps > 0");
@@ -208,9 +212,21 @@ int build_tree(const clover_config& cfg, const clover_tree* t, TreeHost& out, st
   }
   for (int u = 1; u < n; ++u) h.par_row[u] = row_in_level[h.parent[u]];
   h.anc.assign((size_t)2 * n, 0ull);
-  for (int u = 0; u < n; ++u) {
+  for (int u = 0; u < n && n <= CLOVER_MAX_NODES; ++u) {
     if (u > 0) { h.anc[2 * u] = h.anc[2 * h.parent[u]]; h.anc[2 * u + 1] = h.anc[2 * h.parent[u] + 1]; }
     h.anc[2 * u + (u >> 6)] |= 1ull << (u & 63);
+  }
+  // interval labels (Appendix A.1, linear-size mask): subtree sizes bottom-up (children have larger indices), then
+  // enter[child] = enter[parent] + 1 + sizes of the earlier siblings; exit = enter + size - 1
+  {
+    std::vector<int> size(n, 1);
+    for (int u = n - 1; u >= 1; --u) size[h.parent[u]] += size[u];
+    h.iv.assign((size_t)2 * n, 0);
+    for (int u = 0; u < n; ++u) {
+      int e = h.iv[2 * u] + 1;
+      for (int c = h.first_child[u]; c < h.first_child[u] + h.n_child[u]; ++c) { h.iv[2 * c] = e; e += size[c]; }
+      h.iv[2 * u + 1] = h.iv[2 * u] + size[u] - 1;
+    }
   }
   out = std::move(h);
   return CLOVER_OK;
@@ -259,7 +275,7 @@ void carve(clover_ctx* x, char* base, size_t* total) {
   x->d_lvl_nodes = cv.take<int>(R);
   x->d_par_row = cv.take<int>(R);
   x->d_anc = cv.take<unsigned long long>(2 * R);
-  x->d_anc_chain = cv.take<unsigned long long>(2 * R);
+  x->d_iv = cv.take<int>(2 * R);
   x->kc = cv.take<char>(x->k_layer_elems * x->kv_esz * c.n_layers);
   x->vc = cv.take<char>(x->v_layer_elems * x->kv_esz * c.n_layers);
   x->aug_kc = cv.take<char>(x->k_layer_elems * x->kv_esz * c.aug_layers);
@@ -300,6 +316,7 @@ void carve(clover_ctx* x, char* base, size_t* total) {
   x->dyn.t_n_child = cv.take<int>((size_t)rows);
   x->dyn.t_keep = cv.take<int>((size_t)rows);
   x->dyn.t_anc = cv.take<unsigned long long>((size_t)rows * 2);
+  x->dyn.t_iv = cv.take<int>((size_t)rows * 2);
   x->dyn_state = cv.take<float>((size_t)B * DYN_MAX_CAND * H);
   // MFMA path: is every GEMM shape of this model supported, and how large can an output with its
   // split-K partials get?
@@ -523,7 +540,8 @@ void gemm_generic(clover_ctx* x, int cls, const float* X, int ldx, const void* W
 // hold RMSNorm(xres) * next_gain (skipped when next_gain is null).  Generic path: norms are computed here.
 void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMap rm, int M, char* kc_layer,
                char* vc_layer, const int* base_len, const unsigned long long* anc, const void* next_gain,
-               int key_bound, int anc_stride = 0 /* nodes per sequence in a per-sequence mask table */) {
+               int key_bound, int anc_stride = 0 /* nodes per sequence in a per-sequence mask table */,
+               const int* iv = nullptr /* interval labels: decide visibility instead of anc */) {
   const clover_config& c = x->cfg;
   const int H = x->H, d = c.head_dim, F = c.ffn;
   const int sn[3] = {c.n_q_heads * d, c.n_kv_heads * d, c.n_kv_heads * d};
@@ -548,12 +566,12 @@ void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMa
         ap.k_hi = (const bf16_t*)kc_layer; ap.k_plane = x->k_layer_elems;
         ap.v_hi = (const bf16_t*)vc_layer; ap.v_plane = x->v_layer_elems;
         ap.max_seq = c.max_seq; ap.n_kv = c.n_kv_heads; ap.n_q = c.n_q_heads;
-        ap.base_len = base_len; ap.anc = anc; ap.anc_stride = anc_stride; ap.rm = rm;
+        ap.base_len = base_len; ap.anc = anc; ap.iv = iv; ap.anc_stride = anc_stride; ap.rm = rm;
         ap.o_part = x->o_part; ap.ml_part = x->ml_part; ap.rows_total = x->max_rows; ap.max_splits = x->attn_max_splits;
         launch_attn_mfma(ap, key_bound, O.hi, O.lo, x->NQD, x->st);
       } else {
         launch_attn_generic(x->q_rot, x->NQD, kc_layer, vc_layer, x->kvdtype, x->kv, base_len, anc, c.n_q_heads, nullptr,
-                            x->NQD, O.hi, O.lo, rm, x->st, anc_stride);
+                            x->NQD, O.hi, O.lo, rm, x->st, anc_stride, iv);
       } }
     const int sw = gemm_fast1(x, KC_GEMM_WO, O, lw.wo, M, H, x->NQD);
     { Scope s(x, KC_RMSNORM);
@@ -617,7 +635,7 @@ void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMa
                          x->kv, base_len, c.n_q_heads, rm, x->d_err, nullptr, nullptr, 0.f, x->st); }
   { Scope s(x, KC_ATTN);
     launch_attn_generic(x->q_rot, x->NQD, kc_layer, vc_layer, x->kvdtype, x->kv, base_len, anc, c.n_q_heads, x->attn_out,
-                        x->NQD, nullptr, nullptr, rm, x->st, anc_stride); }
+                        x->NQD, nullptr, nullptr, rm, x->st, anc_stride, iv); }
   gemm_generic(x, KC_GEMM_WO, x->attn_out, x->NQD, lw.wo, nullptr, xres, H, M, H, x->NQD, 1);
   { Scope s(x, KC_RMSNORM); launch_rmsnorm(xres, H, lw.ffn_norm, c.dtype, c.rms_eps, x->a_norm, H, H, M, x->st); }
   gemm_generic(x, KC_GEMM_GATEUP, x->a_norm, H, lw.w_gate, nullptr, x->tmp_ffn, F, M, F, H, 0);
@@ -835,6 +853,7 @@ int upload_tree(clover_ctx* x) {
   up(x->d_lvl_nodes, t.lvl_nodes.data(), t.lvl_nodes.size() * sizeof(int));
   up(x->d_par_row, t.par_row.data(), n * sizeof(int));
   up(x->d_anc, t.anc.data(), 2 * n * sizeof(unsigned long long));
+  up(x->d_iv, t.iv.data(), 2 * n * sizeof(int));
   if (e == hipSuccess) e = hipStreamSynchronize(x->st);  // the host vectors may change after return
   if (e != hipSuccess) return fail(x, CLOVER_E_HIP, std::string("tree upload: ") + hipGetErrorString(e));
   return CLOVER_OK;
@@ -959,15 +978,7 @@ int clover_init(const clover_config* cfg, const clover_weights* w, const clover_
   x->aug_ub.assign(cfg->max_batch, 0);
   x->m_upper = cfg->max_nodes;
   x->only_prefills = true;
-  // chain masks for the Augmenting Block's causal rows: row i sees new rows 0..i
-  std::vector<unsigned long long> chain((size_t)2 * cfg->max_nodes, 0ull);
-  for (int u = 0; u < cfg->max_nodes; ++u) {
-    if (u > 0) { chain[2 * u] = chain[2 * (u - 1)]; chain[2 * u + 1] = chain[2 * (u - 1) + 1]; }
-    chain[2 * u + (u >> 6)] |= 1ull << (u & 63);
-  }
-  hipError_t e = hipMemcpyAsync(x->d_anc_chain, chain.data(), chain.size() * sizeof(unsigned long long), hipMemcpyHostToDevice, x->st);
-  if (e == hipSuccess) e = hipStreamSynchronize(x->st);
-  if (e != hipSuccess) { std::string m = hipGetErrorString(e); delete x; return fail(nullptr, CLOVER_E_HIP, "init upload: " + m); }
+  x->interval = (cfg->flags & CLOVER_FLAG_INTERVAL_MASK) != 0;
   launch_fill_i32(x->d_seq_len, 0, cfg->max_batch, x->st);
   launch_fill_i32(x->d_aug_len, 0, cfg->max_batch, x->st);
   launch_fill_i32(x->d_err, 0, 1, x->st);
@@ -1045,6 +1056,7 @@ int clover_set_dynamic_tree(clover_ctx* x, int32_t n_nodes, int32_t topk, int32_
   if (!x) return CLOVER_E_NULL;
   const clover_config& c = x->cfg;
   if (n_nodes < 1 || n_nodes > c.max_nodes) return fail(x, CLOVER_E_TREE, "n_nodes outside [1, max_nodes]");
+  if (n_nodes > CLOVER_MAX_NODES) return fail(x, CLOVER_E_TREE, "a dynamic tree has at most 128 nodes");
   if (topk < 1 || topk > CLOVER_MAX_RANK) return fail(x, CLOVER_E_TREE, "topk outside [1, 16]");
   if (frontier < 1 || frontier > DYN_MAX_FRONT || frontier > c.max_nodes)
     return fail(x, CLOVER_E_TREE, "frontier outside [1, min(64, max_nodes)]");
@@ -1137,7 +1149,7 @@ int draft_tree(clover_ctx* x, int32_t batch, const float* hid_acc, const int32_t
   }
   for (int l = 0; l < c.aug_layers; ++l)
     run_layer(x, x->aug[l], x->xd, rm, M, x->aug_kc + (size_t)l * x->k_layer_elems * x->kv_esz,
-              x->aug_vc + (size_t)l * x->v_layer_elems * x->kv_esz, x->d_aug_len, x->d_anc_chain,
+              x->aug_vc + (size_t)l * x->v_layer_elems * x->kv_esz, x->d_aug_len, nullptr /* the new rows form a chain */,
               l + 1 < c.aug_layers ? x->aug[l + 1].attn_norm : nullptr, aug_bound);
   {
     // root state and token: node 0 of the static tree, candidate 0 of the dynamic one
@@ -1239,6 +1251,7 @@ int verify_tree(clover_ctx* x, int32_t batch, const int32_t* tree_tokens, float*
   // topology tables: one static tree for all sequences, or the tables draft_tree wrote per sequence
   const int* depth_tab = x->dyn_on ? x->dyn.t_depth : x->d_depth;
   const unsigned long long* anc_tab = x->dyn_on ? x->dyn.t_anc : x->d_anc;
+  const int* iv_tab = !x->interval ? nullptr : x->dyn_on ? x->dyn.t_iv : x->d_iv;
   const int topo_stride = x->dyn_on ? R : 0;
   for (int b = 0; b < B; ++b)
     if (x->len_ub[b] + n_nodes > c.max_seq) return fail(x, CLOVER_E_CAPACITY, "sequence could exceed max_seq (call clover_seq_len to refresh the bound)");
@@ -1253,7 +1266,7 @@ int verify_tree(clover_ctx* x, int32_t batch, const int32_t* tree_tokens, float*
   for (int l = 0; l < c.n_layers; ++l)
     run_layer(x, x->layers[l], hidden, rm, M, x->kc + (size_t)l * x->k_layer_elems * x->kv_esz,
               x->vc + (size_t)l * x->v_layer_elems * x->kv_esz, x->d_seq_len, anc_tab,
-              l + 1 < c.n_layers ? x->layers[l + 1].attn_norm : x->w.final_norm, key_bound, topo_stride);
+              l + 1 < c.n_layers ? x->layers[l + 1].attn_norm : x->w.final_norm, key_bound, topo_stride, iv_tab);
   if (x->fast) {
     Planes A = planes_of(x, x->a_norm, 2 * H);
     A.ld = H;

@@ -47,7 +47,8 @@ void launch_rope_kv_write(const float* qkv, int ldqkv, int qkv_splits, size_t qk
 void launch_attn_generic(const float* q, int ldq, const void* k_cache, const void* v_cache, int kvdtype, KVLayout kv,
                          const int* base_len, const unsigned long long* anc /*[n][2]*/, int n_q, float* out, int ldo,
                          bf16_t* out_hi, bf16_t* out_lo /*planes instead of fp32 when non-null*/, RowMap rm,
-                         hipStream_t st, int anc_stride = 0 /*nodes per sequence in a per-sequence mask table, 0: shared*/);
+                         hipStream_t st, int anc_stride = 0 /*nodes per sequence in a per-sequence mask table, 0: shared*/,
+                         const int* iv = nullptr /*[n][2] interval labels: decide visibility instead of anc when given*/);
 // mode 0: Y = X W^T (+bias); mode 1: Y += X W^T (+bias)
 void launch_gemm_generic(const float* X, int ldx, const void* W, const void* bias, int wdtype, float* Y, int ldy,
                          int M, int N, int K, int mode, hipStream_t st);
@@ -137,7 +138,9 @@ struct AttnParams {
   const bf16_t* v_hi; size_t v_plane;    // V^T planes [B][n_kv][128][max_seq]
   int max_seq, n_kv, n_q;
   const int* base_len;                   // dev [B]
-  const unsigned long long* anc;         // dev [n][2]
+  const unsigned long long* anc;         // dev [n][2]; null (and no interval labels): the nodes form a chain
+  const int* iv;                         // dev [n][2] interval labels (enter, exit) of a depth-first numbering, or null:
+                                         //   when given they decide visibility instead of the bit sets
   int anc_stride;                        // nodes per sequence in a per-sequence mask table, 0: one table for all
   RowMap rm;
   float* o_part;                         // [max_splits][rows_total][n_q][128]
@@ -249,6 +252,7 @@ struct DynTree {
   int* frontier;                           // dev [B][CLOVER_MAX_DEPTH][DYN_MAX_FRONT]: expanded candidates, best first
   int *t_parent, *t_rank, *t_depth, *t_first_child, *t_n_child, *t_keep;   // dev [B][R]: the tree as verified
   unsigned long long* t_anc;               // dev [B][R][2]
+  int* t_iv;                               // dev [B][R][2]: interval labels (enter, exit) of the tree as verified
 };
 // per row of z[rows, V]: ids and values of the k best entries (value descending, id ascending) and the row's
 // log-sum-exp.  cand: [rows][chunks][16] 64-bit keys, aux: [rows][chunks][2] floats, chunks = ceil(V / 2048)
@@ -262,7 +266,7 @@ void launch_accept_sample(const float* logits, int V, const float* lse, float in
 void launch_dyn_assign(const DynTree& t, int j, int B, const int* ids, const float* vals, const float* lse, const int* m,
                        hipStream_t st);
 void launch_dyn_frontier(const DynTree& t, int j, int B, const int* m, hipStream_t st);
-void launch_dyn_finalize(const DynTree& t, int B, int R, const int* m, int* tree_tokens, hipStream_t st);
+void launch_dyn_finalize(const DynTree& t, int B, int R, const int* m, int* tree_tokens, hipStream_t st);   // (also t.t_iv when set)
 
 // ---- tuning knobs -------------------------------------------------------------------------------
 // The shipped library reads no environment variable: every knob is its default.  A build with

@@ -4,7 +4,9 @@
 // G*N query rows; they attend to the L cached keys (all visible) and to the N tree keys, of which
 // node u sees exactly those on its own root path (one bit per tree node in anc[u]).  Without a mask table
 // (anc == null) the nodes form a chain of any length -- a prompt chunk: node u sees tree keys 0..u, and the key tiles
-// behind a node group's last row are skipped.
+// behind a node group's last row are skipped.  With interval labels (iv: enter and exit of a depth-first numbering,
+// two integers per node) tree key w is visible to node u iff enter[w] <= enter[u] <= exit[w]; the labels of the tree
+// keys sit in the LDS behind the stage buffers, so the test is two integer compares against LDS values.
 //
 // Work split: a workgroup = (sequence, KV head, group of 32 nodes, range of 32-key tiles); its G
 // wavefronts are the G query heads.  K and V^T tiles are staged once per workgroup in LDS and
@@ -59,6 +61,7 @@ constexpr int AT_VLD = AT_TK + 8;
 constexpr int AT_KPLANE = AT_TK * AT_KLD;
 constexpr int AT_VPLANE = AT_D * AT_VLD;
 constexpr int AT_BUF = 2 * AT_KPLANE + 2 * AT_VPLANE;  // one stage: K hi, K lo, V^T hi, V^T lo
+constexpr int AT_MAX_IV = CLOVER_MAX_NODES_INTERVAL;   // interval labels of the tree keys kept in the LDS
 
 template <int G, int WM>
 __global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
@@ -103,19 +106,25 @@ __global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
   const int L = p.base_len[b];
   if (ng * 32 >= nv || L + nv > p.max_seq) return;  // whole workgroup
   const int total = L + nv;
-  const bool chain = p.anc == nullptr;
+  const bool chain = p.anc == nullptr && p.iv == nullptr;
+  int2* kiv = (int2*)(sm + 2 * AT_BUF);   // [AT_MAX_IV] (enter, exit) of the tree keys; published by the first barrier
+  if (p.iv)
+    for (int w = tid; w < nv; w += NT) kiv[w] = *(const int2*)(p.iv + 2 * ((size_t)b * p.anc_stride + w));
   const int n_tiles = ((chain ? min(total, L + ng * 32 + 32) : total) + AT_TK - 1) / AT_TK;
   const int t1 = min(n_tiles, t0 + p.tiles_per_split);
 
   // ---- Q fragments (already scaled and split by the RoPE kernel), ancestor masks ----
   Frag qh[AT_MB][4], ql[AT_MB][4];
   unsigned long long a0[AT_MB], a1[AT_MB];
+  int my_enter[AT_MB];
 #pragma unroll
   for (int mb = 0; mb < AT_MB; ++mb) {
     const int node = ng * 32 + nsub + mb * 16 + l16;
     const bool ok = node < nv;
-    a0[mb] = !ok ? 0ull : chain ? ~0ull : p.anc[2 * ((size_t)b * p.anc_stride + node)];
-    a1[mb] = !ok ? 0ull : chain ? ~0ull : p.anc[2 * ((size_t)b * p.anc_stride + node) + 1];
+    const bool bits = !chain && !p.iv;
+    a0[mb] = !ok ? 0ull : bits ? p.anc[2 * ((size_t)b * p.anc_stride + node)] : ~0ull;
+    a1[mb] = !ok ? 0ull : bits ? p.anc[2 * ((size_t)b * p.anc_stride + node) + 1] : ~0ull;
+    my_enter[mb] = ok && p.iv ? p.iv[2 * ((size_t)b * p.anc_stride + node)] : 0;
     const size_t qo = ((size_t)b * rm.R + (ok ? node : 0)) * p.ldq + head * AT_D + g4 * 8;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
@@ -187,6 +196,7 @@ __global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
         if (!CACHED && !vis && j < total) {
           const int wn = j - L;
           if (chain) vis = wn <= ng * 32 + nsub + mb * 16 + l16;
+          else if (p.iv) { const int2 ke = kiv[wn]; vis = ke.x <= my_enter[mb] && my_enter[mb] <= ke.y; }
           else vis = ((wn < 64 ? (a0[mb] >> wn) : (a1[mb] >> (wn - 64))) & 1ull) != 0ull;
         }
         if (a0[mb] == 0ull && a1[mb] == 0ull) vis = false;  // padding row
@@ -338,7 +348,7 @@ bool attn_mfma_supported(int head_dim, int n_q, int n_kv, int max_seq) {
 
 template <int G, int WM>
 static void launch_attn_one(const AttnParams& p, dim3 grid, hipStream_t st) {
-  constexpr size_t lds = (size_t)2 * AT_BUF * sizeof(bf16_t);
+  constexpr size_t lds = (size_t)2 * AT_BUF * sizeof(bf16_t) + AT_MAX_IV * sizeof(int2);
   static bool attr_done = false;
   if (!attr_done) {
     hipFuncSetAttribute((const void*)attn_mfma_kernel<G, WM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

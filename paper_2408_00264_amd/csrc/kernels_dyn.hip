@@ -179,6 +179,7 @@ __global__ __launch_bounds__(DYN_MAX_CAND) void dyn_finalize_kernel(DynTree t, i
   __shared__ int dep[DYN_MAX_CAND], par[DYN_MAX_CAND], sel[DYN_MAX_CAND], nid[DYN_MAX_CAND];
   __shared__ int n_child[CLOVER_MAX_NODES], first_child[CLOVER_MAX_NODES];
   __shared__ unsigned long long anc[CLOVER_MAX_NODES][2];
+  __shared__ int pnode[CLOVER_MAX_NODES], sub[CLOVER_MAX_NODES], ent[CLOVER_MAX_NODES];   // parent, subtree size, enter label
   __shared__ int level_count;
   const int b = blockIdx.x, c = threadIdx.x;
   if (m[b] < 1) return;
@@ -232,6 +233,7 @@ __global__ __launch_bounds__(DYN_MAX_CAND) void dyn_finalize_kernel(DynTree t, i
     t.t_rank[ro + node] = c == 0 ? 0 : (c - t.off[my_dep]) % t.topk;
     t.t_depth[ro + node] = my_dep;
     t.t_keep[ro + node] = c;
+    pnode[node] = pn;
     if (c > 0) { atomicAdd(&n_child[pn], 1); atomicMin(&first_child[pn], node); }
   }
   if (c == 0) anc[0][0] = 1ull;
@@ -245,11 +247,25 @@ __global__ __launch_bounds__(DYN_MAX_CAND) void dyn_finalize_kernel(DynTree t, i
     }
   }
   __syncthreads();
+  // interval labels of a depth-first numbering (the linear-size form of the mask): subtree sizes bottom-up (children
+  // have larger numbers than their parents and are numbered consecutively), then enter labels top-down
+  if (c == 0) {
+    for (int u = 0; u < t.N; ++u) sub[u] = 1;
+    for (int u = t.N - 1; u >= 1; --u) sub[pnode[u]] += sub[u];
+    ent[0] = 0;
+    for (int u = 0; u < t.N; ++u) {
+      int e = ent[u] + 1;
+      for (int k = 0; k < n_child[u]; ++k) { ent[first_child[u] + k] = e; e += sub[first_child[u] + k]; }
+    }
+  }
+  __syncthreads();
   if (c < t.N) {
     t.t_n_child[ro + c] = n_child[c];
     t.t_first_child[ro + c] = n_child[c] ? first_child[c] : 0;
     t.t_anc[(ro + c) * 2] = anc[c][0];
     t.t_anc[(ro + c) * 2 + 1] = anc[c][1];
+    t.t_iv[(ro + c) * 2] = ent[c];
+    t.t_iv[(ro + c) * 2 + 1] = ent[c] + sub[c] - 1;
   }
 }
 

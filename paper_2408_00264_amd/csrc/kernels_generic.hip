@@ -329,13 +329,14 @@ void launch_rope_kv_write(const float* qkv, int ldqkv, int qkv_splits, size_t qk
 // tree-masked attention, one wavefront per (row, q head).  Keys: cached slots [0,L) all visible,
 // then the rm.n new rows at slots L+w, visible iff bit w of the row's ancestor mask is set.
 // anc == null: the rows form a chain (row i sees new rows 0..i), any number of rows.
+// iv != null: new row w is visible to row i iff enter[w] <= enter[i] <= exit[w] (interval labels, two ints per node).
 // ------------------------------------------------------------------------------------------
 template <typename KT>
 __global__ void attn_generic_kernel(const float* __restrict__ q, int ldq, const KT* __restrict__ kc,
                                     const KT* __restrict__ vc, KVLayout kv, const int* __restrict__ base_len,
                                     const unsigned long long* __restrict__ anc, int n_q, float* __restrict__ out,
                                     int ldo, bf16_t* __restrict__ out_hi, bf16_t* __restrict__ out_lo, RowMap rm,
-                                    int anc_stride) {
+                                    int anc_stride, const int* __restrict__ iv) {
   __shared__ float qs[128];
   __shared__ float ps[64];
   const int h = blockIdx.x, i = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
@@ -345,9 +346,11 @@ __global__ void attn_generic_kernel(const float* __restrict__ q, int ldq, const 
   const int L = base_len[b];
   if (L + nv > kv.max_seq) return;
   const size_t row = (size_t)b * rm.R + i;
-  const bool chain = anc == nullptr;
-  const unsigned long long a0 = chain ? 0ull : anc[2 * ((size_t)b * anc_stride + i)];
-  const unsigned long long a1 = chain ? 0ull : anc[2 * ((size_t)b * anc_stride + i) + 1];
+  const bool chain = anc == nullptr && iv == nullptr;
+  const bool bits = anc != nullptr && iv == nullptr;
+  const unsigned long long a0 = bits ? anc[2 * ((size_t)b * anc_stride + i)] : 0ull;
+  const unsigned long long a1 = bits ? anc[2 * ((size_t)b * anc_stride + i) + 1] : 0ull;
+  const int my_enter = iv ? iv[2 * ((size_t)b * anc_stride + i)] : 0;
   const int g = h / (n_q / n_kv);
   const float scale = 1.0f / sqrtf((float)d);
   for (int c = lane; c < d; c += 64) qs[c] = q[row * ldq + h * d + c] * scale;
@@ -362,7 +365,9 @@ __global__ void attn_generic_kernel(const float* __restrict__ q, int ldq, const 
     bool vis = s < L;
     if (!vis && s < total) {
       const int w = s - L;
-      vis = chain ? w <= i : ((w < 64 ? (a0 >> w) : (a1 >> (w - 64))) & 1ull) != 0ull;
+      if (chain) vis = w <= i;
+      else if (iv) vis = iv[2 * ((size_t)b * anc_stride + w)] <= my_enter && my_enter <= iv[2 * ((size_t)b * anc_stride + w) + 1];
+      else vis = ((w < 64 ? (a0 >> w) : (a1 >> (w - 64))) & 1ull) != 0ull;
     }
     float sc = -INFINITY;
     if (vis) {
@@ -409,14 +414,14 @@ __global__ void attn_generic_kernel(const float* __restrict__ q, int ldq, const 
 
 void launch_attn_generic(const float* q, int ldq, const void* k_cache, const void* v_cache, int kvdtype, KVLayout kv,
                          const int* base_len, const unsigned long long* anc, int n_q, float* out, int ldo,
-                         bf16_t* out_hi, bf16_t* out_lo, RowMap rm, hipStream_t st, int anc_stride) {
+                         bf16_t* out_hi, bf16_t* out_lo, RowMap rm, hipStream_t st, int anc_stride, const int* iv) {
   dim3 grid(n_q, rm.n, rm.B);
   if (kvdtype == 0)
     attn_generic_kernel<float><<<grid, 64, 0, st>>>(q, ldq, (const float*)k_cache, (const float*)v_cache, kv, base_len,
-                                                    anc, n_q, out, ldo, out_hi, out_lo, rm, anc_stride);
+                                                    anc, n_q, out, ldo, out_hi, out_lo, rm, anc_stride, iv);
   else
     attn_generic_kernel<bf16_t><<<grid, 64, 0, st>>>(q, ldq, (const bf16_t*)k_cache, (const bf16_t*)v_cache, kv,
-                                                     base_len, anc, n_q, out, ldo, out_hi, out_lo, rm, anc_stride);
+                                                     base_len, anc, n_q, out, ldo, out_hi, out_lo, rm, anc_stride, iv);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -59,6 +59,10 @@ def test_workspace_bytes_and_config_errors(lib):
     assert lib.clover_workspace_bytes(C.byref(bad), C.byref(n)) == clover.E_CONFIG
     bad = _cfg(); bad.max_nodes = 129
     assert lib.clover_workspace_bytes(C.byref(bad), C.byref(n)) == clover.E_CONFIG
+    wide = _cfg(max_seq=512); wide.max_nodes = 200; wide.flags = clover.FLAG_INTERVAL_MASK   # the linear-size mask lifts the bound
+    assert lib.clover_workspace_bytes(C.byref(wide), C.byref(n)) == 0
+    wide.max_nodes = 257
+    assert lib.clover_workspace_bytes(C.byref(wide), C.byref(n)) == clover.E_CONFIG
     bad = _cfg(); bad.dtype = 5
     assert lib.clover_workspace_bytes(C.byref(bad), C.byref(n)) == clover.E_CONFIG
     bad = _cfg(); bad.prefill_rows = 257

@@ -275,6 +275,63 @@ def test_long_context_96_node_tree():
 
 
 # ------------------------------------------------------------------------------------------
+# linear-size tree mask (Appendix A.1): interval labels instead of one bit set per node
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("case", ["fp32_generic", "bf16_mfma", "bf16_generic", "bf16_dynamic_batch2"])
+def test_interval_mask(case):
+    """The same lock-step runs as with the bit-set mask, with CLOVER_FLAG_INTERVAL_MASK: random topologies (the mask
+    is the only thing that tells siblings apart), injected accept lengths, a dynamic tree whose labels the selection
+    kernel writes per sequence."""
+    _torch()
+    from tests.parity import bfs_tree_random, truth_hook_factory
+    bf16 = case.startswith("bf16")
+    flags = clover.FLAG_INTERVAL_MASK | (clover.FLAG_GENERIC if "generic" in case else 0)
+    rng = np.random.default_rng(29)
+    if "dynamic" in case:
+        shape = synth.scaled(MINI, batch=2, prompt_len=(20, 40), seed=63)
+        ls = _lockstep(shape, flags=flags, gain_jitter=0.1, batch=2, max_seq=384, max_nodes=32, dynamic=(24, 4, 4))
+        ls.prefill(synth.make_prompts(shape, seed=35), chunk=16)
+        hook = None
+    else:
+        shape = MINI if bf16 else TINY
+        parent, rank = bfs_tree_random(rng, 24 if bf16 else 16, 4 if bf16 else 3)
+        say(f"interval mask {case}: random tree parents", parent.tolist())
+        ls = _lockstep(shape, flags=flags, gain_jitter=0.1, tree=(parent, rank), max_seq=256, max_nodes=len(parent))
+        ls.prefill([synth.make_prompts(shape, seed=9)[0][:37]], chunk=8)
+        hook = None
+    assert ls.gpu.path_info() == (0 if "generic" in case or not bf16 else 3)
+    for s in range(4):
+        ms = ls.step(tree_hook=hook)
+        say(f"  step {s}: m={ms} max|dlogit|={ls.max_logit_err:.2e} ties={ls.tie_events}")
+    assert ls.max_logit_err <= (3e-2 if bf16 else 1e-4)
+
+
+def test_interval_mask_160_node_tree():
+    """A static tree of 160 nodes (beyond the 128 of the bit-set mask): five node groups per KV head in the attention,
+    160 rows per pass through the many-row GEMM; injected accept lengths up to the full depth."""
+    _torch()
+    from tests.parity import truth_hook_factory
+    shape = synth.scaled(MINI, name="mini-160", tree_k=(8, 6, 4, 3), tree_nodes=160, seed=65)
+    ls = _lockstep(shape, flags=clover.FLAG_INTERVAL_MASK, gain_jitter=0.1, max_seq=768)
+    assert len(ls.parent) == 160
+    ls.prefill([synth.make_prompts(shape, seed=5)[0][:70]], chunk=64)
+    want = [5, 2, 1]
+    hook = truth_hook_factory(ls, want)
+    for s in range(len(want)):
+        ties = ls.tie_events
+        ms = ls.step(tree_hook=hook)
+        say(f"  step {s}: want {want[s]} got {ms} max|dlogit|={ls.max_logit_err:.2e} ties={ls.tie_events}")
+        if ls.tie_events == ties:
+            assert ms == [want[s]]
+    ms = ls.step()
+    say(f"  free step: m={ms} max|dlogit|={ls.max_logit_err:.2e}")
+    assert ls.max_logit_err <= 3e-2
+    with pytest.raises(clover.CloverError) as e:      # without the flag the bit sets bound the tree at 128 nodes
+        clover.Clover(shape, ls.dev_w, ls.parent, ls.rank, 1, 768, 160)
+    assert e.value.code == clover.E_CONFIG
+
+
+# ------------------------------------------------------------------------------------------
 # dynamic (score-pruned) tree: a new topology per sequence and step (Sec. 4.1)
 # ------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("case", ["fp32", "fp32_generic_batch2", "bf16", "bf16_generic"])
