@@ -68,7 +68,7 @@ typedef struct {
   int32_t aug_layers;    /* decoder layers in the Augmenting Block (Sec. 3.3) */
   int32_t ad_heads;      /* heads of the Attention Decoder's cosine gate (Appendix A.3) */
   int32_t draft_depths;  /* D: deepest tree level the draft head can fill (FC_0 .. FC_{D-1}) */
-  int32_t max_batch, max_seq, max_nodes;
+  int32_t max_batch, max_seq, max_nodes;   /* max_seq: a multiple of 32 (the page size of the caches) */
   int32_t flags;         /* CLOVER_FLAG_* */
   int32_t prefill_rows;  /* prompt rows clover_prefill processes per pass (0: max_batch * max_nodes); the row buffers
                             of the workspace are sized for max(max_batch * max_nodes, prefill_rows).  At most 256. */
@@ -236,6 +236,13 @@ int clover_accept_forced(clover_ctx *ctx, int32_t batch, const int32_t *tree_tok
  * CLOVER_E_CAPACITY (max_seq). */
 int clover_prefill(clover_ctx *ctx, int32_t b, const int32_t *tokens, int32_t n, float *logits_last,
                    float *hid_last, int32_t *next_tok_out);
+
+/* Paged KV caches (Sec. 1 names the large-batch serving regime; the paper does not describe a cache).  Both caches of
+ * every layer are pools of max_batch * max_seq / 32 pages of 32 positions; position p of sequence b lives in page
+ * table[b * (max_seq / 32) + p / 32].  The default is the identity table.  table_host: HOST int32
+ * [max_batch * max_seq / 32], a permutation of the page numbers (CLOVER_E_SHAPE otherwise); NULL restores the identity.
+ * Rows already cached are not moved: call it on empty sequences (after init or clover_reset).  Synchronises. */
+int clover_set_page_table(clover_ctx *ctx, const int32_t *table_host);
 
 /* Synchronise and read the target cache lengths into out_host[max_batch]; refreshes the
  * host-side bound used by the capacity check.  Returns CLOVER_E_STATE if a device guard fired. */

@@ -23,7 +23,7 @@ STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = [
     "clover_workspace_bytes", "clover_init", "clover_destroy", "clover_reset", "clover_set_tree",
-    "draft_tree", "verify_tree", "accept_and_compact", "accept_and_compact_sampled", "clover_accept_forced", "clover_prefill", "clover_seq_len",
+    "draft_tree", "verify_tree", "accept_and_compact", "accept_and_compact_sampled", "clover_accept_forced", "clover_prefill", "clover_set_page_table", "clover_seq_len",
     "clover_read_kv", "clover_write_kv", "clover_set_seq_len", "clover_capture_draft_logits", "clover_set_dynamic_tree", "clover_read_dynamic_tree", "clover_path_info", "clover_profile_enable", "clover_profile_collect", "clover_kernel_class_count",
     "clover_kernel_class_name", "clover_last_error", "clover_last_global_error",
     "clover_op_gemm_scratch_bytes", "clover_op_gemm", "clover_op_gemm_static",
@@ -361,6 +361,14 @@ class Clover:
                 else:
                     self.set_tree(parent, rank)
             self.draft_tree(B)
+
+    def set_page_table(self, table: Optional[np.ndarray]) -> None:
+        """Page table of the KV caches: int32 [max_batch * max_seq / 32], a permutation; None = identity."""
+        if table is None:
+            self._check(self.lib.clover_set_page_table(self.ctx, None))
+            return
+        t = np.ascontiguousarray(table, dtype=np.int32)
+        self._check(self.lib.clover_set_page_table(self.ctx, t.ctypes.data_as(C.POINTER(C.c_int32))))
 
     def prefill_prompt(self, b: int, tokens) -> None:
         """clover_prefill for sequence b: `tokens` is a device int32 tensor; the last row's logits, hidden state

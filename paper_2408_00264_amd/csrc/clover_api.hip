@@ -88,6 +88,7 @@ struct clover_ctx {
   int *d_seq_len, *d_aug_len, *d_err;
   int *d_depth, *d_parent, *d_rank, *d_first_child, *d_n_child, *d_lvl_nodes, *d_par_row;
   unsigned long long* d_anc;
+  int* d_pages;            // page table [max_batch][max_seq / KV_PAGE] (used once clover_set_page_table was called)
   int* d_iv;               // interval labels of the static tree [R][2]
   bool interval;           // CLOVER_FLAG_INTERVAL_MASK: tree attention reads the labels instead of the bit sets
   char *kc, *vc, *aug_kc, *aug_vc;
@@ -144,6 +145,7 @@ int check_config(const clover_config* c, std::string& why) {
   if (c->aug_layers < 1 || c->aug_layers > 8) return bad("aug_layers must be in [1, 8]");
   if (c->draft_depths < 1 || c->draft_depths > CLOVER_MAX_DEPTH) return bad("draft_depths out of range");
   if (c->max_batch < 1 || c->max_batch > 1024) return bad("max_batch out of range");
+  if (c->max_seq % KV_PAGE != 0) return bad("max_seq must be a multiple of 32 (the page size of the caches)");
   if (c->max_nodes < 1 || c->max_nodes > ((c->flags & CLOVER_FLAG_INTERVAL_MASK) ? CLOVER_MAX_NODES_INTERVAL : CLOVER_MAX_NODES))
     return bad("max_nodes must be in [1, 128] (in [1, 256] with CLOVER_FLAG_INTERVAL_MASK)");
   if (c->prefill_rows < 0 || c->prefill_rows > CLOVER_MAX_PREFILL_ROWS) return bad("prefill_rows must be in [0, 256]");
@@ -262,7 +264,8 @@ void carve(clover_ctx* x, char* base, size_t* total) {
   x->NQD = c.n_q_heads * d;
   x->QKVN = (c.n_q_heads + 2 * c.n_kv_heads) * d;
   x->k_layer_elems = (size_t)B * c.max_seq * c.n_kv_heads * d;
-  x->kv = KVLayout{B, c.max_seq, c.n_kv_heads, d, x->k_layer_elems};
+  x->d_pages = cv.take<int>((size_t)B * (c.max_seq / KV_PAGE));
+  x->kv = KVLayout{B, c.max_seq, c.n_kv_heads, d, x->k_layer_elems, c.max_seq / KV_PAGE, 0, nullptr};
   x->v_layer_elems = x->k_layer_elems;
   x->d_seq_len = cv.take<int>(B);
   x->d_aug_len = cv.take<int>(B);
@@ -541,8 +544,11 @@ void gemm_generic(clover_ctx* x, int cls, const float* X, int ldx, const void* W
 void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMap rm, int M, char* kc_layer,
                char* vc_layer, const int* base_len, const unsigned long long* anc, const void* next_gain,
                int key_bound, int anc_stride = 0 /* nodes per sequence in a per-sequence mask table */,
-               const int* iv = nullptr /* interval labels: decide visibility instead of anc */) {
+               const int* iv = nullptr /* interval labels: decide visibility instead of anc */,
+               int seq0 = 0 /* the rows belong to sequence seq0 + (their index in rm) */) {
   const clover_config& c = x->cfg;
+  KVLayout kvl = x->kv;
+  kvl.b0 = seq0;
   const int H = x->H, d = c.head_dim, F = c.ffn;
   const int sn[3] = {c.n_q_heads * d, c.n_kv_heads * d, c.n_kv_heads * d};
   const void* ws[3] = {lw.wq, lw.wk, lw.wv};
@@ -555,7 +561,7 @@ void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMa
     { Scope s(x, KC_ROPE_KV);
       Planes Q = planes_of(x, x->q_rot, x->NQD);
       launch_rope_kv_write(x->partial, x->QKVN, sq, (size_t)M * x->QKVN, x->cos_t, x->sin_t, x->q_rot, x->NQD, kc_layer,
-                           vc_layer, x->kvdtype, x->kv, base_len, c.n_q_heads, rm, x->d_err,
+                           vc_layer, x->kvdtype, kvl, base_len, c.n_q_heads, rm, x->d_err,
                            x->attn_fast ? Q.hi : nullptr, Q.lo, 1.0f / sqrtf((float)d), x->st); }
     { Scope s(x, KC_ATTN);
       if (x->attn_fast) {
@@ -565,12 +571,12 @@ void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMa
         ap.q_hi = Q.hi; ap.q_lo = Q.lo; ap.ldq = x->NQD;
         ap.k_hi = (const bf16_t*)kc_layer; ap.k_plane = x->k_layer_elems;
         ap.v_hi = (const bf16_t*)vc_layer; ap.v_plane = x->v_layer_elems;
-        ap.max_seq = c.max_seq; ap.n_kv = c.n_kv_heads; ap.n_q = c.n_q_heads;
+        ap.kv = kvl; ap.max_seq = c.max_seq; ap.n_kv = c.n_kv_heads; ap.n_q = c.n_q_heads;
         ap.base_len = base_len; ap.anc = anc; ap.iv = iv; ap.anc_stride = anc_stride; ap.rm = rm;
         ap.o_part = x->o_part; ap.ml_part = x->ml_part; ap.rows_total = x->max_rows; ap.max_splits = x->attn_max_splits;
         launch_attn_mfma(ap, key_bound, O.hi, O.lo, x->NQD, x->st);
       } else {
-        launch_attn_generic(x->q_rot, x->NQD, kc_layer, vc_layer, x->kvdtype, x->kv, base_len, anc, c.n_q_heads, nullptr,
+        launch_attn_generic(x->q_rot, x->NQD, kc_layer, vc_layer, x->kvdtype, kvl, base_len, anc, c.n_q_heads, nullptr,
                             x->NQD, O.hi, O.lo, rm, x->st, anc_stride, iv);
       } }
     const int sw = gemm_fast1(x, KC_GEMM_WO, O, lw.wo, M, H, x->NQD);
@@ -632,9 +638,9 @@ void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMa
     } }
   { Scope s(x, KC_ROPE_KV);
     launch_rope_kv_write(x->qkv, x->QKVN, 1, 0, x->cos_t, x->sin_t, x->q_rot, x->NQD, kc_layer, vc_layer, x->kvdtype,
-                         x->kv, base_len, c.n_q_heads, rm, x->d_err, nullptr, nullptr, 0.f, x->st); }
+                         kvl, base_len, c.n_q_heads, rm, x->d_err, nullptr, nullptr, 0.f, x->st); }
   { Scope s(x, KC_ATTN);
-    launch_attn_generic(x->q_rot, x->NQD, kc_layer, vc_layer, x->kvdtype, x->kv, base_len, anc, c.n_q_heads, x->attn_out,
+    launch_attn_generic(x->q_rot, x->NQD, kc_layer, vc_layer, x->kvdtype, kvl, base_len, anc, c.n_q_heads, x->attn_out,
                         x->NQD, nullptr, nullptr, rm, x->st, anc_stride, iv); }
   gemm_generic(x, KC_GEMM_WO, x->attn_out, x->NQD, lw.wo, nullptr, xres, H, M, H, x->NQD, 1);
   { Scope s(x, KC_RMSNORM); launch_rmsnorm(xres, H, lw.ffn_norm, c.dtype, c.rms_eps, x->a_norm, H, H, M, x->st); }
@@ -1334,8 +1340,6 @@ int clover_prefill(clover_ctx* x, int32_t b, const int32_t* tokens, int32_t n, f
     return fail(x, CLOVER_E_CAPACITY, "prompt would exceed max_seq (call clover_seq_len to refresh the bound)");
   const int H = x->H;
   const int P = std::min(x->max_rows, CLOVER_MAX_PREFILL_ROWS);   // rows per pass
-  // this sequence's part of the caches (both planes of a split cache move by the same element count) and lengths
-  const size_t seq_bytes = (size_t)c.max_seq * c.n_kv_heads * c.head_dim * (x->kvdtype ? 2 : 4);
   int* len_b = x->d_seq_len + b;
   int* aug_len_b = x->d_aug_len + b;
   float* xres = x->d_xs;   // residual stream of the pass (the draft head's staging buffers are idle here)
@@ -1349,9 +1353,9 @@ int clover_prefill(clover_ctx* x, int32_t b, const int32_t* tokens, int32_t n, f
     if (x->fast) norm_planes(x, xres, x->layers[0].attn_norm, M);
     const int key_bound = x->len_ub[b] + M;
     for (int l = 0; l < c.n_layers; ++l)
-      run_layer(x, x->layers[l], xres, rm, M, x->kc + (size_t)l * x->k_layer_elems * x->kv_esz + b * seq_bytes,
-                x->vc + (size_t)l * x->v_layer_elems * x->kv_esz + b * seq_bytes, len_b, nullptr,
-                l + 1 < c.n_layers ? x->layers[l + 1].attn_norm : x->w.final_norm, key_bound);
+      run_layer(x, x->layers[l], xres, rm, M, x->kc + (size_t)l * x->k_layer_elems * x->kv_esz,
+                x->vc + (size_t)l * x->v_layer_elems * x->kv_esz, len_b, nullptr,
+                l + 1 < c.n_layers ? x->layers[l + 1].attn_norm : x->w.final_norm, key_bound, 0, nullptr, b);
     { Scope s(x, KC_DRAFT_MISC); launch_add_scalar(len_b, M, x->st); }
     x->len_ub[b] += M;
     if (last) {
@@ -1384,15 +1388,35 @@ int clover_prefill(clover_ctx* x, int32_t b, const int32_t* tokens, int32_t n, f
       if (x->fast) norm_planes(x, x->xd, x->aug[0].attn_norm, Md);
       const int aug_bound = x->aug_ub[b] + Md;
       for (int l = 0; l < c.aug_layers; ++l)
-        run_layer(x, x->aug[l], x->xd, rd, Md, x->aug_kc + (size_t)l * x->k_layer_elems * x->kv_esz + b * seq_bytes,
-                  x->aug_vc + (size_t)l * x->v_layer_elems * x->kv_esz + b * seq_bytes, aug_len_b, nullptr,
-                  l + 1 < c.aug_layers ? x->aug[l + 1].attn_norm : nullptr, aug_bound);
+        run_layer(x, x->aug[l], x->xd, rd, Md, x->aug_kc + (size_t)l * x->k_layer_elems * x->kv_esz,
+                  x->aug_vc + (size_t)l * x->v_layer_elems * x->kv_esz, aug_len_b, nullptr,
+                  l + 1 < c.aug_layers ? x->aug[l + 1].attn_norm : nullptr, aug_bound, 0, nullptr, b);
       { Scope s(x, KC_DRAFT_MISC); launch_add_scalar(aug_len_b, Md, x->st); }
       x->aug_ub[b] += Md;
     }
   }
   if (x->only_prefills) x->m_upper = 1;
   return finish(x, "clover_prefill");
+}
+
+int clover_set_page_table(clover_ctx* x, const int32_t* table_host) {
+  if (!x) return fail(x, CLOVER_E_NULL, "null argument");
+  if (!table_host) {   // back to the identity mapping
+    x->kv.pages = nullptr;
+    return CLOVER_OK;
+  }
+  const int n = x->cfg.max_batch * x->kv.T;
+  std::vector<char> seen((size_t)n, 0);
+  for (int i = 0; i < n; ++i) {
+    const int pg = table_host[i];
+    if (pg < 0 || pg >= n || seen[pg]) return fail(x, CLOVER_E_SHAPE, "page table must be a permutation of 0 .. max_batch * max_seq / 32 - 1");
+    seen[pg] = 1;
+  }
+  hipError_t e = hipMemcpyAsync(x->d_pages, table_host, (size_t)n * sizeof(int), hipMemcpyHostToDevice, x->st);
+  if (e == hipSuccess) e = hipStreamSynchronize(x->st);
+  if (e != hipSuccess) return fail(x, CLOVER_E_HIP, std::string("page table upload: ") + hipGetErrorString(e));
+  x->kv.pages = x->d_pages;
+  return CLOVER_OK;
 }
 
 int clover_seq_len(clover_ctx* x, int32_t* out_host) {

@@ -24,13 +24,35 @@ struct RowMap {
   const int* n_valid;  // dev [B] or null
 };
 
+constexpr int KV_PAGE = 32;   // cached positions per page (= the key tile of the MFMA attention)
 struct KVLayout {
-  // K: [max_batch][max_seq][n_kv][d]; V (transposed): [max_batch][n_kv][d][max_seq]; one such pair per layer.
+  // Paged caches, one pair per layer.  A page holds KV_PAGE consecutive positions of one sequence for all KV heads:
+  //   K page:  [n_kv][KV_PAGE][d]      V page (transposed):  [n_kv][d][KV_PAGE]
+  // so the K rows and the V^T columns of one (page, head) -- one key tile of the attention -- are one contiguous
+  // block each.  Position `slot` of sequence b lives in page pages[(b + b0) * T + slot / KV_PAGE] (identity when
+  // pages is null), at row slot % KV_PAGE.
   // kvdtype 0: fp32 elements.  kvdtype 1: each cache is two bf16 planes (hi, then lo `plane` elements
   // later) with hi + lo == value to 16 mantissa bits -- the operand format of the MFMA attention.
   int max_batch, max_seq, n_kv, d;
   size_t plane;
+  int T;               // pages per sequence = max_seq / KV_PAGE
+  int b0;              // added to every sequence index (a call that works on one sequence of the batch)
+  const int* pages;    // dev [max_batch * T] page table, or null
 };
+#ifdef __HIPCC__
+__device__ __forceinline__ size_t kv_page_of(const KVLayout& kv, int b, int slot) {
+  const int lp = (b + kv.b0) * kv.T + slot / KV_PAGE;
+  return (size_t)(kv.pages ? kv.pages[lp] : lp);
+}
+// element index of K[b][slot][head][0] (d contiguous elements follow)
+__device__ __forceinline__ size_t kv_k_at(const KVLayout& kv, int b, int slot, int head) {
+  return ((kv_page_of(kv, b, slot) * kv.n_kv + head) * KV_PAGE + slot % KV_PAGE) * kv.d;
+}
+// element index of V^T[b][head][dim][slot] (the rest of the page's positions follow contiguously)
+__device__ __forceinline__ size_t kv_v_at(const KVLayout& kv, int b, int head, int dim, int slot) {
+  return ((kv_page_of(kv, b, slot) * kv.n_kv + head) * kv.d + dim) * KV_PAGE + slot % KV_PAGE;
+}
+#endif
 
 // ---- generic (fp32 ALU) kernels; wdtype: 0 fp32, 1 bf16 ---------------------------------------
 void launch_embed(const void* table, int wdtype, const int* tok, int vocab, float* out, int ldo, int H,
@@ -134,8 +156,9 @@ void launch_gemm_mfma(const MfmaGemm& g, hipStream_t st);
 // ---- MFMA tree attention (head_dim 128, caches as bf16 planes) ---------------------------------
 struct AttnParams {
   const bf16_t *q_hi, *q_lo; int ldq;    // [rows, n_q*128] planes: RoPE applied, scaled by 1/sqrt(128)
-  const bf16_t* k_hi; size_t k_plane;    // K planes [B][max_seq][n_kv][128]; lo = hi + k_plane
-  const bf16_t* v_hi; size_t v_plane;    // V^T planes [B][n_kv][128][max_seq]
+  const bf16_t* k_hi; size_t k_plane;    // K planes of one layer (paged, see KVLayout); lo = hi + k_plane
+  const bf16_t* v_hi; size_t v_plane;    // V^T planes
+  KVLayout kv;
   int max_seq, n_kv, n_q;
   const int* base_len;                   // dev [B]
   const unsigned long long* anc;         // dev [n][2]; null (and no interval labels): the nodes form a chain

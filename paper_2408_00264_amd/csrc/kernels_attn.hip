@@ -54,7 +54,7 @@ __device__ __forceinline__ void a_split2(float a, float b, unsigned& hi, unsigne
 }
 
 constexpr int AT_D = 128;         // head dim
-constexpr int AT_TK = 32;         // keys per tile
+constexpr int AT_TK = KV_PAGE;    // keys per tile = one page of the caches
 // (WM, a template parameter: wavefronts per query head; a workgroup always covers 32 nodes, a wavefront 32 / WM)
 constexpr int AT_KLD = AT_D + 8;  // LDS row strides (bf16) chosen so fragment reads are conflict-free
 constexpr int AT_VLD = AT_TK + 8;
@@ -82,20 +82,23 @@ __global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
   // two register sets: while a tile is multiplied, the next one sits in LDS or lands in one set and
   // the one after it is in flight into the other
   u32x4 krA[KIT], vrA[VIT], krB[KIT], vrB[VIT];
-  const bf16_t* kbase = p.k_hi + (size_t)b * p.max_seq * p.n_kv * AT_D + (size_t)kvh * AT_D;
-  const bf16_t* vbase = p.v_hi + ((size_t)b * p.n_kv + kvh) * AT_D * p.max_seq;
+  // Key tile t of this sequence is page pages[b * T + t] of the paged caches: the K rows and the V^T columns of
+  // (page, KV head) are one contiguous 8 KB block each per plane.
+  const KVLayout& kv = p.kv;
   auto load_tile = [&](u32x4 (&kr)[KIT], u32x4 (&vr)[VIT], int t) __attribute__((always_inline)) {
+    const int lp = (b + kv.b0) * kv.T + min(t, kv.T - 1);
+    const size_t page = (size_t)(kv.pages ? kv.pages[lp] : lp);
+    const bf16_t* kb = p.k_hi + (page * kv.n_kv + kvh) * (size_t)(KV_PAGE * AT_D);
+    const bf16_t* vb = p.v_hi + (page * kv.n_kv + kvh) * (size_t)(AT_D * KV_PAGE);
 #pragma unroll
     for (int it = 0; it < KIT; ++it) {
-      const int idx = it * NT + tid, plane = idx >> 9, rem = idx & 511, key = rem >> 4, sl = rem & 15;
-      const int j = min(t * AT_TK + key, p.max_seq - 1);
-      kr[it] = *(const u32x4*)(kbase + plane * p.k_plane + (size_t)j * p.n_kv * AT_D + sl * 8);
+      const int idx = it * NT + tid, plane = idx >> 9, rem = idx & 511;   // rem = key * 16 + piece
+      kr[it] = *(const u32x4*)(kb + plane * p.k_plane + rem * 8);
     }
 #pragma unroll
     for (int it = 0; it < VIT; ++it) {
-      const int idx = it * NT + tid, plane = idx >> 9, rem = idx & 511, dr = rem >> 2, sl = rem & 3;
-      const int j = min(t * AT_TK + sl * 8, p.max_seq - 8);
-      vr[it] = *(const u32x4*)(vbase + plane * p.v_plane + (size_t)dr * p.max_seq + j);
+      const int idx = it * NT + tid, plane = idx >> 9, rem = idx & 511;   // rem = channel * 4 + piece
+      vr[it] = *(const u32x4*)(vb + plane * p.v_plane + rem * 8);
     }
   };
   // The first key tile is requested before anything else is waited for (its addresses need no memory:
@@ -343,7 +346,7 @@ __global__ __launch_bounds__(MG_HEADS * 32) void attn_merge_kernel(const float* 
 
 bool attn_mfma_supported(int head_dim, int n_q, int n_kv, int max_seq) {
   const int g = n_q / n_kv;
-  return head_dim == AT_D && (g == 1 || g == 2 || g == 4 || g == 8) && max_seq % 8 == 0 && max_seq >= 32;
+  return head_dim == AT_D && (g == 1 || g == 2 || g == 4 || g == 8) && max_seq % KV_PAGE == 0 && max_seq >= KV_PAGE;
 }
 
 template <int G, int WM>

@@ -192,7 +192,7 @@ __global__ void rope_kv_write_kernel(const float* __restrict__ qkv, int ldqkv, i
         q_out[row * ldq + hh * d + ii + half] = o2;
       }
     } else {
-      const size_t base = (((size_t)b * kv.max_seq + slot) * n_kv + (hh - n_q)) * d;
+      const size_t base = kv_k_at(kv, b, slot, hh - n_q);
       stkv(kc, base + ii, kv.plane, o1);
       stkv(kc, base + ii + half, kv.plane, o2);
     }
@@ -203,7 +203,7 @@ __global__ void rope_kv_write_kernel(const float* __restrict__ qkv, int ldqkv, i
       const int node = idx % rm.n, e = vb * 8 + idx / rm.n;
       if (node >= nv || e >= n_kv * d) continue;
       const float v = sum_partials(qkv + ((size_t)b * rm.R + node) * ldqkv + voff + e, nsp, sps);
-      stkv(vc, ((size_t)b * n_kv * d + e) * kv.max_seq + L + node, kv.plane, v);
+      stkv(vc, kv_v_at(kv, b, e / d, e % d, L + node), kv.plane, v);
     }
   }
 }
@@ -265,7 +265,7 @@ __global__ __launch_bounds__(256) void rope_kv_planes_kernel(const float* __rest
       planes4(q_hi, q_lo, row * ldq + hh * d + ii, o1);
       planes4(q_hi, q_lo, row * ldq + hh * d + ii + half, o2);
     } else {
-      const size_t base = (((size_t)b * kv.max_seq + L + i) * n_kv + (hh - n_q)) * d + ii;
+      const size_t base = kv_k_at(kv, b, L + i, hh - n_q) + ii;
       planes4(kc, kc + kv.plane, base, o1);
       planes4(kc, kc + kv.plane, base + half, o2);
     }
@@ -293,7 +293,7 @@ __global__ __launch_bounds__(256) void rope_kv_planes_kernel(const float* __rest
     for (int j = 0; j < 8; ++j) {
       const int e = tid / 64 + 4 * j;
       const float val = tile[nl][e];
-      const size_t at = ((size_t)b * n_kv * d + eb * 32 + e) * kv.max_seq + L + node;
+      const size_t at = kv_v_at(kv, b, (eb * 32 + e) / d, (eb * 32 + e) % d, L + node);
       const bf16_t hb = f32_to_bf16(val);
       vc[at] = hb;
       vc[at + kv.plane] = f32_to_bf16(val - bf16_to_f32(hb));
@@ -358,8 +358,6 @@ __global__ void attn_generic_kernel(const float* __restrict__ q, int ldq, const 
   float mrun = -INFINITY, lrun = 0.f, o0 = 0.f, o1 = 0.f;
   const int total = L + rm.n;
   const int ntiles = (total + 63) / 64;
-  const KT* vrow0 = vc + ((size_t)b * n_kv * d + (size_t)g * d + lane) * kv.max_seq;
-  const KT* vrow1 = vrow0 + (size_t)64 * kv.max_seq;
   for (int t = 0; t < ntiles; ++t) {
     const int s = t * 64 + lane;
     bool vis = s < L;
@@ -371,7 +369,7 @@ __global__ void attn_generic_kernel(const float* __restrict__ q, int ldq, const 
     }
     float sc = -INFINITY;
     if (vis) {
-      const KT* kr = kc + (((size_t)b * kv.max_seq + s) * n_kv + g) * d;
+      const KT* kr = kc + kv_k_at(kv, b, s, g);
       float acc = 0.f;
       for (int c = 0; c < d; ++c) acc += qs[c] * ldkv(kr, c, kv.plane);
       sc = acc;
@@ -391,8 +389,8 @@ __global__ void attn_generic_kernel(const float* __restrict__ q, int ldq, const 
     for (int j = 0; j < jmax; ++j) {
       const float pj = ps[j];
       if (pj != 0.f) {
-        o0 += pj * ldkv(vrow0, t * 64 + j, kv.plane);
-        if (d > 64) o1 += pj * ldkv(vrow1, t * 64 + j, kv.plane);
+        o0 += pj * ldkv(vc, kv_v_at(kv, b, g, lane, t * 64 + j), kv.plane);
+        if (d > 64) o1 += pj * ldkv(vc, kv_v_at(kv, b, g, lane + 64, t * 64 + j), kv.plane);
       }
     }
   }
@@ -789,13 +787,14 @@ __global__ void compact_kv_kernel(KT* __restrict__ kc, KT* __restrict__ vc, KVLa
   if (col >= width) return;
   const int mb = m[b], L = len[b];
   if (mb <= 0 || L + mb > kv.max_seq) return;
-  KT* kbase = kc + (size_t)layer * k_layer_elems + (size_t)b * kv.max_seq * width + col;
-  KT* vbase = vc + (size_t)layer * v_layer_elems + ((size_t)b * width + col) * kv.max_seq;
+  KT* kbase = kc + (size_t)layer * k_layer_elems;
+  KT* vbase = vc + (size_t)layer * v_layer_elems;
+  const int head = col / kv.d, dim = col % kv.d;
   for (int i = 0; i < mb; ++i) {
     const int a = acc_idx[(size_t)b * R + i];
     if (a == i || a < 0 || L + a >= kv.max_seq) continue;
-    mvkv(kbase, (size_t)(L + i) * width, (size_t)(L + a) * width, kv.plane);
-    mvkv(vbase, L + i, L + a, kv.plane);
+    mvkv(kbase, kv_k_at(kv, b, L + i, head) + dim, kv_k_at(kv, b, L + a, head) + dim, kv.plane);
+    mvkv(vbase, kv_v_at(kv, b, head, dim, L + i), kv_v_at(kv, b, head, dim, L + a), kv.plane);
   }
 }
 void launch_compact_kv(void* k_cache, void* v_cache, int kvdtype, KVLayout kv, int n_layers, size_t k_layer_elems,
@@ -832,8 +831,8 @@ __global__ void read_kv_kernel(const KT* __restrict__ kc, const KT* __restrict__
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (size_t)n_slots * width) return;
   const int s = (int)(idx / width), col = (int)(idx % width);
-  k_out[idx] = ldkv(kc, ((size_t)b * kv.max_seq + slot0 + s) * width + col, kv.plane);
-  v_out[idx] = ldkv(vc, ((size_t)b * width + col) * kv.max_seq + slot0 + s, kv.plane);
+  k_out[idx] = ldkv(kc, kv_k_at(kv, b, slot0 + s, col / kv.d) + col % kv.d, kv.plane);
+  v_out[idx] = ldkv(vc, kv_v_at(kv, b, col / kv.d, col % kv.d, slot0 + s), kv.plane);
 }
 void launch_read_kv(const void* k_cache, const void* v_cache, int kvdtype, KVLayout kv, int b, int slot0, int n_slots,
                     float* k_out, float* v_out, hipStream_t st) {
@@ -855,8 +854,8 @@ __global__ void write_kv_kernel(KT* __restrict__ kc, KT* __restrict__ vc, KVLayo
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (size_t)n_slots * width) return;
   const int s = (int)(idx / width), col = (int)(idx % width);
-  stkv(kc, ((size_t)b * kv.max_seq + slot0 + s) * width + col, kv.plane, k_in[idx]);
-  stkv(vc, ((size_t)b * width + col) * kv.max_seq + slot0 + s, kv.plane, v_in[idx]);
+  stkv(kc, kv_k_at(kv, b, slot0 + s, col / kv.d) + col % kv.d, kv.plane, k_in[idx]);
+  stkv(vc, kv_v_at(kv, b, col / kv.d, col % kv.d, slot0 + s), kv.plane, v_in[idx]);
 }
 void launch_write_kv(void* k_cache, void* v_cache, int kvdtype, KVLayout kv, int b, int slot0, int n_slots,
                      const float* k_in, const float* v_in, hipStream_t st) {

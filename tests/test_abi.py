@@ -63,6 +63,8 @@ def test_workspace_bytes_and_config_errors(lib):
     assert lib.clover_workspace_bytes(C.byref(wide), C.byref(n)) == 0
     wide.max_nodes = 257
     assert lib.clover_workspace_bytes(C.byref(wide), C.byref(n)) == clover.E_CONFIG
+    bad = _cfg(max_seq=120)                   # the caches are pools of 32-position pages
+    assert lib.clover_workspace_bytes(C.byref(bad), C.byref(n)) == clover.E_CONFIG
     bad = _cfg(); bad.dtype = 5
     assert lib.clover_workspace_bytes(C.byref(bad), C.byref(n)) == clover.E_CONFIG
     bad = _cfg(); bad.prefill_rows = 257

@@ -275,6 +275,47 @@ def test_long_context_96_node_tree():
 
 
 # ------------------------------------------------------------------------------------------
+# paged KV caches: any permutation of the pages gives the same results
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("case", ["fp32_generic", "bf16_mfma_batch3", "bf16_mfma_prefill_call"])
+def test_paged_kv_shuffled_page_table(case):
+    """The caches are pools of 32-position pages; with a random permutation as page table (pages of one sequence
+    scattered between those of the others) every cache row read back, every logit and every accepted token must be
+    what the oracle computes: writes (RoPE/KV kernel, cache-row upload), reads (both attention kernels, the read-back)
+    and moves (compaction across a page boundary) all go through the table."""
+    _torch()
+    from tests.parity import truth_hook_factory
+    bf16 = case.startswith("bf16")
+    batch = 3 if "batch3" in case else (2 if "prefill_call" in case else 1)
+    if bf16:
+        shape = synth.scaled(MINI, batch=batch, prompt_len=(28, 95), seed=67)
+    else:
+        shape = TINY
+    max_seq = 256
+    ls = _lockstep(shape, flags=0 if bf16 else 0, gain_jitter=0.1, batch=batch, max_seq=max_seq,
+                   prefill_rows=64 if "prefill_call" in case else 0)
+    perm = np.random.default_rng(77).permutation(batch * (max_seq // 32)).astype(np.int32)
+    ls.gpu.set_page_table(perm)
+    prompts = synth.make_prompts(shape, seed=15) if batch > 1 else [synth.make_prompts(shape, seed=15)[0][:61]]
+    say(f"paged KV {case}: prompts {[len(p) for p in prompts]}, page table {perm[:8].tolist()}...")
+    if "prefill_call" in case:
+        ls.prefill_prompts(prompts, oracle_chunk=32)
+    else:
+        ls.prefill(prompts, chunk=16)
+    want = [3, 1, 4, 2]
+    hook = truth_hook_factory(ls, want)
+    for s in range(len(want)):
+        ms = ls.step(tree_hook=hook)
+        say(f"  step {s}: want {want[s]} got {ms} max|dlogit|={ls.max_logit_err:.2e} max|dKV|={ls.max_kv_err:.2e}")
+    for s in range(2):
+        ls.step()
+    assert ls.max_logit_err <= (3e-2 if bf16 else 1e-4)
+    with pytest.raises(clover.CloverError) as e:
+        ls.gpu.set_page_table(np.zeros(batch * (max_seq // 32), np.int32))     # not a permutation
+    assert e.value.code == clover.E_SHAPE
+
+
+# ------------------------------------------------------------------------------------------
 # linear-size tree mask (Appendix A.1): interval labels instead of one bit set per node
 # ------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("case", ["fp32_generic", "bf16_mfma", "bf16_generic", "bf16_dynamic_batch2"])
@@ -551,7 +592,7 @@ def test_accept_and_compact_crafted_paths(bf16, case):
 # ------------------------------------------------------------------------------------------
 def test_capacity_and_shape_errors():
     _torch()
-    ls = _lockstep(TINY, max_seq=40)
+    ls = _lockstep(TINY, max_seq=64)
     g = ls.gpu
     with pytest.raises(clover.CloverError) as e:
         g.verify_tree(2)
@@ -560,10 +601,10 @@ def test_capacity_and_shape_errors():
     g.verify_tree(1)
     g.accept_and_compact(1)
     with pytest.raises(clover.CloverError) as e:      # the host-side length bound grows by D+1 per step
-        for _ in range(6):
+        for _ in range(12):
             g.draft_tree(1); g.verify_tree(1); g.accept_and_compact(1)
     assert e.value.code == clover.E_CAPACITY
-    assert g.seq_len()[0] <= 40
+    assert g.seq_len()[0] <= 64
 
 
 # ------------------------------------------------------------------------------------------
