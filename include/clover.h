@@ -297,8 +297,7 @@ const char *clover_last_global_error(void);
  * kernel (bf16, M <= 64, K % 256 == 0, N % 16 == 0, ldy % 4 == 0), 4 = as 3 reusing the copy;
  * 5 = the panel kernel over ranges of K (narrow N with long K, e.g. 4096 x 14336; CLOVER_E_SHAPE
  * where the launcher would not pick it) followed by the sum of the ranges, 6 = as 5 reusing the copy;
- * 7 = the tiled kernel for many rows (M <= 256, K % 64 == 0, N % 16 == 0) over ranges of K, then their sum;
- * 9 = as 7 in the kernel's 128-row x 256-column form (the one passes of 129..256 rows take).
+ * 7 = the tiled kernel for many rows (M <= 256, K % 64 == 0, N % 16 == 0) over ranges of K, then their sum.
  * `scratch` dev, >= clover_op_gemm_scratch_bytes(M,N,K).  Stream as given. */
 size_t clover_op_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K);
 int clover_op_gemm(int32_t path, int32_t dtype, const float *X, const void *W, float *Y, int32_t ldy,

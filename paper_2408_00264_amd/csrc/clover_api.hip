@@ -104,7 +104,6 @@ struct clover_ctx {
   const void* lm_head_pk;
   bool fast;               // bf16 model on the MFMA path
   bool panel;              // full-K panel GEMM for the gate+up projection and the LM head
-  int tile_wide = 1;       // 129..256 rows: the 128 x 256 form of the tiled GEMM
   int tile_min_kp = 65;    // narrow outputs over K ranges take the tiled GEMM's 128 x 256 form from this many rows on
   int tile_min = 129;      // passes of at least this many rows (up to 256) take the tiled GEMM: one weight pass
   int row_batch_max = 64;
@@ -352,7 +351,7 @@ void carve(clover_ctx* x, char* base, size_t* total) {
       const int rb = std::min(rows, 256);
       for (const GemmShape& g : shp)
         if (g.mode != 2 && tile_gemm_supported(rb, g.N, g.K, 0))
-          pbytes = std::max(pbytes, (size_t)std::max(tile_gemm_pick_k_parts(rb, g.N, g.K), tile_wide_pick_k_parts(rb, g.N, g.K)) *
+          pbytes = std::max(pbytes, (size_t)tile_gemm_pick_k_parts(rb, g.N, g.K) *
                                         rb * g.N * sizeof(float));
     }
     // 65..256 rows in batches of 64 through the K-slice kernel: partial tiles of the whole pass
@@ -375,8 +374,7 @@ void carve(clover_ctx* x, char* base, size_t* total) {
   x->row_batch_max = (fast && !tune_int("CLOVER_NO_ROW_BATCH", 0)) ? 256 : 64;
   x->row_batch = (x->panel && !tune_int("CLOVER_ROW_BATCH_64", 0)) ? 128 : 64;
   x->tile_min = fast ? tune_int("CLOVER_TILE_MIN", 129) : 1 << 30;
-  x->tile_wide = tune_int("CLOVER_TILE_WIDE", 1);
-  x->tile_min_kp = fast && x->tile_wide ? tune_int("CLOVER_TILE_MIN_KP", 65) : 1 << 30;
+  x->tile_min_kp = fast ? tune_int("CLOVER_TILE_MIN_KP", 65) : 1 << 30;
   x->kvdtype = fast ? 1 : 0;
   x->kv_layer_stride = fast ? 2 * x->k_layer_elems : x->k_layer_elems;
   x->attn_fast = fast && attn_mfma_supported(d, c.n_q_heads, c.n_kv_heads, c.max_seq);
@@ -439,14 +437,14 @@ int gemm_fast(clover_ctx* x, int cls, Planes X, int nseg, const void* const* W, 
   if (!direct && M >= std::min(x->tile_min, x->tile_min_kp) && M <= 256 && tile_gemm_supported(M, N, K, 0)) {
     bool adjacent = true;
     for (int s = 1; s < nseg; ++s) adjacent = adjacent && ws[s] == ws[s - 1] + (size_t)seg_n[s - 1] * K;
-    const int kp = x->tile_wide ? tile_wide_pick_k_parts(M, N, K) : tile_gemm_pick_k_parts(M, N, K);
+    const int kp = tile_gemm_pick_k_parts(M, N, K);
     if (adjacent && (size_t)kp * M * N * sizeof(float) <= x->partial_bytes) {
       TileGemm g;
       memset(&g, 0, sizeof(g));
       g.Xhi = X.hi; g.Xlo = X.lo; g.ldx = X.ld;
       g.W[0] = g.W[1] = ws[0];
       g.Y = part; g.ldy = N; g.k_parts = kp; g.split_stride = (size_t)M * N;
-      g.M = M; g.N = N; g.K = K; g.epi = 0; g.wide = x->tile_wide;
+      g.M = M; g.N = N; g.K = K; g.epi = 0;
       launch_gemm_tile(g, x->st);
       return kp;
     }
@@ -590,7 +588,7 @@ void run_layer(clover_ctx* x, const clover_layer_weights& lw, float* xres, RowMa
       g.Xhi = A.hi; g.Xlo = A.lo; g.ldx = H;
       g.W[0] = (const bf16_t*)lw.w_gate; g.W[1] = (const bf16_t*)lw.w_up;
       g.Yhi = Hf.hi; g.Ylo = Hf.lo; g.ldo = F;
-      g.M = M; g.N = F; g.K = H; g.epi = 1; g.k_parts = 1; g.wide = x->tile_wide;
+      g.M = M; g.N = F; g.K = H; g.epi = 1; g.k_parts = 1;
       launch_gemm_tile(g, x->st);
     } else if (x->panel && M <= x->row_batch_max && panel_gemm_supported(std::min(M, 64), F, H, 1)) {
       Scope s(x, KC_GEMM_GATEUP);
@@ -702,7 +700,7 @@ void lm_head_fast(clover_ctx* x, Planes A, int rows, float* out) {
     memset(&g, 0, sizeof(g));
     g.Xhi = A.hi; g.Xlo = A.lo; g.ldx = A.ld;
     g.W[0] = g.W[1] = (const bf16_t*)x->lm_head_pk;
-    g.Y = out; g.ldy = c.vocab; g.M = rows; g.N = c.vocab; g.K = x->H; g.epi = 0; g.k_parts = 1; g.wide = x->tile_wide;
+    g.Y = out; g.ldy = c.vocab; g.M = rows; g.N = c.vocab; g.K = x->H; g.epi = 0; g.k_parts = 1;
     launch_gemm_tile(g, x->st);
     return;
   }
@@ -1539,7 +1537,7 @@ size_t clover_op_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K) {
     if (stream_gemm_supported(M, N, K)) out = std::max(out, stream_gemm_out_bytes(M, N, K));
     out = std::max(out, (size_t)std::max(panel_gemm_pick_k_parts(M, N, K), 0) * M * N * sizeof(float));
     if (tile_gemm_supported(M, N, K, 0))
-      out = std::max(out, (size_t)std::max(tile_gemm_pick_k_parts(M, N, K), tile_wide_pick_k_parts(M, N, K)) * M * N * sizeof(float));
+      out = std::max(out, (size_t)tile_gemm_pick_k_parts(M, N, K) * M * N * sizeof(float));
     bytes += align256((size_t)M * K * 4) + align256(out) + align256((size_t)N * K * 2);
   }
   return bytes;
@@ -1585,15 +1583,15 @@ int op_gemm_impl(int32_t path, int32_t dtype, const float* X, const void* W, flo
     if (path & 1) launch_pack_weight(W, wp, N, K, st);
     launch_split_planes(X, K, hi, lo, K, M, K, st);
     int splits;
-    if (path == 7 || path == 9) {   // tiled kernel (9: its 128 x 256 form) over K ranges, then the sum of the ranges
+    if (path == 7) {   // tiled kernel over K ranges, then the sum of the ranges
       if (!tile_gemm_supported(M, N, K, 0)) return fail(nullptr, CLOVER_E_SHAPE, "shape not supported by the tiled GEMM");
-      const int kp = path == 9 ? tile_wide_pick_k_parts(M, N, K) : tile_gemm_pick_k_parts(M, N, K);
+      const int kp = tile_gemm_pick_k_parts(M, N, K);
       TileGemm g;
       memset(&g, 0, sizeof(g));
       g.Xhi = hi; g.Xlo = lo; g.ldx = K;
       g.W[0] = g.W[1] = wp;
       g.Y = part; g.ldy = N; g.k_parts = kp; g.split_stride = (size_t)M * N;
-      g.M = M; g.N = N; g.K = K; g.epi = 0; g.wide = path == 9;
+      g.M = M; g.N = N; g.K = K; g.epi = 0;
       launch_gemm_tile(g, st);
       launch_reduce(part, kp, (size_t)M * N, N, nullptr, dtype, Y, ldy, M, N, 0, st);
       const hipError_t e = hipGetLastError();

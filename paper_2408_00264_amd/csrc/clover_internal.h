@@ -216,7 +216,7 @@ bool panel_gemm_supported(int M, int N, int K, int epi);
 int panel_gemm_pick_k_parts(int M, int N, int K);
 void launch_gemm_panel(const PanelGemm& g, hipStream_t st);
 
-// ---- tiled GEMM for 65..256 rows: one weight pass, wavefronts tile rows x columns ------------------
+// ---- tiled GEMM for 65..256 rows: one weight pass, 128-row x 256-column workgroup tiles ------------------
 struct TileGemm {
   const bf16_t *Xhi, *Xlo; int ldx;   // activation planes [M, K]
   const bf16_t* W[2];                 // fragment-major; epi 1: W[0] = gate, W[1] = up, each [N, K]
@@ -226,12 +226,10 @@ struct TileGemm {
   int epi;                            // 0 plain, 1 SwiGLU
   int k_parts; size_t split_stride;   // epi 0 only
   int dbg;                            // ablation builds only: 1 no activation staging, 2 no LDS reads, 4 no weight loads, 8 no barrier
-  int wide;                           // 1: the 128-row x 256-column form (one wavefront per SIMD)
-  int n_units;                        // filled in by launch_gemm_tile (wide form): column tiles x K ranges
+  int n_units;                        // filled in by launch_gemm_tile: column tiles x K ranges
 };
 bool tile_gemm_supported(int M, int N, int K, int epi);
 int tile_gemm_pick_k_parts(int M, int N, int K);
-int tile_wide_pick_k_parts(int M, int N, int K);
 void launch_gemm_tile(const TileGemm& g, hipStream_t st);
 
 // ---- fused bookkeeping kernels of the draft head (MFMA path, bf16 weights) ----------------------

@@ -7,12 +7,7 @@
 // weight fragments against ALL rows (kernels_stream / kernels_panel).  With 128..256 rows that layout reads
 // 16 KB of activation fragments from the LDS per 32 matrix instructions of a wavefront -- the whole LDS
 // bandwidth of the CU -- so the 128-row form of the panel kernel sits at ~30 % of the matrix peak and 256 rows
-// need two weight passes.  Here a workgroup owns a 128-column tile of the output for all rows and its
-// wavefronts tile it in two dimensions: wavefront (wm, wn) multiplies rows [64 wm, 64 wm + 64) by columns
-// [64 wn, 64 wn + 64), i.e. 4 x 4 blocks of 16 x 16 with 12 fragment reads per 32 matrix instructions, of
-// which only the 8 activation fragments come from the LDS (the 4 weight fragments are read from global memory
-// in the library's fragment-major order; the wavefronts that share them hit the CU's L1).  Activations are
-// staged through the LDS in 64-column stages, double buffered, one barrier per stage; activations are
+// need two weight passes.  Here the wavefronts of a workgroup tile the output in two dimensions; activations are
 // hi + lo bf16 planes (two matrix instructions per fragment pair), accumulation in fp32.
 #include "clover_internal.h"
 
@@ -34,7 +29,6 @@ union Frag {
 
 constexpr int TL_KST = 64;            // K columns per activation stage (2 k-tiles of 32)
 constexpr int TL_LDK = TL_KST + 8;    // LDS row stride (bf16): +16 B keeps the 16 rows of a fragment read on distinct banks
-constexpr int TL_NW = 2;              // wavefront columns per workgroup (64 output columns each)
 
 template <int I, int N, class F>
 __device__ __forceinline__ void static_for(F&& f) {
@@ -46,186 +40,14 @@ __device__ __forceinline__ void static_for(F&& f) {
 
 __device__ __forceinline__ unsigned t_rn(float a) { return (unsigned)__builtin_bit_cast(unsigned short, (__bf16)a); }
 
-// MQ: 64-row quarters (1..4); the workgroup has MQ x 2 wavefronts
-template <int MQ, int EPI>
-__global__ __launch_bounds__(MQ * TL_NW * 64) void gemm_tile_kernel(TileGemm p) {
-  constexpr int NT = MQ * TL_NW * 64;
-  constexpr int ROWS = MQ * 64;
-  constexpr int PLANE = ROWS * TL_LDK;                 // bf16 elements per plane of one stage buffer
-  constexpr int BUF = 2 * PLANE;
-  constexpr int XIT = 2 * ROWS * (TL_KST / 8) / NT;    // 16-byte pieces per thread and stage (= 8)
-  extern __shared__ __attribute__((aligned(16))) bf16_t xs[];   // [2 buffers][hi, lo][ROWS][TL_LDK]
-
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int l16 = lane & 15, g4 = lane >> 4;
-  const int wm = wave / TL_NW, wn = wave % TL_NW;
-  const int KT = p.K / 32;
-  const int part = (int)blockIdx.x % p.k_parts, tile = (int)blockIdx.x / p.k_parts;
-  const int NS = p.K / TL_KST / p.k_parts;             // stages of this workgroup's K range
-  const int ks0 = part * NS;
-
-  // the four 16-column weight blocks of this wavefront
-  const bf16_t* wbase[4];
-  int nb[4];
-#pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    if (EPI == 1) {   // 32 columns of F per wavefront: blocks 0,1 gate rows, blocks 2,3 the up rows of the same columns
-      nb[c] = min((tile * TL_NW + wn) * 2 + (c & 1), p.N / 16 - 1);
-      wbase[c] = p.W[c >> 1] + (size_t)nb[c] * KT * 512 + lane * 8;
-    } else {
-      nb[c] = min((tile * TL_NW + wn) * 4 + c, p.N / 16 - 1);
-      wbase[c] = p.W[0] + (size_t)nb[c] * KT * 512 + lane * 8;
-    }
-  }
-
-  f32x4 acc[4][4];   // [column block][row block]
-#pragma unroll
-  for (int c = 0; c < 4; ++c)
-#pragma unroll
-    for (int rb = 0; rb < 4; ++rb) acc[c][rb] = (f32x4){0.f, 0.f, 0.f, 0.f};
-
-  // Weight fragments are requested RING - 1 k-tiles ahead of their use (a ring of register buffers): with two
-  // wavefronts per SIMD the matrix pipe only stays busy if a k-tile's 32 instructions never wait for memory.  Three
-  // buffers where the 256-register budget of eight wavefronts per CU is tight, four otherwise.
-  constexpr int RING = MQ >= 3 ? 3 : 4;
-  Frag w[RING][4];   // [k-tile modulo RING][column block]
-  const int n_kt = NS * 2;
-  auto load_w = [&](auto tc, int kt) {   // kt: k-tile within this workgroup's K range
-    constexpr int t = decltype(tc)::value;
-    const size_t off = (size_t)(ks0 * 2 + kt) * 512;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      if (CLV_DBG(p, 4) && kt > 2) continue;
-      w[t][c].u = *(const u32x4*)(wbase[c] + off);   // (plain load: the wavefronts of the other row quarters read the same fragment from the L1)
-    }
-  };
-  u32x4 xv[XIT];
-  auto x_load = [&](int s) {
-#pragma unroll
-    for (int it = 0; it < XIT; ++it) {
-      const int idx = it * NT + tid;
-      const int rp = idx / (TL_KST / 8), sl = idx % (TL_KST / 8), plane = rp / ROWS, r = rp % ROWS;
-      const bf16_t* src = (plane ? p.Xlo : p.Xhi) + (size_t)min(r, p.M - 1) * p.ldx + (ks0 + s) * TL_KST + sl * 8;
-      u32x4 v = (u32x4){0u, 0u, 0u, 0u};
-      if (!CLV_DBG(p, 1)) v = *(const u32x4*)src;
-      xv[it] = r < p.M ? v : (u32x4){0u, 0u, 0u, 0u};
-    }
-  };
-  auto x_store = [&](int b) {
-    if (CLV_DBG(p, 1)) return;
-#pragma unroll
-    for (int it = 0; it < XIT; ++it) {
-      const int idx = it * NT + tid;
-      const int rp = idx / (TL_KST / 8), sl = idx % (TL_KST / 8), plane = rp / ROWS, r = rp % ROWS;
-      *(u32x4*)(xs + b * BUF + plane * PLANE + r * TL_LDK + sl * 8) = xv[it];
-    }
-  };
-  auto compute = [&](auto tc, int b, int half) {
-    constexpr int t = decltype(tc)::value;
-    const bf16_t* hi = xs + b * BUF + (wm * 64 + l16) * TL_LDK + g4 * 8 + half * 32;
-    const bf16_t* lo = hi + PLANE;
-#pragma unroll
-    for (int rb = 0; rb < 4; ++rb) {
-      Frag bh, bl;
-      if (CLV_DBG(p, 2)) { bh.u = w[t][rb].u; bl.u = w[t][3 - rb].u; }
-      else {
-        bh.u = *(const u32x4*)(hi + rb * 16 * TL_LDK);
-        bl.u = *(const u32x4*)(lo + rb * 16 * TL_LDK);
-      }
-#pragma unroll
-      for (int c = 0; c < 4; ++c) acc[c][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[t][c].v, bl.v, acc[c][rb], 0, 0, 0);
-#pragma unroll
-      for (int c = 0; c < 4; ++c) acc[c][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[t][c].v, bh.v, acc[c][rb], 0, 0, 0);
-    }
-  };
-
-  static_for<0, RING - 1>([&](auto ic) {
-    if (decltype(ic)::value < n_kt) load_w(ic, decltype(ic)::value);
-  });
-  x_load(0);
-  x_store(0);
-  __syncthreads();
-  // one k-tile: request the tile RING - 1 ahead into the buffer that was multiplied last, multiply this one
-  auto tile_step = [&](auto cur, auto nxt, int kt, int b) {
-    if (kt + RING - 1 < n_kt) load_w(nxt, kt + RING - 1);
-    __builtin_amdgcn_sched_barrier(0);
-    compute(cur, b, kt & 1);
-    __builtin_amdgcn_sched_barrier(0);
-  };
-  for (int s0 = 0; s0 < NS; s0 += RING) {   // RING stages = 2 RING k-tiles per iteration: static buffer indices
-    static_for<0, RING>([&](auto jc) {
-      constexpr int j = decltype(jc)::value;
-      const int st = s0 + j;
-      if (st < NS) {                          // uniform over the workgroup
-        const int b = st & 1;
-        if (st + 1 < NS) x_load(st + 1);
-        tile_step(std::integral_constant<int, (2 * j) % RING>{}, std::integral_constant<int, (2 * j + RING - 1) % RING>{}, 2 * st, b);
-        tile_step(std::integral_constant<int, (2 * j + 1) % RING>{}, std::integral_constant<int, (2 * j + RING) % RING>{}, 2 * st + 1, b);
-        if (st + 1 < NS) x_store(b ^ 1);
-        if (!CLV_DBG(p, 8)) __syncthreads();
-      }
-    });
-  }
-
-  // ---- epilogue: lane holds rows rb*16 + l16 of its quarter, columns 4*g4 .. 4*g4+3 of each block ----
-  if (EPI == 1) {
-    const int fblock = (tile * TL_NW + wn) * 2;
-#pragma unroll
-    for (int c = 0; c < 2; ++c) {
-      if ((fblock + c) * 16 >= p.N) continue;
-      const int col = (fblock + c) * 16 + 4 * g4;
-#pragma unroll
-      for (int rb = 0; rb < 4; ++rb) {
-        const int m = wm * 64 + rb * 16 + l16;
-        if (m >= p.M) continue;
-        unsigned h[4], l[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const float g = acc[c][rb][r], u = acc[c + 2][rb][r];
-          const float o = g / (1.0f + expf(-g)) * u;
-          h[r] = t_rn(o);
-          l[r] = t_rn(o - __uint_as_float(h[r] << 16));
-        }
-        *(uint2*)(p.Yhi + (size_t)m * p.ldo + col) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
-        *(uint2*)(p.Ylo + (size_t)m * p.ldo + col) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
-      }
-    }
-  } else {
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const int blk = (tile * TL_NW + wn) * 4 + c;
-      if (blk * 16 >= p.N) continue;
-      const int col = blk * 16 + 4 * g4;
-#pragma unroll
-      for (int rb = 0; rb < 4; ++rb) {
-        const int m = wm * 64 + rb * 16 + l16;
-        const f32x4 v = acc[c][rb];
-        if (m < p.M) *(float4*)(p.Y + part * p.split_stride + (size_t)m * p.ldy + col) = make_float4(v[0], v[1], v[2], v[3]);
-      }
-    }
-  }
-}
-
-template <int MQ, int EPI>
-void launch_tile_one(const TileGemm& g, int wgs, hipStream_t st) {
-  constexpr size_t lds = (size_t)2 * 2 * MQ * 64 * TL_LDK * sizeof(bf16_t);
-  static_assert(lds <= 160 * 1024, "stage buffers exceed the LDS");
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipFuncSetAttribute((const void*)gemm_tile_kernel<MQ, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    attr_done = true;
-  }
-  gemm_tile_kernel<MQ, EPI><<<wgs, MQ * TL_NW * 64, lds, st>>>(g);
-}
-
-
 // ------------------------------------------------------------------------------------------
-// Wide form: workgroup tile 128 rows x 256 columns, four wavefronts (one per SIMD), wavefront tile 128 x 64.
+// Workgroup tile 128 rows x 256 columns, four wavefronts (one per SIMD), wavefront tile 128 x 64.
 //
-// Why.  In the 256 x 128 form above a compute unit moves, per 64-column K stage, 64 KB of activations and 64 KB of
-// weight fragments through its vector L1 (every weight fragment is fetched by the four wavefronts of the four row
-// quarters): at 64 B/clk that is exactly as long as the stage's 2048 matrix-pipe cycles, so nothing overlaps for
-// free.  A 128 x 256 tile needs half the activation rows per column and lets every wavefront own its columns:
+// Why this shape.  A first version (256 x 128 tiles, 4 x 2 wavefronts of 64 x 64, two per SIMD) moved, per 64-column
+// K stage, 64 KB of activations and 64 KB of weight fragments through a compute unit's vector L1 (every weight
+// fragment fetched by the four wavefronts of the four row quarters): at 64 B/clk exactly as long as the stage's 2048
+// matrix-pipe cycles, so nothing overlapped for free, and it ran at 0.30 of the matrix peak.  A 128 x 256 tile
+// needs half the activation rows per column and lets every wavefront own its columns:
 // per stage 32 KB of activations + 32 KB of weight fragments (each fetched once) pass the L1, the LDS serves 128 KB of
 // fragment reads and takes 32 KB of stores (62 % of the stage).  One wavefront per SIMD has the 512-register budget
 // that the software pipeline needs: 128 accumulators, two sets of 16 activation fragments (the next k-tile's
@@ -495,18 +317,10 @@ bool tile_gemm_supported(int M, int N, int K, int epi) {
   if (M < 1 || M > 256 || K % TL_KST != 0 || N % 16 != 0) return false;
   return epi == 1 || N % 4 == 0;
 }
-// K ranges for an output too narrow to give every CU a tile: the largest divisor of the stage count that keeps the grid
-// within one workgroup per CU and at least 8 stages per range; 1 when the tiles alone fill the chip
+// K ranges for an output too narrow to give every CU a workgroup: the largest divisor of the stage count that keeps
+// the grid within one workgroup per CU and at least 8 stages per range; column tiles of 256 (epi 1: 128 columns of
+// F), one or two row halves
 int tile_gemm_pick_k_parts(int M, int N, int K) {
-  const int tiles = (N / 16 + 7) / 8, NS = K / TL_KST;
-  int best = 1;
-  for (int d = 1; d <= NS; ++d)
-    if (NS % d == 0 && tiles * d <= 256 && NS / d >= 8) best = d;
-  return best;
-}
-
-// wide form: column tiles of 256 (epi 1: 128 columns of F), one or two row halves
-int tile_wide_pick_k_parts(int M, int N, int K) {
   const int tiles = (N / 16 + 15) / 16 * (M > TW_ROWS ? 2 : 1), NS = K / TL_KST;
   int best = 1;
   for (int d = 1; d <= NS; ++d)
@@ -518,29 +332,12 @@ void launch_gemm_tile(const TileGemm& g_in, hipStream_t st) {
   TileGemm g = g_in;
   g.dbg = tune_int("CLOVER_TILE_DBG", 0);
   if (g.k_parts < 1 || g.epi == 1) g.k_parts = 1;
-  if (g.wide) {
-    const int blocks = g.N / 16;
-    const int tiles = g.epi == 1 ? (blocks + 7) / 8 : (blocks + 15) / 16;
-    g.n_units = tiles * g.k_parts;
-    const int wgs = g.M > TW_ROWS ? (g.n_units + 7) / 8 * 8 * 2 : g.n_units;
-    if (g.epi == 1) launch_tile_wide<1>(g, wgs, st);
-    else launch_tile_wide<0>(g, wgs, st);
-    return;
-  }
   const int blocks = g.N / 16;
-  const int tiles = g.epi == 1 ? (blocks + 3) / 4 : (blocks + 7) / 8;   // 64 columns of F (gate + up) or 128 columns
-  const int wgs = tiles * g.k_parts;
-  const int mq = (g.M + 63) / 64;
-#define CLV_TL(MQ_)                                              \
-  if (g.epi == 1) launch_tile_one<MQ_, 1>(g, wgs, st);            \
-  else launch_tile_one<MQ_, 0>(g, wgs, st);
-  switch (mq) {
-    case 1: CLV_TL(1) break;
-    case 2: CLV_TL(2) break;
-    case 3: CLV_TL(3) break;
-    default: CLV_TL(4) break;
-  }
-#undef CLV_TL
+  const int tiles = g.epi == 1 ? (blocks + 7) / 8 : (blocks + 15) / 16;
+  g.n_units = tiles * g.k_parts;
+  const int wgs = g.M > TW_ROWS ? (g.n_units + 7) / 8 * 8 * 2 : g.n_units;
+  if (g.epi == 1) launch_tile_wide<1>(g, wgs, st);
+  else launch_tile_wide<0>(g, wgs, st);
 }
 
 }  // namespace clv

@@ -41,12 +41,10 @@ GEMM_CASES = [
     # 65..128 rows in one weight pass (eight row blocks, 128-column stages): plain, odd rows, K ranges
     (3, 1, 128, 4096, 1024), (3, 1, 97, 28672, 4096), (5, 1, 96, 4096, 14336), (5, 1, 128, 6144, 4096),
     (5, 1, 65, 4096, 4096),
-    # tiled kernel (one weight pass for up to 256 rows): full, ragged rows in every 64-row quarter, narrow and odd widths
-    (7, 1, 256, 4096, 4096), (7, 1, 160, 6144, 4096), (7, 1, 97, 4096, 14336), (7, 1, 33, 1040, 512), (7, 1, 200, 8208, 1024),
-    (7, 1, 256, 28672, 4096),
-    # its 128-row x 256-column form: two row halves, a ragged second half, one half only, odd widths, K ranges, one stage
-    (9, 1, 256, 4096, 4096), (9, 1, 160, 6144, 4096), (9, 1, 129, 4096, 14336), (9, 1, 97, 1040, 512), (9, 1, 200, 8208, 1024),
-    (9, 1, 256, 28672, 4096), (9, 1, 255, 512, 128), (9, 1, 256, 2064, 384),
+    # tiled kernel (one weight pass for up to 256 rows, 128 x 256 workgroup tiles): two row halves, a ragged second half,
+    # one half only, odd widths, K ranges, one stage
+    (7, 1, 256, 4096, 4096), (7, 1, 160, 6144, 4096), (7, 1, 129, 4096, 14336), (7, 1, 97, 1040, 512), (7, 1, 200, 8208, 1024),
+    (7, 1, 256, 28672, 4096), (7, 1, 255, 512, 128), (7, 1, 256, 2064, 384), (7, 1, 33, 1040, 512), (7, 1, 97, 4096, 14336),
 ]
 
 
