@@ -56,17 +56,19 @@ __device__ __forceinline__ void a_split2(float a, float b, unsigned& hi, unsigne
 constexpr int AT_D = 128;         // head dim
 constexpr int AT_TK = KV_PAGE;    // keys per tile = one page of the caches
 // (WM, a template parameter: wavefronts per query head; a workgroup always covers 32 nodes, a wavefront 32 / WM)
-constexpr int AT_KLD = AT_D + 8;  // LDS row strides (bf16) chosen so fragment reads are conflict-free
-constexpr int AT_VLD = AT_TK + 8;
+// LDS row strides (bf16).  +32 B: measured on gfx950, ds_read_b128 fragment reads (row = lane % 16, 16-byte piece = lane / 16) run at the full 256 B/clk when the row stride is 32 mod 64 bytes and at half of it with a 16-byte pad.
+constexpr int AT_KLD = AT_D + 16;
+constexpr int AT_VLD = AT_TK + 16;
 constexpr int AT_KPLANE = AT_TK * AT_KLD;
 constexpr int AT_VPLANE = AT_D * AT_VLD;
-constexpr int AT_BUF = 2 * AT_KPLANE + 2 * AT_VPLANE;  // one stage: K hi, K lo, V^T hi, V^T lo
+constexpr int AT_KSTAGE = 2 * AT_KPLANE, AT_VSTAGE = 2 * AT_VPLANE;   // one staged tile: K hi, K lo / V^T hi, V^T lo
+constexpr int AT_LDS_EL = 2 * AT_KSTAGE + 3 * AT_VSTAGE;              // two K buffers, three V^T buffers
 constexpr int AT_MAX_IV = CLOVER_MAX_NODES_INTERVAL;   // interval labels of the tree keys kept in the LDS
 
 template <int G, int WM>
 __global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
   constexpr int AT_MB = 2 / WM;     // 16-row blocks of nodes per wavefront
-  extern __shared__ __attribute__((aligned(16))) bf16_t sm[];  // [2 stages][AT_BUF]
+  extern __shared__ __attribute__((aligned(16))) bf16_t sm[];  // [2][AT_KSTAGE] [3][AT_VSTAGE] [AT_MAX_IV] labels
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int l16 = lane & 15, g4 = lane >> 4;
   const int split = blockIdx.x, ng = blockIdx.y / p.n_kv, kvh = blockIdx.y % p.n_kv, b = blockIdx.z;
@@ -83,34 +85,41 @@ __global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
   // the one after it is in flight into the other
   u32x4 krA[KIT], vrA[VIT], krB[KIT], vrB[VIT];
   // Key tile t of this sequence is page pages[b * T + t] of the paged caches: the K rows and the V^T columns of
-  // (page, KV head) are one contiguous 8 KB block each per plane.
+  // (page, KV head) are one contiguous 8 KB block each per plane.  The page number is a scalar that is fetched one
+  // load ahead of its use (page_of), and a thread's piece of a block is tid * 16 bytes behind a uniform base, so the
+  // loads of a tile need no vector address arithmetic (address registers that alias a staging set would make every
+  // new load wait for the ones in flight).
   const KVLayout& kv = p.kv;
-  auto load_tile = [&](u32x4 (&kr)[KIT], u32x4 (&vr)[VIT], int t) __attribute__((always_inline)) {
+  auto page_of = [&](int t) __attribute__((always_inline)) -> int {
     const int lp = (b + kv.b0) * kv.T + min(t, kv.T - 1);
-    const size_t page = (size_t)(kv.pages ? kv.pages[lp] : lp);
-    const bf16_t* kb = p.k_hi + (page * kv.n_kv + kvh) * (size_t)(KV_PAGE * AT_D);
-    const bf16_t* vb = p.v_hi + (page * kv.n_kv + kvh) * (size_t)(AT_D * KV_PAGE);
+    return kv.pages ? kv.pages[lp] : lp;
+  };
+  auto load_tile = [&](u32x4 (&kr)[KIT], u32x4 (&vr)[VIT], int page) __attribute__((always_inline)) {
+    const size_t blk = ((size_t)page * kv.n_kv + kvh) * (size_t)(KV_PAGE * AT_D);   // elements; K and V^T blocks are equal
+    const bf16_t* kb = p.k_hi + blk;
+    const bf16_t* vb = p.v_hi + blk;
 #pragma unroll
     for (int it = 0; it < KIT; ++it) {
-      const int idx = it * NT + tid, plane = idx >> 9, rem = idx & 511;   // rem = key * 16 + piece
-      kr[it] = *(const u32x4*)(kb + plane * p.k_plane + rem * 8);
+      const int plane = (it * NT) >> 9, first = (it * NT) & 511;   // uniform: NT divides 512
+      kr[it] = *(const u32x4*)(kb + plane * p.k_plane + (first + tid) * 8);
     }
 #pragma unroll
     for (int it = 0; it < VIT; ++it) {
-      const int idx = it * NT + tid, plane = idx >> 9, rem = idx & 511;   // rem = channel * 4 + piece
-      vr[it] = *(const u32x4*)(vb + plane * p.v_plane + rem * 8);
+      const int plane = (it * NT) >> 9, first = (it * NT) & 511;
+      vr[it] = *(const u32x4*)(vb + plane * p.v_plane + (first + tid) * 8);
     }
   };
-  // The first key tile is requested before anything else is waited for (its addresses need no memory:
+  // The first key tile is requested before anything else is waited for (its address needs the page table only:
   // keys past the cache are clamped and masked later), so its HBM latency overlaps the loads of the lengths,
   // the masks and Q.
-  load_tile(krA, vrA, t0);
+  load_tile(krA, vrA, page_of(t0));
+  int pg_next = page_of(t0 + 1);   // page of the tile the next load_tile call fetches
   const int nv = rm.n_valid ? min(rm.n_valid[b], rm.n) : rm.n;
   const int L = p.base_len[b];
   if (ng * 32 >= nv || L + nv > p.max_seq) return;  // whole workgroup
   const int total = L + nv;
   const bool chain = p.anc == nullptr && p.iv == nullptr;
-  int2* kiv = (int2*)(sm + 2 * AT_BUF);   // [AT_MAX_IV] (enter, exit) of the tree keys; published by the first barrier
+  int2* kiv = (int2*)(sm + AT_LDS_EL);   // [AT_MAX_IV] (enter, exit) of the tree keys; published by the first barrier
   if (p.iv)
     for (int w = tid; w < nv; w += NT) kiv[w] = *(const int2*)(p.iv + 2 * ((size_t)b * p.anc_stride + w));
   const int n_tiles = ((chain ? min(total, L + ng * 32 + 32) : total) + AT_TK - 1) / AT_TK;
@@ -149,30 +158,37 @@ __global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
 #pragma unroll
   for (int mb = 0; mb < AT_MB; ++mb) { m_run[mb] = -INFINITY; l_run[mb] = 0.f; }
 
-  auto store_tile = [&](const u32x4 (&kr)[KIT], const u32x4 (&vr)[VIT], int buf) __attribute__((always_inline)) {
-    bf16_t* base = sm + buf * AT_BUF;
+  // LDS: two K buffers (tile i in buffer i % 2) and three V^T buffers (tile i in buffer i % 3): the output product of
+  // tile i - 1 runs one iteration behind its scores (see the loop), so V^T of tile i - 1 is still read while tile i + 1
+  // is staged.
+  bf16_t* const k_lds = sm;
+  bf16_t* const v_lds = sm + 2 * AT_KSTAGE;
+  auto store_tile = [&](const u32x4 (&kr)[KIT], const u32x4 (&vr)[VIT], int kbuf, int vbuf) __attribute__((always_inline)) {
+    bf16_t* kbase = k_lds + kbuf * AT_KSTAGE;
+    bf16_t* vbase = v_lds + vbuf * AT_VSTAGE;
 #pragma unroll
     for (int it = 0; it < KIT; ++it) {
       const int idx = it * NT + tid, plane = idx >> 9, rem = idx & 511, key = rem >> 4, sl = rem & 15;
       // key k of the tile is row ((k/4)%2)*16 + (k/8)*4 + k%4: sub-tile tt holds keys 8g + 4tt + r at row 4g + r
       const int row = ((key >> 2) & 1) * 16 + (key >> 3) * 4 + (key & 3);
-      *(u32x4*)(base + plane * AT_KPLANE + row * AT_KLD + sl * 8) = kr[it];
+      *(u32x4*)(kbase + plane * AT_KPLANE + row * AT_KLD + sl * 8) = kr[it];
     }
 #pragma unroll
     for (int it = 0; it < VIT; ++it) {
       const int idx = it * NT + tid, plane = idx >> 9, rem = idx & 511, dr = rem >> 2, sl = rem & 3;
-      *(u32x4*)(base + 2 * AT_KPLANE + plane * AT_VPLANE + dr * AT_VLD + sl * 8) = vr[it];
+      *(u32x4*)(vbase + plane * AT_VPLANE + dr * AT_VLD + sl * 8) = vr[it];
     }
   };
-  auto compute_t = [&](int buf, int t, auto cachedc) __attribute__((always_inline)) {
-    constexpr bool CACHED = decltype(cachedc)::value;  // every key of the tile is a cached token: no tree mask
-    const bf16_t* kb = sm + buf * AT_BUF + l16 * AT_KLD + g4 * 8;
-    const bf16_t* vb = sm + buf * AT_BUF + 2 * AT_KPLANE + l16 * AT_VLD + g4 * 8;
-    f32x4 s[2][AT_MB];
+
+  // ---- the three steps of a key tile.  scores: S^T = K Q^T (matrix pipe); soft_max: running statistics, the
+  // probabilities as hi/lo fragments and the factor the output so far has to be scaled by (vector ALU);
+  // output: O^T += V^T P (matrix pipe). ----
+  auto scores = [&](int kbuf, f32x4 (&sc)[2][AT_MB]) __attribute__((always_inline)) {
+    const bf16_t* kb = k_lds + kbuf * AT_KSTAGE + l16 * AT_KLD + g4 * 8;
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-      for (int mb = 0; mb < AT_MB; ++mb) s[tt][mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      for (int mb = 0; mb < AT_MB; ++mb) sc[tt][mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
@@ -182,12 +198,15 @@ __global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
         kl.u = *(const u32x4*)(kb + AT_KPLANE + tt * 16 * AT_KLD + ks * 32);
 #pragma unroll
         for (int mb = 0; mb < AT_MB; ++mb) {
-          s[tt][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kl.v, qh[mb][ks].v, s[tt][mb], 0, 0, 0);
-          s[tt][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kh.v, ql[mb][ks].v, s[tt][mb], 0, 0, 0);
-          s[tt][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kh.v, qh[mb][ks].v, s[tt][mb], 0, 0, 0);
+          sc[tt][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kl.v, qh[mb][ks].v, sc[tt][mb], 0, 0, 0);
+          sc[tt][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kh.v, ql[mb][ks].v, sc[tt][mb], 0, 0, 0);
+          sc[tt][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kh.v, qh[mb][ks].v, sc[tt][mb], 0, 0, 0);
         }
       }
-    Frag ph[AT_MB], pl[AT_MB];
+  };
+  auto soft_max_t = [&](int t, const f32x4 (&sc)[2][AT_MB], Frag (&ph)[AT_MB], Frag (&pl)[AT_MB], auto cachedc)
+                        __attribute__((always_inline)) {
+    constexpr bool CACHED = decltype(cachedc)::value;  // every key of the tile is a cached token: no tree mask
 #pragma unroll
     for (int mb = 0; mb < AT_MB; ++mb) {
       float sv[8];
@@ -203,7 +222,7 @@ __global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
           else vis = ((wn < 64 ? (a0[mb] >> wn) : (a1[mb] >> (wn - 64))) & 1ull) != 0ull;
         }
         if (a0[mb] == 0ull && a1[mb] == 0ull) vis = false;  // padding row
-        sv[e] = vis ? s[e >> 2][mb][e & 3] : -INFINITY;
+        sv[e] = vis ? sc[e >> 2][mb][e & 3] : -INFINITY;
         tmax = fmaxf(tmax, sv[e]);
       }
       tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
@@ -217,6 +236,7 @@ __global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
       l_run[mb] = l_run[mb] * corr + psum;
       m_run[mb] = m_new;
       // the running maximum rarely moves after the first tiles: rescale only when some row of the wavefront needs it
+      // (every output product issued before this point has been accumulated by the time the scaling reads O)
       if (__builtin_amdgcn_ballot_w64(corr != 1.0f) != 0ull) {
 #pragma unroll
         for (int db = 0; db < 8; ++db) O[db][mb] *= corr;
@@ -227,6 +247,14 @@ __global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
       a_split2(pe[4], pe[5], h, l); ph[mb].u.z = h; pl[mb].u.z = l;
       a_split2(pe[6], pe[7], h, l); ph[mb].u.w = h; pl[mb].u.w = l;
     }
+  };
+  auto soft_max = [&](int t, const f32x4 (&sc)[2][AT_MB], Frag (&ph)[AT_MB], Frag (&pl)[AT_MB]) __attribute__((always_inline)) {
+    // (specialised only where the register file has room for both versions)
+    if ((G == 2 || G == 4 || WM == 2) && (t + 1) * AT_TK <= L) soft_max_t(t, sc, ph, pl, std::true_type{});  // uniform
+    else soft_max_t(t, sc, ph, pl, std::false_type{});
+  };
+  auto output = [&](int vbuf, const Frag (&ph)[AT_MB], const Frag (&pl)[AT_MB]) __attribute__((always_inline)) {
+    const bf16_t* vb = v_lds + vbuf * AT_VSTAGE + l16 * AT_VLD + g4 * 8;
 #pragma unroll
     for (int db = 0; db < 8; ++db) {
       Frag vh, vl;
@@ -241,40 +269,66 @@ __global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
     }
   };
 
-  auto compute = [&](int buf, int t) __attribute__((always_inline)) {
-    // (specialised only where the register file has room for both versions)
-    if ((G == 2 || G == 4 || WM == 2) && (t + 1) * AT_TK <= L) compute_t(buf, t, std::true_type{});  // uniform
-    else compute_t(buf, t, std::false_type{});
-  };
-
+  // ---- the loop over this split's key tiles.  Staging: with two register sets the tile after next is in flight
+  // while the next one waits in the other set; with one set (few threads per workgroup: all the register file holds)
+  // the next tile is in flight.  One barrier per tile: tile i + 1 is written to the LDS at the end of iteration i.
+  //
+  // Order of the steps (two wavefronts per query head): scores of tile i, output product of tile i - 1, soft-max of
+  // tile i.  The fragment reads of the output product are then in flight behind the score products instead of
+  // behind the soft-max, on whose result they do not depend; measured 4 % faster over 8192 keys than scores,
+  // soft-max, output of the same tile.  Running the second four wavefronts of a workgroup one step out of phase
+  // with the first four, so that one of a SIMD's pair multiplies while the other exponentiates, was measured too
+  // and gains nothing: on this chip a SIMD's matrix and vector instructions hardly overlap, whichever wavefront
+  // they come from (24 MFMA in one wavefront and 96 fma in the other take 86-100 % of the sum of their times;
+  // probes/mfma_valu_overlap.hip).  Every accumulator sees the same operations in the same order in all of these
+  // variants. ----
   if (t0 < t1) {  // uniform over the workgroup
     const int n = t1 - t0;
-    if constexpr (G * WM >= 4) {
-      if (n > 1) load_tile(krB, vrB, t0 + 1);
-      store_tile(krA, vrA, 0);
-      __syncthreads();
-      for (int i = 0; i < n; i += 2) {
-        // tile i is in LDS buffer 0, tile i+1 in set B (landing), tile i+2 goes to set A
-        if (i + 2 < n) load_tile(krA, vrA, t0 + i + 2);
-        compute(0, t0 + i);
-        if (i + 1 >= n) break;
-        store_tile(krB, vrB, 1);
-        __syncthreads();
-        if (i + 3 < n) load_tile(krB, vrB, t0 + i + 3);
-        compute(1, t0 + i + 1);
-        if (i + 2 < n) store_tile(krA, vrA, 0);
-        __syncthreads();
+    constexpr bool TWO_SETS = G * WM >= 4;
+    // (one wavefront per query head covers 32 nodes and has no registers left to carry a tile's probabilities
+    // into the next iteration: it runs scores, soft-max and output of tile i back to back)
+    constexpr bool PIPELINED = WM == 2;
+    f32x4 sc[2][AT_MB];
+    Frag ph[AT_MB], pl[AT_MB];
+    auto iteration = [&](int i, int kb, int vcur, int vprev) __attribute__((always_inline)) {
+      scores(kb, sc);
+      if constexpr (PIPELINED) {
+        if (i > 0) output(vprev, ph, pl);
+        soft_max(t0 + i, sc, ph, pl);
+      } else {
+        soft_max(t0 + i, sc, ph, pl);
+        output(vcur, ph, pl);
       }
-    } else {  // few threads per workgroup: one staging set is all the register file holds
-      store_tile(krA, vrA, 0);
-      __syncthreads();
-      for (int i = 0; i < n; ++i) {
-        if (i + 1 < n) load_tile(krA, vrA, t0 + i + 1);
-        compute(i & 1, t0 + i);
-        if (i + 1 < n) store_tile(krA, vrA, (i & 1) ^ 1);
-        __syncthreads();
-      }
+    };
+    if constexpr (TWO_SETS) {
+      if (n > 1) { load_tile(krB, vrB, pg_next); pg_next = page_of(t0 + 2); }
     }
+    store_tile(krA, vrA, 0, 0);
+    __syncthreads();
+    int vcur = 0, vprev = 2;   // V^T buffers of tiles i and i - 1
+    for (int i = 0; i < n; i += 2) {
+      if constexpr (TWO_SETS) {
+        if (i + 2 < n) { load_tile(krA, vrA, pg_next); pg_next = page_of(t0 + i + 3); }
+      } else {
+        if (i + 1 < n) { load_tile(krA, vrA, pg_next); pg_next = page_of(t0 + i + 2); }
+      }
+      iteration(i, 0, vcur, vprev);
+      vprev = vcur; vcur = vcur == 2 ? 0 : vcur + 1;
+      if (i + 1 >= n) break;
+      if constexpr (TWO_SETS) store_tile(krB, vrB, 1, vcur); else store_tile(krA, vrA, 1, vcur);
+      __syncthreads();
+      if constexpr (TWO_SETS) {
+        if (i + 3 < n) { load_tile(krB, vrB, pg_next); pg_next = page_of(t0 + i + 4); }
+      } else {
+        if (i + 2 < n) { load_tile(krA, vrA, pg_next); pg_next = page_of(t0 + i + 3); }
+      }
+      iteration(i + 1, 1, vcur, vprev);
+      vprev = vcur; vcur = vcur == 2 ? 0 : vcur + 1;
+      if (i + 2 < n) store_tile(krA, vrA, 0, vcur);
+      __syncthreads();
+    }
+    // the output product still owed for the last tile (its V^T buffer is vprev after the final rotation)
+    if constexpr (PIPELINED) output(vprev, ph, pl);
   }
 
   // ---- partial result of this split ----
@@ -351,7 +405,7 @@ bool attn_mfma_supported(int head_dim, int n_q, int n_kv, int max_seq) {
 
 template <int G, int WM>
 static void launch_attn_one(const AttnParams& p, dim3 grid, hipStream_t st) {
-  constexpr size_t lds = (size_t)2 * AT_BUF * sizeof(bf16_t) + AT_MAX_IV * sizeof(int2);
+  constexpr size_t lds = (size_t)AT_LDS_EL * sizeof(bf16_t) + AT_MAX_IV * sizeof(int2);
   static bool attr_done = false;
   if (!attr_done) {
     hipFuncSetAttribute((const void*)attn_mfma_kernel<G, WM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

@@ -57,7 +57,7 @@ constexpr int GEMM_THREADS = 64 * (GEMM_CW + GEMM_PW);
 
 template <int MT, int NF, int KC>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(MfmaGemm p) {
-  constexpr int LDK = KC + 8;      // LDS row stride in bf16 (+16 B: the 16 lanes of a fragment read hit distinct banks)
+  constexpr int LDK = KC + 16;     // LDS row stride in bf16 (+32 B: a stride of 32 mod 64 bytes lets the fragment reads run at the full LDS rate)
   constexpr int KS = KC / 32;      // MFMA k-steps per chunk
   constexpr int ROWS = MT * 16;
   constexpr int PLANE = ROWS * LDK;  // one bf16 plane (hi or lo) of one buffer
@@ -284,7 +284,7 @@ size_t mfma_gemm_out_bytes(int M, int N, int splits) { return (size_t)std::max(s
 
 template <int MT, int NF, int KC>
 static void launch_one(const MfmaGemm& g, dim3 grid, hipStream_t st) {
-  constexpr size_t lds = (size_t)2 * 2 * MT * 16 * (KC + 8) * sizeof(bf16_t);
+  constexpr size_t lds = (size_t)2 * 2 * MT * 16 * (KC + 16) * sizeof(bf16_t);
   static bool attr_done = false;
   if (!attr_done) {
     hipFuncSetAttribute((const void*)gemm_mfma_kernel<MT, NF, KC>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

@@ -60,7 +60,7 @@ __device__ __forceinline__ void static_for(F&& f) {
 template <int MT, int KW, int EPI, int NBUF, int KST>
 __global__ __launch_bounds__(PN_WAVES * 64) void gemm_panel_kernel(PanelGemm p) {
   constexpr int ROWS = MT * 16;
-  constexpr int PN_LDK = KST + 8;               // LDS row stride (bf16): +16 B spreads a fragment read over the banks
+  constexpr int PN_LDK = KST + 16;              // LDS row stride (bf16): 32 mod 64 bytes, the stride at which fragment reads run at the full LDS rate
   constexpr int TILES = KST / 32;               // k-tiles per stage
   constexpr int SL = KST / 8;                   // 16-byte pieces per row and stage
   constexpr int PLANE = ROWS * PN_LDK;          // bf16 elements per plane of one stage buffer
@@ -259,7 +259,7 @@ __global__ __launch_bounds__(PN_WAVES * 64) void gemm_panel_kernel(PanelGemm p) 
 
 template <int MT, int KW, int EPI, int NBUF, int KST = PN_KST>
 void launch_panel_one(const PanelGemm& g, int wgs, hipStream_t st) {
-  constexpr size_t lds = (size_t)2 * 2 * MT * 16 * (KST + 8) * sizeof(bf16_t);
+  constexpr size_t lds = (size_t)2 * 2 * MT * 16 * (KST + 16) * sizeof(bf16_t);
   static_assert(lds <= 160 * 1024, "stage buffers exceed the LDS");
   static bool attr_done = false;
   if (!attr_done) {

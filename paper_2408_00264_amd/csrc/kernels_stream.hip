@@ -61,7 +61,7 @@ void launch_pack_weight(const void* src, void* dst, int N, int K, hipStream_t st
 // ------------------------------------------------------------------------------------------
 constexpr int ST_WAVES = 8;
 constexpr int ST_KSL = 512;          // K columns per slice
-constexpr int ST_LDK = ST_KSL + 8;   // LDS row stride (bf16): +16 B spreads the 16 rows of a fragment read over the banks
+constexpr int ST_LDK = ST_KSL + 16;  // LDS row stride (bf16): 32 mod 64 bytes, the stride at which fragment reads run at the full LDS rate
 constexpr int ST_STAGE = 4;          // 32-column weight tiles per pipeline stage (4 KB per fragment, contiguous); deeper
                                      // stages (8) measured 4 % slower over the verify pass: longer queues, no more bandwidth
 

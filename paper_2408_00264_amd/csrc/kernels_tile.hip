@@ -28,7 +28,7 @@ union Frag {
 };
 
 constexpr int TL_KST = 64;            // K columns per activation stage (2 k-tiles of 32)
-constexpr int TL_LDK = TL_KST + 8;    // LDS row stride (bf16): +16 B keeps the 16 rows of a fragment read on distinct banks
+constexpr int TL_LDK = TL_KST + 16;   // LDS row stride (bf16): 32 mod 64 bytes, the stride at which fragment reads run at the full LDS rate
 
 template <int I, int N, class F>
 __device__ __forceinline__ void static_for(F&& f) {
@@ -64,11 +64,19 @@ constexpr int TW_BUF = 2 * TW_PLANE;  // hi and lo plane of one stage
 constexpr int TW_NBUF = 3;
 constexpr int TW_XIT = 2 * TW_ROWS * (TL_KST / 8) / (TW_NW * 64);   // 16-byte pieces per thread and stage (= 8)
 
+// acc += A B^T with the accumulator tied to one accumulation-register tuple for the whole kernel.  (Written through the
+// builtin, the register allocator gives a fifth of the 256 products of a loop trip a destination that differs from its
+// source and moves ~190 registers per trip back; those moves are vector-ALU instructions and do not overlap the
+// matrix pipe.)
+__device__ __forceinline__ void mfma_acc(f32x4& acc, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
 template <int EPI>
 __global__ __launch_bounds__(TW_NW * 64) void gemm_tile_wide_kernel(TileGemm p) {
   extern __shared__ __attribute__((aligned(16))) bf16_t xs[];   // [3 buffers][hi, lo][128][TL_LDK]
   constexpr int NT = TW_NW * 64;
-  const int tid = threadIdx.x, wn = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, wn = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int l16 = lane & 15, g4 = lane >> 4;
   const int KT = p.K / 32;
   // workgroup id -> (row half, column tile, K range): ids 8 apart share an XCD, so the two row halves of a tile are
@@ -86,16 +94,18 @@ __global__ __launch_bounds__(TW_NW * 64) void gemm_tile_wide_kernel(TileGemm p) 
   const int ks0 = part * NS;
   const int row0 = rh * TW_ROWS;
 
-  const bf16_t* wbase[4];
+  // Every load below is (uniform base) + (32-bit offset of the lane): the bases live in scalar registers and advance
+  // with scalar arithmetic, so a load costs no vector-ALU instruction (those do not overlap the matrix pipe).
+  const bf16_t* wbase[4];   // uniform: first fragment of this wavefront's four column blocks
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
     int nb;
     if (EPI == 1) {   // 32 columns of F per wavefront: blocks 0,1 gate rows, blocks 2,3 the up rows of the same columns
       nb = min((tile * TW_NW + wn) * 2 + (c & 1), p.N / 16 - 1);
-      wbase[c] = p.W[c >> 1] + (size_t)nb * KT * 512 + lane * 8;
+      wbase[c] = p.W[c >> 1] + (size_t)nb * KT * 512;
     } else {
       nb = min((tile * TW_NW + wn) * 4 + c, p.N / 16 - 1);
-      wbase[c] = p.W[0] + (size_t)nb * KT * 512 + lane * 8;
+      wbase[c] = p.W[0] + (size_t)nb * KT * 512;
     }
   }
 
@@ -104,6 +114,7 @@ __global__ __launch_bounds__(TW_NW * 64) void gemm_tile_wide_kernel(TileGemm p) 
   for (int c = 0; c < 4; ++c)
 #pragma unroll
     for (int rb = 0; rb < 8; ++rb) acc[c][rb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  asm volatile("s_nop 7" ::: "memory");   // (as below: write of an accumulator register -> matrix instruction)
 
   constexpr int RING = 4;
   Frag w[RING][4];      // [k-tile modulo 4][column block]
@@ -111,56 +122,80 @@ __global__ __launch_bounds__(TW_NW * 64) void gemm_tile_wide_kernel(TileGemm p) 
   u32x4 xv[TW_XIT];
   const int n_kt = NS * 2;
 
-  auto load_w = [&](auto tc, int kt) {
+  const unsigned lane_off = (unsigned)lane * 8u;
+  // (the empty statements pin the uniform part of an address in a scalar register pair and keep the widening of the
+  // lane's 32-bit offset next to the load -- `fresh`, once per stage: otherwise the optimiser folds the offset into a
+  // per-lane 64-bit pointer outside the loop and adds the moving part with vector instructions)
+  auto fresh = [](unsigned v) __attribute__((always_inline)) { asm("" : "+v"(v)); return v; };
+  typedef const __attribute__((address_space(1))) char* gbyte_ptr;
+  typedef const __attribute__((address_space(1))) u32x4* gvec_ptr;
+  auto at = [](const bf16_t* uniform, unsigned lane_el) __attribute__((always_inline)) -> gvec_ptr {
+    gbyte_ptr g = (gbyte_ptr)uniform;
+    asm("" : "+s"(g));
+    return (gvec_ptr)(g + lane_el * 2u);
+  };
+  // ---- the pieces a stage is made of: one instruction each, so that the stage can place them between the matrix
+  // instructions by hand (the scheduler neither moves memory operations across the asm statements nor knows that
+  // they are matrix instructions) ----
+  auto load_w1 = [&](auto tc, int kt, int c, unsigned lo) __attribute__((always_inline)) {
     constexpr int t = decltype(tc)::value;
     const size_t off = (size_t)(ks0 * 2 + kt) * 512;
     if (CLV_DBG(p, 4) && kt > 3) return;
+    w[t][c].u = __builtin_nontemporal_load(at(wbase[c] + off, lo));
+  };
+  auto load_w = [&](auto tc, int kt) __attribute__((always_inline)) {
+    const unsigned lo = fresh(lane_off);
 #pragma unroll
-    for (int c = 0; c < 4; ++c) w[t][c].u = __builtin_nontemporal_load((const u32x4*)(wbase[c] + off));
+    for (int c = 0; c < 4; ++c) load_w1(tc, kt, c, lo);
   };
   // rows past M read row M - 1 again: an output row depends on its own activation row only, and the epilogue
   // never stores rows >= M, so their accumulators may hold anything
-  const bf16_t* xsrc[TW_XIT];
+  // (piece it of a thread: plane it / 4, and the same row and 16-byte slot in both planes)
+  unsigned xoff[TW_XIT / 2];
+  int xdst[TW_XIT / 2];     // LDS element offset of the piece inside a plane
 #pragma unroll
-  for (int it = 0; it < TW_XIT; ++it) {
+  for (int it = 0; it < TW_XIT / 2; ++it) {
     const int idx = it * NT + tid;
-    const int rp = idx / (TL_KST / 8), sl = idx % (TL_KST / 8), plane = rp / TW_ROWS, r = rp % TW_ROWS;
-    xsrc[it] = (plane ? p.Xlo : p.Xhi) + (size_t)min(row0 + r, p.M - 1) * p.ldx + ks0 * TL_KST + sl * 8;
+    const int r = idx / (TL_KST / 8), sl = idx % (TL_KST / 8);
+    xoff[it] = (unsigned)(min(row0 + r, p.M - 1) * p.ldx + sl * 8);
+    xdst[it] = r * TL_LDK + sl * 8;
   }
-  auto x_load = [&](int s) {
+  const bf16_t* const xhi0 = p.Xhi + (size_t)ks0 * TL_KST;
+  const bf16_t* const xlo0 = p.Xlo + (size_t)ks0 * TL_KST;
+  auto x_load1 = [&](int s, int it, unsigned xo) __attribute__((always_inline)) {   // xo: this thread's xoff[it % 4]
     if (CLV_DBG(p, 1) && s > 1) return;
-#pragma unroll
-    for (int it = 0; it < TW_XIT; ++it) xv[it] = *(const u32x4*)(xsrc[it] + s * TL_KST);
+    xv[it] = *at((it < TW_XIT / 2 ? xhi0 : xlo0) + (size_t)s * TL_KST, xo);
   };
-  auto x_store = [&](int b) {
+  auto x_store1 = [&](int b, int it) __attribute__((always_inline)) {
     if (CLV_DBG(p, 16)) return;
-#pragma unroll
-    for (int it = 0; it < TW_XIT; ++it) {
-      const int idx = it * NT + tid;
-      const int rp = idx / (TL_KST / 8), sl = idx % (TL_KST / 8), plane = rp / TW_ROWS, r = rp % TW_ROWS;
-      *(u32x4*)(xs + b * TW_BUF + plane * TW_PLANE + r * TL_LDK + sl * 8) = xv[it];
-    }
+    *(u32x4*)(xs + b * TW_BUF + (it / (TW_XIT / 2)) * TW_PLANE + xdst[it % (TW_XIT / 2)]) = xv[it];
   };
-  // fragments of row blocks 4 q .. 4 q + 3 of k-tile `half` of the stage in buffer b
-  auto frag_load = [&](Frag (&xf)[8], int b, int half, int q) {
-    const bf16_t* hi = xs + b * TW_BUF + (q * 64 + l16) * TL_LDK + g4 * 8 + half * 32;
+  auto x_load = [&](int s) __attribute__((always_inline)) {
+    unsigned xo[TW_XIT / 2];
+#pragma unroll
+    for (int it = 0; it < TW_XIT / 2; ++it) xo[it] = fresh(xoff[it]);
+#pragma unroll
+    for (int it = 0; it < TW_XIT; ++it) x_load1(s, it, xo[it % (TW_XIT / 2)]);
+  };
+  auto x_store = [&](int b) __attribute__((always_inline)) {
+#pragma unroll
+    for (int it = 0; it < TW_XIT; ++it) x_store1(b, it);
+  };
+  // fragment j (row block j / 2, plane j % 2) of row blocks 4 q .. 4 q + 3 of k-tile `half` of the stage in buffer b
+  auto frag1 = [&](Frag (&xf)[8], int b, int half, int q, int j) __attribute__((always_inline)) {
     if (CLV_DBG(p, 2)) return;
-#pragma unroll
-    for (int rb = 0; rb < 4; ++rb) {
-      xf[2 * rb].u = *(const u32x4*)(hi + rb * 16 * TL_LDK);
-      xf[2 * rb + 1].u = *(const u32x4*)(hi + TW_PLANE + rb * 16 * TL_LDK);
-    }
+    xf[j].u = *(const u32x4*)(xs + b * TW_BUF + (j & 1) * TW_PLANE + (q * 64 + (j >> 1) * 16 + l16) * TL_LDK + g4 * 8 + half * 32);
   };
-  // 32 matrix instructions: row blocks 4 q .. 4 q + 3 (fragments xf) against the four weight fragments of ring slot t
-  auto mult = [&](auto tc, auto qc, const Frag (&xf)[8]) {
+  auto frag_load = [&](Frag (&xf)[8], int b, int half, int q) __attribute__((always_inline)) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) frag1(xf, b, half, q, j);
+  };
+  // matrix instruction m (0..31) of a group: row blocks 4 q .. 4 q + 3 (fragments xf) against the four weight
+  // fragments of ring slot t; per row block the lo plane against the four column blocks, then the hi plane
+  auto mm = [&](auto tc, auto qc, const Frag (&xf)[8], int m) __attribute__((always_inline)) {
     constexpr int t = decltype(tc)::value, q = decltype(qc)::value;
-#pragma unroll
-    for (int rb = 0; rb < 4; ++rb) {
-#pragma unroll
-      for (int c = 0; c < 4; ++c) acc[c][4 * q + rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[t][c].v, xf[2 * rb + 1].v, acc[c][4 * q + rb], 0, 0, 0);
-#pragma unroll
-      for (int c = 0; c < 4; ++c) acc[c][4 * q + rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[t][c].v, xf[2 * rb].v, acc[c][4 * q + rb], 0, 0, 0);
-    }
+    const int rb = m >> 3, c = m & 3, lo = ((m >> 2) & 1) ^ 1;
+    mfma_acc(acc[c][4 * q + rb], w[t][c].v, xf[2 * rb + lo].v);
   };
 
   // ---- prologue: weight ring, stages 0 and 1 in the LDS, stage 2 in registers, the first fragments ----
@@ -178,67 +213,64 @@ __global__ __launch_bounds__(TW_NW * 64) void gemm_tile_wide_kernel(TileGemm p) 
   // one group is multiplied the next group's fragments are read from the LDS into the other fragment set.  Around
   // them: the activations of stage st + 2 (in registers since the previous stage) go to the LDS and stage st + 3 is
   // requested (first group), the weights of k-tiles 2 st + 3 and 2 st + 4 are requested (second and third group).
-  // With one wavefront per SIMD nothing else hides the issue of these instructions, so in the FULL stages (every
-  // load unconditional: straight-line code) the group barriers spread them between the matrix instructions.
-  constexpr int G_MFMA = 0x008, G_VMEM = 0x020, G_DSR = 0x100, G_DSW = 0x200;
+  // With one wavefront per SIMD nothing else hides the issue of these instructions, so each of them is placed
+  // between two matrix instructions, where it issues while the matrix pipe is busy.
   using Q0 = std::integral_constant<int, 0>;
   using Q1 = std::integral_constant<int, 1>;
   auto stage = [&](auto w0, auto w1, auto w3, auto fullc, int st, int b /* st % 3 */) {
     // w0, w1: ring slots of this stage's k-tiles; w3: slot of k-tile 2 st + 3; k-tile 2 st + 4 reuses w0
     constexpr bool FULL = decltype(fullc)::value;
     const int b1 = b == TW_NBUF - 1 ? 0 : b + 1, b2 = b1 == TW_NBUF - 1 ? 0 : b1 + 1;
-    // group 0
-    if (FULL || st + 2 < NS) x_store(b2);
-    if (FULL || st + 3 < NS) x_load(st + 3);
-    frag_load(xb, b, 0, 1);
-    mult(w0, Q0{}, xa);
-    if constexpr (FULL) {
+    const bool do_store = FULL || st + 2 < NS, do_xload = FULL || st + 3 < NS;
+    const bool do_w3 = FULL || 2 * st + 3 < n_kt, do_w4 = FULL || 2 * st + 4 < n_kt, do_next = FULL || st + 1 < NS;
+    const unsigned lo = fresh(lane_off);
+    unsigned xo[TW_XIT / 2];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        __builtin_amdgcn_sched_group_barrier(G_MFMA, 1, 0); __builtin_amdgcn_sched_group_barrier(G_DSW, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(G_MFMA, 1, 0); __builtin_amdgcn_sched_group_barrier(G_DSR, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(G_MFMA, 1, 0); __builtin_amdgcn_sched_group_barrier(G_VMEM, 1, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(G_MFMA, 8, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    // group 1
-    if (FULL || 2 * st + 3 < n_kt) load_w(w3, 2 * st + 3);
-    frag_load(xa, b, 1, 0);
-    mult(w0, Q1{}, xb);
-    if constexpr (FULL) {
+    for (int it = 0; it < TW_XIT / 2; ++it) xo[it] = fresh(xoff[it]);
+    // group 0: 8 x (product, LDS store, product, fragment read, product, activation load), 8 products
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        __builtin_amdgcn_sched_group_barrier(G_MFMA, 2, 0); __builtin_amdgcn_sched_group_barrier(G_DSR, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(G_MFMA, 2, 0); __builtin_amdgcn_sched_group_barrier(G_DSR, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(G_MFMA, 1, 0); __builtin_amdgcn_sched_group_barrier(G_VMEM, 1, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(G_MFMA, 12, 0);
+    for (int i = 0; i < 8; ++i) {
+      mm(w0, Q0{}, xa, 3 * i);
+      if (do_store) x_store1(b2, i);
+      mm(w0, Q0{}, xa, 3 * i + 1);
+      frag1(xb, b, 0, 1, i);
+      mm(w0, Q0{}, xa, 3 * i + 2);
+      if (do_xload) x_load1(st + 3, i, xo[i % (TW_XIT / 2)]);
     }
-    __builtin_amdgcn_sched_barrier(0);
-    // group 2
-    if (FULL || 2 * st + 4 < n_kt) load_w(w0, 2 * st + 4);
-    frag_load(xb, b, 1, 1);
-    mult(w1, Q0{}, xa);
-    if constexpr (FULL) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        __builtin_amdgcn_sched_group_barrier(G_MFMA, 2, 0); __builtin_amdgcn_sched_group_barrier(G_DSR, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(G_MFMA, 2, 0); __builtin_amdgcn_sched_group_barrier(G_DSR, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(G_MFMA, 1, 0); __builtin_amdgcn_sched_group_barrier(G_VMEM, 1, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(G_MFMA, 12, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    // group 3
-    if (FULL || st + 1 < NS) frag_load(xa, b1, 0, 0);
-    mult(w1, Q1{}, xb);
-    if constexpr (FULL) {
+    for (int m = 24; m < 32; ++m) mm(w0, Q0{}, xa, m);
+    // group 1: 4 x (2 products, fragment read, 2 products, fragment read, product, weight load), 12 products
 #pragma unroll
-      for (int i = 0; i < 8; ++i) { __builtin_amdgcn_sched_group_barrier(G_MFMA, 3, 0); __builtin_amdgcn_sched_group_barrier(G_DSR, 1, 0); }
-      __builtin_amdgcn_sched_group_barrier(G_MFMA, 8, 0);
+    for (int i = 0; i < 4; ++i) {
+      mm(w0, Q1{}, xb, 5 * i); mm(w0, Q1{}, xb, 5 * i + 1);
+      frag1(xa, b, 1, 0, 2 * i);
+      mm(w0, Q1{}, xb, 5 * i + 2); mm(w0, Q1{}, xb, 5 * i + 3);
+      frag1(xa, b, 1, 0, 2 * i + 1);
+      mm(w0, Q1{}, xb, 5 * i + 4);
+      if (do_w3) load_w1(w3, 2 * st + 3, i, lo);
     }
-    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int m = 20; m < 32; ++m) mm(w0, Q1{}, xb, m);
+    // group 2: the same with the other k-tile; the weight slot of k-tile 2 st is free now and takes k-tile 2 st + 4
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      mm(w1, Q0{}, xa, 5 * i); mm(w1, Q0{}, xa, 5 * i + 1);
+      frag1(xb, b, 1, 1, 2 * i);
+      mm(w1, Q0{}, xa, 5 * i + 2); mm(w1, Q0{}, xa, 5 * i + 3);
+      frag1(xb, b, 1, 1, 2 * i + 1);
+      mm(w1, Q0{}, xa, 5 * i + 4);
+      if (do_w4) load_w1(w0, 2 * st + 4, i, lo);
+    }
+#pragma unroll
+    for (int m = 20; m < 32; ++m) mm(w1, Q0{}, xa, m);
+    // group 3: 8 x (3 products, fragment read of the next stage's first group), 8 products
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      mm(w1, Q1{}, xb, 3 * i); mm(w1, Q1{}, xb, 3 * i + 1); mm(w1, Q1{}, xb, 3 * i + 2);
+      if (do_next) frag1(xa, b1, 0, 0, i);
+    }
+#pragma unroll
+    for (int m = 24; m < 32; ++m) mm(w1, Q1{}, xb, m);
     if (!CLV_DBG(p, 8)) __syncthreads();
   };
   using I0 = std::integral_constant<int, 0>;
@@ -259,6 +291,9 @@ __global__ __launch_bounds__(TW_NW * 64) void gemm_tile_wide_kernel(TileGemm p) 
     b = b == TW_NBUF - 1 ? 0 : b + 1;
   }
 
+  // (the compiler does not know that the asm statements are matrix instructions, so the wait states between the last
+  // of them and the first read of an accumulator are spelled out: two no-ops of 16 cover the longest one)
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
   // ---- epilogue: lane holds rows rb*16 + l16 of the tile, columns 4*g4 .. 4*g4+3 of each block ----
   if (EPI == 1) {
     const int fblock = (tile * TW_NW + wn) * 2;
