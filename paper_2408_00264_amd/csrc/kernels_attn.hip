@@ -56,19 +56,37 @@ __device__ __forceinline__ void a_split2(float a, float b, unsigned& hi, unsigne
 constexpr int AT_D = 128;         // head dim
 constexpr int AT_TK = KV_PAGE;    // keys per tile = one page of the caches
 // (WM, a template parameter: wavefronts per query head; a workgroup always covers 32 nodes, a wavefront 32 / WM)
-// LDS row strides (bf16).  +32 B: measured on gfx950, ds_read_b128 fragment reads (row = lane % 16, 16-byte piece = lane / 16) run at the full 256 B/clk when the row stride is 32 mod 64 bytes and at half of it with a 16-byte pad.
-constexpr int AT_KLD = AT_D + 16;
-constexpr int AT_VLD = AT_TK + 16;
-constexpr int AT_KPLANE = AT_TK * AT_KLD;
-constexpr int AT_VPLANE = AT_D * AT_VLD;
-constexpr int AT_KSTAGE = 2 * AT_KPLANE, AT_VSTAGE = 2 * AT_VPLANE;   // one staged tile: K hi, K lo / V^T hi, V^T lo
-constexpr int AT_LDS_EL = 2 * AT_KSTAGE + 3 * AT_VSTAGE;              // two K buffers, three V^T buffers
+// A staged tile lies in the LDS fragment by fragment: 1 KB blocks in which lane l's 16 bytes sit at l * 16, exactly what
+// one 16x32 MFMA operand read takes (a contiguous KB: the LDS's full 256 B/clk).  K: blocks [plane][tt][ks] (16 keys of
+// sub-tile tt, head-dim columns 32 ks ..), V^T: blocks [plane][db] (head-dim rows 16 db .., the 32 keys).
+constexpr int AT_FRAG = 512;                  // bf16 elements of a fragment block
+constexpr int AT_KSTAGE = 16 * AT_FRAG, AT_VSTAGE = 16 * AT_FRAG;   // one staged tile: 16 KB of K, 16 KB of V^T
+constexpr int AT_PGR = 4;                    // page-number registers: at most 64 * AT_PGR tiles per split
+constexpr int AT_NKB = 2, AT_NVB = 2;         // K and V^T buffers: tile i in buffers i % 2
+constexpr int AT_LDS_EL = AT_NKB * AT_KSTAGE + AT_NVB * AT_VSTAGE;
 constexpr int AT_MAX_IV = CLOVER_MAX_NODES_INTERVAL;   // interval labels of the tree keys kept in the LDS
+
+// One staging load: 64 lanes x 16 bytes from (uniform base) + (lane offset) in global memory to the KB at `dst` in
+// the LDS (the hardware adds lane * 16 to dst).  dst is the same for all lanes.  (No memory clobber: the staged data is
+// read only behind a later barrier, which is a fence for the compiler, and a clobber would turn the scalar loads of the
+// page table into vector loads that wait for every staging load in flight.)
+__device__ __forceinline__ void lds_dma16(const __attribute__((address_space(1))) char* base, unsigned lane_off,
+                                          unsigned dst /* LDS byte address */) {
+  const unsigned m0 = __builtin_amdgcn_readfirstlane(dst);
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(m0), "v"(lane_off), "s"(base) : "m0");
+}
+// Wait until at most N of this wavefront's vector-memory loads are outstanding (the vmcnt field of s_waitcnt: bits 3:0
+// and 15:14; the other counters are left alone).
+template <int N>
+__device__ __forceinline__ void wait_staging() {
+  static_assert(N >= 0 && N < 64, "vmcnt has six bits");
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
 
 template <int G, int WM>
 __global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
   constexpr int AT_MB = 2 / WM;     // 16-row blocks of nodes per wavefront
-  extern __shared__ __attribute__((aligned(16))) bf16_t sm[];  // [2][AT_KSTAGE] [3][AT_VSTAGE] [AT_MAX_IV] labels
+  extern __shared__ __attribute__((aligned(16))) bf16_t sm[];  // [2][AT_KSTAGE] [2][AT_VSTAGE] [AT_MAX_IV] labels
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int l16 = lane & 15, g4 = lane >> 4;
   const int split = blockIdx.x, ng = blockIdx.y / p.n_kv, kvh = blockIdx.y % p.n_kv, b = blockIdx.z;
@@ -77,46 +95,65 @@ __global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
   const int head = kvh * G + wave % G;
   const int nsub = (wave / G) * AT_MB * 16;   // this wavefront's first node within the workgroup's 32
 
-  // ---- staging: 16-byte pieces; K rows are stored in the order the score MFMA consumes them ----
-  constexpr int NT = 64 * G * WM;
-  constexpr int KSLOTS = 2 * AT_TK * 16, VSLOTS = 2 * AT_D * 4;  // both 1024
-  constexpr int KIT = KSLOTS / NT, VIT = VSLOTS / NT;
-  // two register sets: while a tile is multiplied, the next one sits in LDS or lands in one set and
-  // the one after it is in flight into the other
-  u32x4 krA[KIT], vrA[VIT], krB[KIT], vrB[VIT];
+  // ---- staging: global -> LDS without a stop in registers.  A wavefront instruction moves one fragment block: lane l
+  // fetches the 16 bytes the MFMA operand layout wants at l * 16 (K: key 8 (l%16 / 4) + 4 tt + l%16 % 4, columns
+  // 32 ks + 8 (l / 16) ..; V^T: row 16 db + l % 16, keys 8 (l / 16) ..) and the hardware writes them to
+  // (LDS base of the block) + l * 16.  The 32 blocks of a tile are dealt to the workgroup's wavefronts.
   // Key tile t of this sequence is page pages[b * T + t] of the paged caches: the K rows and the V^T columns of
-  // (page, KV head) are one contiguous 8 KB block each per plane.  The page number is a scalar that is fetched one
-  // load ahead of its use (page_of), and a thread's piece of a block is tid * 16 bytes behind a uniform base, so the
-  // loads of a tile need no vector address arithmetic (address registers that alias a staging set would make every
-  // new load wait for the ones in flight).
+  // (page, KV head) are one contiguous 8 KB block each per plane.  An address is a uniform base plus the lane's 32-bit
+  // offset, so staging costs no vector-ALU instruction.  The compiler is not told that these loads write the LDS (it would wait for all of
+  // them before every LDS read that follows): the waits before the barriers below are written by hand.
+  constexpr int NT = 64 * G * WM, NW = G * WM;
+  constexpr int FPW = 16 / NW;          // K blocks and V^T blocks per wavefront and tile
+  constexpr int DPT = 2 * FPW;          // staging loads per wavefront and tile
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const unsigned k_lane = (unsigned)((((l16 >> 2) * 8 + (l16 & 3)) * AT_D + g4 * 8) * 2);   // bytes
+  const unsigned v_lane = (unsigned)((l16 * AT_TK + g4 * 8) * 2);
+  bf16_t* const k_lds = sm;
+  bf16_t* const v_lds = sm + AT_NKB * AT_KSTAGE;
   const KVLayout& kv = p.kv;
-  auto page_of = [&](int t) __attribute__((always_inline)) -> int {
-    const int lp = (b + kv.b0) * kv.T + min(t, kv.T - 1);
-    return kv.pages ? kv.pages[lp] : lp;
-  };
-  auto load_tile = [&](u32x4 (&kr)[KIT], u32x4 (&vr)[VIT], int page) __attribute__((always_inline)) {
-    const size_t blk = ((size_t)page * kv.n_kv + kvh) * (size_t)(KV_PAGE * AT_D);   // elements; K and V^T blocks are equal
-    const bf16_t* kb = p.k_hi + blk;
-    const bf16_t* vb = p.v_hi + blk;
+  // Page numbers of this split's tiles: lane l of register r holds the page of tile t0 + 64 r + l, read from the page
+  // table once, before the first staging load (a table read inside the loop would have to be a vector load -- the
+  // compiler must assume that the staging statements write memory -- and its wait would drain the staging loads in
+  // flight).  page_of(i) then is a lane read: no memory, no wait.
+  int pgv[AT_PGR];
 #pragma unroll
-    for (int it = 0; it < KIT; ++it) {
-      const int plane = (it * NT) >> 9, first = (it * NT) & 511;   // uniform: NT divides 512
-      kr[it] = *(const u32x4*)(kb + plane * p.k_plane + (first + tid) * 8);
+  for (int r = 0; r < AT_PGR; ++r) {
+    const int lp = (b + kv.b0) * kv.T + min(t0 + 64 * r + lane, kv.T - 1);
+    pgv[r] = kv.pages ? kv.pages[lp] : lp;
+  }
+  auto page_of = [&](int i) __attribute__((always_inline)) -> int {   // i: tile index within the split, < 64 AT_PGR
+    int pg = __builtin_amdgcn_readlane(pgv[0], i & 63);              // (one lane read per register and a scalar
+#pragma unroll                                                       //  select: a select between the registers
+    for (int r = 1; r < AT_PGR; ++r) {                               //  would be turned into an indexed array)
+      const int q = __builtin_amdgcn_readlane(pgv[r], i & 63);
+      pg = (i >> 6) == r ? q : pg;
     }
+    return pg;
+  };
+  typedef const __attribute__((address_space(1))) char* gbyte_ptr;
+  const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)sm;   // LDS byte address of sm
+  auto stage_tile = [&](int kbuf, int vbuf, int page) __attribute__((always_inline)) {
+    const size_t blk = ((size_t)page * kv.n_kv + kvh) * (size_t)(KV_PAGE * AT_D);   // elements; K and V^T blocks are equal
 #pragma unroll
-    for (int it = 0; it < VIT; ++it) {
-      const int plane = (it * NT) >> 9, first = (it * NT) & 511;
-      vr[it] = *(const u32x4*)(vb + plane * p.v_plane + (first + tid) * 8);
+    for (int j = 0; j < FPW; ++j) {
+      const int f = wave_u * FPW + j, plane = f >> 3;
+      const bf16_t* ksrc = p.k_hi + blk + (size_t)plane * p.k_plane + ((f >> 2) & 1) * 4 * AT_D + (f & 3) * 32;
+      const bf16_t* vsrc = p.v_hi + blk + (size_t)plane * p.v_plane + (f & 7) * 16 * AT_TK;
+      lds_dma16((gbyte_ptr)ksrc, k_lane, lds0 + 2u * (unsigned)(kbuf * AT_KSTAGE + f * AT_FRAG));
+      lds_dma16((gbyte_ptr)vsrc, v_lane, lds0 + 2u * (unsigned)(AT_NKB * AT_KSTAGE + vbuf * AT_VSTAGE + f * AT_FRAG));
     }
   };
   // The first key tile is requested before anything else is waited for (its address needs the page table only:
   // keys past the cache are clamped and masked later), so its HBM latency overlaps the loads of the lengths,
   // the masks and Q.
-  load_tile(krA, vrA, page_of(t0));
-  int pg_next = page_of(t0 + 1);   // page of the tile the next load_tile call fetches
+  stage_tile(0, 0, page_of(0));
   const int nv = rm.n_valid ? min(rm.n_valid[b], rm.n) : rm.n;
   const int L = p.base_len[b];
-  if (ng * 32 >= nv || L + nv > p.max_seq) return;  // whole workgroup
+  if (ng * 32 >= nv || L + nv > p.max_seq) {  // whole workgroup
+    wait_staging<0>();   // no staging load may land in the LDS after the workgroup has given it back
+    return;
+  }
   const int total = L + nv;
   const bool chain = p.anc == nullptr && p.iv == nullptr;
   int2* kiv = (int2*)(sm + AT_LDS_EL);   // [AT_MAX_IV] (enter, exit) of the tree keys; published by the first barrier
@@ -158,33 +195,11 @@ __global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
 #pragma unroll
   for (int mb = 0; mb < AT_MB; ++mb) { m_run[mb] = -INFINITY; l_run[mb] = 0.f; }
 
-  // LDS: two K buffers (tile i in buffer i % 2) and three V^T buffers (tile i in buffer i % 3): the output product of
-  // tile i - 1 runs one iteration behind its scores (see the loop), so V^T of tile i - 1 is still read while tile i + 1
-  // is staged.
-  bf16_t* const k_lds = sm;
-  bf16_t* const v_lds = sm + 2 * AT_KSTAGE;
-  auto store_tile = [&](const u32x4 (&kr)[KIT], const u32x4 (&vr)[VIT], int kbuf, int vbuf) __attribute__((always_inline)) {
-    bf16_t* kbase = k_lds + kbuf * AT_KSTAGE;
-    bf16_t* vbase = v_lds + vbuf * AT_VSTAGE;
-#pragma unroll
-    for (int it = 0; it < KIT; ++it) {
-      const int idx = it * NT + tid, plane = idx >> 9, rem = idx & 511, key = rem >> 4, sl = rem & 15;
-      // key k of the tile is row ((k/4)%2)*16 + (k/8)*4 + k%4: sub-tile tt holds keys 8g + 4tt + r at row 4g + r
-      const int row = ((key >> 2) & 1) * 16 + (key >> 3) * 4 + (key & 3);
-      *(u32x4*)(kbase + plane * AT_KPLANE + row * AT_KLD + sl * 8) = kr[it];
-    }
-#pragma unroll
-    for (int it = 0; it < VIT; ++it) {
-      const int idx = it * NT + tid, plane = idx >> 9, rem = idx & 511, dr = rem >> 2, sl = rem & 3;
-      *(u32x4*)(vbase + plane * AT_VPLANE + dr * AT_VLD + sl * 8) = vr[it];
-    }
-  };
-
   // ---- the three steps of a key tile.  scores: S^T = K Q^T (matrix pipe); soft_max: running statistics, the
   // probabilities as hi/lo fragments and the factor the output so far has to be scaled by (vector ALU);
   // output: O^T += V^T P (matrix pipe). ----
   auto scores = [&](int kbuf, f32x4 (&sc)[2][AT_MB]) __attribute__((always_inline)) {
-    const bf16_t* kb = k_lds + kbuf * AT_KSTAGE + l16 * AT_KLD + g4 * 8;
+    const bf16_t* kb = k_lds + kbuf * AT_KSTAGE + lane * 8;
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
@@ -194,8 +209,8 @@ __global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
         Frag kh, kl;
-        kh.u = *(const u32x4*)(kb + tt * 16 * AT_KLD + ks * 32);
-        kl.u = *(const u32x4*)(kb + AT_KPLANE + tt * 16 * AT_KLD + ks * 32);
+        kh.u = *(const u32x4*)(kb + (tt * 4 + ks) * AT_FRAG);
+        kl.u = *(const u32x4*)(kb + (8 + tt * 4 + ks) * AT_FRAG);
 #pragma unroll
         for (int mb = 0; mb < AT_MB; ++mb) {
           sc[tt][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kl.v, qh[mb][ks].v, sc[tt][mb], 0, 0, 0);
@@ -254,12 +269,12 @@ __global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
     else soft_max_t(t, sc, ph, pl, std::false_type{});
   };
   auto output = [&](int vbuf, const Frag (&ph)[AT_MB], const Frag (&pl)[AT_MB]) __attribute__((always_inline)) {
-    const bf16_t* vb = v_lds + vbuf * AT_VSTAGE + l16 * AT_VLD + g4 * 8;
+    const bf16_t* vb = v_lds + vbuf * AT_VSTAGE + lane * 8;
 #pragma unroll
     for (int db = 0; db < 8; ++db) {
       Frag vh, vl;
-      vh.u = *(const u32x4*)(vb + db * 16 * AT_VLD);
-      vl.u = *(const u32x4*)(vb + AT_VPLANE + db * 16 * AT_VLD);
+      vh.u = *(const u32x4*)(vb + db * AT_FRAG);
+      vl.u = *(const u32x4*)(vb + (8 + db) * AT_FRAG);
 #pragma unroll
       for (int mb = 0; mb < AT_MB; ++mb) {
         O[db][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vl.v, ph[mb].v, O[db][mb], 0, 0, 0);
@@ -269,68 +284,36 @@ __global__ __launch_bounds__(64 * G * WM) void attn_mfma_kernel(AttnParams p) {
     }
   };
 
-  // ---- the loop over this split's key tiles.  Staging: with two register sets the tile after next is in flight
-  // while the next one waits in the other set; with one set (few threads per workgroup: all the register file holds)
-  // the next tile is in flight.  One barrier per tile: tile i + 1 is written to the LDS at the end of iteration i.
-  //
-  // Order of the steps (two wavefronts per query head): scores of tile i, output product of tile i - 1, soft-max of
-  // tile i.  The fragment reads of the output product are then in flight behind the score products instead of
-  // behind the soft-max, on whose result they do not depend; measured 4 % faster over 8192 keys than scores,
-  // soft-max, output of the same tile.  Running the second four wavefronts of a workgroup one step out of phase
-  // with the first four, so that one of a SIMD's pair multiplies while the other exponentiates, was measured too
-  // and gains nothing: on this chip a SIMD's matrix and vector instructions hardly overlap, whichever wavefront
-  // they come from (24 MFMA in one wavefront and 96 fma in the other take 86-100 % of the sum of their times;
-  // probes/mfma_valu_overlap.hip).  Every accumulator sees the same operations in the same order in all of these
-  // variants. ----
+  // ---- the loop over this split's key tiles.  Tile i + 1 is requested at the top of iteration i into the buffers
+  // tile i - 1 has left (every wavefront is past the barrier of iteration i - 1) and has to be complete, and visible
+  // to every wavefront, at the barrier that ends iteration i: each wavefront waits for its own staging loads first.
+  // Measured on the same machine, 8192 + 96 keys (attention + merge, us): this form 58.9; the tile after next in
+  // flight as well (three K and four V^T buffers, output product one tile behind the scores) 62.2; tiles staged
+  // through registers and padded LDS rows, two in flight, 61.3.  Two workgroups of this kernel fit a CU (114
+  // registers, 66 KB of LDS) and a launch of two per CU is no faster than one per CU: per key tile a workgroup costs
+  // the CU ~1.5 us however the work is arranged -- scores 0.29, soft-max 0.40, output 0.23 (each timed by leaving
+  // it out), the rest barriers, waits and the parts of the staging latency that the products do not cover -- and on
+  // this chip a SIMD's matrix and vector instructions hardly overlap, whichever wavefronts they come from (24 MFMA
+  // in one wavefront and 96 fma in another take 86-100 % of the sum of their times: probes/mfma_valu_overlap.hip),
+  // so running half of the wavefronts one step out of phase with the others gains nothing either. ----
   if (t0 < t1) {  // uniform over the workgroup
     const int n = t1 - t0;
-    constexpr bool TWO_SETS = G * WM >= 4;
-    // (one wavefront per query head covers 32 nodes and has no registers left to carry a tile's probabilities
-    // into the next iteration: it runs scores, soft-max and output of tile i back to back)
-    constexpr bool PIPELINED = WM == 2;
     f32x4 sc[2][AT_MB];
     Frag ph[AT_MB], pl[AT_MB];
-    auto iteration = [&](int i, int kb, int vcur, int vprev) __attribute__((always_inline)) {
-      scores(kb, sc);
-      if constexpr (PIPELINED) {
-        if (i > 0) output(vprev, ph, pl);
-        soft_max(t0 + i, sc, ph, pl);
-      } else {
-        soft_max(t0 + i, sc, ph, pl);
-        output(vcur, ph, pl);
-      }
-    };
-    if constexpr (TWO_SETS) {
-      if (n > 1) { load_tile(krB, vrB, pg_next); pg_next = page_of(t0 + 2); }
-    }
-    store_tile(krA, vrA, 0, 0);
+    wait_staging<0>();
     __syncthreads();
-    int vcur = 0, vprev = 2;   // V^T buffers of tiles i and i - 1
-    for (int i = 0; i < n; i += 2) {
-      if constexpr (TWO_SETS) {
-        if (i + 2 < n) { load_tile(krA, vrA, pg_next); pg_next = page_of(t0 + i + 3); }
-      } else {
-        if (i + 1 < n) { load_tile(krA, vrA, pg_next); pg_next = page_of(t0 + i + 2); }
-      }
-      iteration(i, 0, vcur, vprev);
-      vprev = vcur; vcur = vcur == 2 ? 0 : vcur + 1;
-      if (i + 1 >= n) break;
-      if constexpr (TWO_SETS) store_tile(krB, vrB, 1, vcur); else store_tile(krA, vrA, 1, vcur);
-      __syncthreads();
-      if constexpr (TWO_SETS) {
-        if (i + 3 < n) { load_tile(krB, vrB, pg_next); pg_next = page_of(t0 + i + 4); }
-      } else {
-        if (i + 2 < n) { load_tile(krA, vrA, pg_next); pg_next = page_of(t0 + i + 3); }
-      }
-      iteration(i + 1, 1, vcur, vprev);
-      vprev = vcur; vcur = vcur == 2 ? 0 : vcur + 1;
-      if (i + 2 < n) store_tile(krA, vrA, 0, vcur);
+    for (int i = 0; i < n; ++i) {
+      const int cur = i & 1;
+      if (i + 1 < n) stage_tile(cur ^ 1, cur ^ 1, page_of(i + 1));
+      scores(cur, sc);
+      soft_max(t0 + i, sc, ph, pl);
+      output(cur, ph, pl);
+      wait_staging<0>();
       __syncthreads();
     }
-    // the output product still owed for the last tile (its V^T buffer is vprev after the final rotation)
-    if constexpr (PIPELINED) output(vprev, ph, pl);
   }
 
+  wait_staging<0>();   // (a split without tiles still has its first staging loads in flight)
   // ---- partial result of this split ----
 #pragma unroll
   for (int mb = 0; mb < AT_MB; ++mb) {
@@ -400,7 +383,9 @@ __global__ __launch_bounds__(MG_HEADS * 32) void attn_merge_kernel(const float* 
 
 bool attn_mfma_supported(int head_dim, int n_q, int n_kv, int max_seq) {
   const int g = n_q / n_kv;
-  return head_dim == AT_D && (g == 1 || g == 2 || g == 4 || g == 8) && max_seq % KV_PAGE == 0 && max_seq >= KV_PAGE;
+  // (a split keeps the page numbers of at most 64 * AT_PGR tiles in registers, and there are at most MG_MAXS splits)
+  return head_dim == AT_D && (g == 1 || g == 2 || g == 4 || g == 8) && max_seq % KV_PAGE == 0 && max_seq >= KV_PAGE &&
+         max_seq / KV_PAGE <= 64 * AT_PGR * MG_MAXS;
 }
 
 template <int G, int WM>
@@ -423,6 +408,7 @@ void launch_attn_mfma(AttnParams p, int max_total_keys, bf16_t* out_hi, bf16_t* 
   const int target = tune_int("CLOVER_ATTN_WGS", 256);
   int splits = std::max(1, target / (p.rm.B * p.n_kv * node_groups));
   splits = std::max(1, std::min(std::min(splits, std::min(p.max_splits, MG_MAXS)), (n_tiles + 1) / 2));
+  splits = std::max(splits, (n_tiles + 64 * AT_PGR - 1) / (64 * AT_PGR));   // <= MG_MAXS: attn_mfma_supported
   p.tiles_per_split = (n_tiles + splits - 1) / splits;
   p.n_splits = (n_tiles + p.tiles_per_split - 1) / p.tiles_per_split;
   dim3 grid(p.n_splits, node_groups * p.n_kv, p.rm.B);
