@@ -801,6 +801,35 @@ def test_config5_8192_cached_keys_96_node_tree():
     assert ls.max_logit_err <= 3e-2
 
 
+def test_long_key_splits_with_shuffled_pages():
+    """Batch 8 over caches of up to 8400 keys: 64 (sequence, KV head) pairs leave four key splits of 66 tiles each, more
+    than the 64 page numbers one register of the attention kernel holds per split, and the page table is a random
+    permutation, so the tiles past the 64th of a split are fetched through the second page-number register from
+    scattered pages.  Ragged lengths: short sequences end inside the first split."""
+    _torch()
+    from tests.parity import truth_hook_factory
+    lengths = [8400, 300, 8211, 1500, 64, 8388, 4000, 700]
+    max_seq = 8576
+    O = __import__("oracle.clover2_oracle", fromlist=["x"])
+    shape = synth.scaled(synth.CONFIGS[4], name="wide-4-long-splits", n_layers=2, batch=len(lengths), seed=43)
+    ls = _lockstep(shape, batch=len(lengths), max_seq=max_seq)
+    assert ls.gpu.path_info() & 3 == 3
+    perm = np.random.default_rng(78).permutation(len(lengths) * (max_seq // 32)).astype(np.int32)
+    ls.gpu.set_page_table(perm)
+    ls.ocfg.dtype = np.float32
+    ls.W = O.Weights(ls.store.get_f32, np.float32)
+    ls.seqs = [O.SeqState(ls.ocfg) for _ in lengths]
+    ls.seed_cache(lengths, 43)
+    say(f"long key splits: lengths {lengths}, shuffled page table {perm[:6].tolist()}...")
+    want = [2, 3]
+    hook = truth_hook_factory(ls, want)
+    for s in range(len(want)):
+        ms = ls.step(tree_hook=hook)
+        say(f"  step {s}: want {want[s]} got {ms} max|dlogit|={ls.max_logit_err:.3e} max|dhidden|={ls.max_hidden_err:.3e} "
+            f"max|dKV|={ls.max_kv_err:.3e} ties={ls.tie_events}")
+    assert ls.max_logit_err <= 3e-2
+
+
 def test_config4_ragged_256_to_2048_cached_keys():
     """The batch-8 workload at its real widths and cache lengths (the recipe's eight lengths, uniform in
     [256, 2048]), 32-node trees, 256 rows per pass, 2 layers."""
