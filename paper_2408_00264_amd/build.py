@@ -23,14 +23,17 @@ def _hipcc() -> str:
     return "hipcc"
 
 
-def build(verbose: bool = False, ablate: bool = False, out: str = "") -> str:
+def build(verbose: bool = False, ablate: bool = False, out: str = "", defines=()) -> str:
     """Compile every source and link the library.  `ablate` adds -DCLOVER_ABLATE (kernel-tuning builds that read
-    CLOVER_* environment switches; never the shipped library) and needs an explicit `out` path."""
-    if ablate and not out:
+    CLOVER_* environment switches; never the shipped library) and needs an explicit `out` path; `defines` are further
+    NAME=VALUE macros of such a build (the compile-time ablation bits of a kernel, e.g. CLOVER_TILE_ABLATE=17)."""
+    if (ablate or defines) and not out:
         raise ValueError("an ablation build must not overwrite the shipped library: pass out=<path>")
+    if defines and not ablate:
+        raise ValueError("macros are for ablation builds only")
     build_dir = BUILD + ("_ablate" if ablate else "")
     lib_path = out or LIB
-    flags = FLAGS + (["-DCLOVER_ABLATE"] if ablate else [])
+    flags = FLAGS + (["-DCLOVER_ABLATE"] if ablate else []) + ["-D" + d for d in defines]
     os.makedirs(build_dir, exist_ok=True)
     hipcc = _hipcc()
     srcs = [s for s in SOURCES if os.path.exists(os.path.join(CSRC, s))]
@@ -70,5 +73,7 @@ if __name__ == "__main__":
     ap = argparse.ArgumentParser()
     ap.add_argument("--ablate", action="store_true", help="tuning build that reads CLOVER_* switches (needs --out)")
     ap.add_argument("--out", default="")
+    ap.add_argument("--define", action="append", default=[], metavar="NAME=VALUE",
+                    help="macro for an ablation build, e.g. CLOVER_TILE_ABLATE=17 (repeatable)")
     a = ap.parse_args()
-    print(build(verbose=True, ablate=a.ablate, out=a.out))
+    print(build(verbose=True, ablate=a.ablate, out=a.out, defines=tuple(a.define)))

@@ -225,7 +225,6 @@ struct TileGemm {
   int M, N, K;
   int epi;                            // 0 plain, 1 SwiGLU
   int k_parts; size_t split_stride;   // epi 0 only
-  int dbg;                            // ablation builds only: 1 no activation staging, 2 no LDS reads, 4 no weight loads, 8 no barrier
   int n_units;                        // filled in by launch_gemm_tile: column tiles x K ranges
 };
 bool tile_gemm_supported(int M, int N, int K, int epi);

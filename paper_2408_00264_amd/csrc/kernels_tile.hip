@@ -62,6 +62,15 @@ constexpr int TW_NW = 4;              // wavefronts, 64 output columns each
 constexpr int TW_PLANE = TW_ROWS * TL_LDK;
 constexpr int TW_BUF = 2 * TW_PLANE;  // hi and lo plane of one stage
 constexpr int TW_NBUF = 3;
+// Ablation bits, compile time only (a tuning build compiled with -DCLOVER_TILE_ABLATE=<bits>; 0 in every library that
+// computes): 1 no activation loads after the third stage, 16 no activation stores to the LDS, 2 no LDS fragment
+// reads, 4 no weight loads after the first four k-tiles, 8 no barrier.  Run-time switches would put branches between
+// the hand-placed instructions of a stage and break the schedule they are meant to measure.
+#ifdef CLOVER_TILE_ABLATE
+constexpr int TW_ABLATE = CLOVER_TILE_ABLATE;
+#else
+constexpr int TW_ABLATE = 0;
+#endif
 constexpr int TW_XIT = 2 * TW_ROWS * (TL_KST / 8) / (TW_NW * 64);   // 16-byte pieces per thread and stage (= 8)
 
 // acc += A B^T with the accumulator tied to one accumulation-register tuple for the whole kernel.  (Written through the
@@ -140,7 +149,7 @@ __global__ __launch_bounds__(TW_NW * 64) void gemm_tile_wide_kernel(TileGemm p) 
   auto load_w1 = [&](auto tc, int kt, int c, unsigned lo) __attribute__((always_inline)) {
     constexpr int t = decltype(tc)::value;
     const size_t off = (size_t)(ks0 * 2 + kt) * 512;
-    if (CLV_DBG(p, 4) && kt > 3) return;
+    if ((TW_ABLATE & 4) && kt > 3) return;
     w[t][c].u = __builtin_nontemporal_load(at(wbase[c] + off, lo));
   };
   auto load_w = [&](auto tc, int kt) __attribute__((always_inline)) {
@@ -163,11 +172,11 @@ __global__ __launch_bounds__(TW_NW * 64) void gemm_tile_wide_kernel(TileGemm p) 
   const bf16_t* const xhi0 = p.Xhi + (size_t)ks0 * TL_KST;
   const bf16_t* const xlo0 = p.Xlo + (size_t)ks0 * TL_KST;
   auto x_load1 = [&](int s, int it, unsigned xo) __attribute__((always_inline)) {   // xo: this thread's xoff[it % 4]
-    if (CLV_DBG(p, 1) && s > 1) return;
+    if ((TW_ABLATE & 1) && s > 2) return;
     xv[it] = *at((it < TW_XIT / 2 ? xhi0 : xlo0) + (size_t)s * TL_KST, xo);
   };
   auto x_store1 = [&](int b, int it) __attribute__((always_inline)) {
-    if (CLV_DBG(p, 16)) return;
+    if (TW_ABLATE & 16) return;
     *(u32x4*)(xs + b * TW_BUF + (it / (TW_XIT / 2)) * TW_PLANE + xdst[it % (TW_XIT / 2)]) = xv[it];
   };
   auto x_load = [&](int s) __attribute__((always_inline)) {
@@ -183,7 +192,7 @@ __global__ __launch_bounds__(TW_NW * 64) void gemm_tile_wide_kernel(TileGemm p) 
   };
   // fragment j (row block j / 2, plane j % 2) of row blocks 4 q .. 4 q + 3 of k-tile `half` of the stage in buffer b
   auto frag1 = [&](Frag (&xf)[8], int b, int half, int q, int j) __attribute__((always_inline)) {
-    if (CLV_DBG(p, 2)) return;
+    if (TW_ABLATE & 2) return;
     xf[j].u = *(const u32x4*)(xs + b * TW_BUF + (j & 1) * TW_PLANE + (q * 64 + (j >> 1) * 16 + l16) * TL_LDK + g4 * 8 + half * 32);
   };
   auto frag_load = [&](Frag (&xf)[8], int b, int half, int q) __attribute__((always_inline)) {
@@ -271,7 +280,7 @@ __global__ __launch_bounds__(TW_NW * 64) void gemm_tile_wide_kernel(TileGemm p) 
     }
 #pragma unroll
     for (int m = 24; m < 32; ++m) mm(w1, Q1{}, xb, m);
-    if (!CLV_DBG(p, 8)) __syncthreads();
+    if (!(TW_ABLATE & 8)) __syncthreads();
   };
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
@@ -365,7 +374,6 @@ int tile_gemm_pick_k_parts(int M, int N, int K) {
 
 void launch_gemm_tile(const TileGemm& g_in, hipStream_t st) {
   TileGemm g = g_in;
-  g.dbg = tune_int("CLOVER_TILE_DBG", 0);
   if (g.k_parts < 1 || g.epi == 1) g.k_parts = 1;
   const int blocks = g.N / 16;
   const int tiles = g.epi == 1 ? (blocks + 7) / 8 : (blocks + 15) / 16;
