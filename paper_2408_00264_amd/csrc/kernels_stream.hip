@@ -6,7 +6,7 @@
 // Why this shape.  With M <= 64 the GEMM is bound by streaming W from HBM, and what has to be kept
 // small is everything else that crosses the L2 fabric.  A workgroup is therefore tied to ONE slice of
 // K (512 columns): its activation slice (hi and lo bf16 planes, 64 x 512 x 4 B = 128 KB) is copied
-// into LDS once, and from then on its eight wavefronts do nothing but stream weight fragments
+// into LDS once (global -> LDS directly, a row per instruction), and from then on its eight wavefronts do nothing but stream weight fragments
 // (global -> registers, 16 KB in flight per wavefront) and multiply them against the resident slice:
 // no barrier and no activation traffic in the steady state.  Each workgroup walks a contiguous range
 // of 16-row weight blocks; the per-slice partial tiles are summed, in slice order, by whichever
@@ -126,25 +126,28 @@ __global__ __launch_bounds__(ST_WAVES * 64) void gemm_stream_kernel(StreamGemm p
   constexpr std::integral_constant<int, 1> B1{};
   if (n_items > 0) load(B0, 0);  // the HBM stream starts before the activation slice is staged
 
-  // ---- activation slice -> LDS (rows >= M are zero); all loads are issued before the first store.
-  // One wavefront instruction moves one row of one plane (64 lanes x 16 B = 512 columns), so the
-  // index arithmetic is shifts only.
+  // ---- activation slice -> LDS, without a stop in registers: one wavefront instruction moves one row of one plane
+  // (64 lanes x 16 B = 512 columns) from global memory to the row's place in the LDS (the hardware writes lane l's 16
+  // bytes at row base + 16 l).  Rows >= M read row M - 1 again: an output row depends on its own activation row only
+  // and rows >= M are never stored.  In a last slice shorter than 512 columns the lanes past it re-read its last
+  // piece (the products never touch those LDS columns).  The compiler is not told that these loads write the LDS;
+  // the wait before the barrier is written by hand. ----
   {
     const int slots = kt_n * 4;  // 16-byte pieces per row and plane (<= 64)
+    const unsigned lane_off = (unsigned)(min(lane, slots - 1) * 16);
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)xs;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     constexpr int XIT = 2 * ROWS / ST_WAVES;
-    u32x4 v[XIT];
 #pragma unroll
     for (int it = 0; it < XIT; ++it) {
-      const int rp = it * ST_WAVES + wave, plane = rp / ROWS, r = rp % ROWS;
-      v[it] = (u32x4){0u, 0u, 0u, 0u};
-      if (lane < slots && r < p.M && !CLV_DBG(p, 1))
-        v[it] = *(const u32x4*)((plane ? p.Xlo : p.Xhi) + (size_t)r * p.ldx + k0 + lane * 8);
+      const int rp = it * ST_WAVES + wave_u, plane = rp / ROWS, r = rp % ROWS;
+      if (CLV_DBG(p, 1)) continue;
+      const bf16_t* src = (plane ? p.Xlo : p.Xhi) + (size_t)min(r, p.M - 1) * p.ldx + k0;
+      const unsigned m0 = __builtin_amdgcn_readfirstlane(lds0 + 2u * (unsigned)(plane * PLANE + r * ST_LDK));
+      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(m0), "v"(lane_off),
+                   "s"((const __attribute__((address_space(1))) char*)src) : "m0");
     }
-#pragma unroll
-    for (int it = 0; it < XIT; ++it) {
-      const int rp = it * ST_WAVES + wave, plane = rp / ROWS, r = rp % ROWS;
-      if (lane < slots) *(u32x4*)(xs + plane * PLANE + r * ST_LDK + lane * 8) = v[it];
-    }
+    __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));   // vmcnt(0): this wavefront's rows are in the LDS
   }
   __syncthreads();
   if (n_items == 0) return;
