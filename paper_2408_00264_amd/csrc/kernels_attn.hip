@@ -403,8 +403,9 @@ void launch_attn_mfma(AttnParams p, int max_total_keys, bf16_t* out_hi, bf16_t* 
   const int g = p.n_q / p.n_kv;
   const int node_groups = (p.rm.n + 31) / 32;
   const int n_tiles = (max_total_keys + AT_TK - 1) / AT_TK;
-  // about one workgroup per CU (two on a CU do not overlap: a CU finishes one key tile per ~4 us either way, so a
-  // launch of 1.5 workgroups per CU takes as long as one of 2), at least two tiles per split, within the partial buffer
+  // about one workgroup per CU (two fit and do not overlap: a key tile costs the CU ~1.5 us of a workgroup's time
+  // whether the workgroup shares the CU or not, so a launch of 1.5 workgroups per CU takes as long as one of 2), at
+  // least two tiles per split, within the partial buffer
   const int target = tune_int("CLOVER_ATTN_WGS", 256);
   int splits = std::max(1, target / (p.rm.B * p.n_kv * node_groups));
   splits = std::max(1, std::min(std::min(splits, std::min(p.max_splits, MG_MAXS)), (n_tiles + 1) / 2));
@@ -412,8 +413,9 @@ void launch_attn_mfma(AttnParams p, int max_total_keys, bf16_t* out_hi, bf16_t* 
   p.tiles_per_split = (n_tiles + splits - 1) / splits;
   p.n_splits = (n_tiles + p.tiles_per_split - 1) / p.tiles_per_split;
   dim3 grid(p.n_splits, node_groups * p.n_kv, p.rm.B);
-  // Two wavefronts per head (16 nodes each) share a SIMD, so one's matrix products overlap the other's soft-max
-  // arithmetic, and both share the staged K / V^T tile.
+  // Two wavefronts per head (16 nodes each, two per SIMD): while one waits for fragments, a shuffle or the
+  // barrier the other issues, and both share the staged K / V^T tile (one wavefront per head with 32 nodes measured
+  // slower at every launch size).
   const int wm1 = tune_int("CLOVER_ATTN_WM1", 0);
   switch (g) {
     case 1: if (wm1) launch_attn_one<1, 1>(p, grid, st); else launch_attn_one<1, 2>(p, grid, st); break;
