@@ -128,3 +128,14 @@ def test_shipped_library_reads_no_environment_switch(lib):
         assert name.decode() in header, name
     syms = subprocess.run(["nm", "-D", clover.LIB_PATH], capture_output=True, text=True).stdout
     assert "getenv" not in syms
+
+
+def test_tuning_builds_never_overwrite_the_shipped_library():
+    """Ablation switches and extra macros exist only in builds that name their own output file."""
+    from paper_2408_00264_amd import build as B
+    with pytest.raises(ValueError):
+        B.build(ablate=True)                                   # no output path
+    with pytest.raises(ValueError):
+        B.build(defines=("CLOVER_TILE_ABLATE=1",), out="/tmp/x.so")   # macros without --ablate
+    with pytest.raises(ValueError):
+        B.build(ablate=True, defines=("CLOVER_TILE_ABLATE=1",))
