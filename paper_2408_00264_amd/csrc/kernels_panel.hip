@@ -57,7 +57,8 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-template <int MT, int KW, int EPI, int NBUF, int KST>
+// NOPAD: the launch has exactly MT * 16 rows (no padding rows in the tile).
+template <int MT, int KW, int EPI, int NBUF, int KST, bool NOPAD>
 __global__ __launch_bounds__(PN_WAVES * 64) void gemm_panel_kernel(PanelGemm p) {
   constexpr int ROWS = MT * 16;
   constexpr int PN_LDK = KST + 16;              // LDS row stride (bf16): 32 mod 64 bytes, the stride at which fragment reads run at the full LDS rate
@@ -127,11 +128,16 @@ __global__ __launch_bounds__(PN_WAVES * 64) void gemm_panel_kernel(PanelGemm p) 
     for (int it = 0; it < XIT; ++it) {
       const int idx = it * (PN_WAVES * 64) + tid;
       const int rp = idx / SL, sl = idx % SL, plane = rp / ROWS, r = rp % ROWS;
-      // always load (row clamped), then zero the padding rows: no branch around a load
-      const bf16_t* src = (plane ? p.Xlo : p.Xhi) + (size_t)min(r, p.M - 1) * p.ldx + ks * KST + sl * 8;
+      // Rows past M read row M - 1 again and are then zeroed by a predicate, which the compiler turns into a branch
+      // around every load: good when M is well below the tile's rows (the padding rows' loads are skipped: the LM
+      // head at 17..32 rows is 8 us faster with it), 0.7 % of the verify pass lost at exactly 64 rows -- hence the
+      // NOPAD form without predicate for a tile with no padding rows.  (Choosing between the two at run time inside
+      // one kernel loses the gain again; the 128-row form without its branches measured 5 % slower.)
+      const bf16_t* src = (plane ? p.Xlo : p.Xhi) + (size_t)(NOPAD ? r : min(r, p.M - 1)) * p.ldx + ks * KST + sl * 8;
       u32x4 v = (u32x4){0u, 0u, 0u, 0u};
       if (!CLV_DBG(p, 1)) v = *(const u32x4*)src;
-      xv[it] = r < p.M ? v : (u32x4){0u, 0u, 0u, 0u};
+      if constexpr (NOPAD) xv[it] = v;
+      else xv[it] = r < p.M ? v : (u32x4){0u, 0u, 0u, 0u};
     }
   };
   auto x_store = [&](int b) {
@@ -257,16 +263,21 @@ __global__ __launch_bounds__(PN_WAVES * 64) void gemm_panel_kernel(PanelGemm p) 
   }
 }
 
-template <int MT, int KW, int EPI, int NBUF, int KST = PN_KST>
-void launch_panel_one(const PanelGemm& g, int wgs, hipStream_t st) {
+template <int MT, int KW, int EPI, int NBUF, int KST, bool NOPAD>
+void launch_panel_kernel(const PanelGemm& g, int wgs, hipStream_t st) {
   constexpr size_t lds = (size_t)2 * 2 * MT * 16 * (KST + 16) * sizeof(bf16_t);
   static_assert(lds <= 160 * 1024, "stage buffers exceed the LDS");
   static bool attr_done = false;
   if (!attr_done) {
-    hipFuncSetAttribute((const void*)gemm_panel_kernel<MT, KW, EPI, NBUF, KST>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipFuncSetAttribute((const void*)gemm_panel_kernel<MT, KW, EPI, NBUF, KST, NOPAD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_done = true;
   }
-  gemm_panel_kernel<MT, KW, EPI, NBUF, KST><<<wgs * g.k_parts, PN_WAVES * 64, lds, st>>>(g);
+  gemm_panel_kernel<MT, KW, EPI, NBUF, KST, NOPAD><<<wgs * g.k_parts, PN_WAVES * 64, lds, st>>>(g);
+}
+template <int MT, int KW, int EPI, int NBUF, int KST = PN_KST>
+void launch_panel_one(const PanelGemm& g, int wgs, hipStream_t st) {
+  if (MT == 4 && g.M == MT * 16) launch_panel_kernel<MT, KW, EPI, NBUF, KST, MT == 4>(g, wgs, st);   // (only the 64-row form has a NOPAD kernel)
+  else launch_panel_kernel<MT, KW, EPI, NBUF, KST, false>(g, wgs, st);
 }
 
 }  // namespace
